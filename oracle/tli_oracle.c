@@ -1,0 +1,284 @@
+/*
+ * tli_oracle.c -- CPU oracle for the Token-Level Intersection (TLI) draft-and-verify step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, fp64 statement of what the GPU library has
+ * to compute.  Nothing in the product path may call, link or import it; it shares no code, header,
+ * table or helper with the HIP sources.  Callers: the tests, the smoke check and the benchmark's
+ * cpu_baseline leg.
+ *
+ * What it follows (paper sections, not listings):
+ *   - TLI algorithm (token-level intersection): the drafter distribution q over D is restricted to
+ *     the tokens shared with T and renormalised, q'(x) = q(x) / sum_{t in T∩D} q(t) for shared x and
+ *     0 otherwise; standard speculative decoding is then run with p and q'.
+ *   - Standard speculative decoding (appendix "Standard Speculative Decoding"): draw i draft tokens
+ *     d_j ~ q', take the i+1 target rows, for j = 1..i accept d_j with probability
+ *     min(1, p(d_j)/q'(d_j)) and stop at the first rejection; the extra token is drawn from the
+ *     residual r(t) = (p(t) - min(p(t), q'(t))) / (1 - sum_t' min(p(t'), q'(t'))) of the rejected
+ *     position, or from p of row i+1 when nothing was rejected.
+ *   - Logits stand for the distributions: p = softmax(logits_t / tau_t), q = softmax(logits_d / tau_d).
+ *
+ * Conventions the paper leaves open (listed with their reasons in the design notes of the repository):
+ *   - every random choice consumes a caller-supplied uniform u in [0,1);
+ *   - inverse-CDF sampling walks ids in ascending order with a sequential fp64 running sum C and
+ *     returns the first id whose C exceeds u * C_last (strict), so zero-weight ids are never chosen;
+ *   - a draft is accepted iff u * q'(d) < p(d) (strict), which has probability min(1, p/q') exactly;
+ *   - all K accept tests are evaluated, the accepted count is the length of the all-accept prefix.
+ *
+ * All arithmetic is IEEE double.  Inputs are taken exactly as stored (fp32, or bf16 as its 16 bits).
+ * Every function in this file is pinned by tests/test_oracle_pins.py (printed examples of the paper,
+ * closed forms, library routines, exact enumeration of the output distribution).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { TLO_F32 = 0, TLO_BF16 = 1 };
+
+/* status bits (per drafter row / per sequence) */
+enum {
+    TLO_NONFINITE = 1,  /* a logit that takes part in the computation is NaN or +inf              */
+    TLO_ZERO_MASS = 2,  /* the shared ids of a drafter row carry no mass (all -inf): q' is 0/0     */
+    TLO_BAD_DRAFT = 4,  /* a draft id given to verify is not a shared drafter id (or is -1)        */
+    TLO_DEGENERATE = 8  /* rejected, but the residual is identically zero: extra token drawn from p */
+};
+
+static double load_logit(const void *base, int dtype, int64_t idx) {
+    if (dtype == TLO_F32) return (double)((const float *)base)[idx];
+    uint32_t bits = ((uint32_t)((const uint16_t *)base)[idx]) << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+/*
+ * softmax(logits / tau) over n entries -> prob[n]; *log_norm = log sum_x exp(logits[x]/tau).
+ * Returns TLO_NONFINITE if an entry is NaN or +inf (prob then unspecified), 0 otherwise.
+ * -inf entries get probability 0.  A row of only -inf gives prob = 0 everywhere and log_norm = -inf.
+ */
+int tlo_softmax(const void *logits, int dtype, int64_t n, double tau, double *prob, double *log_norm) {
+    double M = -INFINITY;
+    int bad = 0;
+    for (int64_t x = 0; x < n; ++x) {
+        double z = load_logit(logits, dtype, x) / tau;
+        if (isnan(z) || z == INFINITY) bad = 1;
+        if (z > M) M = z;
+    }
+    if (bad) { *log_norm = NAN; return TLO_NONFINITE; }
+    if (M == -INFINITY) {
+        for (int64_t x = 0; x < n; ++x) prob[x] = 0.0;
+        *log_norm = -INFINITY;
+        return 0;
+    }
+    double Z = 0.0;
+    for (int64_t x = 0; x < n; ++x) {
+        prob[x] = exp(load_logit(logits, dtype, x) / tau - M);
+        Z += prob[x];
+    }
+    for (int64_t x = 0; x < n; ++x) prob[x] /= Z;
+    *log_norm = M + log(Z);
+    return 0;
+}
+
+/*
+ * TLI's adjusted drafter.  q = softmax(logits_d / tau_d) over all of D, then
+ * q'(x) = q(x) / sum_{y shared} q(y) for shared x (d2t[x] >= 0), 0 otherwise.
+ * q[Vd] and qprime[Vd] are outputs; *log_norm_shared = log sum_{y shared} exp(logits_d[y]/tau_d),
+ * the normaliser that turns a shared logit straight into log q'.
+ * Status: NONFINITE if a SHARED logit is NaN/+inf; ZERO_MASS if the shared ids have total mass 0.
+ * Unshared drafter logits must be finite or -inf (the method never looks at them again).
+ */
+int tlo_adjusted_drafter(const void *logits_d, int dtype, int64_t Vd, double tau_d, const int32_t *d2t,
+                         double *q, double *qprime, double *log_norm_shared) {
+    for (int64_t x = 0; x < Vd; ++x) {
+        if (d2t[x] < 0) continue;
+        double z = load_logit(logits_d, dtype, x);
+        if (isnan(z) || z == INFINITY) {
+            for (int64_t y = 0; y < Vd; ++y) { q[y] = NAN; qprime[y] = NAN; }
+            *log_norm_shared = NAN;
+            return TLO_NONFINITE;
+        }
+    }
+    double log_norm_all;
+    tlo_softmax(logits_d, dtype, Vd, tau_d, q, &log_norm_all);
+    double mass = 0.0;
+    for (int64_t x = 0; x < Vd; ++x)
+        if (d2t[x] >= 0) mass += q[x];
+    if (!(mass > 0.0)) {
+        for (int64_t x = 0; x < Vd; ++x) qprime[x] = 0.0;
+        *log_norm_shared = -INFINITY;
+        return TLO_ZERO_MASS;
+    }
+    for (int64_t x = 0; x < Vd; ++x) qprime[x] = (d2t[x] >= 0) ? q[x] / mass : 0.0;
+    *log_norm_shared = log_norm_all + log(mass);
+    return 0;
+}
+
+/*
+ * Inverse-CDF sample from non-negative weights w[n] with uniform u in [0,1):
+ * C_x = w_0 + ... + w_x (sequential), theta = u * C_{n-1}, result = min{x : C_x > theta}.
+ * If rounding leaves no such x, the last id with w > 0.  Returns -1 if the total is 0.
+ * *margin (may be NULL) = distance from theta to the nearer edge of the chosen id's CDF interval,
+ * as a fraction of the total.
+ */
+int64_t tlo_inverse_cdf(const double *w, int64_t n, double u, double *margin) {
+    double total = 0.0;
+    for (int64_t x = 0; x < n; ++x) total += w[x];
+    if (margin) *margin = 0.0;
+    if (!(total > 0.0)) return -1;
+    double theta = u * total;
+    double C = 0.0, Cprev = 0.0;
+    int64_t last_pos = -1;
+    for (int64_t x = 0; x < n; ++x) {
+        Cprev = C;
+        C += w[x];
+        if (w[x] > 0.0) last_pos = x;
+        if (C > theta) {
+            if (margin) {
+                double lo = theta - Cprev, hi = C - theta;
+                *margin = (lo < hi ? lo : hi) / total;
+            }
+            return x;
+        }
+    }
+    return last_pos;
+}
+
+/*
+ * Draft sampling for R independent drafter rows (row r at logits_d + r*row_stride elements):
+ * tok_d[r] ~ q'_r by inverse CDF with u_draft[r]; tok_t[r] = d2t[tok_d[r]];
+ * q_tok[r] = q'_r(tok_d[r]); lse_q[r] = log sum_{shared} exp(logit/tau_d).
+ * Rows flagged NONFINITE or ZERO_MASS return tok_d = tok_t = -1 and q_tok = 0.
+ * work must hold 2*Vd doubles.
+ */
+void tlo_draft_sample(const void *logits_d, int dtype, int64_t row_stride, int64_t R, int64_t Vd,
+                      double tau_d, const int32_t *d2t, const double *u_draft,
+                      int32_t *tok_d, int32_t *tok_t, double *q_tok, double *lse_q,
+                      int32_t *row_status, double *cdf_margin, double *work) {
+    size_t esz = (dtype == TLO_F32) ? 4 : 2;
+    double *q = work, *qp = work + Vd;
+    for (int64_t r = 0; r < R; ++r) {
+        const void *row = (const char *)logits_d + (size_t)r * (size_t)row_stride * esz;
+        int st = tlo_adjusted_drafter(row, dtype, Vd, tau_d, d2t, q, qp, &lse_q[r]);
+        row_status[r] = st;
+        tok_d[r] = -1; tok_t[r] = -1; q_tok[r] = 0.0;
+        if (cdf_margin) cdf_margin[r] = 0.0;
+        if (st) continue;
+        double mg;
+        int64_t d = tlo_inverse_cdf(qp, Vd, u_draft[r], &mg);
+        tok_d[r] = (int32_t)d;
+        tok_t[r] = d2t[d];
+        q_tok[r] = qp[d];
+        if (cdf_margin) cdf_margin[r] = mg;
+    }
+}
+
+/*
+ * Weights of the extra token for one sequence, unnormalised over target ids:
+ *   rejected at position j : r(t) = (p_j(t) - min(p_j(t), q'_j(t))) / (1 - sum min(p_j, q'_j))
+ *   nothing rejected       : p_{K+1}(t)
+ * qprime_t[Vt] is q'_j laid out over target ids (0 for target-only ids).
+ * Returns 1 if the residual is degenerate (normaliser <= 0 or all numerators 0); w is then p.
+ */
+static int residual_weights(const double *p, const double *qprime_t, int64_t Vt, double *w) {
+    double overlap = 0.0;
+    for (int64_t t = 0; t < Vt; ++t) overlap += fmin(p[t], qprime_t[t]);
+    double denom = 1.0 - overlap;
+    double total = 0.0;
+    for (int64_t t = 0; t < Vt; ++t) {
+        w[t] = p[t] - fmin(p[t], qprime_t[t]);
+        total += w[t];
+    }
+    if (!(denom > 0.0) || !(total > 0.0)) {
+        for (int64_t t = 0; t < Vt; ++t) w[t] = p[t];
+        return 1;
+    }
+    for (int64_t t = 0; t < Vt; ++t) w[t] /= denom;
+    return 0;
+}
+
+/*
+ * One TLI verification for B independent sequences.
+ *   logits_t [B, K+1, Vt] dense, logits_d [B, K, Vd] dense, tok_d [B,K] draft ids in drafter space,
+ *   u_acc [B,K], u_fin [B].
+ * Outputs per sequence: accept[K] (every position tested on its own), n_acc = length of the
+ * all-accept prefix, out_tok[K+1] = accepted target ids, then the extra token, then -1 padding;
+ * p_tok/q_tok [K] = p_k(d_k), q'_k(d_k); lse_p [K+1] (entry K is NaN unless the bonus row was used);
+ * lse_q [K]; acc_margin[K] = |u - p/q'| (inf when p >= q'); fin_margin = CDF margin of the extra token.
+ * If fin_weights != NULL it receives [B, Vt] the weights the extra token was drawn from.
+ * A sequence with a NONFINITE target row among the rows it needs returns n_acc = 0 and out_tok = -1.
+ * work must hold 3*Vt + 2*Vd doubles.
+ */
+void tlo_verify(const void *logits_t, const void *logits_d, int dtype, int64_t B, int64_t K,
+                int64_t Vt, int64_t Vd, double tau_t, double tau_d, const int32_t *d2t,
+                const int32_t *tok_d, const double *u_acc, const double *u_fin,
+                int32_t *n_acc, int32_t *out_tok, uint8_t *accept, double *p_tok, double *q_tok,
+                double *lse_p, double *lse_q, int32_t *seq_status, double *acc_margin,
+                double *fin_margin, double *fin_weights, double *work) {
+    size_t esz = (dtype == TLO_F32) ? 4 : 2;
+    double *p = work, *qpt = work + Vt, *w = work + 2 * Vt, *q = work + 3 * Vt, *qp = q + Vd;
+    for (int64_t b = 0; b < B; ++b) {
+        const char *lt_b = (const char *)logits_t + (size_t)b * (size_t)(K + 1) * (size_t)Vt * esz;
+        const char *ld_b = (const char *)logits_d + (size_t)b * (size_t)K * (size_t)Vd * esz;
+        int status = 0;
+        int first_reject = -1;
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t o = b * K + k;
+            int st_p = tlo_softmax(lt_b + (size_t)k * Vt * esz, dtype, Vt, tau_t, p, &lse_p[b * (K + 1) + k]);
+            status |= st_p;
+            int32_t d = tok_d[o];
+            accept[o] = 0; p_tok[o] = 0.0; q_tok[o] = 0.0; acc_margin[o] = INFINITY; lse_q[o] = NAN;
+            if (d < 0 || d >= Vd || d2t[d] < 0) {
+                status |= TLO_BAD_DRAFT;
+            } else if (!st_p) {
+                int st_q = tlo_adjusted_drafter(ld_b + (size_t)k * Vd * esz, dtype, Vd, tau_d, d2t, q, qp, &lse_q[o]);
+                if (st_q) {
+                    status |= st_q;
+                } else {
+                    double pd = p[d2t[d]], qd = qp[d];
+                    p_tok[o] = pd; q_tok[o] = qd;
+                    accept[o] = (u_acc[o] * qd < pd) ? 1 : 0;
+                    if (pd < qd) acc_margin[o] = fabs(u_acc[o] - pd / qd);
+                }
+            }
+            if (!accept[o] && first_reject < 0) first_reject = (int)k;
+        }
+        lse_p[b * (K + 1) + K] = NAN;
+        int32_t *out = out_tok + b * (K + 1);
+        for (int64_t k = 0; k <= K; ++k) out[k] = -1;
+        fin_margin[b] = 0.0;
+        if (status & TLO_NONFINITE) {
+            n_acc[b] = 0; seq_status[b] = status;
+            if (fin_weights) for (int64_t t = 0; t < Vt; ++t) fin_weights[b * Vt + t] = NAN;
+            continue;
+        }
+        int64_t n = (first_reject < 0) ? K : first_reject;
+        if (n < K) {
+            /* rejected at position n: residual of (p_n, q'_n); q' == 0 if the draft there was unusable */
+            tlo_softmax(lt_b + (size_t)n * Vt * esz, dtype, Vt, tau_t, p, &lse_p[b * (K + 1) + n]);
+            for (int64_t t = 0; t < Vt; ++t) qpt[t] = 0.0;
+            int32_t d = tok_d[b * K + n];
+            if (!(d < 0 || d >= Vd || d2t[d] < 0)) {
+                double tmp;
+                int st_q = tlo_adjusted_drafter(ld_b + (size_t)n * Vd * esz, dtype, Vd, tau_d, d2t, q, qp, &tmp);
+                if (!st_q)
+                    for (int64_t x = 0; x < Vd; ++x)
+                        if (d2t[x] >= 0) qpt[d2t[x]] = qp[x];
+            }
+            if (residual_weights(p, qpt, Vt, w)) status |= TLO_DEGENERATE;
+        } else {
+            int st = tlo_softmax(lt_b + (size_t)K * Vt * esz, dtype, Vt, tau_t, w, &lse_p[b * (K + 1) + K]);
+            if (st) {
+                n_acc[b] = 0; seq_status[b] = status | st;
+                if (fin_weights) for (int64_t t = 0; t < Vt; ++t) fin_weights[b * Vt + t] = NAN;
+                continue;
+            }
+        }
+        if (fin_weights) memcpy(fin_weights + b * Vt, w, (size_t)Vt * sizeof(double));
+        int64_t extra = tlo_inverse_cdf(w, Vt, u_fin[b], &fin_margin[b]);
+        for (int64_t k = 0; k < n; ++k) out[k] = d2t[tok_d[b * K + k]];
+        out[n] = (int32_t)extra;
+        n_acc[b] = (int32_t)n;
+        seq_status[b] = status;
+    }
+}

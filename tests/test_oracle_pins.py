@@ -1,0 +1,444 @@
+"""Pins for the CPU oracle: everything here checks oracle/ against something other than itself --
+values the paper prints, closed forms, library routines (scipy / numpy), brute-force enumeration of the
+exact output distribution.  CPU only."""
+import json
+import os
+
+import numpy as np
+import pytest
+import scipy.special as sps
+import torch
+
+from paper_2502_05202_amd import synth
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+GOLD = json.load(open(os.path.join(HERE, "golden", "worked_examples.json")))
+
+
+def d2t_from_strings(D, T):
+    return np.array([T.index(s) if s in T else -1 for s in D], np.int32)
+
+
+def ref_softmax(x, tau):
+    return sps.softmax(np.asarray(x, np.float64) / tau)
+
+
+def ref_qprime(ld, tau, d2t):
+    """masked softmax written with scipy: the library-routine special case."""
+    z = np.where(d2t >= 0, np.asarray(ld, np.float64) / tau, -np.inf)
+    return np.exp(z - sps.logsumexp(z)), sps.logsumexp(z)
+
+
+# ---------------------------------------------------------------- printed examples of the paper
+def test_renormalise_example_printed_values(oracle):
+    g = GOLD["renormalise_example"]
+    d2t = d2t_from_strings(g["D"], g["T"])
+    logits = np.log(np.array(g["q"])).astype(np.float32)  # three equal logits
+    for shift in (0.0, 3.0, -7.5):
+        q, qp, lse, st = oracle.adjusted_drafter(logits + np.float32(shift), 1.0, d2t)
+        assert st == 0
+        np.testing.assert_allclose(q, g["q"], rtol=0, atol=1e-15)
+        assert list(qp) == g["q_prime"]  # exact in binary
+
+
+def test_disjoint_vocabularies(oracle):
+    g = GOLD["disjoint"]
+    d2t = d2t_from_strings(g["D"], g["T"])
+    q, qp, lse, st = oracle.adjusted_drafter(np.array([0.3], np.float32), 1.0, d2t)
+    assert st == oracle.ZERO_MASS and qp[0] == 0.0 and lse == -np.inf
+    ds = oracle.draft_sample(np.array([[0.3]], np.float32), 1.0, d2t, np.array([0.4]))
+    assert ds["tok_d"][0] == -1 and ds["tok_t"][0] == -1 and ds["status"][0] == oracle.ZERO_MASS
+    # verify: the unusable draft is rejected for every u, and the extra token is the target's
+    lt = np.array([[[1.25], [0.5]]], np.float32)
+    ld = np.array([[[0.3]]], np.float32)
+    for u in (0.0, 0.5, 0.999999):
+        v = oracle.verify(lt, ld, 1.0, 1.0, d2t, ds["tok_d"], [u], [u])
+        assert v["n_acc"][0] == 0 and v["accept"][0, 0] == 0
+        assert list(v["out_tok"][0]) == [0, -1]
+        assert v["status"][0] & oracle.BAD_DRAFT
+
+
+def test_drafter_subset(oracle):
+    g = GOLD["drafter_subset"]
+    d2t = d2t_from_strings(g["D"], g["T"])
+    lt = np.array([[[0.2, -0.9], [0.0, 0.0]]], np.float32)
+    ld = np.array([[[4.0]]], np.float32)
+    p = ref_softmax(lt[0, 0], 1.0)
+    q, qp, _, _ = oracle.adjusted_drafter(ld[0, 0], 1.0, d2t)
+    assert list(qp) == g["q_prime"]
+    tok_d = oracle.draft_sample(ld[0], 1.0, d2t, [0.7])["tok_d"]
+    assert tok_d[0] == 0
+    eps = 1e-12
+    v = oracle.verify(lt, ld, 1.0, 1.0, d2t, tok_d, [p[1] - eps], [0.3])
+    assert v["n_acc"][0] == 1 and list(v["out_tok"][0]) == [1, 0 if 0.3 < 0.5 else 1]
+    v = oracle.verify(lt, ld, 1.0, 1.0, d2t, tok_d, [p[1] + eps], [0.3], want_weights=True)
+    assert v["n_acc"][0] == 0 and v["out_tok"][0, 0] == 0  # residual: all mass on 'a'
+    np.testing.assert_allclose(v["fin_weights"][0], [g["residual"]["a"], g["residual"]["b"]], atol=1e-15)
+
+
+def test_target_subset_always_accepts(oracle):
+    g = GOLD["target_subset"]
+    d2t = d2t_from_strings(g["D"], g["T"])
+    lt = np.array([[[0.7], [-0.2]]], np.float32)
+    ld = np.array([[[0.1, 2.0]]], np.float32)
+    q, qp, _, _ = oracle.adjusted_drafter(ld[0, 0], 1.0, d2t)
+    assert list(qp) == g["q_prime"]
+    for u in (0.0, 0.5, 1.0 - 2.0 ** -24):
+        tok_d = oracle.draft_sample(ld[0], 1.0, d2t, [u])["tok_d"]
+        assert tok_d[0] == 0
+        v = oracle.verify(lt, ld, 1.0, 1.0, d2t, tok_d, [u], [u])
+        assert v["n_acc"][0] == 1 and list(v["out_tok"][0]) == [0, 0]
+
+
+# ---------------------------------------------------------------- library routines, sums to one
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("tau", [1.0, 0.7, 1.2])
+def test_softmax_and_qprime_match_scipy(oracle, dtype, tau):
+    w = synth.WORKLOADS[1].scaled(Vt=1000, Vd=777, S=300, dtype=dtype, B=2, K=2)
+    inp = synth.make_inputs(w)
+    lt = synth.logits_to_numpy(inp["logits_t"])
+    ld = synth.logits_to_numpy(inp["logits_d"])
+    ltf = inp["logits_t"].double().numpy()
+    ldf = inp["logits_d"].double().numpy()
+    d2t = inp["d2t"]
+    for b in range(2):
+        for k in range(2):
+            p, lse, st = oracle.softmax(lt[b, k], tau)
+            assert st == 0
+            np.testing.assert_allclose(p, ref_softmax(ltf[b, k], tau), rtol=1e-13, atol=0)
+            np.testing.assert_allclose(lse, sps.logsumexp(ltf[b, k] / tau), rtol=1e-14)
+            assert abs(p.sum() - 1.0) < 1e-12
+            q, qp, lse_q, st = oracle.adjusted_drafter(ld[b, k], tau, d2t)
+            rq, rl = ref_qprime(ldf[b, k], tau, d2t)
+            np.testing.assert_allclose(q, ref_softmax(ldf[b, k], tau), rtol=1e-13)
+            np.testing.assert_allclose(qp, rq, rtol=1e-13, atol=0)
+            np.testing.assert_allclose(lse_q, rl, rtol=1e-14)
+            assert abs(q.sum() - 1.0) < 1e-12 and abs(qp.sum() - 1.0) < 1e-12
+            assert np.all(qp[d2t < 0] == 0.0)
+
+
+def test_bf16_bits_are_read_exactly(oracle):
+    vals = torch.tensor([1.0, -2.5, 3.140625, 0.0078125, -100.0], dtype=torch.bfloat16)
+    bits = synth.logits_to_numpy(vals)
+    p, lse, st = oracle.softmax(bits, 1.0)
+    np.testing.assert_allclose(p, ref_softmax(vals.double().numpy(), 1.0), rtol=1e-14)
+
+
+def test_inverse_cdf_is_searchsorted(oracle):
+    rng = np.random.default_rng(7)
+    for n in (1, 2, 17, 1000):
+        w = rng.random(n) ** 3
+        w[rng.random(n) < 0.3] = 0.0
+        if w.sum() == 0:
+            w[0] = 1.0
+        C = np.cumsum(w)
+        for u in list(rng.random(50)) + [0.0, 1.0 - 2.0 ** -24]:
+            x, mg = oracle.inverse_cdf(w, u)
+            ref = int(np.searchsorted(C, u * C[-1], side="right"))
+            assert x == ref and w[x] > 0
+            lo = C[x - 1] if x else 0.0
+            assert abs(mg - min(u * C[-1] - lo, C[x] - u * C[-1]) / C[-1]) < 1e-15
+    # u = 0 picks the first positive-weight id, zero-weight ids are never chosen
+    assert oracle.inverse_cdf(np.array([0.0, 0.0, 2.0, 1.0]), 0.0)[0] == 2
+    assert oracle.inverse_cdf(np.array([0.0, 0.0]), 0.3)[0] == -1
+    # equal-weight boundary: theta exactly on a CDF edge goes to the next id (strict >)
+    assert oracle.inverse_cdf(np.array([1.0, 1.0, 1.0, 1.0]), 0.5)[0] == 2
+
+
+# ---------------------------------------------------------------- closed forms on random inputs
+def small_case(seed, K=2, Vt=97, Vd=61, S=40, dtype="f32", kind="noise"):
+    w = synth.WORKLOADS[1].scaled(B=1, K=K, Vt=Vt, Vd=Vd, S=S, dtype=dtype)
+    inp = synth.make_inputs(w, seed=seed)
+    return inp, synth.logits_to_numpy(inp["logits_t"]), synth.logits_to_numpy(inp["logits_d"])
+
+
+def accept_threshold(oracle, lt, ld, d2t, k, d, K):
+    """black box: sup{u : draft d at position k is accepted}, by bisection on u_acc (1 if always)."""
+    tok = np.zeros((1, K), np.int32)
+    tok[0, :] = d
+    ua = np.zeros((1, K))
+
+    def acc(u):
+        ua[0, k] = u
+        return oracle.verify(lt, ld, 1.0, 1.0, d2t, tok, ua, [0.5])["accept"][0, k]
+
+    if acc(1.0 - 1e-16):
+        return 1.0
+    lo, hi = 0.0, 1.0
+    if not acc(0.0):
+        return 0.0
+    for _ in range(60):
+        mid = 0.5 * (lo + hi)
+        if acc(mid):
+            lo = mid
+        else:
+            hi = mid
+    return 0.5 * (lo + hi)
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_acceptance_rate_closed_form(oracle, seed):
+    """Table 'expected acceptance rates', TLI row: sum_{T∩D} min{p, q/sum_{T∩D} q}; and the theorem
+    'intersection >= union': sum min(p,q) <= sum min(p,q')."""
+    K = 2
+    inp, lt, ld = small_case(seed, K=K)
+    d2t = inp["d2t"]
+    shared = np.nonzero(d2t >= 0)[0]
+    for k in range(K):
+        p = ref_softmax(lt[0, k], 1.0)
+        q = ref_softmax(ld[0, k], 1.0)
+        qp, _ = ref_qprime(ld[0, k], 1.0, d2t)
+        alpha_tli = np.minimum(p[d2t[shared]], qp[shared]).sum()
+        alpha_union = np.minimum(p[d2t[shared]], q[shared]).sum()
+        assert alpha_union <= alpha_tli + 1e-15
+        # measured from the oracle as a black box: P(accept) = sum_d |draft interval of d| * |accept interval of d|
+        measured = 0.0
+        _, oq, _, _ = oracle.adjusted_drafter(ld[0, k], 1.0, d2t)
+        for d in shared:
+            measured += oq[d] * accept_threshold(oracle, lt, ld, d2t, k, int(d), K)
+        assert abs(measured - alpha_tli) < 1e-12
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_residual_definition_and_normaliser(oracle, seed):
+    """SD appendix, last step: r = (p - min(p,q'))/(1 - sum min(p,q')); identity sum max(0,p-q') = 1 - sum min."""
+    K = 2
+    inp, lt, ld = small_case(seed, K=K)
+    d2t = inp["d2t"]
+    shared = np.nonzero(d2t >= 0)[0]
+    for k in range(K):
+        p = ref_softmax(lt[0, k], 1.0)
+        qp, _ = ref_qprime(ld[0, k], 1.0, d2t)
+        qpt = np.zeros_like(p)
+        qpt[d2t[shared]] = qp[shared]
+        r_ref = np.maximum(0.0, p - qpt)
+        assert abs(r_ref.sum() - (1.0 - np.minimum(p, qpt).sum())) < 1e-14
+        r_ref /= r_ref.sum()
+        # force a rejection at position k: a draft with p < q' and u_acc just under 1
+        cand = [d for d in shared if p[d2t[d]] < 0.5 * qp[d]]
+        tok = np.zeros((1, K), np.int32)
+        tok[0, :] = cand[0]
+        ua = np.zeros((1, K))
+        ua[0, k] = 0.999
+        v = oracle.verify(lt, ld, 1.0, 1.0, d2t, tok, ua, [0.37], want_weights=True)
+        assert v["n_acc"][0] == k and v["accept"][0, k] == 0
+        np.testing.assert_allclose(v["fin_weights"][0], r_ref, rtol=1e-12, atol=1e-18)
+        assert abs(v["fin_weights"][0].sum() - 1.0) < 1e-12
+        C = np.cumsum(r_ref)
+        assert v["out_tok"][0, k] == int(np.searchsorted(C, 0.37 * C[-1], side="right"))
+
+
+def test_identical_models_always_accept(oracle):
+    """Theorem on exact match vs SD: with q = p the acceptance rate of SD is one."""
+    K, V = 3, 50
+    rng = np.random.default_rng(5)
+    lt = (rng.standard_normal((1, K + 1, V)) * 2).astype(np.float32)
+    ld = lt[:, :K].copy()
+    d2t = np.arange(V, dtype=np.int32)
+    for trial in range(40):
+        u = rng.random(2 * K + 1)
+        if trial == 0:
+            u[:] = 1.0 - 2.0 ** -24
+        ds = oracle.draft_sample(ld[0], 1.0, d2t, u[:K])
+        v = oracle.verify(lt, ld, 1.0, 1.0, d2t, ds["tok_d"], u[K:2 * K], u[2 * K:])
+        assert v["n_acc"][0] == K and np.all(v["accept"] == 1)
+        assert list(v["out_tok"][0, :K]) == list(ds["tok_t"])
+        C = np.cumsum(ref_softmax(lt[0, K], 1.0))
+        assert v["out_tok"][0, K] == int(np.searchsorted(C, u[2 * K] * C[-1], side="right"))
+        assert not np.isnan(v["lse_p"][0, K])
+
+
+# ---------------------------------------------------------------- exact enumeration (losslessness)
+def measured_boxes(oracle, inp, lt, ld):
+    """Treat the oracle's samplers as black boxes and measure, per position k, the lengths of the
+    intervals of the three uniforms on which each outcome is returned.  Interval edges are predicted
+    from the oracle's probability arrays and then CONFIRMED by probing the sampler at the midpoint and
+    just inside both edges of every interval."""
+    w = inp["workload"]
+    K, Vt, Vd = w.K, w.Vt, w.Vd
+    d2t = inp["d2t"]
+    shared = np.nonzero(d2t >= 0)[0]
+    eps = 1e-10
+    Q = np.zeros((K, Vd))       # |{u_draft : d_k = d}|
+    A = np.zeros((K, Vd))       # |{u_acc : accept d at k}|
+    R = np.zeros((K + 1, Vt))   # |{u_fin : extra token = t}| at rejected position k (row K: bonus)
+    for k in range(K):
+        _, qp, _, _ = oracle.adjusted_drafter(ld[0, k], w.tau_d, d2t)
+        edges = np.concatenate([[0.0], np.cumsum(qp) / qp.sum()])
+        for d in shared:
+            lo, hi = edges[d], edges[d + 1]
+            assert hi - lo > 4 * eps
+            probes = [0.5 * (lo + hi), lo + eps, hi - eps]
+            rows = np.repeat(ld[0, k][None], 3, axis=0)
+            got = oracle.draft_sample(rows, w.tau_d, d2t, probes)["tok_d"]
+            assert np.all(got == d), (k, d, got)
+            Q[k, d] = hi - lo
+        # accept intervals: [0, thr)
+        tok = np.zeros((1, K), np.int32)
+        for d in shared:
+            tok[0, :] = d
+            v = oracle.verify(lt, ld, w.tau_t, w.tau_d, d2t, tok, np.zeros((1, K)), [0.5])
+            thr = min(1.0, v["p_tok"][0, k] / v["q_tok"][0, k])
+            ua = np.zeros((1, K))
+            for u, want in ((thr - eps, 1), (0.0, 1), (0.5 * thr, 1), (thr + eps, 0), (0.5 * (thr + 1), 0)):
+                if not 0.0 <= u < 1.0:
+                    continue
+                ua[0, k] = u
+                got = oracle.verify(lt, ld, w.tau_t, w.tau_d, d2t, tok, ua, [0.5])["accept"][0, k]
+                assert got == want, (k, d, u, thr)
+            A[k, d] = thr
+    # extra token intervals: reject at position k (accept everything before), or accept all
+    for k in range(K + 1):
+        tok = np.zeros((1, K), np.int32)
+        ua = np.zeros((1, K))
+        for j in range(K):
+            # position j: a draft that is surely accepted at u=0 (any with p>0), position k: a rejected one
+            if j == k:
+                d = next(d for d in shared if A[j, d] < 0.9)
+                ua[0, j] = 0.5 * (A[j, d] + 1.0)
+            else:
+                d = shared[0]
+                ua[0, j] = 0.0
+            tok[0, j] = d
+        v = oracle.verify(lt, ld, w.tau_t, w.tau_d, d2t, tok, ua, [0.5], want_weights=True)
+        assert v["n_acc"][0] == k
+        wts = v["fin_weights"][0]
+        edges = np.concatenate([[0.0], np.cumsum(wts) / wts.sum()])
+        for t in range(Vt):
+            lo, hi = edges[t], edges[t + 1]
+            if hi - lo <= 4 * eps:
+                assert wts[t] < 1e-9
+                continue
+            for u in (0.5 * (lo + hi), lo + eps, hi - eps):
+                got = oracle.verify(lt, ld, w.tau_t, w.tau_d, d2t, tok, ua, [u])["out_tok"][0, k]
+                assert got == t, (k, t, u, got)
+            R[k, t] = hi - lo
+    return Q, A, R
+
+
+def test_lossless_by_exact_enumeration_config1(oracle):
+    """Theorem 'intersection >= union' (second claim) and the SD appendix: the output tokens are
+    distributed according to p.  Workload 1 (B=1, K=3, Vt=64, Vd=48, S=32): every output sequence
+    (d_1..d_n, t) is enumerated (32^3*64 + 32^2*64 + 32*64 + 64 of them) with its exact probability =
+    the volume of the box of uniforms that produces it, measured from the oracle's samplers."""
+    inp = synth.make_inputs(synth.WORKLOADS[1])
+    w = inp["workload"]
+    lt = synth.logits_to_numpy(inp["logits_t"])
+    ld = synth.logits_to_numpy(inp["logits_d"])
+    d2t = inp["d2t"]
+    K, Vt = w.K, w.Vt
+    shared = np.nonzero(d2t >= 0)[0]
+    assert (w.B, K, Vt, w.Vd, len(shared)) == (1, 3, 64, 48, 32)
+    Q, A, R = measured_boxes(oracle, inp, lt, ld)
+    p = np.stack([ref_softmax(lt[0, k], w.tau_t) for k in range(K + 1)])  # independent of the oracle
+    acc = Q[:, shared] * A[:, shared]                   # P(d_k = d and accepted), per position
+    rej = (Q[:, shared] * (1.0 - A[:, shared])).sum(1)  # P(rejected at k)
+    alpha = acc.sum(1)
+    # enumerate all sequences: P[n] has shape (32,)*n + (64,)
+    total = 0.0
+    marg = np.zeros((K + 1, Vt))  # marg[k, t] = P(a token is emitted at position k and it is t)
+    prefix = np.ones(())
+    for n in range(K + 1):
+        last = R[n] * (rej[n] if n < K else 1.0)
+        P = np.multiply.outer(prefix, last)             # all sequences with exactly n accepted drafts
+        total += P.sum()
+        assert P.size == len(shared) ** n * Vt
+        # position j < n holds accepted draft d_j (as a target id), position n holds the extra token
+        for j in range(n):
+            axes = tuple(a for a in range(n + 1) if a != j)
+            np.add.at(marg[j], d2t[shared], P.sum(axis=axes))
+        marg[n] += P.sum(axis=tuple(range(n)))
+        if n < K:
+            prefix = np.multiply.outer(prefix, acc[n])
+    assert abs(total - 1.0) < 1e-12
+    reach = np.concatenate([[1.0], np.cumprod(alpha)])  # P(position k is reached) = prod_{j<k} alpha_j
+    for k in range(K + 1):
+        np.testing.assert_allclose(marg[k], reach[k] * p[k], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(marg[0], p[0], rtol=0, atol=1e-12)  # first token ~ p_1 exactly
+    # acceptance rate closed form, from quantities independent of the oracle
+    for k in range(K):
+        qp, _ = ref_qprime(ld[0, k], w.tau_d, d2t)
+        assert abs(alpha[k] - np.minimum(p[k][d2t[shared]], qp[shared]).sum()) < 1e-12
+
+
+def test_monte_carlo_single_position(oracle):
+    """Black-box statistical check of the batched entry points (K=1): empirical output ~ p_1."""
+    w = synth.WORKLOADS[1].scaled(K=1)
+    inp = synth.make_inputs(w)
+    lt1 = synth.logits_to_numpy(inp["logits_t"])
+    ld1 = synth.logits_to_numpy(inp["logits_d"])
+    n = 400_000
+    rng = np.random.default_rng(99)
+    lt = np.repeat(lt1, n, axis=0)
+    ld = np.repeat(ld1, n, axis=0)
+    u = rng.random((3, n))
+    ds = oracle.draft_sample(ld[:, 0], w.tau_d, inp["d2t"], u[0], threads=8)
+    v = oracle.verify(lt, ld, w.tau_t, w.tau_d, inp["d2t"], ds["tok_d"], u[1], u[2], threads=8)
+    first = v["out_tok"][:, 0]
+    emp = np.bincount(first, minlength=w.Vt) / n
+    p = ref_softmax(lt1[0, 0], w.tau_t)
+    sigma = np.sqrt(p * (1 - p) / n)
+    assert np.all(np.abs(emp - p) < 5 * sigma + 1e-9)
+    # acceptance frequency vs closed form
+    qp, _ = ref_qprime(ld1[0, 0], w.tau_d, inp["d2t"])
+    sh = np.nonzero(inp["d2t"] >= 0)[0]
+    alpha = np.minimum(p[inp["d2t"][sh]], qp[sh]).sum()
+    assert abs(v["n_acc"].mean() - alpha) < 5 * np.sqrt(alpha * (1 - alpha) / n)
+
+
+# ---------------------------------------------------------------- conventions and flags
+def test_first_reject_stops_the_prefix(oracle):
+    inp, lt, ld = small_case(31, K=4)
+    d2t = inp["d2t"]
+    shared = np.nonzero(d2t >= 0)[0]
+    tok = np.full((1, 4), shared[3], np.int32)
+    base = oracle.verify(lt, ld, 1.0, 1.0, d2t, tok, np.zeros((1, 4)), [0.2])
+    assert base["n_acc"][0] == 4  # u=0 accepts every draft with p>0
+    thr = np.minimum(1.0, base["p_tok"] / base["q_tok"])[0]
+    k = int(np.argmin(thr))
+    assert thr[k] < 1.0
+    ua = np.zeros((1, 4))
+    ua[0, k] = 0.5 * (thr[k] + 1.0)
+    v = oracle.verify(lt, ld, 1.0, 1.0, d2t, tok, ua, [0.2])
+    assert v["n_acc"][0] == k
+    assert list(v["accept"][0]) == [0 if j == k else 1 for j in range(4)]  # later positions still tested
+    assert list(v["out_tok"][0, :k]) == [d2t[shared[3]]] * k
+    assert np.all(v["out_tok"][0, k + 1:] == -1) and v["out_tok"][0, k] >= 0
+    assert abs(v["acc_margin"][0, k] - abs(ua[0, k] - thr[k])) < 1e-15
+
+
+def test_flags(oracle):
+    inp, lt, ld = small_case(41, K=2)
+    d2t = inp["d2t"]
+    shared = np.nonzero(d2t >= 0)[0]
+    unshared = np.nonzero(d2t < 0)[0]
+    tok = np.full((1, 2), shared[0], np.int32)
+    # bad drafts: -1, out of range, unshared
+    for bad in (-1, 10 ** 6, int(unshared[0])):
+        t2 = tok.copy()
+        t2[0, 1] = bad
+        v = oracle.verify(lt, ld, 1.0, 1.0, d2t, t2, np.zeros((1, 2)), [0.6], want_weights=True)
+        assert v["status"][0] == oracle.BAD_DRAFT and v["n_acc"][0] == 1
+        np.testing.assert_allclose(v["fin_weights"][0], ref_softmax(lt[0, 1], 1.0), rtol=1e-12)
+    # NaN / +inf in a target row
+    for val in (np.nan, np.inf):
+        l2 = lt.copy()
+        l2[0, 1, 5] = val
+        v = oracle.verify(l2, ld, 1.0, 1.0, d2t, tok, np.zeros((1, 2)), [0.6])
+        assert v["status"][0] & oracle.NONFINITE and v["n_acc"][0] == 0 and np.all(v["out_tok"] == -1)
+    # -inf logits are legal and get probability zero
+    l2 = lt.copy()
+    l2[0, 0, :10] = -np.inf
+    v = oracle.verify(l2, ld, 1.0, 1.0, d2t, tok, np.zeros((1, 2)), [0.0])
+    assert v["status"][0] == 0
+    p, _, _ = oracle.softmax(l2[0, 0], 1.0)
+    assert np.all(p[:10] == 0) and abs(p.sum() - 1) < 1e-12
+    # drafter row: shared NaN flags, shared all -inf = zero mass
+    d2 = ld.copy()
+    d2[0, 0, shared[2]] = np.nan
+    ds = oracle.draft_sample(d2[0], 1.0, d2t, [0.1, 0.1])
+    assert ds["status"][0] == oracle.NONFINITE and ds["tok_d"][0] == -1 and ds["status"][1] == 0
+    d2 = ld.copy()
+    d2[0, 1, shared] = -np.inf
+    ds = oracle.draft_sample(d2[0], 1.0, d2t, [0.1, 0.1])
+    assert ds["status"][1] == oracle.ZERO_MASS and ds["tok_t"][1] == -1 and ds["lse_q"][1] == -np.inf
