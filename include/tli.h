@@ -1,0 +1,129 @@
+/*
+ * tli.h -- C ABI of the MI355X (gfx950) Token-Level Intersection draft-and-verify library.
+ *
+ * One iteration of speculative decoding for heterogeneous vocabularies by token-level intersection:
+ * the drafter distribution q over vocabulary D is restricted to the tokens it shares with the target
+ * vocabulary T and renormalised (q'), K draft tokens are drawn from q', and the target's K+1
+ * distributions p verify them with the lossless rejection rule of standard speculative decoding.
+ * (Paper: section "Speculative Decoding for Heterogeneous Vocabularies with Token-Level Verification",
+ * the intersection algorithm; appendix "Standard Speculative Decoding".)
+ *
+ * Conventions shared by every entry point
+ *   - "dev" pointers are device pointers on the device that was current when the map was built;
+ *     "host" pointers are ordinary host memory.  The library never takes ownership of a buffer the
+ *     caller passes; it owns only the tli_map object.
+ *   - Logits stand for distributions: p = softmax(logits_t / temp_t) over T, q = softmax(logits_d /
+ *     temp_d) over D.  Logit storage is fp32 or bf16 (tli_dtype); all arithmetic is fp32 with fp64
+ *     combination of partial sums and fp64 scalar decisions.
+ *   - Logit base pointers must be 16-byte aligned and every row must start on a 16-byte boundary
+ *     (row strides are multiples of 4 fp32 / 8 bf16 elements).  -inf logits are legal (probability 0).
+ *   - Randomness is supplied by the caller as fp32 uniforms in [0,1).
+ *   - Inverse-CDF sampling walks ids in ascending order and returns the first id whose running sum
+ *     exceeds u * total (strict), so zero-probability ids are never returned.
+ *   - The hot calls (tli_draft_sample, tli_verify) only enqueue kernels on the given HIP stream: no
+ *     allocation, no synchronisation.  On a non-zero return nothing was enqueued.
+ *   - Data-dependent trouble is reported per row / per sequence as TLI_FLAG_* bits, never by aborting.
+ */
+#ifndef TLI_H
+#define TLI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tli_map tli_map; /* opaque, device-resident vocabulary intersection */
+
+typedef enum { TLI_F32 = 0, TLI_BF16 = 1 } tli_dtype;
+
+typedef enum {
+    TLI_OK = 0,
+    TLI_ERR_INVALID_ARG = -1,        /* null pointer, non-positive size or temperature, bad alignment */
+    TLI_ERR_OUT_OF_RANGE = -2,       /* a d2t entry is neither -1 nor in [0, Vt)                       */
+    TLI_ERR_NOT_INJECTIVE = -3,      /* two drafter ids map to the same target id                      */
+    TLI_ERR_EMPTY_INTERSECTION = -4, /* no shared token: q' would be 0/0 and nothing can be accepted   */
+    TLI_ERR_ALLOC = -5,              /* device allocation failed, or the workspace is too small        */
+    TLI_ERR_HIP = -6                 /* a HIP runtime call failed                                      */
+} tli_status;
+
+/* bits of row_status / seq_status */
+enum {
+    TLI_FLAG_NONFINITE = 1,  /* a logit that takes part in the computation is NaN or +inf           */
+    TLI_FLAG_ZERO_MASS = 2,  /* the shared ids of a drafter row carry no mass (all -inf)            */
+    TLI_FLAG_BAD_DRAFT = 4,  /* a draft id given to tli_verify is not a shared drafter id (or -1)   */
+    TLI_FLAG_DEGENERATE = 8  /* rejected, but the residual is identically zero; extra token from p  */
+};
+
+/*
+ * Vocabulary intersection T∩D (the paper treats vocabularies as sets of strings; two tokens are
+ * shared iff their strings are equal, which the caller resolves into d2t).
+ *   d2t_host [Vd] host : target id of drafter id x, or -1 if x is not in T.  Must be injective on
+ *                        the ids it maps.
+ *   out_map            : receives the new map (tables live on the current HIP device).
+ *   out_num_shared     : receives |T∩D| (may be NULL).
+ * All argument checks run before the first HIP call, so every TLI_ERR_* except ALLOC/HIP can be
+ * returned on a machine without a GPU.  Synchronous.  Free with tli_free_map.
+ */
+int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out_map, int32_t* out_num_shared);
+void tli_free_map(tli_map* map);
+/* Vd, Vt and |T∩D| of a map (any pointer may be NULL). */
+int tli_map_info(const tli_map* map, int32_t* Vd, int32_t* Vt, int32_t* num_shared);
+
+/*
+ * Bytes of device scratch that tli_draft_sample (with R <= B*K rows) and tli_verify (with these B, K)
+ * need for vocabularies of these sizes.  The caller allocates it (256-byte aligned) and may reuse it
+ * across calls on one stream.  Returns 0 on invalid arguments.
+ */
+size_t tli_workspace_bytes(int32_t B, int32_t K, int32_t Vt, int32_t Vd, tli_dtype dtype);
+
+/*
+ * Draft step of the intersection algorithm: for each of R independent drafter rows build
+ * q'(x) = q(x) / sum_{t in T∩D} q(t) on shared ids (0 elsewhere) and draw one token from it.
+ *   logits_d   dev [R rows, row_stride_elems apart, Vd valid entries each]
+ *   u_draft    dev [R] fp32 in [0,1)
+ *   tok_d      dev [R] int32  sampled drafter id            (-1 if the row is flagged)
+ *   tok_t      dev [R] int32  the same token's target id    (-1 if the row is flagged)
+ *   q_tok      dev [R] fp64   q'(tok_d)                      (may be NULL)
+ *   lse_q      dev [R] fp64   log sum_{x shared} exp(logits_d[x]/temp_d): log q'(x) = logit/temp - lse_q
+ *   row_status dev [R] int32  TLI_FLAG_NONFINITE / TLI_FLAG_ZERO_MASS, else 0
+ * Unshared drafter logits are never inspected.
+ */
+int tli_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems,
+                     int32_t R, float temp_d, const float* u_draft, int32_t* tok_d, int32_t* tok_t,
+                     double* q_tok, double* lse_q, int32_t* row_status, void* workspace,
+                     size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Verification step (standard speculative decoding run with p and q'): every position k tests its
+ * draft d_k with "accept iff u_acc * q'_k(d_k) < p_k(d_k)" (probability min(1, p/q')); n_accepted is
+ * the length of the all-accept prefix; the extra token comes from the residual
+ * norm(max(0, p_j - q'_j)) of the first rejected position j, or from p_{K+1} if nothing was rejected.
+ *   logits_t   dev [B, K+1, Vt] dense      logits_d dev [B, K, Vd] dense
+ *   tok_d      dev [B,K] int32 draft ids in DRAFTER id space (as returned by tli_draft_sample)
+ *   lse_q      dev [B,K] fp64  as returned by tli_draft_sample for the same rows
+ *   u_acc      dev [B,K] fp32, u_fin dev [B] fp32
+ *   n_accepted dev [B]     int32
+ *   out_tok    dev [B,K+1] int32 : n_accepted target ids, then the extra token, then -1 padding
+ *   accept     dev [B,K]   uint8 : outcome of each position's own test (may be NULL)
+ *   p_tok,q_tok dev [B,K]  fp64  : p_k(d_k), q'_k(d_k)                    (may be NULL)
+ *   lse_p      dev [B,K+1] fp64  : log-normalisers of the target rows; entry K is NaN unless the
+ *                                  bonus row was used (may be NULL)
+ *   seq_status dev [B]     int32 : TLI_FLAG_* bits.  A draft id that is -1, out of range or unshared is
+ *                                  rejected with q' = 0 (BAD_DRAFT): the extra token is then drawn from
+ *                                  p_j itself.  NONFINITE sequences return n_accepted 0, out_tok -1.
+ */
+int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype, int32_t B,
+               int32_t K, float temp_t, float temp_d, const int32_t* tok_d, const double* lse_q,
+               const float* u_acc, const float* u_fin, int32_t* n_accepted, int32_t* out_tok,
+               uint8_t* accept, double* p_tok, double* q_tok, double* lse_p, int32_t* seq_status,
+               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Human-readable name of a tli_status value. */
+const char* tli_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TLI_H */

@@ -1,0 +1,190 @@
+"""Thin ctypes binding over the C ABI in include/tli.h (same names, argument marshalling only).
+
+torch is used for device buffers and the current HIP stream; every step of the path runs in the
+library's kernels.  There is no CPU fallback: if libtli.so is missing or fails to load, the first
+call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtli.so")
+
+TLI_F32, TLI_BF16 = 0, 1
+FLAG_NONFINITE, FLAG_ZERO_MASS, FLAG_BAD_DRAFT, FLAG_DEGENERATE = 1, 2, 4, 8
+
+EXPORTS = (
+    "tli_build_map", "tli_free_map", "tli_map_info", "tli_workspace_bytes", "tli_draft_sample", "tli_verify",
+    "tli_status_string",
+)
+
+_lib = None
+
+
+class TliError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} ({code})")
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libtli.so built in-tree (see build.py).  Raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2502_05202_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    lib.tli_build_map.argtypes = [vp, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(i32)]
+    lib.tli_build_map.restype = ctypes.c_int
+    lib.tli_free_map.argtypes = [vp]
+    lib.tli_free_map.restype = None
+    lib.tli_map_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.tli_map_info.restype = ctypes.c_int
+    lib.tli_workspace_bytes.argtypes = [i32, i32, i32, i32, ctypes.c_int]
+    lib.tli_workspace_bytes.restype = ctypes.c_size_t
+    lib.tli_draft_sample.argtypes = [vp, vp, ctypes.c_int, i64, i32, f32, vp, vp, vp, vp, vp, vp, vp,
+                                     ctypes.c_size_t, vp]
+    lib.tli_draft_sample.restype = ctypes.c_int
+    lib.tli_verify.argtypes = [vp, vp, vp, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                               vp, vp, vp, ctypes.c_size_t, vp]
+    lib.tli_verify.restype = ctypes.c_int
+    lib.tli_status_string.argtypes = [ctypes.c_int]
+    lib.tli_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load_library().tli_status_string(int(code)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return TLI_F32
+    if t.dtype == torch.bfloat16:
+        return TLI_BF16
+    raise TypeError(f"logits must be float32 or bfloat16, got {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+class TliMap:
+    """Owner of a tli_map (device tables of the vocabulary intersection)."""
+
+    def __init__(self, handle: int, Vd: int, Vt: int, num_shared: int):
+        self._h = ctypes.c_void_p(handle)
+        self.Vd, self.Vt, self.num_shared = Vd, Vt, num_shared
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise RuntimeError("tli_map already freed")
+        return self._h
+
+    def free(self):
+        if self._h is not None:
+            load_library().tli_free_map(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def tli_build_map(d2t, Vt: int) -> TliMap:
+    """d2t: host int32 array [Vd], target id of each drafter id or -1."""
+    lib = load_library()
+    arr = np.ascontiguousarray(np.asarray(d2t), dtype=np.int32)
+    out = ctypes.c_void_p()
+    S = ctypes.c_int32()
+    rc = lib.tli_build_map(arr.ctypes.data_as(ctypes.c_void_p), arr.shape[0], int(Vt), ctypes.byref(out),
+                           ctypes.byref(S))
+    if rc != 0:
+        raise TliError(rc, "tli_build_map")
+    return TliMap(out.value, int(arr.shape[0]), int(Vt), S.value)
+
+
+def tli_workspace_bytes(B: int, K: int, Vt: int, Vd: int, dtype: int) -> int:
+    return int(load_library().tli_workspace_bytes(B, K, Vt, Vd, dtype))
+
+
+def alloc_workspace(B: int, K: int, m: TliMap, dtype: int, device) -> torch.Tensor:
+    n = tli_workspace_bytes(B, K, m.Vt, m.Vd, dtype)
+    if n == 0:
+        raise TliError(-1, "tli_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def tli_draft_sample(m: TliMap, logits_d: torch.Tensor, temp_d: float, u_draft: torch.Tensor,
+                     workspace: torch.Tensor, out: dict | None = None, stream=None) -> dict:
+    """logits_d [..., Vd] with contiguous last dim; leading dims are flattened into R rows."""
+    lib = load_library()
+    assert logits_d.is_cuda and logits_d.stride(-1) == 1
+    ld = logits_d.reshape(-1, logits_d.shape[-1])
+    R, Vd = ld.shape
+    assert Vd == m.Vd and u_draft.numel() == R and u_draft.dtype == torch.float32 and u_draft.is_contiguous()
+    dev = ld.device
+    if out is None:
+        out = dict(tok_d=torch.empty(R, dtype=torch.int32, device=dev),
+                   tok_t=torch.empty(R, dtype=torch.int32, device=dev),
+                   q_tok=torch.empty(R, dtype=torch.float64, device=dev),
+                   lse_q=torch.empty(R, dtype=torch.float64, device=dev),
+                   status=torch.empty(R, dtype=torch.int32, device=dev))
+    rc = lib.tli_draft_sample(m.handle, _ptr(ld), _dtype_code(ld), ld.stride(0), R, float(temp_d), _ptr(u_draft),
+                              _ptr(out["tok_d"]), _ptr(out["tok_t"]), _ptr(out.get("q_tok")), _ptr(out["lse_q"]),
+                              _ptr(out["status"]), _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc != 0:
+        raise TliError(rc, "tli_draft_sample")
+    return out
+
+
+def alloc_verify_outputs(B: int, K: int, device) -> dict:
+    return dict(n_accepted=torch.empty(B, dtype=torch.int32, device=device),
+                out_tok=torch.empty((B, K + 1), dtype=torch.int32, device=device),
+                accept=torch.empty((B, K), dtype=torch.uint8, device=device),
+                p_tok=torch.empty((B, K), dtype=torch.float64, device=device),
+                q_tok=torch.empty((B, K), dtype=torch.float64, device=device),
+                lse_p=torch.empty((B, K + 1), dtype=torch.float64, device=device),
+                status=torch.empty(B, dtype=torch.int32, device=device))
+
+
+def tli_verify(m: TliMap, logits_t: torch.Tensor, logits_d: torch.Tensor, temp_t: float, temp_d: float,
+               tok_d: torch.Tensor, lse_q: torch.Tensor, u_acc: torch.Tensor, u_fin: torch.Tensor,
+               workspace: torch.Tensor, out: dict | None = None, stream=None) -> dict:
+    """logits_t [B,K+1,Vt], logits_d [B,K,Vd] dense; tok_d int32 [B,K]; lse_q float64 [B,K]."""
+    lib = load_library()
+    B, K1, Vt = logits_t.shape
+    K = K1 - 1
+    assert logits_t.is_cuda and logits_t.is_contiguous() and logits_d.is_contiguous()
+    assert tuple(logits_d.shape) == (B, K, m.Vd) and Vt == m.Vt and logits_t.dtype == logits_d.dtype
+    assert tok_d.dtype == torch.int32 and tok_d.numel() == B * K and tok_d.is_contiguous()
+    assert lse_q.dtype == torch.float64 and lse_q.numel() == B * K and lse_q.is_contiguous()
+    assert u_acc.dtype == torch.float32 and u_acc.numel() == B * K and u_acc.is_contiguous()
+    assert u_fin.dtype == torch.float32 and u_fin.numel() == B and u_fin.is_contiguous()
+    if out is None:
+        out = alloc_verify_outputs(B, K, logits_t.device)
+    rc = lib.tli_verify(m.handle, _ptr(logits_t), _ptr(logits_d), _dtype_code(logits_t), B, K, float(temp_t),
+                        float(temp_d), _ptr(tok_d), _ptr(lse_q), _ptr(u_acc), _ptr(u_fin), _ptr(out["n_accepted"]),
+                        _ptr(out["out_tok"]), _ptr(out.get("accept")), _ptr(out.get("p_tok")), _ptr(out.get("q_tok")),
+                        _ptr(out.get("lse_p")), _ptr(out["status"]), _ptr(workspace), workspace.numel(),
+                        _stream(stream))
+    if rc != 0:
+        raise TliError(rc, "tli_verify")
+    return out

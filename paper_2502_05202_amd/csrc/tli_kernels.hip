@@ -1,0 +1,937 @@
+// tli_kernels.hip -- gfx950 kernels and C ABI of the TLI draft-and-verify path.
+//
+// Path (paper: the token-level intersection algorithm + appendix "Standard Speculative Decoding"):
+//   draft : q' = softmax over the shared drafter ids (the drafter restricted to T∩D, renormalised),
+//           one inverse-CDF sample per row.
+//   verify: log-normaliser of each of the K target rows -> accept test per position -> first-reject
+//           scan -> extra token from the residual norm(max(0, p - q')) or from the bonus row.
+//
+// Every kernel here is a streaming scan of logit rows: HBM-bound, no dense contraction, no MFMA.
+// A row is cut into chunks of 64 lanes x 4 16-byte loads (2048 bf16 / 1024 fp32 elements); a wave
+// owns a chunk, keeps the next chunk's loads in flight while it works on the current one, and
+// reduces it to a pair (ref, s) with  sum_{x in chunk} 2^(logit_x * c) = s * 2^ref,  c = log2(e)/temp.
+// Chunk pairs are combined in fp64.  Samplers keep the per-chunk pairs, locate the chunk that
+// contains u * total and re-read only that chunk.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "tli.h"
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kWG = 256;
+constexpr int kWaves = kWG / kWave;
+constexpr int kLoads = 4;
+constexpr int kMaxK = 64;
+constexpr double kLn2 = 0.693147180559945309417232121458;
+constexpr double kLog2e = 1.44269504088896340735992468100;
+
+template <int DT> struct Traits;
+template <> struct Traits<TLI_F32> {
+    static constexpr int EPV = 4;  // elements per 16-byte vector
+    static constexpr int ESZ = 4;
+};
+template <> struct Traits<TLI_BF16> {
+    static constexpr int EPV = 8;
+    static constexpr int ESZ = 2;
+};
+template <int DT> constexpr int chunk_elems() { return kWave * kLoads * Traits<DT>::EPV; }
+
+__device__ inline float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ inline uint32_t as_u(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+template <int DT> __device__ inline void unpack(const uint4& v, float* x);
+template <> __device__ inline void unpack<TLI_F32>(const uint4& v, float* x) {
+    x[0] = as_f(v.x); x[1] = as_f(v.y); x[2] = as_f(v.z); x[3] = as_f(v.w);
+}
+template <> __device__ inline void unpack<TLI_BF16>(const uint4& v, float* x) {
+    x[0] = as_f(v.x << 16); x[1] = as_f(v.x & 0xffff0000u);
+    x[2] = as_f(v.y << 16); x[3] = as_f(v.y & 0xffff0000u);
+    x[4] = as_f(v.z << 16); x[5] = as_f(v.z & 0xffff0000u);
+    x[6] = as_f(v.w << 16); x[7] = as_f(v.w & 0xffff0000u);
+}
+
+template <int DT> __device__ inline float load_elem(const void* base, int64_t idx);
+template <> __device__ inline float load_elem<TLI_F32>(const void* base, int64_t idx) {
+    return static_cast<const float*>(base)[idx];
+}
+template <> __device__ inline float load_elem<TLI_BF16>(const void* base, int64_t idx) {
+    return as_f(static_cast<uint32_t>(static_cast<const uint16_t*>(base)[idx]) << 16);
+}
+
+// ---- wave64 reductions on the DPP network (result broadcast through an SGPR) -------------------
+template <int CTRL, int ROW_MASK> __device__ inline float dpp(float old, float v) {
+    return as_f(__builtin_amdgcn_update_dpp(as_u(old), as_u(v), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ inline float wave_sum(float v) {
+    v += dpp<0xB1, 0xF>(0.f, v);   // quad_perm [1,0,3,2]
+    v += dpp<0x4E, 0xF>(0.f, v);   // quad_perm [2,3,0,1]
+    v += dpp<0x124, 0xF>(0.f, v);  // row_ror 4
+    v += dpp<0x128, 0xF>(0.f, v);  // row_ror 8
+    v += dpp<0x142, 0xA>(0.f, v);  // row_bcast 15 into rows 1,3
+    v += dpp<0x143, 0xC>(0.f, v);  // row_bcast 31 into rows 2,3
+    return as_f(__builtin_amdgcn_readlane(as_u(v), 63));
+}
+__device__ inline float wave_max(float v) {
+    const float ninf = -INFINITY;
+    v = fmaxf(v, dpp<0xB1, 0xF>(ninf, v));
+    v = fmaxf(v, dpp<0x4E, 0xF>(ninf, v));
+    v = fmaxf(v, dpp<0x124, 0xF>(ninf, v));
+    v = fmaxf(v, dpp<0x128, 0xF>(ninf, v));
+    v = fmaxf(v, dpp<0x142, 0xA>(ninf, v));
+    v = fmaxf(v, dpp<0x143, 0xC>(ninf, v));
+    return as_f(__builtin_amdgcn_readlane(as_u(v), 63));
+}
+
+__device__ inline float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---- chunk loads ------------------------------------------------------------------------------
+// Chunk c of a row = vectors [c*256, c*256+256); load j of lane l is vector c*256 + j*64 + l.
+struct ChunkRegs {
+    uint4 v[kLoads];
+};
+
+template <int DT>
+__device__ inline void load_chunk(const uint4* rowv, int64_t c, int lane, int nvec, ChunkRegs& r) {
+    const uint4 ninf = (DT == TLI_BF16) ? make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u)
+                                        : make_uint4(0xff800000u, 0xff800000u, 0xff800000u, 0xff800000u);
+    const int64_t v0 = c * (kWave * kLoads) + lane;
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+        const int64_t vi = v0 + j * kWave;
+        r.v[j] = (vi < nvec) ? rowv[vi] : ninf;  // whole chunks never take the second arm
+    }
+}
+
+// Bits of the shared-id mask for the EPV elements of vector vi.
+template <int DT> __device__ inline uint32_t mask_bits(const uint8_t* bits, int64_t vi) {
+    if (DT == TLI_BF16) return bits[vi];
+    return (bits[vi >> 1] >> ((vi & 1) * 4)) & 0xFu;
+}
+
+// Reduce one chunk held in registers to (ref, s): sum 2^(x*c) over the chunk = s * 2^ref, with
+// ref = max over the chunk of fp32(x*c) (-inf and s = 0 for a chunk without finite entries).
+// A NaN or +inf logit turns s into NaN.  Wave-uniform results.
+template <int DT, bool MASKED>
+__device__ inline void reduce_chunk(const ChunkRegs& r, int64_t c, int lane, int V, float cs,
+                                    const uint8_t* bits, float& ref_out, float& s_out) {
+    constexpr int EPV = Traits<DT>::EPV;
+    constexpr int N = EPV * kLoads;
+    float x[N];
+    const int64_t v0 = c * (kWave * kLoads) + lane;
+    const bool whole = (c + 1) * (int64_t)chunk_elems<DT>() <= V;
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+        unpack<DT>(r.v[j], x + j * EPV);
+        const int64_t vi = v0 + j * kWave;
+        if (!whole) {
+#pragma unroll
+            for (int i = 0; i < EPV; ++i)
+                if (vi * EPV + i >= V) x[j * EPV + i] = -INFINITY;
+        }
+        if (MASKED) {
+            const uint32_t mb = (vi * EPV < V) ? mask_bits<DT>(bits, vi) : 0u;
+#pragma unroll
+            for (int i = 0; i < EPV; ++i)
+                if (!((mb >> i) & 1u)) x[j * EPV + i] = -INFINITY;
+        }
+    }
+    float m = x[0];
+#pragma unroll
+    for (int i = 1; i < N; ++i) m = fmaxf(m, x[i]);
+    const float ref = m * cs;
+    const float nref = (m == -INFINITY) ? 0.f : -ref;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[i & 3] += exp2_hw(fmaf(x[i], cs, nref));
+    float s = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    const float R = wave_max(ref);
+    s = (m == -INFINITY) ? 0.f : s * exp2_hw(ref - R);
+    ref_out = R;
+    s_out = wave_sum(s);
+}
+
+// running (ref, sum) of a wave, sum kept in fp64
+struct Running {
+    float ref = -INFINITY;
+    double s = 0.0;
+    __device__ inline void add(float r, float sc) {
+        const float nr = fmaxf(ref, r);
+        if (nr == -INFINITY) return;
+        const float a = (ref == -INFINITY) ? 0.f : exp2_hw(ref - nr);
+        const float b = (r == -INFINITY) ? 0.f : exp2_hw(r - nr);
+        s = s * (double)a + (double)sc * (double)b;
+        ref = nr;
+    }
+};
+
+struct Part {  // partial log-normaliser of (a split of) a row: sum 2^(x*c) = s * 2^ref
+    float ref;
+    float pad;
+    double s;
+};
+
+__device__ inline double exp2_diff(float a, float b) {  // 2^(a-b) in fp64, 0 if a = -inf
+    return (a == -INFINITY) ? 0.0 : exp2((double)a - (double)b);
+}
+
+// ---- kernel: log-normaliser partials of the K target rows each sequence needs -----------------
+// Standard SD appendix, verification loop: p_k(d_k) needs the normaliser of every target row k < K.
+// grid (rows * nsplit); row r = (b, k) with b = r / K, k = r % K.
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, int K, int64_t seq_stride,
+                                              int64_t row_stride, int V, int nC, int cps, int nsplit, float cs,
+                                              Part* __restrict__ part) {
+    constexpr int EPV = Traits<DT>::EPV;
+    const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
+    const int b = row / K, k = row - b * K;
+    const uint4* rowv = reinterpret_cast<const uint4*>(static_cast<const char*>(logits) +
+                                                        (b * seq_stride + k * row_stride) * Traits<DT>::ESZ);
+    const int nvec = (V + EPV - 1) / EPV;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int c_end = min(nC, (split + 1) * cps);
+    Running run;
+    ChunkRegs cur, nxt;
+    int c = split * cps + wave;
+    if (c < c_end) load_chunk<DT>(rowv, c, lane, nvec, cur);
+    for (; c < c_end; c += kWaves) {
+        const bool more = c + kWaves < c_end;
+        if (more) load_chunk<DT>(rowv, c + kWaves, lane, nvec, nxt);
+        float r, s;
+        reduce_chunk<DT, false>(cur, c, lane, V, cs, nullptr, r, s);
+        run.add(r, s);
+        if (more) cur = nxt;
+    }
+    __shared__ float sref[kWaves];
+    __shared__ double ssum[kWaves];
+    if (lane == 0) { sref[wave] = run.ref; ssum[wave] = run.s; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float R = sref[0];
+        for (int w = 1; w < kWaves; ++w) R = fmaxf(R, sref[w]);
+        double S = 0.0;
+        for (int w = 0; w < kWaves; ++w) S += ssum[w] * exp2_diff(sref[w], R);
+        Part p; p.ref = R; p.pad = 0.f; p.s = S;
+        part[(int64_t)row * nsplit + split] = p;
+    }
+}
+
+// ---- kernel: per-chunk (ref, s) table of a softmax row, optionally masked to the shared ids ----
+// Used for drafter rows (masked: the intersection algorithm's q') and for the bonus target row.
+// Workgroup `split` of a row owns chunks [split*cps, (split+1)*cps).
+template <int DT, bool MASKED>
+__device__ inline void table_scan(const uint4* rowv, int split, int V, int nC, int cps, float cs, const uint8_t* bits,
+                                  float* tab_ref, float* tab_s) {
+    constexpr int EPV = Traits<DT>::EPV;
+    const int nvec = (V + EPV - 1) / EPV;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int c_end = min(nC, (split + 1) * cps);
+    ChunkRegs cur, nxt;
+    int c = split * cps + wave;
+    if (c < c_end) load_chunk<DT>(rowv, c, lane, nvec, cur);
+    for (; c < c_end; c += kWaves) {
+        const bool more = c + kWaves < c_end;
+        if (more) load_chunk<DT>(rowv, c + kWaves, lane, nvec, nxt);
+        float r, s;
+        reduce_chunk<DT, MASKED>(cur, c, lane, V, cs, bits, r, s);
+        if (lane == 0) { tab_ref[c] = r; tab_s[c] = s; }
+        if (more) cur = nxt;
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_draft_scan(const void* __restrict__ logits, int64_t row_stride, int V,
+                                                     int nC, int cps, int nsplit, float cs,
+                                                     const uint8_t* __restrict__ bits, float* __restrict__ tab_ref,
+                                                     float* __restrict__ tab_s) {
+    const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
+    const uint4* rowv = reinterpret_cast<const uint4*>(static_cast<const char*>(logits) +
+                                                        (int64_t)row * row_stride * Traits<DT>::ESZ);
+    table_scan<DT, true>(rowv, split, V, nC, cps, cs, bits, tab_ref + (int64_t)row * nC, tab_s + (int64_t)row * nC);
+}
+
+// ---- block-level helpers for the pick kernels (256 threads) ----------------------------------
+struct PickShared {
+    double wsum[kWaves];
+    float wmax[kWaves];
+    int cand;
+    int last_pos;
+    double theta_local;
+    double total;
+};
+
+__device__ inline float block_max(float v, PickShared& sh) {
+    v = wave_max(v);
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh.wmax[wave] = v;
+    __syncthreads();
+    float m = sh.wmax[0];
+    for (int w = 1; w < kWaves; ++w) m = fmaxf(m, sh.wmax[w]);
+    return m;
+}
+
+// exclusive prefix of v over the block's threads in fp64; *total = block sum
+__device__ inline double block_excl_scan(double v, PickShared& sh, double* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    double inc = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const double t = __shfl_up(inc, d, kWave);
+        if (lane >= d) inc += t;
+    }
+    __syncthreads();
+    if (lane == kWave - 1) sh.wsum[wave] = inc;
+    __syncthreads();
+    double base = 0.0, tot = 0.0;
+    for (int w = 0; w < kWaves; ++w) {
+        if (w < wave) base += sh.wsum[w];
+        tot += sh.wsum[w];
+    }
+    *total = tot;
+    return base + (inc - v);
+}
+
+// Chunk search.  T_c (fp64 chunk masses) for this thread's contiguous chunks [c0, c1) are produced
+// by `mass(c)`.  Returns the first chunk whose inclusive prefix exceeds theta = u * total and
+// theta - (prefix before that chunk); -1 if total is not positive.  *total_out = total.
+template <class MassFn>
+__device__ inline int find_chunk(int nC, double u, MassFn mass, PickShared& sh, double* theta_local,
+                                 double* total_out) {
+    const int per = (nC + kWG - 1) / kWG;
+    const int c0 = min(nC, (int)threadIdx.x * per), c1 = min(nC, c0 + per);
+    double mine = 0.0;
+    for (int c = c0; c < c1; ++c) mine += mass(c);
+    double total;
+    const double excl = block_excl_scan(mine, sh, &total);
+    *total_out = total;
+    if (!(total > 0.0)) return -1;  // zero, negative or NaN
+    const double theta = u * total;
+    if (threadIdx.x == 0) { sh.cand = 0x7fffffff; sh.last_pos = -1; }
+    __syncthreads();
+    double run = excl;
+    int found = -1;
+    double before = 0.0;
+    int last_pos = -1;
+    for (int c = c0; c < c1; ++c) {
+        const double t = mass(c);
+        if (t > 0.0) last_pos = c;
+        if (found < 0 && run + t > theta) { found = c; before = run; }
+        run += t;
+    }
+    if (found >= 0) atomicMin(&sh.cand, found);
+    if (last_pos >= 0) atomicMax(&sh.last_pos, last_pos);
+    __syncthreads();
+    int pick = sh.cand;
+    const bool none = (pick == 0x7fffffff);
+    if (none) pick = sh.last_pos;  // rounding left no crossing: last chunk with mass, take its last id
+    __syncthreads();
+    if (found == pick && found >= 0) sh.theta_local = theta - before;
+    if (none && threadIdx.x == 0) sh.theta_local = INFINITY;
+    __syncthreads();
+    *theta_local = sh.theta_local;
+    return pick;
+}
+
+// In-chunk search: thread t holds the weights of elements [e0, e0+N) in order.  Returns the first
+// element whose inclusive prefix exceeds theta_local; if none, the last element with weight > 0.
+template <int N>
+__device__ inline int find_in_chunk(const double (&w)[N], int64_t e0, double theta_local, PickShared& sh) {
+    double mine = 0.0;
+#pragma unroll
+    for (int i = 0; i < N; ++i) mine += w[i];
+    double total;
+    const double excl = block_excl_scan(mine, sh, &total);
+    if (threadIdx.x == 0) { sh.cand = 0x7fffffff; sh.last_pos = -1; }
+    __syncthreads();
+    double run = excl;
+    int found = -1, last_pos = -1;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        run += w[i];
+        if (w[i] > 0.0) last_pos = (int)(e0 + i);
+        if (found < 0 && run > theta_local) found = (int)(e0 + i);
+    }
+    if (found >= 0) atomicMin(&sh.cand, found);
+    if (last_pos >= 0) atomicMax(&sh.last_pos, last_pos);
+    __syncthreads();
+    const int pick = (sh.cand == 0x7fffffff) ? sh.last_pos : sh.cand;
+    __syncthreads();
+    return pick;
+}
+
+// weights of one 16-byte vector of a softmax row relative to reference `nref` (= -ref), as in
+// reduce_chunk: 2^(x*c - ref); elements >= V or masked out get 0.
+template <int DT, bool MASKED>
+__device__ inline void softmax_vec_weights(const uint4* rowv, int64_t vi, int V, float cs, float nref,
+                                           const uint8_t* bits, double* w) {
+    constexpr int EPV = Traits<DT>::EPV;
+    float x[EPV];
+    if (vi * EPV < V) {
+        unpack<DT>(rowv[vi], x);
+        const uint32_t mb = MASKED ? mask_bits<DT>(bits, vi) : 0xffu;
+#pragma unroll
+        for (int i = 0; i < EPV; ++i) {
+            const bool live = (vi * EPV + i < V) && ((mb >> i) & 1u);
+            w[i] = live ? (double)exp2_hw(fmaf(x[i], cs, nref)) : 0.0;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < EPV; ++i) w[i] = 0.0;
+    }
+}
+
+// ---- kernel: draw the draft token of each drafter row from its chunk table ---------------------
+// Standard SD appendix, drafting loop, with q' of the intersection algorithm.  grid (R).
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_draft_pick(const void* __restrict__ logits, int64_t row_stride, int V,
+                                                     int nC, float cs, double c_ratio, double inv_temp,
+                                                     const uint8_t* __restrict__ bits,
+                                                     const int32_t* __restrict__ d2t,
+                                                     const float* __restrict__ tab_ref,
+                                                     const float* __restrict__ tab_s,
+                                                     const float* __restrict__ u_draft, int32_t* __restrict__ tok_d,
+                                                     int32_t* __restrict__ tok_t, double* __restrict__ q_tok,
+                                                     double* __restrict__ lse_q, int32_t* __restrict__ row_status) {
+    constexpr int EPV = Traits<DT>::EPV;
+    __shared__ PickShared sh;
+    const int row = blockIdx.x;
+    const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
+    const uint4* rowv = reinterpret_cast<const uint4*>(rowp);
+    const float* tr = tab_ref + (int64_t)row * nC;
+    const float* ts = tab_s + (int64_t)row * nC;
+    float m = -INFINITY;
+    for (int c = threadIdx.x; c < nC; c += kWG) m = fmaxf(m, tr[c]);
+    const float M = block_max(m, sh);
+    double theta_local, total;
+    const int c = find_chunk(nC, (double)u_draft[row],
+                             [&](int cc) { return (double)ts[cc] * exp2_diff(tr[cc], M); }, sh, &theta_local, &total);
+    if (c < 0) {  // no usable mass: NaN/+inf among the shared logits, or all of them -inf
+        if (threadIdx.x == 0) {
+            const bool nonfinite = (total != total) || (M == INFINITY);
+            tok_d[row] = -1; tok_t[row] = -1;
+            if (q_tok) q_tok[row] = 0.0;
+            lse_q[row] = nonfinite ? NAN : -INFINITY;
+            row_status[row] = nonfinite ? TLI_FLAG_NONFINITE : TLI_FLAG_ZERO_MASS;
+        }
+        return;
+    }
+    double w[EPV];
+    const int64_t vi = (int64_t)c * (kWave * kLoads) + threadIdx.x;
+    softmax_vec_weights<DT, true>(rowv, vi, V, cs, -M, bits, w);
+    const int d = find_in_chunk<EPV>(w, vi * EPV, theta_local, sh);
+    if (threadIdx.x == 0) {
+        const double lse = kLn2 * ((double)M * c_ratio + log2(total));
+        tok_d[row] = d;
+        tok_t[row] = d2t[d];
+        lse_q[row] = lse;
+        if (q_tok) q_tok[row] = exp((double)load_elem<DT>(rowp, d) * inv_temp - lse);
+        row_status[row] = 0;
+    }
+}
+
+// ---- kernel: accept tests and first-reject scan ------------------------------------------------
+// Standard SD appendix, verification loop and the count of accepted drafts.  grid (B), 64 threads;
+// lane k owns position k.
+template <int DT>
+__global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logits_t, const void* __restrict__ logits_d,
+                                                   int K, int Vt, int Vd, int nsplit, const Part* __restrict__ part,
+                                                   double ratio_t, double inv_temp_t, double inv_temp_d,
+                                                   const int32_t* __restrict__ d2t, const int32_t* __restrict__ tok_d,
+                                                   const double* __restrict__ lse_q, const float* __restrict__ u_acc,
+                                                   int32_t* __restrict__ n_accepted, int32_t* __restrict__ out_tok,
+                                                   uint8_t* __restrict__ accept, double* __restrict__ p_tok,
+                                                   double* __restrict__ q_tok, double* __restrict__ lse_p,
+                                                   int32_t* __restrict__ seq_status, double* __restrict__ ws_lse_p) {
+    const int b = blockIdx.x, k = threadIdx.x;
+    bool acc = true, nonfinite = false, bad = false;
+    int tt = -1;
+    if (k < K) {
+        const int64_t row = (int64_t)b * K + k;
+        const Part* pr = part + row * nsplit;
+        float R = pr[0].ref;
+        for (int s = 1; s < nsplit; ++s) R = fmaxf(R, pr[s].ref);
+        double S = 0.0;
+        for (int s = 0; s < nsplit; ++s) S += pr[s].s * exp2_diff(pr[s].ref, R);
+        nonfinite = (S != S) || (R == INFINITY);
+        const double lse = kLn2 * ((double)R * ratio_t + log2(S));
+        ws_lse_p[row] = lse;
+        if (lse_p) lse_p[(int64_t)b * (K + 1) + k] = lse;
+        const int d = tok_d[row];
+        double pd = 0.0, qd = 0.0;
+        acc = false;
+        if (d < 0 || d >= Vd || d2t[d] < 0) {
+            bad = true;
+        } else if (!nonfinite) {
+            tt = d2t[d];
+            const char* lt = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + k) * Vt * Traits<DT>::ESZ;
+            const char* ld = static_cast<const char*>(logits_d) + row * Vd * Traits<DT>::ESZ;
+            pd = exp((double)load_elem<DT>(lt, tt) * inv_temp_t - lse);
+            qd = exp((double)load_elem<DT>(ld, d) * inv_temp_d - lse_q[row]);
+            acc = (double)u_acc[row] * qd < pd;
+        }
+        if (accept) accept[row] = acc ? 1 : 0;
+        if (p_tok) p_tok[row] = pd;
+        if (q_tok) q_tok[row] = qd;
+    }
+    const unsigned long long rej = __ballot(k < K && !acc);
+    const bool any_nonfinite = __ballot(nonfinite) != 0ull;
+    const bool any_bad = __ballot(bad) != 0ull;
+    int n = rej ? (int)__builtin_ctzll(rej) : K;
+    if (any_nonfinite) n = 0;
+    if (k < K) out_tok[(int64_t)b * (K + 1) + k] = (k < n) ? tt : -1;
+    if (k == 0) {
+        out_tok[(int64_t)b * (K + 1) + K] = -1;
+        n_accepted[b] = n;
+        seq_status[b] = (any_nonfinite ? TLI_FLAG_NONFINITE : 0) | (any_bad ? TLI_FLAG_BAD_DRAFT : 0);
+        if (lse_p) lse_p[(int64_t)b * (K + 1) + K] = NAN;
+    }
+}
+
+// ---- extra token: weights of one vector of the residual row -----------------------------------
+// Standard SD appendix, last step: r(t) ∝ p(t) - min(p(t), q'(t)) = max(0, p(t) - q'(t)); q'(t) is
+// the adjusted drafter's probability of the drafter id that maps to t (0 for target-only ids).
+// p and q' are evaluated as 2^(x*c - L) with c and L split into fp32 hi + lo parts, so both carry
+// about one ulp of error: the difference of two nearly equal probabilities must not inherit the
+// rounding of a large exponent.
+struct ResidualParams {
+    float ct_hi, ct_lo, lp_hi, lp_lo;  // target: exponent = x*ct - Lp
+    float cd_hi, cd_lo, lq_hi, lq_lo;  // drafter
+    bool use_q;
+};
+
+__device__ inline void split_hi_lo(double v, float& hi, float& lo) {
+    hi = (float)v;
+    lo = (float)(v - (double)hi);
+}
+
+template <int DT>
+__device__ inline void residual_vec(const uint4& v, int64_t e0, int V, const ResidualParams& rp,
+                                    const int32_t* __restrict__ t2d, const void* __restrict__ ld_row, float* p,
+                                    float* w) {
+    constexpr int EPV = Traits<DT>::EPV;
+    float x[EPV];
+    unpack<DT>(v, x);
+    int32_t d[EPV];
+    if (rp.use_q && e0 < V) {
+#pragma unroll
+        for (int i = 0; i < EPV; i += 4) {
+            const int4 t = *reinterpret_cast<const int4*>(t2d + e0 + i);  // t2d is padded to a multiple of 8
+            d[i] = t.x; d[i + 1] = t.y; d[i + 2] = t.z; d[i + 3] = t.w;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < EPV; ++i) {
+        const bool live = e0 + i < V;
+        float pi = exp2_hw(fmaf(x[i], rp.ct_hi, -rp.lp_hi) + fmaf(x[i], rp.ct_lo, -rp.lp_lo));
+        pi = live ? pi : 0.f;
+        float qi = 0.f;
+        if (rp.use_q && live && d[i] >= 0) {
+            const float y = load_elem<DT>(ld_row, d[i]);
+            qi = exp2_hw(fmaf(y, rp.cd_hi, -rp.lq_hi) + fmaf(y, rp.cd_lo, -rp.lq_lo));
+        }
+        p[i] = pi;
+        w[i] = fmaxf(0.f, pi - qi);
+        if (qi != qi) w[i] = qi;  // NaN in the drafter row must surface (fmaxf would drop it)
+    }
+}
+
+struct FinalRow {
+    bool skip;      // sequence is flagged NONFINITE
+    bool bonus;     // nothing rejected: sample from p of row K
+    int n;          // accepted count = index of the row the extra token comes from
+    ResidualParams rp;
+};
+
+template <int DT>
+__device__ inline FinalRow final_row(int b, int K, int Vd, const int32_t* n_accepted, const int32_t* seq_status,
+                                     const int32_t* tok_d, const int32_t* d2t, const double* ws_lse_p,
+                                     const double* lse_q, double c_t, double c_d) {
+    FinalRow f;
+    f.skip = (seq_status[b] & TLI_FLAG_NONFINITE) != 0;
+    f.n = n_accepted[b];
+    f.bonus = (f.n == K);
+    f.rp.use_q = false;
+    if (f.skip || f.bonus) return f;
+    const int64_t row = (int64_t)b * K + f.n;
+    split_hi_lo(c_t, f.rp.ct_hi, f.rp.ct_lo);
+    split_hi_lo(ws_lse_p[row] * kLog2e, f.rp.lp_hi, f.rp.lp_lo);
+    const int d = tok_d[row];
+    if (d >= 0 && d < Vd && d2t[d] >= 0) {
+        const double lq = lse_q[row];
+        if (lq > -INFINITY || lq != lq) {  // a zero-mass drafter row has q' = 0 everywhere
+            f.rp.use_q = true;
+            split_hi_lo(c_d, f.rp.cd_hi, f.rp.cd_lo);
+            split_hi_lo(lq * kLog2e, f.rp.lq_hi, f.rp.lq_lo);
+        }
+    }
+    return f;
+}
+
+// ---- kernel: chunk tables of the row the extra token is drawn from -----------------------------
+// grid (B * nsplit).  Bonus rows: (ref, s) softmax table.  Residual rows: tab_s = chunk sums of
+// max(0, p - q'), tab_p = chunk sums of p (used only if the residual is identically zero), ref = 0.
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_final_scan(const void* __restrict__ logits_t, const void* __restrict__ logits_d,
+                                                     int K, int Vt, int Vd, int nC, int cps, int nsplit, float cs_t,
+                                                     double c_t, double c_d, const int32_t* __restrict__ d2t,
+                                                     const int32_t* __restrict__ t2d, const int32_t* __restrict__ tok_d,
+                                                     const double* __restrict__ lse_q,
+                                                     const int32_t* __restrict__ n_accepted,
+                                                     const int32_t* __restrict__ seq_status,
+                                                     const double* __restrict__ ws_lse_p, float* __restrict__ tab_ref,
+                                                     float* __restrict__ tab_s, float* __restrict__ tab_p) {
+    constexpr int EPV = Traits<DT>::EPV;
+    const int b = blockIdx.x / nsplit, split = blockIdx.x - b * nsplit;
+    const FinalRow f = final_row<DT>(b, K, Vd, n_accepted, seq_status, tok_d, d2t, ws_lse_p, lse_q, c_t, c_d);
+    if (f.skip) return;
+    const char* rowp = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + f.n) * Vt * Traits<DT>::ESZ;
+    const uint4* rowv = reinterpret_cast<const uint4*>(rowp);
+    float* tr = tab_ref + (int64_t)b * nC;
+    float* ts = tab_s + (int64_t)b * nC;
+    float* tp = tab_p + (int64_t)b * nC;
+    if (f.bonus) {
+        table_scan<DT, false>(rowv, split, Vt, nC, cps, cs_t, nullptr, tr, ts);
+        return;
+    }
+    const char* ldp = static_cast<const char*>(logits_d) + ((int64_t)b * K + f.n) * Vd * Traits<DT>::ESZ;
+    const int nvec = (Vt + EPV - 1) / EPV;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int c_end = min(nC, (split + 1) * cps);
+    for (int c = split * cps + wave; c < c_end; c += kWaves) {
+        ChunkRegs r;
+        load_chunk<DT>(rowv, c, lane, nvec, r);
+        float sw = 0.f, sp = 0.f;
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            const int64_t vi = (int64_t)c * (kWave * kLoads) + j * kWave + lane;
+            float p[EPV], w[EPV];
+            residual_vec<DT>(r.v[j], vi * EPV, Vt, f.rp, t2d, ldp, p, w);
+            float a = 0.f, q = 0.f;
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) { a += w[i]; q += p[i]; }
+            sw += a; sp += q;
+        }
+        sw = wave_sum(sw);
+        sp = wave_sum(sp);
+        if (lane == 0) { tr[c] = 0.f; ts[c] = sw; tp[c] = sp; }
+    }
+}
+
+// ---- kernel: draw the extra token ------------------------------------------------------------
+// grid (B).  Writes out_tok[b, n_accepted[b]]; for bonus rows also lse_p[b, K].
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_final_pick(const void* __restrict__ logits_t, const void* __restrict__ logits_d,
+                                                     int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
+                                                     double c_t, double c_d, const int32_t* __restrict__ d2t,
+                                                     const int32_t* __restrict__ t2d, const int32_t* __restrict__ tok_d,
+                                                     const double* __restrict__ lse_q, const float* __restrict__ u_fin,
+                                                     const double* __restrict__ ws_lse_p,
+                                                     const float* __restrict__ tab_ref, const float* __restrict__ tab_s,
+                                                     const float* __restrict__ tab_p, int32_t* __restrict__ n_accepted,
+                                                     int32_t* __restrict__ out_tok, double* __restrict__ lse_p,
+                                                     int32_t* __restrict__ seq_status) {
+    constexpr int EPV = Traits<DT>::EPV;
+    __shared__ PickShared sh;
+    const int b = blockIdx.x;
+    const FinalRow f = final_row<DT>(b, K, Vd, n_accepted, seq_status, tok_d, d2t, ws_lse_p, lse_q, c_t, c_d);
+    if (f.skip) return;
+    const char* rowp = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + f.n) * Vt * Traits<DT>::ESZ;
+    const uint4* rowv = reinterpret_cast<const uint4*>(rowp);
+    const char* ldp = static_cast<const char*>(logits_d) + ((int64_t)b * K + min(f.n, K - 1)) * Vd * Traits<DT>::ESZ;
+    const float* tr = tab_ref + (int64_t)b * nC;
+    const float* ts = tab_s + (int64_t)b * nC;
+    const float* tp = tab_p + (int64_t)b * nC;
+    const double u = (double)u_fin[b];
+    int tok = -1;
+    int add_flags = 0;
+    bool nonfinite = false;
+    if (f.bonus) {
+        float m = -INFINITY;
+        for (int c = threadIdx.x; c < nC; c += kWG) m = fmaxf(m, tr[c]);
+        const float M = block_max(m, sh);
+        double theta_local, total;
+        const int c = find_chunk(nC, u, [&](int cc) { return (double)ts[cc] * exp2_diff(tr[cc], M); }, sh,
+                                 &theta_local, &total);
+        if (c < 0) {
+            nonfinite = true;  // NaN/+inf, or a bonus row of only -inf: no distribution to sample
+        } else {
+            double w[EPV];
+            const int64_t vi = (int64_t)c * (kWave * kLoads) + threadIdx.x;
+            softmax_vec_weights<DT, false>(rowv, vi, Vt, cs_t, -M, nullptr, w);
+            tok = find_in_chunk<EPV>(w, vi * EPV, theta_local, sh);
+            if (threadIdx.x == 0 && lse_p) lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
+        }
+    } else {
+        double theta_local, total;
+        int c = find_chunk(nC, u, [&](int cc) { return (double)ts[cc]; }, sh, &theta_local, &total);
+        bool degenerate = false;
+        if (c < 0) {
+            if (total != total) {
+                nonfinite = true;
+            } else {  // residual identically zero: fall back to p of the same row
+                degenerate = true;
+                add_flags |= TLI_FLAG_DEGENERATE;
+                c = find_chunk(nC, u, [&](int cc) { return (double)tp[cc]; }, sh, &theta_local, &total);
+                if (c < 0) nonfinite = true;
+            }
+        }
+        if (!nonfinite) {
+            const int64_t vi = (int64_t)c * (kWave * kLoads) + threadIdx.x;
+            float p[EPV], w[EPV];
+            double wd[EPV];
+            if (vi * EPV < Vt) {
+                residual_vec<DT>(rowv[vi], vi * EPV, Vt, f.rp, t2d, ldp, p, w);
+#pragma unroll
+                for (int i = 0; i < EPV; ++i) wd[i] = degenerate ? (double)p[i] : (double)w[i];
+            } else {
+#pragma unroll
+                for (int i = 0; i < EPV; ++i) wd[i] = 0.0;
+            }
+            tok = find_in_chunk<EPV>(wd, vi * EPV, theta_local, sh);
+        }
+    }
+    if (threadIdx.x == 0) {
+        if (nonfinite) {
+            n_accepted[b] = 0;
+            for (int k = 0; k <= K; ++k) out_tok[(int64_t)b * (K + 1) + k] = -1;
+            seq_status[b] |= TLI_FLAG_NONFINITE;
+        } else {
+            out_tok[(int64_t)b * (K + 1) + f.n] = tok;
+            if (add_flags) seq_status[b] |= add_flags;
+        }
+    }
+}
+
+// ======================================= host side ============================================
+
+struct Plan {
+    int nC;      // chunks per row
+    int nsplit;  // workgroups per row
+    int cps;     // chunks per workgroup
+};
+
+Plan make_plan(int V, int rows, int chunk) {
+    Plan p;
+    p.nC = (V + chunk - 1) / chunk;
+    const int target_wgs = 2048;  // ~8 workgroups of 4 waves on each of the 256 CUs
+    int want = (target_wgs + rows - 1) / rows;
+    int cap = (p.nC + kWaves - 1) / kWaves;  // keep at least one chunk per wave
+    p.nsplit = want < 1 ? 1 : (want > cap ? cap : want);
+    p.cps = (p.nC + p.nsplit - 1) / p.nsplit;
+    p.nsplit = (p.nC + p.cps - 1) / p.cps;
+    return p;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Workspace {  // offsets into the caller's scratch
+    size_t part, ws_lse_p, tab_ref, tab_s, tab_p, total;
+};
+
+Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
+    const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
+    const int64_t rows = (int64_t)B * K;
+    const Plan pl = make_plan(Vt, (int)rows, chunk);
+    const int nCt = (Vt + chunk - 1) / chunk, nCd = (Vd + chunk - 1) / chunk;
+    const size_t tab_rows_d = (size_t)rows * nCd, tab_rows_t = (size_t)B * nCt;
+    const size_t tab = tab_rows_d > tab_rows_t ? tab_rows_d : tab_rows_t;
+    Workspace w;
+    size_t off = 0;
+    w.part = off; off += align256((size_t)rows * pl.nsplit * sizeof(Part));
+    w.ws_lse_p = off; off += align256((size_t)rows * sizeof(double));
+    w.tab_ref = off; off += align256(tab * sizeof(float));
+    w.tab_s = off; off += align256(tab * sizeof(float));
+    w.tab_p = off; off += align256(tab_rows_t * sizeof(float));
+    w.total = off;
+    return w;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+struct tli_map {
+    int32_t Vd, Vt, S;
+    int device;
+    int32_t* d2t;    // dev [Vd padded to 8]
+    int32_t* t2d;    // dev [Vt padded to 8]
+    uint8_t* bits;   // dev: bit x set iff drafter id x is shared
+};
+
+extern "C" {
+
+const char* tli_status_string(int status) {
+    switch (status) {
+        case TLI_OK: return "TLI_OK";
+        case TLI_ERR_INVALID_ARG: return "TLI_ERR_INVALID_ARG";
+        case TLI_ERR_OUT_OF_RANGE: return "TLI_ERR_OUT_OF_RANGE";
+        case TLI_ERR_NOT_INJECTIVE: return "TLI_ERR_NOT_INJECTIVE";
+        case TLI_ERR_EMPTY_INTERSECTION: return "TLI_ERR_EMPTY_INTERSECTION";
+        case TLI_ERR_ALLOC: return "TLI_ERR_ALLOC";
+        case TLI_ERR_HIP: return "TLI_ERR_HIP";
+        default: return "TLI_ERR_UNKNOWN";
+    }
+}
+
+int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out_map, int32_t* out_num_shared) {
+    if (out_map) *out_map = nullptr;
+    if (out_num_shared) *out_num_shared = 0;
+    if (!d2t_host || !out_map || Vd < 1 || Vt < 1) return TLI_ERR_INVALID_ARG;
+    const size_t Vd_pad = ((size_t)Vd + 7) & ~(size_t)7, Vt_pad = ((size_t)Vt + 7) & ~(size_t)7;
+    std::vector<int32_t> d2t(Vd_pad, -1), t2d(Vt_pad, -1);
+    std::vector<uint8_t> bits(Vd_pad / 8 + 16, 0);
+    int32_t S = 0;
+    for (int32_t x = 0; x < Vd; ++x) {
+        const int32_t t = d2t_host[x];
+        if (t == -1) continue;
+        if (t < 0 || t >= Vt) return TLI_ERR_OUT_OF_RANGE;
+        if (t2d[t] != -1) return TLI_ERR_NOT_INJECTIVE;
+        t2d[t] = x;
+        d2t[x] = t;
+        bits[x >> 3] |= (uint8_t)(1u << (x & 7));
+        ++S;
+    }
+    if (S == 0) return TLI_ERR_EMPTY_INTERSECTION;
+    tli_map* m = new (std::nothrow) tli_map();
+    if (!m) return TLI_ERR_ALLOC;
+    m->Vd = Vd; m->Vt = Vt; m->S = S; m->d2t = nullptr; m->t2d = nullptr; m->bits = nullptr;
+    if (hipGetDevice(&m->device) != hipSuccess) { delete m; return TLI_ERR_HIP; }
+    bool ok = hipMalloc(&m->d2t, d2t.size() * 4) == hipSuccess && hipMalloc(&m->t2d, t2d.size() * 4) == hipSuccess &&
+              hipMalloc(&m->bits, bits.size()) == hipSuccess;
+    if (!ok) { tli_free_map(m); return TLI_ERR_ALLOC; }
+    ok = hipMemcpy(m->d2t, d2t.data(), d2t.size() * 4, hipMemcpyHostToDevice) == hipSuccess &&
+         hipMemcpy(m->t2d, t2d.data(), t2d.size() * 4, hipMemcpyHostToDevice) == hipSuccess &&
+         hipMemcpy(m->bits, bits.data(), bits.size(), hipMemcpyHostToDevice) == hipSuccess;
+    if (!ok) { tli_free_map(m); return TLI_ERR_HIP; }
+    *out_map = m;
+    if (out_num_shared) *out_num_shared = S;
+    return TLI_OK;
+}
+
+void tli_free_map(tli_map* m) {
+    if (!m) return;
+    if (m->d2t) (void)hipFree(m->d2t);
+    if (m->t2d) (void)hipFree(m->t2d);
+    if (m->bits) (void)hipFree(m->bits);
+    delete m;
+}
+
+int tli_map_info(const tli_map* m, int32_t* Vd, int32_t* Vt, int32_t* S) {
+    if (!m) return TLI_ERR_INVALID_ARG;
+    if (Vd) *Vd = m->Vd;
+    if (Vt) *Vt = m->Vt;
+    if (S) *S = m->S;
+    return TLI_OK;
+}
+
+size_t tli_workspace_bytes(int32_t B, int32_t K, int32_t Vt, int32_t Vd, tli_dtype dtype) {
+    if (B < 1 || K < 1 || K > kMaxK || Vt < 1 || Vd < 1 || (dtype != TLI_F32 && dtype != TLI_BF16)) return 0;
+    if ((int64_t)B * K > 0x7fffffff / 64) return 0;
+    return layout(B, K, Vt, Vd, dtype).total;
+}
+
+int tli_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems, int32_t R,
+                     float temp_d, const float* u_draft, int32_t* tok_d, int32_t* tok_t, double* q_tok, double* lse_q,
+                     int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!map || !logits_d || !u_draft || !tok_d || !tok_t || !lse_q || !row_status || !workspace)
+        return TLI_ERR_INVALID_ARG;
+    if (R < 1 || R > 0x7fffffff / 64 || !(temp_d > 0.f) || !std::isfinite(temp_d)) return TLI_ERR_INVALID_ARG;
+    if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
+    const int epv = dtype == TLI_BF16 ? 8 : 4;
+    if (row_stride_elems < map->Vd || row_stride_elems % epv != 0 || !aligned16(logits_d) || !aligned16(workspace))
+        return TLI_ERR_INVALID_ARG;
+    const int Vd = map->Vd;
+    const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
+    const Plan pl = make_plan(Vd, R, chunk);
+    const size_t tab_bytes = align256((size_t)R * pl.nC * sizeof(float));
+    if (workspace_bytes < 2 * tab_bytes) return TLI_ERR_ALLOC;
+    float* tab_ref = reinterpret_cast<float*>(workspace);
+    float* tab_s = reinterpret_cast<float*>(static_cast<char*>(workspace) + tab_bytes);
+    const double c_true = kLog2e / (double)temp_d;
+    const float cs = (float)c_true;
+    const double ratio = c_true / (double)cs;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const dim3 g1((unsigned)R * pl.nsplit), g2(R);
+    if (dtype == TLI_BF16) {
+        hipLaunchKernelGGL(k_draft_scan<TLI_BF16>, g1, dim3(kWG), 0, st, logits_d, row_stride_elems, Vd, pl.nC, pl.cps,
+                           pl.nsplit, cs, map->bits, tab_ref, tab_s);
+        hipLaunchKernelGGL(k_draft_pick<TLI_BF16>, g2, dim3(kWG), 0, st, logits_d, row_stride_elems, Vd, pl.nC, cs,
+                           ratio, 1.0 / (double)temp_d, map->bits, map->d2t, tab_ref, tab_s, u_draft, tok_d, tok_t,
+                           q_tok, lse_q, row_status);
+    } else {
+        hipLaunchKernelGGL(k_draft_scan<TLI_F32>, g1, dim3(kWG), 0, st, logits_d, row_stride_elems, Vd, pl.nC, pl.cps,
+                           pl.nsplit, cs, map->bits, tab_ref, tab_s);
+        hipLaunchKernelGGL(k_draft_pick<TLI_F32>, g2, dim3(kWG), 0, st, logits_d, row_stride_elems, Vd, pl.nC, cs,
+                           ratio, 1.0 / (double)temp_d, map->bits, map->d2t, tab_ref, tab_s, u_draft, tok_d, tok_t,
+                           q_tok, lse_q, row_status);
+    }
+    return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
+}
+
+int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype, int32_t B, int32_t K,
+               float temp_t, float temp_d, const int32_t* tok_d, const double* lse_q, const float* u_acc,
+               const float* u_fin, int32_t* n_accepted, int32_t* out_tok, uint8_t* accept, double* p_tok,
+               double* q_tok, double* lse_p, int32_t* seq_status, void* workspace, size_t workspace_bytes,
+               void* hip_stream) {
+    if (!map || !logits_t || !logits_d || !tok_d || !lse_q || !u_acc || !u_fin || !n_accepted || !out_tok ||
+        !seq_status || !workspace)
+        return TLI_ERR_INVALID_ARG;
+    if (B < 1 || K < 1 || K > kMaxK || (int64_t)B * K > 0x7fffffff / 64) return TLI_ERR_INVALID_ARG;
+    if (!(temp_t > 0.f) || !(temp_d > 0.f) || !std::isfinite(temp_t) || !std::isfinite(temp_d))
+        return TLI_ERR_INVALID_ARG;
+    if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
+    const int epv = dtype == TLI_BF16 ? 8 : 4;
+    const int Vt = map->Vt, Vd = map->Vd;
+    // dense rows must each start on a 16-byte boundary
+    if (Vt % epv != 0 || Vd % epv != 0 || !aligned16(logits_t) || !aligned16(logits_d) || !aligned16(workspace))
+        return TLI_ERR_INVALID_ARG;
+    const Workspace w = layout(B, K, Vt, Vd, dtype);
+    if (workspace_bytes < w.total) return TLI_ERR_ALLOC;
+    char* ws = static_cast<char*>(workspace);
+    Part* part = reinterpret_cast<Part*>(ws + w.part);
+    double* ws_lse_p = reinterpret_cast<double*>(ws + w.ws_lse_p);
+    float* tab_ref = reinterpret_cast<float*>(ws + w.tab_ref);
+    float* tab_s = reinterpret_cast<float*>(ws + w.tab_s);
+    float* tab_p = reinterpret_cast<float*>(ws + w.tab_p);
+    const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
+    const int rows = B * K;
+    const Plan pl = make_plan(Vt, rows, chunk);
+    const Plan pf = make_plan(Vt, B, chunk);
+    const double c_t = kLog2e / (double)temp_t, c_d = kLog2e / (double)temp_d;
+    const float cs_t = (float)c_t;
+    const double ratio_t = c_t / (double)cs_t;
+    const double inv_t = 1.0 / (double)temp_t, inv_d = 1.0 / (double)temp_d;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+#define TLI_LAUNCH_VERIFY(DT)                                                                                         \
+    hipLaunchKernelGGL(k_lse<DT>, dim3((unsigned)rows * pl.nsplit), dim3(kWG), 0, st, logits_t, K, (int64_t)(K + 1) * Vt, \
+                       (int64_t)Vt, Vt, pl.nC, pl.cps, pl.nsplit, cs_t, part);                                                   \
+    hipLaunchKernelGGL(k_accept<DT>, dim3(B), dim3(kWave), 0, st, logits_t, logits_d, K, Vt, Vd, pl.nsplit, part,     \
+                       ratio_t, inv_t, inv_d, map->d2t, tok_d, lse_q, u_acc, n_accepted, out_tok, accept, p_tok,      \
+                       q_tok, lse_p, seq_status, ws_lse_p);                                                           \
+    hipLaunchKernelGGL(k_final_scan<DT>, dim3((unsigned)B * pf.nsplit), dim3(kWG), 0, st, logits_t, logits_d, K, Vt, Vd, pf.nC, \
+                       pf.cps, pf.nsplit, cs_t, c_t, c_d, map->d2t, map->t2d, tok_d, lse_q, n_accepted, seq_status, ws_lse_p,    \
+                       tab_ref, tab_s, tab_p);                                                                        \
+    hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWG), 0, st, logits_t, logits_d, K, Vt, Vd, pf.nC, cs_t,       \
+                       ratio_t, c_t, c_d, map->d2t, map->t2d, tok_d, lse_q, u_fin, ws_lse_p, tab_ref, tab_s, tab_p,   \
+                       n_accepted, out_tok, lse_p, seq_status);
+    if (dtype == TLI_BF16) {
+        TLI_LAUNCH_VERIFY(TLI_BF16)
+    } else {
+        TLI_LAUNCH_VERIFY(TLI_F32)
+    }
+#undef TLI_LAUNCH_VERIFY
+    return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every function include/tli.h declares,
+and its argument validation (which runs before any HIP call) returns the documented codes."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2502_05202_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "tli.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tli_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def _build(lib, d2t, Vt):
+    arr = np.ascontiguousarray(d2t, dtype=np.int32)
+    out = ctypes.c_void_p()
+    S = ctypes.c_int32(-5)
+    rc = lib.tli_build_map(arr.ctypes.data_as(ctypes.c_void_p), arr.shape[0], Vt, ctypes.byref(out), ctypes.byref(S))
+    return rc, out, S.value
+
+
+def test_build_map_validation(lib):
+    assert _build(lib, [0, 1, 7], 7)[0] == -2          # 7 is not in [0, 7)
+    assert _build(lib, [0, -2, 1], 7)[0] == -2         # only -1 marks "not shared"
+    assert _build(lib, [3, 1, 3], 7)[0] == -3          # two drafter ids on one target id
+    rc, out, S = _build(lib, [-1, -1, -1], 7)          # disjoint vocabularies
+    assert rc == -4 and out.value is None and S == 0
+    assert lib.tli_build_map(None, 3, 7, ctypes.byref(ctypes.c_void_p()), None) == -1
+    arr = np.zeros(3, np.int32)
+    assert lib.tli_build_map(arr.ctypes.data_as(ctypes.c_void_p), 0, 7, ctypes.byref(ctypes.c_void_p()), None) == -1
+    assert lib.tli_build_map(arr.ctypes.data_as(ctypes.c_void_p), 3, 0, ctypes.byref(ctypes.c_void_p()), None) == -1
+    assert lib.tli_build_map(arr.ctypes.data_as(ctypes.c_void_p), 3, 7, None, None) == -1
+
+
+def test_status_strings_and_workspace(lib):
+    assert binding.status_string(0) == "TLI_OK"
+    assert binding.status_string(-3) == "TLI_ERR_NOT_INJECTIVE"
+    assert binding.status_string(99) == "TLI_ERR_UNKNOWN"
+    big = binding.tli_workspace_bytes(256, 8, 256000, 128256, binding.TLI_BF16)
+    small = binding.tli_workspace_bytes(1, 3, 64, 48, binding.TLI_F32)
+    assert 0 < small < big < (1 << 30)
+    assert big % 256 == 0
+    for bad in ((0, 8, 10, 10), (1, 0, 10, 10), (1, 65, 10, 10), (1, 1, 0, 10), (1, 1, 10, 0)):
+        assert binding.tli_workspace_bytes(*bad, binding.TLI_F32) == 0
+    assert binding.tli_workspace_bytes(1, 1, 10, 10, 7) == 0
+
+
+def test_hot_calls_reject_null_arguments(lib):
+    z = ctypes.c_void_p(0)
+    assert lib.tli_draft_sample(z, z, 0, 8, 1, 1.0, z, z, z, z, z, z, z, 0, z) == -1
+    assert lib.tli_verify(z, z, z, 0, 1, 1, 1.0, 1.0, z, z, z, z, z, z, z, z, z, z, z, z, 0, z) == -1
+    assert lib.tli_map_info(z, None, None, None) == -1
+    lib.tli_free_map(z)  # freeing NULL is a no-op

@@ -1,0 +1,212 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on the
+seeded workloads -- at reduced sizes that still span several chunks and a ragged tail, and at the
+full sizes of the five workloads in the launch configuration the benchmark times."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_05202_amd import binding, synth
+
+import parity
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _check(res, allow_near=True):
+    for name in ("draft", "verify", "chained"):
+        rep = res[name]
+        if rep is None:
+            continue
+        print(name, dict(rep))
+        assert rep["hard"] == 0, f"{name}: hard mismatches {dict(rep)}"
+        if not allow_near:
+            assert rep["accept_near_ties"] == 0 and rep["token_near_ties"] == 0
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_workload1_tiny_exact(oracle, seed):
+    w = synth.WORKLOADS[1]
+    inp = synth.make_inputs(w, DEV, seed=synth.BASE_SEED + 1 + 1000 * seed)
+    _check(parity.run_case(oracle, inp), allow_near=False)
+
+
+def test_workload1_many_uniforms(oracle):
+    """Same logits, 4096 different uniform triples (B copies of workload 1)."""
+    w1 = synth.WORKLOADS[1]
+    inp1 = synth.make_inputs(w1, DEV)
+    B = 4096
+    w = w1.scaled(B=B)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(77)
+    inp = dict(inp1)
+    inp["workload"] = w
+    inp["logits_t"] = inp1["logits_t"].expand(B, -1, -1).contiguous()
+    inp["logits_d"] = inp1["logits_d"].expand(B, -1, -1).contiguous()
+    inp["u_draft"] = synth._uniform24(B * w.K, gen, DEV).reshape(B, w.K)
+    inp["u_acc"] = synth._uniform24(B * w.K, gen, DEV).reshape(B, w.K)
+    inp["u_fin"] = synth._uniform24(B, gen, DEV)
+    res = parity.run_case(oracle, inp)
+    _check(res)
+    # the batch exercises both endings
+    n = res["ref_verify"]["n_acc"]
+    assert (n == w.K).any() and (n < w.K).any()
+
+
+RAGGED = [
+    # (Vt, Vd, S, dtype, B, K, tau_t, tau_d): several chunks (2048 bf16 / 1024 fp32) + ragged tails
+    (2048 * 3 + 8 * 5, 2048 * 2 + 8 * 3, 1500, "bf16", 5, 3, 0.7, 0.9),
+    (1024 * 4 + 4 * 7, 1024 + 4, 700, "f32", 3, 4, 1.0, 1.0),
+    (2048, 2048, 2048, "bf16", 2, 2, 1.3, 0.6),
+    (8, 8, 3, "bf16", 3, 2, 1.0, 1.0),
+    (4, 8, 1, "f32", 2, 1, 0.5, 2.0),
+    (10000, 30000, 9000, "bf16", 7, 6, 0.8, 0.8),
+    (50000, 20000, 1, "f32", 2, 3, 1.0, 1.0),
+]
+
+
+@pytest.mark.parametrize("case", RAGGED, ids=[f"Vt{c[0]}_Vd{c[1]}_{c[3]}" for c in RAGGED])
+def test_ragged_sizes(oracle, case):
+    Vt, Vd, S, dtype, B, K, tt, td = case
+    w = synth.WORKLOADS[3].scaled(Vt=Vt, Vd=Vd, S=S, dtype=dtype, B=B, K=K, tau_t=tt, tau_d=td, cfg=50)
+    inp = synth.make_inputs(w, DEV)
+    _check(parity.run_case(oracle, inp))
+
+
+def test_max_lookahead_and_zipf(oracle):
+    w = synth.WORKLOADS[5].scaled(Vt=4096 + 64, Vd=2048 + 24, S=900, B=3, K=64)
+    _check(parity.run_case(oracle, synth.make_inputs(w, DEV)))
+
+
+def test_identical_models_take_the_bonus_path(oracle):
+    V, B, K = 5000, 6, 4
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    lt = (torch.randn(B, K + 1, V, generator=gen, device=DEV) * 3).to(torch.bfloat16)
+    w = synth.WORKLOADS[3].scaled(Vt=V, Vd=V, S=V, B=B, K=K, tau_t=0.9, tau_d=0.9)
+    inp = dict(workload=w, d2t=np.arange(V, dtype=np.int32), logits_t=lt, logits_d=lt[:, :K].contiguous(),
+               u_draft=synth._uniform24(B * K, gen, DEV).reshape(B, K),
+               u_acc=synth._uniform24(B * K, gen, DEV).reshape(B, K), u_fin=synth._uniform24(B, gen, DEV))
+    res = parity.run_case(oracle, inp)
+    _check(res)
+    assert np.all(res["gpu_verify"]["n_accepted"] == K)
+    assert not np.isnan(res["gpu_verify"]["lse_p"]).any()
+
+
+def test_row_stride_and_unaligned_vocab(oracle):
+    """tli_draft_sample on rows that are views into a wider buffer; Vd not a multiple of the vector."""
+    Vd, Vt, S, R, stride = 3001, 4000, 1200, 9, 3008
+    d2t = synth.make_d2t(Vd, Vt, S, 123)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(9)
+    for dt in (torch.bfloat16, torch.float32):
+        buf = (torch.randn(R, stride, generator=gen, device=DEV) * 3).to(dt)
+        buf[:, Vd:] = 50.0  # padding beyond Vd must be ignored even if it is large
+        view = buf[:, :Vd]
+        u = synth._uniform24(R, gen, DEV)
+        m = binding.tli_build_map(d2t, Vt)
+        ws = binding.alloc_workspace(R, 1, m, binding._dtype_code(buf), DEV)
+        g = binding.tli_draft_sample(m, view, 0.8, u, ws)
+        torch.cuda.synchronize()
+        ld_np = synth.logits_to_numpy(view.contiguous())
+        rep, _ = parity.compare_draft(oracle, ld_np, 0.8, d2t, u.cpu().numpy().astype(np.float64), parity.to_host(g))
+        assert rep["hard"] == 0
+        m.free()
+
+
+def test_flags_and_edge_inputs(oracle):
+    w = synth.WORKLOADS[3].scaled(Vt=6000, Vd=4104, S=2000, B=8, K=3)
+    inp = synth.make_inputs(w, DEV)
+    d2t = inp["d2t"]
+    shared = np.nonzero(d2t >= 0)[0]
+    unshared = np.nonzero(d2t < 0)[0]
+    lt, ld = inp["logits_t"], inp["logits_d"]
+    # drafter rows: NaN on a shared id (seq 0 pos 1), +inf on a shared id (seq 1 pos 0), all shared -inf (seq 2 pos 2)
+    ld[0, 1, int(shared[5])] = float("nan")
+    ld[1, 0, int(shared[7])] = float("inf")
+    ld[2, 2, torch.from_numpy(shared).to(DEV)] = float("-inf")
+    ld[4, 0, int(shared[0])] = float("-inf")  # a single -inf is legal
+    # target rows: NaN (seq 5), a stretch of -inf (seq 6)
+    lt[5, 1, 17] = float("nan")
+    lt[6, 0, :3000] = float("-inf")
+    # u = 0 and u = largest fp32 below 1
+    inp["u_draft"][7, :] = 0.0
+    inp["u_fin"][7] = 1.0 - 2.0 ** -24
+    inp["u_fin"][6] = 0.0
+    res = parity.run_case(oracle, inp, chain=True)
+    _check(res)
+    st = res["ref_draft"]["status"].reshape(w.B, w.K)
+    assert st[0, 1] == oracle.NONFINITE and st[1, 0] == oracle.NONFINITE and st[2, 2] == oracle.ZERO_MASS
+    assert st.sum() == 2 * oracle.NONFINITE + oracle.ZERO_MASS
+    sv = res["ref_verify"]["status"]
+    assert sv[5] & oracle.NONFINITE and sv[0] & oracle.BAD_DRAFT and sv[2] & oracle.BAD_DRAFT
+    # explicit bad drafts: unshared id, out of range
+    m = binding.tli_build_map(d2t, w.Vt)
+    ws = binding.alloc_workspace(w.B, w.K, m, binding.TLI_BF16, DEV)
+    tok = res["ref_draft"]["tok_d"].reshape(w.B, w.K).copy()
+    tok[3, 0] = int(unshared[0])
+    tok[4, 2] = w.Vd + 5
+    tok[7, 1] = -7
+    lse_q = res["ref_draft"]["lse_q"].copy()
+    g = binding.tli_verify(m, lt, ld, w.tau_t, w.tau_d, torch.from_numpy(tok).to(DEV), torch.from_numpy(lse_q).to(DEV),
+                           inp["u_acc"].reshape(-1), inp["u_fin"], ws)
+    torch.cuda.synchronize()
+    rep, ref = parity.compare_verify(oracle, synth.logits_to_numpy(lt), synth.logits_to_numpy(ld), w.tau_t, w.tau_d,
+                                     d2t, tok, inp["u_acc"].cpu().numpy().astype(np.float64),
+                                     inp["u_fin"].cpu().numpy().astype(np.float64), parity.to_host(g))
+    assert rep["hard"] == 0
+    assert ref["n_acc"][3] == 0 and ref["status"][3] & oracle.BAD_DRAFT and ref["status"][4] & oracle.BAD_DRAFT
+    m.free()
+
+
+def test_deterministic(oracle):
+    w = synth.WORKLOADS[3].scaled(B=16, K=3, Vt=20000, Vd=12000, S=5000)
+    inp = synth.make_inputs(w, DEV)
+    m = binding.tli_build_map(inp["d2t"], w.Vt)
+    ws = binding.alloc_workspace(w.B, w.K, m, binding.TLI_BF16, DEV)
+    outs = []
+    for _ in range(3):
+        d = binding.tli_draft_sample(m, inp["logits_d"], w.tau_d, inp["u_draft"].reshape(-1), ws)
+        v = binding.tli_verify(m, inp["logits_t"], inp["logits_d"], w.tau_t, w.tau_d, d["tok_d"], d["lse_q"],
+                               inp["u_acc"].reshape(-1), inp["u_fin"], ws)
+        torch.cuda.synchronize()
+        outs.append({**{"d_" + k: t.clone() for k, t in d.items()}, **{k: t.clone() for k, t in v.items()}})
+    for o in outs[1:]:
+        for k in o:
+            assert torch.equal(o[k].view(torch.uint8), outs[0][k].view(torch.uint8)), k
+    m.free()
+
+
+def test_hot_calls_reject_bad_arguments():
+    w = synth.WORKLOADS[1]
+    inp = synth.make_inputs(w, DEV)
+    m = binding.tli_build_map(inp["d2t"], w.Vt)
+    ws = binding.alloc_workspace(w.B, w.K, m, binding.TLI_F32, DEV)
+    u = inp["u_draft"].reshape(-1)
+    for bad_temp in (0.0, -1.0, float("nan"), float("inf")):
+        with pytest.raises(binding.TliError) as e:
+            binding.tli_draft_sample(m, inp["logits_d"], bad_temp, u, ws)
+        assert e.value.code == -1
+    with pytest.raises(binding.TliError) as e:  # workspace too small
+        binding.tli_draft_sample(m, inp["logits_d"], 1.0, u, ws[:16])
+    assert e.value.code == -5
+    with pytest.raises(binding.TliError) as e:  # misaligned logits
+        binding.tli_draft_sample(m, inp["logits_d"].reshape(-1)[1:1 + 2 * w.Vd].reshape(2, w.Vd), 1.0, u[:2], ws)
+    assert e.value.code == -1
+    m.free()
+
+
+FULL = [2, 3, 4, 5]
+
+
+@pytest.mark.parametrize("cfg", FULL)
+def test_full_size_workloads(oracle, cfg):
+    """The five workloads at full size, every output compared (the oracle is fanned out over the host
+    cores, one block of sequences per thread)."""
+    w = synth.WORKLOADS[cfg]
+    inp = synth.make_inputs(w, DEV)
+    res = parity.run_case(oracle, inp, threads=16, chain=(cfg != 4))
+    _check(res)
+    acc = res["ref_verify"]["accept"].mean()
+    print(f"workload {cfg}: acceptance {acc:.3f}, mean accepted {res['ref_verify']['n_acc'].mean():.2f}")
