@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the TLI draft-and-verify hot path on one MI355X.
+
+A step = one pass of the whole path over one batch of synthetic input already resident in HBM:
+tli_draft_sample on all B*K drafter rows, then tli_verify on the B sequences.  The workload is the
+large-vocabulary batch (B=256, K=8, Vt=256000, Vd=128256, ~90000 shared ids, bf16 logits, temperature
+0.7).  Prints ONE JSON line: whole-path throughput in verified draft positions/s, the roofline figures
+of the dominant kernel (the target-row normaliser scan of tli_verify) measured with HIP events on the
+launch stream inside the timed region, and the CPU oracle timed on a bounded sample of the same batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", type=int, default=4, help="1..5 (default 4 = the headline configuration)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences in the oracle's sample (0 = auto)")
+    ap.add_argument("--breakdown", action="store_true", help="also time every kernel in a second pass")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (sequences are independent: N GPUs would each take "
+              "B/N sequences with no exchange); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2502_05202_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    binding.load_library()  # raises if the HIP library is missing: there is no fallback
+    dev = "cuda:0"
+    w = synth.WORKLOADS[args.workload]
+    inp = synth.make_inputs(w, dev)
+    code = binding.TLI_F32 if w.dtype == "f32" else binding.TLI_BF16
+    esz = 4 if w.dtype == "f32" else 2
+    m = binding.tli_build_map(inp["d2t"], w.Vt)
+    ws = binding.alloc_workspace(w.B, w.K, m, code, dev)
+    u_draft = inp["u_draft"].reshape(-1).contiguous()
+    u_acc = inp["u_acc"].reshape(-1).contiguous()
+    R = w.B * w.K
+    d_out = dict(tok_d=torch.empty(R, dtype=torch.int32, device=dev), tok_t=torch.empty(R, dtype=torch.int32, device=dev),
+                 q_tok=torch.empty(R, dtype=torch.float64, device=dev), lse_q=torch.empty(R, dtype=torch.float64, device=dev),
+                 status=torch.empty(R, dtype=torch.int32, device=dev))
+    v_out = binding.alloc_verify_outputs(w.B, w.K, dev)
+
+    def step():
+        binding.tli_draft_sample(m, inp["logits_d"], w.tau_d, u_draft, ws, out=d_out)
+        binding.tli_verify(m, inp["logits_t"], inp["logits_d"], w.tau_t, w.tau_d, d_out["tok_d"], d_out["lse_q"], u_acc,
+                           inp["u_fin"], ws, out=v_out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` steps; HIP events around the dominant kernel on the launch stream
+    binding.tli_profile_enable(["lse", "draft_scan"], args.steps)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    lse_ms, lse_n = binding.tli_profile_collect("lse")
+    dscan_ms, dscan_n = binding.tli_profile_collect("draft_scan")
+    binding.tli_profile_disable()
+    total_s = t1 - t0
+    ms_per_step = 1e3 * total_s / args.steps
+    positions = w.B * w.K
+    value = positions * args.steps / total_s
+
+    # ---- separate timings of the two calls (outside the timed region)
+    def time_call(fn, n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    n_sep = max(5, args.steps // 2)
+    draft_ms = time_call(lambda: binding.tli_draft_sample(m, inp["logits_d"], w.tau_d, u_draft, ws, out=d_out), n_sep)
+    verify_ms = time_call(lambda: binding.tli_verify(m, inp["logits_t"], inp["logits_d"], w.tau_t, w.tau_d, d_out["tok_d"],
+                                                     d_out["lse_q"], u_acc, inp["u_fin"], ws, out=v_out), n_sep)
+    breakdown = None
+    if args.breakdown:
+        binding.tli_profile_enable(binding.KERNELS, n_sep)
+        for _ in range(n_sep):
+            step()
+        torch.cuda.synchronize()
+        breakdown = {}
+        for k in binding.KERNELS:
+            ms, n = binding.tli_profile_collect(k)
+            breakdown[k + "_us"] = round(1e3 * ms / max(n, 1), 2)
+        binding.tli_profile_disable()
+
+    # ---- algorithmic bytes
+    n_acc = v_out["n_accepted"].cpu().numpy()
+    lse_bytes = positions * w.Vt * esz                       # K target rows per sequence, once
+    n_bonus = int((n_acc == w.K).sum())
+    verify_bytes = lse_bytes + n_bonus * w.Vt * esz + (w.B - n_bonus) * w.Vd * esz
+    draft_bytes = R * w.Vd * esz
+    lse_avg_s = 1e-3 * lse_ms / max(lse_n, 1)
+    achieved = lse_bytes / lse_avg_s / 1e9
+    roofline = dict(bound="hbm", kernel="k_lse (target-row log-normalisers)", achieved=round(achieved, 1),
+                    peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    bytes_per_launch=lse_bytes, avg_launch_us=round(1e6 * lse_avg_s, 2), launches=lse_n)
+    extra = dict(
+        draft_ms=round(draft_ms, 4), verify_ms=round(verify_ms, 4),
+        verify_only_positions_per_s=round(positions / (1e-3 * verify_ms), 1),
+        verify_algorithmic_gbs=round(verify_bytes / (1e-3 * verify_ms) / 1e9, 1),
+        verify_frac_of_peak=round(verify_bytes / (1e-3 * verify_ms) / 1e9 / HBM_PEAK_GBS, 4),
+        draft_rows_per_s=round(R / (1e-3 * draft_ms), 1),
+        draft_algorithmic_gbs=round(draft_bytes / (1e-3 * draft_ms) / 1e9, 1),
+        draft_scan_avg_us=round(1e3 * dscan_ms / max(dscan_n, 1), 2),
+        draft_scan_gbs=round(draft_bytes / (1e-3 * dscan_ms / max(dscan_n, 1)) / 1e9, 1),
+        mean_accepted=round(float(n_acc.mean()), 3),
+    )
+    if breakdown:
+        extra["kernel_breakdown"] = breakdown
+
+    # ---- CPU oracle on a bounded sample of the same batch
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        oracle.build()
+        cores = min(16, len(os.sched_getaffinity(0)))
+        per_seq_s = 0.12 * (w.K * (w.Vt + w.Vd)) / (8 * (256000 + 128256))  # rough single-thread cost
+        nseq = args.cpu_seqs or int(max(1, min(w.B, 20.0 * cores / max(per_seq_s, 1e-6))))
+        nseq = max(min(nseq, w.B), 1)
+        lt = synth.logits_to_numpy(inp["logits_t"][:nseq])
+        ld = synth.logits_to_numpy(inp["logits_d"][:nseq])
+        ud = inp["u_draft"][:nseq].cpu().numpy().astype(np.float64)
+        ua = inp["u_acc"][:nseq].cpu().numpy().astype(np.float64)
+        uf = inp["u_fin"][:nseq].cpu().numpy().astype(np.float64)
+        c0 = time.perf_counter()
+        ds = oracle.draft_sample(ld.reshape(nseq * w.K, w.Vd), w.tau_d, inp["d2t"], ud, threads=cores)
+        oracle.verify(lt, ld, w.tau_t, w.tau_d, inp["d2t"], ds["tok_d"], ua, uf, threads=cores)
+        c1 = time.perf_counter()
+        n1 = max(1, min(nseq, 8))
+        s0 = time.perf_counter()
+        ds1 = oracle.draft_sample(ld[:n1].reshape(n1 * w.K, w.Vd), w.tau_d, inp["d2t"], ud[:n1], threads=1)
+        oracle.verify(lt[:n1], ld[:n1], w.tau_t, w.tau_d, inp["d2t"], ds1["tok_d"], ua[:n1], uf[:n1], threads=1)
+        s1 = time.perf_counter()
+        cpu = dict(value=round(nseq * w.K / (c1 - c0), 2), unit="positions/s", cores=cores, kind="oracle",
+                   sample=f"first {nseq} of {w.B} sequences of the same batch, draft+verify, {cores} threads, "
+                          f"{c1 - c0:.1f} s",
+                   single_thread_value=round(n1 * w.K / (s1 - s0), 2), single_thread_sample=f"first {n1} sequences",
+                   host_cpus=os.cpu_count())
+
+    line = dict(
+        metric="verified_draft_positions_per_s", value=round(value, 1), unit="positions/s", n_gpus=1, steps=args.steps,
+        warmup=args.warmup, ms_per_step=round(ms_per_step, 4), higher_is_better=True, scaling="weak", vs_baseline=None,
+        dtype="f32", data="synthetic",
+        config=dict(workload=w.name, B=w.B, K=w.K, Vt=w.Vt, Vd=w.Vd, shared=w.S, storage=w.dtype, temp_t=w.tau_t,
+                    temp_d=w.tau_d, step="tli_draft_sample(B*K rows) + tli_verify(B sequences)"),
+        roofline=roofline, cpu_baseline=cpu, **extra,
+    )
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

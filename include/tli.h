@@ -120,6 +120,28 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
                uint8_t* accept, double* p_tok, double* q_tok, double* lse_p, int32_t* seq_status,
                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Optional per-kernel timing for benchmarks (not part of the method): while enabled, the hot calls
+ * record a HIP event pair around each selected kernel on the caller's stream.  Not thread-safe.
+ *   tli_profile_enable  : creates 2*max_calls events per selected kernel (bit k of kernel_mask selects
+ *                         kernel k of tli_kernel_id); recording stops silently once they are used up.
+ *   tli_profile_collect : waits for the recorded events of one kernel, returns the summed duration
+ *                         in milliseconds and the number of launches, and resets that kernel's counter.
+ *   tli_profile_disable : destroys the events.
+ */
+typedef enum {
+    TLI_KERNEL_LSE = 0,        /* tli_verify: log-normalisers of the K target rows of every sequence  */
+    TLI_KERNEL_ACCEPT = 1,     /* tli_verify: accept tests + first-reject scan                        */
+    TLI_KERNEL_FINAL_SCAN = 2, /* tli_verify: chunk masses of the residual / bonus row                */
+    TLI_KERNEL_FINAL_PICK = 3, /* tli_verify: draw the extra token                                    */
+    TLI_KERNEL_DRAFT_SCAN = 4, /* tli_draft_sample: chunk masses of q' over the shared ids            */
+    TLI_KERNEL_DRAFT_PICK = 5, /* tli_draft_sample: draw the draft token                              */
+    TLI_KERNEL_COUNT = 6
+} tli_kernel_id;
+int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls);
+int tli_profile_collect(int32_t kernel, double* total_ms, int32_t* launches);
+void tli_profile_disable(void);
+
 /* Human-readable name of a tli_status value. */
 const char* tli_status_string(int status);
 

@@ -20,8 +20,9 @@ FLAG_NONFINITE, FLAG_ZERO_MASS, FLAG_BAD_DRAFT, FLAG_DEGENERATE = 1, 2, 4, 8
 
 EXPORTS = (
     "tli_build_map", "tli_free_map", "tli_map_info", "tli_workspace_bytes", "tli_draft_sample", "tli_verify",
-    "tli_status_string",
+    "tli_status_string", "tli_profile_enable", "tli_profile_collect", "tli_profile_disable",
 )
+KERNELS = ("lse", "accept", "final_scan", "final_pick", "draft_scan", "draft_pick")
 
 _lib = None
 
@@ -56,6 +57,12 @@ def load_library() -> ctypes.CDLL:
     lib.tli_verify.argtypes = [vp, vp, vp, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                vp, vp, vp, ctypes.c_size_t, vp]
     lib.tli_verify.restype = ctypes.c_int
+    lib.tli_profile_enable.argtypes = [ctypes.c_uint32, i32]
+    lib.tli_profile_enable.restype = ctypes.c_int
+    lib.tli_profile_collect.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+    lib.tli_profile_collect.restype = ctypes.c_int
+    lib.tli_profile_disable.argtypes = []
+    lib.tli_profile_disable.restype = None
     lib.tli_status_string.argtypes = [ctypes.c_int]
     lib.tli_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -188,3 +195,26 @@ def tli_verify(m: TliMap, logits_t: torch.Tensor, logits_d: torch.Tensor, temp_t
     if rc != 0:
         raise TliError(rc, "tli_verify")
     return out
+
+
+def tli_profile_enable(kernels, max_calls: int) -> None:
+    """kernels: iterable of names from KERNELS."""
+    mask = 0
+    for k in kernels:
+        mask |= 1 << KERNELS.index(k)
+    rc = load_library().tli_profile_enable(mask, int(max_calls))
+    if rc != 0:
+        raise TliError(rc, "tli_profile_enable")
+
+
+def tli_profile_collect(kernel: str):
+    """-> (total milliseconds, launches) of one kernel since the last collect."""
+    ms, n = ctypes.c_double(), ctypes.c_int32()
+    rc = load_library().tli_profile_collect(KERNELS.index(kernel), ctypes.byref(ms), ctypes.byref(n))
+    if rc != 0:
+        raise TliError(rc, "tli_profile_collect")
+    return ms.value, n.value
+
+
+def tli_profile_disable() -> None:
+    load_library().tli_profile_disable()

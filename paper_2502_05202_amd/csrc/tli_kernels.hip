@@ -431,11 +431,12 @@ __global__ __launch_bounds__(kWG) void k_draft_pick(const void* __restrict__ log
     const int d = find_in_chunk<EPV>(w, vi * EPV, theta_local, sh);
     if (threadIdx.x == 0) {
         const double lse = kLn2 * ((double)M * c_ratio + log2(total));
+        const bool have = d >= 0;  // the located chunk always holds a positive weight; never index with -1
         tok_d[row] = d;
-        tok_t[row] = d2t[d];
+        tok_t[row] = have ? d2t[d] : -1;
         lse_q[row] = lse;
-        if (q_tok) q_tok[row] = exp((double)load_elem<DT>(rowp, d) * inv_temp - lse);
-        row_status[row] = 0;
+        if (q_tok) q_tok[row] = have ? exp((double)load_elem<DT>(rowp, d) * inv_temp - lse) : 0.0;
+        row_status[row] = have ? 0 : TLI_FLAG_ZERO_MASS;
     }
 }
 
@@ -509,6 +510,12 @@ struct ResidualParams {
     bool use_q;
 };
 
+// 2^(x*(c_hi+c_lo) - (l_hi+l_lo)).  The low-order term sees x clamped to the finite range, so that a
+// -inf logit gives -inf (probability 0) whatever the sign of c_lo, instead of inf - inf.
+__device__ inline float exp2_split(float x, float c_hi, float c_lo, float l_hi, float l_lo) {
+    return exp2_hw(fmaf(x, c_hi, -l_hi) + fmaf(fmaxf(x, -3.0e38f), c_lo, -l_lo));
+}
+
 __device__ inline void split_hi_lo(double v, float& hi, float& lo) {
     hi = (float)v;
     lo = (float)(v - (double)hi);
@@ -532,12 +539,12 @@ __device__ inline void residual_vec(const uint4& v, int64_t e0, int V, const Res
 #pragma unroll
     for (int i = 0; i < EPV; ++i) {
         const bool live = e0 + i < V;
-        float pi = exp2_hw(fmaf(x[i], rp.ct_hi, -rp.lp_hi) + fmaf(x[i], rp.ct_lo, -rp.lp_lo));
+        float pi = exp2_split(x[i], rp.ct_hi, rp.ct_lo, rp.lp_hi, rp.lp_lo);
         pi = live ? pi : 0.f;
         float qi = 0.f;
         if (rp.use_q && live && d[i] >= 0) {
             const float y = load_elem<DT>(ld_row, d[i]);
-            qi = exp2_hw(fmaf(y, rp.cd_hi, -rp.lq_hi) + fmaf(y, rp.cd_lo, -rp.lq_lo));
+            qi = exp2_split(y, rp.cd_hi, rp.cd_lo, rp.lq_hi, rp.lq_lo);
         }
         p[i] = pi;
         w[i] = fmaxf(0.f, pi - qi);
@@ -759,6 +766,58 @@ Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// ---- optional per-kernel timing with HIP events on the caller's stream -------------------------
+struct Profile {
+    bool on = false;
+    uint32_t mask = 0;
+    int cap = 0;
+    std::vector<hipEvent_t> ev[TLI_KERNEL_COUNT];  // start/stop pairs
+    int used[TLI_KERNEL_COUNT] = {};
+} g_prof;
+
+struct KernelTimer {  // records start on construction, stop on destruction, if kernel `id` is being profiled
+    int id;
+    hipStream_t st;
+    bool live;
+    KernelTimer(int id_, hipStream_t st_) : id(id_), st(st_), live(false) {
+        if (g_prof.on && (g_prof.mask >> id & 1u) && g_prof.used[id] + 2 <= (int)g_prof.ev[id].size()) {
+            live = true;
+            (void)hipEventRecord(g_prof.ev[id][g_prof.used[id]], st);
+        }
+    }
+    ~KernelTimer() {
+        if (live) {
+            (void)hipEventRecord(g_prof.ev[id][g_prof.used[id] + 1], st);
+            g_prof.used[id] += 2;
+        }
+    }
+};
+
+template <int DT>
+void launch_draft(const tli_map* map, const void* logits_d, int64_t row_stride, int R, float temp_d, const Plan& pl,
+                  float cs, double ratio, const float* u_draft, int32_t* tok_d, int32_t* tok_t, double* q_tok,
+                  double* lse_q, int32_t* row_status, float* tab_ref, float* tab_s, hipStream_t st);
+
+struct VerifyArgs {
+    const tli_map* map;
+    const void *logits_t, *logits_d;
+    int B, K;
+    Plan pl, pf;
+    double c_t, c_d, ratio_t, inv_t, inv_d;
+    float cs_t;
+    const int32_t* tok_d;
+    const double* lse_q;
+    const float *u_acc, *u_fin;
+    int32_t *n_accepted, *out_tok;
+    uint8_t* accept;
+    double *p_tok, *q_tok, *lse_p;
+    int32_t* seq_status;
+    Part* part;
+    double* ws_lse_p;
+    float *tab_ref, *tab_s, *tab_p;
+};
+template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st);
+
 }  // namespace
 
 struct tli_map {
@@ -769,7 +828,98 @@ struct tli_map {
     uint8_t* bits;   // dev: bit x set iff drafter id x is shared
 };
 
+namespace {
+
+template <int DT>
+void launch_draft(const tli_map* map, const void* logits_d, int64_t row_stride, int R, float temp_d, const Plan& pl,
+                  float cs, double ratio, const float* u_draft, int32_t* tok_d, int32_t* tok_t, double* q_tok,
+                  double* lse_q, int32_t* row_status, float* tab_ref, float* tab_s, hipStream_t st) {
+    const int Vd = map->Vd;
+    {
+        KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
+        hipLaunchKernelGGL(k_draft_scan<DT>, dim3((unsigned)R * pl.nsplit), dim3(kWG), 0, st, logits_d, row_stride, Vd,
+                           pl.nC, pl.cps, pl.nsplit, cs, map->bits, tab_ref, tab_s);
+    }
+    {
+        KernelTimer t(TLI_KERNEL_DRAFT_PICK, st);
+        hipLaunchKernelGGL(k_draft_pick<DT>, dim3(R), dim3(kWG), 0, st, logits_d, row_stride, Vd, pl.nC, cs, ratio,
+                           1.0 / (double)temp_d, map->bits, map->d2t, tab_ref, tab_s, u_draft, tok_d, tok_t, q_tok,
+                           lse_q, row_status);
+    }
+}
+
+template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
+    const int Vt = a.map->Vt, Vd = a.map->Vd, B = a.B, K = a.K, rows = B * K;
+    {
+        KernelTimer t(TLI_KERNEL_LSE, st);
+        hipLaunchKernelGGL(k_lse<DT>, dim3((unsigned)rows * a.pl.nsplit), dim3(kWG), 0, st, a.logits_t, K,
+                           (int64_t)(K + 1) * Vt, (int64_t)Vt, Vt, a.pl.nC, a.pl.cps, a.pl.nsplit, a.cs_t, a.part);
+    }
+    {
+        KernelTimer t(TLI_KERNEL_ACCEPT, st);
+        hipLaunchKernelGGL(k_accept<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pl.nsplit,
+                           a.part, a.ratio_t, a.inv_t, a.inv_d, a.map->d2t, a.tok_d, a.lse_q, a.u_acc, a.n_accepted,
+                           a.out_tok, a.accept, a.p_tok, a.q_tok, a.lse_p, a.seq_status, a.ws_lse_p);
+    }
+    {
+        KernelTimer t(TLI_KERNEL_FINAL_SCAN, st);
+        hipLaunchKernelGGL(k_final_scan<DT>, dim3((unsigned)B * a.pf.nsplit), dim3(kWG), 0, st, a.logits_t, a.logits_d,
+                           K, Vt, Vd, a.pf.nC, a.pf.cps, a.pf.nsplit, a.cs_t, a.c_t, a.c_d, a.map->d2t, a.map->t2d,
+                           a.tok_d, a.lse_q, a.n_accepted, a.seq_status, a.ws_lse_p, a.tab_ref, a.tab_s, a.tab_p);
+    }
+    {
+        KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
+        hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWG), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pf.nC,
+                           a.cs_t, a.ratio_t, a.c_t, a.c_d, a.map->d2t, a.map->t2d, a.tok_d, a.lse_q, a.u_fin,
+                           a.ws_lse_p, a.tab_ref, a.tab_s, a.tab_p, a.n_accepted, a.out_tok, a.lse_p, a.seq_status);
+    }
+}
+
+}  // namespace
+
 extern "C" {
+
+int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls) {
+    tli_profile_disable();
+    if (max_calls < 1 || max_calls > (1 << 20)) return TLI_ERR_INVALID_ARG;
+    for (int k = 0; k < TLI_KERNEL_COUNT; ++k) {
+        if (!(kernel_mask >> k & 1u)) continue;
+        g_prof.ev[k].resize((size_t)2 * max_calls);
+        for (auto& e : g_prof.ev[k])
+            if (hipEventCreate(&e) != hipSuccess) { tli_profile_disable(); return TLI_ERR_HIP; }
+    }
+    g_prof.mask = kernel_mask;
+    g_prof.cap = max_calls;
+    g_prof.on = true;
+    return TLI_OK;
+}
+
+int tli_profile_collect(int32_t kernel, double* total_ms, int32_t* launches) {
+    if (kernel < 0 || kernel >= TLI_KERNEL_COUNT || !total_ms || !launches) return TLI_ERR_INVALID_ARG;
+    double tot = 0.0;
+    const int n = g_prof.used[kernel];
+    for (int i = 0; i + 1 < n; i += 2) {
+        if (hipEventSynchronize(g_prof.ev[kernel][i + 1]) != hipSuccess) return TLI_ERR_HIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_prof.ev[kernel][i], g_prof.ev[kernel][i + 1]) != hipSuccess) return TLI_ERR_HIP;
+        tot += ms;
+    }
+    *total_ms = tot;
+    *launches = n / 2;
+    g_prof.used[kernel] = 0;
+    return TLI_OK;
+}
+
+void tli_profile_disable(void) {
+    for (int k = 0; k < TLI_KERNEL_COUNT; ++k) {
+        for (auto& e : g_prof.ev[k])
+            if (e) (void)hipEventDestroy(e);
+        g_prof.ev[k].clear();
+        g_prof.used[k] = 0;
+    }
+    g_prof.on = false;
+    g_prof.mask = 0;
+}
 
 const char* tli_status_string(int status) {
     switch (status) {
@@ -862,20 +1012,12 @@ int tli_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, 
     const float cs = (float)c_true;
     const double ratio = c_true / (double)cs;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const dim3 g1((unsigned)R * pl.nsplit), g2(R);
-    if (dtype == TLI_BF16) {
-        hipLaunchKernelGGL(k_draft_scan<TLI_BF16>, g1, dim3(kWG), 0, st, logits_d, row_stride_elems, Vd, pl.nC, pl.cps,
-                           pl.nsplit, cs, map->bits, tab_ref, tab_s);
-        hipLaunchKernelGGL(k_draft_pick<TLI_BF16>, g2, dim3(kWG), 0, st, logits_d, row_stride_elems, Vd, pl.nC, cs,
-                           ratio, 1.0 / (double)temp_d, map->bits, map->d2t, tab_ref, tab_s, u_draft, tok_d, tok_t,
-                           q_tok, lse_q, row_status);
-    } else {
-        hipLaunchKernelGGL(k_draft_scan<TLI_F32>, g1, dim3(kWG), 0, st, logits_d, row_stride_elems, Vd, pl.nC, pl.cps,
-                           pl.nsplit, cs, map->bits, tab_ref, tab_s);
-        hipLaunchKernelGGL(k_draft_pick<TLI_F32>, g2, dim3(kWG), 0, st, logits_d, row_stride_elems, Vd, pl.nC, cs,
-                           ratio, 1.0 / (double)temp_d, map->bits, map->d2t, tab_ref, tab_s, u_draft, tok_d, tok_t,
-                           q_tok, lse_q, row_status);
-    }
+    if (dtype == TLI_BF16)
+        launch_draft<TLI_BF16>(map, logits_d, row_stride_elems, R, temp_d, pl, cs, ratio, u_draft, tok_d, tok_t, q_tok,
+                               lse_q, row_status, tab_ref, tab_s, st);
+    else
+        launch_draft<TLI_F32>(map, logits_d, row_stride_elems, R, temp_d, pl, cs, ratio, u_draft, tok_d, tok_t, q_tok,
+                              lse_q, row_status, tab_ref, tab_s, st);
     return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
 }
 
@@ -913,24 +1055,15 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
     const double ratio_t = c_t / (double)cs_t;
     const double inv_t = 1.0 / (double)temp_t, inv_d = 1.0 / (double)temp_d;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-#define TLI_LAUNCH_VERIFY(DT)                                                                                         \
-    hipLaunchKernelGGL(k_lse<DT>, dim3((unsigned)rows * pl.nsplit), dim3(kWG), 0, st, logits_t, K, (int64_t)(K + 1) * Vt, \
-                       (int64_t)Vt, Vt, pl.nC, pl.cps, pl.nsplit, cs_t, part);                                                   \
-    hipLaunchKernelGGL(k_accept<DT>, dim3(B), dim3(kWave), 0, st, logits_t, logits_d, K, Vt, Vd, pl.nsplit, part,     \
-                       ratio_t, inv_t, inv_d, map->d2t, tok_d, lse_q, u_acc, n_accepted, out_tok, accept, p_tok,      \
-                       q_tok, lse_p, seq_status, ws_lse_p);                                                           \
-    hipLaunchKernelGGL(k_final_scan<DT>, dim3((unsigned)B * pf.nsplit), dim3(kWG), 0, st, logits_t, logits_d, K, Vt, Vd, pf.nC, \
-                       pf.cps, pf.nsplit, cs_t, c_t, c_d, map->d2t, map->t2d, tok_d, lse_q, n_accepted, seq_status, ws_lse_p,    \
-                       tab_ref, tab_s, tab_p);                                                                        \
-    hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWG), 0, st, logits_t, logits_d, K, Vt, Vd, pf.nC, cs_t,       \
-                       ratio_t, c_t, c_d, map->d2t, map->t2d, tok_d, lse_q, u_fin, ws_lse_p, tab_ref, tab_s, tab_p,   \
-                       n_accepted, out_tok, lse_p, seq_status);
-    if (dtype == TLI_BF16) {
-        TLI_LAUNCH_VERIFY(TLI_BF16)
-    } else {
-        TLI_LAUNCH_VERIFY(TLI_F32)
-    }
-#undef TLI_LAUNCH_VERIFY
+    VerifyArgs a;
+    a.map = map; a.logits_t = logits_t; a.logits_d = logits_d; a.B = B; a.K = K; a.pl = pl; a.pf = pf;
+    a.c_t = c_t; a.c_d = c_d; a.cs_t = cs_t; a.ratio_t = ratio_t; a.inv_t = inv_t; a.inv_d = inv_d;
+    a.tok_d = tok_d; a.lse_q = lse_q; a.u_acc = u_acc; a.u_fin = u_fin; a.n_accepted = n_accepted;
+    a.out_tok = out_tok; a.accept = accept; a.p_tok = p_tok; a.q_tok = q_tok; a.lse_p = lse_p;
+    a.seq_status = seq_status; a.part = part; a.ws_lse_p = ws_lse_p; a.tab_ref = tab_ref; a.tab_s = tab_s;
+    a.tab_p = tab_p;
+    if (dtype == TLI_BF16) launch_verify<TLI_BF16>(a, st);
+    else launch_verify<TLI_F32>(a, st);
     return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
 }
 
