@@ -94,19 +94,33 @@ __device__ inline float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---- chunk loads ------------------------------------------------------------------------------
 // Chunk c of a row = vectors [c*256, c*256+256); load j of lane l is vector c*256 + j*64 + l.
+// Rows are streamed once, so the loads are non-temporal (they bypass cache allocation).
+typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+
 struct ChunkRegs {
-    uint4 v[kLoads];
+    u4v v[kLoads];
 };
 
+__device__ inline uint4 to_uint4(const u4v& t) { return make_uint4(t.x, t.y, t.z, t.w); }
+
+// whole chunk: every vector is in range, no guards
+__device__ inline void load_chunk_whole(const u4v* rowv, int c, int lane, ChunkRegs& r) {
+    const u4v* p = rowv + (int64_t)c * (kWave * kLoads) + lane;
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) r.v[j] = __builtin_nontemporal_load(p + j * kWave);
+}
+
+// last, partial chunk of a row: vectors past the end read as -inf
 template <int DT>
-__device__ inline void load_chunk(const uint4* rowv, int64_t c, int lane, int nvec, ChunkRegs& r) {
-    const uint4 ninf = (DT == TLI_BF16) ? make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u)
-                                        : make_uint4(0xff800000u, 0xff800000u, 0xff800000u, 0xff800000u);
-    const int64_t v0 = c * (kWave * kLoads) + lane;
+__device__ inline void load_chunk_tail(const u4v* rowv, int c, int lane, int nvec, ChunkRegs& r) {
+    const unsigned int pat = (DT == TLI_BF16) ? 0xff80ff80u : 0xff800000u;
+    const int64_t v0 = (int64_t)c * (kWave * kLoads) + lane;
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
         const int64_t vi = v0 + j * kWave;
-        r.v[j] = (vi < nvec) ? rowv[vi] : ninf;  // whole chunks never take the second arm
+        u4v t = {pat, pat, pat, pat};
+        if (vi < nvec) t = rowv[vi];
+        r.v[j] = t;
     }
 }
 
@@ -118,26 +132,25 @@ template <int DT> __device__ inline uint32_t mask_bits(const uint8_t* bits, int6
 
 // Reduce one chunk held in registers to (ref, s): sum 2^(x*c) over the chunk = s * 2^ref, with
 // ref = max over the chunk of fp32(x*c) (-inf and s = 0 for a chunk without finite entries).
-// A NaN or +inf logit turns s into NaN.  Wave-uniform results.
-template <int DT, bool MASKED>
-__device__ inline void reduce_chunk(const ChunkRegs& r, int64_t c, int lane, int V, float cs,
-                                    const uint8_t* bits, float& ref_out, float& s_out) {
+// A NaN or +inf logit turns s into NaN.  Wave-uniform results.  WHOLE: every element is < V.
+template <int DT, bool MASKED, bool WHOLE>
+__device__ inline void reduce_chunk(const ChunkRegs& r, int c, int lane, int V, float cs, const uint8_t* bits,
+                                    float& ref_out, float& s_out) {
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int N = EPV * kLoads;
     float x[N];
-    const int64_t v0 = c * (kWave * kLoads) + lane;
-    const bool whole = (c + 1) * (int64_t)chunk_elems<DT>() <= V;
+    const int64_t v0 = (int64_t)c * (kWave * kLoads) + lane;
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
-        unpack<DT>(r.v[j], x + j * EPV);
+        unpack<DT>(to_uint4(r.v[j]), x + j * EPV);
         const int64_t vi = v0 + j * kWave;
-        if (!whole) {
+        if (!WHOLE) {
 #pragma unroll
             for (int i = 0; i < EPV; ++i)
                 if (vi * EPV + i >= V) x[j * EPV + i] = -INFINITY;
         }
         if (MASKED) {
-            const uint32_t mb = (vi * EPV < V) ? mask_bits<DT>(bits, vi) : 0u;
+            const uint32_t mb = (WHOLE || vi * EPV < V) ? mask_bits<DT>(bits, vi) : 0u;
 #pragma unroll
             for (int i = 0; i < EPV; ++i)
                 if (!((mb >> i) & 1u)) x[j * EPV + i] = -INFINITY;
@@ -156,6 +169,54 @@ __device__ inline void reduce_chunk(const ChunkRegs& r, int64_t c, int lane, int
     s = (m == -INFINITY) ? 0.f : s * exp2_hw(ref - R);
     ref_out = R;
     s_out = wave_sum(s);
+}
+
+// Stream the chunks c_begin + wave, + kWaves, ... < c_end of one row through reduce_chunk and hand
+// each (c, ref, s) to `sink`.  Whole chunks run in a two-stage register pipeline: the loads of the
+// next chunk are in flight while the current one is reduced.  A row has at most one partial chunk
+// (its last); the wave that owns it handles it after its whole chunks.
+template <int DT, bool MASKED, class Sink>
+__device__ inline void scan_chunks(const u4v* rowv, int V, int c_begin, int c_end, float cs, const uint8_t* bits,
+                                   Sink&& sink) {
+    constexpr int EPV = Traits<DT>::EPV;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int n_whole = V / chunk_elems<DT>();
+    const int hot_end = min(c_end, n_whole);
+    int c = c_begin + wave;
+    float r, s;
+    if (c < hot_end) {
+        ChunkRegs a, b;
+        load_chunk_whole(rowv, c, lane, a);
+        while (true) {
+            if (c + kWaves >= hot_end) {
+                reduce_chunk<DT, MASKED, true>(a, c, lane, V, cs, bits, r, s);
+                sink(c, r, s);
+                c += kWaves;
+                break;
+            }
+            load_chunk_whole(rowv, c + kWaves, lane, b);
+            reduce_chunk<DT, MASKED, true>(a, c, lane, V, cs, bits, r, s);
+            sink(c, r, s);
+            c += kWaves;
+            if (c + kWaves >= hot_end) {
+                reduce_chunk<DT, MASKED, true>(b, c, lane, V, cs, bits, r, s);
+                sink(c, r, s);
+                c += kWaves;
+                break;
+            }
+            load_chunk_whole(rowv, c + kWaves, lane, a);
+            reduce_chunk<DT, MASKED, true>(b, c, lane, V, cs, bits, r, s);
+            sink(c, r, s);
+            c += kWaves;
+        }
+    }
+    if (c < c_end) {  // c == n_whole: the partial chunk
+        ChunkRegs t;
+        load_chunk_tail<DT>(rowv, c, lane, (V + EPV - 1) / EPV, t);
+        reduce_chunk<DT, MASKED, false>(t, c, lane, V, cs, bits, r, s);
+        sink(c, r, s);
+    }
 }
 
 // running (ref, sum) of a wave, sum kept in fp64
@@ -189,27 +250,15 @@ template <int DT>
 __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, int K, int64_t seq_stride,
                                               int64_t row_stride, int V, int nC, int cps, int nsplit, float cs,
                                               Part* __restrict__ part) {
-    constexpr int EPV = Traits<DT>::EPV;
     const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
     const int b = row / K, k = row - b * K;
-    const uint4* rowv = reinterpret_cast<const uint4*>(static_cast<const char*>(logits) +
+    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
                                                         (b * seq_stride + k * row_stride) * Traits<DT>::ESZ);
-    const int nvec = (V + EPV - 1) / EPV;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
-    const int c_end = min(nC, (split + 1) * cps);
     Running run;
-    ChunkRegs cur, nxt;
-    int c = split * cps + wave;
-    if (c < c_end) load_chunk<DT>(rowv, c, lane, nvec, cur);
-    for (; c < c_end; c += kWaves) {
-        const bool more = c + kWaves < c_end;
-        if (more) load_chunk<DT>(rowv, c + kWaves, lane, nvec, nxt);
-        float r, s;
-        reduce_chunk<DT, false>(cur, c, lane, V, cs, nullptr, r, s);
-        run.add(r, s);
-        if (more) cur = nxt;
-    }
+    scan_chunks<DT, false>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, nullptr,
+                           [&](int, float r, float sc) { run.add(r, sc); });
     __shared__ float sref[kWaves];
     __shared__ double ssum[kWaves];
     if (lane == 0) { sref[wave] = run.ref; ssum[wave] = run.s; }
@@ -228,24 +277,12 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
 // Used for drafter rows (masked: the intersection algorithm's q') and for the bonus target row.
 // Workgroup `split` of a row owns chunks [split*cps, (split+1)*cps).
 template <int DT, bool MASKED>
-__device__ inline void table_scan(const uint4* rowv, int split, int V, int nC, int cps, float cs, const uint8_t* bits,
+__device__ inline void table_scan(const u4v* rowv, int split, int V, int nC, int cps, float cs, const uint8_t* bits,
                                   float* tab_ref, float* tab_s) {
-    constexpr int EPV = Traits<DT>::EPV;
-    const int nvec = (V + EPV - 1) / EPV;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
-    const int c_end = min(nC, (split + 1) * cps);
-    ChunkRegs cur, nxt;
-    int c = split * cps + wave;
-    if (c < c_end) load_chunk<DT>(rowv, c, lane, nvec, cur);
-    for (; c < c_end; c += kWaves) {
-        const bool more = c + kWaves < c_end;
-        if (more) load_chunk<DT>(rowv, c + kWaves, lane, nvec, nxt);
-        float r, s;
-        reduce_chunk<DT, MASKED>(cur, c, lane, V, cs, bits, r, s);
-        if (lane == 0) { tab_ref[c] = r; tab_s[c] = s; }
-        if (more) cur = nxt;
-    }
+    scan_chunks<DT, MASKED>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, bits, [&](int c, float r, float sc) {
+        if (lane == 0) { tab_ref[c] = r; tab_s[c] = sc; }
+    });
 }
 
 template <int DT>
@@ -254,8 +291,8 @@ __global__ __launch_bounds__(kWG) void k_draft_scan(const void* __restrict__ log
                                                      const uint8_t* __restrict__ bits, float* __restrict__ tab_ref,
                                                      float* __restrict__ tab_s) {
     const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
-    const uint4* rowv = reinterpret_cast<const uint4*>(static_cast<const char*>(logits) +
-                                                        (int64_t)row * row_stride * Traits<DT>::ESZ);
+    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
+                                                    (int64_t)row * row_stride * Traits<DT>::ESZ);
     table_scan<DT, true>(rowv, split, V, nC, cps, cs, bits, tab_ref + (int64_t)row * nC, tab_s + (int64_t)row * nC);
 }
 
@@ -606,8 +643,9 @@ __global__ __launch_bounds__(kWG) void k_final_scan(const void* __restrict__ log
     float* tr = tab_ref + (int64_t)b * nC;
     float* ts = tab_s + (int64_t)b * nC;
     float* tp = tab_p + (int64_t)b * nC;
+    const u4v* rowq = reinterpret_cast<const u4v*>(rowp);
     if (f.bonus) {
-        table_scan<DT, false>(rowv, split, Vt, nC, cps, cs_t, nullptr, tr, ts);
+        table_scan<DT, false>(rowq, split, Vt, nC, cps, cs_t, nullptr, tr, ts);
         return;
     }
     const char* ldp = static_cast<const char*>(logits_d) + ((int64_t)b * K + f.n) * Vd * Traits<DT>::ESZ;
@@ -617,13 +655,13 @@ __global__ __launch_bounds__(kWG) void k_final_scan(const void* __restrict__ log
     const int c_end = min(nC, (split + 1) * cps);
     for (int c = split * cps + wave; c < c_end; c += kWaves) {
         ChunkRegs r;
-        load_chunk<DT>(rowv, c, lane, nvec, r);
+        load_chunk_tail<DT>(rowq, c, lane, nvec, r);
         float sw = 0.f, sp = 0.f;
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int64_t vi = (int64_t)c * (kWave * kLoads) + j * kWave + lane;
             float p[EPV], w[EPV];
-            residual_vec<DT>(r.v[j], vi * EPV, Vt, f.rp, t2d, ldp, p, w);
+            residual_vec<DT>(to_uint4(r.v[j]), vi * EPV, Vt, f.rp, t2d, ldp, p, w);
             float a = 0.f, q = 0.f;
 #pragma unroll
             for (int i = 0; i < EPV; ++i) { a += w[i]; q += p[i]; }
