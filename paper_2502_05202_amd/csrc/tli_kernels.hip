@@ -19,6 +19,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "tli.h"
@@ -621,50 +622,107 @@ __device__ inline FinalRow final_row(int b, int K, int Vd, const int32_t* n_acce
     return f;
 }
 
-// ---- kernel: chunk tables of the row the extra token is drawn from -----------------------------
-// grid (B * nsplit).  Bonus rows: (ref, s) softmax table.  Residual rows: tab_s = chunk sums of
-// max(0, p - q'), tab_p = chunk sums of p (used only if the residual is identically zero), ref = 0.
+// ---- kernels: chunk tables of the row the extra token is drawn from ----------------------------
+// Bonus rows (nothing rejected): (ref, s) softmax table of target row K.  grid (B * nsplit), 256 threads;
+// workgroups of sequences that rejected a draft exit at once.
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_final_scan(const void* __restrict__ logits_t, const void* __restrict__ logits_d,
-                                                     int K, int Vt, int Vd, int nC, int cps, int nsplit, float cs_t,
-                                                     double c_t, double c_d, const int32_t* __restrict__ d2t,
-                                                     const int32_t* __restrict__ t2d, const int32_t* __restrict__ tok_d,
-                                                     const double* __restrict__ lse_q,
-                                                     const int32_t* __restrict__ n_accepted,
-                                                     const int32_t* __restrict__ seq_status,
-                                                     const double* __restrict__ ws_lse_p, float* __restrict__ tab_ref,
-                                                     float* __restrict__ tab_s, float* __restrict__ tab_p) {
-    constexpr int EPV = Traits<DT>::EPV;
+__global__ __launch_bounds__(kWG) void k_final_scan_bonus(const void* __restrict__ logits_t, int K, int Vt, int nC,
+                                                           int cps, int nsplit, float cs_t,
+                                                           const int32_t* __restrict__ n_accepted,
+                                                           const int32_t* __restrict__ seq_status,
+                                                           float* __restrict__ tab_ref, float* __restrict__ tab_s) {
     const int b = blockIdx.x / nsplit, split = blockIdx.x - b * nsplit;
+    if ((seq_status[b] & TLI_FLAG_NONFINITE) || n_accepted[b] != K) return;
+    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
+                                                    ((int64_t)b * (K + 1) + K) * Vt * Traits<DT>::ESZ);
+    table_scan<DT, false>(rowv, split, Vt, nC, cps, cs_t, nullptr, tab_ref + (int64_t)b * nC, tab_s + (int64_t)b * nC);
+}
+
+// Residual rows (first rejection at position n < K): tab_s = chunk sums of max(0, p_n - q'_n), tab_p =
+// chunk sums of p_n (used only if the residual is identically zero), tab_ref = 0.
+//
+// q'_n lives in drafter-id order, the residual is summed in target-id order, and the two orders are
+// unrelated, so reading q' per target id would be one scattered 2-byte access per shared token.
+// Instead a workgroup owns a SEGMENT of kSegBytes/element-size consecutive target ids and first builds
+// that segment's slice of "drafter logit in target order" in LDS: it walks the map's per-segment list
+// of (drafter id, offset in segment) pairs -- sorted by drafter id, so the reads of the drafter row are
+// ascending and nearly coalesced -- and drops each raw logit at its offset (LDS takes scattered 2-byte
+// writes at full rate).  Ids without a partner keep -inf, i.e. q' = 0.  The target segment is then
+// streamed once with 16-byte global loads next to conflict-free 16-byte LDS reads.
+// grid (B * nseg), 1024 threads; workgroups of bonus / flagged sequences exit at once.
+constexpr int kSegBytes = 128 * 1024;
+constexpr int kSegWG = 1024;
+constexpr int kSegWaves = kSegWG / kWave;
+template <int DT> constexpr int seg_elems() { return kSegBytes / Traits<DT>::ESZ; }
+
+template <int DT>
+__global__ __launch_bounds__(kSegWG) void k_final_scan_residual(
+    const void* __restrict__ logits_t, const void* __restrict__ logits_d, int K, int Vt, int Vd, int nC, int nseg,
+    double c_t, double c_d, const int32_t* __restrict__ d2t, const int32_t* __restrict__ seg_start,
+    const int32_t* __restrict__ seg_x, const uint16_t* __restrict__ seg_off, const int32_t* __restrict__ tok_d,
+    const double* __restrict__ lse_q, const int32_t* __restrict__ n_accepted, const int32_t* __restrict__ seq_status,
+    const double* __restrict__ ws_lse_p, float* __restrict__ tab_ref, float* __restrict__ tab_s,
+    float* __restrict__ tab_p) {
+    constexpr int EPV = Traits<DT>::EPV;
+    constexpr int ESZ = Traits<DT>::ESZ;
+    constexpr int G = seg_elems<DT>();
+    constexpr int CH = chunk_elems<DT>();
+    constexpr int kChunksPerSeg = G / CH;
+    typedef typename std::conditional<DT == TLI_BF16, uint16_t, uint32_t>::type raw_t;
+    __shared__ __attribute__((aligned(16))) raw_t seg[G];
+    const int b = blockIdx.x / nseg, sg = blockIdx.x - b * nseg;
     const FinalRow f = final_row<DT>(b, K, Vd, n_accepted, seq_status, tok_d, d2t, ws_lse_p, lse_q, c_t, c_d);
-    if (f.skip) return;
-    const char* rowp = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + f.n) * Vt * Traits<DT>::ESZ;
-    const uint4* rowv = reinterpret_cast<const uint4*>(rowp);
+    if (f.skip || f.bonus) return;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    if (f.rp.use_q) {
+        const unsigned int pat = (DT == TLI_BF16) ? 0xff80ff80u : 0xff800000u;
+        u4v* segv = reinterpret_cast<u4v*>(seg);
+        const u4v fill = {pat, pat, pat, pat};
+        for (int i = tid; i < kSegBytes / 16; i += kSegWG) segv[i] = fill;
+        __syncthreads();
+        const raw_t* ld_row = reinterpret_cast<const raw_t*>(static_cast<const char*>(logits_d) +
+                                                             ((int64_t)b * K + f.n) * Vd * ESZ);
+        const int i1 = seg_start[sg + 1];
+        for (int i = seg_start[sg] + tid; i < i1; i += kSegWG) seg[seg_off[i]] = ld_row[seg_x[i]];
+        __syncthreads();
+    }
+    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
+                                                    ((int64_t)b * (K + 1) + f.n) * Vt * ESZ);
+    const int nvec = (Vt + EPV - 1) / EPV;
+    const int n_whole = Vt / CH;
     float* tr = tab_ref + (int64_t)b * nC;
     float* ts = tab_s + (int64_t)b * nC;
     float* tp = tab_p + (int64_t)b * nC;
-    const u4v* rowq = reinterpret_cast<const u4v*>(rowp);
-    if (f.bonus) {
-        table_scan<DT, false>(rowq, split, Vt, nC, cps, cs_t, nullptr, tr, ts);
-        return;
-    }
-    const char* ldp = static_cast<const char*>(logits_d) + ((int64_t)b * K + f.n) * Vd * Traits<DT>::ESZ;
-    const int nvec = (Vt + EPV - 1) / EPV;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    const int c_end = min(nC, (split + 1) * cps);
-    for (int c = split * cps + wave; c < c_end; c += kWaves) {
+    for (int cl = wave; cl < kChunksPerSeg; cl += kSegWaves) {
+        const int c = sg * kChunksPerSeg + cl;
+        if (c >= nC) break;
         ChunkRegs r;
-        load_chunk_tail<DT>(rowq, c, lane, nvec, r);
+        if (c < n_whole) load_chunk_whole(rowv, c, lane, r);
+        else load_chunk_tail<DT>(rowv, c, lane, nvec, r);
         float sw = 0.f, sp = 0.f;
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
-            const int64_t vi = (int64_t)c * (kWave * kLoads) + j * kWave + lane;
-            float p[EPV], w[EPV];
-            residual_vec<DT>(to_uint4(r.v[j]), vi * EPV, Vt, f.rp, t2d, ldp, p, w);
+            float x[EPV], y[EPV];
+            unpack<DT>(to_uint4(r.v[j]), x);
+            if (f.rp.use_q) {
+                const u4v yv = reinterpret_cast<const u4v*>(seg)[cl * (kWave * kLoads) + j * kWave + lane];
+                unpack<DT>(to_uint4(yv), y);
+            }
             float a = 0.f, q = 0.f;
 #pragma unroll
-            for (int i = 0; i < EPV; ++i) { a += w[i]; q += p[i]; }
+            for (int i = 0; i < EPV; ++i) {
+                const float pi = exp2_split(x[i], f.rp.ct_hi, f.rp.ct_lo, f.rp.lp_hi, f.rp.lp_lo);
+                float wi = pi;
+                if (f.rp.use_q) {
+                    const float qi = exp2_split(y[i], f.rp.cd_hi, f.rp.cd_lo, f.rp.lq_hi, f.rp.lq_lo);
+                    wi = fmaxf(0.f, pi - qi);
+                    if (qi != qi) wi = qi;  // NaN in the drafter row must surface (fmaxf would drop it)
+                }
+                a += wi;
+                q += pi;
+            }
             sw += a; sp += q;
         }
         sw = wave_sum(sw);
@@ -864,6 +922,13 @@ struct tli_map {
     int32_t* d2t;    // dev [Vd padded to 8]
     int32_t* t2d;    // dev [Vt padded to 8]
     uint8_t* bits;   // dev: bit x set iff drafter id x is shared
+    // Per dtype (index = tli_dtype): shared pairs bucketed by target segment (seg_elems<dtype>() target ids
+    // each), drafter ids ascending inside a bucket.  seg_start [nseg+1], seg_x [S] drafter id, seg_off [S]
+    // offset of the partner target id inside its segment.
+    int32_t nseg[2];
+    int32_t* seg_start[2];
+    int32_t* seg_x[2];
+    uint16_t* seg_off[2];
 };
 
 namespace {
@@ -901,9 +966,14 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_SCAN, st);
-        hipLaunchKernelGGL(k_final_scan<DT>, dim3((unsigned)B * a.pf.nsplit), dim3(kWG), 0, st, a.logits_t, a.logits_d,
-                           K, Vt, Vd, a.pf.nC, a.pf.cps, a.pf.nsplit, a.cs_t, a.c_t, a.c_d, a.map->d2t, a.map->t2d,
-                           a.tok_d, a.lse_q, a.n_accepted, a.seq_status, a.ws_lse_p, a.tab_ref, a.tab_s, a.tab_p);
+        const int nseg = a.map->nseg[DT];
+        hipLaunchKernelGGL(k_final_scan_residual<DT>, dim3((unsigned)B * nseg), dim3(kSegWG), 0, st, a.logits_t,
+                           a.logits_d, K, Vt, Vd, a.pf.nC, nseg, a.c_t, a.c_d, a.map->d2t, a.map->seg_start[DT],
+                           a.map->seg_x[DT], a.map->seg_off[DT], a.tok_d, a.lse_q, a.n_accepted, a.seq_status,
+                           a.ws_lse_p, a.tab_ref, a.tab_s, a.tab_p);
+        hipLaunchKernelGGL(k_final_scan_bonus<DT>, dim3((unsigned)B * a.pf.nsplit), dim3(kWG), 0, st, a.logits_t, K,
+                           Vt, a.pf.nC, a.pf.cps, a.pf.nsplit, a.cs_t, a.n_accepted, a.seq_status, a.tab_ref,
+                           a.tab_s);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
@@ -991,9 +1061,34 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
         ++S;
     }
     if (S == 0) return TLI_ERR_EMPTY_INTERSECTION;
+    // shared pairs bucketed by target segment, drafter ids ascending inside a bucket (one set per dtype)
+    std::vector<int32_t> seg_start[2], seg_x[2];
+    std::vector<uint16_t> seg_off[2];
+    int nseg[2];
+    for (int dt = 0; dt < 2; ++dt) {
+        const int G = dt == TLI_BF16 ? seg_elems<TLI_BF16>() : seg_elems<TLI_F32>();
+        nseg[dt] = (Vt + G - 1) / G;
+        seg_start[dt].assign(nseg[dt] + 1, 0);
+        seg_x[dt].resize(S);
+        seg_off[dt].resize(S);
+        for (int32_t x = 0; x < Vd; ++x)
+            if (d2t[x] >= 0) ++seg_start[dt][d2t[x] / G + 1];
+        for (int g = 0; g < nseg[dt]; ++g) seg_start[dt][g + 1] += seg_start[dt][g];
+        std::vector<int32_t> fill(seg_start[dt].begin(), seg_start[dt].end() - 1);
+        for (int32_t x = 0; x < Vd; ++x) {
+            if (d2t[x] < 0) continue;
+            const int g = d2t[x] / G;
+            seg_x[dt][fill[g]] = x;
+            seg_off[dt][fill[g]] = (uint16_t)(d2t[x] - g * G);
+            ++fill[g];
+        }
+    }
     tli_map* m = new (std::nothrow) tli_map();
     if (!m) return TLI_ERR_ALLOC;
     m->Vd = Vd; m->Vt = Vt; m->S = S; m->d2t = nullptr; m->t2d = nullptr; m->bits = nullptr;
+    for (int dt = 0; dt < 2; ++dt) {
+        m->nseg[dt] = nseg[dt]; m->seg_start[dt] = nullptr; m->seg_x[dt] = nullptr; m->seg_off[dt] = nullptr;
+    }
     if (hipGetDevice(&m->device) != hipSuccess) { delete m; return TLI_ERR_HIP; }
     bool ok = hipMalloc(&m->d2t, d2t.size() * 4) == hipSuccess && hipMalloc(&m->t2d, t2d.size() * 4) == hipSuccess &&
               hipMalloc(&m->bits, bits.size()) == hipSuccess;
@@ -1002,6 +1097,17 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
          hipMemcpy(m->t2d, t2d.data(), t2d.size() * 4, hipMemcpyHostToDevice) == hipSuccess &&
          hipMemcpy(m->bits, bits.data(), bits.size(), hipMemcpyHostToDevice) == hipSuccess;
     if (!ok) { tli_free_map(m); return TLI_ERR_HIP; }
+    for (int dt = 0; dt < 2; ++dt) {
+        ok = hipMalloc(&m->seg_start[dt], seg_start[dt].size() * 4) == hipSuccess &&
+             hipMalloc(&m->seg_x[dt], (size_t)S * 4) == hipSuccess &&
+             hipMalloc(&m->seg_off[dt], (size_t)S * 2) == hipSuccess;
+        if (!ok) { tli_free_map(m); return TLI_ERR_ALLOC; }
+        ok = hipMemcpy(m->seg_start[dt], seg_start[dt].data(), seg_start[dt].size() * 4, hipMemcpyHostToDevice) ==
+                 hipSuccess &&
+             hipMemcpy(m->seg_x[dt], seg_x[dt].data(), (size_t)S * 4, hipMemcpyHostToDevice) == hipSuccess &&
+             hipMemcpy(m->seg_off[dt], seg_off[dt].data(), (size_t)S * 2, hipMemcpyHostToDevice) == hipSuccess;
+        if (!ok) { tli_free_map(m); return TLI_ERR_HIP; }
+    }
     *out_map = m;
     if (out_num_shared) *out_num_shared = S;
     return TLI_OK;
@@ -1012,6 +1118,11 @@ void tli_free_map(tli_map* m) {
     if (m->d2t) (void)hipFree(m->d2t);
     if (m->t2d) (void)hipFree(m->t2d);
     if (m->bits) (void)hipFree(m->bits);
+    for (int dt = 0; dt < 2; ++dt) {
+        if (m->seg_start[dt]) (void)hipFree(m->seg_start[dt]);
+        if (m->seg_x[dt]) (void)hipFree(m->seg_x[dt]);
+        if (m->seg_off[dt]) (void)hipFree(m->seg_off[dt]);
+    }
     delete m;
 }
 
