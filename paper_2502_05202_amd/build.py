@@ -19,7 +19,8 @@ HIPCC_FLAGS = [
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-o", LIB, *SOURCES]
+    extra = os.environ.get("TLI_HIPCC_EXTRA", "").split()  # e.g. -D switches for kernel experiments
+    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-o", LIB, *SOURCES]
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, capture_output=True, text=True)

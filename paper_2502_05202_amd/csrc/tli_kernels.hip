@@ -548,15 +548,22 @@ struct ResidualParams {
     bool use_q;
 };
 
-// 2^(x*(c_hi+c_lo) - (l_hi+l_lo)).  The low-order term sees x clamped to the finite range, so that a
-// -inf logit gives -inf (probability 0) whatever the sign of c_lo, instead of inf - inf.
+// 2^(x*(c_hi+c_lo) - (l_hi+l_lo)) with one rounding of each partial product.  c_lo is strictly positive
+// (see split_scale), so a -inf logit gives -inf + -inf = -inf (probability 0), never inf - inf.
 __device__ inline float exp2_split(float x, float c_hi, float c_lo, float l_hi, float l_lo) {
-    return exp2_hw(fmaf(x, c_hi, -l_hi) + fmaf(fmaxf(x, -3.0e38f), c_lo, -l_lo));
+    return exp2_hw(fmaf(x, c_hi, -l_hi) + fmaf(x, c_lo, -l_lo));
 }
 
 __device__ inline void split_hi_lo(double v, float& hi, float& lo) {
     hi = (float)v;
     lo = (float)(v - (double)hi);
+}
+
+// scale c > 0 as hi + lo with hi < c, so that lo > 0
+__device__ inline void split_scale(double c, float& hi, float& lo) {
+    hi = (float)c;
+    if ((double)hi >= c) hi = as_f(as_u(hi) - 1u);
+    lo = (float)(c - (double)hi);
 }
 
 template <int DT>
@@ -586,7 +593,7 @@ __device__ inline void residual_vec(const uint4& v, int64_t e0, int V, const Res
         }
         p[i] = pi;
         w[i] = fmaxf(0.f, pi - qi);
-        if (qi != qi) w[i] = qi;  // NaN in the drafter row must surface (fmaxf would drop it)
+        if (!(qi <= 3.0e38f)) w[i] = NAN;  // NaN or +inf in the drafter row must surface (fmaxf would drop it)
     }
 }
 
@@ -608,14 +615,14 @@ __device__ inline FinalRow final_row(int b, int K, int Vd, const int32_t* n_acce
     f.rp.use_q = false;
     if (f.skip || f.bonus) return f;
     const int64_t row = (int64_t)b * K + f.n;
-    split_hi_lo(c_t, f.rp.ct_hi, f.rp.ct_lo);
+    split_scale(c_t, f.rp.ct_hi, f.rp.ct_lo);
     split_hi_lo(ws_lse_p[row] * kLog2e, f.rp.lp_hi, f.rp.lp_lo);
     const int d = tok_d[row];
     if (d >= 0 && d < Vd && d2t[d] >= 0) {
         const double lq = lse_q[row];
         if (lq > -INFINITY || lq != lq) {  // a zero-mass drafter row has q' = 0 everywhere
             f.rp.use_q = true;
-            split_hi_lo(c_d, f.rp.cd_hi, f.rp.cd_lo);
+            split_scale(c_d, f.rp.cd_hi, f.rp.cd_lo);
             split_hi_lo(lq * kLog2e, f.rp.lq_hi, f.rp.lq_lo);
         }
     }
@@ -653,6 +660,7 @@ __global__ __launch_bounds__(kWG) void k_final_scan_bonus(const void* __restrict
 constexpr int kSegBytes = 128 * 1024;
 constexpr int kSegWG = 1024;
 constexpr int kSegWaves = kSegWG / kWave;
+constexpr int kGatherU = 12;
 template <int DT> constexpr int seg_elems() { return kSegBytes / Traits<DT>::ESZ; }
 
 template <int DT>
@@ -676,41 +684,84 @@ __global__ __launch_bounds__(kSegWG) void k_final_scan_residual(
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
-    if (f.rp.use_q) {
-        const unsigned int pat = (DT == TLI_BF16) ? 0xff80ff80u : 0xff800000u;
-        u4v* segv = reinterpret_cast<u4v*>(seg);
-        const u4v fill = {pat, pat, pat, pat};
-        for (int i = tid; i < kSegBytes / 16; i += kSegWG) segv[i] = fill;
-        __syncthreads();
-        const raw_t* ld_row = reinterpret_cast<const raw_t*>(static_cast<const char*>(logits_d) +
-                                                             ((int64_t)b * K + f.n) * Vd * ESZ);
-        const int i1 = seg_start[sg + 1];
-        for (int i = seg_start[sg] + tid; i < i1; i += kSegWG) seg[seg_off[i]] = ld_row[seg_x[i]];
-        __syncthreads();
-    }
+    // the target chunks this wave owns do not depend on LDS: get their loads in flight first
+    constexpr int CPW = (kChunksPerSeg + kSegWaves - 1) / kSegWaves;
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
                                                     ((int64_t)b * (K + 1) + f.n) * Vt * ESZ);
     const int nvec = (Vt + EPV - 1) / EPV;
     const int n_whole = Vt / CH;
+    ChunkRegs r[CPW];
+#pragma unroll
+    for (int k = 0; k < CPW; ++k) {
+        const int cl = wave + k * kSegWaves;
+        const int c = sg * kChunksPerSeg + cl;
+        if (cl < kChunksPerSeg && c < nC) {
+            if (c < n_whole) load_chunk_whole(rowv, c, lane, r[k]);
+            else load_chunk_tail<DT>(rowv, c, lane, nvec, r[k]);
+        }
+    }
+    if (f.rp.use_q) {
+        const raw_t* ld_row = reinterpret_cast<const raw_t*>(static_cast<const char*>(logits_d) +
+                                                             ((int64_t)b * K + f.n) * Vd * ESZ);
+        // pairs of this segment, kGatherU per thread per batch: list loads, then the drafter-row reads they
+        // address, then (after the fill) the LDS stores -- each stage issued for the whole batch at once
+        constexpr int U = kGatherU;
+        const int i1 = seg_start[sg + 1];
+        int i0 = seg_start[sg] + tid;
+        int32_t xs[U];
+        uint16_t os[U];
+        raw_t ys[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            const int i = i0 + k * kSegWG;
+            xs[k] = i < i1 ? seg_x[i] : -1;
+            os[k] = i < i1 ? seg_off[i] : (uint16_t)0;
+        }
+        const unsigned int pat = (DT == TLI_BF16) ? 0xff80ff80u : 0xff800000u;
+        u4v* segv = reinterpret_cast<u4v*>(seg);
+        const u4v fill = {pat, pat, pat, pat};
+#pragma unroll
+        for (int i = 0; i < kSegBytes / 16 / kSegWG; ++i) segv[tid + i * kSegWG] = fill;
+#pragma unroll
+        for (int k = 0; k < U; ++k)
+            if (xs[k] >= 0) ys[k] = ld_row[xs[k]];
+        __syncthreads();
+        while (true) {
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (xs[k] >= 0) seg[os[k]] = ys[k];
+            i0 += U * kSegWG;
+            if (i0 - tid >= i1) break;  // uniform: the batch start of thread 0
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                const int i = i0 + k * kSegWG;
+                xs[k] = i < i1 ? seg_x[i] : -1;
+                os[k] = i < i1 ? seg_off[i] : (uint16_t)0;
+            }
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (xs[k] >= 0) ys[k] = ld_row[xs[k]];
+        }
+        __syncthreads();
+    }
     float* tr = tab_ref + (int64_t)b * nC;
     float* ts = tab_s + (int64_t)b * nC;
     float* tp = tab_p + (int64_t)b * nC;
-    for (int cl = wave; cl < kChunksPerSeg; cl += kSegWaves) {
+#pragma unroll
+    for (int k = 0; k < CPW; ++k) {
+        const int cl = wave + k * kSegWaves;
         const int c = sg * kChunksPerSeg + cl;
-        if (c >= nC) break;
-        ChunkRegs r;
-        if (c < n_whole) load_chunk_whole(rowv, c, lane, r);
-        else load_chunk_tail<DT>(rowv, c, lane, nvec, r);
-        float sw = 0.f, sp = 0.f;
+        if (cl >= kChunksPerSeg || c >= nC) break;
+        float sw = 0.f, sp = 0.f, sq = 0.f;
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             float x[EPV], y[EPV];
-            unpack<DT>(to_uint4(r.v[j]), x);
+            unpack<DT>(to_uint4(r[k].v[j]), x);
             if (f.rp.use_q) {
                 const u4v yv = reinterpret_cast<const u4v*>(seg)[cl * (kWave * kLoads) + j * kWave + lane];
                 unpack<DT>(to_uint4(yv), y);
             }
-            float a = 0.f, q = 0.f;
+            float a = 0.f, q = 0.f, g = 0.f;
 #pragma unroll
             for (int i = 0; i < EPV; ++i) {
                 const float pi = exp2_split(x[i], f.rp.ct_hi, f.rp.ct_lo, f.rp.lp_hi, f.rp.lp_lo);
@@ -718,15 +769,18 @@ __global__ __launch_bounds__(kSegWG) void k_final_scan_residual(
                 if (f.rp.use_q) {
                     const float qi = exp2_split(y[i], f.rp.cd_hi, f.rp.cd_lo, f.rp.lq_hi, f.rp.lq_lo);
                     wi = fmaxf(0.f, pi - qi);
-                    if (qi != qi) wi = qi;  // NaN in the drafter row must surface (fmaxf would drop it)
+                    g += qi;
                 }
                 a += wi;
                 q += pi;
             }
-            sw += a; sp += q;
+            sw += a; sp += q; sq += g;
         }
         sw = wave_sum(sw);
         sp = wave_sum(sp);
+        sq = wave_sum(sq);
+        // NaN or +inf among the drafter logits shows in the sum of q' (fmaxf above would drop it)
+        if (!(sq <= 3.0e38f)) sw = NAN;
         if (lane == 0) { tr[c] = 0.f; ts[c] = sw; tp[c] = sp; }
     }
 }
