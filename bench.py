@@ -69,6 +69,13 @@ def main():
         binding.tli_verify(m, inp["logits_t"], inp["logits_d"], w.tau_t, w.tau_d, d_out["tok_d"], d_out["lse_q"], u_acc,
                            inp["u_fin"], ws, out=v_out)
 
+    # one plain copy of known size (256 MiB read + 256 MiB written): the yardstick for rocprofv3's byte counters
+    calib_src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+    calib_dst = torch.empty_like(calib_src)
+    binding.tli_calib_copy(calib_src, calib_dst)
+    torch.cuda.synchronize()
+    del calib_src, calib_dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

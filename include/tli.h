@@ -142,6 +142,13 @@ int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls);
 int tli_profile_collect(int32_t kernel, double* total_ms, int32_t* launches);
 void tli_profile_disable(void);
 
+/*
+ * Benchmark utility (not part of the method): a plain device-to-device copy of `bytes` (multiple of
+ * 16, both pointers 16-byte aligned) by kernel k_calib_copy.  Hardware byte counters read for it are
+ * compared with its known traffic (bytes read + bytes written) to calibrate those counters.
+ */
+int tli_calib_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_stream);
+
 /* Human-readable name of a tli_status value. */
 const char* tli_status_string(int status);
 

@@ -20,7 +20,7 @@ FLAG_NONFINITE, FLAG_ZERO_MASS, FLAG_BAD_DRAFT, FLAG_DEGENERATE = 1, 2, 4, 8
 
 EXPORTS = (
     "tli_build_map", "tli_free_map", "tli_map_info", "tli_workspace_bytes", "tli_draft_sample", "tli_verify",
-    "tli_status_string", "tli_profile_enable", "tli_profile_collect", "tli_profile_disable",
+    "tli_status_string", "tli_profile_enable", "tli_profile_collect", "tli_profile_disable", "tli_calib_copy",
 )
 KERNELS = ("lse", "accept", "final_scan", "final_pick", "draft_scan", "draft_pick")
 
@@ -63,6 +63,8 @@ def load_library() -> ctypes.CDLL:
     lib.tli_profile_collect.restype = ctypes.c_int
     lib.tli_profile_disable.argtypes = []
     lib.tli_profile_disable.restype = None
+    lib.tli_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.tli_calib_copy.restype = ctypes.c_int
     lib.tli_status_string.argtypes = [ctypes.c_int]
     lib.tli_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -218,3 +220,12 @@ def tli_profile_collect(kernel: str):
 
 def tli_profile_disable() -> None:
     load_library().tli_profile_disable()
+
+
+def tli_calib_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    """Plain copy of src into dst (same byte size) by the library's calibration kernel."""
+    n = src.numel() * src.element_size()
+    assert n == dst.numel() * dst.element_size()
+    rc = load_library().tli_calib_copy(_ptr(src), _ptr(dst), n, _stream(stream))
+    if rc != 0:
+        raise TliError(rc, "tli_calib_copy")

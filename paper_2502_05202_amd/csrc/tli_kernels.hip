@@ -656,7 +656,7 @@ __global__ __launch_bounds__(kWG) void k_final_scan_bonus(const void* __restrict
 // ascending and nearly coalesced -- and drops each raw logit at its offset (LDS takes scattered 2-byte
 // writes at full rate).  Ids without a partner keep -inf, i.e. q' = 0.  The target segment is then
 // streamed once with 16-byte global loads next to conflict-free 16-byte LDS reads.
-// grid (B * nseg), 1024 threads; workgroups of bonus / flagged sequences exit at once.
+// grid (B rounded up to 8, times nseg), 1024 threads; workgroups of bonus / flagged sequences exit at once.
 constexpr int kSegBytes = 128 * 1024;
 constexpr int kSegWG = 1024;
 constexpr int kSegWaves = kSegWG / kWave;
@@ -665,8 +665,8 @@ template <int DT> constexpr int seg_elems() { return kSegBytes / Traits<DT>::ESZ
 
 template <int DT>
 __global__ __launch_bounds__(kSegWG) void k_final_scan_residual(
-    const void* __restrict__ logits_t, const void* __restrict__ logits_d, int K, int Vt, int Vd, int nC, int nseg,
-    double c_t, double c_d, const int32_t* __restrict__ d2t, const int32_t* __restrict__ seg_start,
+    const void* __restrict__ logits_t, const void* __restrict__ logits_d, int B, int K, int Vt, int Vd, int nC,
+    int nseg, double c_t, double c_d, const int32_t* __restrict__ d2t, const int32_t* __restrict__ seg_start,
     const int32_t* __restrict__ seg_x, const uint16_t* __restrict__ seg_off, const int32_t* __restrict__ tok_d,
     const double* __restrict__ lse_q, const int32_t* __restrict__ n_accepted, const int32_t* __restrict__ seq_status,
     const double* __restrict__ ws_lse_p, float* __restrict__ tab_ref, float* __restrict__ tab_s,
@@ -678,7 +678,12 @@ __global__ __launch_bounds__(kSegWG) void k_final_scan_residual(
     constexpr int kChunksPerSeg = G / CH;
     typedef typename std::conditional<DT == TLI_BF16, uint16_t, uint32_t>::type raw_t;
     __shared__ __attribute__((aligned(16))) raw_t seg[G];
-    const int b = blockIdx.x / nseg, sg = blockIdx.x - b * nseg;
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  The segments of one row all
+    // read that row's drafter logits, so they are given ids that land on the same XCD, next to each other
+    // in time: id = slot * 8 + xcd, row = (slot / nseg) * 8 + xcd, segment = slot % nseg.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int b = (slot / nseg) * 8 + xcd, sg = slot % nseg;
+    if (b >= B) return;
     const FinalRow f = final_row<DT>(b, K, Vd, n_accepted, seq_status, tok_d, d2t, ws_lse_p, lse_q, c_t, c_d);
     if (f.skip || f.bonus) return;
     const int tid = threadIdx.x;
@@ -870,6 +875,12 @@ __global__ __launch_bounds__(kWG) void k_final_pick(const void* __restrict__ log
     }
 }
 
+// ---- plain copy, used only to calibrate hardware byte counters against a known size -----------
+__global__ __launch_bounds__(kWG) void k_calib_copy(const u4v* __restrict__ src, u4v* __restrict__ dst, size_t nvec) {
+    const size_t stride = (size_t)gridDim.x * kWG;
+    for (size_t i = (size_t)blockIdx.x * kWG + threadIdx.x; i < nvec; i += stride) dst[i] = src[i];
+}
+
 // ======================================= host side ============================================
 
 struct Plan {
@@ -1021,8 +1032,8 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     {
         KernelTimer t(TLI_KERNEL_FINAL_SCAN, st);
         const int nseg = a.map->nseg[DT];
-        hipLaunchKernelGGL(k_final_scan_residual<DT>, dim3((unsigned)B * nseg), dim3(kSegWG), 0, st, a.logits_t,
-                           a.logits_d, K, Vt, Vd, a.pf.nC, nseg, a.c_t, a.c_d, a.map->d2t, a.map->seg_start[DT],
+        hipLaunchKernelGGL(k_final_scan_residual<DT>, dim3((unsigned)((B + 7) / 8) * 8 * nseg), dim3(kSegWG), 0, st,
+                           a.logits_t, a.logits_d, B, K, Vt, Vd, a.pf.nC, nseg, a.c_t, a.c_d, a.map->d2t, a.map->seg_start[DT],
                            a.map->seg_x[DT], a.map->seg_off[DT], a.tok_d, a.lse_q, a.n_accepted, a.seq_status,
                            a.ws_lse_p, a.tab_ref, a.tab_s, a.tab_p);
         hipLaunchKernelGGL(k_final_scan_bonus<DT>, dim3((unsigned)B * a.pf.nsplit), dim3(kWG), 0, st, a.logits_t, K,
@@ -1040,6 +1051,13 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
 }  // namespace
 
 extern "C" {
+
+int tli_calib_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
+    if (!src || !dst || bytes == 0 || bytes % 16 != 0 || !aligned16(src) || !aligned16(dst)) return TLI_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(k_calib_copy, dim3(4096), dim3(kWG), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const u4v*>(src), static_cast<u4v*>(dst), bytes / 16);
+    return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
+}
 
 int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls) {
     tli_profile_disable();
