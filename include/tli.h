@@ -130,12 +130,12 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
  *   tli_profile_disable : destroys the events.
  */
 typedef enum {
-    TLI_KERNEL_LSE = 0,        /* tli_verify: log-normalisers of the K target rows of every sequence  */
-    TLI_KERNEL_ACCEPT = 1,     /* tli_verify: accept tests + first-reject scan                        */
-    TLI_KERNEL_FINAL_SCAN = 2, /* tli_verify: chunk masses of the residual / bonus row                */
-    TLI_KERNEL_FINAL_PICK = 3, /* tli_verify: draw the extra token                                    */
-    TLI_KERNEL_DRAFT_SCAN = 4, /* tli_draft_sample: chunk masses of q' over the shared ids            */
-    TLI_KERNEL_DRAFT_PICK = 5, /* tli_draft_sample: draw the draft token                              */
+    TLI_KERNEL_LSE = 0,        /* tli_verify: log-normalisers of the K target rows of every sequence      */
+    TLI_KERNEL_ACCEPT = 1,     /* tli_verify: accept tests + first-reject scan                            */
+    TLI_KERNEL_FINAL_SCAN = 2, /* tli_verify: chunk masses of the residual / bonus rows                   */
+    TLI_KERNEL_FINAL_PICK = 3, /* tli_verify: draw of the extra token                                     */
+    TLI_KERNEL_DRAFT_SCAN = 4, /* tli_draft_sample: q' over the shared ids (+ the draw, one workgroup/row) */
+    TLI_KERNEL_DRAFT_PICK = 5, /* tli_draft_sample: the draw, only when rows are split over workgroups     */
     TLI_KERNEL_COUNT = 6
 } tli_kernel_id;
 int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls);

@@ -45,33 +45,33 @@ template <> struct Traits<TLI_BF16> {
 };
 template <int DT> constexpr int chunk_elems() { return kWave * kLoads * Traits<DT>::EPV; }
 
-__device__ inline float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
-__device__ inline uint32_t as_u(float f) { return __builtin_bit_cast(uint32_t, f); }
+__device__ __forceinline__ float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u(float f) { return __builtin_bit_cast(uint32_t, f); }
 
-template <int DT> __device__ inline void unpack(const uint4& v, float* x);
-template <> __device__ inline void unpack<TLI_F32>(const uint4& v, float* x) {
+template <int DT> __device__ __forceinline__ void unpack(const uint4& v, float* x);
+template <> __device__ __forceinline__ void unpack<TLI_F32>(const uint4& v, float* x) {
     x[0] = as_f(v.x); x[1] = as_f(v.y); x[2] = as_f(v.z); x[3] = as_f(v.w);
 }
-template <> __device__ inline void unpack<TLI_BF16>(const uint4& v, float* x) {
+template <> __device__ __forceinline__ void unpack<TLI_BF16>(const uint4& v, float* x) {
     x[0] = as_f(v.x << 16); x[1] = as_f(v.x & 0xffff0000u);
     x[2] = as_f(v.y << 16); x[3] = as_f(v.y & 0xffff0000u);
     x[4] = as_f(v.z << 16); x[5] = as_f(v.z & 0xffff0000u);
     x[6] = as_f(v.w << 16); x[7] = as_f(v.w & 0xffff0000u);
 }
 
-template <int DT> __device__ inline float load_elem(const void* base, int64_t idx);
-template <> __device__ inline float load_elem<TLI_F32>(const void* base, int64_t idx) {
+template <int DT> __device__ __forceinline__ float load_elem(const void* base, int64_t idx);
+template <> __device__ __forceinline__ float load_elem<TLI_F32>(const void* base, int64_t idx) {
     return static_cast<const float*>(base)[idx];
 }
-template <> __device__ inline float load_elem<TLI_BF16>(const void* base, int64_t idx) {
+template <> __device__ __forceinline__ float load_elem<TLI_BF16>(const void* base, int64_t idx) {
     return as_f(static_cast<uint32_t>(static_cast<const uint16_t*>(base)[idx]) << 16);
 }
 
 // ---- wave64 reductions on the DPP network (result broadcast through an SGPR) -------------------
-template <int CTRL, int ROW_MASK> __device__ inline float dpp(float old, float v) {
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp(float old, float v) {
     return as_f(__builtin_amdgcn_update_dpp(as_u(old), as_u(v), CTRL, ROW_MASK, 0xF, false));
 }
-__device__ inline float wave_sum(float v) {
+__device__ __forceinline__ float wave_sum(float v) {
     v += dpp<0xB1, 0xF>(0.f, v);   // quad_perm [1,0,3,2]
     v += dpp<0x4E, 0xF>(0.f, v);   // quad_perm [2,3,0,1]
     v += dpp<0x124, 0xF>(0.f, v);  // row_ror 4
@@ -80,7 +80,7 @@ __device__ inline float wave_sum(float v) {
     v += dpp<0x143, 0xC>(0.f, v);  // row_bcast 31 into rows 2,3
     return as_f(__builtin_amdgcn_readlane(as_u(v), 63));
 }
-__device__ inline float wave_max(float v) {
+__device__ __forceinline__ float wave_max(float v) {
     const float ninf = -INFINITY;
     v = fmaxf(v, dpp<0xB1, 0xF>(ninf, v));
     v = fmaxf(v, dpp<0x4E, 0xF>(ninf, v));
@@ -91,7 +91,7 @@ __device__ inline float wave_max(float v) {
     return as_f(__builtin_amdgcn_readlane(as_u(v), 63));
 }
 
-__device__ inline float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---- chunk loads ------------------------------------------------------------------------------
 // Chunk c of a row = vectors [c*256, c*256+256); load j of lane l is vector c*256 + j*64 + l.
@@ -102,10 +102,10 @@ struct ChunkRegs {
     u4v v[kLoads];
 };
 
-__device__ inline uint4 to_uint4(const u4v& t) { return make_uint4(t.x, t.y, t.z, t.w); }
+__device__ __forceinline__ uint4 to_uint4(const u4v& t) { return make_uint4(t.x, t.y, t.z, t.w); }
 
 // whole chunk: every vector is in range, no guards
-__device__ inline void load_chunk_whole(const u4v* rowv, int c, int lane, ChunkRegs& r) {
+__device__ __forceinline__ void load_chunk_whole(const u4v* rowv, int c, int lane, ChunkRegs& r) {
     const u4v* p = rowv + (int64_t)c * (kWave * kLoads) + lane;
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) r.v[j] = __builtin_nontemporal_load(p + j * kWave);
@@ -113,7 +113,7 @@ __device__ inline void load_chunk_whole(const u4v* rowv, int c, int lane, ChunkR
 
 // last, partial chunk of a row: vectors past the end read as -inf
 template <int DT>
-__device__ inline void load_chunk_tail(const u4v* rowv, int c, int lane, int nvec, ChunkRegs& r) {
+__device__ __forceinline__ void load_chunk_tail(const u4v* rowv, int c, int lane, int nvec, ChunkRegs& r) {
     const unsigned int pat = (DT == TLI_BF16) ? 0xff80ff80u : 0xff800000u;
     const int64_t v0 = (int64_t)c * (kWave * kLoads) + lane;
 #pragma unroll
@@ -126,16 +126,16 @@ __device__ inline void load_chunk_tail(const u4v* rowv, int c, int lane, int nve
 }
 
 // Bits of the shared-id mask for the EPV elements of vector vi.
-template <int DT> __device__ inline uint32_t mask_bits(const uint8_t* bits, int64_t vi) {
+template <int DT> __device__ __forceinline__ uint32_t mask_bits(const uint8_t* bits, int64_t vi) {
     if (DT == TLI_BF16) return bits[vi];
     return (bits[vi >> 1] >> ((vi & 1) * 4)) & 0xFu;
 }
 
 // Reduce one chunk held in registers to (ref, s): sum 2^(x*c) over the chunk = s * 2^ref, with
-// ref = max over the chunk of fp32(x*c) (-inf and s = 0 for a chunk without finite entries).
+// ref = ceil(max over the chunk of fp32(x*c)) (-inf and s = 0 for a chunk without finite entries).
 // A NaN or +inf logit turns s into NaN.  Wave-uniform results.  WHOLE: every element is < V.
 template <int DT, bool MASKED, bool WHOLE>
-__device__ inline void reduce_chunk(const ChunkRegs& r, int c, int lane, int V, float cs, const uint8_t* bits,
+__device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane, int V, float cs, const uint8_t* bits,
                                     float& ref_out, float& s_out) {
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int N = EPV * kLoads;
@@ -166,7 +166,9 @@ __device__ inline void reduce_chunk(const ChunkRegs& r, int c, int lane, int V, 
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[i & 3] += exp2_hw(fmaf(x[i], cs, nref));
     float s = (acc[0] + acc[1]) + (acc[2] + acc[3]);
-    const float R = wave_max(ref);
+    // the chunk's reference is rounded up to an integer: every later rescaling between references is then
+    // an exact power of two (ldexp), in fp32 and fp64 alike
+    const float R = ceilf(wave_max(ref));
     s = (m == -INFINITY) ? 0.f : s * exp2_hw(ref - R);
     ref_out = R;
     s_out = wave_sum(s);
@@ -177,7 +179,7 @@ __device__ inline void reduce_chunk(const ChunkRegs& r, int c, int lane, int V, 
 // next chunk are in flight while the current one is reduced.  A row has at most one partial chunk
 // (its last); the wave that owns it handles it after its whole chunks.
 template <int DT, bool MASKED, class Sink>
-__device__ inline void scan_chunks(const u4v* rowv, int V, int c_begin, int c_end, float cs, const uint8_t* bits,
+__device__ __forceinline__ void scan_chunks(const u4v* rowv, int V, int c_begin, int c_end, float cs, const uint8_t* bits,
                                    Sink&& sink) {
     constexpr int EPV = Traits<DT>::EPV;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -220,16 +222,28 @@ __device__ inline void scan_chunks(const u4v* rowv, int V, int c_begin, int c_en
     }
 }
 
+// 2^(a-b) for integer-valued references a <= b (or -inf / +inf): exact.  0 if a = -inf, NaN if both +inf.
+__device__ __forceinline__ float pow2_diff_f(float a, float b) {
+    if (a == -INFINITY) return 0.f;
+    const float d = a - b;
+    if (d != d) return NAN;
+    return ldexpf(1.f, (int)fmaxf(d, -200.f));
+}
+__device__ __forceinline__ double exp2_diff(float a, float b) {
+    if (a == -INFINITY) return 0.0;
+    const float d = a - b;
+    if (d != d) return NAN;
+    return ldexp(1.0, (int)fmaxf(d, -1100.f));
+}
+
 // running (ref, sum) of a wave, sum kept in fp64
 struct Running {
     float ref = -INFINITY;
     double s = 0.0;
-    __device__ inline void add(float r, float sc) {
+    __device__ __forceinline__ void add(float r, float sc) {
         const float nr = fmaxf(ref, r);
         if (nr == -INFINITY) return;
-        const float a = (ref == -INFINITY) ? 0.f : exp2_hw(ref - nr);
-        const float b = (r == -INFINITY) ? 0.f : exp2_hw(r - nr);
-        s = s * (double)a + (double)sc * (double)b;
+        s = s * (double)pow2_diff_f(ref, nr) + (double)sc * (double)pow2_diff_f(r, nr);
         ref = nr;
     }
 };
@@ -240,9 +254,6 @@ struct Part {  // partial log-normaliser of (a split of) a row: sum 2^(x*c) = s 
     double s;
 };
 
-__device__ inline double exp2_diff(float a, float b) {  // 2^(a-b) in fp64, 0 if a = -inf
-    return (a == -INFINITY) ? 0.0 : exp2((double)a - (double)b);
-}
 
 // ---- kernel: log-normaliser partials of the K target rows each sequence needs -----------------
 // Standard SD appendix, verification loop: p_k(d_k) needs the normaliser of every target row k < K.
@@ -278,7 +289,7 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
 // Used for drafter rows (masked: the intersection algorithm's q') and for the bonus target row.
 // Workgroup `split` of a row owns chunks [split*cps, (split+1)*cps).
 template <int DT, bool MASKED>
-__device__ inline void table_scan(const u4v* rowv, int split, int V, int nC, int cps, float cs, const uint8_t* bits,
+__device__ __forceinline__ void table_scan(const u4v* rowv, int split, int V, int nC, int cps, float cs, const uint8_t* bits,
                                   float* tab_ref, float* tab_s) {
     const int lane = threadIdx.x & 63;
     scan_chunks<DT, MASKED>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, bits, [&](int c, float r, float sc) {
@@ -297,29 +308,28 @@ __global__ __launch_bounds__(kWG) void k_draft_scan(const void* __restrict__ log
     table_scan<DT, true>(rowv, split, V, nC, cps, cs, bits, tab_ref + (int64_t)row * nC, tab_s + (int64_t)row * nC);
 }
 
-// ---- block-level helpers for the pick kernels (256 threads) ----------------------------------
-struct PickShared {
-    double wsum[kWaves];
-    float wmax[kWaves];
+// ---- block-level helpers for the samplers (NT threads) ---------------------------------------
+template <int NT> struct PickShared {
+    double wsum[NT / kWave];
+    float wmax[NT / kWave];
     int cand;
     int last_pos;
     double theta_local;
-    double total;
 };
 
-__device__ inline float block_max(float v, PickShared& sh) {
+template <int NT> __device__ __forceinline__ float block_max(float v, PickShared<NT>& sh) {
     v = wave_max(v);
     const int wave = threadIdx.x >> 6;
     __syncthreads();
     if ((threadIdx.x & 63) == 0) sh.wmax[wave] = v;
     __syncthreads();
     float m = sh.wmax[0];
-    for (int w = 1; w < kWaves; ++w) m = fmaxf(m, sh.wmax[w]);
+    for (int w = 1; w < NT / kWave; ++w) m = fmaxf(m, sh.wmax[w]);
     return m;
 }
 
 // exclusive prefix of v over the block's threads in fp64; *total = block sum
-__device__ inline double block_excl_scan(double v, PickShared& sh, double* total) {
+template <int NT> __device__ __forceinline__ double block_excl_scan(double v, PickShared<NT>& sh, double* total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     double inc = v;
 #pragma unroll
@@ -331,7 +341,7 @@ __device__ inline double block_excl_scan(double v, PickShared& sh, double* total
     if (lane == kWave - 1) sh.wsum[wave] = inc;
     __syncthreads();
     double base = 0.0, tot = 0.0;
-    for (int w = 0; w < kWaves; ++w) {
+    for (int w = 0; w < NT / kWave; ++w) {
         if (w < wave) base += sh.wsum[w];
         tot += sh.wsum[w];
     }
@@ -342,15 +352,16 @@ __device__ inline double block_excl_scan(double v, PickShared& sh, double* total
 // Chunk search.  T_c (fp64 chunk masses) for this thread's contiguous chunks [c0, c1) are produced
 // by `mass(c)`.  Returns the first chunk whose inclusive prefix exceeds theta = u * total and
 // theta - (prefix before that chunk); -1 if total is not positive.  *total_out = total.
-template <class MassFn>
-__device__ inline int find_chunk(int nC, double u, MassFn mass, PickShared& sh, double* theta_local,
+template <int NT, class MassFn>
+__device__ __forceinline__ int find_chunk(int nC, double u, MassFn mass, PickShared<NT>& sh, double* theta_local,
                                  double* total_out) {
-    const int per = (nC + kWG - 1) / kWG;
+    const int per = (nC + NT - 1) / NT;
     const int c0 = min(nC, (int)threadIdx.x * per), c1 = min(nC, c0 + per);
-    double mine = 0.0;
-    for (int c = c0; c < c1; ++c) mine += mass(c);
+    const double first = (c0 < c1) ? mass(c0) : 0.0;  // the common case is one chunk per thread: keep it
+    double mine = first;
+    for (int c = c0 + 1; c < c1; ++c) mine += mass(c);
     double total;
-    const double excl = block_excl_scan(mine, sh, &total);
+    const double excl = block_excl_scan<NT>(mine, sh, &total);
     *total_out = total;
     if (!(total > 0.0)) return -1;  // zero, negative or NaN
     const double theta = u * total;
@@ -361,7 +372,7 @@ __device__ inline int find_chunk(int nC, double u, MassFn mass, PickShared& sh, 
     double before = 0.0;
     int last_pos = -1;
     for (int c = c0; c < c1; ++c) {
-        const double t = mass(c);
+        const double t = (c == c0) ? first : mass(c);
         if (t > 0.0) last_pos = c;
         if (found < 0 && run + t > theta) { found = c; before = run; }
         run += t;
@@ -380,15 +391,16 @@ __device__ inline int find_chunk(int nC, double u, MassFn mass, PickShared& sh, 
     return pick;
 }
 
-// In-chunk search: thread t holds the weights of elements [e0, e0+N) in order.  Returns the first
-// element whose inclusive prefix exceeds theta_local; if none, the last element with weight > 0.
-template <int N>
-__device__ inline int find_in_chunk(const double (&w)[N], int64_t e0, double theta_local, PickShared& sh) {
+// In-chunk search: thread t holds the weights of elements [e0, e0+N) in order (threads beyond the
+// chunk hold zeros).  Returns the first element whose inclusive prefix exceeds theta_local; if none,
+// the last element with weight > 0.
+template <int N, int NT>
+__device__ __forceinline__ int find_in_chunk(const double (&w)[N], int64_t e0, double theta_local, PickShared<NT>& sh) {
     double mine = 0.0;
 #pragma unroll
     for (int i = 0; i < N; ++i) mine += w[i];
     double total;
-    const double excl = block_excl_scan(mine, sh, &total);
+    const double excl = block_excl_scan<NT>(mine, sh, &total);
     if (threadIdx.x == 0) { sh.cand = 0x7fffffff; sh.last_pos = -1; }
     __syncthreads();
     double run = excl;
@@ -408,13 +420,14 @@ __device__ inline int find_in_chunk(const double (&w)[N], int64_t e0, double the
 }
 
 // weights of one 16-byte vector of a softmax row relative to reference `nref` (= -ref), as in
-// reduce_chunk: 2^(x*c - ref); elements >= V or masked out get 0.
+// reduce_chunk: 2^(x*c - ref); elements >= V or masked out get 0.  Threads with vi outside the
+// chunk [vlo, vhi) get zeros.
 template <int DT, bool MASKED>
-__device__ inline void softmax_vec_weights(const uint4* rowv, int64_t vi, int V, float cs, float nref,
+__device__ __forceinline__ void softmax_vec_weights(const uint4* rowv, int64_t vi, int64_t vhi, int V, float cs, float nref,
                                            const uint8_t* bits, double* w) {
     constexpr int EPV = Traits<DT>::EPV;
     float x[EPV];
-    if (vi * EPV < V) {
+    if (vi < vhi && vi * EPV < V) {
         unpack<DT>(rowv[vi], x);
         const uint32_t mb = MASKED ? mask_bits<DT>(bits, vi) : 0xffu;
 #pragma unroll
@@ -428,54 +441,96 @@ __device__ inline void softmax_vec_weights(const uint4* rowv, int64_t vi, int V,
     }
 }
 
-// ---- kernel: draw the draft token of each drafter row from its chunk table ---------------------
-// Standard SD appendix, drafting loop, with q' of the intersection algorithm.  grid (R).
+// Inverse-CDF sample of a (masked) softmax row from its chunk table.  Returns the id, or -1 if the
+// row has no usable mass (then *total_out is NaN for a NaN/+inf logit, else 0).  *M_out = table max.
+template <int DT, bool MASKED, int NT>
+__device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int nC, float cs, const uint8_t* bits,
+                                         const float* tr, const float* ts, double u, PickShared<NT>& sh,
+                                         float* M_out, double* total_out) {
+    constexpr int EPV = Traits<DT>::EPV;
+    float m = -INFINITY;
+    for (int c = threadIdx.x; c < nC; c += NT) m = fmaxf(m, tr[c]);
+    const float M = block_max<NT>(m, sh);
+    *M_out = M;
+    double theta_local;
+    const int c = find_chunk<NT>(
+        nC, u, [&](int cc) { return (double)ts[cc] * exp2_diff(tr[cc], M); }, sh,
+        &theta_local, total_out);
+    if (c < 0) {
+        if (M == INFINITY) *total_out = NAN;
+        return -1;
+    }
+    double w[EPV];
+    const int64_t v0 = (int64_t)c * (kWave * kLoads);
+    const int64_t vi = v0 + threadIdx.x;
+    softmax_vec_weights<DT, MASKED>(static_cast<const uint4*>(rowp), vi, v0 + kWave * kLoads, V, cs, -M, bits, w);
+    return find_in_chunk<EPV, NT>(w, vi * EPV, theta_local, sh);
+}
+
+// ---- draft token of one drafter row from its chunk table ----------------------------------------
+// Standard SD appendix, drafting loop, with q' of the intersection algorithm.
+struct DraftOut {
+    const float* u_draft;
+    int32_t *tok_d, *tok_t;
+    double *q_tok, *lse_q;
+    int32_t* row_status;
+};
+
+template <int DT, int NT>
+__device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V, int nC, float cs, double c_ratio,
+                                      double inv_temp, const uint8_t* bits, const int32_t* d2t, const float* tr,
+                                      const float* ts, const DraftOut& o, PickShared<NT>& sh) {
+    float M;
+    double total;
+    const int d = sample_softmax_row<DT, true, NT>(rowp, V, nC, cs, bits, tr, ts, (double)o.u_draft[row], sh,
+                                                             &M, &total);
+    if (threadIdx.x != 0) return;
+    if (d < 0) {  // no usable mass: NaN/+inf among the shared logits, or all of them -inf
+        const bool nonfinite = (total != total);
+        o.tok_d[row] = -1; o.tok_t[row] = -1;
+        if (o.q_tok) o.q_tok[row] = 0.0;
+        o.lse_q[row] = nonfinite ? NAN : -INFINITY;
+        o.row_status[row] = nonfinite ? TLI_FLAG_NONFINITE : TLI_FLAG_ZERO_MASS;
+        return;
+    }
+    const double lse = kLn2 * ((double)M * c_ratio + log2(total));
+    o.tok_d[row] = d;
+    o.tok_t[row] = d2t[d];
+    o.lse_q[row] = lse;
+    if (o.q_tok) o.q_tok[row] = exp((double)load_elem<DT>(rowp, d) * inv_temp - lse);
+    o.row_status[row] = 0;
+}
+
+// kernel: sampler of the split path (rows cut over several workgroups by k_draft_scan).  grid (R).
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_draft_pick(const void* __restrict__ logits, int64_t row_stride, int V,
                                                      int nC, float cs, double c_ratio, double inv_temp,
                                                      const uint8_t* __restrict__ bits,
                                                      const int32_t* __restrict__ d2t,
                                                      const float* __restrict__ tab_ref,
-                                                     const float* __restrict__ tab_s,
-                                                     const float* __restrict__ u_draft, int32_t* __restrict__ tok_d,
-                                                     int32_t* __restrict__ tok_t, double* __restrict__ q_tok,
-                                                     double* __restrict__ lse_q, int32_t* __restrict__ row_status) {
-    constexpr int EPV = Traits<DT>::EPV;
-    __shared__ PickShared sh;
+                                                     const float* __restrict__ tab_s, DraftOut o) {
+    __shared__ PickShared<kWG> sh;
     const int row = blockIdx.x;
     const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
-    const uint4* rowv = reinterpret_cast<const uint4*>(rowp);
-    const float* tr = tab_ref + (int64_t)row * nC;
-    const float* ts = tab_s + (int64_t)row * nC;
-    float m = -INFINITY;
-    for (int c = threadIdx.x; c < nC; c += kWG) m = fmaxf(m, tr[c]);
-    const float M = block_max(m, sh);
-    double theta_local, total;
-    const int c = find_chunk(nC, (double)u_draft[row],
-                             [&](int cc) { return (double)ts[cc] * exp2_diff(tr[cc], M); }, sh, &theta_local, &total);
-    if (c < 0) {  // no usable mass: NaN/+inf among the shared logits, or all of them -inf
-        if (threadIdx.x == 0) {
-            const bool nonfinite = (total != total) || (M == INFINITY);
-            tok_d[row] = -1; tok_t[row] = -1;
-            if (q_tok) q_tok[row] = 0.0;
-            lse_q[row] = nonfinite ? NAN : -INFINITY;
-            row_status[row] = nonfinite ? TLI_FLAG_NONFINITE : TLI_FLAG_ZERO_MASS;
-        }
-        return;
-    }
-    double w[EPV];
-    const int64_t vi = (int64_t)c * (kWave * kLoads) + threadIdx.x;
-    softmax_vec_weights<DT, true>(rowv, vi, V, cs, -M, bits, w);
-    const int d = find_in_chunk<EPV>(w, vi * EPV, theta_local, sh);
-    if (threadIdx.x == 0) {
-        const double lse = kLn2 * ((double)M * c_ratio + log2(total));
-        const bool have = d >= 0;  // the located chunk always holds a positive weight; never index with -1
-        tok_d[row] = d;
-        tok_t[row] = have ? d2t[d] : -1;
-        lse_q[row] = lse;
-        if (q_tok) q_tok[row] = have ? exp((double)load_elem<DT>(rowp, d) * inv_temp - lse) : 0.0;
-        row_status[row] = have ? 0 : TLI_FLAG_ZERO_MASS;
-    }
+    draft_pick_row<DT, kWG>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tab_ref + (int64_t)row * nC,
+                                   tab_s + (int64_t)row * nC, o, sh);
+}
+
+// kernel: one workgroup per drafter row scans it into a chunk table in LDS and samples from it at
+// once, while the other workgroups on the CU keep streaming their rows.  grid (R); nC <= kLdsChunks.
+constexpr int kLdsChunks = 1024;
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ logits, int64_t row_stride, int V,
+                                                      int nC, float cs, double c_ratio, double inv_temp,
+                                                      const uint8_t* __restrict__ bits,
+                                                      const int32_t* __restrict__ d2t, DraftOut o) {
+    __shared__ PickShared<kWG> sh;
+    __shared__ float tr[kLdsChunks], ts[kLdsChunks];
+    const int row = blockIdx.x;
+    const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
+    table_scan<DT, true>(reinterpret_cast<const u4v*>(rowp), 0, V, nC, nC, cs, bits, tr, ts);
+    __syncthreads();
+    draft_pick_row<DT, kWG>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tr, ts, o, sh);
 }
 
 // ---- kernel: accept tests and first-reject scan ------------------------------------------------
@@ -550,24 +605,24 @@ struct ResidualParams {
 
 // 2^(x*(c_hi+c_lo) - (l_hi+l_lo)) with one rounding of each partial product.  c_lo is strictly positive
 // (see split_scale), so a -inf logit gives -inf + -inf = -inf (probability 0), never inf - inf.
-__device__ inline float exp2_split(float x, float c_hi, float c_lo, float l_hi, float l_lo) {
+__device__ __forceinline__ float exp2_split(float x, float c_hi, float c_lo, float l_hi, float l_lo) {
     return exp2_hw(fmaf(x, c_hi, -l_hi) + fmaf(x, c_lo, -l_lo));
 }
 
-__device__ inline void split_hi_lo(double v, float& hi, float& lo) {
+__device__ __forceinline__ void split_hi_lo(double v, float& hi, float& lo) {
     hi = (float)v;
     lo = (float)(v - (double)hi);
 }
 
 // scale c > 0 as hi + lo with hi < c, so that lo > 0
-__device__ inline void split_scale(double c, float& hi, float& lo) {
+__device__ __forceinline__ void split_scale(double c, float& hi, float& lo) {
     hi = (float)c;
     if ((double)hi >= c) hi = as_f(as_u(hi) - 1u);
     lo = (float)(c - (double)hi);
 }
 
 template <int DT>
-__device__ inline void residual_vec(const uint4& v, int64_t e0, int V, const ResidualParams& rp,
+__device__ __forceinline__ void residual_vec(const uint4& v, int64_t e0, int V, const ResidualParams& rp,
                                     const int32_t* __restrict__ t2d, const void* __restrict__ ld_row, float* p,
                                     float* w) {
     constexpr int EPV = Traits<DT>::EPV;
@@ -605,7 +660,7 @@ struct FinalRow {
 };
 
 template <int DT>
-__device__ inline FinalRow final_row(int b, int K, int Vd, const int32_t* n_accepted, const int32_t* seq_status,
+__device__ __forceinline__ FinalRow final_row(int b, int K, int Vd, const int32_t* n_accepted, const int32_t* seq_status,
                                      const int32_t* tok_d, const int32_t* d2t, const double* ws_lse_p,
                                      const double* lse_q, double c_t, double c_d) {
     FinalRow f;
@@ -629,20 +684,87 @@ __device__ inline FinalRow final_row(int b, int K, int Vd, const int32_t* n_acce
     return f;
 }
 
+// ---- extra token of one sequence from the chunk tables of its row ------------------------------
+// Standard SD appendix, last step: writes out_tok[b, n_accepted[b]]; for bonus rows also lse_p[b, K].
+struct FinalOut {
+    const float* u_fin;
+    int32_t *n_accepted, *out_tok;
+    double* lse_p;
+    int32_t* seq_status;
+};
+
+template <int DT, int NT>
+__device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const void* logits_t, const void* logits_d, int K,
+                                      int Vt, int Vd, int nC, float cs_t, double ratio_t, const int32_t* t2d,
+                                      const float* tr, const float* ts, const float* tp, const FinalOut& o,
+                                      PickShared<NT>& sh) {
+    constexpr int EPV = Traits<DT>::EPV;
+    const char* rowp = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + f.n) * Vt * Traits<DT>::ESZ;
+    const double u = (double)o.u_fin[b];
+    int tok = -1;
+    int add_flags = 0;
+    bool nonfinite = false;
+    if (f.bonus) {
+        float M;
+        double total;
+        tok = sample_softmax_row<DT, false, NT>(rowp, Vt, nC, cs_t, nullptr, tr, ts, u, sh, &M, &total);
+        // no usable mass: NaN/+inf, or a bonus row of only -inf -- no distribution to sample either way
+        if (tok < 0) nonfinite = true;
+        else if (threadIdx.x == 0 && o.lse_p) o.lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
+    } else {
+        const char* ldp = static_cast<const char*>(logits_d) + ((int64_t)b * K + f.n) * Vd * Traits<DT>::ESZ;
+        double theta_local, total;
+        int c = find_chunk<NT>(nC, u, [&](int cc) { return (double)ts[cc]; }, sh, &theta_local, &total);
+        bool degenerate = false;
+        if (c < 0) {
+            if (total != total) {
+                nonfinite = true;
+            } else {  // residual identically zero: fall back to p of the same row
+                degenerate = true;
+                add_flags |= TLI_FLAG_DEGENERATE;
+                c = find_chunk<NT>(nC, u, [&](int cc) { return (double)tp[cc]; }, sh, &theta_local, &total);
+                if (c < 0) nonfinite = true;
+            }
+        }
+        if (!nonfinite) {
+            const int64_t v0 = (int64_t)c * (kWave * kLoads);
+            const int64_t vi = v0 + threadIdx.x;
+            double wd[EPV];
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) wd[i] = 0.0;
+            if (threadIdx.x < kWave * kLoads && vi * EPV < Vt) {
+                float p[EPV], w[EPV];
+                residual_vec<DT>(reinterpret_cast<const uint4*>(rowp)[vi], vi * EPV, Vt, f.rp, t2d, ldp, p, w);
+#pragma unroll
+                for (int i = 0; i < EPV; ++i) wd[i] = degenerate ? (double)p[i] : (double)w[i];
+            }
+            tok = find_in_chunk<EPV, NT>(wd, vi * EPV, theta_local, sh);
+        }
+    }
+    if (threadIdx.x == 0) {
+        if (nonfinite) {
+            o.n_accepted[b] = 0;
+            for (int k = 0; k <= K; ++k) o.out_tok[(int64_t)b * (K + 1) + k] = -1;
+            o.seq_status[b] |= TLI_FLAG_NONFINITE;
+        } else {
+            o.out_tok[(int64_t)b * (K + 1) + f.n] = tok;
+            if (add_flags) o.seq_status[b] |= add_flags;
+        }
+    }
+}
+
 // ---- kernels: chunk tables of the row the extra token is drawn from ----------------------------
-// Bonus rows (nothing rejected): (ref, s) softmax table of target row K.  grid (B * nsplit), 256 threads;
-// workgroups of sequences that rejected a draft exit at once.
+// Bonus rows (nothing rejected): (ref, s) softmax table of target row K.  grid (B * nsplit), 256 threads; workgroups of sequences that rejected a draft exit at once.
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_final_scan_bonus(const void* __restrict__ logits_t, int K, int Vt, int nC,
-                                                           int cps, int nsplit, float cs_t,
-                                                           const int32_t* __restrict__ n_accepted,
-                                                           const int32_t* __restrict__ seq_status,
-                                                           float* __restrict__ tab_ref, float* __restrict__ tab_s) {
+__global__ __launch_bounds__(kWG) void k_final_bonus(const void* __restrict__ logits_t, int K, int Vt, int nC, int cps,
+                                                      int nsplit, float cs_t, const int32_t* __restrict__ n_accepted,
+                                                      const int32_t* __restrict__ seq_status,
+                                                      float* __restrict__ tab_ref, float* __restrict__ tab_s) {
     const int b = blockIdx.x / nsplit, split = blockIdx.x - b * nsplit;
     if ((seq_status[b] & TLI_FLAG_NONFINITE) || n_accepted[b] != K) return;
-    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
-                                                    ((int64_t)b * (K + 1) + K) * Vt * Traits<DT>::ESZ);
-    table_scan<DT, false>(rowv, split, Vt, nC, cps, cs_t, nullptr, tab_ref + (int64_t)b * nC, tab_s + (int64_t)b * nC);
+    const char* rowp = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + K) * Vt * Traits<DT>::ESZ;
+    table_scan<DT, false>(reinterpret_cast<const u4v*>(rowp), split, Vt, nC, cps, cs_t, nullptr,
+                          tab_ref + (int64_t)b * nC, tab_s + (int64_t)b * nC);
 }
 
 // Residual rows (first rejection at position n < K): tab_s = chunk sums of max(0, p_n - q'_n), tab_p =
@@ -664,7 +786,7 @@ constexpr int kGatherU = 12;
 template <int DT> constexpr int seg_elems() { return kSegBytes / Traits<DT>::ESZ; }
 
 template <int DT>
-__global__ __launch_bounds__(kSegWG) void k_final_scan_residual(
+__global__ __launch_bounds__(kSegWG) void k_final_residual(
     const void* __restrict__ logits_t, const void* __restrict__ logits_d, int B, int K, int Vt, int Vd, int nC,
     int nseg, double c_t, double c_d, const int32_t* __restrict__ d2t, const int32_t* __restrict__ seg_start,
     const int32_t* __restrict__ seg_x, const uint16_t* __restrict__ seg_off, const int32_t* __restrict__ tok_d,
@@ -790,89 +912,22 @@ __global__ __launch_bounds__(kSegWG) void k_final_scan_residual(
     }
 }
 
-// ---- kernel: draw the extra token ------------------------------------------------------------
-// grid (B).  Writes out_tok[b, n_accepted[b]]; for bonus rows also lse_p[b, K].
+// kernel: draw the extra token of every sequence from its row's chunk tables.  grid (B), 256 threads.
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_final_pick(const void* __restrict__ logits_t, const void* __restrict__ logits_d,
                                                      int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
                                                      double c_t, double c_d, const int32_t* __restrict__ d2t,
                                                      const int32_t* __restrict__ t2d, const int32_t* __restrict__ tok_d,
-                                                     const double* __restrict__ lse_q, const float* __restrict__ u_fin,
+                                                     const double* __restrict__ lse_q,
                                                      const double* __restrict__ ws_lse_p,
                                                      const float* __restrict__ tab_ref, const float* __restrict__ tab_s,
-                                                     const float* __restrict__ tab_p, int32_t* __restrict__ n_accepted,
-                                                     int32_t* __restrict__ out_tok, double* __restrict__ lse_p,
-                                                     int32_t* __restrict__ seq_status) {
-    constexpr int EPV = Traits<DT>::EPV;
-    __shared__ PickShared sh;
+                                                     const float* __restrict__ tab_p, FinalOut o) {
+    __shared__ PickShared<kWG> sh;
     const int b = blockIdx.x;
-    const FinalRow f = final_row<DT>(b, K, Vd, n_accepted, seq_status, tok_d, d2t, ws_lse_p, lse_q, c_t, c_d);
+    const FinalRow f = final_row<DT>(b, K, Vd, o.n_accepted, o.seq_status, tok_d, d2t, ws_lse_p, lse_q, c_t, c_d);
     if (f.skip) return;
-    const char* rowp = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + f.n) * Vt * Traits<DT>::ESZ;
-    const uint4* rowv = reinterpret_cast<const uint4*>(rowp);
-    const char* ldp = static_cast<const char*>(logits_d) + ((int64_t)b * K + min(f.n, K - 1)) * Vd * Traits<DT>::ESZ;
-    const float* tr = tab_ref + (int64_t)b * nC;
-    const float* ts = tab_s + (int64_t)b * nC;
-    const float* tp = tab_p + (int64_t)b * nC;
-    const double u = (double)u_fin[b];
-    int tok = -1;
-    int add_flags = 0;
-    bool nonfinite = false;
-    if (f.bonus) {
-        float m = -INFINITY;
-        for (int c = threadIdx.x; c < nC; c += kWG) m = fmaxf(m, tr[c]);
-        const float M = block_max(m, sh);
-        double theta_local, total;
-        const int c = find_chunk(nC, u, [&](int cc) { return (double)ts[cc] * exp2_diff(tr[cc], M); }, sh,
-                                 &theta_local, &total);
-        if (c < 0) {
-            nonfinite = true;  // NaN/+inf, or a bonus row of only -inf: no distribution to sample
-        } else {
-            double w[EPV];
-            const int64_t vi = (int64_t)c * (kWave * kLoads) + threadIdx.x;
-            softmax_vec_weights<DT, false>(rowv, vi, Vt, cs_t, -M, nullptr, w);
-            tok = find_in_chunk<EPV>(w, vi * EPV, theta_local, sh);
-            if (threadIdx.x == 0 && lse_p) lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
-        }
-    } else {
-        double theta_local, total;
-        int c = find_chunk(nC, u, [&](int cc) { return (double)ts[cc]; }, sh, &theta_local, &total);
-        bool degenerate = false;
-        if (c < 0) {
-            if (total != total) {
-                nonfinite = true;
-            } else {  // residual identically zero: fall back to p of the same row
-                degenerate = true;
-                add_flags |= TLI_FLAG_DEGENERATE;
-                c = find_chunk(nC, u, [&](int cc) { return (double)tp[cc]; }, sh, &theta_local, &total);
-                if (c < 0) nonfinite = true;
-            }
-        }
-        if (!nonfinite) {
-            const int64_t vi = (int64_t)c * (kWave * kLoads) + threadIdx.x;
-            float p[EPV], w[EPV];
-            double wd[EPV];
-            if (vi * EPV < Vt) {
-                residual_vec<DT>(rowv[vi], vi * EPV, Vt, f.rp, t2d, ldp, p, w);
-#pragma unroll
-                for (int i = 0; i < EPV; ++i) wd[i] = degenerate ? (double)p[i] : (double)w[i];
-            } else {
-#pragma unroll
-                for (int i = 0; i < EPV; ++i) wd[i] = 0.0;
-            }
-            tok = find_in_chunk<EPV>(wd, vi * EPV, theta_local, sh);
-        }
-    }
-    if (threadIdx.x == 0) {
-        if (nonfinite) {
-            n_accepted[b] = 0;
-            for (int k = 0; k <= K; ++k) out_tok[(int64_t)b * (K + 1) + k] = -1;
-            seq_status[b] |= TLI_FLAG_NONFINITE;
-        } else {
-            out_tok[(int64_t)b * (K + 1) + f.n] = tok;
-            if (add_flags) seq_status[b] |= add_flags;
-        }
-    }
+    final_pick_row<DT, kWG>(f, b, logits_t, logits_d, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
+                            tab_s + (int64_t)b * nC, tab_p + (int64_t)b * nC, o, sh);
 }
 
 // ---- plain copy, used only to calibrate hardware byte counters against a known size -----------
@@ -1003,6 +1058,15 @@ void launch_draft(const tli_map* map, const void* logits_d, int64_t row_stride, 
                   float cs, double ratio, const float* u_draft, int32_t* tok_d, int32_t* tok_t, double* q_tok,
                   double* lse_q, int32_t* row_status, float* tab_ref, float* tab_s, hipStream_t st) {
     const int Vd = map->Vd;
+    DraftOut o;
+    o.u_draft = u_draft; o.tok_d = tok_d; o.tok_t = tok_t; o.q_tok = q_tok; o.lse_q = lse_q; o.row_status = row_status;
+    const double inv_temp = 1.0 / (double)temp_d;
+    if (pl.nsplit == 1 && pl.nC <= kLdsChunks) {  // enough rows to fill the chip with one workgroup per row
+        KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
+        hipLaunchKernelGGL(k_draft_fused<DT>, dim3(R), dim3(kWG), 0, st, logits_d, row_stride, Vd, pl.nC, cs, ratio,
+                           inv_temp, map->bits, map->d2t, o);
+        return;
+    }
     {
         KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
         hipLaunchKernelGGL(k_draft_scan<DT>, dim3((unsigned)R * pl.nsplit), dim3(kWG), 0, st, logits_d, row_stride, Vd,
@@ -1011,13 +1075,15 @@ void launch_draft(const tli_map* map, const void* logits_d, int64_t row_stride, 
     {
         KernelTimer t(TLI_KERNEL_DRAFT_PICK, st);
         hipLaunchKernelGGL(k_draft_pick<DT>, dim3(R), dim3(kWG), 0, st, logits_d, row_stride, Vd, pl.nC, cs, ratio,
-                           1.0 / (double)temp_d, map->bits, map->d2t, tab_ref, tab_s, u_draft, tok_d, tok_t, q_tok,
-                           lse_q, row_status);
+                           inv_temp, map->bits, map->d2t, tab_ref, tab_s, o);
     }
 }
 
 template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     const int Vt = a.map->Vt, Vd = a.map->Vd, B = a.B, K = a.K, rows = B * K;
+    FinalOut fo;
+    fo.u_fin = a.u_fin; fo.n_accepted = a.n_accepted; fo.out_tok = a.out_tok; fo.lse_p = a.lse_p;
+    fo.seq_status = a.seq_status;
     {
         KernelTimer t(TLI_KERNEL_LSE, st);
         hipLaunchKernelGGL(k_lse<DT>, dim3((unsigned)rows * a.pl.nsplit), dim3(kWG), 0, st, a.logits_t, K,
@@ -1032,19 +1098,18 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     {
         KernelTimer t(TLI_KERNEL_FINAL_SCAN, st);
         const int nseg = a.map->nseg[DT];
-        hipLaunchKernelGGL(k_final_scan_residual<DT>, dim3((unsigned)((B + 7) / 8) * 8 * nseg), dim3(kSegWG), 0, st,
-                           a.logits_t, a.logits_d, B, K, Vt, Vd, a.pf.nC, nseg, a.c_t, a.c_d, a.map->d2t, a.map->seg_start[DT],
-                           a.map->seg_x[DT], a.map->seg_off[DT], a.tok_d, a.lse_q, a.n_accepted, a.seq_status,
-                           a.ws_lse_p, a.tab_ref, a.tab_s, a.tab_p);
-        hipLaunchKernelGGL(k_final_scan_bonus<DT>, dim3((unsigned)B * a.pf.nsplit), dim3(kWG), 0, st, a.logits_t, K,
-                           Vt, a.pf.nC, a.pf.cps, a.pf.nsplit, a.cs_t, a.n_accepted, a.seq_status, a.tab_ref,
-                           a.tab_s);
+        hipLaunchKernelGGL(k_final_residual<DT>, dim3((unsigned)((B + 7) / 8) * 8 * nseg), dim3(kSegWG), 0, st,
+                           a.logits_t, a.logits_d, B, K, Vt, Vd, a.pf.nC, nseg, a.c_t, a.c_d, a.map->d2t,
+                           a.map->seg_start[DT], a.map->seg_x[DT], a.map->seg_off[DT], a.tok_d, a.lse_q, a.n_accepted,
+                           a.seq_status, a.ws_lse_p, a.tab_ref, a.tab_s, a.tab_p);
+        hipLaunchKernelGGL(k_final_bonus<DT>, dim3((unsigned)B * a.pf.nsplit), dim3(kWG), 0, st, a.logits_t, K, Vt,
+                           a.pf.nC, a.pf.cps, a.pf.nsplit, a.cs_t, a.n_accepted, a.seq_status, a.tab_ref, a.tab_s);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
         hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWG), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pf.nC,
-                           a.cs_t, a.ratio_t, a.c_t, a.c_d, a.map->d2t, a.map->t2d, a.tok_d, a.lse_q, a.u_fin,
-                           a.ws_lse_p, a.tab_ref, a.tab_s, a.tab_p, a.n_accepted, a.out_tok, a.lse_p, a.seq_status);
+                           a.cs_t, a.ratio_t, a.c_t, a.c_d, a.map->d2t, a.map->t2d, a.tok_d, a.lse_q, a.ws_lse_p,
+                           a.tab_ref, a.tab_s, a.tab_p, fo);
     }
 }
 
