@@ -20,6 +20,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the dominant kernel as read by rocprofv3 (FETCH_SIZE + WRITE_SIZE, each scaled by
+# what the same counter reads for the library's plain copy kernel); from profiles/*_hbm_traffic_pmc.md.
+# Counters cannot be read from inside this process, so the figure is carried here per workload.
+MEASURED_TRAFFIC_BYTES = {"large_vocab": 1048.60e6 + 0.07e6}
 
 
 def parse():
@@ -82,7 +86,6 @@ def main():
 
     # ---- timed region: exactly `steps` steps; HIP events around the dominant kernel on the launch stream
     binding.tli_profile_enable(["lse", "draft_scan"], args.steps)
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -133,7 +136,8 @@ def main():
     lse_avg_s = 1e-3 * lse_ms / max(lse_n, 1)
     achieved = lse_bytes / lse_avg_s / 1e9
     roofline = dict(bound="hbm", kernel="k_lse (target-row log-normalisers)", achieved=round(achieved, 1),
-                    peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
+                    traffic=MEASURED_TRAFFIC_BYTES.get(w.name),
                     bytes_per_launch=lse_bytes, avg_launch_us=round(1e6 * lse_avg_s, 2), launches=lse_n)
     extra = dict(
         draft_ms=round(draft_ms, 4), verify_ms=round(verify_ms, 4),
