@@ -125,17 +125,25 @@ __device__ __forceinline__ void load_chunk_tail(const u4v* rowv, int c, int lane
     }
 }
 
-// Bits of the shared-id mask for the EPV elements of vector vi.
-template <int DT> __device__ __forceinline__ uint32_t mask_bits(const uint8_t* bits, int64_t vi) {
-    if (DT == TLI_BF16) return bits[vi];
-    return (bits[vi >> 1] >> ((vi & 1) * 4)) & 0xFu;
+// Shared-id mask in "lane mask" layout: for chunk c, load j and element i of a vector, the 64-bit word
+// lmask[(c*kLoads + j)*EPV + i] has bit l set iff the id held by lane l there -- id
+// ((c*kLoads + j)*64 + l)*EPV + i -- is shared (ids past the vocabulary read as not shared).  A wave
+// fetches the word with one scalar load and uses it directly as the select mask of a v_cndmask.
+template <int DT> __device__ __forceinline__ uint32_t mask_bits(const uint64_t* lmask, int64_t vi) {
+    constexpr int EPV = Traits<DT>::EPV;
+    const uint64_t* w = lmask + (vi >> 6) * EPV;
+    const int l = (int)(vi & 63);
+    uint32_t mb = 0;
+#pragma unroll
+    for (int i = 0; i < EPV; ++i) mb |= (uint32_t)((w[i] >> l) & 1ull) << i;
+    return mb;
 }
 
 // Reduce one chunk held in registers to (ref, s): sum 2^(x*c) over the chunk = s * 2^ref, with
 // ref = ceil(max over the chunk of fp32(x*c)) (-inf and s = 0 for a chunk without finite entries).
 // A NaN or +inf logit turns s into NaN.  Wave-uniform results.  WHOLE: every element is < V.
 template <int DT, bool MASKED, bool WHOLE>
-__device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane, int V, float cs, const uint8_t* bits,
+__device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane, int V, float cs, const uint64_t* bits,
                                     float& ref_out, float& s_out) {
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int N = EPV * kLoads;
@@ -151,10 +159,12 @@ __device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane
                 if (vi * EPV + i >= V) x[j * EPV + i] = -INFINITY;
         }
         if (MASKED) {
-            const uint32_t mb = (WHOLE || vi * EPV < V) ? mask_bits<DT>(bits, vi) : 0u;
+            const uint64_t* w = bits + ((int64_t)c * kLoads + j) * EPV;  // wave-uniform address: scalar loads
 #pragma unroll
-            for (int i = 0; i < EPV; ++i)
-                if (!((mb >> i) & 1u)) x[j * EPV + i] = -INFINITY;
+            for (int i = 0; i < EPV; ++i) {
+                const bool keep = __builtin_amdgcn_inverse_ballot_w64(w[i]);
+                x[j * EPV + i] = keep ? x[j * EPV + i] : -INFINITY;
+            }
         }
     }
     float m = x[0];
@@ -179,7 +189,7 @@ __device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane
 // next chunk are in flight while the current one is reduced.  A row has at most one partial chunk
 // (its last); the wave that owns it handles it after its whole chunks.
 template <int DT, bool MASKED, class Sink>
-__device__ __forceinline__ void scan_chunks(const u4v* rowv, int V, int c_begin, int c_end, float cs, const uint8_t* bits,
+__device__ __forceinline__ void scan_chunks(const u4v* rowv, int V, int c_begin, int c_end, float cs, const uint64_t* bits,
                                    Sink&& sink) {
     constexpr int EPV = Traits<DT>::EPV;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -289,7 +299,7 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
 // Used for drafter rows (masked: the intersection algorithm's q') and for the bonus target row.
 // Workgroup `split` of a row owns chunks [split*cps, (split+1)*cps).
 template <int DT, bool MASKED>
-__device__ __forceinline__ void table_scan(const u4v* rowv, int split, int V, int nC, int cps, float cs, const uint8_t* bits,
+__device__ __forceinline__ void table_scan(const u4v* rowv, int split, int V, int nC, int cps, float cs, const uint64_t* bits,
                                   float* tab_ref, float* tab_s) {
     const int lane = threadIdx.x & 63;
     scan_chunks<DT, MASKED>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, bits, [&](int c, float r, float sc) {
@@ -300,7 +310,7 @@ __device__ __forceinline__ void table_scan(const u4v* rowv, int split, int V, in
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_draft_scan(const void* __restrict__ logits, int64_t row_stride, int V,
                                                      int nC, int cps, int nsplit, float cs,
-                                                     const uint8_t* __restrict__ bits, float* __restrict__ tab_ref,
+                                                     const uint64_t* __restrict__ bits, float* __restrict__ tab_ref,
                                                      float* __restrict__ tab_s) {
     const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
@@ -424,12 +434,12 @@ __device__ __forceinline__ int find_in_chunk(const double (&w)[N], int64_t e0, d
 // chunk [vlo, vhi) get zeros.
 template <int DT, bool MASKED>
 __device__ __forceinline__ void softmax_vec_weights(const uint4* rowv, int64_t vi, int64_t vhi, int V, float cs, float nref,
-                                           const uint8_t* bits, double* w) {
+                                           const uint64_t* bits, double* w) {
     constexpr int EPV = Traits<DT>::EPV;
     float x[EPV];
     if (vi < vhi && vi * EPV < V) {
         unpack<DT>(rowv[vi], x);
-        const uint32_t mb = MASKED ? mask_bits<DT>(bits, vi) : 0xffu;
+        const uint32_t mb = MASKED ? mask_bits<DT>(bits, vi) : 0xffu;  // same lane-mask words as the scan
 #pragma unroll
         for (int i = 0; i < EPV; ++i) {
             const bool live = (vi * EPV + i < V) && ((mb >> i) & 1u);
@@ -444,7 +454,7 @@ __device__ __forceinline__ void softmax_vec_weights(const uint4* rowv, int64_t v
 // Inverse-CDF sample of a (masked) softmax row from its chunk table.  Returns the id, or -1 if the
 // row has no usable mass (then *total_out is NaN for a NaN/+inf logit, else 0).  *M_out = table max.
 template <int DT, bool MASKED, int NT>
-__device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int nC, float cs, const uint8_t* bits,
+__device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int nC, float cs, const uint64_t* bits,
                                          const float* tr, const float* ts, double u, PickShared<NT>& sh,
                                          float* M_out, double* total_out) {
     constexpr int EPV = Traits<DT>::EPV;
@@ -478,7 +488,7 @@ struct DraftOut {
 
 template <int DT, int NT>
 __device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V, int nC, float cs, double c_ratio,
-                                      double inv_temp, const uint8_t* bits, const int32_t* d2t, const float* tr,
+                                      double inv_temp, const uint64_t* bits, const int32_t* d2t, const float* tr,
                                       const float* ts, const DraftOut& o, PickShared<NT>& sh) {
     float M;
     double total;
@@ -505,7 +515,7 @@ __device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V,
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_draft_pick(const void* __restrict__ logits, int64_t row_stride, int V,
                                                      int nC, float cs, double c_ratio, double inv_temp,
-                                                     const uint8_t* __restrict__ bits,
+                                                     const uint64_t* __restrict__ bits,
                                                      const int32_t* __restrict__ d2t,
                                                      const float* __restrict__ tab_ref,
                                                      const float* __restrict__ tab_s, DraftOut o) {
@@ -522,7 +532,7 @@ constexpr int kLdsChunks = 1024;
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ logits, int64_t row_stride, int V,
                                                       int nC, float cs, double c_ratio, double inv_temp,
-                                                      const uint8_t* __restrict__ bits,
+                                                      const uint64_t* __restrict__ bits,
                                                       const int32_t* __restrict__ d2t, DraftOut o) {
     __shared__ PickShared<kWG> sh;
     __shared__ float tr[kLdsChunks], ts[kLdsChunks];
@@ -1041,7 +1051,7 @@ struct tli_map {
     int device;
     int32_t* d2t;    // dev [Vd padded to 8]
     int32_t* t2d;    // dev [Vt padded to 8]
-    uint8_t* bits;   // dev: bit x set iff drafter id x is shared
+    uint64_t* lmask[2];  // dev, per dtype: shared-id mask of the drafter vocabulary in lane-mask layout
     // Per dtype (index = tli_dtype): shared pairs bucketed by target segment (seg_elems<dtype>() target ids
     // each), drafter ids ascending inside a bucket.  seg_start [nseg+1], seg_x [S] drafter id, seg_off [S]
     // offset of the partner target id inside its segment.
@@ -1064,18 +1074,18 @@ void launch_draft(const tli_map* map, const void* logits_d, int64_t row_stride, 
     if (pl.nsplit == 1 && pl.nC <= kLdsChunks) {  // enough rows to fill the chip with one workgroup per row
         KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
         hipLaunchKernelGGL(k_draft_fused<DT>, dim3(R), dim3(kWG), 0, st, logits_d, row_stride, Vd, pl.nC, cs, ratio,
-                           inv_temp, map->bits, map->d2t, o);
+                           inv_temp, map->lmask[DT], map->d2t, o);
         return;
     }
     {
         KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
         hipLaunchKernelGGL(k_draft_scan<DT>, dim3((unsigned)R * pl.nsplit), dim3(kWG), 0, st, logits_d, row_stride, Vd,
-                           pl.nC, pl.cps, pl.nsplit, cs, map->bits, tab_ref, tab_s);
+                           pl.nC, pl.cps, pl.nsplit, cs, map->lmask[DT], tab_ref, tab_s);
     }
     {
         KernelTimer t(TLI_KERNEL_DRAFT_PICK, st);
         hipLaunchKernelGGL(k_draft_pick<DT>, dim3(R), dim3(kWG), 0, st, logits_d, row_stride, Vd, pl.nC, cs, ratio,
-                           inv_temp, map->bits, map->d2t, tab_ref, tab_s, o);
+                           inv_temp, map->lmask[DT], map->d2t, tab_ref, tab_s, o);
     }
 }
 
@@ -1185,7 +1195,6 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
     if (!d2t_host || !out_map || Vd < 1 || Vt < 1) return TLI_ERR_INVALID_ARG;
     const size_t Vd_pad = ((size_t)Vd + 7) & ~(size_t)7, Vt_pad = ((size_t)Vt + 7) & ~(size_t)7;
     std::vector<int32_t> d2t(Vd_pad, -1), t2d(Vt_pad, -1);
-    std::vector<uint8_t> bits(Vd_pad / 8 + 16, 0);
     int32_t S = 0;
     for (int32_t x = 0; x < Vd; ++x) {
         const int32_t t = d2t_host[x];
@@ -1194,7 +1203,6 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
         if (t2d[t] != -1) return TLI_ERR_NOT_INJECTIVE;
         t2d[t] = x;
         d2t[x] = t;
-        bits[x >> 3] |= (uint8_t)(1u << (x & 7));
         ++S;
     }
     if (S == 0) return TLI_ERR_EMPTY_INTERSECTION;
@@ -1220,19 +1228,34 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
             ++fill[g];
         }
     }
+    // shared-id mask of the drafter vocabulary in lane-mask layout (see mask_bits), padded to whole chunks
+    std::vector<uint64_t> lmask[2];
+    for (int dt = 0; dt < 2; ++dt) {
+        const int epv = dt == TLI_BF16 ? 8 : 4;
+        const int chunk = kWave * kLoads * epv;
+        const size_t nchunks = ((size_t)Vd + chunk - 1) / chunk;
+        lmask[dt].assign(nchunks * kLoads * epv, 0);
+        for (int32_t x = 0; x < Vd; ++x) {
+            if (d2t[x] < 0) continue;
+            const int64_t vi = x / epv;
+            lmask[dt][(vi >> 6) * epv + (x % epv)] |= 1ull << (vi & 63);
+        }
+    }
     tli_map* m = new (std::nothrow) tli_map();
     if (!m) return TLI_ERR_ALLOC;
-    m->Vd = Vd; m->Vt = Vt; m->S = S; m->d2t = nullptr; m->t2d = nullptr; m->bits = nullptr;
+    m->Vd = Vd; m->Vt = Vt; m->S = S; m->d2t = nullptr; m->t2d = nullptr; m->lmask[0] = m->lmask[1] = nullptr;
     for (int dt = 0; dt < 2; ++dt) {
         m->nseg[dt] = nseg[dt]; m->seg_start[dt] = nullptr; m->seg_x[dt] = nullptr; m->seg_off[dt] = nullptr;
     }
     if (hipGetDevice(&m->device) != hipSuccess) { delete m; return TLI_ERR_HIP; }
     bool ok = hipMalloc(&m->d2t, d2t.size() * 4) == hipSuccess && hipMalloc(&m->t2d, t2d.size() * 4) == hipSuccess &&
-              hipMalloc(&m->bits, bits.size()) == hipSuccess;
+              hipMalloc(&m->lmask[0], lmask[0].size() * 8) == hipSuccess &&
+              hipMalloc(&m->lmask[1], lmask[1].size() * 8) == hipSuccess;
     if (!ok) { tli_free_map(m); return TLI_ERR_ALLOC; }
     ok = hipMemcpy(m->d2t, d2t.data(), d2t.size() * 4, hipMemcpyHostToDevice) == hipSuccess &&
          hipMemcpy(m->t2d, t2d.data(), t2d.size() * 4, hipMemcpyHostToDevice) == hipSuccess &&
-         hipMemcpy(m->bits, bits.data(), bits.size(), hipMemcpyHostToDevice) == hipSuccess;
+         hipMemcpy(m->lmask[0], lmask[0].data(), lmask[0].size() * 8, hipMemcpyHostToDevice) == hipSuccess &&
+         hipMemcpy(m->lmask[1], lmask[1].data(), lmask[1].size() * 8, hipMemcpyHostToDevice) == hipSuccess;
     if (!ok) { tli_free_map(m); return TLI_ERR_HIP; }
     for (int dt = 0; dt < 2; ++dt) {
         ok = hipMalloc(&m->seg_start[dt], seg_start[dt].size() * 4) == hipSuccess &&
@@ -1254,7 +1277,8 @@ void tli_free_map(tli_map* m) {
     if (!m) return;
     if (m->d2t) (void)hipFree(m->d2t);
     if (m->t2d) (void)hipFree(m->t2d);
-    if (m->bits) (void)hipFree(m->bits);
+    if (m->lmask[0]) (void)hipFree(m->lmask[0]);
+    if (m->lmask[1]) (void)hipFree(m->lmask[1]);
     for (int dt = 0; dt < 2; ++dt) {
         if (m->seg_start[dt]) (void)hipFree(m->seg_start[dt]);
         if (m->seg_x[dt]) (void)hipFree(m->seg_x[dt]);
