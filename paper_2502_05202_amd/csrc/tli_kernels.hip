@@ -318,126 +318,103 @@ __global__ __launch_bounds__(kWG) void k_draft_scan(const void* __restrict__ log
     table_scan<DT, true>(rowv, split, V, nC, cps, cs, bits, tab_ref + (int64_t)row * nC, tab_s + (int64_t)row * nC);
 }
 
-// ---- block-level helpers for the samplers (NT threads) ---------------------------------------
-template <int NT> struct PickShared {
-    double wsum[NT / kWave];
-    float wmax[NT / kWave];
-    int cand;
-    int last_pos;
-    double theta_local;
-};
+// ---- wave-level sampler: one wave draws the token of a row from the row's chunk table ----------
+// (One wave is enough for a few hundred chunks and one 2048-id chunk; it needs no barriers, and in
+// the fused draft kernel the other three waves of the workgroup retire at once.)
 
-template <int NT> __device__ __forceinline__ float block_max(float v, PickShared<NT>& sh) {
-    v = wave_max(v);
-    const int wave = threadIdx.x >> 6;
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sh.wmax[wave] = v;
-    __syncthreads();
-    float m = sh.wmax[0];
-    for (int w = 1; w < NT / kWave; ++w) m = fmaxf(m, sh.wmax[w]);
-    return m;
-}
-
-// exclusive prefix of v over the block's threads in fp64; *total = block sum
-template <int NT> __device__ __forceinline__ double block_excl_scan(double v, PickShared<NT>& sh, double* total) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+// exclusive prefix of v over the 64 lanes in fp64; *total = the wave's sum (uniform)
+__device__ __forceinline__ double wave_excl_scan(double v, double* total) {
+    const int lane = threadIdx.x & 63;
     double inc = v;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
         const double t = __shfl_up(inc, d, kWave);
         if (lane >= d) inc += t;
     }
-    __syncthreads();
-    if (lane == kWave - 1) sh.wsum[wave] = inc;
-    __syncthreads();
-    double base = 0.0, tot = 0.0;
-    for (int w = 0; w < NT / kWave; ++w) {
-        if (w < wave) base += sh.wsum[w];
-        tot += sh.wsum[w];
-    }
-    *total = tot;
-    return base + (inc - v);
+    *total = __shfl(inc, kWave - 1, kWave);
+    return inc - v;
 }
 
-// Chunk search.  T_c (fp64 chunk masses) for this thread's contiguous chunks [c0, c1) are produced
-// by `mass(c)`.  Returns the first chunk whose inclusive prefix exceeds theta = u * total and
-// theta - (prefix before that chunk); -1 if total is not positive.  *total_out = total.
-template <int NT, class MassFn>
-__device__ __forceinline__ int find_chunk(int nC, double u, MassFn mass, PickShared<NT>& sh, double* theta_local,
-                                 double* total_out) {
-    const int per = (nC + NT - 1) / NT;
-    const int c0 = min(nC, (int)threadIdx.x * per), c1 = min(nC, c0 + per);
-    const double first = (c0 < c1) ? mass(c0) : 0.0;  // the common case is one chunk per thread: keep it
-    double mine = first;
-    for (int c = c0 + 1; c < c1; ++c) mine += mass(c);
+__device__ __forceinline__ int wave_max_int(int v) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) v = max(v, __shfl_xor(v, d, kWave));
+    return v;
+}
+
+// Chunk search.  Lane l owns the contiguous chunks [l*per, (l+1)*per); `mass(c)` is chunk c's fp64 mass.
+// Returns the first chunk whose inclusive prefix exceeds theta = u * total, with theta - (prefix before
+// it) in *theta_local; if rounding leaves no crossing, the last chunk with mass and +inf; -1 if the
+// total is not positive (zero, negative or NaN).  All results are wave-uniform.
+template <class MassFn>
+__device__ __forceinline__ int find_chunk(int nC, double u, MassFn mass, double* theta_local, double* total_out) {
+    const int lane = threadIdx.x & 63;
+    const int per = (nC + kWave - 1) / kWave;
+    const int c0 = min(nC, lane * per), c1 = min(nC, c0 + per);
+    double mine = 0.0;
+    for (int c = c0; c < c1; ++c) mine += mass(c);
     double total;
-    const double excl = block_excl_scan<NT>(mine, sh, &total);
+    const double excl = wave_excl_scan(mine, &total);
     *total_out = total;
-    if (!(total > 0.0)) return -1;  // zero, negative or NaN
+    if (!(total > 0.0)) return -1;
     const double theta = u * total;
-    if (threadIdx.x == 0) { sh.cand = 0x7fffffff; sh.last_pos = -1; }
-    __syncthreads();
-    double run = excl;
-    int found = -1;
-    double before = 0.0;
-    int last_pos = -1;
+    double run = excl, before = 0.0;
+    int found = -1, last_pos = -1;
     for (int c = c0; c < c1; ++c) {
-        const double t = (c == c0) ? first : mass(c);
+        const double t = mass(c);
         if (t > 0.0) last_pos = c;
         if (found < 0 && run + t > theta) { found = c; before = run; }
         run += t;
     }
-    if (found >= 0) atomicMin(&sh.cand, found);
-    if (last_pos >= 0) atomicMax(&sh.last_pos, last_pos);
-    __syncthreads();
-    int pick = sh.cand;
-    const bool none = (pick == 0x7fffffff);
-    if (none) pick = sh.last_pos;  // rounding left no crossing: last chunk with mass, take its last id
-    __syncthreads();
-    if (found == pick && found >= 0) sh.theta_local = theta - before;
-    if (none && threadIdx.x == 0) sh.theta_local = INFINITY;
-    __syncthreads();
-    *theta_local = sh.theta_local;
-    return pick;
+    const unsigned long long hit = __ballot(found >= 0);
+    if (hit == 0ull) {
+        *theta_local = INFINITY;
+        return wave_max_int(last_pos);
+    }
+    const int src = (int)__builtin_ctzll(hit);  // lanes own ascending chunk ranges: lowest lane = first chunk
+    *theta_local = theta - __shfl(before, src, kWave);
+    return __shfl(found, src, kWave);
 }
 
-// In-chunk search: thread t holds the weights of elements [e0, e0+N) in order (threads beyond the
-// chunk hold zeros).  Returns the first element whose inclusive prefix exceeds theta_local; if none,
-// the last element with weight > 0.
-template <int N, int NT>
-__device__ __forceinline__ int find_in_chunk(const double (&w)[N], int64_t e0, double theta_local, PickShared<NT>& sh) {
+// In-chunk search state: vectors are visited in id order (load j = 0..3, then lane, then element).
+struct ChunkWalk {
+    double base = 0.0;   // mass of the vectors already visited
+    int found = -1;      // first id whose inclusive prefix exceeds theta_local (uniform once set)
+    int last_pos = -1;   // per lane: last id with positive weight seen so far
+};
+
+// feed the weights of this lane's vector (ids e0 .. e0+N-1) of load j; returns true when found
+template <int N>
+__device__ __forceinline__ bool walk_vector(ChunkWalk& st, const double (&w)[N], int64_t e0, double theta_local) {
     double mine = 0.0;
 #pragma unroll
     for (int i = 0; i < N; ++i) mine += w[i];
-    double total;
-    const double excl = block_excl_scan<NT>(mine, sh, &total);
-    if (threadIdx.x == 0) { sh.cand = 0x7fffffff; sh.last_pos = -1; }
-    __syncthreads();
-    double run = excl;
-    int found = -1, last_pos = -1;
+    double tot;
+    double run = st.base + wave_excl_scan(mine, &tot);
+    int f = -1;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         run += w[i];
-        if (w[i] > 0.0) last_pos = (int)(e0 + i);
-        if (found < 0 && run > theta_local) found = (int)(e0 + i);
+        if (w[i] > 0.0) st.last_pos = (int)(e0 + i);
+        if (f < 0 && run > theta_local) f = (int)(e0 + i);
     }
-    if (found >= 0) atomicMin(&sh.cand, found);
-    if (last_pos >= 0) atomicMax(&sh.last_pos, last_pos);
-    __syncthreads();
-    const int pick = (sh.cand == 0x7fffffff) ? sh.last_pos : sh.cand;
-    __syncthreads();
-    return pick;
+    st.base += tot;
+    const unsigned long long hit = __ballot(f >= 0);
+    if (hit == 0ull) return false;
+    st.found = __shfl(f, (int)__builtin_ctzll(hit), kWave);
+    return true;
+}
+__device__ __forceinline__ int walk_result(const ChunkWalk& st) {
+    return st.found >= 0 ? st.found : wave_max_int(st.last_pos);  // no crossing: last id with weight > 0
 }
 
 // weights of one 16-byte vector of a softmax row relative to reference `nref` (= -ref), as in
-// reduce_chunk: 2^(x*c - ref); elements >= V or masked out get 0.  Threads with vi outside the
-// chunk [vlo, vhi) get zeros.
+// reduce_chunk: 2^(x*c - ref); elements >= V or masked out get 0.
 template <int DT, bool MASKED>
-__device__ __forceinline__ void softmax_vec_weights(const uint4* rowv, int64_t vi, int64_t vhi, int V, float cs, float nref,
-                                           const uint64_t* bits, double* w) {
+__device__ __forceinline__ void softmax_vec_weights(const uint4* rowv, int64_t vi, int V, float cs, float nref,
+                                                    const uint64_t* bits, double* w) {
     constexpr int EPV = Traits<DT>::EPV;
     float x[EPV];
-    if (vi < vhi && vi * EPV < V) {
+    if (vi * EPV < V) {
         unpack<DT>(rowv[vi], x);
         const uint32_t mb = MASKED ? mask_bits<DT>(bits, vi) : 0xffu;  // same lane-mask words as the scan
 #pragma unroll
@@ -451,30 +428,34 @@ __device__ __forceinline__ void softmax_vec_weights(const uint4* rowv, int64_t v
     }
 }
 
-// Inverse-CDF sample of a (masked) softmax row from its chunk table.  Returns the id, or -1 if the
-// row has no usable mass (then *total_out is NaN for a NaN/+inf logit, else 0).  *M_out = table max.
-template <int DT, bool MASKED, int NT>
+// Inverse-CDF sample of a (masked) softmax row from its chunk table, by one wave.  Returns the id, or
+// -1 if the row has no usable mass (then *total_out is NaN for a NaN/+inf logit, else 0).
+template <int DT, bool MASKED>
 __device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int nC, float cs, const uint64_t* bits,
-                                         const float* tr, const float* ts, double u, PickShared<NT>& sh,
-                                         float* M_out, double* total_out) {
+                                                  const float* tr, const float* ts, double u, float* M_out,
+                                                  double* total_out) {
     constexpr int EPV = Traits<DT>::EPV;
+    const int lane = threadIdx.x & 63;
     float m = -INFINITY;
-    for (int c = threadIdx.x; c < nC; c += NT) m = fmaxf(m, tr[c]);
-    const float M = block_max<NT>(m, sh);
+    for (int c = lane; c < nC; c += kWave) m = fmaxf(m, tr[c]);
+    const float M = wave_max(m);
     *M_out = M;
     double theta_local;
-    const int c = find_chunk<NT>(
-        nC, u, [&](int cc) { return (double)ts[cc] * exp2_diff(tr[cc], M); }, sh,
-        &theta_local, total_out);
+    const int c = find_chunk(nC, u, [&](int cc) { return (double)ts[cc] * exp2_diff(tr[cc], M); }, &theta_local,
+                             total_out);
     if (c < 0) {
         if (M == INFINITY) *total_out = NAN;
         return -1;
     }
-    double w[EPV];
-    const int64_t v0 = (int64_t)c * (kWave * kLoads);
-    const int64_t vi = v0 + threadIdx.x;
-    softmax_vec_weights<DT, MASKED>(static_cast<const uint4*>(rowp), vi, v0 + kWave * kLoads, V, cs, -M, bits, w);
-    return find_in_chunk<EPV, NT>(w, vi * EPV, theta_local, sh);
+    ChunkWalk st;
+#pragma unroll 1
+    for (int j = 0; j < kLoads; ++j) {
+        const int64_t vi = ((int64_t)c * kLoads + j) * kWave + lane;
+        double w[EPV];
+        softmax_vec_weights<DT, MASKED>(static_cast<const uint4*>(rowp), vi, V, cs, -M, bits, w);
+        if (walk_vector<EPV>(st, w, vi * EPV, theta_local)) break;
+    }
+    return walk_result(st);
 }
 
 // ---- draft token of one drafter row from its chunk table ----------------------------------------
@@ -486,15 +467,14 @@ struct DraftOut {
     int32_t* row_status;
 };
 
-template <int DT, int NT>
+template <int DT>
 __device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V, int nC, float cs, double c_ratio,
                                       double inv_temp, const uint64_t* bits, const int32_t* d2t, const float* tr,
-                                      const float* ts, const DraftOut& o, PickShared<NT>& sh) {
+                                      const float* ts, const DraftOut& o) {
     float M;
     double total;
-    const int d = sample_softmax_row<DT, true, NT>(rowp, V, nC, cs, bits, tr, ts, (double)o.u_draft[row], sh,
-                                                             &M, &total);
-    if (threadIdx.x != 0) return;
+    const int d = sample_softmax_row<DT, true>(rowp, V, nC, cs, bits, tr, ts, (double)o.u_draft[row], &M, &total);
+    if ((threadIdx.x & 63) != 0) return;
     if (d < 0) {  // no usable mass: NaN/+inf among the shared logits, or all of them -inf
         const bool nonfinite = (total != total);
         o.tok_d[row] = -1; o.tok_t[row] = -1;
@@ -511,36 +491,36 @@ __device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V,
     o.row_status[row] = 0;
 }
 
-// kernel: sampler of the split path (rows cut over several workgroups by k_draft_scan).  grid (R).
+// kernel: sampler of the split path (rows cut over several workgroups by k_draft_scan).  grid (R), one wave.
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_draft_pick(const void* __restrict__ logits, int64_t row_stride, int V,
+__global__ __launch_bounds__(kWave) void k_draft_pick(const void* __restrict__ logits, int64_t row_stride, int V,
                                                      int nC, float cs, double c_ratio, double inv_temp,
                                                      const uint64_t* __restrict__ bits,
                                                      const int32_t* __restrict__ d2t,
                                                      const float* __restrict__ tab_ref,
                                                      const float* __restrict__ tab_s, DraftOut o) {
-    __shared__ PickShared<kWG> sh;
     const int row = blockIdx.x;
     const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
-    draft_pick_row<DT, kWG>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tab_ref + (int64_t)row * nC,
-                                   tab_s + (int64_t)row * nC, o, sh);
+    draft_pick_row<DT>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tab_ref + (int64_t)row * nC,
+                       tab_s + (int64_t)row * nC, o);
 }
 
 // kernel: one workgroup per drafter row scans it into a chunk table in LDS and samples from it at
-// once, while the other workgroups on the CU keep streaming their rows.  grid (R); nC <= kLdsChunks.
+// once (by its first wave), while the other workgroups on the CU keep streaming their rows.
+// grid (R); nC <= kLdsChunks.
 constexpr int kLdsChunks = 1024;
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ logits, int64_t row_stride, int V,
                                                       int nC, float cs, double c_ratio, double inv_temp,
                                                       const uint64_t* __restrict__ bits,
                                                       const int32_t* __restrict__ d2t, DraftOut o) {
-    __shared__ PickShared<kWG> sh;
     __shared__ float tr[kLdsChunks], ts[kLdsChunks];
     const int row = blockIdx.x;
     const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
     table_scan<DT, true>(reinterpret_cast<const u4v*>(rowp), 0, V, nC, nC, cs, bits, tr, ts);
     __syncthreads();
-    draft_pick_row<DT, kWG>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tr, ts, o, sh);
+    if (threadIdx.x >= kWave) return;  // the first wave samples; the others retire and free their slots
+    draft_pick_row<DT>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tr, ts, o);
 }
 
 // ---- kernel: accept tests and first-reject scan ------------------------------------------------
@@ -631,20 +611,30 @@ __device__ __forceinline__ void split_scale(double c, float& hi, float& lo) {
     lo = (float)(c - (double)hi);
 }
 
+// Weights of vector vi of the residual row, for the sampler's re-read of one chunk.  All loads are
+// unconditional (indices clamped into range, results masked afterwards) so that the loads of the
+// chunk's four vectors, then their t2d entries, then the drafter logits they point at, each go out
+// as one batch instead of a chain of dependent round trips.
 template <int DT>
-__device__ __forceinline__ void residual_vec(const uint4& v, int64_t e0, int V, const ResidualParams& rp,
-                                    const int32_t* __restrict__ t2d, const void* __restrict__ ld_row, float* p,
-                                    float* w) {
+__device__ __forceinline__ void residual_vec(const void* rowp, int64_t vi, int V, const ResidualParams& rp,
+                                             const int32_t* __restrict__ t2d, const void* __restrict__ ld_row,
+                                             float* p, float* w) {
     constexpr int EPV = Traits<DT>::EPV;
+    const int64_t nvec = (V + EPV - 1) / EPV;
+    const int64_t vc = vi < nvec ? vi : nvec - 1;
+    const int64_t e0 = vi * EPV;
     float x[EPV];
-    unpack<DT>(v, x);
+    unpack<DT>(static_cast<const uint4*>(rowp)[vc], x);
+    float y[EPV];
     int32_t d[EPV];
-    if (rp.use_q && e0 < V) {
+    if (rp.use_q) {
 #pragma unroll
         for (int i = 0; i < EPV; i += 4) {
-            const int4 t = *reinterpret_cast<const int4*>(t2d + e0 + i);  // t2d is padded to a multiple of 8
+            const int4 t = *reinterpret_cast<const int4*>(t2d + vc * EPV + i);  // t2d is padded to a multiple of 8
             d[i] = t.x; d[i + 1] = t.y; d[i + 2] = t.z; d[i + 3] = t.w;
         }
+#pragma unroll
+        for (int i = 0; i < EPV; ++i) y[i] = load_elem<DT>(ld_row, d[i] > 0 ? d[i] : 0);
     }
 #pragma unroll
     for (int i = 0; i < EPV; ++i) {
@@ -652,9 +642,9 @@ __device__ __forceinline__ void residual_vec(const uint4& v, int64_t e0, int V, 
         float pi = exp2_split(x[i], rp.ct_hi, rp.ct_lo, rp.lp_hi, rp.lp_lo);
         pi = live ? pi : 0.f;
         float qi = 0.f;
-        if (rp.use_q && live && d[i] >= 0) {
-            const float y = load_elem<DT>(ld_row, d[i]);
-            qi = exp2_split(y, rp.cd_hi, rp.cd_lo, rp.lq_hi, rp.lq_lo);
+        if (rp.use_q) {
+            qi = exp2_split(y[i], rp.cd_hi, rp.cd_lo, rp.lq_hi, rp.lq_lo);
+            qi = (live && d[i] >= 0) ? qi : 0.f;
         }
         p[i] = pi;
         w[i] = fmaxf(0.f, pi - qi);
@@ -703,12 +693,13 @@ struct FinalOut {
     int32_t* seq_status;
 };
 
-template <int DT, int NT>
-__device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const void* logits_t, const void* logits_d, int K,
-                                      int Vt, int Vd, int nC, float cs_t, double ratio_t, const int32_t* t2d,
-                                      const float* tr, const float* ts, const float* tp, const FinalOut& o,
-                                      PickShared<NT>& sh) {
+template <int DT>
+__device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const void* logits_t, const void* logits_d,
+                                               int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
+                                               const int32_t* t2d, const float* tr, const float* ts, const float* tp,
+                                               const FinalOut& o) {
     constexpr int EPV = Traits<DT>::EPV;
+    const int lane = threadIdx.x & 63;
     const char* rowp = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + f.n) * Vt * Traits<DT>::ESZ;
     const double u = (double)o.u_fin[b];
     int tok = -1;
@@ -717,14 +708,14 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
     if (f.bonus) {
         float M;
         double total;
-        tok = sample_softmax_row<DT, false, NT>(rowp, Vt, nC, cs_t, nullptr, tr, ts, u, sh, &M, &total);
+        tok = sample_softmax_row<DT, false>(rowp, Vt, nC, cs_t, nullptr, tr, ts, u, &M, &total);
         // no usable mass: NaN/+inf, or a bonus row of only -inf -- no distribution to sample either way
         if (tok < 0) nonfinite = true;
-        else if (threadIdx.x == 0 && o.lse_p) o.lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
+        else if (lane == 0 && o.lse_p) o.lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
     } else {
         const char* ldp = static_cast<const char*>(logits_d) + ((int64_t)b * K + f.n) * Vd * Traits<DT>::ESZ;
         double theta_local, total;
-        int c = find_chunk<NT>(nC, u, [&](int cc) { return (double)ts[cc]; }, sh, &theta_local, &total);
+        int c = find_chunk(nC, u, [&](int cc) { return (double)ts[cc]; }, &theta_local, &total);
         bool degenerate = false;
         if (c < 0) {
             if (total != total) {
@@ -732,26 +723,28 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
             } else {  // residual identically zero: fall back to p of the same row
                 degenerate = true;
                 add_flags |= TLI_FLAG_DEGENERATE;
-                c = find_chunk<NT>(nC, u, [&](int cc) { return (double)tp[cc]; }, sh, &theta_local, &total);
+                c = find_chunk(nC, u, [&](int cc) { return (double)tp[cc]; }, &theta_local, &total);
                 if (c < 0) nonfinite = true;
             }
         }
         if (!nonfinite) {
-            const int64_t v0 = (int64_t)c * (kWave * kLoads);
-            const int64_t vi = v0 + threadIdx.x;
-            double wd[EPV];
+            float p[kLoads][EPV], w[kLoads][EPV];
 #pragma unroll
-            for (int i = 0; i < EPV; ++i) wd[i] = 0.0;
-            if (threadIdx.x < kWave * kLoads && vi * EPV < Vt) {
-                float p[EPV], w[EPV];
-                residual_vec<DT>(reinterpret_cast<const uint4*>(rowp)[vi], vi * EPV, Vt, f.rp, t2d, ldp, p, w);
+            for (int j = 0; j < kLoads; ++j)
+                residual_vec<DT>(rowp, ((int64_t)c * kLoads + j) * kWave + lane, Vt, f.rp, t2d, ldp, p[j], w[j]);
+            ChunkWalk st;
 #pragma unroll
-                for (int i = 0; i < EPV; ++i) wd[i] = degenerate ? (double)p[i] : (double)w[i];
+            for (int j = 0; j < kLoads; ++j) {
+                const int64_t vi = ((int64_t)c * kLoads + j) * kWave + lane;
+                double wd[EPV];
+#pragma unroll
+                for (int i = 0; i < EPV; ++i) wd[i] = degenerate ? (double)p[j][i] : (double)w[j][i];
+                if (walk_vector<EPV>(st, wd, vi * EPV, theta_local)) break;
             }
-            tok = find_in_chunk<EPV, NT>(wd, vi * EPV, theta_local, sh);
+            tok = walk_result(st);
         }
     }
-    if (threadIdx.x == 0) {
+    if (lane == 0) {
         if (nonfinite) {
             o.n_accepted[b] = 0;
             for (int k = 0; k <= K; ++k) o.out_tok[(int64_t)b * (K + 1) + k] = -1;
@@ -922,9 +915,9 @@ __global__ __launch_bounds__(kSegWG) void k_final_residual(
     }
 }
 
-// kernel: draw the extra token of every sequence from its row's chunk tables.  grid (B), 256 threads.
+// kernel: draw the extra token of every sequence from its row's chunk tables.  grid (B), one wave.
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_final_pick(const void* __restrict__ logits_t, const void* __restrict__ logits_d,
+__global__ __launch_bounds__(kWave) void k_final_pick(const void* __restrict__ logits_t, const void* __restrict__ logits_d,
                                                      int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
                                                      double c_t, double c_d, const int32_t* __restrict__ d2t,
                                                      const int32_t* __restrict__ t2d, const int32_t* __restrict__ tok_d,
@@ -932,12 +925,11 @@ __global__ __launch_bounds__(kWG) void k_final_pick(const void* __restrict__ log
                                                      const double* __restrict__ ws_lse_p,
                                                      const float* __restrict__ tab_ref, const float* __restrict__ tab_s,
                                                      const float* __restrict__ tab_p, FinalOut o) {
-    __shared__ PickShared<kWG> sh;
     const int b = blockIdx.x;
     const FinalRow f = final_row<DT>(b, K, Vd, o.n_accepted, o.seq_status, tok_d, d2t, ws_lse_p, lse_q, c_t, c_d);
     if (f.skip) return;
-    final_pick_row<DT, kWG>(f, b, logits_t, logits_d, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
-                            tab_s + (int64_t)b * nC, tab_p + (int64_t)b * nC, o, sh);
+    final_pick_row<DT>(f, b, logits_t, logits_d, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
+                       tab_s + (int64_t)b * nC, tab_p + (int64_t)b * nC, o);
 }
 
 // ---- plain copy, used only to calibrate hardware byte counters against a known size -----------
@@ -1084,7 +1076,7 @@ void launch_draft(const tli_map* map, const void* logits_d, int64_t row_stride, 
     }
     {
         KernelTimer t(TLI_KERNEL_DRAFT_PICK, st);
-        hipLaunchKernelGGL(k_draft_pick<DT>, dim3(R), dim3(kWG), 0, st, logits_d, row_stride, Vd, pl.nC, cs, ratio,
+        hipLaunchKernelGGL(k_draft_pick<DT>, dim3(R), dim3(kWave), 0, st, logits_d, row_stride, Vd, pl.nC, cs, ratio,
                            inv_temp, map->lmask[DT], map->d2t, tab_ref, tab_s, o);
     }
 }
@@ -1117,7 +1109,7 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
-        hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWG), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pf.nC,
+        hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pf.nC,
                            a.cs_t, a.ratio_t, a.c_t, a.c_d, a.map->d2t, a.map->t2d, a.tok_d, a.lse_q, a.ws_lse_p,
                            a.tab_ref, a.tab_s, a.tab_p, fo);
     }
