@@ -85,7 +85,8 @@ def main():
     torch.cuda.synchronize()
 
     # ---- timed region: exactly `steps` steps; HIP events around the dominant kernel on the launch stream
-    binding.tli_profile_enable(["lse", "draft_scan"], args.steps)
+    # (an event pair costs ~10 us of idle GPU, so one step in five carries it)
+    binding.tli_profile_enable(["lse"], args.steps, every=5)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -93,7 +94,6 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     lse_ms, lse_n = binding.tli_profile_collect("lse")
-    dscan_ms, dscan_n = binding.tli_profile_collect("draft_scan")
     binding.tli_profile_disable()
     total_s = t1 - t0
     ms_per_step = 1e3 * total_s / args.steps
@@ -146,8 +146,6 @@ def main():
         verify_frac_of_peak=round(verify_bytes / (1e-3 * verify_ms) / 1e9 / HBM_PEAK_GBS, 4),
         draft_rows_per_s=round(R / (1e-3 * draft_ms), 1),
         draft_algorithmic_gbs=round(draft_bytes / (1e-3 * draft_ms) / 1e9, 1),
-        draft_scan_avg_us=round(1e3 * dscan_ms / max(dscan_n, 1), 2),
-        draft_scan_gbs=round(draft_bytes / (1e-3 * dscan_ms / max(dscan_n, 1)) / 1e9, 1),
         mean_accepted=round(float(n_acc.mean()), 3),
     )
     if breakdown:

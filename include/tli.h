@@ -124,7 +124,9 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
  * Optional per-kernel timing for benchmarks (not part of the method): while enabled, the hot calls
  * record a HIP event pair around each selected kernel on the caller's stream.  Not thread-safe.
  *   tli_profile_enable  : creates 2*max_calls events per selected kernel (bit k of kernel_mask selects
- *                         kernel k of tli_kernel_id); recording stops silently once they are used up.
+ *                         kernel k of tli_kernel_id) and records one launch in `every` (an event between two
+ *                         kernels costs a few microseconds of idle GPU, so a timed loop samples);
+ *                         recording stops silently once the events are used up.
  *   tli_profile_collect : waits for the recorded events of one kernel, returns the summed duration
  *                         in milliseconds and the number of launches, and resets that kernel's counter.
  *   tli_profile_disable : destroys the events.
@@ -138,7 +140,7 @@ typedef enum {
     TLI_KERNEL_DRAFT_PICK = 5, /* tli_draft_sample: the draw, only when rows are split over workgroups     */
     TLI_KERNEL_COUNT = 6
 } tli_kernel_id;
-int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls);
+int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls, int32_t every);
 int tli_profile_collect(int32_t kernel, double* total_ms, int32_t* launches);
 void tli_profile_disable(void);
 

@@ -57,7 +57,7 @@ def load_library() -> ctypes.CDLL:
     lib.tli_verify.argtypes = [vp, vp, vp, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                vp, vp, vp, ctypes.c_size_t, vp]
     lib.tli_verify.restype = ctypes.c_int
-    lib.tli_profile_enable.argtypes = [ctypes.c_uint32, i32]
+    lib.tli_profile_enable.argtypes = [ctypes.c_uint32, i32, i32]
     lib.tli_profile_enable.restype = ctypes.c_int
     lib.tli_profile_collect.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     lib.tli_profile_collect.restype = ctypes.c_int
@@ -199,12 +199,12 @@ def tli_verify(m: TliMap, logits_t: torch.Tensor, logits_d: torch.Tensor, temp_t
     return out
 
 
-def tli_profile_enable(kernels, max_calls: int) -> None:
-    """kernels: iterable of names from KERNELS."""
+def tli_profile_enable(kernels, max_calls: int, every: int = 1) -> None:
+    """kernels: iterable of names from KERNELS; one launch in `every` is timed."""
     mask = 0
     for k in kernels:
         mask |= 1 << KERNELS.index(k)
-    rc = load_library().tli_profile_enable(mask, int(max_calls))
+    rc = load_library().tli_profile_enable(mask, int(max_calls), int(every))
     if rc != 0:
         raise TliError(rc, "tli_profile_enable")
 

@@ -184,11 +184,11 @@ __device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane
     s_out = wave_sum(s);
 }
 
-// Stream the chunks c_begin + wave, + kWaves, ... < c_end of one row through reduce_chunk and hand
+// Stream the chunks c_begin + wave, + NW, ... < c_end of one row (NW = waves in the workgroup) through reduce_chunk and hand
 // each (c, ref, s) to `sink`.  Whole chunks run in a two-stage register pipeline: the loads of the
 // next chunk are in flight while the current one is reduced.  A row has at most one partial chunk
 // (its last); the wave that owns it handles it after its whole chunks.
-template <int DT, bool MASKED, class Sink>
+template <int DT, bool MASKED, int NW, class Sink>
 __device__ __forceinline__ void scan_chunks(const u4v* rowv, int V, int c_begin, int c_end, float cs, const uint64_t* bits,
                                    Sink&& sink) {
     constexpr int EPV = Traits<DT>::EPV;
@@ -202,26 +202,26 @@ __device__ __forceinline__ void scan_chunks(const u4v* rowv, int V, int c_begin,
         ChunkRegs a, b;
         load_chunk_whole(rowv, c, lane, a);
         while (true) {
-            if (c + kWaves >= hot_end) {
+            if (c + NW >= hot_end) {
                 reduce_chunk<DT, MASKED, true>(a, c, lane, V, cs, bits, r, s);
                 sink(c, r, s);
-                c += kWaves;
+                c += NW;
                 break;
             }
-            load_chunk_whole(rowv, c + kWaves, lane, b);
+            load_chunk_whole(rowv, c + NW, lane, b);
             reduce_chunk<DT, MASKED, true>(a, c, lane, V, cs, bits, r, s);
             sink(c, r, s);
-            c += kWaves;
-            if (c + kWaves >= hot_end) {
+            c += NW;
+            if (c + NW >= hot_end) {
                 reduce_chunk<DT, MASKED, true>(b, c, lane, V, cs, bits, r, s);
                 sink(c, r, s);
-                c += kWaves;
+                c += NW;
                 break;
             }
-            load_chunk_whole(rowv, c + kWaves, lane, a);
+            load_chunk_whole(rowv, c + NW, lane, a);
             reduce_chunk<DT, MASKED, true>(b, c, lane, V, cs, bits, r, s);
             sink(c, r, s);
-            c += kWaves;
+            c += NW;
         }
     }
     if (c < c_end) {  // c == n_whole: the partial chunk
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     Running run;
-    scan_chunks<DT, false>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, nullptr,
+    scan_chunks<DT, false, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, nullptr,
                            [&](int, float r, float sc) { run.add(r, sc); });
     __shared__ float sref[kWaves];
     __shared__ double ssum[kWaves];
@@ -302,7 +302,7 @@ template <int DT, bool MASKED>
 __device__ __forceinline__ void table_scan(const u4v* rowv, int split, int V, int nC, int cps, float cs, const uint64_t* bits,
                                   float* tab_ref, float* tab_s) {
     const int lane = threadIdx.x & 63;
-    scan_chunks<DT, MASKED>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, bits, [&](int c, float r, float sc) {
+    scan_chunks<DT, MASKED, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, bits, [&](int c, float r, float sc) {
         if (lane == 0) { tab_ref[c] = r; tab_s[c] = sc; }
     });
 }
@@ -757,19 +757,6 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
 }
 
 // ---- kernels: chunk tables of the row the extra token is drawn from ----------------------------
-// Bonus rows (nothing rejected): (ref, s) softmax table of target row K.  grid (B * nsplit), 256 threads; workgroups of sequences that rejected a draft exit at once.
-template <int DT>
-__global__ __launch_bounds__(kWG) void k_final_bonus(const void* __restrict__ logits_t, int K, int Vt, int nC, int cps,
-                                                      int nsplit, float cs_t, const int32_t* __restrict__ n_accepted,
-                                                      const int32_t* __restrict__ seq_status,
-                                                      float* __restrict__ tab_ref, float* __restrict__ tab_s) {
-    const int b = blockIdx.x / nsplit, split = blockIdx.x - b * nsplit;
-    if ((seq_status[b] & TLI_FLAG_NONFINITE) || n_accepted[b] != K) return;
-    const char* rowp = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + K) * Vt * Traits<DT>::ESZ;
-    table_scan<DT, false>(reinterpret_cast<const u4v*>(rowp), split, Vt, nC, cps, cs_t, nullptr,
-                          tab_ref + (int64_t)b * nC, tab_s + (int64_t)b * nC);
-}
-
 // Residual rows (first rejection at position n < K): tab_s = chunk sums of max(0, p_n - q'_n), tab_p =
 // chunk sums of p_n (used only if the residual is identically zero), tab_ref = 0.
 //
@@ -781,7 +768,9 @@ __global__ __launch_bounds__(kWG) void k_final_bonus(const void* __restrict__ lo
 // ascending and nearly coalesced -- and drops each raw logit at its offset (LDS takes scattered 2-byte
 // writes at full rate).  Ids without a partner keep -inf, i.e. q' = 0.  The target segment is then
 // streamed once with 16-byte global loads next to conflict-free 16-byte LDS reads.
-// grid (B rounded up to 8, times nseg), 1024 threads; workgroups of bonus / flagged sequences exit at once.
+// Bonus rows (nothing rejected) go through the same grid: the workgroup scans its segment of target row
+// K into a plain (ref, s) softmax table.
+// grid (B rounded up to 8, times nseg), 1024 threads; workgroups of flagged sequences exit at once.
 constexpr int kSegBytes = 128 * 1024;
 constexpr int kSegWG = 1024;
 constexpr int kSegWaves = kSegWG / kWave;
@@ -789,9 +778,9 @@ constexpr int kGatherU = 12;
 template <int DT> constexpr int seg_elems() { return kSegBytes / Traits<DT>::ESZ; }
 
 template <int DT>
-__global__ __launch_bounds__(kSegWG) void k_final_residual(
+__global__ __launch_bounds__(kSegWG) void k_final_scan(
     const void* __restrict__ logits_t, const void* __restrict__ logits_d, int B, int K, int Vt, int Vd, int nC,
-    int nseg, double c_t, double c_d, const int32_t* __restrict__ d2t, const int32_t* __restrict__ seg_start,
+    int nseg, float cs_t, double c_t, double c_d, const int32_t* __restrict__ d2t, const int32_t* __restrict__ seg_start,
     const int32_t* __restrict__ seg_x, const uint16_t* __restrict__ seg_off, const int32_t* __restrict__ tok_d,
     const double* __restrict__ lse_q, const int32_t* __restrict__ n_accepted, const int32_t* __restrict__ seq_status,
     const double* __restrict__ ws_lse_p, float* __restrict__ tab_ref, float* __restrict__ tab_s,
@@ -810,7 +799,19 @@ __global__ __launch_bounds__(kSegWG) void k_final_residual(
     const int b = (slot / nseg) * 8 + xcd, sg = slot % nseg;
     if (b >= B) return;
     const FinalRow f = final_row<DT>(b, K, Vd, n_accepted, seq_status, tok_d, d2t, ws_lse_p, lse_q, c_t, c_d);
-    if (f.skip || f.bonus) return;
+    if (f.skip) return;
+    if (f.bonus) {
+        const u4v* rowk = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
+                                                        ((int64_t)b * (K + 1) + K) * Vt * ESZ);
+        float* br = tab_ref + (int64_t)b * nC;
+        float* bs = tab_s + (int64_t)b * nC;
+        const int lane0 = threadIdx.x & 63;
+        scan_chunks<DT, false, kSegWaves>(rowk, Vt, sg * kChunksPerSeg, min(nC, (sg + 1) * kChunksPerSeg), cs_t, nullptr,
+                                          [&](int c, float r, float sc) {
+                                              if (lane0 == 0) { br[c] = r; bs[c] = sc; }
+                                          });
+        return;
+    }
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
@@ -991,6 +992,8 @@ struct Profile {
     int cap = 0;
     std::vector<hipEvent_t> ev[TLI_KERNEL_COUNT];  // start/stop pairs
     int used[TLI_KERNEL_COUNT] = {};
+    int every = 1;                      // record one launch in `every`
+    int seen[TLI_KERNEL_COUNT] = {};
 } g_prof;
 
 struct KernelTimer {  // records start on construction, stop on destruction, if kernel `id` is being profiled
@@ -998,7 +1001,8 @@ struct KernelTimer {  // records start on construction, stop on destruction, if 
     hipStream_t st;
     bool live;
     KernelTimer(int id_, hipStream_t st_) : id(id_), st(st_), live(false) {
-        if (g_prof.on && (g_prof.mask >> id & 1u) && g_prof.used[id] + 2 <= (int)g_prof.ev[id].size()) {
+        if (g_prof.on && (g_prof.mask >> id & 1u) && (g_prof.seen[id]++ % g_prof.every) == 0 &&
+            g_prof.used[id] + 2 <= (int)g_prof.ev[id].size()) {
             live = true;
             (void)hipEventRecord(g_prof.ev[id][g_prof.used[id]], st);
         }
@@ -1100,12 +1104,10 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     {
         KernelTimer t(TLI_KERNEL_FINAL_SCAN, st);
         const int nseg = a.map->nseg[DT];
-        hipLaunchKernelGGL(k_final_residual<DT>, dim3((unsigned)((B + 7) / 8) * 8 * nseg), dim3(kSegWG), 0, st,
-                           a.logits_t, a.logits_d, B, K, Vt, Vd, a.pf.nC, nseg, a.c_t, a.c_d, a.map->d2t,
+        hipLaunchKernelGGL(k_final_scan<DT>, dim3((unsigned)((B + 7) / 8) * 8 * nseg), dim3(kSegWG), 0, st, a.logits_t,
+                           a.logits_d, B, K, Vt, Vd, a.pf.nC, nseg, a.cs_t, a.c_t, a.c_d, a.map->d2t,
                            a.map->seg_start[DT], a.map->seg_x[DT], a.map->seg_off[DT], a.tok_d, a.lse_q, a.n_accepted,
                            a.seq_status, a.ws_lse_p, a.tab_ref, a.tab_s, a.tab_p);
-        hipLaunchKernelGGL(k_final_bonus<DT>, dim3((unsigned)B * a.pf.nsplit), dim3(kWG), 0, st, a.logits_t, K, Vt,
-                           a.pf.nC, a.pf.cps, a.pf.nsplit, a.cs_t, a.n_accepted, a.seq_status, a.tab_ref, a.tab_s);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
@@ -1126,9 +1128,9 @@ int tli_calib_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
     return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
 }
 
-int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls) {
+int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls, int32_t every) {
     tli_profile_disable();
-    if (max_calls < 1 || max_calls > (1 << 20)) return TLI_ERR_INVALID_ARG;
+    if (max_calls < 1 || max_calls > (1 << 20) || every < 1) return TLI_ERR_INVALID_ARG;
     for (int k = 0; k < TLI_KERNEL_COUNT; ++k) {
         if (!(kernel_mask >> k & 1u)) continue;
         g_prof.ev[k].resize((size_t)2 * max_calls);
@@ -1137,6 +1139,7 @@ int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls) {
     }
     g_prof.mask = kernel_mask;
     g_prof.cap = max_calls;
+    g_prof.every = every;
     g_prof.on = true;
     return TLI_OK;
 }
@@ -1163,6 +1166,7 @@ void tli_profile_disable(void) {
             if (e) (void)hipEventDestroy(e);
         g_prof.ev[k].clear();
         g_prof.used[k] = 0;
+        g_prof.seen[k] = 0;
     }
     g_prof.on = false;
     g_prof.mask = 0;
