@@ -1309,7 +1309,9 @@ int tli_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, 
         return TLI_ERR_INVALID_ARG;
     const int Vd = map->Vd;
     const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
-    const Plan pl = make_plan(Vd, R, chunk);
+    Plan pl = make_plan(Vd, R, chunk);
+    // from 4 workgroups per CU on, a row per workgroup (scan and draw in one kernel) beats splitting rows
+    if (R >= 1024 && pl.nC <= kLdsChunks) { pl.nsplit = 1; pl.cps = pl.nC; }
     const size_t tab_bytes = align256((size_t)R * pl.nC * sizeof(float));
     if (workspace_bytes < 2 * tab_bytes) return TLI_ERR_ALLOC;
     float* tab_ref = reinterpret_cast<float*>(workspace);
