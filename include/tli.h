@@ -102,7 +102,9 @@ int tli_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, 
  * norm(max(0, p_j - q'_j)) of the first rejected position j, or from p_{K+1} if nothing was rejected.
  *   logits_t   dev [B, K+1, Vt] dense      logits_d dev [B, K, Vd] dense
  *   tok_d      dev [B,K] int32 draft ids in DRAFTER id space (as returned by tli_draft_sample)
- *   lse_q      dev [B,K] fp64  as returned by tli_draft_sample for the same rows
+ *   lse_q      dev [B,K] fp64  as returned by tli_draft_sample for the same rows, or NULL: the library
+ *                              then recomputes it with one extra scan of the drafter rows (K*Vd more
+ *                              logits read per sequence)
  *   u_acc      dev [B,K] fp32, u_fin dev [B] fp32
  *   n_accepted dev [B]     int32
  *   out_tok    dev [B,K+1] int32 : n_accepted target ids, then the extra token, then -1 padding

@@ -177,14 +177,15 @@ def alloc_verify_outputs(B: int, K: int, device) -> dict:
 def tli_verify(m: TliMap, logits_t: torch.Tensor, logits_d: torch.Tensor, temp_t: float, temp_d: float,
                tok_d: torch.Tensor, lse_q: torch.Tensor, u_acc: torch.Tensor, u_fin: torch.Tensor,
                workspace: torch.Tensor, out: dict | None = None, stream=None) -> dict:
-    """logits_t [B,K+1,Vt], logits_d [B,K,Vd] dense; tok_d int32 [B,K]; lse_q float64 [B,K]."""
+    """logits_t [B,K+1,Vt], logits_d [B,K,Vd] dense; tok_d int32 [B,K]; lse_q float64 [B,K] or None
+    (None: the library recomputes the drafter normalisers)."""
     lib = load_library()
     B, K1, Vt = logits_t.shape
     K = K1 - 1
     assert logits_t.is_cuda and logits_t.is_contiguous() and logits_d.is_contiguous()
     assert tuple(logits_d.shape) == (B, K, m.Vd) and Vt == m.Vt and logits_t.dtype == logits_d.dtype
     assert tok_d.dtype == torch.int32 and tok_d.numel() == B * K and tok_d.is_contiguous()
-    assert lse_q.dtype == torch.float64 and lse_q.numel() == B * K and lse_q.is_contiguous()
+    assert lse_q is None or (lse_q.dtype == torch.float64 and lse_q.numel() == B * K and lse_q.is_contiguous())
     assert u_acc.dtype == torch.float32 and u_acc.numel() == B * K and u_acc.is_contiguous()
     assert u_fin.dtype == torch.float32 and u_fin.numel() == B and u_fin.is_contiguous()
     if out is None:

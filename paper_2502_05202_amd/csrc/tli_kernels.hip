@@ -265,22 +265,24 @@ struct Part {  // partial log-normaliser of (a split of) a row: sum 2^(x*c) = s 
 };
 
 
-// ---- kernel: log-normaliser partials of the K target rows each sequence needs -----------------
-// Standard SD appendix, verification loop: p_k(d_k) needs the normaliser of every target row k < K.
+// ---- kernel: log-normaliser partials of rows -----------------------------------------------------
+// Standard SD appendix, verification loop: p_k(d_k) needs the normaliser of every target row k < K
+// (MASKED = false).  With MASKED = true the same scan runs over drafter rows restricted to the shared
+// ids (the normaliser of q' in the intersection algorithm), for callers that do not pass lse_q.
 // grid (rows * nsplit); row r = (b, k) with b = r / K, k = r % K.
-template <int DT>
+template <int DT, bool MASKED>
 __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, int K, int64_t seq_stride,
                                               int64_t row_stride, int V, int nC, int cps, int nsplit, float cs,
-                                              Part* __restrict__ part) {
+                                              const uint64_t* __restrict__ bits, Part* __restrict__ part) {
     const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
     const int b = row / K, k = row - b * K;
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
-                                                        (b * seq_stride + k * row_stride) * Traits<DT>::ESZ);
+                                                    (b * seq_stride + k * row_stride) * Traits<DT>::ESZ);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     Running run;
-    scan_chunks<DT, false, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, nullptr,
-                           [&](int, float r, float sc) { run.add(r, sc); });
+    scan_chunks<DT, MASKED, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, bits,
+                                    [&](int, float r, float sc) { run.add(r, sc); });
     __shared__ float sref[kWaves];
     __shared__ double ssum[kWaves];
     if (lane == 0) { sref[wave] = run.ref; ssum[wave] = run.s; }
@@ -293,6 +295,26 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
         Part p; p.ref = R; p.pad = 0.f; p.s = S;
         part[(int64_t)row * nsplit + split] = p;
     }
+}
+
+// log-normaliser of a row from its partials: ln sum exp(x/temp) = ln2 * (ref * c_true/c + log2 S), where the
+// factor c_true/c takes out the common part of the fp32 rounding of c.  NaN if a logit was NaN/+inf,
+// -inf if the row has no mass.
+__device__ __forceinline__ double combine_parts(const Part* pr, int nsplit, double ratio) {
+    float R = pr[0].ref;
+    for (int s = 1; s < nsplit; ++s) R = fmaxf(R, pr[s].ref);
+    double S = 0.0;
+    for (int s = 0; s < nsplit; ++s) S += pr[s].s * exp2_diff(pr[s].ref, R);
+    if (S != S || R == INFINITY) return NAN;
+    if (!(S > 0.0)) return -INFINITY;
+    return kLn2 * ((double)R * ratio + log2(S));
+}
+
+// kernel: lse[row] from the partials of k_lse.  grid (ceil(rows / 256)).
+__global__ __launch_bounds__(kWG) void k_lse_finish(const Part* __restrict__ part, int rows, int nsplit, double ratio,
+                                                     double* __restrict__ lse) {
+    const int row = blockIdx.x * kWG + threadIdx.x;
+    if (row < rows) lse[row] = combine_parts(part + (int64_t)row * nsplit, nsplit, ratio);
 }
 
 // ---- kernel: per-chunk (ref, s) table of a softmax row, optionally masked to the shared ids ----
@@ -541,13 +563,8 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
     int tt = -1;
     if (k < K) {
         const int64_t row = (int64_t)b * K + k;
-        const Part* pr = part + row * nsplit;
-        float R = pr[0].ref;
-        for (int s = 1; s < nsplit; ++s) R = fmaxf(R, pr[s].ref);
-        double S = 0.0;
-        for (int s = 0; s < nsplit; ++s) S += pr[s].s * exp2_diff(pr[s].ref, R);
-        nonfinite = (S != S) || (R == INFINITY);
-        const double lse = kLn2 * ((double)R * ratio_t + log2(S));
+        const double lse = combine_parts(part + row * nsplit, nsplit, ratio_t);
+        nonfinite = lse != lse;
         ws_lse_p[row] = lse;
         if (lse_p) lse_p[(int64_t)b * (K + 1) + k] = lse;
         const int d = tok_d[row];
@@ -559,7 +576,7 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
             tt = d2t[d];
             const char* lt = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + k) * Vt * Traits<DT>::ESZ;
             const char* ld = static_cast<const char*>(logits_d) + row * Vd * Traits<DT>::ESZ;
-            pd = exp((double)load_elem<DT>(lt, tt) * inv_temp_t - lse);
+            pd = (lse == -INFINITY) ? 0.0 : exp((double)load_elem<DT>(lt, tt) * inv_temp_t - lse);
             qd = exp((double)load_elem<DT>(ld, d) * inv_temp_d - lse_q[row]);
             acc = (double)u_acc[row] * qd < pd;
         }
@@ -962,7 +979,7 @@ Plan make_plan(int V, int rows, int chunk) {
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {  // offsets into the caller's scratch
-    size_t part, ws_lse_p, tab_ref, tab_s, tab_p, total;
+    size_t part, part_d, ws_lse_p, ws_lse_q, tab_ref, tab_s, tab_p, total;
 };
 
 Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
@@ -974,8 +991,11 @@ Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
     const size_t tab = tab_rows_d > tab_rows_t ? tab_rows_d : tab_rows_t;
     Workspace w;
     size_t off = 0;
+    const Plan pd = make_plan(Vd, (int)rows, chunk);
     w.part = off; off += align256((size_t)rows * pl.nsplit * sizeof(Part));
+    w.part_d = off; off += align256((size_t)rows * pd.nsplit * sizeof(Part));
     w.ws_lse_p = off; off += align256((size_t)rows * sizeof(double));
+    w.ws_lse_q = off; off += align256((size_t)rows * sizeof(double));
     w.tab_ref = off; off += align256(tab * sizeof(float));
     w.tab_s = off; off += align256(tab * sizeof(float));
     w.tab_p = off; off += align256(tab_rows_t * sizeof(float));
@@ -1034,8 +1054,11 @@ struct VerifyArgs {
     uint8_t* accept;
     double *p_tok, *q_tok, *lse_p;
     int32_t* seq_status;
-    Part* part;
-    double* ws_lse_p;
+    Part *part, *part_d;
+    double *ws_lse_p, *ws_lse_q;
+    Plan pd;
+    float cs_d;
+    double ratio_d;
     float *tab_ref, *tab_s, *tab_p;
 };
 template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st);
@@ -1090,15 +1113,25 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     FinalOut fo;
     fo.u_fin = a.u_fin; fo.n_accepted = a.n_accepted; fo.out_tok = a.out_tok; fo.lse_p = a.lse_p;
     fo.seq_status = a.seq_status;
+    const double* lse_q = a.lse_q;
+    if (!lse_q) {  // the caller did not keep the drafter normalisers: one masked scan of the drafter rows
+        hipLaunchKernelGGL((k_lse<DT, true>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), 0, st, a.logits_d, K,
+                           (int64_t)K * Vd, (int64_t)Vd, Vd, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d,
+                           a.map->lmask[DT], a.part_d);
+        hipLaunchKernelGGL(k_lse_finish, dim3((rows + kWG - 1) / kWG), dim3(kWG), 0, st, a.part_d, rows, a.pd.nsplit,
+                           a.ratio_d, a.ws_lse_q);
+        lse_q = a.ws_lse_q;
+    }
     {
         KernelTimer t(TLI_KERNEL_LSE, st);
-        hipLaunchKernelGGL(k_lse<DT>, dim3((unsigned)rows * a.pl.nsplit), dim3(kWG), 0, st, a.logits_t, K,
-                           (int64_t)(K + 1) * Vt, (int64_t)Vt, Vt, a.pl.nC, a.pl.cps, a.pl.nsplit, a.cs_t, a.part);
+        hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * a.pl.nsplit), dim3(kWG), 0, st, a.logits_t, K,
+                           (int64_t)(K + 1) * Vt, (int64_t)Vt, Vt, a.pl.nC, a.pl.cps, a.pl.nsplit, a.cs_t, nullptr,
+                           a.part);
     }
     {
         KernelTimer t(TLI_KERNEL_ACCEPT, st);
         hipLaunchKernelGGL(k_accept<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pl.nsplit,
-                           a.part, a.ratio_t, a.inv_t, a.inv_d, a.map->d2t, a.tok_d, a.lse_q, a.u_acc, a.n_accepted,
+                           a.part, a.ratio_t, a.inv_t, a.inv_d, a.map->d2t, a.tok_d, lse_q, a.u_acc, a.n_accepted,
                            a.out_tok, a.accept, a.p_tok, a.q_tok, a.lse_p, a.seq_status, a.ws_lse_p);
     }
     {
@@ -1106,13 +1139,13 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
         const int nseg = a.map->nseg[DT];
         hipLaunchKernelGGL(k_final_scan<DT>, dim3((unsigned)((B + 7) / 8) * 8 * nseg), dim3(kSegWG), 0, st, a.logits_t,
                            a.logits_d, B, K, Vt, Vd, a.pf.nC, nseg, a.cs_t, a.c_t, a.c_d, a.map->d2t,
-                           a.map->seg_start[DT], a.map->seg_x[DT], a.map->seg_off[DT], a.tok_d, a.lse_q, a.n_accepted,
+                           a.map->seg_start[DT], a.map->seg_x[DT], a.map->seg_off[DT], a.tok_d, lse_q, a.n_accepted,
                            a.seq_status, a.ws_lse_p, a.tab_ref, a.tab_s, a.tab_p);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
         hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pf.nC,
-                           a.cs_t, a.ratio_t, a.c_t, a.c_d, a.map->d2t, a.map->t2d, a.tok_d, a.lse_q, a.ws_lse_p,
+                           a.cs_t, a.ratio_t, a.c_t, a.c_d, a.map->d2t, a.map->t2d, a.tok_d, lse_q, a.ws_lse_p,
                            a.tab_ref, a.tab_s, a.tab_p, fo);
     }
 }
@@ -1334,7 +1367,7 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
                const float* u_fin, int32_t* n_accepted, int32_t* out_tok, uint8_t* accept, double* p_tok,
                double* q_tok, double* lse_p, int32_t* seq_status, void* workspace, size_t workspace_bytes,
                void* hip_stream) {
-    if (!map || !logits_t || !logits_d || !tok_d || !lse_q || !u_acc || !u_fin || !n_accepted || !out_tok ||
+    if (!map || !logits_t || !logits_d || !tok_d || !u_acc || !u_fin || !n_accepted || !out_tok ||
         !seq_status || !workspace)
         return TLI_ERR_INVALID_ARG;
     if (B < 1 || K < 1 || K > kMaxK || (int64_t)B * K > 0x7fffffff / 64) return TLI_ERR_INVALID_ARG;
@@ -1368,7 +1401,9 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
     a.c_t = c_t; a.c_d = c_d; a.cs_t = cs_t; a.ratio_t = ratio_t; a.inv_t = inv_t; a.inv_d = inv_d;
     a.tok_d = tok_d; a.lse_q = lse_q; a.u_acc = u_acc; a.u_fin = u_fin; a.n_accepted = n_accepted;
     a.out_tok = out_tok; a.accept = accept; a.p_tok = p_tok; a.q_tok = q_tok; a.lse_p = lse_p;
-    a.seq_status = seq_status; a.part = part; a.ws_lse_p = ws_lse_p; a.tab_ref = tab_ref; a.tab_s = tab_s;
+    a.seq_status = seq_status; a.part = part; a.ws_lse_p = ws_lse_p;
+    a.part_d = reinterpret_cast<Part*>(ws + w.part_d); a.ws_lse_q = reinterpret_cast<double*>(ws + w.ws_lse_q);
+    a.pd = make_plan(Vd, rows, chunk); a.cs_d = (float)c_d; a.ratio_d = c_d / (double)a.cs_d; a.tab_ref = tab_ref; a.tab_s = tab_s;
     a.tab_p = tab_p;
     if (dtype == TLI_BF16) launch_verify<TLI_BF16>(a, st);
     else launch_verify<TLI_F32>(a, st);

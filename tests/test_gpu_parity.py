@@ -160,6 +160,29 @@ def test_flags_and_edge_inputs(oracle):
     m.free()
 
 
+def test_verify_recomputes_missing_lse_q(oracle):
+    """tli_verify with lse_q = NULL (one extra masked scan of the drafter rows) against the oracle."""
+    for w in (synth.WORKLOADS[3].scaled(B=12, K=4, Vt=30000, Vd=2048 * 5 + 64, S=4000),
+              synth.WORKLOADS[2].scaled(B=3, K=5, Vt=9000, Vd=7000, S=2500)):
+        inp = synth.make_inputs(w, DEV)
+        m = binding.tli_build_map(inp["d2t"], w.Vt)
+        code = binding.TLI_F32 if w.dtype == "f32" else binding.TLI_BF16
+        ws = binding.alloc_workspace(w.B, w.K, m, code, DEV)
+        lt_np, ld_np = synth.logits_to_numpy(inp["logits_t"]), synth.logits_to_numpy(inp["logits_d"])
+        ud = inp["u_draft"].cpu().numpy().astype(np.float64)
+        ref_d = oracle.draft_sample(ld_np.reshape(w.B * w.K, w.Vd), w.tau_d, inp["d2t"], ud, threads=8)
+        tok = torch.from_numpy(ref_d["tok_d"]).to(DEV)
+        g = binding.tli_verify(m, inp["logits_t"], inp["logits_d"], w.tau_t, w.tau_d, tok, None,
+                               inp["u_acc"].reshape(-1), inp["u_fin"], ws)
+        torch.cuda.synchronize()
+        rep, _ = parity.compare_verify(oracle, lt_np, ld_np, w.tau_t, w.tau_d, inp["d2t"], ref_d["tok_d"],
+                                       inp["u_acc"].cpu().numpy().astype(np.float64),
+                                       inp["u_fin"].cpu().numpy().astype(np.float64), parity.to_host(g), threads=8)
+        print(dict(rep))
+        assert rep["hard"] == 0
+        m.free()
+
+
 def test_deterministic(oracle):
     w = synth.WORKLOADS[3].scaled(B=16, K=3, Vt=20000, Vd=12000, S=5000)
     inp = synth.make_inputs(w, DEV)
