@@ -158,6 +158,7 @@ def main():
 
         oracle.build()
         cores = min(16, len(os.sched_getaffinity(0)))
+        tau_t, tau_d = float(np.float32(w.tau_t)), float(np.float32(w.tau_d))  # the C ABI's temperatures are fp32
         per_seq_s = 0.12 * (w.K * (w.Vt + w.Vd)) / (8 * (256000 + 128256))  # rough single-thread cost
         nseq = args.cpu_seqs or int(max(1, min(w.B, 20.0 * cores / max(per_seq_s, 1e-6))))
         nseq = max(min(nseq, w.B), 1)
@@ -167,13 +168,13 @@ def main():
         ua = inp["u_acc"][:nseq].cpu().numpy().astype(np.float64)
         uf = inp["u_fin"][:nseq].cpu().numpy().astype(np.float64)
         c0 = time.perf_counter()
-        ds = oracle.draft_sample(ld.reshape(nseq * w.K, w.Vd), w.tau_d, inp["d2t"], ud, threads=cores)
-        oracle.verify(lt, ld, w.tau_t, w.tau_d, inp["d2t"], ds["tok_d"], ua, uf, threads=cores)
+        ds = oracle.draft_sample(ld.reshape(nseq * w.K, w.Vd), tau_d, inp["d2t"], ud, threads=cores)
+        oracle.verify(lt, ld, tau_t, tau_d, inp["d2t"], ds["tok_d"], ua, uf, threads=cores)
         c1 = time.perf_counter()
         n1 = max(1, min(nseq, 8))
         s0 = time.perf_counter()
-        ds1 = oracle.draft_sample(ld[:n1].reshape(n1 * w.K, w.Vd), w.tau_d, inp["d2t"], ud[:n1], threads=1)
-        oracle.verify(lt[:n1], ld[:n1], w.tau_t, w.tau_d, inp["d2t"], ds1["tok_d"], ua[:n1], uf[:n1], threads=1)
+        ds1 = oracle.draft_sample(ld[:n1].reshape(n1 * w.K, w.Vd), tau_d, inp["d2t"], ud[:n1], threads=1)
+        oracle.verify(lt[:n1], ld[:n1], tau_t, tau_d, inp["d2t"], ds1["tok_d"], ua[:n1], uf[:n1], threads=1)
         s1 = time.perf_counter()
         cpu = dict(value=round(nseq * w.K / (c1 - c0), 2), unit="positions/s", cores=cores, kind="oracle",
                    sample=f"first {nseq} of {w.B} sequences of the same batch, draft+verify, {cores} threads, "

@@ -11,6 +11,9 @@ LIB = os.path.join(_HERE, "libtli.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    # no implicit a*b+c fusion: the kernels rely on products being rounded exactly where they say so (a chunk's
+    # reference must be THE fp32 number the exponents were formed against); wanted FMAs are written as fmaf
+    "-ffp-contract=off",
     # packed fp32 instructions are disabled for the device pass (the host pass does not know the feature)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"),

@@ -143,8 +143,8 @@ template <int DT> __device__ __forceinline__ uint32_t mask_bits(const uint64_t* 
 // ref = ceil(max over the chunk of fp32(x*c)) (-inf and s = 0 for a chunk without finite entries).
 // A NaN or +inf logit turns s into NaN.  Wave-uniform results.  WHOLE: every element is < V.
 template <int DT, bool MASKED, bool WHOLE>
-__device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane, int V, float cs, const uint64_t* bits,
-                                    float& ref_out, float& s_out) {
+__device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane, int V, float cs, float dl,
+                                             const uint64_t* bits, float& ref_out, float& s_out) {
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int N = EPV * kLoads;
     float x[N];
@@ -170,6 +170,9 @@ __device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane
     float m = x[0];
 #pragma unroll
     for (int i = 1; i < N; ++i) m = fmaxf(m, x[i]);
+    // ref must be THE rounded product that the fma below subtracts.  (Built with -ffp-contract=off: fused into
+    // the later `ref - R`, the multiply would enter there unrounded and the lane's sum would be rescaled
+    // against a reference it was not formed with -- an error of up to 1.4e-6, measured.)
     const float ref = m * cs;
     const float nref = (m == -INFINITY) ? 0.f : -ref;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
@@ -179,7 +182,10 @@ __device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane
     // the chunk's reference is rounded up to an integer: every later rescaling between references is then
     // an exact power of two (ldexp), in fp32 and fp64 alike
     const float R = ceilf(wave_max(ref));
-    s = (m == -INFINITY) ? 0.f : s * exp2_hw(ref - R);
+    // (1 + dl) = c_true / c: the lane is moved to the chunk reference in the TRUE scale, which takes the
+    // fp32 rounding of c out of everything but the spread of logits inside one lane
+    const float e = ref - R;
+    s = (m == -INFINITY) ? 0.f : s * exp2_hw(fmaf(e, dl, e));
     ref_out = R;
     s_out = wave_sum(s);
 }
@@ -189,7 +195,8 @@ __device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane
 // next chunk are in flight while the current one is reduced.  A row has at most one partial chunk
 // (its last); the wave that owns it handles it after its whole chunks.
 template <int DT, bool MASKED, int NW, class Sink>
-__device__ __forceinline__ void scan_chunks(const u4v* rowv, int V, int c_begin, int c_end, float cs, const uint64_t* bits,
+__device__ __forceinline__ void scan_chunks(const u4v* rowv, int V, int c_begin, int c_end, float cs, float dl,
+                                            const uint64_t* bits,
                                    Sink&& sink) {
     constexpr int EPV = Traits<DT>::EPV;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -203,23 +210,23 @@ __device__ __forceinline__ void scan_chunks(const u4v* rowv, int V, int c_begin,
         load_chunk_whole(rowv, c, lane, a);
         while (true) {
             if (c + NW >= hot_end) {
-                reduce_chunk<DT, MASKED, true>(a, c, lane, V, cs, bits, r, s);
+                reduce_chunk<DT, MASKED, true>(a, c, lane, V, cs, dl, bits, r, s);
                 sink(c, r, s);
                 c += NW;
                 break;
             }
             load_chunk_whole(rowv, c + NW, lane, b);
-            reduce_chunk<DT, MASKED, true>(a, c, lane, V, cs, bits, r, s);
+            reduce_chunk<DT, MASKED, true>(a, c, lane, V, cs, dl, bits, r, s);
             sink(c, r, s);
             c += NW;
             if (c + NW >= hot_end) {
-                reduce_chunk<DT, MASKED, true>(b, c, lane, V, cs, bits, r, s);
+                reduce_chunk<DT, MASKED, true>(b, c, lane, V, cs, dl, bits, r, s);
                 sink(c, r, s);
                 c += NW;
                 break;
             }
             load_chunk_whole(rowv, c + NW, lane, a);
-            reduce_chunk<DT, MASKED, true>(b, c, lane, V, cs, bits, r, s);
+            reduce_chunk<DT, MASKED, true>(b, c, lane, V, cs, dl, bits, r, s);
             sink(c, r, s);
             c += NW;
         }
@@ -227,33 +234,30 @@ __device__ __forceinline__ void scan_chunks(const u4v* rowv, int V, int c_begin,
     if (c < c_end) {  // c == n_whole: the partial chunk
         ChunkRegs t;
         load_chunk_tail<DT>(rowv, c, lane, (V + EPV - 1) / EPV, t);
-        reduce_chunk<DT, MASKED, false>(t, c, lane, V, cs, bits, r, s);
+        reduce_chunk<DT, MASKED, false>(t, c, lane, V, cs, dl, bits, r, s);
         sink(c, r, s);
     }
 }
 
-// 2^(a-b) for integer-valued references a <= b (or -inf / +inf): exact.  0 if a = -inf, NaN if both +inf.
-__device__ __forceinline__ float pow2_diff_f(float a, float b) {
-    if (a == -INFINITY) return 0.f;
-    const float d = a - b;
-    if (d != d) return NAN;
-    return ldexpf(1.f, (int)fmaxf(d, -200.f));
-}
-__device__ __forceinline__ double exp2_diff(float a, float b) {
+// 2^((a-b) * c_true/c) for integer-valued references a <= b (or -inf / +inf), with c_true/c = 1 + delta and
+// kd = delta * ln 2: an exact ldexp times the first-order factor (delta ~ 1e-8, the rest is < 1e-12).
+// 0 if a = -inf, NaN if both are +inf.
+__device__ __forceinline__ double exp2_diff(float a, float b, double kd) {
     if (a == -INFINITY) return 0.0;
     const float d = a - b;
     if (d != d) return NAN;
-    return ldexp(1.0, (int)fmaxf(d, -1100.f));
+    const float dc = fmaxf(d, -1100.f);
+    return ldexp(1.0 + kd * (double)dc, (int)dc);
 }
 
 // running (ref, sum) of a wave, sum kept in fp64
 struct Running {
     float ref = -INFINITY;
     double s = 0.0;
-    __device__ __forceinline__ void add(float r, float sc) {
+    __device__ __forceinline__ void add(float r, float sc, double kd) {
         const float nr = fmaxf(ref, r);
         if (nr == -INFINITY) return;
-        s = s * (double)pow2_diff_f(ref, nr) + (double)sc * (double)pow2_diff_f(r, nr);
+        s = s * exp2_diff(ref, nr, kd) + (double)sc * exp2_diff(r, nr, kd);
         ref = nr;
     }
 };
@@ -273,16 +277,18 @@ struct Part {  // partial log-normaliser of (a split of) a row: sum 2^(x*c) = s 
 template <int DT, bool MASKED>
 __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, int K, int64_t seq_stride,
                                               int64_t row_stride, int V, int nC, int cps, int nsplit, float cs,
-                                              const uint64_t* __restrict__ bits, Part* __restrict__ part) {
+                                              double ratio, const uint64_t* __restrict__ bits,
+                                              Part* __restrict__ part) {
     const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
     const int b = row / K, k = row - b * K;
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
                                                     (b * seq_stride + k * row_stride) * Traits<DT>::ESZ);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
+    const double kd = (ratio - 1.0) * kLn2;
     Running run;
-    scan_chunks<DT, MASKED, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, bits,
-                                    [&](int, float r, float sc) { run.add(r, sc); });
+    scan_chunks<DT, MASKED, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, (float)(ratio - 1.0), bits,
+                                    [&](int, float r, float sc) { run.add(r, sc, kd); });
     __shared__ float sref[kWaves];
     __shared__ double ssum[kWaves];
     if (lane == 0) { sref[wave] = run.ref; ssum[wave] = run.s; }
@@ -291,7 +297,7 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
         float R = sref[0];
         for (int w = 1; w < kWaves; ++w) R = fmaxf(R, sref[w]);
         double S = 0.0;
-        for (int w = 0; w < kWaves; ++w) S += ssum[w] * exp2_diff(sref[w], R);
+        for (int w = 0; w < kWaves; ++w) S += ssum[w] * exp2_diff(sref[w], R, kd);
         Part p; p.ref = R; p.pad = 0.f; p.s = S;
         part[(int64_t)row * nsplit + split] = p;
     }
@@ -304,7 +310,7 @@ __device__ __forceinline__ double combine_parts(const Part* pr, int nsplit, doub
     float R = pr[0].ref;
     for (int s = 1; s < nsplit; ++s) R = fmaxf(R, pr[s].ref);
     double S = 0.0;
-    for (int s = 0; s < nsplit; ++s) S += pr[s].s * exp2_diff(pr[s].ref, R);
+    for (int s = 0; s < nsplit; ++s) S += pr[s].s * exp2_diff(pr[s].ref, R, (ratio - 1.0) * kLn2);
     if (S != S || R == INFINITY) return NAN;
     if (!(S > 0.0)) return -INFINITY;
     return kLn2 * ((double)R * ratio + log2(S));
@@ -321,23 +327,26 @@ __global__ __launch_bounds__(kWG) void k_lse_finish(const Part* __restrict__ par
 // Used for drafter rows (masked: the intersection algorithm's q') and for the bonus target row.
 // Workgroup `split` of a row owns chunks [split*cps, (split+1)*cps).
 template <int DT, bool MASKED>
-__device__ __forceinline__ void table_scan(const u4v* rowv, int split, int V, int nC, int cps, float cs, const uint64_t* bits,
+__device__ __forceinline__ void table_scan(const u4v* rowv, int split, int V, int nC, int cps, float cs, double ratio,
+                                           const uint64_t* bits,
                                   float* tab_ref, float* tab_s) {
     const int lane = threadIdx.x & 63;
-    scan_chunks<DT, MASKED, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, bits, [&](int c, float r, float sc) {
+    scan_chunks<DT, MASKED, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, (float)(ratio - 1.0), bits,
+                                    [&](int c, float r, float sc) {
         if (lane == 0) { tab_ref[c] = r; tab_s[c] = sc; }
     });
 }
 
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_draft_scan(const void* __restrict__ logits, int64_t row_stride, int V,
-                                                     int nC, int cps, int nsplit, float cs,
+                                                     int nC, int cps, int nsplit, float cs, double ratio,
                                                      const uint64_t* __restrict__ bits, float* __restrict__ tab_ref,
                                                      float* __restrict__ tab_s) {
     const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
                                                     (int64_t)row * row_stride * Traits<DT>::ESZ);
-    table_scan<DT, true>(rowv, split, V, nC, cps, cs, bits, tab_ref + (int64_t)row * nC, tab_s + (int64_t)row * nC);
+    table_scan<DT, true>(rowv, split, V, nC, cps, cs, ratio, bits, tab_ref + (int64_t)row * nC,
+                         tab_s + (int64_t)row * nC);
 }
 
 // ---- wave-level sampler: one wave draws the token of a row from the row's chunk table ----------
@@ -453,7 +462,8 @@ __device__ __forceinline__ void softmax_vec_weights(const uint4* rowv, int64_t v
 // Inverse-CDF sample of a (masked) softmax row from its chunk table, by one wave.  Returns the id, or
 // -1 if the row has no usable mass (then *total_out is NaN for a NaN/+inf logit, else 0).
 template <int DT, bool MASKED>
-__device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int nC, float cs, const uint64_t* bits,
+__device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int nC, float cs, double ratio,
+                                                  const uint64_t* bits,
                                                   const float* tr, const float* ts, double u, float* M_out,
                                                   double* total_out) {
     constexpr int EPV = Traits<DT>::EPV;
@@ -462,8 +472,9 @@ __device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int n
     for (int c = lane; c < nC; c += kWave) m = fmaxf(m, tr[c]);
     const float M = wave_max(m);
     *M_out = M;
+    const double kd = (ratio - 1.0) * kLn2;
     double theta_local;
-    const int c = find_chunk(nC, u, [&](int cc) { return (double)ts[cc] * exp2_diff(tr[cc], M); }, &theta_local,
+    const int c = find_chunk(nC, u, [&](int cc) { return (double)ts[cc] * exp2_diff(tr[cc], M, kd); }, &theta_local,
                              total_out);
     if (c < 0) {
         if (M == INFINITY) *total_out = NAN;
@@ -495,7 +506,7 @@ __device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V,
                                       const float* ts, const DraftOut& o) {
     float M;
     double total;
-    const int d = sample_softmax_row<DT, true>(rowp, V, nC, cs, bits, tr, ts, (double)o.u_draft[row], &M, &total);
+    const int d = sample_softmax_row<DT, true>(rowp, V, nC, cs, c_ratio, bits, tr, ts, (double)o.u_draft[row], &M, &total);
     if ((threadIdx.x & 63) != 0) return;
     if (d < 0) {  // no usable mass: NaN/+inf among the shared logits, or all of them -inf
         const bool nonfinite = (total != total);
@@ -539,7 +550,7 @@ __global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ lo
     __shared__ float tr[kLdsChunks], ts[kLdsChunks];
     const int row = blockIdx.x;
     const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
-    table_scan<DT, true>(reinterpret_cast<const u4v*>(rowp), 0, V, nC, nC, cs, bits, tr, ts);
+    table_scan<DT, true>(reinterpret_cast<const u4v*>(rowp), 0, V, nC, nC, cs, c_ratio, bits, tr, ts);
     __syncthreads();
     if (threadIdx.x >= kWave) return;  // the first wave samples; the others retire and free their slots
     draft_pick_row<DT>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tr, ts, o);
@@ -725,7 +736,7 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
     if (f.bonus) {
         float M;
         double total;
-        tok = sample_softmax_row<DT, false>(rowp, Vt, nC, cs_t, nullptr, tr, ts, u, &M, &total);
+        tok = sample_softmax_row<DT, false>(rowp, Vt, nC, cs_t, ratio_t, nullptr, tr, ts, u, &M, &total);
         // no usable mass: NaN/+inf, or a bonus row of only -inf -- no distribution to sample either way
         if (tok < 0) nonfinite = true;
         else if (lane == 0 && o.lse_p) o.lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
@@ -797,7 +808,8 @@ template <int DT> constexpr int seg_elems() { return kSegBytes / Traits<DT>::ESZ
 template <int DT>
 __global__ __launch_bounds__(kSegWG) void k_final_scan(
     const void* __restrict__ logits_t, const void* __restrict__ logits_d, int B, int K, int Vt, int Vd, int nC,
-    int nseg, float cs_t, double c_t, double c_d, const int32_t* __restrict__ d2t, const int32_t* __restrict__ seg_start,
+    int nseg, float cs_t, double ratio_t, double c_t, double c_d, const int32_t* __restrict__ d2t,
+    const int32_t* __restrict__ seg_start,
     const int32_t* __restrict__ seg_x, const uint16_t* __restrict__ seg_off, const int32_t* __restrict__ tok_d,
     const double* __restrict__ lse_q, const int32_t* __restrict__ n_accepted, const int32_t* __restrict__ seq_status,
     const double* __restrict__ ws_lse_p, float* __restrict__ tab_ref, float* __restrict__ tab_s,
@@ -823,7 +835,8 @@ __global__ __launch_bounds__(kSegWG) void k_final_scan(
         float* br = tab_ref + (int64_t)b * nC;
         float* bs = tab_s + (int64_t)b * nC;
         const int lane0 = threadIdx.x & 63;
-        scan_chunks<DT, false, kSegWaves>(rowk, Vt, sg * kChunksPerSeg, min(nC, (sg + 1) * kChunksPerSeg), cs_t, nullptr,
+        scan_chunks<DT, false, kSegWaves>(rowk, Vt, sg * kChunksPerSeg, min(nC, (sg + 1) * kChunksPerSeg), cs_t,
+                                          (float)(ratio_t - 1.0), nullptr,
                                           [&](int c, float r, float sc) {
                                               if (lane0 == 0) { br[c] = r; bs[c] = sc; }
                                           });
@@ -1099,7 +1112,7 @@ void launch_draft(const tli_map* map, const void* logits_d, int64_t row_stride, 
     {
         KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
         hipLaunchKernelGGL(k_draft_scan<DT>, dim3((unsigned)R * pl.nsplit), dim3(kWG), 0, st, logits_d, row_stride, Vd,
-                           pl.nC, pl.cps, pl.nsplit, cs, map->lmask[DT], tab_ref, tab_s);
+                           pl.nC, pl.cps, pl.nsplit, cs, ratio, map->lmask[DT], tab_ref, tab_s);
     }
     {
         KernelTimer t(TLI_KERNEL_DRAFT_PICK, st);
@@ -1116,7 +1129,7 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     const double* lse_q = a.lse_q;
     if (!lse_q) {  // the caller did not keep the drafter normalisers: one masked scan of the drafter rows
         hipLaunchKernelGGL((k_lse<DT, true>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), 0, st, a.logits_d, K,
-                           (int64_t)K * Vd, (int64_t)Vd, Vd, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d,
+                           (int64_t)K * Vd, (int64_t)Vd, Vd, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d, a.ratio_d,
                            a.map->lmask[DT], a.part_d);
         hipLaunchKernelGGL(k_lse_finish, dim3((rows + kWG - 1) / kWG), dim3(kWG), 0, st, a.part_d, rows, a.pd.nsplit,
                            a.ratio_d, a.ws_lse_q);
@@ -1125,8 +1138,8 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     {
         KernelTimer t(TLI_KERNEL_LSE, st);
         hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * a.pl.nsplit), dim3(kWG), 0, st, a.logits_t, K,
-                           (int64_t)(K + 1) * Vt, (int64_t)Vt, Vt, a.pl.nC, a.pl.cps, a.pl.nsplit, a.cs_t, nullptr,
-                           a.part);
+                           (int64_t)(K + 1) * Vt, (int64_t)Vt, Vt, a.pl.nC, a.pl.cps, a.pl.nsplit, a.cs_t, a.ratio_t,
+                           nullptr, a.part);
     }
     {
         KernelTimer t(TLI_KERNEL_ACCEPT, st);
@@ -1138,7 +1151,7 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
         KernelTimer t(TLI_KERNEL_FINAL_SCAN, st);
         const int nseg = a.map->nseg[DT];
         hipLaunchKernelGGL(k_final_scan<DT>, dim3((unsigned)((B + 7) / 8) * 8 * nseg), dim3(kSegWG), 0, st, a.logits_t,
-                           a.logits_d, B, K, Vt, Vd, a.pf.nC, nseg, a.cs_t, a.c_t, a.c_d, a.map->d2t,
+                           a.logits_d, B, K, Vt, Vd, a.pf.nC, nseg, a.cs_t, a.ratio_t, a.c_t, a.c_d, a.map->d2t,
                            a.map->seg_start[DT], a.map->seg_x[DT], a.map->seg_off[DT], a.tok_d, lse_q, a.n_accepted,
                            a.seq_status, a.ws_lse_p, a.tab_ref, a.tab_s, a.tab_p);
     }

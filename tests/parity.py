@@ -42,8 +42,14 @@ def _cdf_distance(weights: np.ndarray, tok: int, u: float) -> float:
     return max(lo - u, u - hi, 0.0)
 
 
+def f32(x) -> float:
+    """The C ABI takes temperatures as fp32: the oracle must be given the same (rounded) number."""
+    return float(np.float32(x))
+
+
 def compare_draft(oracle_mod, ld_np, tau_d, d2t, u_draft, gpu: dict, ref: dict | None = None, threads=16):
     """gpu: dict of host numpy arrays tok_d, tok_t, q_tok, lse_q, status [R]."""
+    tau_d = f32(tau_d)
     R = ld_np.shape[0]
     if ref is None:
         ref = oracle_mod.draft_sample(ld_np, tau_d, d2t, u_draft, threads=threads)
@@ -79,6 +85,7 @@ def compare_draft(oracle_mod, ld_np, tau_d, d2t, u_draft, gpu: dict, ref: dict |
 
 def compare_verify(oracle_mod, lt_np, ld_np, tau_t, tau_d, d2t, tok_d, u_acc, u_fin, gpu: dict, threads=16):
     """gpu: dict of host numpy arrays n_accepted, out_tok, accept, p_tok, q_tok, lse_p, status."""
+    tau_t, tau_d = f32(tau_t), f32(tau_d)
     B, K1, Vt = lt_np.shape
     K = K1 - 1
     ref = oracle_mod.verify(lt_np, ld_np, tau_t, tau_d, d2t, tok_d, u_acc, u_fin, threads=threads)
