@@ -31,6 +31,7 @@ constexpr int kWG = 256;
 constexpr int kWaves = kWG / kWave;
 constexpr int kLoads = 4;
 constexpr int kMaxK = 64;
+constexpr int kLdsChunks = 1024;  // chunk-table entries a workgroup may park in LDS
 constexpr double kLn2 = 0.693147180559945309417232121458;
 constexpr double kLog2e = 1.44269504088896340735992468100;
 
@@ -278,7 +279,7 @@ template <int DT, bool MASKED>
 __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, int K, int64_t seq_stride,
                                               int64_t row_stride, int V, int nC, int cps, int nsplit, float cs,
                                               double ratio, const uint64_t* __restrict__ bits,
-                                              Part* __restrict__ part) {
+                                              Part* __restrict__ part, float2* __restrict__ ctab) {
     const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
     const int b = row / K, k = row - b * K;
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
@@ -286,13 +287,28 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const double kd = (ratio - 1.0) * kLn2;
+    __shared__ float2 stash[kLdsChunks];
     Running run;
     scan_chunks<DT, MASKED, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, (float)(ratio - 1.0), bits,
-                                    [&](int, float r, float sc) { run.add(r, sc, kd); });
+                                    [&](int c, float r, float sc) {
+                                        run.add(r, sc, kd);
+                                        // per-chunk pairs are kept too (the residual of a rejected row takes the
+                                        // chunk sums of p from here instead of re-summing the row); parked in LDS
+                                        // so that no global store sits between the streaming loads
+                                        if (ctab && lane == 0) {
+                                            const int i = c - split * cps;
+                                            if (i < kLdsChunks) stash[i] = make_float2(r, sc);
+                                            else ctab[(int64_t)row * nC + c] = make_float2(r, sc);
+                                        }
+                                    });
     __shared__ float sref[kWaves];
     __shared__ double ssum[kWaves];
     if (lane == 0) { sref[wave] = run.ref; ssum[wave] = run.s; }
     __syncthreads();
+    if (ctab) {
+        const int n_here = min(min(nC, (split + 1) * cps) - split * cps, kLdsChunks);
+        for (int i = threadIdx.x; i < n_here; i += kWG) ctab[(int64_t)row * nC + split * cps + i] = stash[i];
+    }
     if (threadIdx.x == 0) {
         float R = sref[0];
         for (int w = 1; w < kWaves; ++w) R = fmaxf(R, sref[w]);
@@ -541,7 +557,6 @@ __global__ __launch_bounds__(kWave) void k_draft_pick(const void* __restrict__ l
 // kernel: one workgroup per drafter row scans it into a chunk table in LDS and samples from it at
 // once (by its first wave), while the other workgroups on the CU keep streaming their rows.
 // grid (R); nC <= kLdsChunks.
-constexpr int kLdsChunks = 1024;
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ logits, int64_t row_stride, int V,
                                                       int nC, float cs, double c_ratio, double inv_temp,
@@ -556,6 +571,32 @@ __global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ lo
     draft_pick_row<DT>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tr, ts, o);
 }
 
+// ---- what the final kernels need to know about a sequence, written once by the accept kernel ----
+struct ResidualParams {
+    float ct_hi, ct_lo, lp_hi, lp_lo;  // target: p = 2^(x*ct - Lp), Lp = lse_p * log2 e
+    float cd_hi, cd_lo, lq_hi, lq_lo;  // drafter: q' = 2^(y*cd - Lq)
+    int use_q;                         // 0: the rejected draft was unusable, q' = 0 everywhere
+};
+struct FinalRow {
+    int skip;       // sequence is flagged NONFINITE
+    int bonus;      // nothing rejected: sample from p of row K
+    int n;          // accepted count = index of the row the extra token comes from
+    ResidualParams rp;
+    double l2p;     // lse_p of row n, in log2 units
+};
+
+__device__ __forceinline__ void split_hi_lo(double v, float& hi, float& lo) {
+    hi = (float)v;
+    lo = (float)(v - (double)hi);
+}
+
+// scale c > 0 as hi + lo with hi < c, so that lo > 0
+__device__ __forceinline__ void split_scale(double c, float& hi, float& lo) {
+    hi = (float)c;
+    if ((double)hi >= c) hi = as_f(as_u(hi) - 1u);
+    lo = (float)(c - (double)hi);
+}
+
 // ---- kernel: accept tests and first-reject scan ------------------------------------------------
 // Standard SD appendix, verification loop and the count of accepted drafts.  grid (B), 64 threads;
 // lane k owns position k.
@@ -568,17 +609,21 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
                                                    int32_t* __restrict__ n_accepted, int32_t* __restrict__ out_tok,
                                                    uint8_t* __restrict__ accept, double* __restrict__ p_tok,
                                                    double* __restrict__ q_tok, double* __restrict__ lse_p,
-                                                   int32_t* __restrict__ seq_status, double* __restrict__ ws_lse_p) {
+                                                   int32_t* __restrict__ seq_status, double* __restrict__ ws_lse_p, double c_t,
+                                                   double c_d, FinalRow* __restrict__ frow) {
     const int b = blockIdx.x, k = threadIdx.x;
     bool acc = true, nonfinite = false, bad = false;
     int tt = -1;
+    double my_lse = 0.0, my_lq = 0.0;
     if (k < K) {
         const int64_t row = (int64_t)b * K + k;
         const double lse = combine_parts(part + row * nsplit, nsplit, ratio_t);
         nonfinite = lse != lse;
+        my_lse = lse;
         ws_lse_p[row] = lse;
         if (lse_p) lse_p[(int64_t)b * (K + 1) + k] = lse;
         const int d = tok_d[row];
+        my_lq = lse_q[row];
         double pd = 0.0, qd = 0.0;
         acc = false;
         if (d < 0 || d >= Vd || d2t[d] < 0) {
@@ -588,7 +633,7 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
             const char* lt = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + k) * Vt * Traits<DT>::ESZ;
             const char* ld = static_cast<const char*>(logits_d) + row * Vd * Traits<DT>::ESZ;
             pd = (lse == -INFINITY) ? 0.0 : exp((double)load_elem<DT>(lt, tt) * inv_temp_t - lse);
-            qd = exp((double)load_elem<DT>(ld, d) * inv_temp_d - lse_q[row]);
+            qd = exp((double)load_elem<DT>(ld, d) * inv_temp_d - my_lq);
             acc = (double)u_acc[row] * qd < pd;
         }
         if (accept) accept[row] = acc ? 1 : 0;
@@ -607,6 +652,30 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
         seq_status[b] = (any_nonfinite ? TLI_FLAG_NONFINITE : 0) | (any_bad ? TLI_FLAG_BAD_DRAFT : 0);
         if (lse_p) lse_p[(int64_t)b * (K + 1) + K] = NAN;
     }
+    // one record per sequence for the final kernels, written by the lane that owns the row they will use
+    const bool residual = !any_nonfinite && n < K;
+    if (residual ? (k == n) : (k == 0)) {
+        FinalRow f;
+        f.skip = any_nonfinite ? 1 : 0;
+        f.bonus = (!any_nonfinite && n == K) ? 1 : 0;
+        f.n = n;
+        f.l2p = 0.0;
+        f.rp.use_q = 0;
+        f.rp.ct_hi = f.rp.ct_lo = f.rp.lp_hi = f.rp.lp_lo = 0.f;
+        f.rp.cd_hi = f.rp.cd_lo = f.rp.lq_hi = f.rp.lq_lo = 0.f;
+        if (residual) {
+            f.l2p = my_lse * kLog2e;
+            split_scale(c_t, f.rp.ct_hi, f.rp.ct_lo);
+            split_hi_lo(f.l2p, f.rp.lp_hi, f.rp.lp_lo);
+            // an unusable draft, or a drafter row without mass, has q' = 0 everywhere
+            if (!bad && (my_lq > -INFINITY || my_lq != my_lq)) {
+                f.rp.use_q = 1;
+                split_scale(c_d, f.rp.cd_hi, f.rp.cd_lo);
+                split_hi_lo(my_lq * kLog2e, f.rp.lq_hi, f.rp.lq_lo);
+            }
+        }
+        frow[b] = f;
+    }
 }
 
 // ---- extra token: weights of one vector of the residual row -----------------------------------
@@ -615,34 +684,12 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
 // p and q' are evaluated as 2^(x*c - L) with c and L split into fp32 hi + lo parts, so both carry
 // about one ulp of error: the difference of two nearly equal probabilities must not inherit the
 // rounding of a large exponent.
-struct ResidualParams {
-    float ct_hi, ct_lo, lp_hi, lp_lo;  // target: exponent = x*ct - Lp
-    float cd_hi, cd_lo, lq_hi, lq_lo;  // drafter
-    bool use_q;
-};
-
 // 2^(x*(c_hi+c_lo) - (l_hi+l_lo)) with one rounding of each partial product.  c_lo is strictly positive
 // (see split_scale), so a -inf logit gives -inf + -inf = -inf (probability 0), never inf - inf.
 __device__ __forceinline__ float exp2_split(float x, float c_hi, float c_lo, float l_hi, float l_lo) {
     return exp2_hw(fmaf(x, c_hi, -l_hi) + fmaf(x, c_lo, -l_lo));
 }
 
-__device__ __forceinline__ void split_hi_lo(double v, float& hi, float& lo) {
-    hi = (float)v;
-    lo = (float)(v - (double)hi);
-}
-
-// scale c > 0 as hi + lo with hi < c, so that lo > 0
-__device__ __forceinline__ void split_scale(double c, float& hi, float& lo) {
-    hi = (float)c;
-    if ((double)hi >= c) hi = as_f(as_u(hi) - 1u);
-    lo = (float)(c - (double)hi);
-}
-
-// Weights of vector vi of the residual row, for the sampler's re-read of one chunk.  All loads are
-// unconditional (indices clamped into range, results masked afterwards) so that the loads of the
-// chunk's four vectors, then their t2d entries, then the drafter logits they point at, each go out
-// as one batch instead of a chain of dependent round trips.
 template <int DT>
 __device__ __forceinline__ void residual_vec(const void* rowp, int64_t vi, int V, const ResidualParams& rp,
                                              const int32_t* __restrict__ t2d, const void* __restrict__ ld_row,
@@ -678,38 +725,6 @@ __device__ __forceinline__ void residual_vec(const void* rowp, int64_t vi, int V
         w[i] = fmaxf(0.f, pi - qi);
         if (!(qi <= 3.0e38f)) w[i] = NAN;  // NaN or +inf in the drafter row must surface (fmaxf would drop it)
     }
-}
-
-struct FinalRow {
-    bool skip;      // sequence is flagged NONFINITE
-    bool bonus;     // nothing rejected: sample from p of row K
-    int n;          // accepted count = index of the row the extra token comes from
-    ResidualParams rp;
-};
-
-template <int DT>
-__device__ __forceinline__ FinalRow final_row(int b, int K, int Vd, const int32_t* n_accepted, const int32_t* seq_status,
-                                     const int32_t* tok_d, const int32_t* d2t, const double* ws_lse_p,
-                                     const double* lse_q, double c_t, double c_d) {
-    FinalRow f;
-    f.skip = (seq_status[b] & TLI_FLAG_NONFINITE) != 0;
-    f.n = n_accepted[b];
-    f.bonus = (f.n == K);
-    f.rp.use_q = false;
-    if (f.skip || f.bonus) return f;
-    const int64_t row = (int64_t)b * K + f.n;
-    split_scale(c_t, f.rp.ct_hi, f.rp.ct_lo);
-    split_hi_lo(ws_lse_p[row] * kLog2e, f.rp.lp_hi, f.rp.lp_lo);
-    const int d = tok_d[row];
-    if (d >= 0 && d < Vd && d2t[d] >= 0) {
-        const double lq = lse_q[row];
-        if (lq > -INFINITY || lq != lq) {  // a zero-mass drafter row has q' = 0 everywhere
-            f.rp.use_q = true;
-            split_scale(c_d, f.rp.cd_hi, f.rp.cd_lo);
-            split_hi_lo(lq * kLog2e, f.rp.lq_hi, f.rp.lq_lo);
-        }
-    }
-    return f;
 }
 
 // ---- extra token of one sequence from the chunk tables of its row ------------------------------
@@ -799,8 +814,8 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
 // Bonus rows (nothing rejected) go through the same grid: the workgroup scans its segment of target row
 // K into a plain (ref, s) softmax table.
 // grid (B rounded up to 8, times nseg), 1024 threads; workgroups of flagged sequences exit at once.
-constexpr int kSegBytes = 128 * 1024;
-constexpr int kSegWG = 1024;
+constexpr int kSegBytes = 32 * 1024;
+constexpr int kSegWG = 512;
 constexpr int kSegWaves = kSegWG / kWave;
 constexpr int kGatherU = 12;
 template <int DT> constexpr int seg_elems() { return kSegBytes / Traits<DT>::ESZ; }
@@ -808,12 +823,9 @@ template <int DT> constexpr int seg_elems() { return kSegBytes / Traits<DT>::ESZ
 template <int DT>
 __global__ __launch_bounds__(kSegWG) void k_final_scan(
     const void* __restrict__ logits_t, const void* __restrict__ logits_d, int B, int K, int Vt, int Vd, int nC,
-    int nseg, float cs_t, double ratio_t, double c_t, double c_d, const int32_t* __restrict__ d2t,
-    const int32_t* __restrict__ seg_start,
-    const int32_t* __restrict__ seg_x, const uint16_t* __restrict__ seg_off, const int32_t* __restrict__ tok_d,
-    const double* __restrict__ lse_q, const int32_t* __restrict__ n_accepted, const int32_t* __restrict__ seq_status,
-    const double* __restrict__ ws_lse_p, float* __restrict__ tab_ref, float* __restrict__ tab_s,
-    float* __restrict__ tab_p) {
+    int nseg, float cs_t, double ratio_t, const FinalRow* __restrict__ frow, const int32_t* __restrict__ seg_start,
+    const int32_t* __restrict__ seg_x, const uint16_t* __restrict__ seg_off, const float2* __restrict__ ctab,
+    float* __restrict__ tab_ref, float* __restrict__ tab_s, float* __restrict__ tab_p) {
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int ESZ = Traits<DT>::ESZ;
     constexpr int G = seg_elems<DT>();
@@ -827,7 +839,7 @@ __global__ __launch_bounds__(kSegWG) void k_final_scan(
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int b = (slot / nseg) * 8 + xcd, sg = slot % nseg;
     if (b >= B) return;
-    const FinalRow f = final_row<DT>(b, K, Vd, n_accepted, seq_status, tok_d, d2t, ws_lse_p, lse_q, c_t, c_d);
+    const FinalRow f = frow[b];
     if (f.skip) return;
     if (f.bonus) {
         const u4v* rowk = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
@@ -842,30 +854,24 @@ __global__ __launch_bounds__(kSegWG) void k_final_scan(
                                           });
         return;
     }
+    // ---- residual row.  Chunk sums of p come from the table the normaliser kernel left for this row:
+    // sum_chunk p = S_c * 2^(R_c * c_true/c - lse_p * log2 e).  What remains is sum_chunk min(p, q') over the
+    // SHARED ids of the chunk, and chunk mass = sum p - sum min(p, q') (= sum max(0, p - q')).
     const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lane = tid & 63;
-    // the target chunks this wave owns do not depend on LDS: get their loads in flight first
-    constexpr int CPW = (kChunksPerSeg + kSegWaves - 1) / kSegWaves;
-    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
-                                                    ((int64_t)b * (K + 1) + f.n) * Vt * ESZ);
-    const int nvec = (Vt + EPV - 1) / EPV;
-    const int n_whole = Vt / CH;
-    ChunkRegs r[CPW];
-#pragma unroll
-    for (int k = 0; k < CPW; ++k) {
-        const int cl = wave + k * kSegWaves;
-        const int c = sg * kChunksPerSeg + cl;
-        if (cl < kChunksPerSeg && c < nC) {
-            if (c < n_whole) load_chunk_whole(rowv, c, lane, r[k]);
-            else load_chunk_tail<DT>(rowv, c, lane, nvec, r[k]);
-        }
-    }
+    __shared__ unsigned long long acc[kChunksPerSeg];  // sum of min(p, q') per chunk, fixed point 2^-44
+    __shared__ int bad;
+    if (tid < kChunksPerSeg) acc[tid] = 0ull;
+    if (tid == 0) bad = 0;
+    float2 rs = make_float2(-INFINITY, 0.f);  // this thread's chunk of the p table: needed last, asked for first
+    if (tid < kChunksPerSeg && sg * kChunksPerSeg + tid < nC)
+        rs = ctab[((int64_t)b * K + f.n) * nC + sg * kChunksPerSeg + tid];
     if (f.rp.use_q) {
         const raw_t* ld_row = reinterpret_cast<const raw_t*>(static_cast<const char*>(logits_d) +
                                                              ((int64_t)b * K + f.n) * Vd * ESZ);
-        // pairs of this segment, kGatherU per thread per batch: list loads, then the drafter-row reads they
-        // address, then (after the fill) the LDS stores -- each stage issued for the whole batch at once
+        const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
+                                                        ((int64_t)b * (K + 1) + f.n) * Vt * ESZ);
+        // (1) pair list of this segment and the drafter logits it points at (kGatherU pairs per thread per
+        //     batch: list loads, then the reads they address, each stage issued for the whole batch at once)
         constexpr int U = kGatherU;
         const int i1 = seg_start[sg + 1];
         int i0 = seg_start[sg] + tid;
@@ -878,19 +884,57 @@ __global__ __launch_bounds__(kSegWG) void k_final_scan(
             xs[k] = i < i1 ? seg_x[i] : -1;
             os[k] = i < i1 ? seg_off[i] : (uint16_t)0;
         }
-        const unsigned int pat = (DT == TLI_BF16) ? 0xff80ff80u : 0xff800000u;
-        u4v* segv = reinterpret_cast<u4v*>(seg);
-        const u4v fill = {pat, pat, pat, pat};
+        // (2) this segment of the target row, streamed once into LDS (vectors past the row end: -inf)
+        {
+            const int nvec = (Vt + EPV - 1) / EPV;
+            const unsigned int pat = (DT == TLI_BF16) ? 0xff80ff80u : 0xff800000u;
+            const u4v ninf = {pat, pat, pat, pat};
+            u4v* segv = reinterpret_cast<u4v*>(seg);
+            constexpr int VPT = kSegBytes / 16 / kSegWG;  // vectors per thread
+            u4v t[VPT];
 #pragma unroll
-        for (int i = 0; i < kSegBytes / 16 / kSegWG; ++i) segv[tid + i * kSegWG] = fill;
-#pragma unroll
-        for (int k = 0; k < U; ++k)
-            if (xs[k] >= 0) ys[k] = ld_row[xs[k]];
-        __syncthreads();
-        while (true) {
+            for (int k = 0; k < VPT; ++k) {
+                const int vi = sg * (G / EPV) + tid + k * kSegWG;
+                t[k] = __builtin_nontemporal_load(rowv + (vi < nvec ? vi : nvec - 1));
+                if (vi >= nvec) t[k] = ninf;
+            }
 #pragma unroll
             for (int k = 0; k < U; ++k)
-                if (xs[k] >= 0) seg[os[k]] = ys[k];
+#ifndef EXP_NOGATHER
+                if (xs[k] >= 0) ys[k] = ld_row[xs[k]];
+#else
+                if (xs[k] >= 0) ys[k] = (raw_t)xs[k];
+#endif
+#pragma unroll
+            for (int k = 0; k < VPT; ++k) segv[tid + k * kSegWG] = t[k];
+        }
+        __syncthreads();
+        // (3) one pair at a time: p from the target logit in LDS, q' from the gathered drafter logit
+        bool my_bad = false;
+        while (true) {
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                if (xs[k] < 0) continue;
+                float xv, yv;
+                if (DT == TLI_BF16) {
+                    xv = as_f((uint32_t)seg[os[k]] << 16);
+                    yv = as_f((uint32_t)ys[k] << 16);
+                } else {
+                    xv = as_f((uint32_t)seg[os[k]]);
+                    yv = as_f((uint32_t)ys[k]);
+                }
+                const float pi = exp2_split(xv, f.rp.ct_hi, f.rp.ct_lo, f.rp.lp_hi, f.rp.lp_lo);
+                const float qi = exp2_split(yv, f.rp.cd_hi, f.rp.cd_lo, f.rp.lq_hi, f.rp.lq_lo);
+                if (!(qi <= 3.0e38f)) my_bad = true;  // NaN or +inf in the drafter row must surface
+                const float mn = fminf(pi, qi);
+                // fixed point makes the chunk sum independent of the order in which lanes arrive
+                const unsigned long long fx = (unsigned long long)((double)mn * 17592186044416.0);
+#ifndef EXP_NOATOMIC
+                atomicAdd(&acc[os[k] / CH], fx);
+#else
+                if (fx == 12345ull) bad = 1;
+#endif
+            }
             i0 += U * kSegWG;
             if (i0 - tid >= i1) break;  // uniform: the batch start of thread 0
 #pragma unroll
@@ -903,61 +947,35 @@ __global__ __launch_bounds__(kSegWG) void k_final_scan(
             for (int k = 0; k < U; ++k)
                 if (xs[k] >= 0) ys[k] = ld_row[xs[k]];
         }
-        __syncthreads();
+        if (my_bad) bad = 1;
     }
-    float* tr = tab_ref + (int64_t)b * nC;
-    float* ts = tab_s + (int64_t)b * nC;
-    float* tp = tab_p + (int64_t)b * nC;
-#pragma unroll
-    for (int k = 0; k < CPW; ++k) {
-        const int cl = wave + k * kSegWaves;
-        const int c = sg * kChunksPerSeg + cl;
-        if (cl >= kChunksPerSeg || c >= nC) break;
-        float sw = 0.f, sp = 0.f, sq = 0.f;
-#pragma unroll
-        for (int j = 0; j < kLoads; ++j) {
-            float x[EPV], y[EPV];
-            unpack<DT>(to_uint4(r[k].v[j]), x);
-            if (f.rp.use_q) {
-                const u4v yv = reinterpret_cast<const u4v*>(seg)[cl * (kWave * kLoads) + j * kWave + lane];
-                unpack<DT>(to_uint4(yv), y);
-            }
-            float a = 0.f, q = 0.f, g = 0.f;
-#pragma unroll
-            for (int i = 0; i < EPV; ++i) {
-                const float pi = exp2_split(x[i], f.rp.ct_hi, f.rp.ct_lo, f.rp.lp_hi, f.rp.lp_lo);
-                float wi = pi;
-                if (f.rp.use_q) {
-                    const float qi = exp2_split(y[i], f.rp.cd_hi, f.rp.cd_lo, f.rp.lq_hi, f.rp.lq_lo);
-                    wi = fmaxf(0.f, pi - qi);
-                    g += qi;
-                }
-                a += wi;
-                q += pi;
-            }
-            sw += a; sp += q; sq += g;
+    __syncthreads();
+    if (tid < kChunksPerSeg) {
+        const int c = sg * kChunksPerSeg + tid;
+        if (c < nC) {
+            const double P = (rs.x == -INFINITY) ? 0.0 : (double)rs.y * exp2((double)rs.x * ratio_t - f.l2p);
+            const double Mn = (double)acc[tid] * (1.0 / 17592186044416.0);
+            double T = P - Mn;
+            if (T < 0.0) T = 0.0;
+            if (bad) T = NAN;
+            tab_ref[(int64_t)b * nC + c] = 0.f;
+            tab_s[(int64_t)b * nC + c] = (float)T;
+            tab_p[(int64_t)b * nC + c] = (float)P;
         }
-        sw = wave_sum(sw);
-        sp = wave_sum(sp);
-        sq = wave_sum(sq);
-        // NaN or +inf among the drafter logits shows in the sum of q' (fmaxf above would drop it)
-        if (!(sq <= 3.0e38f)) sw = NAN;
-        if (lane == 0) { tr[c] = 0.f; ts[c] = sw; tp[c] = sp; }
     }
 }
 
 // kernel: draw the extra token of every sequence from its row's chunk tables.  grid (B), one wave.
 template <int DT>
 __global__ __launch_bounds__(kWave) void k_final_pick(const void* __restrict__ logits_t, const void* __restrict__ logits_d,
-                                                     int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
-                                                     double c_t, double c_d, const int32_t* __restrict__ d2t,
-                                                     const int32_t* __restrict__ t2d, const int32_t* __restrict__ tok_d,
-                                                     const double* __restrict__ lse_q,
-                                                     const double* __restrict__ ws_lse_p,
-                                                     const float* __restrict__ tab_ref, const float* __restrict__ tab_s,
-                                                     const float* __restrict__ tab_p, FinalOut o) {
+                                                       int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
+                                                       const FinalRow* __restrict__ frow,
+                                                       const int32_t* __restrict__ t2d,
+                                                       const float* __restrict__ tab_ref,
+                                                       const float* __restrict__ tab_s,
+                                                       const float* __restrict__ tab_p, FinalOut o) {
     const int b = blockIdx.x;
-    const FinalRow f = final_row<DT>(b, K, Vd, o.n_accepted, o.seq_status, tok_d, d2t, ws_lse_p, lse_q, c_t, c_d);
+    const FinalRow f = frow[b];
     if (f.skip) return;
     final_pick_row<DT>(f, b, logits_t, logits_d, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
                        tab_s + (int64_t)b * nC, tab_p + (int64_t)b * nC, o);
@@ -992,7 +1010,7 @@ Plan make_plan(int V, int rows, int chunk) {
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {  // offsets into the caller's scratch
-    size_t part, part_d, ws_lse_p, ws_lse_q, tab_ref, tab_s, tab_p, total;
+    size_t part, part_d, ws_lse_p, ws_lse_q, ctab, frow, tab_ref, tab_s, tab_p, total;
 };
 
 Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
@@ -1009,6 +1027,8 @@ Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
     w.part_d = off; off += align256((size_t)rows * pd.nsplit * sizeof(Part));
     w.ws_lse_p = off; off += align256((size_t)rows * sizeof(double));
     w.ws_lse_q = off; off += align256((size_t)rows * sizeof(double));
+    w.ctab = off; off += align256((size_t)rows * nCt * sizeof(float2));
+    w.frow = off; off += align256((size_t)B * sizeof(FinalRow));
     w.tab_ref = off; off += align256(tab * sizeof(float));
     w.tab_s = off; off += align256(tab * sizeof(float));
     w.tab_p = off; off += align256(tab_rows_t * sizeof(float));
@@ -1073,6 +1093,8 @@ struct VerifyArgs {
     float cs_d;
     double ratio_d;
     float *tab_ref, *tab_s, *tab_p;
+    float2* ctab;
+    FinalRow* frow;
 };
 template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st);
 
@@ -1130,7 +1152,7 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     if (!lse_q) {  // the caller did not keep the drafter normalisers: one masked scan of the drafter rows
         hipLaunchKernelGGL((k_lse<DT, true>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), 0, st, a.logits_d, K,
                            (int64_t)K * Vd, (int64_t)Vd, Vd, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d, a.ratio_d,
-                           a.map->lmask[DT], a.part_d);
+                           a.map->lmask[DT], a.part_d, (float2*)nullptr);
         hipLaunchKernelGGL(k_lse_finish, dim3((rows + kWG - 1) / kWG), dim3(kWG), 0, st, a.part_d, rows, a.pd.nsplit,
                            a.ratio_d, a.ws_lse_q);
         lse_q = a.ws_lse_q;
@@ -1139,27 +1161,25 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
         KernelTimer t(TLI_KERNEL_LSE, st);
         hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * a.pl.nsplit), dim3(kWG), 0, st, a.logits_t, K,
                            (int64_t)(K + 1) * Vt, (int64_t)Vt, Vt, a.pl.nC, a.pl.cps, a.pl.nsplit, a.cs_t, a.ratio_t,
-                           nullptr, a.part);
+                           nullptr, a.part, a.ctab);
     }
     {
         KernelTimer t(TLI_KERNEL_ACCEPT, st);
         hipLaunchKernelGGL(k_accept<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pl.nsplit,
                            a.part, a.ratio_t, a.inv_t, a.inv_d, a.map->d2t, a.tok_d, lse_q, a.u_acc, a.n_accepted,
-                           a.out_tok, a.accept, a.p_tok, a.q_tok, a.lse_p, a.seq_status, a.ws_lse_p);
+                           a.out_tok, a.accept, a.p_tok, a.q_tok, a.lse_p, a.seq_status, a.ws_lse_p, a.c_t, a.c_d, a.frow);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_SCAN, st);
         const int nseg = a.map->nseg[DT];
         hipLaunchKernelGGL(k_final_scan<DT>, dim3((unsigned)((B + 7) / 8) * 8 * nseg), dim3(kSegWG), 0, st, a.logits_t,
-                           a.logits_d, B, K, Vt, Vd, a.pf.nC, nseg, a.cs_t, a.ratio_t, a.c_t, a.c_d, a.map->d2t,
-                           a.map->seg_start[DT], a.map->seg_x[DT], a.map->seg_off[DT], a.tok_d, lse_q, a.n_accepted,
-                           a.seq_status, a.ws_lse_p, a.tab_ref, a.tab_s, a.tab_p);
+                           a.logits_d, B, K, Vt, Vd, a.pf.nC, nseg, a.cs_t, a.ratio_t, a.frow, a.map->seg_start[DT],
+                           a.map->seg_x[DT], a.map->seg_off[DT], a.ctab, a.tab_ref, a.tab_s, a.tab_p);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
         hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pf.nC,
-                           a.cs_t, a.ratio_t, a.c_t, a.c_d, a.map->d2t, a.map->t2d, a.tok_d, lse_q, a.ws_lse_p,
-                           a.tab_ref, a.tab_s, a.tab_p, fo);
+                           a.cs_t, a.ratio_t, a.frow, a.map->t2d, a.tab_ref, a.tab_s, a.tab_p, fo);
     }
 }
 
@@ -1417,7 +1437,8 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
     a.seq_status = seq_status; a.part = part; a.ws_lse_p = ws_lse_p;
     a.part_d = reinterpret_cast<Part*>(ws + w.part_d); a.ws_lse_q = reinterpret_cast<double*>(ws + w.ws_lse_q);
     a.pd = make_plan(Vd, rows, chunk); a.cs_d = (float)c_d; a.ratio_d = c_d / (double)a.cs_d; a.tab_ref = tab_ref; a.tab_s = tab_s;
-    a.tab_p = tab_p;
+    a.tab_p = tab_p; a.ctab = reinterpret_cast<float2*>(ws + w.ctab);
+    a.frow = reinterpret_cast<FinalRow*>(ws + w.frow);
     if (dtype == TLI_BF16) launch_verify<TLI_BF16>(a, st);
     else launch_verify<TLI_F32>(a, st);
     return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
