@@ -814,8 +814,8 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
 // Bonus rows (nothing rejected) go through the same grid: the workgroup scans its segment of target row
 // K into a plain (ref, s) softmax table.
 // grid (B rounded up to 8, times nseg), 1024 threads; workgroups of flagged sequences exit at once.
-constexpr int kSegBytes = 32 * 1024;
-constexpr int kSegWG = 512;
+constexpr int kSegBytes = 64 * 1024;
+constexpr int kSegWG = 1024;
 constexpr int kSegWaves = kSegWG / kWave;
 constexpr int kGatherU = 12;
 template <int DT> constexpr int seg_elems() { return kSegBytes / Traits<DT>::ESZ; }
