@@ -803,14 +803,17 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
 // Residual rows (first rejection at position n < K): tab_s = chunk sums of max(0, p_n - q'_n), tab_p =
 // chunk sums of p_n (used only if the residual is identically zero), tab_ref = 0.
 //
-// q'_n lives in drafter-id order, the residual is summed in target-id order, and the two orders are
-// unrelated, so reading q' per target id would be one scattered 2-byte access per shared token.
-// Instead a workgroup owns a SEGMENT of kSegBytes/element-size consecutive target ids and first builds
-// that segment's slice of "drafter logit in target order" in LDS: it walks the map's per-segment list
-// of (drafter id, offset in segment) pairs -- sorted by drafter id, so the reads of the drafter row are
-// ascending and nearly coalesced -- and drops each raw logit at its offset (LDS takes scattered 2-byte
-// writes at full rate).  Ids without a partner keep -inf, i.e. q' = 0.  The target segment is then
-// streamed once with 16-byte global loads next to conflict-free 16-byte LDS reads.
+// sum_chunk max(0, p - q') = sum_chunk p - sum_{shared ids of the chunk} min(p, q').  The first sum is
+// already known: the normaliser kernel left the chunk table (ref, s) of every target row, and
+// sum_chunk p = s * 2^(ref * c_true/c - lse_p * log2 e).  Only the second sum is computed here, and it
+// runs over the shared pairs alone (a third of the ids): two exponentials per PAIR instead of two per id.
+// A pair needs a target logit and a drafter logit, and the two vocabularies' orders are unrelated, so
+// one side has to be random access.  A workgroup therefore owns a SEGMENT of kSegBytes/element-size
+// consecutive target ids, streams that slice of the target row into LDS once (coalesced), and walks the
+// map's list of the segment's pairs (drafter id, offset in segment) -- sorted by drafter id, so the reads
+// of the drafter row are ascending and nearly coalesced -- taking the target logit from LDS at random.
+// Chunk sums are accumulated with LDS atomics in 2^-44 fixed point: integer adds commute, so the result
+// does not depend on the order in which lanes arrive (runs are bit-identical).
 // Bonus rows (nothing rejected) go through the same grid: the workgroup scans its segment of target row
 // K into a plain (ref, s) softmax table.
 // grid (B rounded up to 8, times nseg), 1024 threads; workgroups of flagged sequences exit at once.
