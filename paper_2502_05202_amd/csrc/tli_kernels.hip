@@ -92,6 +92,25 @@ __device__ __forceinline__ float wave_max(float v) {
     return as_f(__builtin_amdgcn_readlane(as_u(v), 63));
 }
 
+// the same network for a double: its two halves travel separately (DPP moves 32-bit registers)
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ double dpp_f64(double v) {
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = __builtin_amdgcn_update_dpp(0u, (uint32_t)b, CTRL, ROW_MASK, 0xF, false);
+    const uint32_t hi = __builtin_amdgcn_update_dpp(0u, (uint32_t)(b >> 32), CTRL, ROW_MASK, 0xF, false);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);  // lanes outside ROW_MASK receive +0.0
+}
+__device__ __forceinline__ double wave_sum_f64(double v) {
+    v += dpp_f64<0xB1, 0xF>(v);
+    v += dpp_f64<0x4E, 0xF>(v);
+    v += dpp_f64<0x124, 0xF>(v);
+    v += dpp_f64<0x128, 0xF>(v);
+    v += dpp_f64<0x142, 0xA>(v);
+    v += dpp_f64<0x143, 0xC>(v);
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)b, 63), hi = __builtin_amdgcn_readlane((uint32_t)(b >> 32), 63);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
 __device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---- chunk loads ------------------------------------------------------------------------------
@@ -610,7 +629,7 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
                                                    uint8_t* __restrict__ accept, double* __restrict__ p_tok,
                                                    double* __restrict__ q_tok, double* __restrict__ lse_p,
                                                    int32_t* __restrict__ seq_status, double* __restrict__ ws_lse_p, double c_t,
-                                                   double c_d, FinalRow* __restrict__ frow) {
+                                                   double c_d, FinalRow* __restrict__ frow, int32_t* __restrict__ fbad) {
     const int b = blockIdx.x, k = threadIdx.x;
     bool acc = true, nonfinite = false, bad = false;
     int tt = -1;
@@ -650,6 +669,7 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
         out_tok[(int64_t)b * (K + 1) + K] = -1;
         n_accepted[b] = n;
         seq_status[b] = (any_nonfinite ? TLI_FLAG_NONFINITE : 0) | (any_bad ? TLI_FLAG_BAD_DRAFT : 0);
+        fbad[b] = 0;  // raised by the residual scan if the drafter row it reads holds NaN or +inf
         if (lse_p) lse_p[(int64_t)b * (K + 1) + K] = NAN;
     }
     // one record per sequence for the final kernels, written by the lane that owns the row they will use
@@ -739,8 +759,9 @@ struct FinalOut {
 template <int DT>
 __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const void* logits_t, const void* logits_d,
                                                int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
-                                               const int32_t* t2d, const float* tr, const float* ts, const float* tp,
-                                               const FinalOut& o) {
+                                               const int32_t* t2d, const float* tr, const float* ts,
+                                               const float2* ctab, const double* mn, int nparts, int64_t mn_stride,
+                                               const int32_t* fbad, const FinalOut& o) {
     constexpr int EPV = Traits<DT>::EPV;
     const int lane = threadIdx.x & 63;
     const char* rowp = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + f.n) * Vt * Traits<DT>::ESZ;
@@ -757,17 +778,35 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
         else if (lane == 0 && o.lse_p) o.lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
     } else {
         const char* ldp = static_cast<const char*>(logits_d) + ((int64_t)b * K + f.n) * Vd * Traits<DT>::ESZ;
+        // chunk masses: sum_chunk p (from the normaliser kernel's table of row n) minus the parts' sums of min(p, q')
+        const float2* crow = ctab + ((int64_t)b * K + f.n) * nC;
+        auto p_mass = [&](int cc) {
+            const float2 rs = crow[cc];
+            return (rs.x == -INFINITY) ? 0.0 : (double)rs.y * exp2((double)rs.x * ratio_t - f.l2p);
+        };
+        auto r_mass = [&](int cc) {
+            double m = 0.0;
+            if (f.rp.use_q)
+                for (int pp = 0; pp < nparts; ++pp) m += mn[pp * mn_stride + cc];
+            const double t = p_mass(cc) - m;
+            return t > 0.0 ? t : (t != t ? t : 0.0);
+        };
         double theta_local, total;
-        int c = find_chunk(nC, u, [&](int cc) { return (double)ts[cc]; }, &theta_local, &total);
+        int c = -1;
         bool degenerate = false;
-        if (c < 0) {
-            if (total != total) {
-                nonfinite = true;
-            } else {  // residual identically zero: fall back to p of the same row
-                degenerate = true;
-                add_flags |= TLI_FLAG_DEGENERATE;
-                c = find_chunk(nC, u, [&](int cc) { return (double)tp[cc]; }, &theta_local, &total);
-                if (c < 0) nonfinite = true;
+        if (f.rp.use_q && fbad[b]) {  // NaN or +inf among the shared drafter logits of row n
+            nonfinite = true;
+        } else {
+            c = find_chunk(nC, u, r_mass, &theta_local, &total);
+            if (c < 0) {
+                if (total != total) {
+                    nonfinite = true;
+                } else {  // residual identically zero: fall back to p of the same row
+                    degenerate = true;
+                    add_flags |= TLI_FLAG_DEGENERATE;
+                    c = find_chunk(nC, u, p_mass, &theta_local, &total);
+                    if (c < 0) nonfinite = true;
+                }
             }
         }
         if (!nonfinite) {
@@ -799,173 +838,186 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
     }
 }
 
-// ---- kernels: chunk tables of the row the extra token is drawn from ----------------------------
-// Residual rows (first rejection at position n < K): tab_s = chunk sums of max(0, p_n - q'_n), tab_p =
-// chunk sums of p_n (used only if the residual is identically zero), tab_ref = 0.
-//
-// sum_chunk max(0, p - q') = sum_chunk p - sum_{shared ids of the chunk} min(p, q').  The first sum is
-// already known: the normaliser kernel left the chunk table (ref, s) of every target row, and
-// sum_chunk p = s * 2^(ref * c_true/c - lse_p * log2 e).  Only the second sum is computed here, and it
-// runs over the shared pairs alone (a third of the ids): two exponentials per PAIR instead of two per id.
-// A pair needs a target logit and a drafter logit, and the two vocabularies' orders are unrelated, so
-// one side has to be random access.  A workgroup therefore owns a SEGMENT of kSegBytes/element-size
-// consecutive target ids, streams that slice of the target row into LDS once (coalesced), and walks the
-// map's list of the segment's pairs (drafter id, offset in segment) -- sorted by drafter id, so the reads
-// of the drafter row are ascending and nearly coalesced -- taking the target logit from LDS at random.
-// Chunk sums are accumulated with LDS atomics in 2^-44 fixed point: integer adds commute, so the result
-// does not depend on the order in which lanes arrive (runs are bit-identical).
-// Bonus rows (nothing rejected) go through the same grid: the workgroup scans its segment of target row
-// K into a plain (ref, s) softmax table.
-// grid (B rounded up to 8, times nseg), 1024 threads; workgroups of flagged sequences exit at once.
-constexpr int kSegBytes = 64 * 1024;
-constexpr int kSegWG = 1024;
-constexpr int kSegWaves = kSegWG / kWave;
-constexpr int kGatherU = 12;
-template <int DT> constexpr int seg_elems() { return kSegBytes / Traits<DT>::ESZ; }
+// ---- kernel: chunk masses of the row the extra token is drawn from ------------------------------
+// Residual rows (first rejection at position n < K).  The extra token is drawn from
+// r(t) ∝ max(0, p_n(t) - q'_n(t)), and per chunk of target ids
+//     sum_chunk max(0, p - q') = sum_chunk p - sum_{shared ids of the chunk} min(p, q').
+// The first sum is known: the normaliser kernel left the chunk table (ref, s) of every target row, and
+// sum_chunk p = s * 2^(ref * c_true/c - lse_p * log2 e).  Only the second sum is computed here; it runs over
+// the shared PAIRS (target id, drafter id) alone.  The two vocabularies' orders are unrelated, so a pair
+// needs one random access on each side -- and random access is cheap only in LDS.  A workgroup therefore
+// keeps a PART of the drafter row resident in LDS: the logits of up to part_cap shared drafter ids,
+// compacted in rank order (rank = position among the shared ids, ascending drafter id; gathered once
+// through the map's rank -> drafter id list, nearly coalesced).  Its 16 waves then stream target chunks
+// past it: a wave parks a chunk in its private LDS slot and walks the map's list of the pairs that fall
+// into (this part, this chunk), each entry = (byte offset in chunk, byte offset in part), reading both
+// logits from LDS.  Every pair is owned by one lane of one wave and sums are per-lane, then fp64 across
+// lanes, so results do not depend on timing.
+// Output: mn[part][b][chunk] = the part's share of sum min(p, q'); the draw kernel forms the masses.
+// The loop is deliberately NOT unrolled into a multi-chunk register pipeline: the kernel runs for tens of
+// microseconds, every instruction is executed a handful of times, and cold instruction fetch of a larger
+// body cost more than the latency it hid (measured: one chunk in flight per wave 66 us, three 76 us).
+// Bonus rows (nothing rejected) go through the same grid: the workgroups of a sequence split target row K
+// and scan it into a plain (ref, s) softmax table.
+// grid (B rounded up to 8) x nparts x nsplit, 1024 threads; workgroups of flagged sequences exit at once.
+// nsplit > 1 (few sequences): the chunks of one (sequence, part) are dealt to nsplit workgroups, each with
+// its own copy of the part.
+constexpr int kScanWG = 1024;
+constexpr int kScanWaves = kScanWG / kWave;
+constexpr int kPartBytes = 92 * 1024;  // + one 4 KB chunk slot per wave = 156 KB of the CU's 160 KB
+constexpr int kPairU = 8;              // list entries per lane fetched with a chunk (512 pairs; more: late loop)
+constexpr int kStageU = 8;
+constexpr int kWaitVm0 = 0x0F70;       // s_waitcnt vmcnt(0) alone (expcnt and lgkmcnt fields at their maximum)
+constexpr int kPairShift = 12;         // entry = byte offset in chunk (< 4096) | byte offset in part << 12
+template <int DT> constexpr int part_cap() { return kPartBytes / Traits<DT>::ESZ; }
 
 template <int DT>
-__global__ __launch_bounds__(kSegWG) void k_final_scan(
+__global__ __launch_bounds__(kScanWG) void k_final_scan(
     const void* __restrict__ logits_t, const void* __restrict__ logits_d, int B, int K, int Vt, int Vd, int nC,
-    int nseg, float cs_t, double ratio_t, const FinalRow* __restrict__ frow, const int32_t* __restrict__ seg_start,
-    const int32_t* __restrict__ seg_x, const uint16_t* __restrict__ seg_off, const float2* __restrict__ ctab,
-    float* __restrict__ tab_ref, float* __restrict__ tab_s, float* __restrict__ tab_p) {
+    int nparts, int nsplit, int per, int S, float cs_t, double ratio_t, const FinalRow* __restrict__ frow,
+    const int32_t* __restrict__ sh_x, const int32_t* __restrict__ pl_start, const uint32_t* __restrict__ pl_e,
+    float* __restrict__ tab_ref, float* __restrict__ tab_s, double* __restrict__ mn, int32_t* __restrict__ fbad) {
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int ESZ = Traits<DT>::ESZ;
-    constexpr int G = seg_elems<DT>();
     constexpr int CH = chunk_elems<DT>();
-    constexpr int kChunksPerSeg = G / CH;
     typedef typename std::conditional<DT == TLI_BF16, uint16_t, uint32_t>::type raw_t;
-    __shared__ __attribute__((aligned(16))) raw_t seg[G];
-    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  The segments of one row all
-    // read that row's drafter logits, so they are given ids that land on the same XCD, next to each other
-    // in time: id = slot * 8 + xcd, row = (slot / nseg) * 8 + xcd, segment = slot % nseg.
+    __shared__ __attribute__((aligned(16))) raw_t dpart[part_cap<DT>()];
+    __shared__ __attribute__((aligned(16))) raw_t tstage[kScanWaves][CH];
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  The workgroups of one sequence
+    // stream the same rows, so they are given ids that land on the same XCD, next to each other in time:
+    // id = slot * 8 + xcd, sequence = (slot / per_seq) * 8 + xcd, (part, split) = slot % per_seq.
+    const int per_seq = nparts * nsplit;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int b = (slot / nseg) * 8 + xcd, sg = slot % nseg;
+    const int b = (slot / per_seq) * 8 + xcd, sub = slot % per_seq;
+    const int p = sub / nsplit, sp = sub - p * nsplit;
     if (b >= B) return;
     const FinalRow f = frow[b];
     if (f.skip) return;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
     if (f.bonus) {
         const u4v* rowk = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
                                                         ((int64_t)b * (K + 1) + K) * Vt * ESZ);
         float* br = tab_ref + (int64_t)b * nC;
         float* bs = tab_s + (int64_t)b * nC;
-        const int lane0 = threadIdx.x & 63;
-        scan_chunks<DT, false, kSegWaves>(rowk, Vt, sg * kChunksPerSeg, min(nC, (sg + 1) * kChunksPerSeg), cs_t,
-                                          (float)(ratio_t - 1.0), nullptr,
-                                          [&](int c, float r, float sc) {
-                                              if (lane0 == 0) { br[c] = r; bs[c] = sc; }
-                                          });
+        const int cps = (nC + per_seq - 1) / per_seq;
+        scan_chunks<DT, false, kScanWaves>(rowk, Vt, min(nC, sub * cps), min(nC, (sub + 1) * cps), cs_t,
+                                           (float)(ratio_t - 1.0), nullptr, [&](int c, float r, float sc) {
+                                               if (lane == 0) { br[c] = r; bs[c] = sc; }
+                                           });
         return;
     }
-    // ---- residual row.  Chunk sums of p come from the table the normaliser kernel left for this row:
-    // sum_chunk p = S_c * 2^(R_c * c_true/c - lse_p * log2 e).  What remains is sum_chunk min(p, q') over the
-    // SHARED ids of the chunk, and chunk mass = sum p - sum min(p, q') (= sum max(0, p - q')).
-    const int tid = threadIdx.x;
-    __shared__ unsigned long long acc[kChunksPerSeg];  // sum of min(p, q') per chunk, fixed point 2^-44
-    __shared__ int bad;
-    if (tid < kChunksPerSeg) acc[tid] = 0ull;
-    if (tid == 0) bad = 0;
-    float2 rs = make_float2(-INFINITY, 0.f);  // this thread's chunk of the p table: needed last, asked for first
-    if (tid < kChunksPerSeg && sg * kChunksPerSeg + tid < nC)
-        rs = ctab[((int64_t)b * K + f.n) * nC + sg * kChunksPerSeg + tid];
-    if (f.rp.use_q) {
-        const raw_t* ld_row = reinterpret_cast<const raw_t*>(static_cast<const char*>(logits_d) +
-                                                             ((int64_t)b * K + f.n) * Vd * ESZ);
-        const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
-                                                        ((int64_t)b * (K + 1) + f.n) * Vt * ESZ);
-        // (1) pair list of this segment and the drafter logits it points at (kGatherU pairs per thread per
-        //     batch: list loads, then the reads they address, each stage issued for the whole batch at once)
-        constexpr int U = kGatherU;
-        const int i1 = seg_start[sg + 1];
-        int i0 = seg_start[sg] + tid;
-        int32_t xs[U];
-        uint16_t os[U];
-        raw_t ys[U];
-#pragma unroll
-        for (int k = 0; k < U; ++k) {
-            const int i = i0 + k * kSegWG;
-            xs[k] = i < i1 ? seg_x[i] : -1;
-            os[k] = i < i1 ? seg_off[i] : (uint16_t)0;
-        }
-        // (2) this segment of the target row, streamed once into LDS (vectors past the row end: -inf)
-        {
-            const int nvec = (Vt + EPV - 1) / EPV;
-            const unsigned int pat = (DT == TLI_BF16) ? 0xff80ff80u : 0xff800000u;
-            const u4v ninf = {pat, pat, pat, pat};
-            u4v* segv = reinterpret_cast<u4v*>(seg);
-            constexpr int VPT = kSegBytes / 16 / kSegWG;  // vectors per thread
-            u4v t[VPT];
-#pragma unroll
-            for (int k = 0; k < VPT; ++k) {
-                const int vi = sg * (G / EPV) + tid + k * kSegWG;
-                t[k] = __builtin_nontemporal_load(rowv + (vi < nvec ? vi : nvec - 1));
-                if (vi >= nvec) t[k] = ninf;
-            }
-#pragma unroll
-            for (int k = 0; k < U; ++k)
-#ifndef EXP_NOGATHER
-                if (xs[k] >= 0) ys[k] = ld_row[xs[k]];
-#else
-                if (xs[k] >= 0) ys[k] = (raw_t)xs[k];
-#endif
-#pragma unroll
-            for (int k = 0; k < VPT; ++k) segv[tid + k * kSegWG] = t[k];
-        }
-        __syncthreads();
-        // (3) one pair at a time: p from the target logit in LDS, q' from the gathered drafter logit
+    if (!f.rp.use_q) return;  // q' = 0 everywhere: the masses are the chunk sums of p, nothing to subtract
+    const raw_t* ld_row =
+        reinterpret_cast<const raw_t*>(static_cast<const char*>(logits_d) + ((int64_t)b * K + f.n) * Vd * ESZ);
+    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
+                                                    ((int64_t)b * (K + 1) + f.n) * Vt * ESZ);
+    const int nvec = (Vt + EPV - 1) / EPV;
+    const int32_t* my_start = pl_start + (int64_t)p * nC;
+
+    // ---- (1) this part of the drafter row -> LDS, compacted to the shared ids (rank order).  Loads are
+    // unconditional (indices clamped into range, validity re-derived from the index when the data is used):
+    // a load under a branch makes the compiler wait for ALL outstanding loads at every use.
+    {
+        const int r0 = p * per, r1 = min(S, r0 + per);
         bool my_bad = false;
-        while (true) {
+        int32_t xs[kStageU], xn[kStageU];
 #pragma unroll
-            for (int k = 0; k < U; ++k) {
-                if (xs[k] < 0) continue;
-                float xv, yv;
-                if (DT == TLI_BF16) {
-                    xv = as_f((uint32_t)seg[os[k]] << 16);
-                    yv = as_f((uint32_t)ys[k] << 16);
-                } else {
-                    xv = as_f((uint32_t)seg[os[k]]);
-                    yv = as_f((uint32_t)ys[k]);
+        for (int k = 0; k < kStageU; ++k) xs[k] = sh_x[min(r0 + tid + k * kScanWG, S - 1)];
+        for (int base = r0; base < r1; base += kStageU * kScanWG) {  // uniform bounds
+            raw_t ys[kStageU];
+#pragma unroll
+            for (int k = 0; k < kStageU; ++k) ys[k] = ld_row[xs[k]];
+#pragma unroll
+            for (int k = 0; k < kStageU; ++k)  // the next batch's ranks travel while the gathers are out
+                xn[k] = sh_x[min(base + kStageU * kScanWG + tid + k * kScanWG, S - 1)];
+#pragma unroll
+            for (int k = 0; k < kStageU; ++k) {
+                const int i = base + tid + k * kScanWG;
+                if (i < r1) {
+                    dpart[i - r0] = ys[k];
+                    // NaN or +inf in a shared drafter logit must surface
+                    const uint32_t em = (DT == TLI_BF16) ? 0x7f80u : 0x7f800000u;
+                    const uint32_t ninf = (DT == TLI_BF16) ? 0xff80u : 0xff800000u;
+                    if (((uint32_t)ys[k] & em) == em && (uint32_t)ys[k] != ninf) my_bad = true;
                 }
-                const float pi = exp2_split(xv, f.rp.ct_hi, f.rp.ct_lo, f.rp.lp_hi, f.rp.lp_lo);
-                const float qi = exp2_split(yv, f.rp.cd_hi, f.rp.cd_lo, f.rp.lq_hi, f.rp.lq_lo);
-                if (!(qi <= 3.0e38f)) my_bad = true;  // NaN or +inf in the drafter row must surface
-                const float mn = fminf(pi, qi);
-                // fixed point makes the chunk sum independent of the order in which lanes arrive
-                const unsigned long long fx = (unsigned long long)((double)mn * 17592186044416.0);
-#ifndef EXP_NOATOMIC
-                atomicAdd(&acc[os[k] / CH], fx);
-#else
-                if (fx == 12345ull) bad = 1;
-#endif
+                xs[k] = xn[k];
             }
-            i0 += U * kSegWG;
-            if (i0 - tid >= i1) break;  // uniform: the batch start of thread 0
-#pragma unroll
-            for (int k = 0; k < U; ++k) {
-                const int i = i0 + k * kSegWG;
-                xs[k] = i < i1 ? seg_x[i] : -1;
-                os[k] = i < i1 ? seg_off[i] : (uint16_t)0;
-            }
-#pragma unroll
-            for (int k = 0; k < U; ++k)
-                if (xs[k] >= 0) ys[k] = ld_row[xs[k]];
         }
-        if (my_bad) bad = 1;
+        if (my_bad) fbad[b] = 1;
     }
     __syncthreads();
-    if (tid < kChunksPerSeg) {
-        const int c = sg * kChunksPerSeg + tid;
-        if (c < nC) {
-            const double P = (rs.x == -INFINITY) ? 0.0 : (double)rs.y * exp2((double)rs.x * ratio_t - f.l2p);
-            const double Mn = (double)acc[tid] * (1.0 / 17592186044416.0);
-            double T = P - Mn;
-            if (T < 0.0) T = 0.0;
-            if (bad) T = NAN;
-            tab_ref[(int64_t)b * nC + c] = 0.f;
-            tab_s[(int64_t)b * nC + c] = (float)T;
-            tab_p[(int64_t)b * nC + c] = (float)P;
+
+    // ---- (2) stream target chunks past it: this wave takes chunks gw, gw + stride, ...
+    double* my_mn = mn + ((int64_t)p * B + b) * nC;
+    const ResidualParams rp = f.rp;
+    const char* tslot = reinterpret_cast<const char*>(tstage[wave]);
+    const char* dbase = reinterpret_cast<const char*>(dpart);
+    // min(p, q') of one pair = 2^min(log2 p, log2 q'): one exponential per pair.  An entry read through a
+    // clamped index is some other valid pair (in-range offsets); the caller drops its value.
+    auto pair_min = [&](uint32_t e) -> float {
+        const uint32_t xr = *reinterpret_cast<const raw_t*>(tslot + (e & ((1u << kPairShift) - 1u)));
+        const uint32_t yr = *reinterpret_cast<const raw_t*>(dbase + (e >> kPairShift));
+        const float xv = as_f(DT == TLI_BF16 ? xr << 16 : xr), yv = as_f(DT == TLI_BF16 ? yr << 16 : yr);
+        const float a = fmaf(xv, rp.ct_hi, -rp.lp_hi) + fmaf(xv, rp.ct_lo, -rp.lp_lo);
+        const float bq = fmaf(yv, rp.cd_hi, -rp.lq_hi) + fmaf(yv, rp.cd_lo, -rp.lq_lo);
+        return exp2_hw(fminf(a, bq));
+    };
+    const int gw = sp * kScanWaves + wave, stride = nsplit * kScanWaves;
+    // Results stay in registers until the wave is through (lane i keeps the sum of the wave's i-th chunk):
+    // a store shares the loads' completion counter and completes out of order with them, so while one may
+    // be pending every wait for a load degrades to a wait for all loads.
+    double keep = 0.0;
+    int it = 0;
+    auto flush = [&](int first_it, int n) {
+        const int c = gw + (first_it + lane) * stride;
+        if (lane < n && c < nC) my_mn[c] = keep;
+    };
+    int ns0 = 0, ns1 = 0;  // list bounds of the next chunk, fetched one chunk ahead
+    if (gw < nC) { ns0 = my_start[gw]; ns1 = my_start[gw + 1]; }
+    for (int c = gw; c < nC; c += stride) {
+        const int s0 = ns0, s1 = ns1;
+        {
+            const int cn = min(c + stride, nC - 1);
+            ns0 = my_start[cn]; ns1 = my_start[cn + 1];
         }
+        u4v v[kLoads];
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j)  // vectors past the row's end re-read its last vector: no pair points there
+            v[j] = rowv[min((c * kLoads + j) * kWave + lane, nvec - 1)];
+        uint32_t e[kPairU];
+#pragma unroll
+        for (int k = 0; k < kPairU; ++k) e[k] = pl_e[min(s0 + k * kWave + lane, S - 1)];
+        u4v* st = reinterpret_cast<u4v*>(tstage[wave]);
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) st[j * kWave + lane] = v[j];
+        // one wave writes and reads its slot: its LDS operations execute in order and the compiler keeps
+        // may-alias accesses in program order; the wave barrier only pins the schedule
+        __builtin_amdgcn_wave_barrier();
+        float m[kPairU];
+#pragma unroll
+        for (int k = 0; k < kPairU; ++k) {
+            const float t = pair_min(e[k]);
+            m[k] = (s0 + k * kWave + lane < s1) ? t : 0.f;
+        }
+#pragma unroll
+        for (int w = 1; w < kPairU; w <<= 1)  // the lane's few terms: pairwise in fp32, everything after in fp64
+#pragma unroll
+            for (int k = 0; k + w < kPairU; k += 2 * w) m[k] += m[k + w];
+        double acc = (double)m[0];
+        for (int i0 = s0 + kPairU * kWave; i0 < s1; i0 += kWave) {  // crowded chunk: the rest of its list
+            const int i = i0 + lane;
+            const float t = pair_min(pl_e[min(i, S - 1)]);
+            acc += (double)(i < s1 ? t : 0.f);
+        }
+        __builtin_amdgcn_wave_barrier();  // the slot is rewritten by the next chunk
+        acc = wave_sum_f64(acc);
+        if (lane == (it & (kWave - 1))) keep = acc;
+        ++it;
+        if ((it & (kWave - 1)) == 0) flush(it - kWave, kWave);  // only rows of more than 1024 chunks get here
     }
+    flush(it & ~(kWave - 1), it & (kWave - 1));
 }
 
 // kernel: draw the extra token of every sequence from its row's chunk tables.  grid (B), one wave.
@@ -976,12 +1028,14 @@ __global__ __launch_bounds__(kWave) void k_final_pick(const void* __restrict__ l
                                                        const int32_t* __restrict__ t2d,
                                                        const float* __restrict__ tab_ref,
                                                        const float* __restrict__ tab_s,
-                                                       const float* __restrict__ tab_p, FinalOut o) {
+                                                       const float2* __restrict__ ctab,
+                                                       const double* __restrict__ mn, int nparts, int B,
+                                                       const int32_t* __restrict__ fbad, FinalOut o) {
     const int b = blockIdx.x;
     const FinalRow f = frow[b];
     if (f.skip) return;
     final_pick_row<DT>(f, b, logits_t, logits_d, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
-                       tab_s + (int64_t)b * nC, tab_p + (int64_t)b * nC, o);
+                       tab_s + (int64_t)b * nC, ctab, mn + (int64_t)b * nC, nparts, (int64_t)B * nC, fbad, o);
 }
 
 // ---- plain copy, used only to calibrate hardware byte counters against a known size -----------
@@ -1013,7 +1067,7 @@ Plan make_plan(int V, int rows, int chunk) {
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {  // offsets into the caller's scratch
-    size_t part, part_d, ws_lse_p, ws_lse_q, ctab, frow, tab_ref, tab_s, tab_p, total;
+    size_t part, part_d, ws_lse_p, ws_lse_q, ctab, frow, fbad, tab_ref, tab_s, mn, total;
 };
 
 Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
@@ -1032,9 +1086,13 @@ Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
     w.ws_lse_q = off; off += align256((size_t)rows * sizeof(double));
     w.ctab = off; off += align256((size_t)rows * nCt * sizeof(float2));
     w.frow = off; off += align256((size_t)B * sizeof(FinalRow));
+    w.fbad = off; off += align256((size_t)B * sizeof(int32_t));
     w.tab_ref = off; off += align256(tab * sizeof(float));
     w.tab_s = off; off += align256(tab * sizeof(float));
-    w.tab_p = off; off += align256(tab_rows_t * sizeof(float));
+    // the residual scan's partial sums: one table per LDS-sized part of the shared ids (at most min(Vd, Vt) ids)
+    const int cap = dtype == TLI_BF16 ? part_cap<TLI_BF16>() : part_cap<TLI_F32>();
+    const int max_parts = ((Vd < Vt ? Vd : Vt) + cap - 1) / cap;
+    w.mn = off; off += align256((size_t)max_parts * tab_rows_t * sizeof(double));
     w.total = off;
     return w;
 }
@@ -1095,9 +1153,11 @@ struct VerifyArgs {
     Plan pd;
     float cs_d;
     double ratio_d;
-    float *tab_ref, *tab_s, *tab_p;
+    float *tab_ref, *tab_s;
+    double* mn;
     float2* ctab;
     FinalRow* frow;
+    int32_t* fbad;
 };
 template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st);
 
@@ -1109,13 +1169,14 @@ struct tli_map {
     int32_t* d2t;    // dev [Vd padded to 8]
     int32_t* t2d;    // dev [Vt padded to 8]
     uint64_t* lmask[2];  // dev, per dtype: shared-id mask of the drafter vocabulary in lane-mask layout
-    // Per dtype (index = tli_dtype): shared pairs bucketed by target segment (seg_elems<dtype>() target ids
-    // each), drafter ids ascending inside a bucket.  seg_start [nseg+1], seg_x [S] drafter id, seg_off [S]
-    // offset of the partner target id inside its segment.
-    int32_t nseg[2];
-    int32_t* seg_start[2];
-    int32_t* seg_x[2];
-    uint16_t* seg_off[2];
+    int32_t* sh_x;   // dev [S]: drafter id of the shared token of rank r (ranks ascend with the drafter id)
+    // Per dtype (index = tli_dtype), for the residual scan: the ranks are cut into nparts parts of `per`
+    // ranks (what one workgroup keeps in LDS); the shared pairs are grouped by (part, target chunk), ranks
+    // ascending inside a group.  pl_start [nparts * nC + 1]; pl_e [S]: offset of the target id in its
+    // chunk | (rank - part * per) << kPairShift.
+    int32_t nparts[2], per[2];
+    int32_t* pl_start[2];
+    uint32_t* pl_e[2];
 };
 
 namespace {
@@ -1170,19 +1231,25 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
         KernelTimer t(TLI_KERNEL_ACCEPT, st);
         hipLaunchKernelGGL(k_accept<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pl.nsplit,
                            a.part, a.ratio_t, a.inv_t, a.inv_d, a.map->d2t, a.tok_d, lse_q, a.u_acc, a.n_accepted,
-                           a.out_tok, a.accept, a.p_tok, a.q_tok, a.lse_p, a.seq_status, a.ws_lse_p, a.c_t, a.c_d, a.frow);
+                           a.out_tok, a.accept, a.p_tok, a.q_tok, a.lse_p, a.seq_status, a.ws_lse_p, a.c_t, a.c_d, a.frow,
+                           a.fbad);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_SCAN, st);
-        const int nseg = a.map->nseg[DT];
-        hipLaunchKernelGGL(k_final_scan<DT>, dim3((unsigned)((B + 7) / 8) * 8 * nseg), dim3(kSegWG), 0, st, a.logits_t,
-                           a.logits_d, B, K, Vt, Vd, a.pf.nC, nseg, a.cs_t, a.ratio_t, a.frow, a.map->seg_start[DT],
-                           a.map->seg_x[DT], a.map->seg_off[DT], a.ctab, a.tab_ref, a.tab_s, a.tab_p);
+        const int nparts = a.map->nparts[DT];
+        // few sequences: deal the chunks of a (sequence, part) to several workgroups, up to one per CU
+        int nsplit = 256 / (B * nparts);
+        nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
+        hipLaunchKernelGGL(k_final_scan<DT>, dim3((unsigned)((B + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0, st,
+                           a.logits_t, a.logits_d, B, K, Vt, Vd, a.pf.nC, nparts, nsplit, a.map->per[DT], a.map->S,
+                           a.cs_t, a.ratio_t, a.frow, a.map->sh_x, a.map->pl_start[DT], a.map->pl_e[DT], a.tab_ref,
+                           a.tab_s, a.mn, a.fbad);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
         hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pf.nC,
-                           a.cs_t, a.ratio_t, a.frow, a.map->t2d, a.tab_ref, a.tab_s, a.tab_p, fo);
+                           a.cs_t, a.ratio_t, a.frow, a.map->t2d, a.tab_ref, a.tab_s, a.ctab, a.mn,
+                           a.map->nparts[DT], B, a.fbad, fo);
     }
 }
 
@@ -1271,26 +1338,34 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
         ++S;
     }
     if (S == 0) return TLI_ERR_EMPTY_INTERSECTION;
-    // shared pairs bucketed by target segment, drafter ids ascending inside a bucket (one set per dtype)
-    std::vector<int32_t> seg_start[2], seg_x[2];
-    std::vector<uint16_t> seg_off[2];
-    int nseg[2];
-    for (int dt = 0; dt < 2; ++dt) {
-        const int G = dt == TLI_BF16 ? seg_elems<TLI_BF16>() : seg_elems<TLI_F32>();
-        nseg[dt] = (Vt + G - 1) / G;
-        seg_start[dt].assign(nseg[dt] + 1, 0);
-        seg_x[dt].resize(S);
-        seg_off[dt].resize(S);
+    // rank -> drafter id, and per dtype the pair lists of the residual scan (see tli_map)
+    std::vector<int32_t> sh_x(S);
+    {
+        int32_t r = 0;
         for (int32_t x = 0; x < Vd; ++x)
-            if (d2t[x] >= 0) ++seg_start[dt][d2t[x] / G + 1];
-        for (int g = 0; g < nseg[dt]; ++g) seg_start[dt][g + 1] += seg_start[dt][g];
-        std::vector<int32_t> fill(seg_start[dt].begin(), seg_start[dt].end() - 1);
-        for (int32_t x = 0; x < Vd; ++x) {
-            if (d2t[x] < 0) continue;
-            const int g = d2t[x] / G;
-            seg_x[dt][fill[g]] = x;
-            seg_off[dt][fill[g]] = (uint16_t)(d2t[x] - g * G);
-            ++fill[g];
+            if (d2t[x] >= 0) sh_x[r++] = x;
+    }
+    std::vector<int32_t> pl_start[2];
+    std::vector<uint32_t> pl_e[2];
+    int nparts[2], per[2];
+    for (int dt = 0; dt < 2; ++dt) {
+        const int CH = dt == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
+        const int cap = dt == TLI_BF16 ? part_cap<TLI_BF16>() : part_cap<TLI_F32>();
+        const int esz = dt == TLI_BF16 ? 2 : 4;
+        const int nC = (Vt + CH - 1) / CH;
+        nparts[dt] = (S + cap - 1) / cap;
+        per[dt] = (S + nparts[dt] - 1) / nparts[dt];
+        const size_t ngroups = (size_t)nparts[dt] * nC;
+        pl_start[dt].assign(ngroups + 1, 0);
+        pl_e[dt].resize(S);
+        for (int32_t r = 0; r < S; ++r) ++pl_start[dt][(size_t)(r / per[dt]) * nC + d2t[sh_x[r]] / CH + 1];
+        for (size_t g = 0; g < ngroups; ++g) pl_start[dt][g + 1] += pl_start[dt][g];
+        std::vector<int32_t> fill(pl_start[dt].begin(), pl_start[dt].end() - 1);
+        for (int32_t r = 0; r < S; ++r) {
+            const int32_t t = d2t[sh_x[r]];
+            const int part = r / per[dt];
+            pl_e[dt][fill[(size_t)part * nC + t / CH]++] =
+                (uint32_t)((t % CH) * esz) | ((uint32_t)((r - part * per[dt]) * esz) << kPairShift);
         }
     }
     // shared-id mask of the drafter vocabulary in lane-mask layout (see mask_bits), padded to whole chunks
@@ -1309,8 +1384,9 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
     tli_map* m = new (std::nothrow) tli_map();
     if (!m) return TLI_ERR_ALLOC;
     m->Vd = Vd; m->Vt = Vt; m->S = S; m->d2t = nullptr; m->t2d = nullptr; m->lmask[0] = m->lmask[1] = nullptr;
+    m->sh_x = nullptr;
     for (int dt = 0; dt < 2; ++dt) {
-        m->nseg[dt] = nseg[dt]; m->seg_start[dt] = nullptr; m->seg_x[dt] = nullptr; m->seg_off[dt] = nullptr;
+        m->nparts[dt] = nparts[dt]; m->per[dt] = per[dt]; m->pl_start[dt] = nullptr; m->pl_e[dt] = nullptr;
     }
     if (hipGetDevice(&m->device) != hipSuccess) { delete m; return TLI_ERR_HIP; }
     bool ok = hipMalloc(&m->d2t, d2t.size() * 4) == hipSuccess && hipMalloc(&m->t2d, t2d.size() * 4) == hipSuccess &&
@@ -1322,15 +1398,18 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
          hipMemcpy(m->lmask[0], lmask[0].data(), lmask[0].size() * 8, hipMemcpyHostToDevice) == hipSuccess &&
          hipMemcpy(m->lmask[1], lmask[1].data(), lmask[1].size() * 8, hipMemcpyHostToDevice) == hipSuccess;
     if (!ok) { tli_free_map(m); return TLI_ERR_HIP; }
+    if (hipMalloc(&m->sh_x, (size_t)S * 4) != hipSuccess) { tli_free_map(m); return TLI_ERR_ALLOC; }
+    if (hipMemcpy(m->sh_x, sh_x.data(), (size_t)S * 4, hipMemcpyHostToDevice) != hipSuccess) {
+        tli_free_map(m);
+        return TLI_ERR_HIP;
+    }
     for (int dt = 0; dt < 2; ++dt) {
-        ok = hipMalloc(&m->seg_start[dt], seg_start[dt].size() * 4) == hipSuccess &&
-             hipMalloc(&m->seg_x[dt], (size_t)S * 4) == hipSuccess &&
-             hipMalloc(&m->seg_off[dt], (size_t)S * 2) == hipSuccess;
+        ok = hipMalloc(&m->pl_start[dt], pl_start[dt].size() * 4) == hipSuccess &&
+             hipMalloc(&m->pl_e[dt], (size_t)S * 4) == hipSuccess;
         if (!ok) { tli_free_map(m); return TLI_ERR_ALLOC; }
-        ok = hipMemcpy(m->seg_start[dt], seg_start[dt].data(), seg_start[dt].size() * 4, hipMemcpyHostToDevice) ==
+        ok = hipMemcpy(m->pl_start[dt], pl_start[dt].data(), pl_start[dt].size() * 4, hipMemcpyHostToDevice) ==
                  hipSuccess &&
-             hipMemcpy(m->seg_x[dt], seg_x[dt].data(), (size_t)S * 4, hipMemcpyHostToDevice) == hipSuccess &&
-             hipMemcpy(m->seg_off[dt], seg_off[dt].data(), (size_t)S * 2, hipMemcpyHostToDevice) == hipSuccess;
+             hipMemcpy(m->pl_e[dt], pl_e[dt].data(), (size_t)S * 4, hipMemcpyHostToDevice) == hipSuccess;
         if (!ok) { tli_free_map(m); return TLI_ERR_HIP; }
     }
     *out_map = m;
@@ -1344,10 +1423,10 @@ void tli_free_map(tli_map* m) {
     if (m->t2d) (void)hipFree(m->t2d);
     if (m->lmask[0]) (void)hipFree(m->lmask[0]);
     if (m->lmask[1]) (void)hipFree(m->lmask[1]);
+    if (m->sh_x) (void)hipFree(m->sh_x);
     for (int dt = 0; dt < 2; ++dt) {
-        if (m->seg_start[dt]) (void)hipFree(m->seg_start[dt]);
-        if (m->seg_x[dt]) (void)hipFree(m->seg_x[dt]);
-        if (m->seg_off[dt]) (void)hipFree(m->seg_off[dt]);
+        if (m->pl_start[dt]) (void)hipFree(m->pl_start[dt]);
+        if (m->pl_e[dt]) (void)hipFree(m->pl_e[dt]);
     }
     delete m;
 }
@@ -1422,7 +1501,6 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
     double* ws_lse_p = reinterpret_cast<double*>(ws + w.ws_lse_p);
     float* tab_ref = reinterpret_cast<float*>(ws + w.tab_ref);
     float* tab_s = reinterpret_cast<float*>(ws + w.tab_s);
-    float* tab_p = reinterpret_cast<float*>(ws + w.tab_p);
     const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
     const int rows = B * K;
     const Plan pl = make_plan(Vt, rows, chunk);
@@ -1440,7 +1518,7 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
     a.seq_status = seq_status; a.part = part; a.ws_lse_p = ws_lse_p;
     a.part_d = reinterpret_cast<Part*>(ws + w.part_d); a.ws_lse_q = reinterpret_cast<double*>(ws + w.ws_lse_q);
     a.pd = make_plan(Vd, rows, chunk); a.cs_d = (float)c_d; a.ratio_d = c_d / (double)a.cs_d; a.tab_ref = tab_ref; a.tab_s = tab_s;
-    a.tab_p = tab_p; a.ctab = reinterpret_cast<float2*>(ws + w.ctab);
+    a.mn = reinterpret_cast<double*>(ws + w.mn); a.fbad = reinterpret_cast<int32_t*>(ws + w.fbad); a.ctab = reinterpret_cast<float2*>(ws + w.ctab);
     a.frow = reinterpret_cast<FinalRow*>(ws + w.frow);
     if (dtype == TLI_BF16) launch_verify<TLI_BF16>(a, st);
     else launch_verify<TLI_F32>(a, st);
