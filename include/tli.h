@@ -88,11 +88,16 @@ size_t tli_workspace_bytes(int32_t B, int32_t K, int32_t Vt, int32_t Vd, tli_dty
  *   q_tok      dev [R] fp64   q'(tok_d)                      (may be NULL)
  *   lse_q      dev [R] fp64   log sum_{x shared} exp(logits_d[x]/temp_d): log q'(x) = logit/temp - lse_q
  *   row_status dev [R] int32  TLI_FLAG_NONFINITE / TLI_FLAG_ZERO_MASS, else 0
+ *   io_stride  >= 1 : row r's entry of u_draft and of every output array is at index r * io_stride.
+ *                     1 = packed arrays.  With io_stride = K and every pointer advanced by k, a call on
+ *                     the B rows logits_d[:, k, :] (row_stride_elems = K*Vd) of a [B,K,Vd] tensor reads
+ *                     and fills column k of [B,K] arrays: the shape of the drafting loop, one call after
+ *                     each drafter forward, whose results tli_verify then takes as they are.
  * Unshared drafter logits are never inspected.
  */
 int tli_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems,
                      int32_t R, float temp_d, const float* u_draft, int32_t* tok_d, int32_t* tok_t,
-                     double* q_tok, double* lse_q, int32_t* row_status, void* workspace,
+                     double* q_tok, double* lse_q, int32_t* row_status, int64_t io_stride, void* workspace,
                      size_t workspace_bytes, void* hip_stream);
 
 /*

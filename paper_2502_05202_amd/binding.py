@@ -51,7 +51,7 @@ def load_library() -> ctypes.CDLL:
     lib.tli_map_info.restype = ctypes.c_int
     lib.tli_workspace_bytes.argtypes = [i32, i32, i32, i32, ctypes.c_int]
     lib.tli_workspace_bytes.restype = ctypes.c_size_t
-    lib.tli_draft_sample.argtypes = [vp, vp, ctypes.c_int, i64, i32, f32, vp, vp, vp, vp, vp, vp, vp,
+    lib.tli_draft_sample.argtypes = [vp, vp, ctypes.c_int, i64, i32, f32, vp, vp, vp, vp, vp, vp, i64, vp,
                                      ctypes.c_size_t, vp]
     lib.tli_draft_sample.restype = ctypes.c_int
     lib.tli_verify.argtypes = [vp, vp, vp, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
@@ -142,23 +142,36 @@ def alloc_workspace(B: int, K: int, m: TliMap, dtype: int, device) -> torch.Tens
 
 
 def tli_draft_sample(m: TliMap, logits_d: torch.Tensor, temp_d: float, u_draft: torch.Tensor,
-                     workspace: torch.Tensor, out: dict | None = None, stream=None) -> dict:
-    """logits_d [..., Vd] with contiguous last dim; leading dims are flattened into R rows."""
+                     workspace: torch.Tensor, out: dict | None = None, stream=None, column=None) -> dict:
+    """logits_d [..., Vd] with contiguous last dim; leading dims are flattened into R rows.
+
+    column=(k, K): the per-step form.  logits_d is then the [B, Vd] view logits[:, k, :] of a [B,K,Vd]
+    tensor, u_draft and the tensors of `out` are the full [B,K] arrays, and the call reads / fills their
+    column k (io_stride = K, pointers advanced by k)."""
     lib = load_library()
     assert logits_d.is_cuda and logits_d.stride(-1) == 1
-    ld = logits_d.reshape(-1, logits_d.shape[-1])
+    ld = logits_d.reshape(-1, logits_d.shape[-1]) if logits_d.dim() != 2 else logits_d
     R, Vd = ld.shape
-    assert Vd == m.Vd and u_draft.numel() == R and u_draft.dtype == torch.float32 and u_draft.is_contiguous()
+    k, io = (0, 1) if column is None else (int(column[0]), int(column[1]))
+    assert 0 <= k < io
+    assert Vd == m.Vd and u_draft.numel() == R * io and u_draft.dtype == torch.float32 and u_draft.is_contiguous()
     dev = ld.device
     if out is None:
-        out = dict(tok_d=torch.empty(R, dtype=torch.int32, device=dev),
-                   tok_t=torch.empty(R, dtype=torch.int32, device=dev),
-                   q_tok=torch.empty(R, dtype=torch.float64, device=dev),
-                   lse_q=torch.empty(R, dtype=torch.float64, device=dev),
-                   status=torch.empty(R, dtype=torch.int32, device=dev))
-    rc = lib.tli_draft_sample(m.handle, _ptr(ld), _dtype_code(ld), ld.stride(0), R, float(temp_d), _ptr(u_draft),
-                              _ptr(out["tok_d"]), _ptr(out["tok_t"]), _ptr(out.get("q_tok")), _ptr(out["lse_q"]),
-                              _ptr(out["status"]), _ptr(workspace), workspace.numel(), _stream(stream))
+        out = dict(tok_d=torch.empty(R * io, dtype=torch.int32, device=dev),
+                   tok_t=torch.empty(R * io, dtype=torch.int32, device=dev),
+                   q_tok=torch.empty(R * io, dtype=torch.float64, device=dev),
+                   lse_q=torch.empty(R * io, dtype=torch.float64, device=dev),
+                   status=torch.empty(R * io, dtype=torch.int32, device=dev))
+
+    def at(t):
+        if t is None:
+            return None
+        assert t.numel() == R * io and t.is_contiguous()
+        return ctypes.c_void_p(t.data_ptr() + k * t.element_size())
+
+    rc = lib.tli_draft_sample(m.handle, _ptr(ld), _dtype_code(ld), ld.stride(0), R, float(temp_d), at(u_draft),
+                              at(out["tok_d"]), at(out["tok_t"]), at(out.get("q_tok")), at(out["lse_q"]),
+                              at(out["status"]), io, _ptr(workspace), workspace.numel(), _stream(stream))
     if rc != 0:
         raise TliError(rc, "tli_draft_sample")
     return out

@@ -533,6 +533,7 @@ struct DraftOut {
     int32_t *tok_d, *tok_t;
     double *q_tok, *lse_q;
     int32_t* row_status;
+    int64_t stride;  // entry of row r of every per-row array (u_draft included) is at index r * stride
 };
 
 template <int DT>
@@ -541,22 +542,23 @@ __device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V,
                                       const float* ts, const DraftOut& o) {
     float M;
     double total;
-    const int d = sample_softmax_row<DT, true>(rowp, V, nC, cs, c_ratio, bits, tr, ts, (double)o.u_draft[row], &M, &total);
+    const int64_t at = (int64_t)row * o.stride;
+    const int d = sample_softmax_row<DT, true>(rowp, V, nC, cs, c_ratio, bits, tr, ts, (double)o.u_draft[at], &M, &total);
     if ((threadIdx.x & 63) != 0) return;
     if (d < 0) {  // no usable mass: NaN/+inf among the shared logits, or all of them -inf
         const bool nonfinite = (total != total);
-        o.tok_d[row] = -1; o.tok_t[row] = -1;
-        if (o.q_tok) o.q_tok[row] = 0.0;
-        o.lse_q[row] = nonfinite ? NAN : -INFINITY;
-        o.row_status[row] = nonfinite ? TLI_FLAG_NONFINITE : TLI_FLAG_ZERO_MASS;
+        o.tok_d[at] = -1; o.tok_t[at] = -1;
+        if (o.q_tok) o.q_tok[at] = 0.0;
+        o.lse_q[at] = nonfinite ? NAN : -INFINITY;
+        o.row_status[at] = nonfinite ? TLI_FLAG_NONFINITE : TLI_FLAG_ZERO_MASS;
         return;
     }
     const double lse = kLn2 * ((double)M * c_ratio + log2(total));
-    o.tok_d[row] = d;
-    o.tok_t[row] = d2t[d];
-    o.lse_q[row] = lse;
-    if (o.q_tok) o.q_tok[row] = exp((double)load_elem<DT>(rowp, d) * inv_temp - lse);
-    o.row_status[row] = 0;
+    o.tok_d[at] = d;
+    o.tok_t[at] = d2t[d];
+    o.lse_q[at] = lse;
+    if (o.q_tok) o.q_tok[at] = exp((double)load_elem<DT>(rowp, d) * inv_temp - lse);
+    o.row_status[at] = 0;
 }
 
 // kernel: sampler of the split path (rows cut over several workgroups by k_draft_scan).  grid (R), one wave.
@@ -1132,7 +1134,7 @@ struct KernelTimer {  // records start on construction, stop on destruction, if 
 template <int DT>
 void launch_draft(const tli_map* map, const void* logits_d, int64_t row_stride, int R, float temp_d, const Plan& pl,
                   float cs, double ratio, const float* u_draft, int32_t* tok_d, int32_t* tok_t, double* q_tok,
-                  double* lse_q, int32_t* row_status, float* tab_ref, float* tab_s, hipStream_t st);
+                  double* lse_q, int32_t* row_status, int64_t io_stride, float* tab_ref, float* tab_s, hipStream_t st);
 
 struct VerifyArgs {
     const tli_map* map;
@@ -1184,10 +1186,11 @@ namespace {
 template <int DT>
 void launch_draft(const tli_map* map, const void* logits_d, int64_t row_stride, int R, float temp_d, const Plan& pl,
                   float cs, double ratio, const float* u_draft, int32_t* tok_d, int32_t* tok_t, double* q_tok,
-                  double* lse_q, int32_t* row_status, float* tab_ref, float* tab_s, hipStream_t st) {
+                  double* lse_q, int32_t* row_status, int64_t io_stride, float* tab_ref, float* tab_s, hipStream_t st) {
     const int Vd = map->Vd;
     DraftOut o;
     o.u_draft = u_draft; o.tok_d = tok_d; o.tok_t = tok_t; o.q_tok = q_tok; o.lse_q = lse_q; o.row_status = row_status;
+    o.stride = io_stride;
     const double inv_temp = 1.0 / (double)temp_d;
     if (pl.nsplit == 1 && pl.nC <= kLdsChunks) {  // enough rows to fill the chip with one workgroup per row
         KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
@@ -1447,10 +1450,12 @@ size_t tli_workspace_bytes(int32_t B, int32_t K, int32_t Vt, int32_t Vd, tli_dty
 
 int tli_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems, int32_t R,
                      float temp_d, const float* u_draft, int32_t* tok_d, int32_t* tok_t, double* q_tok, double* lse_q,
-                     int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                     int32_t* row_status, int64_t io_stride, void* workspace, size_t workspace_bytes,
+                     void* hip_stream) {
     if (!map || !logits_d || !u_draft || !tok_d || !tok_t || !lse_q || !row_status || !workspace)
         return TLI_ERR_INVALID_ARG;
-    if (R < 1 || R > 0x7fffffff / 64 || !(temp_d > 0.f) || !std::isfinite(temp_d)) return TLI_ERR_INVALID_ARG;
+    if (R < 1 || R > 0x7fffffff / 64 || !(temp_d > 0.f) || !std::isfinite(temp_d) || io_stride < 1)
+        return TLI_ERR_INVALID_ARG;
     if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
     const int epv = dtype == TLI_BF16 ? 8 : 4;
     if (row_stride_elems < map->Vd || row_stride_elems % epv != 0 || !aligned16(logits_d) || !aligned16(workspace))
@@ -1470,10 +1475,10 @@ int tli_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (dtype == TLI_BF16)
         launch_draft<TLI_BF16>(map, logits_d, row_stride_elems, R, temp_d, pl, cs, ratio, u_draft, tok_d, tok_t, q_tok,
-                               lse_q, row_status, tab_ref, tab_s, st);
+                               lse_q, row_status, io_stride, tab_ref, tab_s, st);
     else
         launch_draft<TLI_F32>(map, logits_d, row_stride_elems, R, temp_d, pl, cs, ratio, u_draft, tok_d, tok_t, q_tok,
-                              lse_q, row_status, tab_ref, tab_s, st);
+                              lse_q, row_status, io_stride, tab_ref, tab_s, st);
     return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
 }
 

@@ -68,7 +68,7 @@ def test_status_strings_and_workspace(lib):
 
 def test_hot_calls_reject_null_arguments(lib):
     z = ctypes.c_void_p(0)
-    assert lib.tli_draft_sample(z, z, 0, 8, 1, 1.0, z, z, z, z, z, z, z, 0, z) == -1
+    assert lib.tli_draft_sample(z, z, 0, 8, 1, 1.0, z, z, z, z, z, z, 1, z, 0, z) == -1
     assert lib.tli_verify(z, z, z, 0, 1, 1, 1.0, 1.0, z, z, z, z, z, z, z, z, z, z, z, z, 0, z) == -1
     assert lib.tli_map_info(z, None, None, None) == -1
     lib.tli_free_map(z)  # freeing NULL is a no-op

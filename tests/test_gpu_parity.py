@@ -65,6 +65,9 @@ RAGGED = [
     (4, 8, 1, "f32", 2, 1, 0.5, 2.0),
     (10000, 30000, 9000, "bf16", 7, 6, 0.8, 0.8),
     (50000, 20000, 1, "f32", 2, 3, 1.0, 1.0),
+    # more shared ids than one workgroup holds in LDS: the residual scan runs in 3 (fp32) / 2 (bf16) parts
+    (70000, 60000, 50000, "f32", 2, 2, 1.0, 0.9),
+    (2048 * 30 + 16, 2048 * 27 + 8, 50000, "bf16", 3, 2, 0.9, 1.1),
 ]
 
 
