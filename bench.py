@@ -115,6 +115,27 @@ def main():
     draft_ms = time_call(lambda: binding.tli_draft_sample(m, inp["logits_d"], w.tau_d, u_draft, ws, out=d_out), n_sep)
     verify_ms = time_call(lambda: binding.tli_verify(m, inp["logits_t"], inp["logits_d"], w.tau_t, w.tau_d, d_out["tok_d"],
                                                      d_out["lse_q"], u_acc, inp["u_fin"], ws, out=v_out), n_sep)
+    # ---- the drafting loop at its real shape: one tli_draft_sample call per lookahead position on the B rows
+    # logits_d[:, k, :] (as after each drafter forward), then tli_verify; eager, and captured in a HIP graph
+    def iteration():
+        for k in range(w.K):
+            binding.tli_draft_sample(m, inp["logits_d"][:, k, :], w.tau_d, u_draft, ws, out=d_out, column=(k, w.K))
+        binding.tli_verify(m, inp["logits_t"], inp["logits_d"], w.tau_t, w.tau_d, d_out["tok_d"], d_out["lse_q"], u_acc,
+                           inp["u_fin"], ws, out=v_out)
+
+    per_step_eager_ms = time_call(iteration, n_sep)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        iteration()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        iteration()
+    per_step_graph_ms = time_call(graph.replay, n_sep)
+    del graph
+
     breakdown = None
     if args.breakdown:
         binding.tli_profile_enable(binding.KERNELS, n_sep)
@@ -147,6 +168,8 @@ def main():
         draft_rows_per_s=round(R / (1e-3 * draft_ms), 1),
         draft_algorithmic_gbs=round(draft_bytes / (1e-3 * draft_ms) / 1e9, 1),
         mean_accepted=round(float(n_acc.mean()), 3),
+        per_step_iteration=dict(calls=f"{w.K} x tli_draft_sample(R={w.B}) + tli_verify", eager_ms=round(per_step_eager_ms, 4),
+                                hip_graph_ms=round(per_step_graph_ms, 4)),
     )
     if breakdown:
         extra["kernel_breakdown"] = breakdown

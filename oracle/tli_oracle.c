@@ -25,8 +25,9 @@
  *   - all K accept tests are evaluated, the accepted count is the length of the all-accept prefix.
  *
  * All arithmetic is IEEE double.  Inputs are taken exactly as stored (fp32, or bf16 as its 16 bits).
- * Every function in this file is pinned by tests/test_oracle_pins.py (printed examples of the paper,
- * closed forms, library routines, exact enumeration of the output distribution).
+ * Every function in this file is pinned by tests/test_oracle_pins.py and tests/test_oracle_pins_next.py
+ * (printed examples of the paper, its table of expected acceptance rates and its theorems, closed forms,
+ * library routines, exact enumeration of the output distribution).
  */
 #include <math.h>
 #include <stdint.h>
@@ -280,5 +281,267 @@ void tlo_verify(const void *logits_t, const void *logits_d, int dtype, int64_t B
         out[n] = (int32_t)extra;
         n_acc[b] = (int32_t)n;
         seq_status[b] = status;
+    }
+}
+
+/* ======================================================================================================
+ * Beyond the TLI step: the other token-level pieces of the paper that run on the same rows.
+ *   - the "union" algorithm (simple extension of SD to heterogeneous vocabularies): p and q are
+ *     extended by zeros to T ∪ D and standard SD is run unchanged;
+ *   - the table of expected acceptance rates: sum_{T∩D} min{p, q} (union) and
+ *     sum_{T∩D} min{p, q / sum_{T∩D} q} (TLI), and the theorem alpha_union <= alpha_TLI;
+ *   - the data-parallel tail of string-level exact matching (SLEM): one token is drawn from each of the
+ *     m+1 target rows, the first index where it differs from the re-tokenised draft ends the match;
+ *   - temperature zero (the paper runs SLEM at temperature zero): every draw becomes an argmax.
+ * ====================================================================================================== */
+
+/*
+ * Draft step of the union algorithm: d ~ q = softmax(logits_d / tau_d) over ALL of D (no restriction).
+ * tok_t = d2t[d], which is -1 for a token outside T (such a draft is always rejected by the target).
+ * lse_q[r] = log sum_{x in D} exp(logit/tau_d).  Every drafter logit takes part: a NaN/+inf anywhere
+ * in the row flags it NONFINITE; a row of only -inf is ZERO_MASS.  work: Vd doubles.
+ */
+void tlo_union_draft_sample(const void *logits_d, int dtype, int64_t row_stride, int64_t R, int64_t Vd,
+                            double tau_d, const int32_t *d2t, const double *u_draft, int32_t *tok_d,
+                            int32_t *tok_t, double *q_tok, double *lse_q, int32_t *row_status,
+                            double *cdf_margin, double *work) {
+    size_t esz = (dtype == TLO_F32) ? 4 : 2;
+    double *q = work;
+    for (int64_t r = 0; r < R; ++r) {
+        const void *row = (const char *)logits_d + (size_t)r * (size_t)row_stride * esz;
+        int st = tlo_softmax(row, dtype, Vd, tau_d, q, &lse_q[r]);
+        if (!st && lse_q[r] == -INFINITY) st = TLO_ZERO_MASS;
+        row_status[r] = st;
+        tok_d[r] = -1; tok_t[r] = -1; q_tok[r] = 0.0;
+        if (cdf_margin) cdf_margin[r] = 0.0;
+        if (st) continue;
+        double mg;
+        int64_t d = tlo_inverse_cdf(q, Vd, u_draft[r], &mg);
+        tok_d[r] = (int32_t)d;
+        tok_t[r] = d2t[d];
+        q_tok[r] = q[d];
+        if (cdf_margin) cdf_margin[r] = mg;
+    }
+}
+
+/*
+ * Verification of the union algorithm: standard SD with p' (p on T, 0 on D\T) and q' (q on D, 0 on T\D).
+ * A draft outside T has p'(d) = 0 and is rejected for every u; the residual max(0, p' - q') vanishes
+ * outside T, so the extra token is a target token.  Same outputs as tlo_verify; q_tok = q(d), lse_q =
+ * the normaliser of q over all of D.  BAD_DRAFT only for ids that are not drafter ids at all (< 0 or >= Vd):
+ * such a position is rejected with q = 0.  work must hold 3*Vt + Vd doubles.
+ */
+void tlo_union_verify(const void *logits_t, const void *logits_d, int dtype, int64_t B, int64_t K,
+                      int64_t Vt, int64_t Vd, double tau_t, double tau_d, const int32_t *d2t,
+                      const int32_t *tok_d, const double *u_acc, const double *u_fin,
+                      int32_t *n_acc, int32_t *out_tok, uint8_t *accept, double *p_tok, double *q_tok,
+                      double *lse_p, double *lse_q, int32_t *seq_status, double *acc_margin,
+                      double *fin_margin, double *fin_weights, double *work) {
+    size_t esz = (dtype == TLO_F32) ? 4 : 2;
+    double *p = work, *qt = work + Vt, *w = work + 2 * Vt, *q = work + 3 * Vt;
+    for (int64_t b = 0; b < B; ++b) {
+        const char *lt_b = (const char *)logits_t + (size_t)b * (size_t)(K + 1) * (size_t)Vt * esz;
+        const char *ld_b = (const char *)logits_d + (size_t)b * (size_t)K * (size_t)Vd * esz;
+        int status = 0, first_reject = -1;
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t o = b * K + k;
+            int st_p = tlo_softmax(lt_b + (size_t)k * Vt * esz, dtype, Vt, tau_t, p, &lse_p[b * (K + 1) + k]);
+            status |= st_p;
+            int32_t d = tok_d[o];
+            accept[o] = 0; p_tok[o] = 0.0; q_tok[o] = 0.0; acc_margin[o] = INFINITY; lse_q[o] = NAN;
+            if (d < 0 || d >= Vd) {
+                status |= TLO_BAD_DRAFT;
+            } else if (!st_p) {
+                int st_q = tlo_softmax(ld_b + (size_t)k * Vd * esz, dtype, Vd, tau_d, q, &lse_q[o]);
+                if (st_q) {
+                    status |= st_q;
+                } else {
+                    double pd = (d2t[d] >= 0) ? p[d2t[d]] : 0.0, qd = q[d];
+                    p_tok[o] = pd; q_tok[o] = qd;
+                    accept[o] = (u_acc[o] * qd < pd) ? 1 : 0;
+                    if (pd < qd) acc_margin[o] = fabs(u_acc[o] - pd / qd);
+                }
+            }
+            if (!accept[o] && first_reject < 0) first_reject = (int)k;
+        }
+        lse_p[b * (K + 1) + K] = NAN;
+        int32_t *out = out_tok + b * (K + 1);
+        for (int64_t k = 0; k <= K; ++k) out[k] = -1;
+        fin_margin[b] = 0.0;
+        if (status & TLO_NONFINITE) {
+            n_acc[b] = 0; seq_status[b] = status;
+            if (fin_weights) for (int64_t t = 0; t < Vt; ++t) fin_weights[b * Vt + t] = NAN;
+            continue;
+        }
+        int64_t n = (first_reject < 0) ? K : first_reject;
+        if (n < K) {
+            tlo_softmax(lt_b + (size_t)n * Vt * esz, dtype, Vt, tau_t, p, &lse_p[b * (K + 1) + n]);
+            for (int64_t t = 0; t < Vt; ++t) qt[t] = 0.0;
+            int32_t d = tok_d[b * K + n];
+            if (!(d < 0 || d >= Vd)) {
+                double tmp;
+                tlo_softmax(ld_b + (size_t)n * Vd * esz, dtype, Vd, tau_d, q, &tmp);
+                for (int64_t x = 0; x < Vd; ++x)
+                    if (d2t[x] >= 0) qt[d2t[x]] = q[x];
+            }
+            if (residual_weights(p, qt, Vt, w)) status |= TLO_DEGENERATE;
+        } else {
+            int st = tlo_softmax(lt_b + (size_t)K * Vt * esz, dtype, Vt, tau_t, w, &lse_p[b * (K + 1) + K]);
+            if (st) {
+                n_acc[b] = 0; seq_status[b] = status | st;
+                if (fin_weights) for (int64_t t = 0; t < Vt; ++t) fin_weights[b * Vt + t] = NAN;
+                continue;
+            }
+        }
+        if (fin_weights) memcpy(fin_weights + b * Vt, w, (size_t)Vt * sizeof(double));
+        int64_t extra = tlo_inverse_cdf(w, Vt, u_fin[b], &fin_margin[b]);
+        for (int64_t k = 0; k < n; ++k) out[k] = d2t[tok_d[b * K + k]];
+        out[n] = (int32_t)extra;
+        n_acc[b] = (int32_t)n;
+        seq_status[b] = status;
+    }
+}
+
+/*
+ * Expected acceptance rates of one draft token, per row pair (target row r at logits_t + r*stride_t,
+ * drafter row r at logits_d + r*stride_d), as the paper's table states them:
+ *   alpha_union = sum_{t in T∩D} min{p(t), q(t)}
+ *   alpha_tli   = sum_{t in T∩D} min{p(t), q(t) / sum_{x in T∩D} q(x)}
+ * status: NONFINITE if a target logit or ANY drafter logit is NaN/+inf (alphas NaN); ZERO_MASS if the
+ * shared ids carry no drafter mass (alpha_tli = 0, as for an empty intersection).
+ * work must hold Vt + Vd doubles.
+ */
+void tlo_acceptance_rates(const void *logits_t, int64_t stride_t, const void *logits_d, int64_t stride_d,
+                          int dtype, int64_t R, int64_t Vt, int64_t Vd, double tau_t, double tau_d,
+                          const int32_t *d2t, double *alpha_tli, double *alpha_union, int32_t *status,
+                          double *work) {
+    size_t esz = (dtype == TLO_F32) ? 4 : 2;
+    double *p = work, *q = work + Vt;
+    for (int64_t r = 0; r < R; ++r) {
+        const void *lt = (const char *)logits_t + (size_t)r * (size_t)stride_t * esz;
+        const void *ld = (const char *)logits_d + (size_t)r * (size_t)stride_d * esz;
+        double lp, lq;
+        int st = tlo_softmax(lt, dtype, Vt, tau_t, p, &lp) | tlo_softmax(ld, dtype, Vd, tau_d, q, &lq);
+        if (st) { status[r] = TLO_NONFINITE; alpha_tli[r] = NAN; alpha_union[r] = NAN; continue; }
+        double mass = 0.0;
+        for (int64_t x = 0; x < Vd; ++x)
+            if (d2t[x] >= 0) mass += q[x];
+        double au = 0.0, at = 0.0;
+        for (int64_t x = 0; x < Vd; ++x) {
+            if (d2t[x] < 0) continue;
+            au += fmin(p[d2t[x]], q[x]);
+            if (mass > 0.0) at += fmin(p[d2t[x]], q[x] / mass);
+        }
+        alpha_union[r] = au;
+        alpha_tli[r] = at;
+        status[r] = (mass > 0.0) ? 0 : TLO_ZERO_MASS;
+    }
+}
+
+/*
+ * argmax of a row at temperature zero: the largest logit, the lowest id among equal ones (the limit of
+ * the ascending inverse CDF as tau -> 0 puts the draw on the first maximiser for every u below the
+ * reciprocal of their number; one convention is needed and this is it).  If `d2t` != NULL only shared ids
+ * (d2t[x] >= 0) compete.  Returns -1 with *status = NONFINITE if a competing logit is NaN or +inf,
+ * -1 with ZERO_MASS if every competing logit is -inf (or none competes).
+ */
+int64_t tlo_argmax(const void *logits, int dtype, int64_t n, const int32_t *d2t, int32_t *status) {
+    int64_t best = -1;
+    double bv = -INFINITY;
+    *status = 0;
+    for (int64_t x = 0; x < n; ++x) {
+        if (d2t && d2t[x] < 0) continue;
+        double z = load_logit(logits, dtype, x);
+        if (isnan(z) || z == INFINITY) { *status = TLO_NONFINITE; return -1; }
+        if (z > bv) { bv = z; best = x; }
+    }
+    if (best < 0) *status = TLO_ZERO_MASS;
+    return best;
+}
+
+/*
+ * One token from each of R rows: t_r ~ softmax(logits_r / tau) by inverse CDF with u[r], or the argmax
+ * when tau == 0.  p_tok[r] = probability of the returned token (1 at tau == 0), lse[r] = log-normaliser
+ * (NaN at tau == 0).  Flagged rows return -1.  work: V doubles.
+ */
+void tlo_sample_rows(const void *logits, int dtype, int64_t row_stride, int64_t R, int64_t V, double tau,
+                     const double *u, int32_t *tok, double *p_tok, double *lse, int32_t *status,
+                     double *cdf_margin, double *work) {
+    size_t esz = (dtype == TLO_F32) ? 4 : 2;
+    for (int64_t r = 0; r < R; ++r) {
+        const void *row = (const char *)logits + (size_t)r * (size_t)row_stride * esz;
+        tok[r] = -1; p_tok[r] = 0.0; lse[r] = NAN;
+        if (cdf_margin) cdf_margin[r] = 0.0;
+        if (tau == 0.0) {
+            int32_t st;
+            int64_t t = tlo_argmax(row, dtype, V, NULL, &st);
+            status[r] = st;
+            if (!st) { tok[r] = (int32_t)t; p_tok[r] = 1.0; }
+            continue;
+        }
+        int st = tlo_softmax(row, dtype, V, tau, work, &lse[r]);
+        if (!st && lse[r] == -INFINITY) st = TLO_ZERO_MASS;
+        status[r] = st;
+        if (st) continue;
+        double mg;
+        int64_t t = tlo_inverse_cdf(work, V, u[r], &mg);
+        tok[r] = (int32_t)t;
+        p_tok[r] = work[t];
+        if (cdf_margin) cdf_margin[r] = mg;
+    }
+}
+
+/*
+ * Tail of string-level exact matching for B sequences: target rows [B, m+1, Vt], re-tokenised drafts
+ * draft_t [B, m] (target ids; a negative entry = no draft token there).  t'_j is drawn from row j for all
+ * j = 1..m+1 (tau_t == 0: argmax); j* = first j with t'_j != draft_j (m+1 if none); output
+ * draft_1..draft_{j*-1}, t'_{j*}; n_acc = j* - 1.  tgt_tok [B, m+1] receives every t'_j.
+ * A NONFINITE / ZERO_MASS row among the m+1 flags the sequence: n_acc = 0, out_tok = -1.
+ * With tau_t == 0 and draft_t = the target ids of greedy TLI drafts this is TLI's verification at
+ * temperature zero (accept iff the draft is the target's argmax; the extra token is the argmax of the
+ * first rejected row, or of row m+1).  work: Vt doubles.
+ */
+void tlo_exact_match_verify(const void *logits_t, int dtype, int64_t B, int64_t m, int64_t Vt, double tau_t,
+                            const int32_t *draft_t, const double *u, int32_t *n_acc, int32_t *out_tok,
+                            int32_t *tgt_tok, int32_t *seq_status, double *cdf_margin, double *work) {
+    size_t esz = (dtype == TLO_F32) ? 4 : 2;
+    for (int64_t b = 0; b < B; ++b) {
+        const char *lt_b = (const char *)logits_t + (size_t)b * (size_t)(m + 1) * (size_t)Vt * esz;
+        int32_t *tt = tgt_tok + b * (m + 1);
+        int32_t *out = out_tok + b * (m + 1);
+        int status = 0;
+        for (int64_t j = 0; j <= m; ++j) {
+            double pt, l;
+            int32_t st;
+            tlo_sample_rows(lt_b + (size_t)j * Vt * esz, dtype, Vt, 1, Vt, tau_t, &u[b * (m + 1) + j], &tt[j], &pt, &l,
+                            &st, cdf_margin ? &cdf_margin[b * (m + 1) + j] : NULL, work);
+            status |= st;
+            out[j] = -1;
+        }
+        seq_status[b] = status;
+        n_acc[b] = 0;
+        if (status) continue;
+        int64_t j = 0;
+        while (j < m && draft_t[b * m + j] >= 0 && draft_t[b * m + j] == tt[j]) ++j;
+        for (int64_t k = 0; k < j; ++k) out[k] = draft_t[b * m + k];
+        out[j] = tt[j];
+        n_acc[b] = (int32_t)j;
+    }
+}
+
+/*
+ * Greedy draft of TLI (temperature zero): d = argmax of the drafter row over the SHARED ids, lowest id on
+ * ties; tok_t = d2t[d].  Flagged rows (NONFINITE / ZERO_MASS among the shared logits) return -1.
+ */
+void tlo_greedy_draft(const void *logits_d, int dtype, int64_t row_stride, int64_t R, int64_t Vd,
+                      const int32_t *d2t, int32_t *tok_d, int32_t *tok_t, int32_t *row_status) {
+    size_t esz = (dtype == TLO_F32) ? 4 : 2;
+    for (int64_t r = 0; r < R; ++r) {
+        const void *row = (const char *)logits_d + (size_t)r * (size_t)row_stride * esz;
+        int32_t st;
+        int64_t d = tlo_argmax(row, dtype, Vd, d2t, &st);
+        row_status[r] = st;
+        tok_d[r] = (int32_t)d;
+        tok_t[r] = (d >= 0) ? d2t[d] : -1;
     }
 }
