@@ -128,6 +128,83 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
                void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * ---- The neighbouring token-level steps of the paper, on the same rows -------------------------------
+ *
+ * The "union" algorithm (section "Motivating Examples", the simple union strategy: p and q are extended by
+ * zeros to T ∪ D and standard speculative decoding runs unchanged).  Same arguments and outputs as
+ * tli_draft_sample / tli_verify, with these differences: drafts are drawn from q = softmax over ALL of D;
+ * tok_t is -1 for a token outside T; lse_q is the normaliser over all of D (NULL in the verify call: one
+ * unmasked scan recomputes it); a draft outside T is a legal draft that the target rejects for every u
+ * (p = 0), and the residual after it still subtracts q on the shared ids; BAD_DRAFT only marks ids outside
+ * [0, Vd); every drafter logit takes part, so NaN/+inf anywhere in a drafter row flags it.
+ */
+int tli_union_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems,
+                           int32_t R, float temp_d, const float* u_draft, int32_t* tok_d, int32_t* tok_t,
+                           double* q_tok, double* lse_q, int32_t* row_status, int64_t io_stride, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+int tli_union_verify(const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype, int32_t B,
+                     int32_t K, float temp_t, float temp_d, const int32_t* tok_d, const double* lse_q,
+                     const float* u_acc, const float* u_fin, int32_t* n_accepted, int32_t* out_tok,
+                     uint8_t* accept, double* p_tok, double* q_tok, double* lse_p, int32_t* seq_status,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Expected acceptance rate of one draft token at every position (the paper's table of expected acceptance
+ * rates; the theorem on the intersection algorithm states alpha_union <= alpha_tli):
+ *   alpha_union[b,k] = sum_{t in T∩D} min{p_k(t), q_k(t)}
+ *   alpha_tli[b,k]   = sum_{t in T∩D} min{p_k(t), q_k(t) / sum_{x in T∩D} q_k(x)}
+ *   logits_t dev [B,K+1,Vt] (row K of a sequence is not used), logits_d dev [B,K,Vd], both dense
+ *   alpha_tli, alpha_union dev [B,K] fp64; pos_status dev [B,K] int32: NONFINITE (a target logit or ANY drafter
+ *   logit of the position is NaN/+inf: both rates NaN) or ZERO_MASS (no drafter mass on the shared ids: both 0).
+ * Scratch: tli_acceptance_rates_workspace_bytes (it depends on the map).
+ */
+size_t tli_acceptance_rates_workspace_bytes(const tli_map* map, int32_t B, int32_t K, tli_dtype dtype);
+int tli_acceptance_rates(const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype, int32_t B,
+                         int32_t K, float temp_t, float temp_d, double* alpha_tli, double* alpha_union,
+                         int32_t* pos_status, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * One token from each of R rows of any vocabulary (no map): tok[r] ~ softmax(logits_r / temp) by the ascending
+ * inverse CDF with u[r]; temp == 0 takes the argmax instead (largest logit, lowest id among equal ones; u may
+ * then be NULL) -- the paper runs its exact-matching method at temperature zero.
+ *   logits dev [R rows, row_stride_elems apart, V valid entries], u dev fp32, tok dev int32 (-1 if flagged),
+ *   p_tok dev fp64 probability of the returned token (1 at temp 0; may be NULL), lse dev fp64 log-normaliser
+ *   (NaN at temp 0; may be NULL), row_status dev int32 (NONFINITE / ZERO_MASS), io_stride as in tli_draft_sample.
+ * Scratch: tli_sample_rows_workspace_bytes(R, V, dtype).
+ */
+size_t tli_sample_rows_workspace_bytes(int32_t R, int32_t V, tli_dtype dtype);
+int tli_sample_rows(const void* logits, tli_dtype dtype, int64_t row_stride_elems, int32_t R, int32_t V, float temp,
+                    const float* u, int32_t* tok, double* p_tok, double* lse, int32_t* row_status, int64_t io_stride,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Draft step of TLI at temperature zero: tok_d[r] = argmax of drafter row r over the SHARED ids (lowest id on
+ * ties), tok_t = its target id; rows whose shared logits hold NaN/+inf or are all -inf are flagged and return -1.
+ * Scratch: tli_workspace_bytes covers R <= B*K rows.
+ */
+int tli_greedy_draft(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems, int32_t R,
+                     int32_t* tok_d, int32_t* tok_t, int32_t* row_status, int64_t io_stride, void* workspace,
+                     size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Data-parallel tail of string-level exact matching (section "String-Level Exact Match", the steps after the
+ * target forward): one token t'_j is drawn from each of the m+1 target rows (temp_t == 0: argmax), j* is the
+ * first position where it differs from the re-tokenised draft, and draft_1..draft_{j*-1}, t'_{j*} are returned.
+ *   logits_t dev [B, m+1, Vt] dense; draft_t dev [B, m] int32 target ids (negative = no draft token there);
+ *   u dev [B, m+1] fp32 (may be NULL at temp_t == 0); n_accepted dev [B] = j* - 1; out_tok dev [B, m+1] (-1
+ *   padded); tgt_tok dev [B, m+1] every t'_j; seq_status dev [B]: NONFINITE / ZERO_MASS if any of the m+1 rows is
+ *   flagged (then n_accepted = 0 and out_tok = -1).  1 <= m < 64.
+ * With temp_t == 0 and draft_t = the tok_t of tli_greedy_draft this is TLI's verification at temperature zero:
+ * a draft is accepted iff it is the target's argmax, the extra token is the argmax of the first rejected row.
+ * Scratch: tli_exact_match_workspace_bytes.
+ */
+size_t tli_exact_match_workspace_bytes(int32_t B, int32_t m, int32_t Vt, tli_dtype dtype);
+int tli_exact_match_verify(const void* logits_t, tli_dtype dtype, int32_t B, int32_t m, int32_t Vt, float temp_t,
+                           const int32_t* draft_t, const float* u, int32_t* n_accepted, int32_t* out_tok,
+                           int32_t* tgt_tok, int32_t* seq_status, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
+/*
  * Optional per-kernel timing for benchmarks (not part of the method): while enabled, the hot calls
  * record a HIP event pair around each selected kernel on the caller's stream.  Not thread-safe.
  *   tli_profile_enable  : creates 2*max_calls events per selected kernel (bit k of kernel_mask selects
@@ -143,8 +220,8 @@ typedef enum {
     TLI_KERNEL_ACCEPT = 1,     /* tli_verify: accept tests + first-reject scan                            */
     TLI_KERNEL_FINAL_SCAN = 2, /* tli_verify: chunk masses of the residual / bonus rows                   */
     TLI_KERNEL_FINAL_PICK = 3, /* tli_verify: draw of the extra token                                     */
-    TLI_KERNEL_DRAFT_SCAN = 4, /* tli_draft_sample: q' over the shared ids (+ the draw, one workgroup/row) */
-    TLI_KERNEL_DRAFT_PICK = 5, /* tli_draft_sample: the draw, only when rows are split over workgroups     */
+    TLI_KERNEL_DRAFT_SCAN = 4, /* row samplers: scan of the rows (+ the draw, one workgroup/row); argmax scan  */
+    TLI_KERNEL_DRAFT_PICK = 5, /* row samplers: the draw when rows are split over workgroups; argmax finish   */
     TLI_KERNEL_COUNT = 6
 } tli_kernel_id;
 int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls, int32_t every);

@@ -21,6 +21,9 @@ FLAG_NONFINITE, FLAG_ZERO_MASS, FLAG_BAD_DRAFT, FLAG_DEGENERATE = 1, 2, 4, 8
 EXPORTS = (
     "tli_build_map", "tli_free_map", "tli_map_info", "tli_workspace_bytes", "tli_draft_sample", "tli_verify",
     "tli_status_string", "tli_profile_enable", "tli_profile_collect", "tli_profile_disable", "tli_calib_copy",
+    "tli_union_draft_sample", "tli_union_verify", "tli_acceptance_rates_workspace_bytes", "tli_acceptance_rates",
+    "tli_sample_rows_workspace_bytes", "tli_sample_rows", "tli_greedy_draft", "tli_exact_match_workspace_bytes",
+    "tli_exact_match_verify",
 )
 KERNELS = ("lse", "accept", "final_scan", "final_pick", "draft_scan", "draft_pick")
 
@@ -57,6 +60,25 @@ def load_library() -> ctypes.CDLL:
     lib.tli_verify.argtypes = [vp, vp, vp, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                vp, vp, vp, ctypes.c_size_t, vp]
     lib.tli_verify.restype = ctypes.c_int
+    lib.tli_union_draft_sample.argtypes = lib.tli_draft_sample.argtypes
+    lib.tli_union_draft_sample.restype = ctypes.c_int
+    lib.tli_union_verify.argtypes = lib.tli_verify.argtypes
+    lib.tli_union_verify.restype = ctypes.c_int
+    lib.tli_acceptance_rates_workspace_bytes.argtypes = [vp, i32, i32, ctypes.c_int]
+    lib.tli_acceptance_rates_workspace_bytes.restype = ctypes.c_size_t
+    lib.tli_acceptance_rates.argtypes = [vp, vp, vp, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.tli_acceptance_rates.restype = ctypes.c_int
+    lib.tli_sample_rows_workspace_bytes.argtypes = [i32, i32, ctypes.c_int]
+    lib.tli_sample_rows_workspace_bytes.restype = ctypes.c_size_t
+    lib.tli_sample_rows.argtypes = [vp, ctypes.c_int, i64, i32, i32, f32, vp, vp, vp, vp, vp, i64, vp, ctypes.c_size_t, vp]
+    lib.tli_sample_rows.restype = ctypes.c_int
+    lib.tli_greedy_draft.argtypes = [vp, vp, ctypes.c_int, i64, i32, vp, vp, vp, i64, vp, ctypes.c_size_t, vp]
+    lib.tli_greedy_draft.restype = ctypes.c_int
+    lib.tli_exact_match_workspace_bytes.argtypes = [i32, i32, i32, ctypes.c_int]
+    lib.tli_exact_match_workspace_bytes.restype = ctypes.c_size_t
+    lib.tli_exact_match_verify.argtypes = [vp, ctypes.c_int, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp,
+                                           ctypes.c_size_t, vp]
+    lib.tli_exact_match_verify.restype = ctypes.c_int
     lib.tli_profile_enable.argtypes = [ctypes.c_uint32, i32, i32]
     lib.tli_profile_enable.restype = ctypes.c_int
     lib.tli_profile_collect.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
@@ -142,7 +164,8 @@ def alloc_workspace(B: int, K: int, m: TliMap, dtype: int, device) -> torch.Tens
 
 
 def tli_draft_sample(m: TliMap, logits_d: torch.Tensor, temp_d: float, u_draft: torch.Tensor,
-                     workspace: torch.Tensor, out: dict | None = None, stream=None, column=None) -> dict:
+                     workspace: torch.Tensor, out: dict | None = None, stream=None, column=None,
+                     _entry: str = "tli_draft_sample") -> dict:
     """logits_d [..., Vd] with contiguous last dim; leading dims are flattened into R rows.
 
     column=(k, K): the per-step form.  logits_d is then the [B, Vd] view logits[:, k, :] of a [B,K,Vd]
@@ -169,12 +192,17 @@ def tli_draft_sample(m: TliMap, logits_d: torch.Tensor, temp_d: float, u_draft: 
         assert t.numel() == R * io and t.is_contiguous()
         return ctypes.c_void_p(t.data_ptr() + k * t.element_size())
 
-    rc = lib.tli_draft_sample(m.handle, _ptr(ld), _dtype_code(ld), ld.stride(0), R, float(temp_d), at(u_draft),
+    rc = getattr(lib, _entry)(m.handle, _ptr(ld), _dtype_code(ld), ld.stride(0), R, float(temp_d), at(u_draft),
                               at(out["tok_d"]), at(out["tok_t"]), at(out.get("q_tok")), at(out["lse_q"]),
                               at(out["status"]), io, _ptr(workspace), workspace.numel(), _stream(stream))
     if rc != 0:
-        raise TliError(rc, "tli_draft_sample")
+        raise TliError(rc, _entry)
     return out
+
+
+def tli_union_draft_sample(m: TliMap, logits_d, temp_d, u_draft, workspace, out=None, stream=None, column=None) -> dict:
+    """Draft step of the union algorithm: same call as tli_draft_sample, drawn from q over all of D."""
+    return tli_draft_sample(m, logits_d, temp_d, u_draft, workspace, out, stream, column, _entry="tli_union_draft_sample")
 
 
 def alloc_verify_outputs(B: int, K: int, device) -> dict:
@@ -189,7 +217,7 @@ def alloc_verify_outputs(B: int, K: int, device) -> dict:
 
 def tli_verify(m: TliMap, logits_t: torch.Tensor, logits_d: torch.Tensor, temp_t: float, temp_d: float,
                tok_d: torch.Tensor, lse_q: torch.Tensor, u_acc: torch.Tensor, u_fin: torch.Tensor,
-               workspace: torch.Tensor, out: dict | None = None, stream=None) -> dict:
+               workspace: torch.Tensor, out: dict | None = None, stream=None, _entry: str = "tli_verify") -> dict:
     """logits_t [B,K+1,Vt], logits_d [B,K,Vd] dense; tok_d int32 [B,K]; lse_q float64 [B,K] or None
     (None: the library recomputes the drafter normalisers)."""
     lib = load_library()
@@ -203,13 +231,109 @@ def tli_verify(m: TliMap, logits_t: torch.Tensor, logits_d: torch.Tensor, temp_t
     assert u_fin.dtype == torch.float32 and u_fin.numel() == B and u_fin.is_contiguous()
     if out is None:
         out = alloc_verify_outputs(B, K, logits_t.device)
-    rc = lib.tli_verify(m.handle, _ptr(logits_t), _ptr(logits_d), _dtype_code(logits_t), B, K, float(temp_t),
+    rc = getattr(lib, _entry)(m.handle, _ptr(logits_t), _ptr(logits_d), _dtype_code(logits_t), B, K, float(temp_t),
                         float(temp_d), _ptr(tok_d), _ptr(lse_q), _ptr(u_acc), _ptr(u_fin), _ptr(out["n_accepted"]),
                         _ptr(out["out_tok"]), _ptr(out.get("accept")), _ptr(out.get("p_tok")), _ptr(out.get("q_tok")),
                         _ptr(out.get("lse_p")), _ptr(out["status"]), _ptr(workspace), workspace.numel(),
                         _stream(stream))
     if rc != 0:
-        raise TliError(rc, "tli_verify")
+        raise TliError(rc, _entry)
+    return out
+
+
+def tli_union_verify(m: TliMap, logits_t, logits_d, temp_t, temp_d, tok_d, lse_q, u_acc, u_fin, workspace, out=None,
+                     stream=None) -> dict:
+    """Verification of the union algorithm: same call as tli_verify with q over all of D (lse_q over all of D)."""
+    return tli_verify(m, logits_t, logits_d, temp_t, temp_d, tok_d, lse_q, u_acc, u_fin, workspace, out, stream,
+                      _entry="tli_union_verify")
+
+
+def tli_acceptance_rates(m: TliMap, logits_t: torch.Tensor, logits_d: torch.Tensor, temp_t: float, temp_d: float,
+                         workspace: torch.Tensor | None = None, stream=None) -> dict:
+    """alpha_tli, alpha_union [B,K] fp64 and pos_status [B,K] for logits_t [B,K+1,Vt], logits_d [B,K,Vd]."""
+    lib = load_library()
+    B, K1, Vt = logits_t.shape
+    K = K1 - 1
+    assert logits_t.is_contiguous() and logits_d.is_contiguous() and tuple(logits_d.shape) == (B, K, m.Vd) and Vt == m.Vt
+    code = _dtype_code(logits_t)
+    if workspace is None:
+        n = int(lib.tli_acceptance_rates_workspace_bytes(m.handle, B, K, code))
+        if n == 0:
+            raise TliError(-1, "tli_acceptance_rates_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=logits_t.device)
+    dev = logits_t.device
+    out = dict(alpha_tli=torch.empty((B, K), dtype=torch.float64, device=dev),
+               alpha_union=torch.empty((B, K), dtype=torch.float64, device=dev),
+               status=torch.empty((B, K), dtype=torch.int32, device=dev))
+    rc = lib.tli_acceptance_rates(m.handle, _ptr(logits_t), _ptr(logits_d), code, B, K, float(temp_t), float(temp_d),
+                                  _ptr(out["alpha_tli"]), _ptr(out["alpha_union"]), _ptr(out["status"]), _ptr(workspace),
+                                  workspace.numel(), _stream(stream))
+    if rc != 0:
+        raise TliError(rc, "tli_acceptance_rates")
+    out["workspace"] = workspace
+    return out
+
+
+def tli_sample_rows(logits: torch.Tensor, temp: float, u: torch.Tensor | None, workspace: torch.Tensor | None = None,
+                    stream=None) -> dict:
+    """One token per row of logits [R, V] (contiguous last dim): softmax draw, or argmax at temp == 0."""
+    lib = load_library()
+    assert logits.is_cuda and logits.dim() == 2 and logits.stride(-1) == 1
+    R, V = logits.shape
+    code = _dtype_code(logits)
+    if workspace is None:
+        workspace = torch.empty(int(lib.tli_sample_rows_workspace_bytes(R, V, code)), dtype=torch.uint8, device=logits.device)
+    dev = logits.device
+    out = dict(tok=torch.empty(R, dtype=torch.int32, device=dev), p_tok=torch.empty(R, dtype=torch.float64, device=dev),
+               lse=torch.empty(R, dtype=torch.float64, device=dev), status=torch.empty(R, dtype=torch.int32, device=dev))
+    rc = lib.tli_sample_rows(_ptr(logits), code, logits.stride(0), R, V, float(temp), _ptr(u), _ptr(out["tok"]),
+                             _ptr(out["p_tok"]), _ptr(out["lse"]), _ptr(out["status"]), 1, _ptr(workspace),
+                             workspace.numel(), _stream(stream))
+    if rc != 0:
+        raise TliError(rc, "tli_sample_rows")
+    return out
+
+
+def tli_greedy_draft(m: TliMap, logits_d: torch.Tensor, workspace: torch.Tensor, stream=None) -> dict:
+    """TLI draft at temperature zero for logits_d [..., Vd]: argmax over the shared ids."""
+    lib = load_library()
+    ld = logits_d.reshape(-1, logits_d.shape[-1]) if logits_d.dim() != 2 else logits_d
+    R, Vd = ld.shape
+    assert Vd == m.Vd and ld.stride(-1) == 1
+    dev = ld.device
+    out = dict(tok_d=torch.empty(R, dtype=torch.int32, device=dev), tok_t=torch.empty(R, dtype=torch.int32, device=dev),
+               status=torch.empty(R, dtype=torch.int32, device=dev))
+    rc = lib.tli_greedy_draft(m.handle, _ptr(ld), _dtype_code(ld), ld.stride(0), R, _ptr(out["tok_d"]), _ptr(out["tok_t"]),
+                              _ptr(out["status"]), 1, _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc != 0:
+        raise TliError(rc, "tli_greedy_draft")
+    return out
+
+
+def tli_exact_match_verify(logits_t: torch.Tensor, temp_t: float, draft_t: torch.Tensor, u: torch.Tensor | None,
+                           workspace: torch.Tensor | None = None, out: dict | None = None, stream=None) -> dict:
+    """logits_t [B, m+1, Vt] dense, draft_t int32 [B, m] target ids, u fp32 [B, m+1] (None at temp_t == 0)."""
+    lib = load_library()
+    B, m1, Vt = logits_t.shape
+    mm = m1 - 1
+    assert logits_t.is_cuda and logits_t.is_contiguous()
+    assert draft_t.dtype == torch.int32 and draft_t.numel() == B * mm and draft_t.is_contiguous()
+    assert u is None or (u.dtype == torch.float32 and u.numel() == B * m1 and u.is_contiguous())
+    code = _dtype_code(logits_t)
+    if workspace is None:
+        workspace = torch.empty(int(lib.tli_exact_match_workspace_bytes(B, mm, Vt, code)), dtype=torch.uint8,
+                                device=logits_t.device)
+    dev = logits_t.device
+    if out is None:
+        out = dict(n_accepted=torch.empty(B, dtype=torch.int32, device=dev),
+                   out_tok=torch.empty((B, m1), dtype=torch.int32, device=dev),
+                   tgt_tok=torch.empty((B, m1), dtype=torch.int32, device=dev),
+                   status=torch.empty(B, dtype=torch.int32, device=dev))
+    rc = lib.tli_exact_match_verify(_ptr(logits_t), code, B, mm, Vt, float(temp_t), _ptr(draft_t), _ptr(u),
+                                    _ptr(out["n_accepted"]), _ptr(out["out_tok"]), _ptr(out["tgt_tok"]),
+                                    _ptr(out["status"]), _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc != 0:
+        raise TliError(rc, "tli_exact_match_verify")
     return out
 
 

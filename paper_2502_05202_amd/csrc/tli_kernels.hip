@@ -210,53 +210,58 @@ __device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane
     s_out = wave_sum(s);
 }
 
-// Stream the chunks c_begin + wave, + NW, ... < c_end of one row (NW = waves in the workgroup) through reduce_chunk and hand
-// each (c, ref, s) to `sink`.  Whole chunks run in a two-stage register pipeline: the loads of the
-// next chunk are in flight while the current one is reduced.  A row has at most one partial chunk
-// (its last); the wave that owns it handles it after its whole chunks.
-template <int DT, bool MASKED, int NW, class Sink>
-__device__ __forceinline__ void scan_chunks(const u4v* rowv, int V, int c_begin, int c_end, float cs, float dl,
-                                            const uint64_t* bits,
-                                   Sink&& sink) {
+// Stream the chunks c_begin + wave, + NW, ... < c_end of one row (NW = waves in the workgroup) through
+// `proc(regs, c, whole)` (whole: std::true_type if every element of the chunk is < V).  Whole chunks run in
+// a two-stage register pipeline: the loads of the next chunk are in flight while the current one is
+// processed.  A row has at most one partial chunk (its last); the wave that owns it handles it after its
+// whole chunks.
+template <int DT, int NW, class Proc>
+__device__ __forceinline__ void stream_chunks(const u4v* rowv, int V, int c_begin, int c_end, Proc&& proc) {
     constexpr int EPV = Traits<DT>::EPV;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int n_whole = V / chunk_elems<DT>();
     const int hot_end = min(c_end, n_whole);
     int c = c_begin + wave;
-    float r, s;
     if (c < hot_end) {
         ChunkRegs a, b;
         load_chunk_whole(rowv, c, lane, a);
         while (true) {
             if (c + NW >= hot_end) {
-                reduce_chunk<DT, MASKED, true>(a, c, lane, V, cs, dl, bits, r, s);
-                sink(c, r, s);
+                proc(a, c, std::true_type());
                 c += NW;
                 break;
             }
             load_chunk_whole(rowv, c + NW, lane, b);
-            reduce_chunk<DT, MASKED, true>(a, c, lane, V, cs, dl, bits, r, s);
-            sink(c, r, s);
+            proc(a, c, std::true_type());
             c += NW;
             if (c + NW >= hot_end) {
-                reduce_chunk<DT, MASKED, true>(b, c, lane, V, cs, dl, bits, r, s);
-                sink(c, r, s);
+                proc(b, c, std::true_type());
                 c += NW;
                 break;
             }
             load_chunk_whole(rowv, c + NW, lane, a);
-            reduce_chunk<DT, MASKED, true>(b, c, lane, V, cs, dl, bits, r, s);
-            sink(c, r, s);
+            proc(b, c, std::true_type());
             c += NW;
         }
     }
     if (c < c_end) {  // c == n_whole: the partial chunk
         ChunkRegs t;
         load_chunk_tail<DT>(rowv, c, lane, (V + EPV - 1) / EPV, t);
-        reduce_chunk<DT, MASKED, false>(t, c, lane, V, cs, dl, bits, r, s);
-        sink(c, r, s);
+        proc(t, c, std::false_type());
     }
+}
+
+// the softmax scan: every chunk reduced to (ref, s) and handed to `sink(c, ref, s)`
+template <int DT, bool MASKED, int NW, class Sink>
+__device__ __forceinline__ void scan_chunks(const u4v* rowv, int V, int c_begin, int c_end, float cs, float dl,
+                                            const uint64_t* bits, Sink&& sink) {
+    const int lane = threadIdx.x & 63;
+    stream_chunks<DT, NW>(rowv, V, c_begin, c_end, [&](const ChunkRegs& r, int c, auto whole) {
+        float ref, sum;
+        reduce_chunk<DT, MASKED, decltype(whole)::value>(r, c, lane, V, cs, dl, bits, ref, sum);
+        sink(c, ref, sum);
+    });
 }
 
 // 2^((a-b) * c_true/c) for integer-valued references a <= b (or -inf / +inf), with c_true/c = 1 + delta and
@@ -372,7 +377,7 @@ __device__ __forceinline__ void table_scan(const u4v* rowv, int split, int V, in
     });
 }
 
-template <int DT>
+template <int DT, bool MASKED>
 __global__ __launch_bounds__(kWG) void k_draft_scan(const void* __restrict__ logits, int64_t row_stride, int V,
                                                      int nC, int cps, int nsplit, float cs, double ratio,
                                                      const uint64_t* __restrict__ bits, float* __restrict__ tab_ref,
@@ -380,7 +385,7 @@ __global__ __launch_bounds__(kWG) void k_draft_scan(const void* __restrict__ log
     const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
                                                     (int64_t)row * row_stride * Traits<DT>::ESZ);
-    table_scan<DT, true>(rowv, split, V, nC, cps, cs, ratio, bits, tab_ref + (int64_t)row * nC,
+    table_scan<DT, MASKED>(rowv, split, V, nC, cps, cs, ratio, bits, tab_ref + (int64_t)row * nC,
                          tab_s + (int64_t)row * nC);
 }
 
@@ -536,33 +541,37 @@ struct DraftOut {
     int64_t stride;  // entry of row r of every per-row array (u_draft included) is at index r * stride
 };
 
-template <int DT>
+// MASKED: the row is restricted to the shared ids (TLI's q').  Unmasked, the same code draws from the plain
+// softmax of a row of any vocabulary: the union algorithm's draft (d2t then marks tokens outside T with -1)
+// and the one-token-per-target-row draw of exact matching (d2t and tok_t null).
+template <int DT, bool MASKED>
 __device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V, int nC, float cs, double c_ratio,
                                       double inv_temp, const uint64_t* bits, const int32_t* d2t, const float* tr,
                                       const float* ts, const DraftOut& o) {
     float M;
     double total;
     const int64_t at = (int64_t)row * o.stride;
-    const int d = sample_softmax_row<DT, true>(rowp, V, nC, cs, c_ratio, bits, tr, ts, (double)o.u_draft[at], &M, &total);
+    const int d = sample_softmax_row<DT, MASKED>(rowp, V, nC, cs, c_ratio, bits, tr, ts, (double)o.u_draft[at], &M, &total);
     if ((threadIdx.x & 63) != 0) return;
-    if (d < 0) {  // no usable mass: NaN/+inf among the shared logits, or all of them -inf
+    if (d < 0) {  // no usable mass: NaN/+inf among the logits that take part, or all of them -inf
         const bool nonfinite = (total != total);
-        o.tok_d[at] = -1; o.tok_t[at] = -1;
+        o.tok_d[at] = -1;
+        if (o.tok_t) o.tok_t[at] = -1;
         if (o.q_tok) o.q_tok[at] = 0.0;
-        o.lse_q[at] = nonfinite ? NAN : -INFINITY;
+        if (o.lse_q) o.lse_q[at] = nonfinite ? NAN : -INFINITY;
         o.row_status[at] = nonfinite ? TLI_FLAG_NONFINITE : TLI_FLAG_ZERO_MASS;
         return;
     }
     const double lse = kLn2 * ((double)M * c_ratio + log2(total));
     o.tok_d[at] = d;
-    o.tok_t[at] = d2t[d];
-    o.lse_q[at] = lse;
+    if (o.tok_t) o.tok_t[at] = d2t ? d2t[d] : d;
+    if (o.lse_q) o.lse_q[at] = lse;
     if (o.q_tok) o.q_tok[at] = exp((double)load_elem<DT>(rowp, d) * inv_temp - lse);
     o.row_status[at] = 0;
 }
 
 // kernel: sampler of the split path (rows cut over several workgroups by k_draft_scan).  grid (R), one wave.
-template <int DT>
+template <int DT, bool MASKED>
 __global__ __launch_bounds__(kWave) void k_draft_pick(const void* __restrict__ logits, int64_t row_stride, int V,
                                                      int nC, float cs, double c_ratio, double inv_temp,
                                                      const uint64_t* __restrict__ bits,
@@ -571,14 +580,14 @@ __global__ __launch_bounds__(kWave) void k_draft_pick(const void* __restrict__ l
                                                      const float* __restrict__ tab_s, DraftOut o) {
     const int row = blockIdx.x;
     const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
-    draft_pick_row<DT>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tab_ref + (int64_t)row * nC,
+    draft_pick_row<DT, MASKED>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tab_ref + (int64_t)row * nC,
                        tab_s + (int64_t)row * nC, o);
 }
 
 // kernel: one workgroup per drafter row scans it into a chunk table in LDS and samples from it at
 // once (by its first wave), while the other workgroups on the CU keep streaming their rows.
 // grid (R); nC <= kLdsChunks.
-template <int DT>
+template <int DT, bool MASKED>
 __global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ logits, int64_t row_stride, int V,
                                                       int nC, float cs, double c_ratio, double inv_temp,
                                                       const uint64_t* __restrict__ bits,
@@ -586,10 +595,10 @@ __global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ lo
     __shared__ float tr[kLdsChunks], ts[kLdsChunks];
     const int row = blockIdx.x;
     const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
-    table_scan<DT, true>(reinterpret_cast<const u4v*>(rowp), 0, V, nC, nC, cs, c_ratio, bits, tr, ts);
+    table_scan<DT, MASKED>(reinterpret_cast<const u4v*>(rowp), 0, V, nC, nC, cs, c_ratio, bits, tr, ts);
     __syncthreads();
     if (threadIdx.x >= kWave) return;  // the first wave samples; the others retire and free their slots
-    draft_pick_row<DT>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tr, ts, o);
+    draft_pick_row<DT, MASKED>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tr, ts, o);
 }
 
 // ---- what the final kernels need to know about a sequence, written once by the accept kernel ----
@@ -602,6 +611,9 @@ struct FinalRow {
     int skip;       // sequence is flagged NONFINITE
     int bonus;      // nothing rejected: sample from p of row K
     int n;          // accepted count = index of the row the extra token comes from
+    int t_row;      // that row in the target tensor (dense row index), and its partner in the drafter tensor
+    int d_row;
+    float dq;       // diagnostics only: log2 q'(x) - log2 q(x) = (lse_q over D - lse_q over T∩D) * log2 e >= 0
     ResidualParams rp;
     double l2p;     // lse_p of row n, in log2 units
 };
@@ -631,7 +643,7 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
                                                    uint8_t* __restrict__ accept, double* __restrict__ p_tok,
                                                    double* __restrict__ q_tok, double* __restrict__ lse_p,
                                                    int32_t* __restrict__ seq_status, double* __restrict__ ws_lse_p, double c_t,
-                                                   double c_d, FinalRow* __restrict__ frow, int32_t* __restrict__ fbad) {
+                                                   double c_d, FinalRow* __restrict__ frow, int32_t* __restrict__ fbad, int union_mode) {
     const int b = blockIdx.x, k = threadIdx.x;
     bool acc = true, nonfinite = false, bad = false;
     int tt = -1;
@@ -647,14 +659,19 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
         my_lq = lse_q[row];
         double pd = 0.0, qd = 0.0;
         acc = false;
-        if (d < 0 || d >= Vd || d2t[d] < 0) {
+        // TLI: a draft must be a shared drafter id.  Union algorithm: any drafter id is a legal draft; one
+        // outside T has target probability 0 and is rejected by the test itself; every drafter logit takes
+        // part there, so a NaN normaliser (NaN/+inf somewhere in the row) flags the sequence.
+        if (d < 0 || d >= Vd || (!union_mode && d2t[d] < 0)) {
             bad = true;
+        } else if (union_mode && my_lq != my_lq) {
+            nonfinite = true;
         } else if (!nonfinite) {
             tt = d2t[d];
             const char* lt = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + k) * Vt * Traits<DT>::ESZ;
             const char* ld = static_cast<const char*>(logits_d) + row * Vd * Traits<DT>::ESZ;
-            pd = (lse == -INFINITY) ? 0.0 : exp((double)load_elem<DT>(lt, tt) * inv_temp_t - lse);
-            qd = exp((double)load_elem<DT>(ld, d) * inv_temp_d - my_lq);
+            pd = (tt < 0 || lse == -INFINITY) ? 0.0 : exp((double)load_elem<DT>(lt, tt) * inv_temp_t - lse);
+            qd = (union_mode && my_lq == -INFINITY) ? 0.0 : exp((double)load_elem<DT>(ld, d) * inv_temp_d - my_lq);
             acc = (double)u_acc[row] * qd < pd;
         }
         if (accept) accept[row] = acc ? 1 : 0;
@@ -681,6 +698,9 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
         f.skip = any_nonfinite ? 1 : 0;
         f.bonus = (!any_nonfinite && n == K) ? 1 : 0;
         f.n = n;
+        f.t_row = b * (K + 1) + (f.bonus ? K : n);
+        f.d_row = b * K + (f.bonus ? 0 : n);
+        f.dq = 0.f;
         f.l2p = 0.0;
         f.rp.use_q = 0;
         f.rp.ct_hi = f.rp.ct_lo = f.rp.lp_hi = f.rp.lp_lo = 0.f;
@@ -766,7 +786,7 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
                                                const int32_t* fbad, const FinalOut& o) {
     constexpr int EPV = Traits<DT>::EPV;
     const int lane = threadIdx.x & 63;
-    const char* rowp = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + f.n) * Vt * Traits<DT>::ESZ;
+    const char* rowp = static_cast<const char*>(logits_t) + (int64_t)f.t_row * Vt * Traits<DT>::ESZ;
     const double u = (double)o.u_fin[b];
     int tok = -1;
     int add_flags = 0;
@@ -779,9 +799,9 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
         if (tok < 0) nonfinite = true;
         else if (lane == 0 && o.lse_p) o.lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
     } else {
-        const char* ldp = static_cast<const char*>(logits_d) + ((int64_t)b * K + f.n) * Vd * Traits<DT>::ESZ;
+        const char* ldp = static_cast<const char*>(logits_d) + (int64_t)f.d_row * Vd * Traits<DT>::ESZ;
         // chunk masses: sum_chunk p (from the normaliser kernel's table of row n) minus the parts' sums of min(p, q')
-        const float2* crow = ctab + ((int64_t)b * K + f.n) * nC;
+        const float2* crow = ctab + (int64_t)f.d_row * nC;
         auto p_mass = [&](int cc) {
             const float2 rs = crow[cc];
             return (rs.x == -INFINITY) ? 0.0 : (double)rs.y * exp2((double)rs.x * ratio_t - f.l2p);
@@ -873,12 +893,16 @@ constexpr int kWaitVm0 = 0x0F70;       // s_waitcnt vmcnt(0) alone (expcnt and l
 constexpr int kPairShift = 12;         // entry = byte offset in chunk (< 4096) | byte offset in part << 12
 template <int DT> constexpr int part_cap() { return kPartBytes / Traits<DT>::ESZ; }
 
-template <int DT>
+// DIAG (acceptance-rate diagnostics): the items are all B*K positions instead of one row per sequence, and a
+// second sum runs beside the first with the drafter's unrestricted probabilities q = q' * 2^-dq:
+// mn = sum min(p, q') (TLI's expected acceptance rate), mn2 = sum min(p, q) (the union algorithm's).
+template <int DT, bool DIAG>
 __global__ __launch_bounds__(kScanWG) void k_final_scan(
     const void* __restrict__ logits_t, const void* __restrict__ logits_d, int B, int K, int Vt, int Vd, int nC,
     int nparts, int nsplit, int per, int S, float cs_t, double ratio_t, const FinalRow* __restrict__ frow,
     const int32_t* __restrict__ sh_x, const int32_t* __restrict__ pl_start, const uint32_t* __restrict__ pl_e,
-    float* __restrict__ tab_ref, float* __restrict__ tab_s, double* __restrict__ mn, int32_t* __restrict__ fbad) {
+    float* __restrict__ tab_ref, float* __restrict__ tab_s, double* __restrict__ mn, double* __restrict__ mn2,
+    int32_t* __restrict__ fbad) {
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int ESZ = Traits<DT>::ESZ;
     constexpr int CH = chunk_elems<DT>();
@@ -899,8 +923,7 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     if (f.bonus) {
-        const u4v* rowk = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
-                                                        ((int64_t)b * (K + 1) + K) * Vt * ESZ);
+        const u4v* rowk = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) + (int64_t)f.t_row * Vt * ESZ);
         float* br = tab_ref + (int64_t)b * nC;
         float* bs = tab_s + (int64_t)b * nC;
         const int cps = (nC + per_seq - 1) / per_seq;
@@ -912,9 +935,9 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     }
     if (!f.rp.use_q) return;  // q' = 0 everywhere: the masses are the chunk sums of p, nothing to subtract
     const raw_t* ld_row =
-        reinterpret_cast<const raw_t*>(static_cast<const char*>(logits_d) + ((int64_t)b * K + f.n) * Vd * ESZ);
+        reinterpret_cast<const raw_t*>(static_cast<const char*>(logits_d) + (int64_t)f.d_row * Vd * ESZ);
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
-                                                    ((int64_t)b * (K + 1) + f.n) * Vt * ESZ);
+                                                    (int64_t)f.t_row * Vt * ESZ);
     const int nvec = (Vt + EPV - 1) / EPV;
     const int32_t* my_start = pl_start + (int64_t)p * nC;
 
@@ -958,23 +981,29 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     const char* dbase = reinterpret_cast<const char*>(dpart);
     // min(p, q') of one pair = 2^min(log2 p, log2 q'): one exponential per pair.  An entry read through a
     // clamped index is some other valid pair (in-range offsets); the caller drops its value.
-    auto pair_min = [&](uint32_t e) -> float {
+    const float dq = f.dq;
+    auto pair_min = [&](uint32_t e, float& second) -> float {
         const uint32_t xr = *reinterpret_cast<const raw_t*>(tslot + (e & ((1u << kPairShift) - 1u)));
         const uint32_t yr = *reinterpret_cast<const raw_t*>(dbase + (e >> kPairShift));
         const float xv = as_f(DT == TLI_BF16 ? xr << 16 : xr), yv = as_f(DT == TLI_BF16 ? yr << 16 : yr);
         const float a = fmaf(xv, rp.ct_hi, -rp.lp_hi) + fmaf(xv, rp.ct_lo, -rp.lp_lo);
         const float bq = fmaf(yv, rp.cd_hi, -rp.lq_hi) + fmaf(yv, rp.cd_lo, -rp.lq_lo);
+        if (DIAG) second = exp2_hw(fminf(a, bq - dq));
         return exp2_hw(fminf(a, bq));
     };
     const int gw = sp * kScanWaves + wave, stride = nsplit * kScanWaves;
     // Results stay in registers until the wave is through (lane i keeps the sum of the wave's i-th chunk):
     // a store shares the loads' completion counter and completes out of order with them, so while one may
     // be pending every wait for a load degrades to a wait for all loads.
-    double keep = 0.0;
+    double keep = 0.0, keep2 = 0.0;
     int it = 0;
+    double* my_mn2 = DIAG ? mn2 + ((int64_t)p * B + b) * nC : nullptr;
     auto flush = [&](int first_it, int n) {
         const int c = gw + (first_it + lane) * stride;
-        if (lane < n && c < nC) my_mn[c] = keep;
+        if (lane < n && c < nC) {
+            my_mn[c] = keep;
+            if (DIAG) my_mn2[c] = keep2;
+        }
     };
     int ns0 = 0, ns1 = 0;  // list bounds of the next chunk, fetched one chunk ahead
     if (gw < nC) { ns0 = my_start[gw]; ns1 = my_start[gw + 1]; }
@@ -997,25 +1026,37 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         // one wave writes and reads its slot: its LDS operations execute in order and the compiler keeps
         // may-alias accesses in program order; the wave barrier only pins the schedule
         __builtin_amdgcn_wave_barrier();
-        float m[kPairU];
+        float m[kPairU], m2[kPairU];
 #pragma unroll
         for (int k = 0; k < kPairU; ++k) {
-            const float t = pair_min(e[k]);
-            m[k] = (s0 + k * kWave + lane < s1) ? t : 0.f;
+            float t2 = 0.f;
+            const float t = pair_min(e[k], t2);
+            const bool live = s0 + k * kWave + lane < s1;
+            m[k] = live ? t : 0.f;
+            m2[k] = live ? t2 : 0.f;
         }
 #pragma unroll
         for (int w = 1; w < kPairU; w <<= 1)  // the lane's few terms: pairwise in fp32, everything after in fp64
 #pragma unroll
-            for (int k = 0; k + w < kPairU; k += 2 * w) m[k] += m[k + w];
-        double acc = (double)m[0];
+            for (int k = 0; k + w < kPairU; k += 2 * w) {
+                m[k] += m[k + w];
+                if (DIAG) m2[k] += m2[k + w];
+            }
+        double acc = (double)m[0], acc2 = (double)m2[0];
         for (int i0 = s0 + kPairU * kWave; i0 < s1; i0 += kWave) {  // crowded chunk: the rest of its list
             const int i = i0 + lane;
-            const float t = pair_min(pl_e[min(i, S - 1)]);
+            float t2 = 0.f;
+            const float t = pair_min(pl_e[min(i, S - 1)], t2);
             acc += (double)(i < s1 ? t : 0.f);
+            if (DIAG) acc2 += (double)(i < s1 ? t2 : 0.f);
         }
         __builtin_amdgcn_wave_barrier();  // the slot is rewritten by the next chunk
         acc = wave_sum_f64(acc);
         if (lane == (it & (kWave - 1))) keep = acc;
+        if (DIAG) {
+            acc2 = wave_sum_f64(acc2);
+            if (lane == (it & (kWave - 1))) keep2 = acc2;
+        }
         ++it;
         if ((it & (kWave - 1)) == 0) flush(it - kWave, kWave);  // only rows of more than 1024 chunks get here
     }
@@ -1038,6 +1079,220 @@ __global__ __launch_bounds__(kWave) void k_final_pick(const void* __restrict__ l
     if (f.skip) return;
     final_pick_row<DT>(f, b, logits_t, logits_d, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
                        tab_s + (int64_t)b * nC, ctab, mn + (int64_t)b * nC, nparts, (int64_t)B * nC, fbad, o);
+}
+
+// ---- expected acceptance rates of every position ------------------------------------------------
+// Table of expected acceptance rates: alpha_union = sum_{T∩D} min{p, q}, alpha_tli = sum_{T∩D} min{p, q'} with
+// q' = q / sum_{T∩D} q; the theorem on the intersection algorithm states alpha_union <= alpha_tli.
+// kernel: one record per position (b, k) from the three normalisers (target row, drafter row over the
+// shared ids, drafter row over all of D).  grid (ceil(rows / 256)).
+__global__ __launch_bounds__(kWG) void k_diag_rows(const Part* __restrict__ part_t, int nsplit_t,
+                                                    const Part* __restrict__ part_q1, const Part* __restrict__ part_q2,
+                                                    int nsplit_d, int rows, int K, double ratio_t, double ratio_d,
+                                                    double c_t, double c_d, FinalRow* __restrict__ frow,
+                                                    int32_t* __restrict__ fbad, int32_t* __restrict__ status) {
+    const int r = blockIdx.x * kWG + threadIdx.x;
+    if (r >= rows) return;
+    const int b = r / K, k = r - b * K;
+    const double lp = combine_parts(part_t + (int64_t)r * nsplit_t, nsplit_t, ratio_t);
+    const double lq1 = combine_parts(part_q1 + (int64_t)r * nsplit_d, nsplit_d, ratio_d);
+    const double lq2 = combine_parts(part_q2 + (int64_t)r * nsplit_d, nsplit_d, ratio_d);
+    const bool nonfinite = lp != lp || lq2 != lq2 || lq1 != lq1;
+    FinalRow f;
+    f.skip = nonfinite ? 1 : 0;
+    f.bonus = 0;
+    f.n = k;
+    f.t_row = b * (K + 1) + k;
+    f.d_row = r;
+    f.dq = 0.f;
+    f.l2p = 0.0;
+    f.rp.use_q = 0;
+    f.rp.ct_hi = f.rp.ct_lo = f.rp.lp_hi = f.rp.lp_lo = 0.f;
+    f.rp.cd_hi = f.rp.cd_lo = f.rp.lq_hi = f.rp.lq_lo = 0.f;
+    if (!nonfinite && lp > -INFINITY && lq1 > -INFINITY) {
+        f.rp.use_q = 1;
+        f.l2p = lp * kLog2e;
+        split_scale(c_t, f.rp.ct_hi, f.rp.ct_lo);
+        split_hi_lo(f.l2p, f.rp.lp_hi, f.rp.lp_lo);
+        split_scale(c_d, f.rp.cd_hi, f.rp.cd_lo);
+        split_hi_lo(lq1 * kLog2e, f.rp.lq_hi, f.rp.lq_lo);
+        f.dq = (float)((lq2 - lq1) * kLog2e);
+    }
+    frow[r] = f;
+    fbad[r] = 0;
+    status[r] = nonfinite ? TLI_FLAG_NONFINITE : (lq1 == -INFINITY ? TLI_FLAG_ZERO_MASS : 0);
+}
+
+// kernel: alpha of every position = sum over parts and chunks of the scan's partial sums.  grid (rows), one wave.
+__global__ __launch_bounds__(kWave) void k_diag_finish(const FinalRow* __restrict__ frow, const double* __restrict__ mn,
+                                                        const double* __restrict__ mn2, int rows, int nparts, int nC,
+                                                        double* __restrict__ alpha_tli, double* __restrict__ alpha_union) {
+    const int r = blockIdx.x, lane = threadIdx.x;
+    const FinalRow f = frow[r];
+    double a1 = 0.0, a2 = 0.0;
+    if (f.skip) {
+        a1 = a2 = NAN;
+    } else if (f.rp.use_q) {
+        for (int p = 0; p < nparts; ++p) {
+            const double* m1 = mn + ((int64_t)p * rows + r) * nC;
+            const double* m2 = mn2 + ((int64_t)p * rows + r) * nC;
+            for (int c = lane; c < nC; c += kWave) { a1 += m1[c]; a2 += m2[c]; }
+        }
+        a1 = wave_sum_f64(a1);
+        a2 = wave_sum_f64(a2);
+    }
+    if (lane == 0) { alpha_tli[r] = a1; alpha_union[r] = a2; }
+}
+
+// ---- temperature zero: argmax of rows ----------------------------------------------------------
+// At temperature zero every draw of the path becomes an argmax (the paper runs its exact-matching method
+// that way): the largest logit, the lowest id among equal ones.  Same streaming scan as the softmax
+// kernels.  Per chunk a lane only takes the maximum of its 32 elements and remembers the chunk it came
+// from; the id is found at the end by re-reading that one chunk (4 vectors per lane).  MASKED: only the
+// shared ids compete (greedy TLI draft).  NaN or +inf among the competing logits flags the row.
+struct ArgPart {  // best of (a split of) a row
+    float v;
+    int32_t idx;   // -1: nothing competes / everything -inf
+    int32_t bad;   // a competing logit is NaN or +inf
+    int32_t pad;
+};
+
+template <int DT, bool MASKED, bool WHOLE>
+__device__ __forceinline__ void chunk_values(const ChunkRegs& r, int c, int lane, int V, const uint64_t* bits, float* x) {
+    constexpr int EPV = Traits<DT>::EPV;
+    const int64_t v0 = (int64_t)c * (kWave * kLoads) + lane;
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+        unpack<DT>(to_uint4(r.v[j]), x + j * EPV);
+        const int64_t vi = v0 + j * kWave;
+        if (!WHOLE) {
+#pragma unroll
+            for (int i = 0; i < EPV; ++i)
+                if (vi * EPV + i >= V) x[j * EPV + i] = -INFINITY;
+        }
+        if (MASKED) {
+            const uint64_t* w = bits + ((int64_t)c * kLoads + j) * EPV;
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) {
+                const bool keep = __builtin_amdgcn_inverse_ballot_w64(w[i]);
+                x[j * EPV + i] = keep ? x[j * EPV + i] : -INFINITY;
+            }
+        }
+    }
+}
+
+template <int DT, bool MASKED>
+__global__ __launch_bounds__(kWG) void k_argmax(const void* __restrict__ logits, int64_t row_stride, int V, int nC,
+                                                 int cps, int nsplit, const uint64_t* __restrict__ bits,
+                                                 ArgPart* __restrict__ part) {
+    constexpr int EPV = Traits<DT>::EPV;
+    constexpr int N = EPV * kLoads;
+    const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
+    const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
+    const u4v* rowv = reinterpret_cast<const u4v*>(rowp);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    float best = -INFINITY;
+    int bc = -1;
+    bool bad = false;
+    stream_chunks<DT, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), [&](const ChunkRegs& r, int c, auto whole) {
+        float x[N];
+        chunk_values<DT, MASKED, decltype(whole)::value>(r, c, lane, V, bits, x);
+        float m = x[0];
+        bool nan = x[0] != x[0];
+#pragma unroll
+        for (int i = 1; i < N; ++i) {
+            m = fmaxf(m, x[i]);
+            nan |= x[i] != x[i];
+        }
+        bad |= nan;
+        if (m > best) { best = m; bc = c; }  // strict: an equal maximum in a later chunk has a higher id
+    });
+    bad |= best == INFINITY;
+    // the id of the lane's maximum: first element equal to it in the chunk it came from
+    int idx = 0x7fffffff;
+    if (bc >= 0) {
+        ChunkRegs t;
+        load_chunk_tail<DT>(rowv, bc, lane, (V + EPV - 1) / EPV, t);
+        float x[N];
+        chunk_values<DT, MASKED, false>(t, bc, lane, V, bits, x);
+#pragma unroll
+        for (int j = kLoads - 1; j >= 0; --j)
+#pragma unroll
+            for (int i = EPV - 1; i >= 0; --i)
+                if (x[j * EPV + i] == best) idx = (int)((((int64_t)bc * kLoads + j) * kWave + lane) * EPV + i);
+    }
+    // wave: the largest value, then the lowest id among the lanes that hold it
+    const float M = wave_max(best);
+    int cand = (best == M && bc >= 0) ? idx : 0x7fffffff;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) cand = min(cand, __shfl_xor(cand, d, kWave));
+    const bool wbad = __ballot(bad) != 0ull;
+    __shared__ float sv[kWaves];
+    __shared__ int si[kWaves], sb[kWaves];
+    if (lane == 0) { sv[wave] = M; si[wave] = cand; sb[wave] = wbad ? 1 : 0; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        ArgPart a;
+        a.v = -INFINITY; a.idx = 0x7fffffff; a.bad = 0; a.pad = 0;
+        for (int w = 0; w < kWaves; ++w) {
+            a.bad |= sb[w];
+            if (sv[w] > a.v || (sv[w] == a.v && si[w] < a.idx)) { a.v = sv[w]; a.idx = si[w]; }
+        }
+        if (a.idx == 0x7fffffff) a.idx = -1;
+        part[(int64_t)row * nsplit + split] = a;
+    }
+}
+
+// kernel: argmax of every row from the partials of its splits.  grid (ceil(rows / 256)).
+// tok[r] = id (or -1), tok_t[r] = d2t[id] if both given, p_tok = 1, status = NONFINITE / ZERO_MASS / 0;
+// entry of row r at index r * io_stride.
+__global__ __launch_bounds__(kWG) void k_argmax_finish(const ArgPart* __restrict__ part, int rows, int nsplit,
+                                                        const int32_t* __restrict__ d2t, int32_t* __restrict__ tok,
+                                                        int32_t* __restrict__ tok_t, double* __restrict__ p_tok,
+                                                        double* __restrict__ lse, int32_t* __restrict__ status,
+                                                        int64_t io_stride) {
+    const int row = blockIdx.x * kWG + threadIdx.x;
+    if (row >= rows) return;
+    const ArgPart* pr = part + (int64_t)row * nsplit;
+    ArgPart a = pr[0];
+    for (int sidx = 1; sidx < nsplit; ++sidx) {
+        const ArgPart b = pr[sidx];
+        a.bad |= b.bad;
+        if (b.idx >= 0 && (a.idx < 0 || b.v > a.v || (b.v == a.v && b.idx < a.idx))) { a.v = b.v; a.idx = b.idx; }
+    }
+    const int64_t at = (int64_t)row * io_stride;
+    const int st = a.bad ? TLI_FLAG_NONFINITE : (a.idx < 0 || a.v == -INFINITY ? TLI_FLAG_ZERO_MASS : 0);
+    const int id = st ? -1 : a.idx;
+    tok[at] = id;
+    if (tok_t) tok_t[at] = (id >= 0 && d2t) ? d2t[id] : id;
+    if (p_tok) p_tok[at] = st ? 0.0 : 1.0;
+    if (lse) lse[at] = NAN;
+    status[at] = st;
+}
+
+// ---- kernel: first mismatch between the target's own tokens and the re-tokenised draft -----------
+// Exact-matching verification (string-level exact match, its last two steps): j* = first j with
+// t'_j != draft_j, output draft_1..draft_{j*-1}, t'_{j*}.  grid (B), 64 threads; lane j owns position j.
+__global__ __launch_bounds__(kWave) void k_match(const int32_t* __restrict__ tgt_tok, const int32_t* __restrict__ row_status,
+                                                  const int32_t* __restrict__ draft_t, int m,
+                                                  int32_t* __restrict__ n_accepted, int32_t* __restrict__ out_tok,
+                                                  int32_t* __restrict__ seq_status) {
+    const int b = blockIdx.x, j = threadIdx.x;
+    int st = 0, tt = -1, dr = -1;
+    if (j <= m) {
+        st = row_status[(int64_t)b * (m + 1) + j];
+        tt = tgt_tok[(int64_t)b * (m + 1) + j];
+    }
+    if (j < m) dr = draft_t[(int64_t)b * m + j];
+    int any = st;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) any |= __shfl_xor(any, d, kWave);
+    const bool differs = (j < m) ? (dr < 0 || dr != tt) : (j == m);
+    const unsigned long long mism = __ballot(differs);
+    const int n = any ? 0 : (int)__builtin_ctzll(mism);  // bit m is always set
+    if (j <= m) out_tok[(int64_t)b * (m + 1) + j] = any ? -1 : (j < n ? dr : (j == n ? tt : -1));
+    if (j == 0) { n_accepted[b] = n; seq_status[b] = any; }
 }
 
 // ---- plain copy, used only to calibrate hardware byte counters against a known size -----------
@@ -1131,10 +1386,11 @@ struct KernelTimer {  // records start on construction, stop on destruction, if 
     }
 };
 
-template <int DT>
-void launch_draft(const tli_map* map, const void* logits_d, int64_t row_stride, int R, float temp_d, const Plan& pl,
-                  float cs, double ratio, const float* u_draft, int32_t* tok_d, int32_t* tok_t, double* q_tok,
-                  double* lse_q, int32_t* row_status, int64_t io_stride, float* tab_ref, float* tab_s, hipStream_t st);
+struct DraftOut;
+template <int DT, bool MASKED>
+void launch_draft(const void* logits, int64_t row_stride, int R, int V, float temp, const Plan& pl, float cs,
+                  double ratio, const uint64_t* bits, const int32_t* d2t, const DraftOut& o, float* tab_ref,
+                  float* tab_s, hipStream_t st);
 
 struct VerifyArgs {
     const tli_map* map;
@@ -1160,6 +1416,7 @@ struct VerifyArgs {
     float2* ctab;
     FinalRow* frow;
     int32_t* fbad;
+    int union_mode;  // 0: TLI (q' over the shared ids); 1: the union algorithm (q over all of D)
 };
 template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st);
 
@@ -1183,31 +1440,115 @@ struct tli_map {
 
 namespace {
 
-template <int DT>
-void launch_draft(const tli_map* map, const void* logits_d, int64_t row_stride, int R, float temp_d, const Plan& pl,
-                  float cs, double ratio, const float* u_draft, int32_t* tok_d, int32_t* tok_t, double* q_tok,
-                  double* lse_q, int32_t* row_status, int64_t io_stride, float* tab_ref, float* tab_s, hipStream_t st) {
-    const int Vd = map->Vd;
-    DraftOut o;
-    o.u_draft = u_draft; o.tok_d = tok_d; o.tok_t = tok_t; o.q_tok = q_tok; o.lse_q = lse_q; o.row_status = row_status;
-    o.stride = io_stride;
-    const double inv_temp = 1.0 / (double)temp_d;
+template <int DT, bool MASKED>
+void launch_draft(const void* logits, int64_t row_stride, int R, int V, float temp, const Plan& pl, float cs,
+                  double ratio, const uint64_t* bits, const int32_t* d2t, const DraftOut& o, float* tab_ref,
+                  float* tab_s, hipStream_t st) {
+    const double inv_temp = 1.0 / (double)temp;
     if (pl.nsplit == 1 && pl.nC <= kLdsChunks) {  // enough rows to fill the chip with one workgroup per row
         KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
-        hipLaunchKernelGGL(k_draft_fused<DT>, dim3(R), dim3(kWG), 0, st, logits_d, row_stride, Vd, pl.nC, cs, ratio,
-                           inv_temp, map->lmask[DT], map->d2t, o);
+        hipLaunchKernelGGL((k_draft_fused<DT, MASKED>), dim3(R), dim3(kWG), 0, st, logits, row_stride, V, pl.nC, cs, ratio,
+                           inv_temp, bits, d2t, o);
         return;
     }
     {
         KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
-        hipLaunchKernelGGL(k_draft_scan<DT>, dim3((unsigned)R * pl.nsplit), dim3(kWG), 0, st, logits_d, row_stride, Vd,
-                           pl.nC, pl.cps, pl.nsplit, cs, ratio, map->lmask[DT], tab_ref, tab_s);
+        hipLaunchKernelGGL((k_draft_scan<DT, MASKED>), dim3((unsigned)R * pl.nsplit), dim3(kWG), 0, st, logits, row_stride,
+                           V, pl.nC, pl.cps, pl.nsplit, cs, ratio, bits, tab_ref, tab_s);
     }
     {
         KernelTimer t(TLI_KERNEL_DRAFT_PICK, st);
-        hipLaunchKernelGGL(k_draft_pick<DT>, dim3(R), dim3(kWave), 0, st, logits_d, row_stride, Vd, pl.nC, cs, ratio,
-                           inv_temp, map->lmask[DT], map->d2t, tab_ref, tab_s, o);
+        hipLaunchKernelGGL((k_draft_pick<DT, MASKED>), dim3(R), dim3(kWave), 0, st, logits, row_stride, V, pl.nC, cs, ratio,
+                           inv_temp, bits, d2t, tab_ref, tab_s, o);
     }
+}
+
+// One token per row from softmax(logits / temp), restricted to the shared ids if `bits` is given: argument
+// checks, plan, scratch carving and launch shared by the draft entry points and the plain row sampler.
+int sample_rows_impl(const void* logits, int dtype, int64_t row_stride, int R, int V, float temp, uint64_t* const* bits2,
+                     const int32_t* d2t, const float* u, int32_t* tok, int32_t* tok_t, double* p_tok, double* lse,
+                     int32_t* status, int64_t io_stride, void* workspace, size_t workspace_bytes, hipStream_t st) {
+    if (!logits || !u || !tok || !status || !workspace) return TLI_ERR_INVALID_ARG;
+    if (R < 1 || R > 0x7fffffff / 64 || V < 1 || !(temp > 0.f) || !std::isfinite(temp) || io_stride < 1)
+        return TLI_ERR_INVALID_ARG;
+    if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
+    const int epv = dtype == TLI_BF16 ? 8 : 4;
+    if (row_stride < V || row_stride % epv != 0 || !aligned16(logits) || !aligned16(workspace)) return TLI_ERR_INVALID_ARG;
+    const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
+    Plan pl = make_plan(V, R, chunk);
+    // from 4 workgroups per CU on, a row per workgroup (scan and draw in one kernel) beats splitting rows
+    if (R >= 1024 && pl.nC <= kLdsChunks) { pl.nsplit = 1; pl.cps = pl.nC; }
+    const size_t tab_bytes = align256((size_t)R * pl.nC * sizeof(float));
+    if (workspace_bytes < 2 * tab_bytes) return TLI_ERR_ALLOC;
+    float* tab_ref = reinterpret_cast<float*>(workspace);
+    float* tab_s = reinterpret_cast<float*>(static_cast<char*>(workspace) + tab_bytes);
+    const double c_true = kLog2e / (double)temp;
+    const float cs = (float)c_true;
+    const double ratio = c_true / (double)cs;
+    DraftOut o;
+    o.u_draft = u; o.tok_d = tok; o.tok_t = tok_t; o.q_tok = p_tok; o.lse_q = lse; o.row_status = status;
+    o.stride = io_stride;
+    if (bits2) {
+        if (dtype == TLI_BF16)
+            launch_draft<TLI_BF16, true>(logits, row_stride, R, V, temp, pl, cs, ratio, bits2[TLI_BF16], d2t, o, tab_ref, tab_s, st);
+        else
+            launch_draft<TLI_F32, true>(logits, row_stride, R, V, temp, pl, cs, ratio, bits2[TLI_F32], d2t, o, tab_ref, tab_s, st);
+    } else {
+        if (dtype == TLI_BF16)
+            launch_draft<TLI_BF16, false>(logits, row_stride, R, V, temp, pl, cs, ratio, nullptr, d2t, o, tab_ref, tab_s, st);
+        else
+            launch_draft<TLI_F32, false>(logits, row_stride, R, V, temp, pl, cs, ratio, nullptr, d2t, o, tab_ref, tab_s, st);
+    }
+    return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
+}
+
+// argmax of R rows (temperature zero); `bits2` restricts the competition to the shared ids.
+int argmax_rows_impl(const void* logits, int dtype, int64_t row_stride, int R, int V, uint64_t* const* bits2,
+                     const int32_t* d2t, int32_t* tok, int32_t* tok_t, double* p_tok, double* lse, int32_t* status,
+                     int64_t io_stride, void* workspace, size_t workspace_bytes, hipStream_t st) {
+    if (!logits || !tok || !status || !workspace) return TLI_ERR_INVALID_ARG;
+    if (R < 1 || R > 0x7fffffff / 64 || V < 1 || io_stride < 1) return TLI_ERR_INVALID_ARG;
+    if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
+    const int epv = dtype == TLI_BF16 ? 8 : 4;
+    if (row_stride < V || row_stride % epv != 0 || !aligned16(logits) || !aligned16(workspace)) return TLI_ERR_INVALID_ARG;
+    const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
+    const Plan pl = make_plan(V, R, chunk);
+    if (workspace_bytes < (size_t)R * pl.nsplit * sizeof(ArgPart)) return TLI_ERR_ALLOC;
+    ArgPart* part = reinterpret_cast<ArgPart*>(workspace);
+    const dim3 grid((unsigned)R * pl.nsplit);
+    {
+        KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
+        if (bits2) {
+            if (dtype == TLI_BF16)
+                hipLaunchKernelGGL((k_argmax<TLI_BF16, true>), grid, dim3(kWG), 0, st, logits, row_stride, V, pl.nC, pl.cps,
+                                   pl.nsplit, bits2[TLI_BF16], part);
+            else
+                hipLaunchKernelGGL((k_argmax<TLI_F32, true>), grid, dim3(kWG), 0, st, logits, row_stride, V, pl.nC, pl.cps,
+                                   pl.nsplit, bits2[TLI_F32], part);
+        } else {
+            if (dtype == TLI_BF16)
+                hipLaunchKernelGGL((k_argmax<TLI_BF16, false>), grid, dim3(kWG), 0, st, logits, row_stride, V, pl.nC, pl.cps,
+                                   pl.nsplit, (const uint64_t*)nullptr, part);
+            else
+                hipLaunchKernelGGL((k_argmax<TLI_F32, false>), grid, dim3(kWG), 0, st, logits, row_stride, V, pl.nC, pl.cps,
+                                   pl.nsplit, (const uint64_t*)nullptr, part);
+        }
+    }
+    {
+        KernelTimer t(TLI_KERNEL_DRAFT_PICK, st);
+        hipLaunchKernelGGL(k_argmax_finish, dim3((R + kWG - 1) / kWG), dim3(kWG), 0, st, part, R, pl.nsplit, d2t, tok, tok_t,
+                           p_tok, lse, status, io_stride);
+    }
+    return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
+}
+
+// scratch of the row sampler / argmax for R rows of V entries
+size_t rows_workspace(int R, int V, int dtype) {
+    const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
+    const Plan pl = make_plan(V, R, chunk);
+    const size_t tabs = 2 * align256((size_t)R * pl.nC * sizeof(float));
+    const size_t parts = align256((size_t)R * pl.nsplit * sizeof(ArgPart));
+    return tabs > parts ? tabs : parts;
 }
 
 template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
@@ -1216,10 +1557,15 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     fo.u_fin = a.u_fin; fo.n_accepted = a.n_accepted; fo.out_tok = a.out_tok; fo.lse_p = a.lse_p;
     fo.seq_status = a.seq_status;
     const double* lse_q = a.lse_q;
-    if (!lse_q) {  // the caller did not keep the drafter normalisers: one masked scan of the drafter rows
-        hipLaunchKernelGGL((k_lse<DT, true>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), 0, st, a.logits_d, K,
-                           (int64_t)K * Vd, (int64_t)Vd, Vd, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d, a.ratio_d,
-                           a.map->lmask[DT], a.part_d, (float2*)nullptr);
+    if (!lse_q) {  // the caller did not keep the drafter normalisers: one scan of the drafter rows (masked for TLI)
+        if (a.union_mode)
+            hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), 0, st, a.logits_d, K,
+                               (int64_t)K * Vd, (int64_t)Vd, Vd, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d, a.ratio_d,
+                               (const uint64_t*)nullptr, a.part_d, (float2*)nullptr);
+        else
+            hipLaunchKernelGGL((k_lse<DT, true>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), 0, st, a.logits_d, K,
+                               (int64_t)K * Vd, (int64_t)Vd, Vd, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d, a.ratio_d,
+                               a.map->lmask[DT], a.part_d, (float2*)nullptr);
         hipLaunchKernelGGL(k_lse_finish, dim3((rows + kWG - 1) / kWG), dim3(kWG), 0, st, a.part_d, rows, a.pd.nsplit,
                            a.ratio_d, a.ws_lse_q);
         lse_q = a.ws_lse_q;
@@ -1235,7 +1581,7 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
         hipLaunchKernelGGL(k_accept<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pl.nsplit,
                            a.part, a.ratio_t, a.inv_t, a.inv_d, a.map->d2t, a.tok_d, lse_q, a.u_acc, a.n_accepted,
                            a.out_tok, a.accept, a.p_tok, a.q_tok, a.lse_p, a.seq_status, a.ws_lse_p, a.c_t, a.c_d, a.frow,
-                           a.fbad);
+                           a.fbad, a.union_mode);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_SCAN, st);
@@ -1243,10 +1589,10 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
         // few sequences: deal the chunks of a (sequence, part) to several workgroups, up to one per CU
         int nsplit = 256 / (B * nparts);
         nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
-        hipLaunchKernelGGL(k_final_scan<DT>, dim3((unsigned)((B + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0, st,
-                           a.logits_t, a.logits_d, B, K, Vt, Vd, a.pf.nC, nparts, nsplit, a.map->per[DT], a.map->S,
+        hipLaunchKernelGGL((k_final_scan<DT, false>), dim3((unsigned)((B + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0,
+                           st, a.logits_t, a.logits_d, B, K, Vt, Vd, a.pf.nC, nparts, nsplit, a.map->per[DT], a.map->S,
                            a.cs_t, a.ratio_t, a.frow, a.map->sh_x, a.map->pl_start[DT], a.map->pl_e[DT], a.tab_ref,
-                           a.tab_s, a.mn, a.fbad);
+                           a.tab_s, a.mn, (double*)nullptr, a.fbad);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
@@ -1256,6 +1602,63 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     }
 }
 
+}  // namespace
+
+namespace {
+struct DiagLayout { size_t part_t, part_q1, part_q2, frow, fbad, mn, mn2, total; };
+DiagLayout diag_layout(const tli_map* map, int B, int K, int dtype) {
+    const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
+    const int rows = B * K;
+    const Plan pt = make_plan(map->Vt, rows, chunk), pd = make_plan(map->Vd, rows, chunk);
+    DiagLayout w;
+    size_t off = 0;
+    w.part_t = off; off += align256((size_t)rows * pt.nsplit * sizeof(Part));
+    w.part_q1 = off; off += align256((size_t)rows * pd.nsplit * sizeof(Part));
+    w.part_q2 = off; off += align256((size_t)rows * pd.nsplit * sizeof(Part));
+    w.frow = off; off += align256((size_t)rows * sizeof(FinalRow));
+    w.fbad = off; off += align256((size_t)rows * sizeof(int32_t));
+    const size_t tab = (size_t)map->nparts[dtype] * rows * pt.nC * sizeof(double);
+    w.mn = off; off += align256(tab);
+    w.mn2 = off; off += align256(tab);
+    w.total = off;
+    return w;
+}
+
+template <int DT>
+void launch_diag(const tli_map* map, const void* logits_t, const void* logits_d, int B, int K, float temp_t, float temp_d,
+                 double* alpha_tli, double* alpha_union, int32_t* status, char* ws, const DiagLayout& w, hipStream_t st) {
+    const int Vt = map->Vt, Vd = map->Vd, rows = B * K;
+    const int chunk = chunk_elems<DT>();
+    const Plan pt = make_plan(Vt, rows, chunk), pd = make_plan(Vd, rows, chunk);
+    const double c_t = kLog2e / (double)temp_t, c_d = kLog2e / (double)temp_d;
+    const float cs_t = (float)c_t, cs_d = (float)c_d;
+    const double ratio_t = c_t / (double)cs_t, ratio_d = c_d / (double)cs_d;
+    Part* part_t = reinterpret_cast<Part*>(ws + w.part_t);
+    Part* part_q1 = reinterpret_cast<Part*>(ws + w.part_q1);
+    Part* part_q2 = reinterpret_cast<Part*>(ws + w.part_q2);
+    FinalRow* frow = reinterpret_cast<FinalRow*>(ws + w.frow);
+    int32_t* fbad = reinterpret_cast<int32_t*>(ws + w.fbad);
+    double* mn = reinterpret_cast<double*>(ws + w.mn);
+    double* mn2 = reinterpret_cast<double*>(ws + w.mn2);
+    hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * pt.nsplit), dim3(kWG), 0, st, logits_t, K,
+                       (int64_t)(K + 1) * Vt, (int64_t)Vt, Vt, pt.nC, pt.cps, pt.nsplit, cs_t, ratio_t,
+                       (const uint64_t*)nullptr, part_t, (float2*)nullptr);
+    hipLaunchKernelGGL((k_lse<DT, true>), dim3((unsigned)rows * pd.nsplit), dim3(kWG), 0, st, logits_d, K, (int64_t)K * Vd,
+                       (int64_t)Vd, Vd, pd.nC, pd.cps, pd.nsplit, cs_d, ratio_d, map->lmask[DT], part_q1, (float2*)nullptr);
+    hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * pd.nsplit), dim3(kWG), 0, st, logits_d, K, (int64_t)K * Vd,
+                       (int64_t)Vd, Vd, pd.nC, pd.cps, pd.nsplit, cs_d, ratio_d, (const uint64_t*)nullptr, part_q2,
+                       (float2*)nullptr);
+    hipLaunchKernelGGL(k_diag_rows, dim3((rows + kWG - 1) / kWG), dim3(kWG), 0, st, part_t, pt.nsplit, part_q1, part_q2,
+                       pd.nsplit, rows, K, ratio_t, ratio_d, c_t, c_d, frow, fbad, status);
+    const int nparts = map->nparts[DT];
+    int nsplit = 256 / (rows * nparts);
+    nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
+    hipLaunchKernelGGL((k_final_scan<DT, true>), dim3((unsigned)((rows + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0, st,
+                       logits_t, logits_d, rows, K, Vt, Vd, pt.nC, nparts, nsplit, map->per[DT], map->S, cs_t, ratio_t, frow,
+                       map->sh_x, map->pl_start[DT], map->pl_e[DT], (float*)nullptr, (float*)nullptr, mn, mn2, fbad);
+    hipLaunchKernelGGL(k_diag_finish, dim3(rows), dim3(kWave), 0, st, frow, mn, mn2, rows, nparts, pt.nC, alpha_tli,
+                       alpha_union);
+}
 }  // namespace
 
 extern "C" {
@@ -1452,41 +1855,113 @@ int tli_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, 
                      float temp_d, const float* u_draft, int32_t* tok_d, int32_t* tok_t, double* q_tok, double* lse_q,
                      int32_t* row_status, int64_t io_stride, void* workspace, size_t workspace_bytes,
                      void* hip_stream) {
-    if (!map || !logits_d || !u_draft || !tok_d || !tok_t || !lse_q || !row_status || !workspace)
+    if (!map || !tok_t || !lse_q) return TLI_ERR_INVALID_ARG;
+    return sample_rows_impl(logits_d, dtype, row_stride_elems, R, map->Vd, temp_d, map->lmask, map->d2t, u_draft, tok_d,
+                            tok_t, q_tok, lse_q, row_status, io_stride, workspace, workspace_bytes,
+                            static_cast<hipStream_t>(hip_stream));
+}
+
+int tli_union_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems,
+                           int32_t R, float temp_d, const float* u_draft, int32_t* tok_d, int32_t* tok_t,
+                           double* q_tok, double* lse_q, int32_t* row_status, int64_t io_stride, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+    if (!map || !tok_t || !lse_q) return TLI_ERR_INVALID_ARG;
+    return sample_rows_impl(logits_d, dtype, row_stride_elems, R, map->Vd, temp_d, nullptr, map->d2t, u_draft, tok_d,
+                            tok_t, q_tok, lse_q, row_status, io_stride, workspace, workspace_bytes,
+                            static_cast<hipStream_t>(hip_stream));
+}
+
+size_t tli_acceptance_rates_workspace_bytes(const tli_map* map, int32_t B, int32_t K, tli_dtype dtype) {
+    if (!map || B < 1 || K < 1 || (int64_t)B * K > 0x7fffffff / 64 || (dtype != TLI_F32 && dtype != TLI_BF16)) return 0;
+    return diag_layout(map, B, K, dtype).total;
+}
+
+int tli_acceptance_rates(const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype, int32_t B,
+                         int32_t K, float temp_t, float temp_d, double* alpha_tli, double* alpha_union,
+                         int32_t* pos_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!map || !logits_t || !logits_d || !alpha_tli || !alpha_union || !pos_status || !workspace)
         return TLI_ERR_INVALID_ARG;
-    if (R < 1 || R > 0x7fffffff / 64 || !(temp_d > 0.f) || !std::isfinite(temp_d) || io_stride < 1)
-        return TLI_ERR_INVALID_ARG;
+    if (B < 1 || K < 1 || (int64_t)B * K > 0x7fffffff / 64) return TLI_ERR_INVALID_ARG;
+    if (!(temp_t > 0.f) || !(temp_d > 0.f) || !std::isfinite(temp_t) || !std::isfinite(temp_d)) return TLI_ERR_INVALID_ARG;
     if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
     const int epv = dtype == TLI_BF16 ? 8 : 4;
-    if (row_stride_elems < map->Vd || row_stride_elems % epv != 0 || !aligned16(logits_d) || !aligned16(workspace))
+    if (map->Vt % epv != 0 || map->Vd % epv != 0 || !aligned16(logits_t) || !aligned16(logits_d) || !aligned16(workspace))
         return TLI_ERR_INVALID_ARG;
-    const int Vd = map->Vd;
-    const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
-    Plan pl = make_plan(Vd, R, chunk);
-    // from 4 workgroups per CU on, a row per workgroup (scan and draw in one kernel) beats splitting rows
-    if (R >= 1024 && pl.nC <= kLdsChunks) { pl.nsplit = 1; pl.cps = pl.nC; }
-    const size_t tab_bytes = align256((size_t)R * pl.nC * sizeof(float));
-    if (workspace_bytes < 2 * tab_bytes) return TLI_ERR_ALLOC;
-    float* tab_ref = reinterpret_cast<float*>(workspace);
-    float* tab_s = reinterpret_cast<float*>(static_cast<char*>(workspace) + tab_bytes);
-    const double c_true = kLog2e / (double)temp_d;
-    const float cs = (float)c_true;
-    const double ratio = c_true / (double)cs;
+    const DiagLayout w = diag_layout(map, B, K, dtype);
+    if (workspace_bytes < w.total) return TLI_ERR_ALLOC;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (dtype == TLI_BF16)
-        launch_draft<TLI_BF16>(map, logits_d, row_stride_elems, R, temp_d, pl, cs, ratio, u_draft, tok_d, tok_t, q_tok,
-                               lse_q, row_status, io_stride, tab_ref, tab_s, st);
+        launch_diag<TLI_BF16>(map, logits_t, logits_d, B, K, temp_t, temp_d, alpha_tli, alpha_union, pos_status,
+                              static_cast<char*>(workspace), w, st);
     else
-        launch_draft<TLI_F32>(map, logits_d, row_stride_elems, R, temp_d, pl, cs, ratio, u_draft, tok_d, tok_t, q_tok,
-                              lse_q, row_status, io_stride, tab_ref, tab_s, st);
+        launch_diag<TLI_F32>(map, logits_t, logits_d, B, K, temp_t, temp_d, alpha_tli, alpha_union, pos_status,
+                             static_cast<char*>(workspace), w, st);
     return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
 }
 
-int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype, int32_t B, int32_t K,
-               float temp_t, float temp_d, const int32_t* tok_d, const double* lse_q, const float* u_acc,
-               const float* u_fin, int32_t* n_accepted, int32_t* out_tok, uint8_t* accept, double* p_tok,
-               double* q_tok, double* lse_p, int32_t* seq_status, void* workspace, size_t workspace_bytes,
-               void* hip_stream) {
+size_t tli_sample_rows_workspace_bytes(int32_t R, int32_t V, tli_dtype dtype) {
+    if (R < 1 || R > 0x7fffffff / 64 || V < 1 || (dtype != TLI_F32 && dtype != TLI_BF16)) return 0;
+    return rows_workspace(R, V, dtype);
+}
+
+int tli_sample_rows(const void* logits, tli_dtype dtype, int64_t row_stride_elems, int32_t R, int32_t V, float temp,
+                    const float* u, int32_t* tok, double* p_tok, double* lse, int32_t* row_status, int64_t io_stride,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (temp == 0.f)
+        return argmax_rows_impl(logits, dtype, row_stride_elems, R, V, nullptr, nullptr, tok, nullptr, p_tok, lse,
+                                row_status, io_stride, workspace, workspace_bytes, st);
+    return sample_rows_impl(logits, dtype, row_stride_elems, R, V, temp, nullptr, nullptr, u, tok, nullptr, p_tok, lse,
+                            row_status, io_stride, workspace, workspace_bytes, st);
+}
+
+int tli_greedy_draft(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems, int32_t R,
+                     int32_t* tok_d, int32_t* tok_t, int32_t* row_status, int64_t io_stride, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+    if (!map || !tok_t) return TLI_ERR_INVALID_ARG;
+    return argmax_rows_impl(logits_d, dtype, row_stride_elems, R, map->Vd, map->lmask, map->d2t, tok_d, tok_t, nullptr,
+                            nullptr, row_status, io_stride, workspace, workspace_bytes,
+                            static_cast<hipStream_t>(hip_stream));
+}
+
+int tli_exact_match_verify(const void* logits_t, tli_dtype dtype, int32_t B, int32_t m, int32_t Vt, float temp_t,
+                           const int32_t* draft_t, const float* u, int32_t* n_accepted, int32_t* out_tok,
+                           int32_t* tgt_tok, int32_t* seq_status, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+    if (!logits_t || !draft_t || !n_accepted || !out_tok || !tgt_tok || !seq_status || !workspace)
+        return TLI_ERR_INVALID_ARG;
+    if (B < 1 || m < 1 || m >= kMaxK || (int64_t)B * (m + 1) > 0x7fffffff / 64 || Vt < 1) return TLI_ERR_INVALID_ARG;
+    if (!(temp_t >= 0.f) || !std::isfinite(temp_t) || (temp_t > 0.f && !u)) return TLI_ERR_INVALID_ARG;
+    if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
+    const int epv = dtype == TLI_BF16 ? 8 : 4;
+    if (Vt % epv != 0 || !aligned16(workspace)) return TLI_ERR_INVALID_ARG;  // dense rows must start on 16 bytes
+    const int R = B * (m + 1);
+    const size_t st_bytes = align256((size_t)R * sizeof(int32_t));
+    if (workspace_bytes < st_bytes + rows_workspace(R, Vt, dtype)) return TLI_ERR_ALLOC;
+    int32_t* row_status = reinterpret_cast<int32_t*>(workspace);
+    void* ws_rows = static_cast<char*>(workspace) + st_bytes;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int rc = tli_sample_rows(logits_t, dtype, Vt, R, Vt, temp_t, u, tgt_tok, nullptr, nullptr, row_status, 1, ws_rows,
+                                   workspace_bytes - st_bytes, st);
+    if (rc != TLI_OK) return rc;
+    hipLaunchKernelGGL(k_match, dim3(B), dim3(kWave), 0, st, tgt_tok, row_status, draft_t, m, n_accepted, out_tok,
+                       seq_status);
+    return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
+}
+
+size_t tli_exact_match_workspace_bytes(int32_t B, int32_t m, int32_t Vt, tli_dtype dtype) {
+    if (B < 1 || m < 1 || m >= kMaxK || (int64_t)B * (m + 1) > 0x7fffffff / 64 || Vt < 1 ||
+        (dtype != TLI_F32 && dtype != TLI_BF16))
+        return 0;
+    const int R = B * (m + 1);
+    return align256((size_t)R * sizeof(int32_t)) + rows_workspace(R, Vt, dtype);
+}
+
+static int verify_impl(int union_mode, const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype,
+                       int32_t B, int32_t K, float temp_t, float temp_d, const int32_t* tok_d, const double* lse_q,
+                       const float* u_acc, const float* u_fin, int32_t* n_accepted, int32_t* out_tok, uint8_t* accept,
+                       double* p_tok, double* q_tok, double* lse_p, int32_t* seq_status, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
     if (!map || !logits_t || !logits_d || !tok_d || !u_acc || !u_fin || !n_accepted || !out_tok ||
         !seq_status || !workspace)
         return TLI_ERR_INVALID_ARG;
@@ -1525,9 +2000,28 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
     a.pd = make_plan(Vd, rows, chunk); a.cs_d = (float)c_d; a.ratio_d = c_d / (double)a.cs_d; a.tab_ref = tab_ref; a.tab_s = tab_s;
     a.mn = reinterpret_cast<double*>(ws + w.mn); a.fbad = reinterpret_cast<int32_t*>(ws + w.fbad); a.ctab = reinterpret_cast<float2*>(ws + w.ctab);
     a.frow = reinterpret_cast<FinalRow*>(ws + w.frow);
+    a.union_mode = union_mode;
     if (dtype == TLI_BF16) launch_verify<TLI_BF16>(a, st);
     else launch_verify<TLI_F32>(a, st);
     return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
+}
+
+int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype, int32_t B, int32_t K,
+               float temp_t, float temp_d, const int32_t* tok_d, const double* lse_q, const float* u_acc,
+               const float* u_fin, int32_t* n_accepted, int32_t* out_tok, uint8_t* accept, double* p_tok,
+               double* q_tok, double* lse_p, int32_t* seq_status, void* workspace, size_t workspace_bytes,
+               void* hip_stream) {
+    return verify_impl(0, map, logits_t, logits_d, dtype, B, K, temp_t, temp_d, tok_d, lse_q, u_acc, u_fin, n_accepted,
+                       out_tok, accept, p_tok, q_tok, lse_p, seq_status, workspace, workspace_bytes, hip_stream);
+}
+
+int tli_union_verify(const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype, int32_t B,
+                     int32_t K, float temp_t, float temp_d, const int32_t* tok_d, const double* lse_q,
+                     const float* u_acc, const float* u_fin, int32_t* n_accepted, int32_t* out_tok, uint8_t* accept,
+                     double* p_tok, double* q_tok, double* lse_p, int32_t* seq_status, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+    return verify_impl(1, map, logits_t, logits_d, dtype, B, K, temp_t, temp_d, tok_d, lse_q, u_acc, u_fin, n_accepted,
+                       out_tok, accept, p_tok, q_tok, lse_p, seq_status, workspace, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -83,12 +83,15 @@ def compare_draft(oracle_mod, ld_np, tau_d, d2t, u_draft, gpu: dict, ref: dict |
     return rep, ref
 
 
-def compare_verify(oracle_mod, lt_np, ld_np, tau_t, tau_d, d2t, tok_d, u_acc, u_fin, gpu: dict, threads=16):
-    """gpu: dict of host numpy arrays n_accepted, out_tok, accept, p_tok, q_tok, lse_p, status."""
+def compare_verify(oracle_mod, lt_np, ld_np, tau_t, tau_d, d2t, tok_d, u_acc, u_fin, gpu: dict, threads=16,
+                   fn="verify"):
+    """gpu: dict of host numpy arrays n_accepted, out_tok, accept, p_tok, q_tok, lse_p, status.
+    fn: the oracle entry to compare with ("verify" = TLI, "union_verify" = the union algorithm)."""
     tau_t, tau_d = f32(tau_t), f32(tau_d)
     B, K1, Vt = lt_np.shape
     K = K1 - 1
-    ref = oracle_mod.verify(lt_np, ld_np, tau_t, tau_d, d2t, tok_d, u_acc, u_fin, threads=threads)
+    oracle_verify = getattr(oracle_mod, fn)
+    ref = oracle_verify(lt_np, ld_np, tau_t, tau_d, d2t, tok_d, u_acc, u_fin, threads=threads)
     rep = Report()
     u_fin = np.asarray(u_fin, np.float64).reshape(B)
     for b in range(B):
@@ -136,7 +139,7 @@ def compare_verify(oracle_mod, lt_np, ld_np, tau_t, tau_d, d2t, tok_d, u_acc, u_
             assert np.isnan(gpu["lse_p"][b, K])
         g_tok, r_tok = int(gpu["out_tok"][b, n]), int(ref["out_tok"][b, n])
         if g_tok != r_tok:
-            one = oracle_mod.verify(lt_np[b:b + 1], ld_np[b:b + 1], tau_t, tau_d, d2t, tok_d.reshape(B, K)[b:b + 1],
+            one = oracle_verify(lt_np[b:b + 1], ld_np[b:b + 1], tau_t, tau_d, d2t, tok_d.reshape(B, K)[b:b + 1],
                                     np.asarray(u_acc).reshape(B, K)[b:b + 1], u_fin[b:b + 1], want_weights=True)
             m = ref["fin_margin"][b]
             dist = _cdf_distance(one["fin_weights"][0], g_tok, float(u_fin[b])) if 0 <= g_tok < Vt else np.inf
@@ -147,6 +150,28 @@ def compare_verify(oracle_mod, lt_np, ld_np, tau_t, tau_d, d2t, tok_d, u_acc, u_
                 rep["hard"] += 1
                 print(f"HARD extra-token mismatch seq {b}: gpu {g_tok} oracle {r_tok} margin {m} dist {dist}")
     return rep, ref
+
+
+def compare_row_tokens(oracle_mod, rows_np, tau, u, gpu_tok, gpu_status, ref: dict, weights_of_row):
+    """One sampled id per row: equal to the oracle's, or a counted near-tie (oracle CDF margin below NEAR_TIE and u
+    within NEAR_TIE of the GPU id's interval of the oracle's distribution `weights_of_row(r)`)."""
+    rep = Report()
+    R = rows_np.shape[0]
+    rep["compared_tokens"] = R
+    assert np.array_equal(gpu_status, ref["status"]), "row status differs"
+    ok = ref["status"] == 0
+    assert np.all(gpu_tok[~ok] == -1)
+    key = "tok_d" if "tok_d" in ref else "tok"
+    for r in np.nonzero(ok & (gpu_tok != ref[key]))[0]:
+        m = ref["margin"][r]
+        dist = _cdf_distance(weights_of_row(r), int(gpu_tok[r]), float(np.asarray(u).reshape(-1)[r]))
+        if m < NEAR_TIE and dist < NEAR_TIE:
+            rep["token_near_ties"] += 1
+            rep["token_near_ties_tight"] += int(m < TIGHT)
+        else:
+            rep["hard"] += 1
+            print(f"HARD row-token mismatch row {r}: gpu {gpu_tok[r]} oracle {ref[key][r]} margin {m} dist {dist}")
+    return rep
 
 
 def to_host(d: dict) -> dict:

@@ -1,0 +1,236 @@
+"""GPU parity of the entry points beyond the TLI step -- union algorithm, expected acceptance rates, one
+token per row / argmax, greedy TLI draft, exact-match tail -- against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_05202_amd import binding, synth
+
+import parity
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+SHAPES = [
+    # (B, K, Vt, Vd, S, dtype, tau_t, tau_d)
+    (5, 3, 2048 * 3 + 40, 2048 * 2 + 24, 1500, "bf16", 0.7, 0.9),
+    (3, 4, 1024 * 4 + 28, 1024 + 4, 700, "f32", 1.0, 1.0),
+    (40, 2, 10000, 30000, 9000, "bf16", 0.8, 1.1),
+    (2, 2, 2048 * 30 + 16, 2048 * 27 + 8, 50000, "bf16", 0.9, 1.0),
+]
+IDS = [f"B{c[0]}_Vt{c[2]}_{c[5]}" for c in SHAPES]
+
+
+def _inputs(shape, cfg=70):
+    B, K, Vt, Vd, S, dtype, tt, td = shape
+    w = synth.WORKLOADS[3].scaled(B=B, K=K, Vt=Vt, Vd=Vd, S=S, dtype=dtype, tau_t=tt, tau_d=td, cfg=cfg)
+    return w, synth.make_inputs(w, DEV)
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=IDS)
+def test_union_draft_and_verify(oracle, shape):
+    w, inp = _inputs(shape)
+    m = binding.tli_build_map(inp["d2t"], w.Vt)
+    code = binding.TLI_F32 if w.dtype == "f32" else binding.TLI_BF16
+    ws = binding.alloc_workspace(w.B, w.K, m, code, DEV)
+    lt_np, ld_np = synth.logits_to_numpy(inp["logits_t"]), synth.logits_to_numpy(inp["logits_d"])
+    rows = ld_np.reshape(w.B * w.K, w.Vd)
+    ud = inp["u_draft"].cpu().numpy().astype(np.float64).reshape(-1)
+    ua = inp["u_acc"].cpu().numpy().astype(np.float64)
+    uf = inp["u_fin"].cpu().numpy().astype(np.float64)
+    td, tt = parity.f32(w.tau_d), parity.f32(w.tau_t)
+    g = parity.to_host(binding.tli_union_draft_sample(m, inp["logits_d"], w.tau_d, inp["u_draft"].reshape(-1), ws))
+    ref = oracle.union_draft_sample(rows, td, inp["d2t"], ud, threads=8)
+    rep = parity.compare_row_tokens(oracle, rows, td, ud, g["tok_d"], g["status"], ref,
+                                    lambda r: oracle.softmax(rows[r], td)[0])
+    same = (ref["status"] == 0) & (g["tok_d"] == ref["tok_d"])
+    assert np.array_equal(g["tok_t"][same], ref["tok_t"][same])
+    assert w.B * w.K < 12 or (ref["tok_t"] < 0).any()  # some drafts fall outside T
+    assert np.abs(g["lse_q"][same] - ref["lse_q"][same]).max() < 5e-7
+    assert (np.abs(g["q_tok"][same] - ref["q_tok"][same]) / ref["q_tok"][same]).max() < 1e-6
+    assert rep["hard"] == 0, dict(rep)
+    # verify on the oracle's union drafts (some lie outside T), with and without the normalisers
+    tok = torch.from_numpy(ref["tok_d"]).to(DEV)
+    for lse_q in (torch.from_numpy(ref["lse_q"]).to(DEV), None):
+        gv = binding.tli_union_verify(m, inp["logits_t"], inp["logits_d"], w.tau_t, w.tau_d, tok, lse_q,
+                                      inp["u_acc"].reshape(-1), inp["u_fin"], ws)
+        torch.cuda.synchronize()
+        rv, refv = parity.compare_verify(oracle, lt_np, ld_np, w.tau_t, w.tau_d, inp["d2t"], ref["tok_d"], ua, uf,
+                                         parity.to_host(gv), threads=8, fn="union_verify")
+        print(dict(rv))
+        assert rv["hard"] == 0 and rv["max_lse_err"] < 5e-7 and rv["max_prob_rel"] < 1e-6
+    m.free()
+
+
+def test_union_flags(oracle):
+    w, inp = _inputs((6, 3, 6000, 4104, 2000, "bf16", 0.8, 0.8), cfg=71)
+    d2t = inp["d2t"]
+    unshared = np.nonzero(d2t < 0)[0]
+    ld = inp["logits_d"]
+    ld[0, 1, int(unshared[3])] = float("nan")      # an unshared logit matters to the union algorithm
+    ld[1, 0, :] = float("-inf")
+    m = binding.tli_build_map(d2t, w.Vt)
+    ws = binding.alloc_workspace(w.B, w.K, m, binding.TLI_BF16, DEV)
+    rows = synth.logits_to_numpy(ld).reshape(w.B * w.K, w.Vd)
+    ud = inp["u_draft"].cpu().numpy().astype(np.float64).reshape(-1)
+    g = parity.to_host(binding.tli_union_draft_sample(m, ld, w.tau_d, inp["u_draft"].reshape(-1), ws))
+    ref = oracle.union_draft_sample(rows, parity.f32(w.tau_d), d2t, ud, threads=4)
+    assert np.array_equal(g["status"], ref["status"]) and ref["status"][1] == oracle.NONFINITE and ref["status"][3] == oracle.ZERO_MASS
+    # verify: a valid draft id on the NaN row flags the sequence; out-of-range ids are BAD_DRAFT
+    tok = ref["tok_d"].reshape(w.B, w.K).copy()
+    tok[0, 1] = 5
+    tok[2, 0] = w.Vd + 3
+    tok[3, 2] = int(unshared[0])
+    gv = binding.tli_union_verify(m, inp["logits_t"], ld, w.tau_t, w.tau_d, torch.from_numpy(tok).to(DEV), None,
+                                  inp["u_acc"].reshape(-1), inp["u_fin"], ws)
+    torch.cuda.synchronize()
+    rv, refv = parity.compare_verify(oracle, synth.logits_to_numpy(inp["logits_t"]), synth.logits_to_numpy(ld), w.tau_t,
+                                     w.tau_d, d2t, tok, inp["u_acc"].cpu().numpy().astype(np.float64),
+                                     inp["u_fin"].cpu().numpy().astype(np.float64), parity.to_host(gv), threads=4,
+                                     fn="union_verify")
+    assert rv["hard"] == 0
+    assert refv["status"][0] & oracle.NONFINITE and refv["status"][2] & oracle.BAD_DRAFT and refv["status"][3] == 0
+    m.free()
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=IDS)
+def test_acceptance_rates(oracle, shape):
+    w, inp = _inputs(shape, cfg=72)
+    lt, ld = inp["logits_t"], inp["logits_d"]
+    d2t = inp["d2t"]
+    if w.B >= 3:  # flags: NaN in an unshared drafter logit, zero shared mass, -inf stretch in a target row
+        ld[0, 0, int(np.nonzero(d2t < 0)[0][0])] = float("nan")
+        ld[1, 1, torch.from_numpy(np.nonzero(d2t >= 0)[0]).to(DEV)] = float("-inf")
+        lt[2, 0, : w.Vt // 2] = float("-inf")
+    m = binding.tli_build_map(d2t, w.Vt)
+    g = parity.to_host(binding.tli_acceptance_rates(m, lt, ld, w.tau_t, w.tau_d))
+    lt_np = synth.logits_to_numpy(lt)[:, : w.K].reshape(w.B * w.K, w.Vt)
+    ld_np = synth.logits_to_numpy(ld).reshape(w.B * w.K, w.Vd)
+    ref = oracle.acceptance_rates(lt_np, ld_np, parity.f32(w.tau_t), parity.f32(w.tau_d), d2t, threads=8)
+    assert np.array_equal(g["status"].reshape(-1), ref["status"])
+    ok = ref["status"] == 0
+    for name in ("alpha_tli", "alpha_union"):
+        gg, rr = g[name].reshape(-1), ref[name]
+        assert np.all(np.isnan(gg[ref["status"] == oracle.NONFINITE]))
+        assert np.all(gg[ref["status"] == oracle.ZERO_MASS] == 0.0)
+        rel = np.abs(gg[ok] - rr[ok]) / rr[ok]
+        print(name, "max rel err", rel.max(), "range", rr[ok].min(), rr[ok].max())
+        assert rel.max() < 2e-6
+    assert np.all(g["alpha_union"].reshape(-1)[ok] <= g["alpha_tli"].reshape(-1)[ok] * (1 + 1e-9))
+    m.free()
+
+
+@pytest.mark.parametrize("dtype,V,R,stride", [("bf16", 2048 * 3 + 40, 9, 2048 * 3 + 48), ("f32", 5000, 3, 5000),
+                                               ("bf16", 151936, 2, 151936), ("bf16", 4104, 1500, 4104)])
+def test_sample_rows_and_argmax(oracle, dtype, V, R, stride):
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(V + R)
+    buf = (torch.randn(R, stride, generator=gen, device=DEV) * 3).to(torch.bfloat16 if dtype == "bf16" else torch.float32)
+    buf[:, V:] = 60.0  # padding beyond V must be ignored
+    view = buf[:, :V]
+    u = synth._uniform24(R, gen, DEV)
+    rows = synth.logits_to_numpy(view.contiguous())
+    un = u.cpu().numpy().astype(np.float64)
+    for tau in (0.8, 0.0):
+        g = parity.to_host(binding.tli_sample_rows(view, tau, u))
+        ref = oracle.sample_rows(rows, parity.f32(tau), un, threads=8)
+        if tau == 0.0:
+            assert np.array_equal(g["tok"], ref["tok"]) and np.array_equal(g["status"], ref["status"])
+            assert np.all(g["p_tok"] == 1.0) and np.all(np.isnan(g["lse"]))
+        else:
+            rep = parity.compare_row_tokens(oracle, rows, tau, un, g["tok"], g["status"], ref,
+                                            lambda r: oracle.softmax(rows[r], parity.f32(tau))[0])
+            assert rep["hard"] == 0
+            same = g["tok"] == ref["tok"]
+            assert np.abs(g["lse"][same] - ref["lse"][same]).max() < 5e-7
+            assert (np.abs(g["p_tok"][same] - ref["p_tok"][same]) / ref["p_tok"][same]).max() < 1e-6
+
+
+def test_argmax_ties_and_flags(oracle):
+    V, R = 2048 * 2 + 16, 6
+    x = torch.zeros(R, V, dtype=torch.bfloat16, device=DEV)
+    x[0, [5, 4000, 2049]] = 7.0          # equal maxima in different chunks and lanes: the lowest id wins
+    x[1, V - 1] = 1.0                    # the last id of the ragged tail
+    x[2, :] = float("-inf")              # nothing to choose from
+    x[3, 77] = float("nan")
+    x[4, 3000] = float("inf")
+    x[5, :] = float("-inf"); x[5, 2048] = -3.0
+    g = parity.to_host(binding.tli_sample_rows(x, 0.0, None))
+    ref = oracle.sample_rows(synth.logits_to_numpy(x), 0.0, np.zeros(R))
+    assert np.array_equal(g["tok"], ref["tok"]) and list(g["tok"]) == [5, V - 1, -1, -1, -1, 2048]
+    assert np.array_equal(g["status"], ref["status"])
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=IDS)
+def test_greedy_draft_and_temperature_zero_verify(oracle, shape):
+    w, inp = _inputs(shape, cfg=73)
+    d2t = inp["d2t"]
+    lt, ld = inp["logits_t"], inp["logits_d"]
+    sh = np.nonzero(d2t >= 0)[0]
+    # make the target agree with the drafter's shared argmax on a prefix of length b % (K+1)
+    ld_h = ld.float().cpu().numpy()
+    for b in range(w.B):
+        for k in range(b % (w.K + 1)):
+            d = sh[np.argmax(ld_h[b, k, sh])]
+            lt[b, k, int(d2t[d])] = 50.0
+    if w.B >= 3:
+        ld[1, 0, torch.from_numpy(sh).to(DEV)] = float("-inf")
+        ld[2, 1, int(sh[0])] = float("nan")
+    m = binding.tli_build_map(d2t, w.Vt)
+    code = binding.TLI_F32 if w.dtype == "f32" else binding.TLI_BF16
+    ws = binding.alloc_workspace(w.B, w.K, m, code, DEV)
+    g = binding.tli_greedy_draft(m, ld, ws)
+    gh = parity.to_host(g)
+    ref = oracle.greedy_draft(synth.logits_to_numpy(ld).reshape(w.B * w.K, w.Vd), d2t, threads=8)
+    for k in ("tok_d", "tok_t", "status"):
+        assert np.array_equal(gh[k], ref[k]), k
+    v = parity.to_host(binding.tli_exact_match_verify(lt, 0.0, g["tok_t"], None))
+    rv = oracle.exact_match_verify(synth.logits_to_numpy(lt), 0.0, ref["tok_t"].reshape(w.B, w.K),
+                                   np.zeros((w.B, w.K + 1)), threads=8)
+    assert np.array_equal(v["n_accepted"], rv["n_acc"]) and np.array_equal(v["out_tok"], rv["out_tok"])
+    assert np.array_equal(v["tgt_tok"], rv["tgt_tok"]) and np.array_equal(v["status"], rv["status"])
+    if w.B > w.K:
+        assert len(set(rv["n_acc"])) >= 3  # several prefix lengths are exercised
+    m.free()
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=IDS)
+def test_exact_match_tail_sampled(oracle, shape):
+    w, inp = _inputs(shape, cfg=74)
+    lt = inp["logits_t"]
+    B, m = w.B, w.K
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(99)
+    u = synth._uniform24(B * (m + 1), gen, DEV).reshape(B, m + 1)
+    lt_np = synth.logits_to_numpy(lt)
+    un = u.cpu().numpy().astype(np.float64)
+    tau = parity.f32(w.tau_t)
+    own = oracle.sample_rows(lt_np.reshape(-1, w.Vt), tau, un.reshape(-1), threads=8)
+    draft = own["tok"].reshape(B, m + 1)[:, :m].copy()
+    for b in range(B):  # break the match at position b % (m+2) (m: a missing draft token, m+1: nowhere)
+        j = b % (m + 2)
+        if j < m:
+            draft[b, j] = (draft[b, j] + 1) % w.Vt
+        elif j == m:
+            draft[b, m - 1] = -1
+    if B >= 3:
+        lt[2, 1, 9] = float("nan")
+        lt_np = synth.logits_to_numpy(lt)
+    g = parity.to_host(binding.tli_exact_match_verify(lt, w.tau_t, torch.from_numpy(draft).to(DEV), u))
+    ref = oracle.exact_match_verify(lt_np, tau, draft, un, threads=8)
+    assert np.array_equal(g["status"], ref["status"])
+    near = 0
+    for b in range(B):
+        if ref["status"][b]:
+            assert g["n_accepted"][b] == 0 and np.all(g["out_tok"][b] == -1)
+            continue
+        diff = np.nonzero(g["tgt_tok"][b] != ref["tgt_tok"][b])[0]
+        if diff.size:  # a drawn id may differ only inside the near-tie window; the sequence is then compared no further
+            for j in diff:
+                p = oracle.softmax(lt_np[b, j], tau)[0]
+                assert ref["margin"][b, j] < parity.NEAR_TIE and parity._cdf_distance(p, int(g["tgt_tok"][b, j]), un[b, j]) < parity.NEAR_TIE
+            near += 1
+            continue
+        assert g["n_accepted"][b] == ref["n_acc"][b] and np.array_equal(g["out_tok"][b], ref["out_tok"][b])
+    print("sequences with a near-tie draw:", near)
