@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel as read by rocprofv3 (FETCH_SIZE + WRITE_SIZE, each scaled by
 # what the same counter reads for the library's plain copy kernel); from profiles/*_hbm_traffic_pmc.md.
 # Counters cannot be read from inside this process, so the figure is carried here per workload.
-MEASURED_TRAFFIC_BYTES = {"large_vocab": 1048.60e6 + 0.07e6}
+MEASURED_TRAFFIC_BYTES = {"large_vocab": 1048.59e6 + 2.16e6}
 
 
 def parse():
@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences in the oracle's sample (0 = auto)")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel in a second pass")
+    ap.add_argument("--next", action="store_true",
+                    help="also time the neighbouring entry points (union algorithm, acceptance rates, exact-match tail, "
+                         "temperature zero) on the same batch")
     return ap.parse_args()
 
 
@@ -136,6 +139,44 @@ def main():
     per_step_graph_ms = time_call(graph.replay, n_sep)
     del graph
 
+    # ---- the neighbouring steps on the same batch (each timed on its own; algorithmic bytes = rows read once)
+    next_rows = {}
+    if args.next:
+        n_nx = max(3, n_sep // 3)
+        rows_t = w.B * (w.K + 1)
+        u_rows = torch.rand(rows_t, device=dev, dtype=torch.float32)
+        draft_t = d_out["tok_t"].clone()
+        ws_em = torch.empty(int(binding.load_library().tli_exact_match_workspace_bytes(w.B, w.K, w.Vt, code)),
+                            dtype=torch.uint8, device=dev)
+        em_out = binding.tli_exact_match_verify(inp["logits_t"], w.tau_t, draft_t, u_rows, ws_em)
+
+        def timed(name, fn, nbytes):
+            fn()
+            ms = time_call(fn, n_nx)
+            next_rows[name] = dict(ms=round(ms, 4), algorithmic_gbs=round(nbytes / (1e-3 * ms) / 1e9, 1),
+                                   frac_of_peak=round(nbytes / (1e-3 * ms) / 1e9 / HBM_PEAK_GBS, 4))
+
+        timed("exact_match_verify_sampled", lambda: binding.tli_exact_match_verify(
+            inp["logits_t"], w.tau_t, draft_t, u_rows, ws_em, out=em_out), rows_t * w.Vt * esz)
+        timed("exact_match_verify_argmax", lambda: binding.tli_exact_match_verify(
+            inp["logits_t"], 0.0, draft_t, None, ws_em, out=em_out), rows_t * w.Vt * esz)
+        timed("greedy_draft", lambda: binding.tli_greedy_draft(m, inp["logits_d"], ws), R * w.Vd * esz)
+        timed("union_draft_sample", lambda: binding.tli_union_draft_sample(m, inp["logits_d"], w.tau_d, u_draft, ws, out=d_out),
+              R * w.Vd * esz)
+        timed("union_verify", lambda: binding.tli_union_verify(m, inp["logits_t"], inp["logits_d"], w.tau_t, w.tau_d,
+                                                               d_out["tok_d"], d_out["lse_q"], u_acc, inp["u_fin"], ws,
+                                                               out=v_out), positions * w.Vt * esz + w.B * w.Vd * esz)
+        ar = binding.tli_acceptance_rates(m, inp["logits_t"], inp["logits_d"], w.tau_t, w.tau_d)
+        timed("acceptance_rates", lambda: binding.tli_acceptance_rates(m, inp["logits_t"], inp["logits_d"], w.tau_t,
+                                                                       w.tau_d, workspace=ar["workspace"]),
+              positions * (w.Vt + 2 * w.Vd) * esz)
+        ok = ar["status"] == 0
+        next_rows["mean_alpha_tli"] = round(float(ar["alpha_tli"][ok].mean()), 4)
+        next_rows["mean_alpha_union"] = round(float(ar["alpha_union"][ok].mean()), 4)
+        # restore the TLI drafts for the figures below
+        step()
+        torch.cuda.synchronize()
+
     breakdown = None
     if args.breakdown:
         binding.tli_profile_enable(binding.KERNELS, n_sep)
@@ -173,6 +214,8 @@ def main():
     )
     if breakdown:
         extra["kernel_breakdown"] = breakdown
+    if next_rows:
+        extra["next_rows"] = next_rows
 
     # ---- CPU oracle on a bounded sample of the same batch
     cpu = None
