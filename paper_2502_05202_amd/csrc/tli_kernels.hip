@@ -1209,18 +1209,22 @@ __global__ __launch_bounds__(kWG) void k_argmax(const void* __restrict__ logits,
         if (m > best) { best = m; bc = c; }  // strict: an equal maximum in a later chunk has a higher id
     });
     bad |= best == INFINITY;
-    // the id of the lane's maximum: first element equal to it in the chunk it came from
+    // the id of the lane's maximum: first element equal to it in the chunk it came from.  That chunk differs
+    // from lane to lane, so the shared-id mask is taken per lane here (mask_bits), not as a wave-wide word.
     int idx = 0x7fffffff;
     if (bc >= 0) {
-        ChunkRegs t;
-        load_chunk_tail<DT>(rowv, bc, lane, (V + EPV - 1) / EPV, t);
-        float x[N];
-        chunk_values<DT, MASKED, false>(t, bc, lane, V, bits, x);
+        const int64_t nvec = (V + EPV - 1) / EPV;
 #pragma unroll
-        for (int j = kLoads - 1; j >= 0; --j)
+        for (int j = kLoads - 1; j >= 0; --j) {
+            const int64_t vi = ((int64_t)bc * kLoads + j) * kWave + lane;
+            if (vi >= nvec) continue;
+            float x[EPV];
+            unpack<DT>(reinterpret_cast<const uint4*>(rowp)[vi], x);
+            const uint32_t mb = MASKED ? mask_bits<DT>(bits, vi) : 0xffu;
 #pragma unroll
             for (int i = EPV - 1; i >= 0; --i)
-                if (x[j * EPV + i] == best) idx = (int)((((int64_t)bc * kLoads + j) * kWave + lane) * EPV + i);
+                if (vi * EPV + i < V && ((mb >> i) & 1u) && x[i] == best) idx = (int)(vi * EPV + i);
+        }
     }
     // wave: the largest value, then the lowest id among the lanes that hold it
     const float M = wave_max(best);

@@ -195,6 +195,27 @@ def test_greedy_draft_and_temperature_zero_verify(oracle, shape):
     m.free()
 
 
+def test_greedy_draft_many_rows_several_chunks_per_wave(oracle):
+    """Enough rows for one workgroup per row: every wave then owns several chunks, and the lanes of a wave find
+    their maxima in different chunks (the shared-id mask of the final look-up is per lane)."""
+    R, Vd, Vt, S = 2100, 2048 * 9 + 24, 4104, 3000
+    d2t = synth.make_d2t(Vd, Vt, S, 321)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(12)
+    for dt in (torch.bfloat16, torch.float32):
+        ld = (torch.randn(R, Vd, generator=gen, device=DEV) * 3).to(dt)
+        m = binding.tli_build_map(d2t, Vt)
+        ws = binding.alloc_workspace(R, 1, m, binding._dtype_code(ld), DEV)
+        g = parity.to_host(binding.tli_greedy_draft(m, ld, ws))
+        ref = oracle.greedy_draft(synth.logits_to_numpy(ld), d2t, threads=8)
+        for k in ("tok_d", "tok_t", "status"):
+            assert np.array_equal(g[k], ref[k]), k
+        u = synth._uniform24(R, gen, DEV)
+        g0 = parity.to_host(binding.tli_sample_rows(ld, 0.0, None))
+        assert np.array_equal(g0["tok"], oracle.sample_rows(synth.logits_to_numpy(ld), 0.0, np.zeros(R), threads=8)["tok"])
+        m.free()
+
+
 @pytest.mark.parametrize("shape", SHAPES, ids=IDS)
 def test_exact_match_tail_sampled(oracle, shape):
     w, inp = _inputs(shape, cfg=74)
@@ -234,3 +255,73 @@ def test_exact_match_tail_sampled(oracle, shape):
             continue
         assert g["n_accepted"][b] == ref["n_acc"][b] and np.array_equal(g["out_tok"][b], ref["out_tok"][b])
     print("sequences with a near-tie draw:", near)
+
+
+# ---------------------------------------------------------------- full size, in the launch configuration the benchmark times
+def test_full_size_large_vocab_next_rows(oracle):
+    """Workload 4 (B=256, K=8, Vt=256000, Vd=128256, bf16) through every neighbouring entry point; every output
+    is compared (the oracle is fanned out over the host cores)."""
+    w = synth.WORKLOADS[4]
+    inp = synth.make_inputs(w, DEV)
+    d2t = inp["d2t"]
+    lt, ld = inp["logits_t"], inp["logits_d"]
+    m = binding.tli_build_map(d2t, w.Vt)
+    ws = binding.alloc_workspace(w.B, w.K, m, binding.TLI_BF16, DEV)
+    lt_np, ld_np = synth.logits_to_numpy(lt), synth.logits_to_numpy(ld)
+    rows_d = ld_np.reshape(w.B * w.K, w.Vd)
+    tt, td = parity.f32(w.tau_t), parity.f32(w.tau_d)
+    ud = inp["u_draft"].cpu().numpy().astype(np.float64).reshape(-1)
+    ua = inp["u_acc"].cpu().numpy().astype(np.float64)
+    uf = inp["u_fin"].cpu().numpy().astype(np.float64)
+    # union algorithm
+    g = parity.to_host(binding.tli_union_draft_sample(m, ld, w.tau_d, inp["u_draft"].reshape(-1), ws))
+    ref = oracle.union_draft_sample(rows_d, td, d2t, ud, threads=16)
+    rep = parity.compare_row_tokens(oracle, rows_d, td, ud, g["tok_d"], g["status"], ref,
+                                    lambda r: oracle.softmax(rows_d[r], td)[0])
+    assert rep["hard"] == 0 and np.abs(g["lse_q"] - ref["lse_q"]).max() < 5e-7
+    gv = binding.tli_union_verify(m, lt, ld, w.tau_t, w.tau_d, torch.from_numpy(ref["tok_d"]).to(DEV),
+                                  torch.from_numpy(ref["lse_q"]).to(DEV), inp["u_acc"].reshape(-1), inp["u_fin"], ws)
+    torch.cuda.synchronize()
+    rv, _ = parity.compare_verify(oracle, lt_np, ld_np, w.tau_t, w.tau_d, d2t, ref["tok_d"], ua, uf, parity.to_host(gv),
+                                  threads=16, fn="union_verify")
+    print("union verify", dict(rv))
+    assert rv["hard"] == 0 and rv["max_lse_err"] < 5e-7
+    # expected acceptance rates of all 2048 positions
+    ga = parity.to_host(binding.tli_acceptance_rates(m, lt, ld, w.tau_t, w.tau_d))
+    ra = oracle.acceptance_rates(lt_np[:, : w.K].reshape(-1, w.Vt), rows_d, tt, td, d2t, threads=16)
+    assert np.all(ra["status"] == 0) and np.all(ga["status"] == 0)
+    for name in ("alpha_tli", "alpha_union"):
+        rel = np.abs(ga[name].reshape(-1) - ra[name]) / ra[name]
+        print(name, "max rel", rel.max(), "mean", ra[name].mean())
+        assert rel.max() < 2e-6
+    # exact-match tail over the 2304 target rows, sampled and at temperature zero; greedy drafts
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(404)
+    u = synth._uniform24(w.B * (w.K + 1), gen, DEV).reshape(w.B, w.K + 1)
+    un = u.cpu().numpy().astype(np.float64)
+    gd = binding.tli_greedy_draft(m, ld, ws)
+    rd = oracle.greedy_draft(rows_d, d2t, threads=16)
+    assert np.array_equal(parity.to_host(gd)["tok_d"], rd["tok_d"]) and np.all(rd["status"] == 0)
+    for tau in (w.tau_t, 0.0):
+        own = oracle.sample_rows(lt_np.reshape(-1, w.Vt), parity.f32(tau), un.reshape(-1), threads=16)
+        draft = own["tok"].reshape(w.B, w.K + 1)[:, : w.K].copy()
+        for b in range(w.B):
+            j = b % (w.K + 2)
+            if j < w.K:
+                draft[b, j] = (draft[b, j] + 1) % w.Vt
+        ge = parity.to_host(binding.tli_exact_match_verify(lt, tau, torch.from_numpy(draft).to(DEV), u))
+        re_ = oracle.exact_match_verify(lt_np, parity.f32(tau), draft, un, threads=16)
+        near = 0
+        for b in range(w.B):
+            diff = np.nonzero(ge["tgt_tok"][b] != re_["tgt_tok"][b])[0]
+            if diff.size:
+                assert tau > 0
+                for j in diff:
+                    p = oracle.softmax(lt_np[b, j], parity.f32(tau))[0]
+                    assert re_["margin"][b, j] < parity.NEAR_TIE and \
+                        parity._cdf_distance(p, int(ge["tgt_tok"][b, j]), un[b, j]) < parity.NEAR_TIE
+                near += 1
+                continue
+            assert ge["n_accepted"][b] == re_["n_acc"][b] and np.array_equal(ge["out_tok"][b], re_["out_tok"][b])
+        print(f"exact match tau={tau}: near-tie sequences {near}, mean accepted {re_['n_acc'].mean():.2f}")
+    m.free()
