@@ -1209,10 +1209,13 @@ __global__ __launch_bounds__(kWG) void k_argmax(const void* __restrict__ logits,
         if (m > best) { best = m; bc = c; }  // strict: an equal maximum in a later chunk has a higher id
     });
     bad |= best == INFINITY;
-    // the id of the lane's maximum: first element equal to it in the chunk it came from.  That chunk differs
-    // from lane to lane, so the shared-id mask is taken per lane here (mask_bits), not as a wave-wide word.
-    int idx = 0x7fffffff;
-    if (bc >= 0) {
+    // wave: the largest value, then the lowest id among the lanes that hold it.  Only those lanes (one, or a
+    // few on ties) look their id up: the first element equal to the maximum in the chunk the lane took it
+    // from.  That chunk differs from lane to lane, so the shared-id mask is taken per lane here (mask_bits),
+    // not as a wave-wide word.
+    const float M = wave_max(best);
+    int cand = 0x7fffffff;
+    if (bc >= 0 && best == M) {
         const int64_t nvec = (V + EPV - 1) / EPV;
 #pragma unroll
         for (int j = kLoads - 1; j >= 0; --j) {
@@ -1223,12 +1226,9 @@ __global__ __launch_bounds__(kWG) void k_argmax(const void* __restrict__ logits,
             const uint32_t mb = MASKED ? mask_bits<DT>(bits, vi) : 0xffu;
 #pragma unroll
             for (int i = EPV - 1; i >= 0; --i)
-                if (vi * EPV + i < V && ((mb >> i) & 1u) && x[i] == best) idx = (int)(vi * EPV + i);
+                if (vi * EPV + i < V && ((mb >> i) & 1u) && x[i] == best) cand = (int)(vi * EPV + i);
         }
     }
-    // wave: the largest value, then the lowest id among the lanes that hold it
-    const float M = wave_max(best);
-    int cand = (best == M && bc >= 0) ? idx : 0x7fffffff;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) cand = min(cand, __shfl_xor(cand, d, kWave));
     const bool wbad = __ballot(bad) != 0ull;
