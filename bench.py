@@ -173,6 +173,20 @@ def main():
         ok = ar["status"] == 0
         next_rows["mean_alpha_tli"] = round(float(ar["alpha_tli"][ok].mean()), 4)
         next_rows["mean_alpha_union"] = round(float(ar["alpha_union"][ok].mean()), 4)
+        # compact drafter layout: rows hold only the shared tokens' logits (a head pruned to the intersection)
+        sh_x = torch.from_numpy(np.nonzero(inp["d2t"] >= 0)[0]).to(dev)
+        epv = 16 // esz
+        c_stride = (w.S + epv - 1) // epv * epv
+        cbuf = torch.zeros((w.B, w.K, c_stride), dtype=inp["logits_d"].dtype, device=dev)
+        cbuf[:, :, : w.S] = inp["logits_d"].index_select(2, sh_x)
+        ldc = cbuf[:, :, : w.S]
+        step()
+        timed("draft_sample_compact", lambda: binding.tli_draft_sample_compact(
+            m, cbuf.reshape(R, c_stride)[:, : w.S], w.tau_d, u_draft, ws, out=d_out), R * w.S * esz)
+        timed("verify_compact", lambda: binding.tli_verify_compact(
+            m, inp["logits_t"], ldc, w.tau_t, w.tau_d, d_out["tok_d"], d_out["lse_q"], u_acc, inp["u_fin"], ws, out=v_out),
+            positions * w.Vt * esz + w.B * w.S * esz)
+        del cbuf, ldc
         # restore the TLI drafts for the figures below
         step()
         torch.cuda.synchronize()

@@ -128,6 +128,24 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
                void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Compact drafter layout, for a drafter whose output head is pruned to the shared tokens (the intersection
+ * algorithm only ever needs q on T∩D): a row holds |T∩D| logits, entry r = the logit of the shared token of
+ * rank r, ranks ascending with the drafter id.  Same semantics and outputs as tli_draft_sample / tli_verify
+ * (tok_d stays a DRAFTER id); no mask is read and no gather is needed to stage a row.
+ *   logits_c dev [rows, row stride apart (a multiple of 4 fp32 / 8 bf16, >= |T∩D|), |T∩D| valid entries]
+ *            tli_verify_compact: rows of sequence b, position k at (b*K + k) * c_row_stride_elems.
+ */
+int tli_draft_sample_compact(const tli_map* map, const void* logits_c, tli_dtype dtype, int64_t row_stride_elems,
+                             int32_t R, float temp_d, const float* u_draft, int32_t* tok_d, int32_t* tok_t,
+                             double* q_tok, double* lse_q, int32_t* row_status, int64_t io_stride, void* workspace,
+                             size_t workspace_bytes, void* hip_stream);
+int tli_verify_compact(const tli_map* map, const void* logits_t, const void* logits_c, int64_t c_row_stride_elems,
+                       tli_dtype dtype, int32_t B, int32_t K, float temp_t, float temp_d, const int32_t* tok_d,
+                       const double* lse_q, const float* u_acc, const float* u_fin, int32_t* n_accepted,
+                       int32_t* out_tok, uint8_t* accept, double* p_tok, double* q_tok, double* lse_p,
+                       int32_t* seq_status, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * ---- The neighbouring token-level steps of the paper, on the same rows -------------------------------
  *
  * The "union" algorithm (section "Motivating Examples", the simple union strategy: p and q are extended by

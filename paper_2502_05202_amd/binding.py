@@ -23,7 +23,7 @@ EXPORTS = (
     "tli_status_string", "tli_profile_enable", "tli_profile_collect", "tli_profile_disable", "tli_calib_copy",
     "tli_union_draft_sample", "tli_union_verify", "tli_acceptance_rates_workspace_bytes", "tli_acceptance_rates",
     "tli_sample_rows_workspace_bytes", "tli_sample_rows", "tli_greedy_draft", "tli_exact_match_workspace_bytes",
-    "tli_exact_match_verify",
+    "tli_exact_match_verify", "tli_draft_sample_compact", "tli_verify_compact",
 )
 KERNELS = ("lse", "accept", "final_scan", "final_pick", "draft_scan", "draft_pick")
 
@@ -60,6 +60,11 @@ def load_library() -> ctypes.CDLL:
     lib.tli_verify.argtypes = [vp, vp, vp, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                vp, vp, vp, ctypes.c_size_t, vp]
     lib.tli_verify.restype = ctypes.c_int
+    lib.tli_draft_sample_compact.argtypes = lib.tli_draft_sample.argtypes
+    lib.tli_draft_sample_compact.restype = ctypes.c_int
+    lib.tli_verify_compact.argtypes = [vp, vp, vp, i64, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp, vp,
+                                       vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.tli_verify_compact.restype = ctypes.c_int
     lib.tli_union_draft_sample.argtypes = lib.tli_draft_sample.argtypes
     lib.tli_union_draft_sample.restype = ctypes.c_int
     lib.tli_union_verify.argtypes = lib.tli_verify.argtypes
@@ -177,7 +182,8 @@ def tli_draft_sample(m: TliMap, logits_d: torch.Tensor, temp_d: float, u_draft: 
     R, Vd = ld.shape
     k, io = (0, 1) if column is None else (int(column[0]), int(column[1]))
     assert 0 <= k < io
-    assert Vd == m.Vd and u_draft.numel() == R * io and u_draft.dtype == torch.float32 and u_draft.is_contiguous()
+    want_v = m.num_shared if _entry == "tli_draft_sample_compact" else m.Vd
+    assert Vd == want_v and u_draft.numel() == R * io and u_draft.dtype == torch.float32 and u_draft.is_contiguous()
     dev = ld.device
     if out is None:
         out = dict(tok_d=torch.empty(R * io, dtype=torch.int32, device=dev),
@@ -197,6 +203,35 @@ def tli_draft_sample(m: TliMap, logits_d: torch.Tensor, temp_d: float, u_draft: 
                               at(out["status"]), io, _ptr(workspace), workspace.numel(), _stream(stream))
     if rc != 0:
         raise TliError(rc, _entry)
+    return out
+
+
+def tli_draft_sample_compact(m: TliMap, logits_c, temp_d, u_draft, workspace, out=None, stream=None, column=None) -> dict:
+    """tli_draft_sample on rows in compact layout: logits_c [..., S] (a view with a wider row stride is fine),
+    entry r = logit of the shared token of rank r."""
+    return tli_draft_sample(m, logits_c, temp_d, u_draft, workspace, out, stream, column, _entry="tli_draft_sample_compact")
+
+
+def tli_verify_compact(m: TliMap, logits_t: torch.Tensor, logits_c: torch.Tensor, temp_t: float, temp_d: float,
+                       tok_d: torch.Tensor, lse_q, u_acc: torch.Tensor, u_fin: torch.Tensor, workspace: torch.Tensor,
+                       out: dict | None = None, stream=None) -> dict:
+    """tli_verify with the drafter logits in compact layout: logits_c [B, K, S] with stride(1) = row stride."""
+    lib = load_library()
+    B, K1, Vt = logits_t.shape
+    K = K1 - 1
+    assert logits_t.is_cuda and logits_t.is_contiguous() and Vt == m.Vt and logits_t.dtype == logits_c.dtype
+    assert tuple(logits_c.shape) == (B, K, m.num_shared) and logits_c.stride(2) == 1
+    stride = logits_c.stride(1)
+    assert logits_c.stride(0) == K * stride
+    if out is None:
+        out = alloc_verify_outputs(B, K, logits_t.device)
+    rc = lib.tli_verify_compact(m.handle, _ptr(logits_t), _ptr(logits_c), stride, _dtype_code(logits_t), B, K,
+                                float(temp_t), float(temp_d), _ptr(tok_d), _ptr(lse_q), _ptr(u_acc), _ptr(u_fin),
+                                _ptr(out["n_accepted"]), _ptr(out["out_tok"]), _ptr(out.get("accept")),
+                                _ptr(out.get("p_tok")), _ptr(out.get("q_tok")), _ptr(out.get("lse_p")), _ptr(out["status"]),
+                                _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc != 0:
+        raise TliError(rc, "tli_verify_compact")
     return out
 
 

@@ -539,6 +539,7 @@ struct DraftOut {
     double *q_tok, *lse_q;
     int32_t* row_status;
     int64_t stride;  // entry of row r of every per-row array (u_draft included) is at index r * stride
+    const int32_t* r2d;  // compact rows: index in the row (= rank) -> drafter id; nullptr otherwise
 };
 
 // MASKED: the row is restricted to the shared ids (TLI's q').  Unmasked, the same code draws from the plain
@@ -563,8 +564,9 @@ __device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V,
         return;
     }
     const double lse = kLn2 * ((double)M * c_ratio + log2(total));
-    o.tok_d[at] = d;
-    if (o.tok_t) o.tok_t[at] = d2t ? d2t[d] : d;
+    const int id = o.r2d ? o.r2d[d] : d;  // the id reported: a drafter id also when the row is in compact layout
+    o.tok_d[at] = id;
+    if (o.tok_t) o.tok_t[at] = d2t ? d2t[id] : id;
     if (o.lse_q) o.lse_q[at] = lse;
     if (o.q_tok) o.q_tok[at] = exp((double)load_elem<DT>(rowp, d) * inv_temp - lse);
     o.row_status[at] = 0;
@@ -601,6 +603,17 @@ __global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ lo
     draft_pick_row<DT, MASKED>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tr, ts, o);
 }
 
+// ---- how the verification kernels address the drafter logits ------------------------------------
+// Full layout: rows of Vd logits in drafter-id order.  Compact layout (a drafter head pruned to the shared
+// tokens): rows of S logits in rank order (rank = position among the shared ids, ascending drafter id).
+struct DrafterView {
+    const void* base;
+    int64_t row_stride;    // elements between consecutive rows
+    const int32_t* d2x;    // drafter id -> index in a row; nullptr = identity (full layout)
+    const int32_t* t2x;    // target id -> index in a row, -1 for target-only ids (t2d full, t2r compact)
+    const int32_t* stage;  // rank -> index in a row (rank list of the map); nullptr = identity (compact layout)
+};
+
 // ---- what the final kernels need to know about a sequence, written once by the accept kernel ----
 struct ResidualParams {
     float ct_hi, ct_lo, lp_hi, lp_lo;  // target: p = 2^(x*ct - Lp), Lp = lse_p * log2 e
@@ -634,7 +647,7 @@ __device__ __forceinline__ void split_scale(double c, float& hi, float& lo) {
 // Standard SD appendix, verification loop and the count of accepted drafts.  grid (B), 64 threads;
 // lane k owns position k.
 template <int DT>
-__global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logits_t, const void* __restrict__ logits_d,
+__global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logits_t, DrafterView dv,
                                                    int K, int Vt, int Vd, int nsplit, const Part* __restrict__ part,
                                                    double ratio_t, double inv_temp_t, double inv_temp_d,
                                                    const int32_t* __restrict__ d2t, const int32_t* __restrict__ tok_d,
@@ -669,9 +682,10 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
         } else if (!nonfinite) {
             tt = d2t[d];
             const char* lt = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + k) * Vt * Traits<DT>::ESZ;
-            const char* ld = static_cast<const char*>(logits_d) + row * Vd * Traits<DT>::ESZ;
+            const char* ld = static_cast<const char*>(dv.base) + row * dv.row_stride * Traits<DT>::ESZ;
             pd = (tt < 0 || lse == -INFINITY) ? 0.0 : exp((double)load_elem<DT>(lt, tt) * inv_temp_t - lse);
-            qd = (union_mode && my_lq == -INFINITY) ? 0.0 : exp((double)load_elem<DT>(ld, d) * inv_temp_d - my_lq);
+            const int dx = dv.d2x ? dv.d2x[d] : d;
+            qd = (union_mode && my_lq == -INFINITY) ? 0.0 : exp((double)load_elem<DT>(ld, dx) * inv_temp_d - my_lq);
             acc = (double)u_acc[row] * qd < pd;
         }
         if (accept) accept[row] = acc ? 1 : 0;
@@ -779,7 +793,7 @@ struct FinalOut {
 };
 
 template <int DT>
-__device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const void* logits_t, const void* logits_d,
+__device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const void* logits_t, const DrafterView& dv,
                                                int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
                                                const int32_t* t2d, const float* tr, const float* ts,
                                                const float2* ctab, const double* mn, int nparts, int64_t mn_stride,
@@ -799,7 +813,7 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
         if (tok < 0) nonfinite = true;
         else if (lane == 0 && o.lse_p) o.lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
     } else {
-        const char* ldp = static_cast<const char*>(logits_d) + (int64_t)f.d_row * Vd * Traits<DT>::ESZ;
+        const char* ldp = static_cast<const char*>(dv.base) + (int64_t)f.d_row * dv.row_stride * Traits<DT>::ESZ;
         // chunk masses: sum_chunk p (from the normaliser kernel's table of row n) minus the parts' sums of min(p, q')
         const float2* crow = ctab + (int64_t)f.d_row * nC;
         auto p_mass = [&](int cc) {
@@ -898,9 +912,9 @@ template <int DT> constexpr int part_cap() { return kPartBytes / Traits<DT>::ESZ
 // mn = sum min(p, q') (TLI's expected acceptance rate), mn2 = sum min(p, q) (the union algorithm's).
 template <int DT, bool DIAG>
 __global__ __launch_bounds__(kScanWG) void k_final_scan(
-    const void* __restrict__ logits_t, const void* __restrict__ logits_d, int B, int K, int Vt, int Vd, int nC,
+    const void* __restrict__ logits_t, DrafterView dv, int B, int K, int Vt, int Vd, int nC,
     int nparts, int nsplit, int per, int S, float cs_t, double ratio_t, const FinalRow* __restrict__ frow,
-    const int32_t* __restrict__ sh_x, const int32_t* __restrict__ pl_start, const uint32_t* __restrict__ pl_e,
+    const int32_t* __restrict__ pl_start, const uint32_t* __restrict__ pl_e,
     float* __restrict__ tab_ref, float* __restrict__ tab_s, double* __restrict__ mn, double* __restrict__ mn2,
     int32_t* __restrict__ fbad) {
     constexpr int EPV = Traits<DT>::EPV;
@@ -935,7 +949,8 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     }
     if (!f.rp.use_q) return;  // q' = 0 everywhere: the masses are the chunk sums of p, nothing to subtract
     const raw_t* ld_row =
-        reinterpret_cast<const raw_t*>(static_cast<const char*>(logits_d) + (int64_t)f.d_row * Vd * ESZ);
+        reinterpret_cast<const raw_t*>(static_cast<const char*>(dv.base) + (int64_t)f.d_row * dv.row_stride * ESZ);
+    const int32_t* __restrict__ sh_x = dv.stage;
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
                                                     (int64_t)f.t_row * Vt * ESZ);
     const int nvec = (Vt + EPV - 1) / EPV;
@@ -949,14 +964,19 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         bool my_bad = false;
         int32_t xs[kStageU], xn[kStageU];
 #pragma unroll
-        for (int k = 0; k < kStageU; ++k) xs[k] = sh_x[min(r0 + tid + k * kScanWG, S - 1)];
+        for (int k = 0; k < kStageU; ++k) {
+            const int i = min(r0 + tid + k * kScanWG, S - 1);
+            xs[k] = sh_x ? sh_x[i] : i;  // compact rows are in rank order already
+        }
         for (int base = r0; base < r1; base += kStageU * kScanWG) {  // uniform bounds
             raw_t ys[kStageU];
 #pragma unroll
             for (int k = 0; k < kStageU; ++k) ys[k] = ld_row[xs[k]];
 #pragma unroll
-            for (int k = 0; k < kStageU; ++k)  // the next batch's ranks travel while the gathers are out
-                xn[k] = sh_x[min(base + kStageU * kScanWG + tid + k * kScanWG, S - 1)];
+            for (int k = 0; k < kStageU; ++k) {  // the next batch's ranks travel while the gathers are out
+                const int i = min(base + kStageU * kScanWG + tid + k * kScanWG, S - 1);
+                xn[k] = sh_x ? sh_x[i] : i;
+            }
 #pragma unroll
             for (int k = 0; k < kStageU; ++k) {
                 const int i = base + tid + k * kScanWG;
@@ -1065,7 +1085,7 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
 
 // kernel: draw the extra token of every sequence from its row's chunk tables.  grid (B), one wave.
 template <int DT>
-__global__ __launch_bounds__(kWave) void k_final_pick(const void* __restrict__ logits_t, const void* __restrict__ logits_d,
+__global__ __launch_bounds__(kWave) void k_final_pick(const void* __restrict__ logits_t, DrafterView dv,
                                                        int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
                                                        const FinalRow* __restrict__ frow,
                                                        const int32_t* __restrict__ t2d,
@@ -1077,7 +1097,7 @@ __global__ __launch_bounds__(kWave) void k_final_pick(const void* __restrict__ l
     const int b = blockIdx.x;
     const FinalRow f = frow[b];
     if (f.skip) return;
-    final_pick_row<DT>(f, b, logits_t, logits_d, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
+    final_pick_row<DT>(f, b, logits_t, dv, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
                        tab_s + (int64_t)b * nC, ctab, mn + (int64_t)b * nC, nparts, (int64_t)B * nC, fbad, o);
 }
 
@@ -1421,6 +1441,9 @@ struct VerifyArgs {
     FinalRow* frow;
     int32_t* fbad;
     int union_mode;  // 0: TLI (q' over the shared ids); 1: the union algorithm (q over all of D)
+    DrafterView dv;
+    int compact;     // drafter rows hold the S shared logits in rank order
+    int d_valid;     // valid entries of a drafter row (Vd, or S in the compact layout)
 };
 template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st);
 
@@ -1433,6 +1456,8 @@ struct tli_map {
     int32_t* t2d;    // dev [Vt padded to 8]
     uint64_t* lmask[2];  // dev, per dtype: shared-id mask of the drafter vocabulary in lane-mask layout
     int32_t* sh_x;   // dev [S]: drafter id of the shared token of rank r (ranks ascend with the drafter id)
+    int32_t* d2r;    // dev [Vd]: rank of a shared drafter id, -1 otherwise   } the index of a token in a drafter row
+    int32_t* t2r;    // dev [Vt padded to 8]: rank of a shared target id, -1   } stored in compact (rank-order) layout
     // Per dtype (index = tli_dtype), for the residual scan: the ranks are cut into nparts parts of `per`
     // ranks (what one workgroup keeps in LDS); the shared pairs are grouped by (part, target chunk), ranks
     // ascending inside a group.  pl_start [nparts * nC + 1]; pl_e [S]: offset of the target id in its
@@ -1471,7 +1496,8 @@ void launch_draft(const void* logits, int64_t row_stride, int R, int V, float te
 // checks, plan, scratch carving and launch shared by the draft entry points and the plain row sampler.
 int sample_rows_impl(const void* logits, int dtype, int64_t row_stride, int R, int V, float temp, uint64_t* const* bits2,
                      const int32_t* d2t, const float* u, int32_t* tok, int32_t* tok_t, double* p_tok, double* lse,
-                     int32_t* status, int64_t io_stride, void* workspace, size_t workspace_bytes, hipStream_t st) {
+                     int32_t* status, int64_t io_stride, void* workspace, size_t workspace_bytes, hipStream_t st,
+                     const int32_t* r2d = nullptr) {
     if (!logits || !u || !tok || !status || !workspace) return TLI_ERR_INVALID_ARG;
     if (R < 1 || R > 0x7fffffff / 64 || V < 1 || !(temp > 0.f) || !std::isfinite(temp) || io_stride < 1)
         return TLI_ERR_INVALID_ARG;
@@ -1492,6 +1518,7 @@ int sample_rows_impl(const void* logits, int dtype, int64_t row_stride, int R, i
     DraftOut o;
     o.u_draft = u; o.tok_d = tok; o.tok_t = tok_t; o.q_tok = p_tok; o.lse_q = lse; o.row_status = status;
     o.stride = io_stride;
+    o.r2d = r2d;
     if (bits2) {
         if (dtype == TLI_BF16)
             launch_draft<TLI_BF16, true>(logits, row_stride, R, V, temp, pl, cs, ratio, bits2[TLI_BF16], d2t, o, tab_ref, tab_s, st);
@@ -1561,14 +1588,16 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     fo.u_fin = a.u_fin; fo.n_accepted = a.n_accepted; fo.out_tok = a.out_tok; fo.lse_p = a.lse_p;
     fo.seq_status = a.seq_status;
     const double* lse_q = a.lse_q;
-    if (!lse_q) {  // the caller did not keep the drafter normalisers: one scan of the drafter rows (masked for TLI)
-        if (a.union_mode)
-            hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), 0, st, a.logits_d, K,
-                               (int64_t)K * Vd, (int64_t)Vd, Vd, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d, a.ratio_d,
+    if (!lse_q) {  // the caller did not keep the drafter normalisers: one scan of the drafter rows (masked for TLI
+                   // in the full layout; a compact row holds the shared ids only)
+        const int64_t rs = a.dv.row_stride;
+        if (a.union_mode || a.compact)
+            hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), 0, st, a.dv.base, K,
+                               (int64_t)K * rs, rs, a.d_valid, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d, a.ratio_d,
                                (const uint64_t*)nullptr, a.part_d, (float2*)nullptr);
         else
-            hipLaunchKernelGGL((k_lse<DT, true>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), 0, st, a.logits_d, K,
-                               (int64_t)K * Vd, (int64_t)Vd, Vd, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d, a.ratio_d,
+            hipLaunchKernelGGL((k_lse<DT, true>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), 0, st, a.dv.base, K,
+                               (int64_t)K * rs, rs, a.d_valid, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d, a.ratio_d,
                                a.map->lmask[DT], a.part_d, (float2*)nullptr);
         hipLaunchKernelGGL(k_lse_finish, dim3((rows + kWG - 1) / kWG), dim3(kWG), 0, st, a.part_d, rows, a.pd.nsplit,
                            a.ratio_d, a.ws_lse_q);
@@ -1582,7 +1611,7 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     }
     {
         KernelTimer t(TLI_KERNEL_ACCEPT, st);
-        hipLaunchKernelGGL(k_accept<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pl.nsplit,
+        hipLaunchKernelGGL(k_accept<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.dv, K, Vt, Vd, a.pl.nsplit,
                            a.part, a.ratio_t, a.inv_t, a.inv_d, a.map->d2t, a.tok_d, lse_q, a.u_acc, a.n_accepted,
                            a.out_tok, a.accept, a.p_tok, a.q_tok, a.lse_p, a.seq_status, a.ws_lse_p, a.c_t, a.c_d, a.frow,
                            a.fbad, a.union_mode);
@@ -1594,14 +1623,14 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
         int nsplit = 256 / (B * nparts);
         nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
         hipLaunchKernelGGL((k_final_scan<DT, false>), dim3((unsigned)((B + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0,
-                           st, a.logits_t, a.logits_d, B, K, Vt, Vd, a.pf.nC, nparts, nsplit, a.map->per[DT], a.map->S,
-                           a.cs_t, a.ratio_t, a.frow, a.map->sh_x, a.map->pl_start[DT], a.map->pl_e[DT], a.tab_ref,
-                           a.tab_s, a.mn, (double*)nullptr, a.fbad);
+                           st, a.logits_t, a.dv, B, K, Vt, Vd, a.pf.nC, nparts, nsplit, a.map->per[DT], a.map->S,
+                           a.cs_t, a.ratio_t, a.frow, a.map->pl_start[DT], a.map->pl_e[DT], a.tab_ref, a.tab_s, a.mn,
+                           (double*)nullptr, a.fbad);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
-        hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.logits_d, K, Vt, Vd, a.pf.nC,
-                           a.cs_t, a.ratio_t, a.frow, a.map->t2d, a.tab_ref, a.tab_s, a.ctab, a.mn,
+        hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.dv, K, Vt, Vd, a.pf.nC,
+                           a.cs_t, a.ratio_t, a.frow, a.dv.t2x, a.tab_ref, a.tab_s, a.ctab, a.mn,
                            a.map->nparts[DT], B, a.fbad, fo);
     }
 }
@@ -1658,8 +1687,9 @@ void launch_diag(const tli_map* map, const void* logits_t, const void* logits_d,
     int nsplit = 256 / (rows * nparts);
     nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
     hipLaunchKernelGGL((k_final_scan<DT, true>), dim3((unsigned)((rows + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0, st,
-                       logits_t, logits_d, rows, K, Vt, Vd, pt.nC, nparts, nsplit, map->per[DT], map->S, cs_t, ratio_t, frow,
-                       map->sh_x, map->pl_start[DT], map->pl_e[DT], (float*)nullptr, (float*)nullptr, mn, mn2, fbad);
+                       logits_t, DrafterView{logits_d, (int64_t)Vd, nullptr, map->t2d, map->sh_x}, rows, K, Vt, Vd, pt.nC,
+                       nparts, nsplit, map->per[DT], map->S, cs_t, ratio_t, frow, map->pl_start[DT], map->pl_e[DT],
+                       (float*)nullptr, (float*)nullptr, mn, mn2, fbad);
     hipLaunchKernelGGL(k_diag_finish, dim3(rows), dim3(kWave), 0, st, frow, mn, mn2, rows, nparts, pt.nC, alpha_tli,
                        alpha_union);
 }
@@ -1794,7 +1824,7 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
     tli_map* m = new (std::nothrow) tli_map();
     if (!m) return TLI_ERR_ALLOC;
     m->Vd = Vd; m->Vt = Vt; m->S = S; m->d2t = nullptr; m->t2d = nullptr; m->lmask[0] = m->lmask[1] = nullptr;
-    m->sh_x = nullptr;
+    m->sh_x = nullptr; m->d2r = nullptr; m->t2r = nullptr;
     for (int dt = 0; dt < 2; ++dt) {
         m->nparts[dt] = nparts[dt]; m->per[dt] = per[dt]; m->pl_start[dt] = nullptr; m->pl_e[dt] = nullptr;
     }
@@ -1808,8 +1838,16 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
          hipMemcpy(m->lmask[0], lmask[0].data(), lmask[0].size() * 8, hipMemcpyHostToDevice) == hipSuccess &&
          hipMemcpy(m->lmask[1], lmask[1].data(), lmask[1].size() * 8, hipMemcpyHostToDevice) == hipSuccess;
     if (!ok) { tli_free_map(m); return TLI_ERR_HIP; }
-    if (hipMalloc(&m->sh_x, (size_t)S * 4) != hipSuccess) { tli_free_map(m); return TLI_ERR_ALLOC; }
-    if (hipMemcpy(m->sh_x, sh_x.data(), (size_t)S * 4, hipMemcpyHostToDevice) != hipSuccess) {
+    std::vector<int32_t> d2r(Vd_pad, -1), t2r(Vt_pad, -1);
+    for (int32_t r = 0; r < S; ++r) { d2r[sh_x[r]] = r; t2r[d2t[sh_x[r]]] = r; }
+    if (hipMalloc(&m->sh_x, (size_t)S * 4) != hipSuccess || hipMalloc(&m->d2r, d2r.size() * 4) != hipSuccess ||
+        hipMalloc(&m->t2r, t2r.size() * 4) != hipSuccess) {
+        tli_free_map(m);
+        return TLI_ERR_ALLOC;
+    }
+    if (hipMemcpy(m->sh_x, sh_x.data(), (size_t)S * 4, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(m->d2r, d2r.data(), d2r.size() * 4, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(m->t2r, t2r.data(), t2r.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
         tli_free_map(m);
         return TLI_ERR_HIP;
     }
@@ -1834,6 +1872,8 @@ void tli_free_map(tli_map* m) {
     if (m->lmask[0]) (void)hipFree(m->lmask[0]);
     if (m->lmask[1]) (void)hipFree(m->lmask[1]);
     if (m->sh_x) (void)hipFree(m->sh_x);
+    if (m->d2r) (void)hipFree(m->d2r);
+    if (m->t2r) (void)hipFree(m->t2r);
     for (int dt = 0; dt < 2; ++dt) {
         if (m->pl_start[dt]) (void)hipFree(m->pl_start[dt]);
         if (m->pl_e[dt]) (void)hipFree(m->pl_e[dt]);
@@ -1863,6 +1903,16 @@ int tli_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, 
     return sample_rows_impl(logits_d, dtype, row_stride_elems, R, map->Vd, temp_d, map->lmask, map->d2t, u_draft, tok_d,
                             tok_t, q_tok, lse_q, row_status, io_stride, workspace, workspace_bytes,
                             static_cast<hipStream_t>(hip_stream));
+}
+
+int tli_draft_sample_compact(const tli_map* map, const void* logits_c, tli_dtype dtype, int64_t row_stride_elems,
+                             int32_t R, float temp_d, const float* u_draft, int32_t* tok_d, int32_t* tok_t, double* q_tok,
+                             double* lse_q, int32_t* row_status, int64_t io_stride, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+    if (!map || !tok_t || !lse_q) return TLI_ERR_INVALID_ARG;
+    return sample_rows_impl(logits_c, dtype, row_stride_elems, R, map->S, temp_d, nullptr, map->d2t, u_draft, tok_d, tok_t,
+                            q_tok, lse_q, row_status, io_stride, workspace, workspace_bytes,
+                            static_cast<hipStream_t>(hip_stream), map->sh_x);
 }
 
 int tli_union_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems,
@@ -1961,8 +2011,8 @@ size_t tli_exact_match_workspace_bytes(int32_t B, int32_t m, int32_t Vt, tli_dty
     return align256((size_t)R * sizeof(int32_t)) + rows_workspace(R, Vt, dtype);
 }
 
-static int verify_impl(int union_mode, const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype,
-                       int32_t B, int32_t K, float temp_t, float temp_d, const int32_t* tok_d, const double* lse_q,
+static int verify_impl(int union_mode, int64_t compact_stride, const tli_map* map, const void* logits_t,
+                       const void* logits_d, tli_dtype dtype, int32_t B, int32_t K, float temp_t, float temp_d, const int32_t* tok_d, const double* lse_q,
                        const float* u_acc, const float* u_fin, int32_t* n_accepted, int32_t* out_tok, uint8_t* accept,
                        double* p_tok, double* q_tok, double* lse_p, int32_t* seq_status, void* workspace,
                        size_t workspace_bytes, void* hip_stream) {
@@ -1975,9 +2025,10 @@ static int verify_impl(int union_mode, const tli_map* map, const void* logits_t,
     if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
     const int epv = dtype == TLI_BF16 ? 8 : 4;
     const int Vt = map->Vt, Vd = map->Vd;
-    // dense rows must each start on a 16-byte boundary
-    if (Vt % epv != 0 || Vd % epv != 0 || !aligned16(logits_t) || !aligned16(logits_d) || !aligned16(workspace))
-        return TLI_ERR_INVALID_ARG;
+    const bool compact = compact_stride != 0;
+    // dense rows must each start on a 16-byte boundary; compact drafter rows: S valid entries, compact_stride apart
+    if (Vt % epv != 0 || !aligned16(logits_t) || !aligned16(logits_d) || !aligned16(workspace)) return TLI_ERR_INVALID_ARG;
+    if (compact ? (compact_stride < map->S || compact_stride % epv != 0) : (Vd % epv != 0)) return TLI_ERR_INVALID_ARG;
     const Workspace w = layout(B, K, Vt, Vd, dtype);
     if (workspace_bytes < w.total) return TLI_ERR_ALLOC;
     char* ws = static_cast<char*>(workspace);
@@ -2001,7 +2052,14 @@ static int verify_impl(int union_mode, const tli_map* map, const void* logits_t,
     a.out_tok = out_tok; a.accept = accept; a.p_tok = p_tok; a.q_tok = q_tok; a.lse_p = lse_p;
     a.seq_status = seq_status; a.part = part; a.ws_lse_p = ws_lse_p;
     a.part_d = reinterpret_cast<Part*>(ws + w.part_d); a.ws_lse_q = reinterpret_cast<double*>(ws + w.ws_lse_q);
-    a.pd = make_plan(Vd, rows, chunk); a.cs_d = (float)c_d; a.ratio_d = c_d / (double)a.cs_d; a.tab_ref = tab_ref; a.tab_s = tab_s;
+    a.compact = compact ? 1 : 0;
+    a.d_valid = compact ? map->S : Vd;
+    a.dv.base = logits_d;
+    a.dv.row_stride = compact ? compact_stride : (int64_t)Vd;
+    a.dv.d2x = compact ? map->d2r : nullptr;
+    a.dv.t2x = compact ? map->t2r : map->t2d;
+    a.dv.stage = compact ? nullptr : map->sh_x;
+    a.pd = make_plan(a.d_valid, rows, chunk); a.cs_d = (float)c_d; a.ratio_d = c_d / (double)a.cs_d; a.tab_ref = tab_ref; a.tab_s = tab_s;
     a.mn = reinterpret_cast<double*>(ws + w.mn); a.fbad = reinterpret_cast<int32_t*>(ws + w.fbad); a.ctab = reinterpret_cast<float2*>(ws + w.ctab);
     a.frow = reinterpret_cast<FinalRow*>(ws + w.frow);
     a.union_mode = union_mode;
@@ -2015,8 +2073,19 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
                const float* u_fin, int32_t* n_accepted, int32_t* out_tok, uint8_t* accept, double* p_tok,
                double* q_tok, double* lse_p, int32_t* seq_status, void* workspace, size_t workspace_bytes,
                void* hip_stream) {
-    return verify_impl(0, map, logits_t, logits_d, dtype, B, K, temp_t, temp_d, tok_d, lse_q, u_acc, u_fin, n_accepted,
+    return verify_impl(0, 0, map, logits_t, logits_d, dtype, B, K, temp_t, temp_d, tok_d, lse_q, u_acc, u_fin, n_accepted,
                        out_tok, accept, p_tok, q_tok, lse_p, seq_status, workspace, workspace_bytes, hip_stream);
+}
+
+int tli_verify_compact(const tli_map* map, const void* logits_t, const void* logits_c, int64_t c_row_stride_elems,
+                       tli_dtype dtype, int32_t B, int32_t K, float temp_t, float temp_d, const int32_t* tok_d,
+                       const double* lse_q, const float* u_acc, const float* u_fin, int32_t* n_accepted, int32_t* out_tok,
+                       uint8_t* accept, double* p_tok, double* q_tok, double* lse_p, int32_t* seq_status, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+    if (c_row_stride_elems < 1) return TLI_ERR_INVALID_ARG;
+    return verify_impl(0, c_row_stride_elems, map, logits_t, logits_c, dtype, B, K, temp_t, temp_d, tok_d, lse_q, u_acc,
+                       u_fin, n_accepted, out_tok, accept, p_tok, q_tok, lse_p, seq_status, workspace, workspace_bytes,
+                       hip_stream);
 }
 
 int tli_union_verify(const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype, int32_t B,
@@ -2024,7 +2093,7 @@ int tli_union_verify(const tli_map* map, const void* logits_t, const void* logit
                      const float* u_acc, const float* u_fin, int32_t* n_accepted, int32_t* out_tok, uint8_t* accept,
                      double* p_tok, double* q_tok, double* lse_p, int32_t* seq_status, void* workspace,
                      size_t workspace_bytes, void* hip_stream) {
-    return verify_impl(1, map, logits_t, logits_d, dtype, B, K, temp_t, temp_d, tok_d, lse_q, u_acc, u_fin, n_accepted,
+    return verify_impl(1, 0, map, logits_t, logits_d, dtype, B, K, temp_t, temp_d, tok_d, lse_q, u_acc, u_fin, n_accepted,
                        out_tok, accept, p_tok, q_tok, lse_p, seq_status, workspace, workspace_bytes, hip_stream);
 }
 

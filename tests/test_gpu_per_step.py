@@ -103,3 +103,47 @@ def test_iteration_in_a_hip_graph_replays_exactly():
         for k in want:
             assert torch.equal(got[k].view(torch.uint8), want[k].view(torch.uint8)), (rep, k)
     m.free()
+
+
+COMPACT = [(5, 3, 2048 * 3 + 40, 2048 * 2 + 24, 1500, "bf16"), (3, 4, 1024 * 4 + 28, 1024 + 4, 700, "f32"),
+           (300, 2, 5000, 4104, 1501, "bf16"), (2, 2, 2048 * 30 + 16, 2048 * 27 + 8, 50000, "bf16")]
+
+
+@pytest.mark.parametrize("shape", COMPACT, ids=[f"B{c[0]}_S{c[4]}_{c[5]}" for c in COMPACT])
+def test_compact_drafter_layout(oracle, shape):
+    """Drafter rows that hold only the shared tokens' logits (rank order): draft and verify must give what the
+    full-layout oracle gives on the original rows (q' does not depend on the logits outside the intersection)."""
+    B, K, Vt, Vd, S, dtype = shape
+    w = synth.WORKLOADS[3].scaled(B=B, K=K, Vt=Vt, Vd=Vd, S=S, dtype=dtype, cfg=62)
+    inp = synth.make_inputs(w, DEV)
+    d2t = inp["d2t"]
+    m = binding.tli_build_map(d2t, w.Vt)
+    code = binding.TLI_F32 if dtype == "f32" else binding.TLI_BF16
+    ws = binding.alloc_workspace(w.B, w.K, m, code, DEV)
+    sh_x = torch.from_numpy(np.nonzero(d2t >= 0)[0]).to(DEV)
+    epv = 4 if dtype == "f32" else 8
+    stride = (S + epv - 1) // epv * epv + epv  # a wider row than needed; the padding holds large values
+    buf = torch.full((B, K, stride), 40.0, dtype=inp["logits_d"].dtype, device=DEV)
+    buf[:, :, :S] = inp["logits_d"].index_select(2, sh_x)
+    ldc = buf[:, :, :S]
+    ld_np, lt_np = synth.logits_to_numpy(inp["logits_d"]), synth.logits_to_numpy(inp["logits_t"])
+    ud = inp["u_draft"].cpu().numpy().astype(np.float64)
+    g = binding.tli_draft_sample_compact(m, buf.reshape(B * K, stride)[:, :S], w.tau_d, inp["u_draft"].reshape(-1), ws)
+    torch.cuda.synchronize()
+    gh = parity.to_host(g)
+    rep, ref = parity.compare_draft(oracle, ld_np.reshape(B * K, Vd), w.tau_d, d2t, ud, gh, threads=8)
+    assert rep["hard"] == 0 and rep["max_lse_err"] < 5e-7
+    full = parity.to_host(binding.tli_draft_sample(m, inp["logits_d"], w.tau_d, inp["u_draft"].reshape(-1), ws))
+    assert np.array_equal(gh["tok_d"], full["tok_d"]) and np.array_equal(gh["tok_t"], full["tok_t"])
+    ua = inp["u_acc"].cpu().numpy().astype(np.float64)
+    uf = inp["u_fin"].cpu().numpy().astype(np.float64)
+    tok = torch.from_numpy(ref["tok_d"]).to(DEV)
+    for lse_q in (torch.from_numpy(ref["lse_q"]).to(DEV), None):
+        gv = binding.tli_verify_compact(m, inp["logits_t"], ldc, w.tau_t, w.tau_d, tok, lse_q, inp["u_acc"].reshape(-1),
+                                        inp["u_fin"], ws)
+        torch.cuda.synchronize()
+        rv, _ = parity.compare_verify(oracle, lt_np, ld_np, w.tau_t, w.tau_d, d2t, ref["tok_d"], ua, uf, parity.to_host(gv),
+                                      threads=8)
+        print(dict(rv))
+        assert rv["hard"] == 0 and rv["max_lse_err"] < 5e-7 and rv["max_prob_rel"] < 1e-6
+    m.free()
