@@ -962,33 +962,49 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     {
         const int r0 = p * per, r1 = min(S, r0 + per);
         bool my_bad = false;
+        const uint32_t em = (DT == TLI_BF16) ? 0x7f80u : 0x7f800000u;     // NaN or +inf in a shared drafter logit
+        const uint32_t ninf = (DT == TLI_BF16) ? 0xff80u : 0xff800000u;   // must surface (-inf is legal)
+        if (!sh_x) {
+            // compact rows are in rank order already: the part is a contiguous, 16-byte aligned stretch of the row
+            // (parts start at multiples of 8 ranks; the row stride covers S rounded up to a whole vector)
+            const u4v* src = reinterpret_cast<const u4v*>(ld_row + r0);
+            u4v* dst = reinterpret_cast<u4v*>(dpart);
+            const int nv = (r1 - r0 + EPV - 1) / EPV;
+            for (int v = tid; v < nv; v += kScanWG) {
+                const u4v t = src[v];
+                dst[v] = t;
+                uint32_t raw[EPV];
+                if constexpr (DT == TLI_BF16) {
+                    raw[0] = t.x & 0xffffu; raw[1] = t.x >> 16; raw[2] = t.y & 0xffffu; raw[3] = t.y >> 16;
+                    raw[4] = t.z & 0xffffu; raw[5] = t.z >> 16; raw[6] = t.w & 0xffffu; raw[7] = t.w >> 16;
+                } else {
+                    raw[0] = t.x; raw[1] = t.y; raw[2] = t.z; raw[3] = t.w;
+                }
+#pragma unroll
+                for (int i = 0; i < EPV; ++i)
+                    if (r0 + v * EPV + i < r1 && (raw[i] & em) == em && raw[i] != ninf) my_bad = true;
+            }
+        } else {
         int32_t xs[kStageU], xn[kStageU];
 #pragma unroll
-        for (int k = 0; k < kStageU; ++k) {
-            const int i = min(r0 + tid + k * kScanWG, S - 1);
-            xs[k] = sh_x ? sh_x[i] : i;  // compact rows are in rank order already
-        }
+        for (int k = 0; k < kStageU; ++k) xs[k] = sh_x[min(r0 + tid + k * kScanWG, S - 1)];
         for (int base = r0; base < r1; base += kStageU * kScanWG) {  // uniform bounds
             raw_t ys[kStageU];
 #pragma unroll
             for (int k = 0; k < kStageU; ++k) ys[k] = ld_row[xs[k]];
 #pragma unroll
-            for (int k = 0; k < kStageU; ++k) {  // the next batch's ranks travel while the gathers are out
-                const int i = min(base + kStageU * kScanWG + tid + k * kScanWG, S - 1);
-                xn[k] = sh_x ? sh_x[i] : i;
-            }
+            for (int k = 0; k < kStageU; ++k)  // the next batch's ranks travel while the gathers are out
+                xn[k] = sh_x[min(base + kStageU * kScanWG + tid + k * kScanWG, S - 1)];
 #pragma unroll
             for (int k = 0; k < kStageU; ++k) {
                 const int i = base + tid + k * kScanWG;
                 if (i < r1) {
                     dpart[i - r0] = ys[k];
-                    // NaN or +inf in a shared drafter logit must surface
-                    const uint32_t em = (DT == TLI_BF16) ? 0x7f80u : 0x7f800000u;
-                    const uint32_t ninf = (DT == TLI_BF16) ? 0xff80u : 0xff800000u;
                     if (((uint32_t)ys[k] & em) == em && (uint32_t)ys[k] != ninf) my_bad = true;
                 }
                 xs[k] = xn[k];
             }
+        }
         }
         if (my_bad) fbad[b] = 1;
     }
@@ -1794,7 +1810,7 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
         const int esz = dt == TLI_BF16 ? 2 : 4;
         const int nC = (Vt + CH - 1) / CH;
         nparts[dt] = (S + cap - 1) / cap;
-        per[dt] = (S + nparts[dt] - 1) / nparts[dt];
+        per[dt] = ((S + nparts[dt] - 1) / nparts[dt] + 7) & ~7;  // a multiple of 8 (<= cap): parts start on 16 bytes
         const size_t ngroups = (size_t)nparts[dt] * nC;
         pl_start[dt].assign(ngroups + 1, 0);
         pl_e[dt].resize(S);
