@@ -309,6 +309,35 @@ def greedy_draft(logits_d: np.ndarray, d2t: np.ndarray, threads: int = 1):
     return _rows_call("tlo_greedy_draft", ld, R, Vd, threads, args, out)
 
 
+def warp_rows(logits: np.ndarray, tau: float, top_k: int, top_p: float, d2t=None, threads: int = 1):
+    """top-k / top-p thresholds of rows [R, V]: thr, kept, keep_mask [R, V] uint8, status, margin."""
+    lib = _load()
+    lg = np.ascontiguousarray(logits)
+    R, V = lg.shape
+    dd = None if d2t is None else _c(d2t, np.int32)
+    out = dict(thr=np.empty(R, np.float64), kept=np.empty(R, np.int32), keep_mask=np.empty((R, V), np.uint8),
+               status=np.empty(R, np.int32), margin=np.empty(R, np.float64))
+    code = _dtype_code(lg)
+    esz = lg.dtype.itemsize
+
+    def run(lo, hi):
+        if hi <= lo:
+            return
+        work = np.empty(V, np.float64)
+
+        def off(a):
+            per = int(np.prod(a.shape[1:])) if a.ndim > 1 else 1
+            return ctypes.c_void_p(a.ctypes.data + lo * per * a.dtype.itemsize)
+
+        lib.tlo_warp_rows(ctypes.c_void_p(lg.ctypes.data + lo * V * esz), code, ctypes.c_int64(V), ctypes.c_int64(hi - lo),
+                          ctypes.c_int64(V), ctypes.c_double(tau), ctypes.c_void_p(0) if dd is None else _p(dd),
+                          ctypes.c_int64(int(top_k)), ctypes.c_double(float(top_p)), off(out["thr"]), off(out["kept"]),
+                          off(out["keep_mask"]), off(out["status"]), off(out["margin"]), _p(work))
+
+    _fan_out(run, R, threads)
+    return out
+
+
 def _fan_out(run, n, threads):
     """Independent rows / sequences split over `threads` host threads (ctypes drops the GIL)."""
     threads = max(1, min(int(threads), n))

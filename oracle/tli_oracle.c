@@ -545,3 +545,88 @@ void tlo_greedy_draft(const void *logits_d, int dtype, int64_t row_stride, int64
         tok_t[r] = (d >= 0) ? d2t[d] : -1;
     }
 }
+
+/* ======================================================================================================
+ * Logit warpers ahead of the softmax (top-k, top-p).  The paper does not use them (its runs are plain
+ * temperature sampling, or temperature zero); they are the standard serving knobs around the same softmax
+ * and are defined here by value thresholds so that the result does not depend on any sort order:
+ *   top-k : keep the ids whose logit is >= the k-th largest competing logit (equal logits at the
+ *           threshold are all kept, so more than k ids may survive);
+ *   top-p : on the distribution that survived top-k (renormalised), keep id x iff the probability mass of
+ *           the ids with a strictly larger logit is < top_p -- the smallest top set whose mass reaches
+ *           top_p, with equal logits kept or dropped together.  The largest logit is always kept.
+ * A dropped id gets logit -inf, i.e. probability zero in every later step.
+ * ====================================================================================================== */
+typedef struct { double v; } tlo_val;
+static int cmp_desc(const void *a, const void *b) {
+    double x = ((const tlo_val *)a)->v, y = ((const tlo_val *)b)->v;
+    return (x < y) - (x > y);
+}
+
+/*
+ * For each of R rows: threshold thr[r] (a logit value; -inf if nothing is dropped), kept[r] = number of
+ * surviving ids, keep_mask[r*V + x] in {0,1}; margin[r] = distance of the top-p decision from flipping:
+ * min over the two neighbouring cut positions of |mass_above / Z_k - top_p| (inf if top-p is off).
+ * d2t != NULL: only ids with d2t[x] >= 0 compete, the others are dropped outright.
+ * top_k <= 0 switches top-k off, top_p >= 1 switches top-p off.  tau > 0.
+ * status: NONFINITE if a competing logit is NaN/+inf, ZERO_MASS if none competes or all are -inf (then
+ * nothing is kept, thr = NaN).  work: V tlo_val-sized doubles.
+ */
+void tlo_warp_rows(const void *logits, int dtype, int64_t row_stride, int64_t R, int64_t V, double tau,
+                   const int32_t *d2t, int64_t top_k, double top_p, double *thr, int32_t *kept,
+                   uint8_t *keep_mask, int32_t *status, double *margin, double *work) {
+    size_t esz = (dtype == TLO_F32) ? 4 : 2;
+    tlo_val *s = (tlo_val *)work;
+    for (int64_t r = 0; r < R; ++r) {
+        const void *row = (const char *)logits + (size_t)r * (size_t)row_stride * esz;
+        int64_t n = 0;
+        int bad = 0;
+        for (int64_t x = 0; x < V; ++x) {
+            keep_mask[r * V + x] = 0;
+            if (d2t && d2t[x] < 0) continue;
+            double z = load_logit(row, dtype, x);
+            if (isnan(z) || z == INFINITY) bad = 1;
+            if (z > -INFINITY) s[n++].v = z;
+        }
+        thr[r] = NAN; kept[r] = 0; margin[r] = INFINITY;
+        if (bad) { status[r] = TLO_NONFINITE; continue; }
+        if (n == 0) { status[r] = TLO_ZERO_MASS; continue; }
+        status[r] = 0;
+        qsort(s, (size_t)n, sizeof(tlo_val), cmp_desc);
+        /* top-k: value of the k-th largest, all ties kept */
+        int64_t nk = n;
+        double th = -INFINITY;
+        if (top_k > 0 && top_k < n) {
+            th = s[top_k - 1].v;
+            nk = top_k;
+            while (nk < n && s[nk].v == th) ++nk;
+        }
+        /* top-p on the survivors */
+        if (top_p < 1.0) {
+            double M = s[0].v / tau, Z = 0.0;
+            for (int64_t i = 0; i < nk; ++i) Z += exp(s[i].v / tau - M);
+            double above = 0.0;   /* mass of strictly larger logits, as a fraction of Z */
+            int64_t i = 0, cut = nk;
+            double best_margin = INFINITY;
+            while (i < nk) {
+                int64_t j = i;
+                double g = 0.0;
+                while (j < nk && s[j].v == s[i].v) { g += exp(s[j].v / tau - M); ++j; }
+                double frac = above / Z;
+                if (i > 0 && fabs(frac - top_p) < best_margin) best_margin = fabs(frac - top_p);
+                if (!(frac < top_p)) { cut = i; break; }
+                above += g;
+                i = j;
+            }
+            margin[r] = best_margin;
+            if (cut < nk) { nk = cut; th = s[cut - 1].v; }
+        }
+        thr[r] = th;
+        kept[r] = (int32_t)nk;
+        for (int64_t x = 0; x < V; ++x) {
+            if (d2t && d2t[x] < 0) continue;
+            double z = load_logit(row, dtype, x);
+            keep_mask[r * V + x] = (z > -INFINITY && z >= th) ? 1 : 0;
+        }
+    }
+}

@@ -332,3 +332,83 @@ def test_temperature_zero_tli_is_exact_match_on_argmax(oracle):
     assert np.array_equal(cold_d["tok_d"].reshape(B, K)[sep], gd["tok_d"].reshape(B, K)[sep])
     assert np.array_equal(cold_v["n_acc"][sep], v0["n_acc"][sep]) and np.array_equal(cold_v["out_tok"][sep], v0["out_tok"][sep])
     assert set(v0["n_acc"]) == set(range(K + 1))
+
+
+# ---------------------------------------------------------------- logit warpers (top-k, top-p)
+def ref_warp(x, tau, top_k, top_p, comp):
+    """numpy statement of the warpers: grouped by distinct value (np.unique), independent of the oracle's loop."""
+    xs = np.where(comp, x, -np.inf)
+    vals, counts = np.unique(xs[np.isfinite(xs)], return_counts=True)
+    vals, counts = vals[::-1], counts[::-1]  # descending
+    n_above = np.concatenate([[0], np.cumsum(counts)[:-1]])
+    keep_g = np.ones(len(vals), bool)
+    if 0 < top_k < counts.sum():
+        keep_g &= n_above < top_k
+    if top_p < 1.0:
+        w = np.where(keep_g, counts * np.exp((vals - vals[0]) / tau), 0.0)
+        frac_above = np.concatenate([[0.0], np.cumsum(w)[:-1]]) / w.sum()
+        keep_g &= frac_above < top_p
+    thr = vals[keep_g].min() if not keep_g.all() else -np.inf
+    return thr, np.isfinite(xs) & (xs >= thr)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_warp_rows_matches_numpy_and_its_defining_properties(oracle, dtype):
+    w = synth.WORKLOADS[1].scaled(B=3, K=2, Vt=900, Vd=600, S=250, dtype=dtype)
+    inp = synth.make_inputs(w)
+    rows = synth.logits_to_numpy(inp["logits_t"]).reshape(9, 900)
+    rf = inp["logits_t"].double().numpy().reshape(9, 900)
+    rf[0, :50] = -np.inf
+    rows[0, :50] = 0xFF80 if dtype == "bf16" else np.float32(-np.inf)
+    all_ids = np.ones(900, bool)
+    for top_k, top_p, tau in [(0, 1.0, 1.0), (5, 1.0, 1.0), (50, 0.9, 0.7), (0, 0.5, 1.3), (1, 0.3, 1.0), (2000, 0.999, 1.0),
+                              (0, 1e-9, 1.0)]:
+        got = oracle.warp_rows(rows, tau, top_k, top_p)
+        for r in range(9):
+            thr, mask = ref_warp(rf[r], tau, top_k, top_p, all_ids)
+            assert np.array_equal(got["keep_mask"][r].astype(bool), mask), (top_k, top_p, r)
+            assert got["kept"][r] == mask.sum() and (got["thr"][r] == thr)
+            x = rf[r]
+            kept, fin = mask, np.isfinite(rf[r])
+            assert kept.any() and kept[np.argmax(x)]                      # the largest logit always survives
+            assert x[kept].min() >= x[fin & ~kept].max() if (fin & ~kept).any() else True
+            if 0 < top_k < fin.sum():
+                assert (x > x[kept].min()).sum() < max(top_k, 1) or top_p < 1.0
+                assert kept.sum() >= min(top_k, fin.sum()) or top_p < 1.0
+            if top_p < 1.0:
+                # minimality: the survivors reach top_p of the top-k mass, and without their lowest value they do not
+                tk = ref_warp(x, tau, top_k, 1.0, all_ids)[1]
+                p = np.where(tk, np.exp((x - x[fin].max()) / tau), 0.0)
+                p /= p.sum()
+                assert p[kept].sum() >= top_p - 1e-12 or kept.sum() == tk.sum()
+                lowest = kept & (x == x[kept].min())
+                assert p[kept & ~lowest].sum() < top_p
+    # restricted to the shared ids of a map (TLI drafter rows): unshared ids never survive
+    ld = synth.logits_to_numpy(inp["logits_d"]).reshape(6, 600)
+    lf = inp["logits_d"].double().numpy().reshape(6, 600)
+    d2t = inp["d2t"]
+    got = oracle.warp_rows(ld, 0.8, 20, 0.95, d2t=d2t)
+    for r in range(6):
+        thr, mask = ref_warp(lf[r], 0.8, 20, 0.95, d2t >= 0)
+        assert np.array_equal(got["keep_mask"][r].astype(bool), mask) and not mask[d2t < 0].any()
+
+
+def test_warp_rows_ties_margin_and_flags(oracle):
+    x = np.array([[1.0, 3.0, 2.0, 3.0, 0.5, -1.0, 2.0]], np.float32)
+    g = oracle.warp_rows(x, 1.0, 1, 1.0)
+    assert list(g["keep_mask"][0]) == [0, 1, 0, 1, 0, 0, 0] and g["kept"][0] == 2 and g["thr"][0] == 3.0  # ties stay together
+    g = oracle.warp_rows(x, 1.0, 3, 1.0)
+    assert g["kept"][0] == 4 and g["thr"][0] == 2.0
+    p = np.exp(x[0].astype(np.float64))
+    p /= p.sum()
+    top = p[[1, 3]].sum()
+    g = oracle.warp_rows(x, 1.0, 0, top + 1e-9)      # just above the mass of the top group: the next group is needed
+    assert g["kept"][0] == 4 and abs(g["margin"][0] - 1e-9) < 1e-12
+    g = oracle.warp_rows(x, 1.0, 0, top - 1e-9)
+    assert g["kept"][0] == 2 and abs(g["margin"][0] - 1e-9) < 1e-12
+    bad = x.copy()
+    bad[0, 2] = np.nan
+    assert oracle.warp_rows(bad, 1.0, 2, 0.9)["status"][0] == oracle.NONFINITE
+    none = np.full((1, 5), -np.inf, np.float32)
+    g = oracle.warp_rows(none, 1.0, 2, 0.9)
+    assert g["status"][0] == oracle.ZERO_MASS and g["kept"][0] == 0
