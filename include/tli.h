@@ -223,6 +223,27 @@ int tli_exact_match_verify(const void* logits_t, tli_dtype dtype, int32_t B, int
                            void* hip_stream);
 
 /*
+ * Logit warpers ahead of the softmax (the standard serving knobs; the paper itself samples at plain temperature
+ * or temperature zero).  Both are thresholds on the logit VALUE, so equal logits are kept or dropped together:
+ *   top_k > 0 : keep the logits >= the k-th largest competing logit (more than k survive on ties);
+ *   top_p < 1 : on what survived top-k (renormalised at `temp`), keep x iff the probability mass of the strictly
+ *               larger logits is < top_p (the smallest top set reaching top_p; the largest logit always survives).
+ * logits_out receives the rows with every dropped logit set to -inf (same dtype; it may alias `logits`), so every
+ * other entry point runs unchanged on warped rows.  With a map only the shared drafter ids compete (V must be Vd)
+ * and unshared ids are dropped: the warped adjusted drafter of the intersection algorithm.
+ *   logits dev [R rows, row_stride_elems apart, V valid], logits_out dev [R rows, out_stride_elems apart]
+ *   thr dev [R] fp32: the threshold (-inf if nothing was dropped, NaN if the row is flagged); may be NULL
+ *   kept dev [R] int32: number of surviving ids; may be NULL.  row_status dev [R]: NONFINITE / ZERO_MASS (such rows
+ *   come out all -inf).
+ * One workgroup per row and one pass over the rows per radix level: built for batches, not tuned for few rows.
+ */
+size_t tli_warp_workspace_bytes(int32_t R, int32_t V, tli_dtype dtype);
+int tli_warp_rows(const tli_map* map, const void* logits, tli_dtype dtype, int64_t row_stride_elems, int32_t R,
+                  int32_t V, float temp, int32_t top_k, float top_p, void* logits_out, int64_t out_stride_elems,
+                  float* thr, int32_t* kept, int32_t* row_status, void* workspace, size_t workspace_bytes,
+                  void* hip_stream);
+
+/*
  * Optional per-kernel timing for benchmarks (not part of the method): while enabled, the hot calls
  * record a HIP event pair around each selected kernel on the caller's stream.  Not thread-safe.
  *   tli_profile_enable  : creates 2*max_calls events per selected kernel (bit k of kernel_mask selects

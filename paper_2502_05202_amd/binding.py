@@ -24,6 +24,7 @@ EXPORTS = (
     "tli_union_draft_sample", "tli_union_verify", "tli_acceptance_rates_workspace_bytes", "tli_acceptance_rates",
     "tli_sample_rows_workspace_bytes", "tli_sample_rows", "tli_greedy_draft", "tli_exact_match_workspace_bytes",
     "tli_exact_match_verify", "tli_draft_sample_compact", "tli_verify_compact",
+    "tli_warp_workspace_bytes", "tli_warp_rows",
 )
 KERNELS = ("lse", "accept", "final_scan", "final_pick", "draft_scan", "draft_pick")
 
@@ -65,6 +66,11 @@ def load_library() -> ctypes.CDLL:
     lib.tli_verify_compact.argtypes = [vp, vp, vp, i64, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp, vp,
                                        vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.tli_verify_compact.restype = ctypes.c_int
+    lib.tli_warp_workspace_bytes.argtypes = [i32, i32, ctypes.c_int]
+    lib.tli_warp_workspace_bytes.restype = ctypes.c_size_t
+    lib.tli_warp_rows.argtypes = [vp, vp, ctypes.c_int, i64, i32, i32, f32, i32, f32, vp, i64, vp, vp, vp, vp,
+                                  ctypes.c_size_t, vp]
+    lib.tli_warp_rows.restype = ctypes.c_int
     lib.tli_union_draft_sample.argtypes = lib.tli_draft_sample.argtypes
     lib.tli_union_draft_sample.restype = ctypes.c_int
     lib.tli_union_verify.argtypes = lib.tli_verify.argtypes
@@ -327,6 +333,30 @@ def tli_sample_rows(logits: torch.Tensor, temp: float, u: torch.Tensor | None, w
     if rc != 0:
         raise TliError(rc, "tli_sample_rows")
     return out
+
+
+def tli_warp_rows(logits: torch.Tensor, temp: float, top_k: int, top_p: float, m: TliMap | None = None,
+                  out: torch.Tensor | None = None, workspace: torch.Tensor | None = None, stream=None) -> dict:
+    """top-k / top-p on rows logits [R, V]: returns the warped rows (dropped = -inf; `out` may be `logits` itself),
+    thr, kept, status.  With a map only the shared drafter ids compete."""
+    lib = load_library()
+    assert logits.is_cuda and logits.dim() == 2 and logits.stride(-1) == 1
+    R, V = logits.shape
+    code = _dtype_code(logits)
+    if out is None:
+        out = torch.empty_like(logits, memory_format=torch.contiguous_format)
+    assert out.shape == logits.shape and out.dtype == logits.dtype and out.stride(-1) == 1
+    if workspace is None:
+        workspace = torch.empty(int(lib.tli_warp_workspace_bytes(R, V, code)), dtype=torch.uint8, device=logits.device)
+    dev = logits.device
+    res = dict(logits=out, thr=torch.empty(R, dtype=torch.float32, device=dev),
+               kept=torch.empty(R, dtype=torch.int32, device=dev), status=torch.empty(R, dtype=torch.int32, device=dev))
+    rc = lib.tli_warp_rows(None if m is None else m.handle, _ptr(logits), code, logits.stride(0), R, V, float(temp),
+                           int(top_k), float(top_p), _ptr(out), out.stride(0), _ptr(res["thr"]), _ptr(res["kept"]),
+                           _ptr(res["status"]), _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc != 0:
+        raise TliError(rc, "tli_warp_rows")
+    return res
 
 
 def tli_greedy_draft(m: TliMap, logits_d: torch.Tensor, workspace: torch.Tensor, stream=None) -> dict:

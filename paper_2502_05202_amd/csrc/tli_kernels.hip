@@ -1335,6 +1335,247 @@ __global__ __launch_bounds__(kWave) void k_match(const int32_t* __restrict__ tgt
     if (j == 0) { n_accepted[b] = n; seq_status[b] = any; }
 }
 
+// ---- logit warpers ahead of the softmax: top-k and top-p by value thresholds -----------------------
+// The paper samples at plain temperature (or temperature zero); these are the standard serving knobs around
+// the same softmax.  Both are defined by a threshold on the logit VALUE, so equal logits are kept or dropped
+// together and nothing depends on a sort order:
+//   top-k: keep logits >= the k-th largest competing logit;
+//   top-p: on what survived top-k (renormalised), keep x iff the mass of strictly larger logits is < top_p.
+// The threshold is found by a most-significant-digit-first radix descent over an order-preserving integer key
+// of the logit (16 bits for bf16: two 8-bit digits; 32 bits for fp32: digits of 11, 11 and 10 bits).  Each
+// level is one pass over the rows: a workgroup per row histograms the digit of the elements whose higher
+// digits match the prefix found so far -- element counts (top-k) and probability mass (top-p, in 2^-48 fixed
+// point so that sums do not depend on the order of arrival) -- and then picks the digit in which the
+// threshold lies.  A last pass writes the rows with every dropped logit set to -inf.
+constexpr int kWarpBinsMax = 2048;
+constexpr double kMassScale = 281474976710656.0;  // 2^48
+template <int DT> struct WarpKey;
+template <> struct WarpKey<TLI_BF16> {
+    static constexpr int LEVELS = 2;
+    __host__ __device__ static constexpr int bits(int) { return 8; }
+    __host__ __device__ static constexpr int shift(int level) { return level == 0 ? 8 : 0; }
+};
+template <> struct WarpKey<TLI_F32> {
+    static constexpr int LEVELS = 3;
+    __host__ __device__ static constexpr int bits(int level) { return level == 2 ? 10 : 11; }
+    __host__ __device__ static constexpr int shift(int level) { return level == 0 ? 21 : (level == 1 ? 10 : 0); }
+};
+
+// order-preserving key of a logit given as fp32 bits (bf16 logits arrive widened: only the top 16 bits are used);
+// -0 is folded onto +0 so that equal values share a key
+template <int DT> __device__ __forceinline__ uint32_t warp_key(float x) {
+    uint32_t u = as_u(x);
+    if (u == 0x80000000u) u = 0u;
+    const uint32_t k = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return DT == TLI_BF16 ? (k >> 16) : k;
+}
+template <int DT> __device__ __forceinline__ float warp_unkey(uint32_t k) {
+    if (DT == TLI_BF16) k <<= 16;
+    const uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+    return as_f(DT == TLI_BF16 ? (u & 0xffff0000u) : u);
+}
+
+struct WarpRow {
+    double l2;            // log-normaliser of the competing logits, log2 units
+    uint64_t zk;          // mass of the logits that survive top-k (2^-48 fixed point)
+    uint64_t p_above;     // mass strictly above the top-p prefix found so far
+    uint64_t target;      // top_p * zk
+    uint32_t kprefix;     // key digits of the top-k threshold found so far (right-aligned)
+    uint32_t pprefix;     // same for the top-p threshold
+    uint32_t k_rem;       // the threshold is the k_rem-th largest key below the prefix
+    int32_t k_on, p_on;   // the warper is active for this row (top-k turns itself off when k >= competing ids)
+    int32_t status;
+};
+
+// kernel: start the per-row state from the row normalisers.  grid (ceil(R / 256)).
+__global__ __launch_bounds__(kWG) void k_warp_init(const Part* __restrict__ part, int nsplit, double ratio, int R,
+                                                    int top_k, int use_p, WarpRow* __restrict__ st) {
+    const int r = blockIdx.x * kWG + threadIdx.x;
+    if (r >= R) return;
+    const double lse = combine_parts(part + (int64_t)r * nsplit, nsplit, ratio);
+    WarpRow w;
+    w.l2 = lse * kLog2e;
+    w.zk = 0; w.p_above = 0; w.target = 0; w.kprefix = 0; w.pprefix = 0;
+    w.k_rem = top_k > 0 ? (uint32_t)top_k : 0u;
+    w.status = lse != lse ? TLI_FLAG_NONFINITE : (lse == -INFINITY ? TLI_FLAG_ZERO_MASS : 0);
+    w.k_on = (top_k > 0 && !w.status) ? 1 : 0;
+    w.p_on = (use_p && !w.status) ? 1 : 0;
+    st[r] = w;
+}
+
+// kernel: one level of the radix descent.  MODE 0: top-k (counts, and the mass that survives); MODE 1: top-p.
+// grid (R), 256 threads.
+template <int DT, bool MASKED, int MODE>
+__global__ __launch_bounds__(kWG) void k_warp_level(const void* __restrict__ logits, int64_t row_stride, int V, int nC,
+                                                     int level, float top_p, double c_true,
+                                                     const uint64_t* __restrict__ bits, WarpRow* __restrict__ st) {
+    constexpr int EPV = Traits<DT>::EPV;
+    constexpr int N = EPV * kLoads;
+    const int row = blockIdx.x;
+    WarpRow w = st[row];
+    if (MODE == 0 ? !w.k_on : !w.p_on) return;
+    const int nbits = WarpKey<DT>::bits(level), shift = WarpKey<DT>::shift(level), nbins = 1 << nbits;
+    const uint32_t prefix = MODE == 0 ? w.kprefix : w.pprefix;
+    __shared__ uint32_t cnt[kWarpBinsMax];
+    __shared__ unsigned long long mass[kWarpBinsMax];
+    for (int i = threadIdx.x; i < nbins; i += kWG) { cnt[i] = 0u; mass[i] = 0ull; }
+    __syncthreads();
+    float ch, cl, lh, ll;
+    split_scale(c_true, ch, cl);
+    split_hi_lo(w.l2, lh, ll);
+    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ);
+    const int lane = threadIdx.x & 63;
+    stream_chunks<DT, kWaves>(rowv, V, 0, nC, [&](const ChunkRegs& r, int c, auto whole) {
+        float x[N];
+        chunk_values<DT, MASKED, decltype(whole)::value>(r, c, lane, V, bits, x);
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            if (!(x[i] > -INFINITY)) continue;  // dropped, masked out or past the end: does not compete
+            const uint32_t key = warp_key<DT>(x[i]);
+            if (level > 0 && (key >> (shift + nbits)) != prefix) continue;
+            const uint32_t d = (key >> shift) & (uint32_t)(nbins - 1);
+            if (MODE == 0) atomicAdd(&cnt[d], 1u);
+            const float pr = exp2_split(x[i], ch, cl, lh, ll);
+            atomicAdd(&mass[d], (unsigned long long)((double)pr * kMassScale));
+        }
+    });
+    __syncthreads();
+    // suffix sums over the bins (from the top): thread t owns bins [t*per, (t+1)*per)
+    const int per = nbins / kWG > 0 ? nbins / kWG : 1;
+    const int t = threadIdx.x;
+    uint32_t my_c = 0;
+    unsigned long long my_m = 0;
+    if (t * per < nbins)
+        for (int i = 0; i < per; ++i) { my_c += cnt[t * per + i]; my_m += mass[t * per + i]; }
+    __shared__ uint32_t tc[kWG];
+    __shared__ unsigned long long tm[kWG];
+    tc[t] = my_c; tm[t] = my_m;
+    __syncthreads();
+    // counts and mass in the bins of all higher threads (a short serial loop: 256 entries)
+    uint32_t above_c = 0;
+    unsigned long long above_m = 0;
+    for (int u = t + 1; u < kWG; ++u) { above_c += tc[u]; above_m += tm[u]; }
+    __shared__ unsigned long long total_m;
+    __shared__ uint32_t total_c;
+    __shared__ int best_d;
+    if (t == 0) { total_m = above_m + my_m; total_c = above_c + my_c; best_d = 0x7fffffff; }
+    __syncthreads();
+    const bool owns = t * per < nbins;
+    const bool last = level == WarpKey<DT>::LEVELS - 1;
+    if (MODE == 0) {
+        if (level == 0 && total_c <= w.k_rem) {
+            // no more competing ids than k: top-k drops nothing, everything survives
+            if (t == 0) { st[row].k_on = 0; st[row].zk = total_m; }
+            return;
+        }
+        // the digit d with  #above(d) < k_rem <= #above(d) + cnt[d]  (exactly one thread finds it)
+        uint32_t ac = above_c;
+        unsigned long long am = above_m;
+        for (int i = per - 1; owns && i >= 0; --i) {
+            const int d = t * per + i;
+            if (ac < w.k_rem && w.k_rem <= ac + cnt[d]) {
+                WarpRow& o = st[row];
+                o.kprefix = (prefix << nbits) | (uint32_t)d;
+                o.k_rem = w.k_rem - ac;
+                o.zk = w.zk + am + (last ? mass[d] : 0ull);
+            }
+            ac += cnt[d]; am += mass[d];
+        }
+    } else {
+        unsigned long long target = w.target;
+        if (level == 0) {
+            const unsigned long long z = w.k_on ? w.zk : total_m;
+            target = (unsigned long long)((double)top_p * (double)z);
+            if (t == 0) st[row].target = target;
+        }
+        // the lowest digit d with mass whose strictly-above mass is still below the target
+        unsigned long long am = w.p_above + above_m;
+        int found = -1;
+        unsigned long long found_am = 0;
+        for (int i = per - 1; owns && i >= 0; --i) {
+            const int d = t * per + i;
+            if (mass[d] > 0ull && am < target) { found = d; found_am = am; }
+            am += mass[d];
+        }
+        // several threads may hold candidates: the lowest digit wins (the condition is monotone in the digit)
+        if (found >= 0) atomicMin(&best_d, found);
+        __syncthreads();
+        if (found >= 0 && found == best_d) {
+            WarpRow& o = st[row];
+            o.pprefix = (prefix << nbits) | (uint32_t)found;
+            o.p_above = found_am;
+        }
+    }
+}
+
+// kernel: write the warped rows (dropped logits = -inf), thresholds and survivor counts.  grid (R), 256 threads.
+template <int DT, bool MASKED>
+__global__ __launch_bounds__(kWG) void k_warp_apply(const void* __restrict__ logits, int64_t row_stride, int V, int nC,
+                                                     const uint64_t* __restrict__ bits, const WarpRow* __restrict__ st,
+                                                     void* __restrict__ out, int64_t out_stride, float* __restrict__ thr,
+                                                     int32_t* __restrict__ kept, int32_t* __restrict__ status) {
+    constexpr int EPV = Traits<DT>::EPV;
+    const int row = blockIdx.x;
+    const WarpRow w = st[row];
+    uint32_t tkey = 0;  // keep everything that competes
+    bool any = false;
+    if (w.k_on) { tkey = w.kprefix; any = true; }
+    if (w.p_on && (!any || w.pprefix > tkey)) { tkey = w.pprefix; any = true; }
+    const uint4* src = reinterpret_cast<const uint4*>(static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ);
+    uint4* dst = reinterpret_cast<uint4*>(static_cast<char*>(out) + (int64_t)row * out_stride * Traits<DT>::ESZ);
+    const int nvec = (V + EPV - 1) / EPV;
+    const unsigned int npat = (DT == TLI_BF16) ? 0xff80u : 0xff800000u;
+    int n = 0;
+    for (int vi = threadIdx.x; vi < nvec; vi += kWG) {
+        float x[EPV];
+        unpack<DT>(src[vi], x);
+        const uint32_t mb = MASKED ? mask_bits<DT>(bits, vi) : 0xffu;
+        uint32_t o[EPV];
+#pragma unroll
+        for (int i = 0; i < EPV; ++i) {
+            const bool live = vi * EPV + i < V && ((mb >> i) & 1u) && !w.status && x[i] > -INFINITY &&
+                              (!any || warp_key<DT>(x[i]) >= tkey);
+            n += live ? 1 : 0;
+            o[i] = live ? (DT == TLI_BF16 ? as_u(x[i]) >> 16 : as_u(x[i])) : npat;
+        }
+        uint4 v;
+        if constexpr (DT == TLI_BF16) {
+            v.x = o[0] | (o[1] << 16); v.y = o[2] | (o[3] << 16); v.z = o[4] | (o[5] << 16); v.w = o[6] | (o[7] << 16);
+        } else {
+            v.x = o[0]; v.y = o[1]; v.z = o[2]; v.w = o[3];
+        }
+        // the last vector of a row whose length is not a multiple of the vector keeps the caller's padding
+        if ((vi + 1) * EPV > V) {
+            const uint4 keep = src[vi];
+            uint32_t kw[4] = {keep.x, keep.y, keep.z, keep.w}, nw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < EPV; ++i)
+                if (vi * EPV + i >= V) {
+                    if constexpr (DT == TLI_BF16) {
+                        const uint32_t sh = (i & 1) * 16;
+                        nw[i >> 1] = (nw[i >> 1] & ~(0xffffu << sh)) | (kw[i >> 1] & (0xffffu << sh));
+                    } else {
+                        nw[i] = kw[i];
+                    }
+                }
+            v.x = nw[0]; v.y = nw[1]; v.z = nw[2]; v.w = nw[3];
+        }
+        dst[vi] = v;
+    }
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) n += __shfl_xor(n, d, kWave);
+    __shared__ int sn[kWaves];
+    if ((threadIdx.x & 63) == 0) sn[threadIdx.x >> 6] = n;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int tot = 0;
+        for (int i = 0; i < kWaves; ++i) tot += sn[i];
+        if (kept) kept[row] = tot;
+        if (thr) thr[row] = w.status ? NAN : (any ? warp_unkey<DT>(tkey) : -INFINITY);
+        status[row] = w.status;
+    }
+}
+
 // ---- plain copy, used only to calibrate hardware byte counters against a known size -----------
 __global__ __launch_bounds__(kWG) void k_calib_copy(const u4v* __restrict__ src, u4v* __restrict__ dst, size_t nvec) {
     const size_t stride = (size_t)gridDim.x * kWG;
@@ -1966,6 +2207,63 @@ int tli_acceptance_rates(const tli_map* map, const void* logits_t, const void* l
     else
         launch_diag<TLI_F32>(map, logits_t, logits_d, B, K, temp_t, temp_d, alpha_tli, alpha_union, pos_status,
                              static_cast<char*>(workspace), w, st);
+    return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
+}
+
+size_t tli_warp_workspace_bytes(int32_t R, int32_t V, tli_dtype dtype) {
+    if (R < 1 || R > 0x7fffffff / 64 || V < 1 || (dtype != TLI_F32 && dtype != TLI_BF16)) return 0;
+    const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
+    const Plan pl = make_plan(V, R, chunk);
+    return align256((size_t)R * pl.nsplit * sizeof(Part)) + align256((size_t)R * sizeof(WarpRow));
+}
+
+int tli_warp_rows(const tli_map* map, const void* logits, tli_dtype dtype, int64_t row_stride_elems, int32_t R, int32_t V,
+                  float temp, int32_t top_k, float top_p, void* logits_out, int64_t out_stride_elems, float* thr,
+                  int32_t* kept, int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!logits || !logits_out || !row_status || !workspace) return TLI_ERR_INVALID_ARG;
+    if (R < 1 || R > 0x7fffffff / 64 || V < 1 || !(temp > 0.f) || !std::isfinite(temp)) return TLI_ERR_INVALID_ARG;
+    if (!(top_p > 0.f) || (map && V != map->Vd)) return TLI_ERR_INVALID_ARG;
+    if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
+    const int epv = dtype == TLI_BF16 ? 8 : 4;
+    if (row_stride_elems < V || row_stride_elems % epv != 0 || out_stride_elems < V || out_stride_elems % epv != 0 ||
+        !aligned16(logits) || !aligned16(logits_out) || !aligned16(workspace))
+        return TLI_ERR_INVALID_ARG;
+    if (workspace_bytes < tli_warp_workspace_bytes(R, V, dtype)) return TLI_ERR_ALLOC;
+    const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
+    const Plan pl = make_plan(V, R, chunk);
+    Part* part = reinterpret_cast<Part*>(workspace);
+    WarpRow* st = reinterpret_cast<WarpRow*>(static_cast<char*>(workspace) + align256((size_t)R * pl.nsplit * sizeof(Part)));
+    const double c_true = kLog2e / (double)temp;
+    const float cs = (float)c_true;
+    const double ratio = c_true / (double)cs;
+    const int use_p = top_p < 1.f ? 1 : 0;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const dim3 rows_grid(R), lse_grid((unsigned)R * pl.nsplit);
+#define TLI_WARP_RUN(DT, MASKED, BITS)                                                                                   \
+    do {                                                                                                                  \
+        hipLaunchKernelGGL((k_lse<DT, MASKED>), lse_grid, dim3(kWG), 0, s, logits, 1, row_stride_elems, row_stride_elems, \
+                           V, pl.nC, pl.cps, pl.nsplit, cs, ratio, BITS, part, (float2*)nullptr);                        \
+        hipLaunchKernelGGL(k_warp_init, dim3((R + kWG - 1) / kWG), dim3(kWG), 0, s, part, pl.nsplit, ratio, R, top_k,     \
+                           use_p, st);                                                                                    \
+        if (top_k > 0)                                                                                                    \
+            for (int level = 0; level < WarpKey<DT>::LEVELS; ++level)                                                     \
+                hipLaunchKernelGGL((k_warp_level<DT, MASKED, 0>), rows_grid, dim3(kWG), 0, s, logits, row_stride_elems,   \
+                                   V, pl.nC, level, top_p, c_true, BITS, st);                                             \
+        if (use_p)                                                                                                        \
+            for (int level = 0; level < WarpKey<DT>::LEVELS; ++level)                                                     \
+                hipLaunchKernelGGL((k_warp_level<DT, MASKED, 1>), rows_grid, dim3(kWG), 0, s, logits, row_stride_elems,   \
+                                   V, pl.nC, level, top_p, c_true, BITS, st);                                             \
+        hipLaunchKernelGGL((k_warp_apply<DT, MASKED>), rows_grid, dim3(kWG), 0, s, logits, row_stride_elems, V, pl.nC,    \
+                           BITS, st, logits_out, out_stride_elems, thr, kept, row_status);                                \
+    } while (0)
+    if (map) {
+        if (dtype == TLI_BF16) TLI_WARP_RUN(TLI_BF16, true, map->lmask[TLI_BF16]);
+        else TLI_WARP_RUN(TLI_F32, true, map->lmask[TLI_F32]);
+    } else {
+        if (dtype == TLI_BF16) TLI_WARP_RUN(TLI_BF16, false, (const uint64_t*)nullptr);
+        else TLI_WARP_RUN(TLI_F32, false, (const uint64_t*)nullptr);
+    }
+#undef TLI_WARP_RUN
     return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
 }
 

@@ -72,3 +72,21 @@ def test_hot_calls_reject_null_arguments(lib):
     assert lib.tli_verify(z, z, z, 0, 1, 1, 1.0, 1.0, z, z, z, z, z, z, z, z, z, z, z, z, 0, z) == -1
     assert lib.tli_map_info(z, None, None, None) == -1
     lib.tli_free_map(z)  # freeing NULL is a no-op
+
+
+def test_new_entry_points_reject_null_arguments(lib):
+    z = ctypes.c_void_p(0)
+    assert lib.tli_union_draft_sample(z, z, 0, 8, 1, 1.0, z, z, z, z, z, z, 1, z, 0, z) == -1
+    assert lib.tli_draft_sample_compact(z, z, 0, 8, 1, 1.0, z, z, z, z, z, z, 1, z, 0, z) == -1
+    assert lib.tli_union_verify(z, z, z, 0, 1, 1, 1.0, 1.0, z, z, z, z, z, z, z, z, z, z, z, z, 0, z) == -1
+    assert lib.tli_verify_compact(z, z, z, 8, 0, 1, 1, 1.0, 1.0, z, z, z, z, z, z, z, z, z, z, z, z, 0, z) == -1
+    assert lib.tli_acceptance_rates(z, z, z, 0, 1, 1, 1.0, 1.0, z, z, z, z, 0, z) == -1
+    assert lib.tli_sample_rows(z, 0, 8, 1, 8, 1.0, z, z, z, z, z, 1, z, 0, z) == -1
+    assert lib.tli_sample_rows(z, 0, 8, 1, 8, 0.0, z, z, z, z, z, 1, z, 0, z) == -1
+    assert lib.tli_greedy_draft(z, z, 0, 8, 1, z, z, z, 1, z, 0, z) == -1
+    assert lib.tli_exact_match_verify(z, 0, 1, 1, 8, 1.0, z, z, z, z, z, z, z, 0, z) == -1
+    assert lib.tli_warp_rows(z, z, 0, 8, 1, 8, 1.0, 5, 0.9, z, 8, z, z, z, z, 0, z) == -1
+    assert lib.tli_acceptance_rates_workspace_bytes(z, 1, 1, 0) == 0
+    assert lib.tli_sample_rows_workspace_bytes(0, 8, 0) == 0 and lib.tli_sample_rows_workspace_bytes(4, 1000, 1) > 0
+    assert lib.tli_exact_match_workspace_bytes(2, 64, 100, 0) == 0 and lib.tli_exact_match_workspace_bytes(2, 3, 100, 0) > 0
+    assert lib.tli_warp_workspace_bytes(3, 100, 1) > 0 and lib.tli_warp_workspace_bytes(3, 100, 9) == 0

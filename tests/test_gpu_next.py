@@ -325,3 +325,80 @@ def test_full_size_large_vocab_next_rows(oracle):
             assert ge["n_accepted"][b] == re_["n_acc"][b] and np.array_equal(ge["out_tok"][b], re_["out_tok"][b])
         print(f"exact match tau={tau}: near-tie sequences {near}, mean accepted {re_['n_acc'].mean():.2f}")
     m.free()
+
+
+# ---------------------------------------------------------------- logit warpers
+WARP = [("bf16", 2048 * 3 + 40, 9, 2048 * 3 + 48), ("f32", 5000, 4, 5000), ("bf16", 151936, 3, 151936), ("f32", 33000, 2, 33000)]
+
+
+def _check_warp(oracle, view, rows, tau, top_k, top_p, d2t, m):
+    g = binding.tli_warp_rows(view, tau, top_k, top_p, m=m)
+    torch.cuda.synchronize()
+    ref = oracle.warp_rows(rows, parity.f32(tau), top_k, float(np.float32(top_p)), d2t=d2t, threads=8)
+    gs, gk, gt = g["status"].cpu().numpy(), g["kept"].cpu().numpy(), g["thr"].cpu().numpy().astype(np.float64)
+    assert np.array_equal(gs, ref["status"])
+    out = synth.logits_to_numpy(g["logits"])
+    ninf = 0xFF80 if rows.dtype == np.uint16 else np.float32(-np.inf)
+    near = 0
+    for r in range(rows.shape[0]):
+        if ref["status"][r]:
+            assert gk[r] == 0 and np.isnan(gt[r])
+            continue
+        if gk[r] != ref["kept"][r]:
+            # a top-p cut may move by one group of equal logits only if the oracle's own decision was within 1e-6
+            assert ref["margin"][r] < parity.NEAR_TIE, (r, gk[r], ref["kept"][r], ref["margin"][r])
+            near += 1
+            continue
+        assert gt[r] == ref["thr"][r] or (np.isinf(gt[r]) and np.isinf(ref["thr"][r])), (r, gt[r], ref["thr"][r])
+        want = np.where(ref["keep_mask"][r].astype(bool), rows[r], ninf)
+        if rows.dtype == np.float32:
+            assert np.array_equal(out[r].view(np.uint32), want.view(np.uint32)) or np.array_equal(out[r], want)
+        else:
+            assert np.array_equal(out[r], want)
+    return near
+
+
+@pytest.mark.parametrize("dtype,V,R,stride", WARP, ids=[f"{c[0]}_V{c[1]}" for c in WARP])
+def test_warp_rows(oracle, dtype, V, R, stride):
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(V + 7 * R)
+    buf = (torch.randn(R, stride, generator=gen, device=DEV) * 3).to(torch.bfloat16 if dtype == "bf16" else torch.float32)
+    buf[:, V:] = 60.0
+    buf[0, 10:300] = float("-inf")
+    buf[R - 1, 5] = -0.0
+    buf[R - 1, 6] = 0.0
+    view = buf[:, :V]
+    rows = synth.logits_to_numpy(view.contiguous())
+    near = 0
+    for top_k, top_p, tau in [(50, 1.0, 1.0), (1, 1.0, 1.0), (0, 0.9, 0.8), (0, 0.3, 1.2), (200, 0.95, 0.7), (10 ** 7, 0.999, 1.0),
+                              (0, 1e-7, 1.0), (7, 0.5, 1.0)]:
+        near += _check_warp(oracle, view, rows, tau, top_k, top_p, None, None)
+    print("top-p cuts inside the near-tie window:", near)
+    # padding beyond V is left as the caller had it when the warp is done in place
+    g = binding.tli_warp_rows(view, 1.0, 5, 1.0, out=view)
+    torch.cuda.synchronize()
+    assert torch.all(buf[:, V:] == 60.0) and int((buf[:, :V] > float("-inf")).sum()) == int(g["kept"].sum())
+
+
+def test_warp_rows_flags_and_map(oracle):
+    w = synth.WORKLOADS[3].scaled(B=4, K=3, Vt=6000, Vd=4104, S=2000, cfg=75)
+    inp = synth.make_inputs(w, DEV)
+    d2t = inp["d2t"]
+    ld = inp["logits_d"].reshape(12, w.Vd).clone()
+    sh = np.nonzero(d2t >= 0)[0]
+    ld[1, int(sh[3])] = float("nan")
+    ld[2, torch.from_numpy(sh).to(DEV)] = float("-inf")
+    ld[3, int(np.nonzero(d2t < 0)[0][0])] = float("nan")  # unshared: ignored
+    m = binding.tli_build_map(d2t, w.Vt)
+    rows = synth.logits_to_numpy(ld)
+    for top_k, top_p in [(20, 1.0), (0, 0.9), (40, 0.8)]:
+        _check_warp(oracle, ld, rows, 0.9, top_k, top_p, d2t, m)
+    # the warped rows feed the TLI draft: only surviving shared ids can be drawn
+    g = binding.tli_warp_rows(ld, 0.9, 3, 1.0, m=m)
+    ws = binding.alloc_workspace(4, 3, m, binding.TLI_BF16, DEV)
+    u = inp["u_draft"].reshape(-1)
+    d = binding.tli_draft_sample(m, g["logits"], 0.9, u, ws)
+    torch.cuda.synchronize()
+    dr = oracle.draft_sample(synth.logits_to_numpy(g["logits"]), parity.f32(0.9), d2t, u.cpu().numpy().astype(np.float64))
+    assert np.array_equal(d["tok_d"].cpu().numpy(), dr["tok_d"])
+    m.free()
