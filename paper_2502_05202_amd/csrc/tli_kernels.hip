@@ -1346,17 +1346,23 @@ __global__ __launch_bounds__(kWave) void k_match(const int32_t* __restrict__ tgt
 // level is one pass over the rows: a workgroup per row histograms the digit of the elements whose higher
 // digits match the prefix found so far -- element counts (top-k) and probability mass (top-p, in 2^-48 fixed
 // point so that sums do not depend on the order of arrival) -- and then picks the digit in which the
-// threshold lies.  A last pass writes the rows with every dropped logit set to -inf.
+// threshold lies.  Logits crowd into a handful of leading digits (sign and exponent), so the lanes of a wave
+// would queue on the same few LDS words: the histogram is kept in several interleaved copies, one per lane
+// group, and folded after the scan.  A last pass writes the rows with every dropped logit set to -inf.
 constexpr int kWarpBinsMax = 2048;
 constexpr double kMassScale = 281474976710656.0;  // 2^48
 template <int DT> struct WarpKey;
 template <> struct WarpKey<TLI_BF16> {
     static constexpr int LEVELS = 2;
+    static constexpr int COPIES = 16;  // private copies of the histogram (lane & 15 picks one), interleaved per bin
+    static constexpr int BINS = 256;
     __host__ __device__ static constexpr int bits(int) { return 8; }
     __host__ __device__ static constexpr int shift(int level) { return level == 0 ? 8 : 0; }
 };
 template <> struct WarpKey<TLI_F32> {
     static constexpr int LEVELS = 3;
+    static constexpr int COPIES = 2;
+    static constexpr int BINS = 2048;
     __host__ __device__ static constexpr int bits(int level) { return level == 2 ? 10 : 11; }
     __host__ __device__ static constexpr int shift(int level) { return level == 0 ? 21 : (level == 1 ? 10 : 0); }
 };
@@ -1416,9 +1422,17 @@ __global__ __launch_bounds__(kWG) void k_warp_level(const void* __restrict__ log
     if (MODE == 0 ? !w.k_on : !w.p_on) return;
     const int nbits = WarpKey<DT>::bits(level), shift = WarpKey<DT>::shift(level), nbins = 1 << nbits;
     const uint32_t prefix = MODE == 0 ? w.kprefix : w.pprefix;
-    __shared__ uint32_t cnt[kWarpBinsMax];
-    __shared__ unsigned long long mass[kWarpBinsMax];
-    for (int i = threadIdx.x; i < nbins; i += kWG) { cnt[i] = 0u; mass[i] = 0ull; }
+    constexpr int COPIES = WarpKey<DT>::COPIES;
+    constexpr int kSlots = WarpKey<DT>::BINS * COPIES;
+    __shared__ uint32_t cnt_c[kSlots];
+    __shared__ unsigned long long mass_c[kSlots];
+    __shared__ uint32_t cnt[WarpKey<DT>::BINS];
+    __shared__ unsigned long long mass[WarpKey<DT>::BINS];
+    for (int i = threadIdx.x; i < nbins * COPIES; i += kWG) { cnt_c[i] = 0u; mass_c[i] = 0ull; }
+    const int copy = threadIdx.x & (COPIES - 1);
+    __shared__ unsigned long long zk_all;  // mass of the logits that survived top-k
+    if (threadIdx.x == 0) zk_all = 0ull;
+    unsigned long long zk_mine = 0ull;
     __syncthreads();
     float ch, cl, lh, ll;
     split_scale(c_true, ch, cl);
@@ -1433,12 +1447,32 @@ __global__ __launch_bounds__(kWG) void k_warp_level(const void* __restrict__ log
             if (!(x[i] > -INFINITY)) continue;  // dropped, masked out or past the end: does not compete
             const uint32_t key = warp_key<DT>(x[i]);
             if (level > 0 && (key >> (shift + nbits)) != prefix) continue;
+            // top-p is decided among the survivors of top-k: with top-k on, nothing below its threshold can matter
+            if (MODE == 1 && w.k_on && key < w.kprefix) continue;
             const uint32_t d = (key >> shift) & (uint32_t)(nbins - 1);
-            if (MODE == 0) atomicAdd(&cnt[d], 1u);
-            const float pr = exp2_split(x[i], ch, cl, lh, ll);
-            atomicAdd(&mass[d], (unsigned long long)((double)pr * kMassScale));
+            if (MODE == 0) {  // top-k only counts; the mass that survives it is summed by the first top-p pass
+                atomicAdd(&cnt_c[d * COPIES + copy], 1u);
+            } else {
+                const float pr = exp2_split(x[i], ch, cl, lh, ll);
+                const unsigned long long fx = (unsigned long long)((double)pr * kMassScale);
+                atomicAdd(&mass_c[d * COPIES + copy], fx);
+                if (level == 0 && w.k_on && key >= w.kprefix) zk_mine += fx;
+            }
         }
     });
+    if (MODE == 1 && level == 0 && w.k_on) {  // integer sums: the order of arrival does not matter
+#pragma unroll
+        for (int dd = 1; dd < kWave; dd <<= 1) zk_mine += __shfl_xor(zk_mine, dd, kWave);
+        if (lane == 0) atomicAdd(&zk_all, zk_mine);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nbins; i += kWG) {  // fold the copies (integer sums: any order gives the same result)
+        uint32_t c = 0;
+        unsigned long long m = 0;
+#pragma unroll
+        for (int k = 0; k < COPIES; ++k) { c += cnt_c[i * COPIES + k]; m += mass_c[i * COPIES + k]; }
+        cnt[i] = c; mass[i] = m;
+    }
     __syncthreads();
     // suffix sums over the bins (from the top): thread t owns bins [t*per, (t+1)*per)
     const int per = nbins / kWG > 0 ? nbins / kWG : 1;
@@ -1461,32 +1495,29 @@ __global__ __launch_bounds__(kWG) void k_warp_level(const void* __restrict__ log
     if (t == 0) { total_m = above_m + my_m; total_c = above_c + my_c; best_d = 0x7fffffff; }
     __syncthreads();
     const bool owns = t * per < nbins;
-    const bool last = level == WarpKey<DT>::LEVELS - 1;
     if (MODE == 0) {
         if (level == 0 && total_c <= w.k_rem) {
             // no more competing ids than k: top-k drops nothing, everything survives
-            if (t == 0) { st[row].k_on = 0; st[row].zk = total_m; }
+            if (t == 0) st[row].k_on = 0;
             return;
         }
         // the digit d with  #above(d) < k_rem <= #above(d) + cnt[d]  (exactly one thread finds it)
         uint32_t ac = above_c;
-        unsigned long long am = above_m;
         for (int i = per - 1; owns && i >= 0; --i) {
             const int d = t * per + i;
             if (ac < w.k_rem && w.k_rem <= ac + cnt[d]) {
                 WarpRow& o = st[row];
                 o.kprefix = (prefix << nbits) | (uint32_t)d;
                 o.k_rem = w.k_rem - ac;
-                o.zk = w.zk + am + (last ? mass[d] : 0ull);
             }
-            ac += cnt[d]; am += mass[d];
+            ac += cnt[d];
         }
     } else {
         unsigned long long target = w.target;
         if (level == 0) {
-            const unsigned long long z = w.k_on ? w.zk : total_m;
+            const unsigned long long z = w.k_on ? zk_all : total_m;
             target = (unsigned long long)((double)top_p * (double)z);
-            if (t == 0) st[row].target = target;
+            if (t == 0) { st[row].target = target; st[row].zk = z; }
         }
         // the lowest digit d with mass whose strictly-above mass is still below the target
         unsigned long long am = w.p_above + above_m;
@@ -1521,47 +1552,52 @@ __global__ __launch_bounds__(kWG) void k_warp_apply(const void* __restrict__ log
     bool any = false;
     if (w.k_on) { tkey = w.kprefix; any = true; }
     if (w.p_on && (!any || w.pprefix > tkey)) { tkey = w.pprefix; any = true; }
-    const uint4* src = reinterpret_cast<const uint4*>(static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ);
+    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ);
     uint4* dst = reinterpret_cast<uint4*>(static_cast<char*>(out) + (int64_t)row * out_stride * Traits<DT>::ESZ);
     const int nvec = (V + EPV - 1) / EPV;
     const unsigned int npat = (DT == TLI_BF16) ? 0xff80u : 0xff800000u;
+    const int lane = threadIdx.x & 63;
     int n = 0;
-    for (int vi = threadIdx.x; vi < nvec; vi += kWG) {
-        float x[EPV];
-        unpack<DT>(src[vi], x);
-        const uint32_t mb = MASKED ? mask_bits<DT>(bits, vi) : 0xffu;
-        uint32_t o[EPV];
+    stream_chunks<DT, kWaves>(rowv, V, 0, nC, [&](const ChunkRegs& r, int c, auto) {
 #pragma unroll
-        for (int i = 0; i < EPV; ++i) {
-            const bool live = vi * EPV + i < V && ((mb >> i) & 1u) && !w.status && x[i] > -INFINITY &&
-                              (!any || warp_key<DT>(x[i]) >= tkey);
-            n += live ? 1 : 0;
-            o[i] = live ? (DT == TLI_BF16 ? as_u(x[i]) >> 16 : as_u(x[i])) : npat;
-        }
-        uint4 v;
-        if constexpr (DT == TLI_BF16) {
-            v.x = o[0] | (o[1] << 16); v.y = o[2] | (o[3] << 16); v.z = o[4] | (o[5] << 16); v.w = o[6] | (o[7] << 16);
-        } else {
-            v.x = o[0]; v.y = o[1]; v.z = o[2]; v.w = o[3];
-        }
-        // the last vector of a row whose length is not a multiple of the vector keeps the caller's padding
-        if ((vi + 1) * EPV > V) {
-            const uint4 keep = src[vi];
-            uint32_t kw[4] = {keep.x, keep.y, keep.z, keep.w}, nw[4] = {v.x, v.y, v.z, v.w};
+        for (int j = 0; j < kLoads; ++j) {
+            const int vi = (c * kLoads + j) * kWave + lane;
+            if (vi >= nvec) continue;
+            const uint4 in = to_uint4(r.v[j]);
+            float x[EPV];
+            unpack<DT>(in, x);
+            const uint32_t mb = MASKED ? mask_bits<DT>(bits, vi) : 0xffu;
+            uint32_t o[EPV];
 #pragma unroll
-            for (int i = 0; i < EPV; ++i)
-                if (vi * EPV + i >= V) {
-                    if constexpr (DT == TLI_BF16) {
-                        const uint32_t sh = (i & 1) * 16;
-                        nw[i >> 1] = (nw[i >> 1] & ~(0xffffu << sh)) | (kw[i >> 1] & (0xffffu << sh));
-                    } else {
-                        nw[i] = kw[i];
+            for (int i = 0; i < EPV; ++i) {
+                const bool live = vi * EPV + i < V && ((mb >> i) & 1u) && !w.status && x[i] > -INFINITY &&
+                                  (!any || warp_key<DT>(x[i]) >= tkey);
+                n += live ? 1 : 0;
+                o[i] = live ? (DT == TLI_BF16 ? as_u(x[i]) >> 16 : as_u(x[i])) : npat;
+            }
+            uint32_t nw[4];
+            if constexpr (DT == TLI_BF16) {
+                nw[0] = o[0] | (o[1] << 16); nw[1] = o[2] | (o[3] << 16); nw[2] = o[4] | (o[5] << 16); nw[3] = o[6] | (o[7] << 16);
+            } else {
+                nw[0] = o[0]; nw[1] = o[1]; nw[2] = o[2]; nw[3] = o[3];
+            }
+            // the last vector of a row whose length is not a multiple of the vector keeps the caller's padding
+            if ((vi + 1) * EPV > V) {
+                const uint32_t kw[4] = {in.x, in.y, in.z, in.w};
+#pragma unroll
+                for (int i = 0; i < EPV; ++i)
+                    if (vi * EPV + i >= V) {
+                        if constexpr (DT == TLI_BF16) {
+                            const uint32_t sh = (i & 1) * 16;
+                            nw[i >> 1] = (nw[i >> 1] & ~(0xffffu << sh)) | (kw[i >> 1] & (0xffffu << sh));
+                        } else {
+                            nw[i] = kw[i];
+                        }
                     }
-                }
-            v.x = nw[0]; v.y = nw[1]; v.z = nw[2]; v.w = nw[3];
+            }
+            dst[vi] = make_uint4(nw[0], nw[1], nw[2], nw[3]);
         }
-        dst[vi] = v;
-    }
+    });
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) n += __shfl_xor(n, d, kWave);
     __shared__ int sn[kWaves];
