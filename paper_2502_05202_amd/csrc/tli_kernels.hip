@@ -611,7 +611,6 @@ struct DrafterView {
     int64_t row_stride;    // elements between consecutive rows
     const int32_t* d2x;    // drafter id -> index in a row; nullptr = identity (full layout)
     const int32_t* t2x;    // target id -> index in a row, -1 for target-only ids (t2d full, t2r compact)
-    const int32_t* stage;  // rank -> index in a row (rank list of the map); nullptr = identity (compact layout)
 };
 
 // ---- what the final kernels need to know about a sequence, written once by the accept kernel ----
@@ -796,8 +795,8 @@ template <int DT>
 __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const void* logits_t, const DrafterView& dv,
                                                int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
                                                const int32_t* t2d, const float* tr, const float* ts,
-                                               const float2* ctab, const double* mn, int nparts, int64_t mn_stride,
-                                               const int32_t* fbad, const FinalOut& o) {
+                                               const float2* ctab, const double* mn, const int32_t* fbad,
+                                               const FinalOut& o) {
     constexpr int EPV = Traits<DT>::EPV;
     const int lane = threadIdx.x & 63;
     const char* rowp = static_cast<const char*>(logits_t) + (int64_t)f.t_row * Vt * Traits<DT>::ESZ;
@@ -821,9 +820,7 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
             return (rs.x == -INFINITY) ? 0.0 : (double)rs.y * exp2((double)rs.x * ratio_t - f.l2p);
         };
         auto r_mass = [&](int cc) {
-            double m = 0.0;
-            if (f.rp.use_q)
-                for (int pp = 0; pp < nparts; ++pp) m += mn[pp * mn_stride + cc];
+            const double m = f.rp.use_q ? mn[cc] : 0.0;
             const double t = p_mass(cc) - m;
             return t > 0.0 ? t : (t != t ? t : 0.0);
         };
@@ -881,15 +878,15 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
 // The first sum is known: the normaliser kernel left the chunk table (ref, s) of every target row, and
 // sum_chunk p = s * 2^(ref * c_true/c - lse_p * log2 e).  Only the second sum is computed here; it runs over
 // the shared PAIRS (target id, drafter id) alone.  The two vocabularies' orders are unrelated, so a pair
-// needs one random access on each side -- and random access is cheap only in LDS.  A workgroup therefore
-// keeps a PART of the drafter row resident in LDS: the logits of up to part_cap shared drafter ids,
-// compacted in rank order (rank = position among the shared ids, ascending drafter id; gathered once
-// through the map's rank -> drafter id list, nearly coalesced).  Its 16 waves then stream target chunks
-// past it: a wave parks a chunk in its private LDS slot and walks the map's list of the pairs that fall
-// into (this part, this chunk), each entry = (byte offset in chunk, byte offset in part), reading both
-// logits from LDS.  Every pair is owned by one lane of one wave and sums are per-lane, then fp64 across
-// lanes, so results do not depend on timing.
-// Output: mn[part][b][chunk] = the part's share of sum min(p, q'); the draw kernel forms the masses.
+// needs one random access on each side -- and random access is cheap only in LDS.  The target row is cut
+// into PARTS, runs of whole chunks holding at most part_cap pairs.  A workgroup owns one part of one row: it
+// gathers the drafter logits of the part's pairs into LDS once (through the map's list of their positions
+// in the drafter row, ascending, so the reads sweep the row front to back), then its 16 waves stream the
+// part's target chunks: a wave parks a chunk in its private LDS slot and walks the map's list of the
+// chunk's pairs, each entry = (byte offset in chunk, byte offset in the staged part), reading both logits
+// from LDS.  Every target chunk is thus read once per row, every pair is owned by one lane of one wave, and
+// sums are per-lane, then fp64 across lanes, so results do not depend on timing.
+// Output: mn[b][chunk] = sum of min(p, q') over the chunk's pairs; the draw kernel forms the masses.
 // The loop is deliberately NOT unrolled into a multi-chunk register pipeline: the kernel runs for tens of
 // microseconds, every instruction is executed a handful of times, and cold instruction fetch of a larger
 // body cost more than the latency it hid (measured: one chunk in flight per wave 66 us, three 76 us).
@@ -897,14 +894,27 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
 // and scan it into a plain (ref, s) softmax table.
 // grid (B rounded up to 8) x nparts x nsplit, 1024 threads; workgroups of flagged sequences exit at once.
 // nsplit > 1 (few sequences): the chunks of one (sequence, part) are dealt to nsplit workgroups, each with
-// its own copy of the part.
+// its own copy of the part's drafter logits.
 constexpr int kScanWG = 1024;
 constexpr int kScanWaves = kScanWG / kWave;
 constexpr int kPartBytes = 92 * 1024;  // + one 4 KB chunk slot per wave = 156 KB of the CU's 160 KB
-constexpr int kPairU = 8;              // list entries per lane fetched with a chunk (512 pairs; more: late loop)
+#ifndef KPAIRU
+#define KPAIRU 12
+#endif
+constexpr int kPairU = KPAIRU;              // list entries per lane fetched with a chunk (512 pairs; more: late loop)
 constexpr int kStageU = 8;
 constexpr int kWaitVm0 = 0x0F70;       // s_waitcnt vmcnt(0) alone (expcnt and lgkmcnt fields at their maximum)
-constexpr int kPairShift = 12;         // entry = byte offset in chunk (< 4096) | byte offset in part << 12
+constexpr int kPairShift = 12;         // entry = byte offset in chunk (< 4096) | byte offset in the staged part << 12
+
+struct ScanLists {            // the map's lists for one dtype, as the scan kernel reads them
+    int nparts, S;
+    const int32_t* cb;        // [nparts+1] first chunk of every part
+    const int32_t* st_start;  // [nparts+1] first staging entry of every part
+    const int32_t* st_idx;    // [S] position in the drafter row of the pair staged at this place (drafter id in
+                              //     the full layout, rank in the compact one), ascending inside a part
+    const int32_t* pl_start;  // [nC+1] first pair of every chunk
+    const uint32_t* pl_e;     // [S] pairs grouped by chunk
+};
 template <int DT> constexpr int part_cap() { return kPartBytes / Traits<DT>::ESZ; }
 
 // DIAG (acceptance-rate diagnostics): the items are all B*K positions instead of one row per sequence, and a
@@ -912,10 +922,8 @@ template <int DT> constexpr int part_cap() { return kPartBytes / Traits<DT>::ESZ
 // mn = sum min(p, q') (TLI's expected acceptance rate), mn2 = sum min(p, q) (the union algorithm's).
 template <int DT, bool DIAG>
 __global__ __launch_bounds__(kScanWG) void k_final_scan(
-    const void* __restrict__ logits_t, DrafterView dv, int B, int K, int Vt, int Vd, int nC,
-    int nparts, int nsplit, int per, int S, float cs_t, double ratio_t, const FinalRow* __restrict__ frow,
-    const int32_t* __restrict__ pl_start, const uint32_t* __restrict__ pl_e,
-    float* __restrict__ tab_ref, float* __restrict__ tab_s, double* __restrict__ mn, double* __restrict__ mn2,
+    const void* __restrict__ logits_t, DrafterView dv, int B, int K, int Vt, int Vd, int nC, int nsplit, ScanLists ls,
+    float cs_t, double ratio_t, const FinalRow* __restrict__ frow, float* __restrict__ tab_ref, float* __restrict__ tab_s, double* __restrict__ mn, double* __restrict__ mn2,
     int32_t* __restrict__ fbad) {
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int ESZ = Traits<DT>::ESZ;
@@ -926,6 +934,7 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  The workgroups of one sequence
     // stream the same rows, so they are given ids that land on the same XCD, next to each other in time:
     // id = slot * 8 + xcd, sequence = (slot / per_seq) * 8 + xcd, (part, split) = slot % per_seq.
+    const int nparts = ls.nparts, S = ls.S;
     const int per_seq = nparts * nsplit;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int b = (slot / per_seq) * 8 + xcd, sub = slot % per_seq;
@@ -950,68 +959,54 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     if (!f.rp.use_q) return;  // q' = 0 everywhere: the masses are the chunk sums of p, nothing to subtract
     const raw_t* ld_row =
         reinterpret_cast<const raw_t*>(static_cast<const char*>(dv.base) + (int64_t)f.d_row * dv.row_stride * ESZ);
-    const int32_t* __restrict__ sh_x = dv.stage;
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
                                                     (int64_t)f.t_row * Vt * ESZ);
     const int nvec = (Vt + EPV - 1) / EPV;
-    const int32_t* my_start = pl_start + (int64_t)p * nC;
+    const int32_t* __restrict__ my_start = ls.pl_start;
+    const uint32_t* __restrict__ pl_e = ls.pl_e;
+    const int32_t* __restrict__ st_idx = ls.st_idx;
+    const int c_lo = ls.cb[p], c_hi = ls.cb[p + 1];
 
-    // ---- (1) this part of the drafter row -> LDS, compacted to the shared ids (rank order).  Loads are
-    // unconditional (indices clamped into range, validity re-derived from the index when the data is used):
-    // a load under a branch makes the compiler wait for ALL outstanding loads at every use.
+    // ---- (1) the drafter logits of this part's pairs -> LDS.  Loads are unconditional (indices clamped into
+    // range, validity re-derived from the index when the data is used): a load under a branch makes the compiler
+    // wait for ALL outstanding loads at every use.
     {
-        const int r0 = p * per, r1 = min(S, r0 + per);
+        const int r0 = ls.st_start[p], r1 = ls.st_start[p + 1];
         bool my_bad = false;
         const uint32_t em = (DT == TLI_BF16) ? 0x7f80u : 0x7f800000u;     // NaN or +inf in a shared drafter logit
         const uint32_t ninf = (DT == TLI_BF16) ? 0xff80u : 0xff800000u;   // must surface (-inf is legal)
-        if (!sh_x) {
-            // compact rows are in rank order already: the part is a contiguous, 16-byte aligned stretch of the row
-            // (parts start at multiples of 8 ranks; the row stride covers S rounded up to a whole vector)
-            const u4v* src = reinterpret_cast<const u4v*>(ld_row + r0);
-            u4v* dst = reinterpret_cast<u4v*>(dpart);
-            const int nv = (r1 - r0 + EPV - 1) / EPV;
-            for (int v = tid; v < nv; v += kScanWG) {
-                const u4v t = src[v];
-                dst[v] = t;
-                uint32_t raw[EPV];
-                if constexpr (DT == TLI_BF16) {
-                    raw[0] = t.x & 0xffffu; raw[1] = t.x >> 16; raw[2] = t.y & 0xffffu; raw[3] = t.y >> 16;
-                    raw[4] = t.z & 0xffffu; raw[5] = t.z >> 16; raw[6] = t.w & 0xffffu; raw[7] = t.w >> 16;
-                } else {
-                    raw[0] = t.x; raw[1] = t.y; raw[2] = t.z; raw[3] = t.w;
-                }
-#pragma unroll
-                for (int i = 0; i < EPV; ++i)
-                    if (r0 + v * EPV + i < r1 && (raw[i] & em) == em && raw[i] != ninf) my_bad = true;
-            }
-        } else {
+        // Every workgroup of a part walks the SAME lists.  Walking them in step would aim all CUs at the same few
+        // cache lines -- one L2 channel serving everybody while the others idle (measured: the lists, not the
+        // logits, set the pace).  Each sequence therefore starts its walk at its own offset and wraps around.
+        const int ns = r1 - r0;
+        const int rot_s = ns > 0 ? (int)(((unsigned)b * 40503u * 64u) % (unsigned)ns) : 0;
+        auto place = [&](int i) { const int j = i + rot_s; return j >= ns ? j - ns : j; };  // i in [0, ns)
         int32_t xs[kStageU], xn[kStageU];
 #pragma unroll
-        for (int k = 0; k < kStageU; ++k) xs[k] = sh_x[min(r0 + tid + k * kScanWG, S - 1)];
-        for (int base = r0; base < r1; base += kStageU * kScanWG) {  // uniform bounds
+        for (int k = 0; k < kStageU; ++k) xs[k] = st_idx[min(r0 + place(min(tid + k * kScanWG, max(ns - 1, 0))), S - 1)];
+        for (int base = 0; base < ns; base += kStageU * kScanWG) {  // uniform bounds
             raw_t ys[kStageU];
 #pragma unroll
             for (int k = 0; k < kStageU; ++k) ys[k] = ld_row[xs[k]];
 #pragma unroll
-            for (int k = 0; k < kStageU; ++k)  // the next batch's ranks travel while the gathers are out
-                xn[k] = sh_x[min(base + kStageU * kScanWG + tid + k * kScanWG, S - 1)];
+            for (int k = 0; k < kStageU; ++k)  // the next batch's positions travel while the gathers are out
+                xn[k] = st_idx[min(r0 + place(min(base + kStageU * kScanWG + tid + k * kScanWG, ns - 1)), S - 1)];
 #pragma unroll
             for (int k = 0; k < kStageU; ++k) {
                 const int i = base + tid + k * kScanWG;
-                if (i < r1) {
-                    dpart[i - r0] = ys[k];
+                if (i < ns) {
+                    dpart[place(i)] = ys[k];
                     if (((uint32_t)ys[k] & em) == em && (uint32_t)ys[k] != ninf) my_bad = true;
                 }
                 xs[k] = xn[k];
             }
-        }
         }
         if (my_bad) fbad[b] = 1;
     }
     __syncthreads();
 
     // ---- (2) stream target chunks past it: this wave takes chunks gw, gw + stride, ...
-    double* my_mn = mn + ((int64_t)p * B + b) * nC;
+    double* my_mn = mn + (int64_t)b * nC;
     const ResidualParams rp = f.rp;
     const char* tslot = reinterpret_cast<const char*>(tstage[wave]);
     const char* dbase = reinterpret_cast<const char*>(dpart);
@@ -1033,20 +1028,25 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     // be pending every wait for a load degrades to a wait for all loads.
     double keep = 0.0, keep2 = 0.0;
     int it = 0;
-    double* my_mn2 = DIAG ? mn2 + ((int64_t)p * B + b) * nC : nullptr;
+    double* my_mn2 = DIAG ? mn2 + (int64_t)b * nC : nullptr;
+    const int ncp = c_hi - c_lo;  // chunks of this part; walked from a per-sequence offset, wrapping (see above)
+    const int rot_c = ncp > 0 ? (int)(((unsigned)b * 40503u) % (unsigned)ncp) : 0;
+    auto chunk_at = [&](int idx) { const int j = idx + rot_c; return c_lo + (j >= ncp ? j - ncp : j); };  // idx in [0, ncp)
     auto flush = [&](int first_it, int n) {
-        const int c = gw + (first_it + lane) * stride;
-        if (lane < n && c < nC) {
+        const int idx = gw + (first_it + lane) * stride;
+        const int c = chunk_at(min(idx, max(ncp - 1, 0)));
+        if (lane < n && idx < ncp) {
             my_mn[c] = keep;
             if (DIAG) my_mn2[c] = keep2;
         }
     };
     int ns0 = 0, ns1 = 0;  // list bounds of the next chunk, fetched one chunk ahead
-    if (gw < nC) { ns0 = my_start[gw]; ns1 = my_start[gw + 1]; }
-    for (int c = gw; c < nC; c += stride) {
+    if (gw < ncp) { ns0 = my_start[chunk_at(gw)]; ns1 = my_start[chunk_at(gw) + 1]; }
+    for (int idx = gw; idx < ncp; idx += stride) {
+        const int c = chunk_at(idx);
         const int s0 = ns0, s1 = ns1;
         {
-            const int cn = min(c + stride, nC - 1);
+            const int cn = chunk_at(min(idx + stride, ncp - 1));
             ns0 = my_start[cn]; ns1 = my_start[cn + 1];
         }
         u4v v[kLoads];
@@ -1108,13 +1108,13 @@ __global__ __launch_bounds__(kWave) void k_final_pick(const void* __restrict__ l
                                                        const float* __restrict__ tab_ref,
                                                        const float* __restrict__ tab_s,
                                                        const float2* __restrict__ ctab,
-                                                       const double* __restrict__ mn, int nparts, int B,
+                                                       const double* __restrict__ mn,
                                                        const int32_t* __restrict__ fbad, FinalOut o) {
     const int b = blockIdx.x;
     const FinalRow f = frow[b];
     if (f.skip) return;
     final_pick_row<DT>(f, b, logits_t, dv, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
-                       tab_s + (int64_t)b * nC, ctab, mn + (int64_t)b * nC, nparts, (int64_t)B * nC, fbad, o);
+                       tab_s + (int64_t)b * nC, ctab, mn + (int64_t)b * nC, fbad, o);
 }
 
 // ---- expected acceptance rates of every position ------------------------------------------------
@@ -1161,7 +1161,7 @@ __global__ __launch_bounds__(kWG) void k_diag_rows(const Part* __restrict__ part
 
 // kernel: alpha of every position = sum over parts and chunks of the scan's partial sums.  grid (rows), one wave.
 __global__ __launch_bounds__(kWave) void k_diag_finish(const FinalRow* __restrict__ frow, const double* __restrict__ mn,
-                                                        const double* __restrict__ mn2, int rows, int nparts, int nC,
+                                                        const double* __restrict__ mn2, int rows, int nC,
                                                         double* __restrict__ alpha_tli, double* __restrict__ alpha_union) {
     const int r = blockIdx.x, lane = threadIdx.x;
     const FinalRow f = frow[r];
@@ -1169,11 +1169,9 @@ __global__ __launch_bounds__(kWave) void k_diag_finish(const FinalRow* __restric
     if (f.skip) {
         a1 = a2 = NAN;
     } else if (f.rp.use_q) {
-        for (int p = 0; p < nparts; ++p) {
-            const double* m1 = mn + ((int64_t)p * rows + r) * nC;
-            const double* m2 = mn2 + ((int64_t)p * rows + r) * nC;
-            for (int c = lane; c < nC; c += kWave) { a1 += m1[c]; a2 += m2[c]; }
-        }
+        const double* m1 = mn + (int64_t)r * nC;
+        const double* m2 = mn2 + (int64_t)r * nC;
+        for (int c = lane; c < nC; c += kWave) { a1 += m1[c]; a2 += m2[c]; }
         a1 = wave_sum_f64(a1);
         a2 = wave_sum_f64(a2);
     }
@@ -1663,10 +1661,8 @@ Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
     w.fbad = off; off += align256((size_t)B * sizeof(int32_t));
     w.tab_ref = off; off += align256(tab * sizeof(float));
     w.tab_s = off; off += align256(tab * sizeof(float));
-    // the residual scan's partial sums: one table per LDS-sized part of the shared ids (at most min(Vd, Vt) ids)
-    const int cap = dtype == TLI_BF16 ? part_cap<TLI_BF16>() : part_cap<TLI_F32>();
-    const int max_parts = ((Vd < Vt ? Vd : Vt) + cap - 1) / cap;
-    w.mn = off; off += align256((size_t)max_parts * tab_rows_t * sizeof(double));
+    // the residual scan's sums of min(p, q'), one per chunk of the row the extra token is drawn from
+    w.mn = off; off += align256(tab_rows_t * sizeof(double));
     w.total = off;
     return w;
 }
@@ -1751,11 +1747,17 @@ struct tli_map {
     int32_t* sh_x;   // dev [S]: drafter id of the shared token of rank r (ranks ascend with the drafter id)
     int32_t* d2r;    // dev [Vd]: rank of a shared drafter id, -1 otherwise   } the index of a token in a drafter row
     int32_t* t2r;    // dev [Vt padded to 8]: rank of a shared target id, -1   } stored in compact (rank-order) layout
-    // Per dtype (index = tli_dtype), for the residual scan: the ranks are cut into nparts parts of `per`
-    // ranks (what one workgroup keeps in LDS); the shared pairs are grouped by (part, target chunk), ranks
-    // ascending inside a group.  pl_start [nparts * nC + 1]; pl_e [S]: offset of the target id in its
-    // chunk | (rank - part * per) << kPairShift.
-    int32_t nparts[2], per[2];
+    // Per dtype (index = tli_dtype), for the residual scan: the target chunks are cut into nparts parts (runs of
+    // whole chunks with at most part_cap shared pairs).  cb [nparts+1] first chunk of a part; st_start [nparts+1],
+    // st_x / st_r [S]: the pairs of a part in ascending drafter order, as drafter ids and as ranks (what one
+    // workgroup gathers into LDS, from a full or a compact drafter row); pl_start [nC+1], pl_e [S]: the pairs
+    // grouped by target chunk, entry = byte offset of the target id in its chunk | byte offset of the pair in its
+    // part's staging order << kPairShift.
+    int32_t nparts[2];
+    int32_t* cb[2];
+    int32_t* st_start[2];
+    int32_t* st_x[2];
+    int32_t* st_r[2];
     int32_t* pl_start[2];
     uint32_t* pl_e[2];
 };
@@ -1915,16 +1917,16 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
         // few sequences: deal the chunks of a (sequence, part) to several workgroups, up to one per CU
         int nsplit = 256 / (B * nparts);
         nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
+        const ScanLists ls{nparts, a.map->S, a.map->cb[DT], a.map->st_start[DT],
+                           a.compact ? a.map->st_r[DT] : a.map->st_x[DT], a.map->pl_start[DT], a.map->pl_e[DT]};
         hipLaunchKernelGGL((k_final_scan<DT, false>), dim3((unsigned)((B + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0,
-                           st, a.logits_t, a.dv, B, K, Vt, Vd, a.pf.nC, nparts, nsplit, a.map->per[DT], a.map->S,
-                           a.cs_t, a.ratio_t, a.frow, a.map->pl_start[DT], a.map->pl_e[DT], a.tab_ref, a.tab_s, a.mn,
-                           (double*)nullptr, a.fbad);
+                           st, a.logits_t, a.dv, B, K, Vt, Vd, a.pf.nC, nsplit, ls, a.cs_t, a.ratio_t, a.frow, a.tab_ref,
+                           a.tab_s, a.mn, (double*)nullptr, a.fbad);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
         hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.dv, K, Vt, Vd, a.pf.nC,
-                           a.cs_t, a.ratio_t, a.frow, a.dv.t2x, a.tab_ref, a.tab_s, a.ctab, a.mn,
-                           a.map->nparts[DT], B, a.fbad, fo);
+                           a.cs_t, a.ratio_t, a.frow, a.dv.t2x, a.tab_ref, a.tab_s, a.ctab, a.mn, a.fbad, fo);
     }
 }
 
@@ -1943,7 +1945,7 @@ DiagLayout diag_layout(const tli_map* map, int B, int K, int dtype) {
     w.part_q2 = off; off += align256((size_t)rows * pd.nsplit * sizeof(Part));
     w.frow = off; off += align256((size_t)rows * sizeof(FinalRow));
     w.fbad = off; off += align256((size_t)rows * sizeof(int32_t));
-    const size_t tab = (size_t)map->nparts[dtype] * rows * pt.nC * sizeof(double);
+    const size_t tab = (size_t)rows * pt.nC * sizeof(double);
     w.mn = off; off += align256(tab);
     w.mn2 = off; off += align256(tab);
     w.total = off;
@@ -1979,11 +1981,11 @@ void launch_diag(const tli_map* map, const void* logits_t, const void* logits_d,
     const int nparts = map->nparts[DT];
     int nsplit = 256 / (rows * nparts);
     nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
+    const ScanLists ls{nparts, map->S, map->cb[DT], map->st_start[DT], map->st_x[DT], map->pl_start[DT], map->pl_e[DT]};
     hipLaunchKernelGGL((k_final_scan<DT, true>), dim3((unsigned)((rows + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0, st,
-                       logits_t, DrafterView{logits_d, (int64_t)Vd, nullptr, map->t2d, map->sh_x}, rows, K, Vt, Vd, pt.nC,
-                       nparts, nsplit, map->per[DT], map->S, cs_t, ratio_t, frow, map->pl_start[DT], map->pl_e[DT],
-                       (float*)nullptr, (float*)nullptr, mn, mn2, fbad);
-    hipLaunchKernelGGL(k_diag_finish, dim3(rows), dim3(kWave), 0, st, frow, mn, mn2, rows, nparts, pt.nC, alpha_tli,
+                       logits_t, DrafterView{logits_d, (int64_t)Vd, nullptr, map->t2d}, rows, K, Vt, Vd, pt.nC, nsplit, ls,
+                       cs_t, ratio_t, frow, (float*)nullptr, (float*)nullptr, mn, mn2, fbad);
+    hipLaunchKernelGGL(k_diag_finish, dim3(rows), dim3(kWave), 0, st, frow, mn, mn2, rows, pt.nC, alpha_tli,
                        alpha_union);
 }
 }  // namespace
@@ -2078,27 +2080,58 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
         for (int32_t x = 0; x < Vd; ++x)
             if (d2t[x] >= 0) sh_x[r++] = x;
     }
-    std::vector<int32_t> pl_start[2];
+    std::vector<int32_t> pl_start[2], cb[2], st_start[2], st_x[2], st_r[2];
     std::vector<uint32_t> pl_e[2];
-    int nparts[2], per[2];
+    int nparts[2];
     for (int dt = 0; dt < 2; ++dt) {
         const int CH = dt == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
         const int cap = dt == TLI_BF16 ? part_cap<TLI_BF16>() : part_cap<TLI_F32>();
         const int esz = dt == TLI_BF16 ? 2 : 4;
         const int nC = (Vt + CH - 1) / CH;
-        nparts[dt] = (S + cap - 1) / cap;
-        per[dt] = ((S + nparts[dt] - 1) / nparts[dt] + 7) & ~7;  // a multiple of 8 (<= cap): parts start on 16 bytes
-        const size_t ngroups = (size_t)nparts[dt] * nC;
-        pl_start[dt].assign(ngroups + 1, 0);
+        // pairs per chunk, then parts: runs of whole chunks, filled evenly but never beyond what LDS holds
+        std::vector<int32_t> cc(nC, 0);
+        for (int32_t r = 0; r < S; ++r) ++cc[d2t[sh_x[r]] / CH];
+        const int want = (S + cap - 1) / cap;
+        const int64_t even = ((int64_t)S + want - 1) / want;
+        int32_t biggest = 0;
+        for (int c = 0; c < nC; ++c) biggest = cc[c] > biggest ? cc[c] : biggest;
+        const int64_t limit = even + biggest < cap ? even + biggest : cap;
+        cb[dt].assign(1, 0);
+        int64_t acc = 0;
+        for (int c = 0; c < nC; ++c) {
+            if (acc > 0 && acc + cc[c] > limit) { cb[dt].push_back(c); acc = 0; }
+            acc += cc[c];
+        }
+        cb[dt].push_back(nC);
+        nparts[dt] = (int)cb[dt].size() - 1;
+        std::vector<int32_t> part_of_chunk(nC);
+        for (int p = 0; p < nparts[dt]; ++p)
+            for (int c = cb[dt][p]; c < cb[dt][p + 1]; ++c) part_of_chunk[c] = p;
+        // staging order: the pairs of a part by ascending drafter id (ranks ascend with the drafter id)
+        st_start[dt].assign(nparts[dt] + 1, 0);
+        for (int c = 0; c < nC; ++c) st_start[dt][part_of_chunk[c] + 1] += cc[c];
+        for (int p = 0; p < nparts[dt]; ++p) st_start[dt][p + 1] += st_start[dt][p];
+        st_x[dt].resize(S);
+        st_r[dt].resize(S);
+        std::vector<int32_t> pos(S);  // place of pair (rank r) in its part's staging order
+        {
+            std::vector<int32_t> fill(st_start[dt].begin(), st_start[dt].end() - 1);
+            for (int32_t r = 0; r < S; ++r) {
+                const int p = part_of_chunk[d2t[sh_x[r]] / CH];
+                pos[r] = fill[p] - st_start[dt][p];
+                st_x[dt][fill[p]] = sh_x[r];
+                st_r[dt][fill[p]] = r;
+                ++fill[p];
+            }
+        }
+        // pairs grouped by target chunk (ranks ascending inside a chunk)
+        pl_start[dt].assign(nC + 1, 0);
+        for (int c = 0; c < nC; ++c) pl_start[dt][c + 1] = pl_start[dt][c] + cc[c];
         pl_e[dt].resize(S);
-        for (int32_t r = 0; r < S; ++r) ++pl_start[dt][(size_t)(r / per[dt]) * nC + d2t[sh_x[r]] / CH + 1];
-        for (size_t g = 0; g < ngroups; ++g) pl_start[dt][g + 1] += pl_start[dt][g];
         std::vector<int32_t> fill(pl_start[dt].begin(), pl_start[dt].end() - 1);
         for (int32_t r = 0; r < S; ++r) {
             const int32_t t = d2t[sh_x[r]];
-            const int part = r / per[dt];
-            pl_e[dt][fill[(size_t)part * nC + t / CH]++] =
-                (uint32_t)((t % CH) * esz) | ((uint32_t)((r - part * per[dt]) * esz) << kPairShift);
+            pl_e[dt][fill[t / CH]++] = (uint32_t)((t % CH) * esz) | ((uint32_t)(pos[r] * esz) << kPairShift);
         }
     }
     // shared-id mask of the drafter vocabulary in lane-mask layout (see mask_bits), padded to whole chunks
@@ -2119,7 +2152,8 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
     m->Vd = Vd; m->Vt = Vt; m->S = S; m->d2t = nullptr; m->t2d = nullptr; m->lmask[0] = m->lmask[1] = nullptr;
     m->sh_x = nullptr; m->d2r = nullptr; m->t2r = nullptr;
     for (int dt = 0; dt < 2; ++dt) {
-        m->nparts[dt] = nparts[dt]; m->per[dt] = per[dt]; m->pl_start[dt] = nullptr; m->pl_e[dt] = nullptr;
+        m->nparts[dt] = nparts[dt]; m->pl_start[dt] = nullptr; m->pl_e[dt] = nullptr;
+        m->cb[dt] = nullptr; m->st_start[dt] = nullptr; m->st_x[dt] = nullptr; m->st_r[dt] = nullptr;
     }
     if (hipGetDevice(&m->device) != hipSuccess) { delete m; return TLI_ERR_HIP; }
     bool ok = hipMalloc(&m->d2t, d2t.size() * 4) == hipSuccess && hipMalloc(&m->t2d, t2d.size() * 4) == hipSuccess &&
@@ -2146,11 +2180,19 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
     }
     for (int dt = 0; dt < 2; ++dt) {
         ok = hipMalloc(&m->pl_start[dt], pl_start[dt].size() * 4) == hipSuccess &&
-             hipMalloc(&m->pl_e[dt], (size_t)S * 4) == hipSuccess;
+             hipMalloc(&m->pl_e[dt], (size_t)S * 4) == hipSuccess &&
+             hipMalloc(&m->cb[dt], cb[dt].size() * 4) == hipSuccess &&
+             hipMalloc(&m->st_start[dt], st_start[dt].size() * 4) == hipSuccess &&
+             hipMalloc(&m->st_x[dt], (size_t)S * 4) == hipSuccess && hipMalloc(&m->st_r[dt], (size_t)S * 4) == hipSuccess;
         if (!ok) { tli_free_map(m); return TLI_ERR_ALLOC; }
         ok = hipMemcpy(m->pl_start[dt], pl_start[dt].data(), pl_start[dt].size() * 4, hipMemcpyHostToDevice) ==
                  hipSuccess &&
-             hipMemcpy(m->pl_e[dt], pl_e[dt].data(), (size_t)S * 4, hipMemcpyHostToDevice) == hipSuccess;
+             hipMemcpy(m->pl_e[dt], pl_e[dt].data(), (size_t)S * 4, hipMemcpyHostToDevice) == hipSuccess &&
+             hipMemcpy(m->cb[dt], cb[dt].data(), cb[dt].size() * 4, hipMemcpyHostToDevice) == hipSuccess &&
+             hipMemcpy(m->st_start[dt], st_start[dt].data(), st_start[dt].size() * 4, hipMemcpyHostToDevice) ==
+                 hipSuccess &&
+             hipMemcpy(m->st_x[dt], st_x[dt].data(), (size_t)S * 4, hipMemcpyHostToDevice) == hipSuccess &&
+             hipMemcpy(m->st_r[dt], st_r[dt].data(), (size_t)S * 4, hipMemcpyHostToDevice) == hipSuccess;
         if (!ok) { tli_free_map(m); return TLI_ERR_HIP; }
     }
     *out_map = m;
@@ -2170,6 +2212,10 @@ void tli_free_map(tli_map* m) {
     for (int dt = 0; dt < 2; ++dt) {
         if (m->pl_start[dt]) (void)hipFree(m->pl_start[dt]);
         if (m->pl_e[dt]) (void)hipFree(m->pl_e[dt]);
+        if (m->cb[dt]) (void)hipFree(m->cb[dt]);
+        if (m->st_start[dt]) (void)hipFree(m->st_start[dt]);
+        if (m->st_x[dt]) (void)hipFree(m->st_x[dt]);
+        if (m->st_r[dt]) (void)hipFree(m->st_r[dt]);
     }
     delete m;
 }
@@ -2408,7 +2454,6 @@ static int verify_impl(int union_mode, int64_t compact_stride, const tli_map* ma
     a.dv.row_stride = compact ? compact_stride : (int64_t)Vd;
     a.dv.d2x = compact ? map->d2r : nullptr;
     a.dv.t2x = compact ? map->t2r : map->t2d;
-    a.dv.stage = compact ? nullptr : map->sh_x;
     a.pd = make_plan(a.d_valid, rows, chunk); a.cs_d = (float)c_d; a.ratio_d = c_d / (double)a.cs_d; a.tab_ref = tab_ref; a.tab_s = tab_s;
     a.mn = reinterpret_cast<double*>(ws + w.mn); a.fbad = reinterpret_cast<int32_t*>(ws + w.fbad); a.ctab = reinterpret_cast<float2*>(ws + w.ctab);
     a.frow = reinterpret_cast<FinalRow*>(ws + w.frow);
