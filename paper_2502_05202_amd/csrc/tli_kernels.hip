@@ -879,43 +879,96 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
 // sum_chunk p = s * 2^(ref * c_true/c - lse_p * log2 e).  Only the second sum is computed here; it runs over
 // the shared PAIRS (target id, drafter id) alone.  The two vocabularies' orders are unrelated, so a pair
 // needs one random access on each side -- and random access is cheap only in LDS.  The target row is cut
-// into PARTS, runs of whole chunks holding at most part_cap pairs.  A workgroup owns one part of one row: it
-// gathers the drafter logits of the part's pairs into LDS once (through the map's list of their positions
-// in the drafter row, ascending, so the reads sweep the row front to back), then its 16 waves stream the
-// part's target chunks: a wave parks a chunk in its private LDS slot and walks the map's list of the
-// chunk's pairs, each entry = (byte offset in chunk, byte offset in the staged part), reading both logits
-// from LDS.  Every target chunk is thus read once per row, every pair is owned by one lane of one wave, and
-// sums are per-lane, then fp64 across lanes, so results do not depend on timing.
+// into PARTS, runs of whole chunks holding at most part_cap pairs.  A workgroup owns one part of one row.
+//   (1) It sweeps the drafter row with plain 16-byte loads and packs the logits of the part's pairs into LDS in
+//       ascending drafter order.  Beside every vector of the row the map holds one word: which of the vector's
+//       elements belong to the part, and the LDS position of the first of them.  A lane stores all its
+//       elements, the unwanted ones to a scratch word of its own, so the sweep has no branch, no mask
+//       juggling and no index list.  (Gathering the part through an index list was tried first: a 2-byte
+//       gather costs the texture addresser ~30 cycles per wave instruction, more than the whole target row.)
+//   (2) Its waves stream the part's target chunks: a wave parks a chunk in its private LDS slot and walks the
+//       map's list of the chunk's pairs, each entry = (byte offset in chunk, index of the staged drafter
+//       logit), reading both logits from LDS.
+// Every target chunk is thus read once per row, every pair is owned by one lane of one wave, and sums are
+// per lane, then across lanes in a fixed order, so results do not depend on timing.
+// The kernel is short (tens of microseconds) and its waves are few (16 per CU): counters show it bound by
+// instruction issue and by dependent round trips, not by bandwidth.  Hence:
+//   * a chunk's pair list is padded to whole groups of 128 entries (two per lane, one 8-byte load) with
+//     entries that point at a -inf logit (min(p, 0) contributes exactly 0): a group is either all live or
+//     absent and the only test is a wave-uniform one; the list has kPairU groups of slack at its end, so the
+//     first kPairU groups of every chunk are fetched without looking at its length;
+//   * an entry is two 16-bit fields that the address arithmetic reads in place;
+//   * the loads of a wave's next chunk are in flight while it works on the current one (two register sets,
+//     alternating), those of its first chunk are issued before the staging sweep, and the list bounds of
+//     all its chunks come with one vector load (scalar loads would miss the scalar cache at every step, and
+//     a wait for one of them is a wait for everything else the wave has in flight on that counter);
+//   * no load sits under a branch (the compiler would then wait for ALL outstanding loads at every use): a
+//     fetch past the end of the part is made harmless, every lane reading the same few lines again.
 // Output: mn[b][chunk] = sum of min(p, q') over the chunk's pairs; the draw kernel forms the masses.
-// The loop is deliberately NOT unrolled into a multi-chunk register pipeline: the kernel runs for tens of
-// microseconds, every instruction is executed a handful of times, and cold instruction fetch of a larger
-// body cost more than the latency it hid (measured: one chunk in flight per wave 66 us, three 76 us).
 // Bonus rows (nothing rejected) go through the same grid: the workgroups of a sequence split target row K
 // and scan it into a plain (ref, s) softmax table.
-// grid (B rounded up to 8) x nparts x nsplit, 1024 threads; workgroups of flagged sequences exit at once.
+// grid (B rounded up to 8) x nparts x nsplit; workgroups of flagged sequences exit at once.
 // nsplit > 1 (few sequences): the chunks of one (sequence, part) are dealt to nsplit workgroups, each with
 // its own copy of the part's drafter logits.
 constexpr int kScanWG = 1024;
 constexpr int kScanWaves = kScanWG / kWave;
-constexpr int kPartBytes = 92 * 1024;  // + one 4 KB chunk slot per wave = 156 KB of the CU's 160 KB
-#ifndef KPAIRU
-#define KPAIRU 12
-#endif
-constexpr int kPairU = KPAIRU;              // list entries per lane fetched with a chunk (512 pairs; more: late loop)
-constexpr int kStageU = 8;
-constexpr int kWaitVm0 = 0x0F70;       // s_waitcnt vmcnt(0) alone (expcnt and lgkmcnt fields at their maximum)
-constexpr int kPairShift = 12;         // entry = byte offset in chunk (< 4096) | byte offset in the staged part << 12
+constexpr int kSlotBytes = kWave * kLoads * 16;  // one chunk
+constexpr int kTrashBytes = kWave * 4;           // LDS [0, 256): a word per lane for the elements a lane does not keep
+constexpr int kPartBytes = 92 * 1024;            // then the staged drafter logits of a part, the last 16 bytes of the
+                                                 // area hold the -inf logit that padding entries point at
+constexpr int kScanLds = kPartBytes + kScanWaves * kSlotBytes;  // then one chunk slot per wave
+constexpr int kPairG = 2 * kWave;      // entries in a group of a chunk's pair list: two per lane
+constexpr int kPairU = 6;              // groups fetched with a chunk (more: late loop)
+constexpr int kStageV = 8;             // drafter vectors a lane has in flight during the staging sweep
+constexpr int kPairShift = 16;         // entry = byte offset in chunk (< 4096) | index of the staged logit << 16
+constexpr int kMaxPartChunks = kWave * kScanWaves;  // a wave keeps a lane per chunk it handles
+static_assert(kScanLds <= 160 * 1024, "LDS of one CU");
 
-struct ScanLists {            // the map's lists for one dtype, as the scan kernel reads them
-    int nparts, S;
+struct ScanLists {            // the map's lists for one dtype and one drafter-row layout, as the scan kernel reads them
+    int nparts;
+    int row_elems;            // valid entries of a drafter row: |D| (full layout) or |T∩D| (compact)
+    int NV;                   // vectors of a drafter row, rounded up to whole groups of 64
     const int32_t* cb;        // [nparts+1] first chunk of every part
-    const int32_t* st_start;  // [nparts+1] first staging entry of every part
-    const int32_t* st_idx;    // [S] position in the drafter row of the pair staged at this place (drafter id in
-                              //     the full layout, rank in the compact one), ascending inside a part
-    const int32_t* pl_start;  // [nC+1] first pair of every chunk
-    const uint32_t* pl_e;     // [S] pairs grouped by chunk
+    const int32_t* part_n;    // [nparts] pairs of every part
+    const int2* grange;       // [nparts] first and one-past-last group of 64 vectors that hold a logit of the part
+    const uint32_t* stab;     // [nparts][NV] per vector: staged index of its first logit of the part | which of its
+                              //     elements belong to the part << 16
+    const int32_t* pl_g;      // [nC+1] first group of every chunk's pair list
+    const uint2* pl_e;        // pairs grouped by chunk (two per lane and group), kPairU groups of slack at the end
 };
-template <int DT> constexpr int part_cap() { return kPartBytes / Traits<DT>::ESZ; }
+// pairs a part may hold, and the index of the -inf logit
+template <int DT> constexpr int part_cap() { return (kPartBytes - kTrashBytes - 16) / Traits<DT>::ESZ; }
+template <int DT> constexpr int dummy_index() { return part_cap<DT>(); }
+static_assert(dummy_index<TLI_BF16>() < (1 << 16) && dummy_index<TLI_F32>() < (1 << 16), "16-bit staged index");
+
+// NaN or +inf among the staged drafter logits must surface (-inf is legal).  As signed integers the raw
+// patterns of +inf and the positive NaNs are the largest values, as unsigned ones the negative NaNs are (just
+// above -inf): two running maxima, taken on both halves of a dword at once for bf16.
+template <int DT> struct BadTrack;
+template <> struct BadTrack<TLI_BF16> {
+    typedef short s2v __attribute__((ext_vector_type(2)));
+    typedef unsigned short us2v __attribute__((ext_vector_type(2)));
+    s2v sm = {(short)-32768, (short)-32768};
+    us2v um = {0, 0};
+    __device__ __forceinline__ void add(uint32_t w) {
+        sm = __builtin_elementwise_max(sm, __builtin_bit_cast(s2v, w));
+        um = __builtin_elementwise_max(um, __builtin_bit_cast(us2v, w));
+    }
+    __device__ __forceinline__ void add_one(uint32_t raw) { add(raw | (raw << 16)); }
+    __device__ __forceinline__ bool bad() const {
+        return sm.x >= (short)0x7f80 || sm.y >= (short)0x7f80 || um.x > 0xff80u || um.y > 0xff80u;
+    }
+};
+template <> struct BadTrack<TLI_F32> {
+    int32_t sm = INT32_MIN;
+    uint32_t um = 0;
+    __device__ __forceinline__ void add(uint32_t w) {
+        sm = max(sm, (int32_t)w);
+        um = max(um, w);
+    }
+    __device__ __forceinline__ void add_one(uint32_t raw) { add(raw); }
+    __device__ __forceinline__ bool bad() const { return sm >= 0x7f800000 || um > 0xff800000u; }
+};
 
 // DIAG (acceptance-rate diagnostics): the items are all B*K positions instead of one row per sequence, and a
 // second sum runs beside the first with the drafter's unrestricted probabilities q = q' * 2^-dq:
@@ -927,24 +980,40 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     int32_t* __restrict__ fbad) {
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int ESZ = Traits<DT>::ESZ;
-    constexpr int CH = chunk_elems<DT>();
     typedef typename std::conditional<DT == TLI_BF16, uint16_t, uint32_t>::type raw_t;
-    __shared__ __attribute__((aligned(16))) raw_t dpart[part_cap<DT>()];
-    __shared__ __attribute__((aligned(16))) raw_t tstage[kScanWaves][CH];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[kScanLds];
+    unsigned char* const part = lds + kTrashBytes;  // staged logit i at part + i * ESZ
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  The workgroups of one sequence
     // stream the same rows, so they are given ids that land on the same XCD, next to each other in time:
     // id = slot * 8 + xcd, sequence = (slot / per_seq) * 8 + xcd, (part, split) = slot % per_seq.
-    const int nparts = ls.nparts, S = ls.S;
+    const int nparts = ls.nparts;
     const int per_seq = nparts * nsplit;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int b = (slot / per_seq) * 8 + xcd, sub = slot % per_seq;
     const int p = sub / nsplit, sp = sub - p * nsplit;
     if (b >= B) return;
-    const FinalRow f = frow[b];
-    if (f.skip) return;
+    // What the part is and where the lists of this wave's chunks begin do not depend on the sequence: they are
+    // fetched beside the sequence's record rather than after it.
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
+    const int c_lo = ls.cb[p], c_hi = ls.cb[p + 1];
+    const int2 gr = ls.grange[p];
+    const int ns = ls.part_n[p];
+    const int ncp = c_hi - c_lo;  // 1 .. kMaxPartChunks
+    const int gw = sp * kScanWaves + wave, stride = nsplit * kScanWaves;  // this wave takes chunks gw, gw + stride, ...
+    const int32_t* __restrict__ pl_g = ls.pl_g;
+    const uint2* __restrict__ pl_e = ls.pl_e;
+    // The list bounds (in groups of kPairG entries) of the wave's chunks: lane k holds those of its k-th chunk,
+    // lanes past the wave's last chunk those of the part's first chunk.
+    int2 gbv;
+    {
+        const int idx = gw + lane * stride;
+        const int c = c_lo + (idx < ncp ? idx : 0);
+        gbv = make_int2(pl_g[c], pl_g[c + 1]);
+    }
+    const FinalRow f = frow[b];
+    if (f.skip) return;
     if (f.bonus) {
         const u4v* rowk = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) + (int64_t)f.t_row * Vt * ESZ);
         float* br = tab_ref + (int64_t)b * nC;
@@ -957,146 +1026,163 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         return;
     }
     if (!f.rp.use_q) return;  // q' = 0 everywhere: the masses are the chunk sums of p, nothing to subtract
-    const raw_t* ld_row =
-        reinterpret_cast<const raw_t*>(static_cast<const char*>(dv.base) + (int64_t)f.d_row * dv.row_stride * ESZ);
-    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
-                                                    (int64_t)f.t_row * Vt * ESZ);
+    // rows as byte pointers: every offset below fits 32 bits, which keeps the address arithmetic to one instruction
+    const char* __restrict__ drow = static_cast<const char*>(dv.base) + (int64_t)f.d_row * dv.row_stride * ESZ;
+    const char* __restrict__ trow = static_cast<const char*>(logits_t) + (int64_t)f.t_row * Vt * ESZ;
     const int nvec = (Vt + EPV - 1) / EPV;
-    const int32_t* __restrict__ my_start = ls.pl_start;
-    const uint32_t* __restrict__ pl_e = ls.pl_e;
-    const int32_t* __restrict__ st_idx = ls.st_idx;
-    const int c_lo = ls.cb[p], c_hi = ls.cb[p + 1];
 
-    // ---- (1) the drafter logits of this part's pairs -> LDS.  Loads are unconditional (indices clamped into
-    // range, validity re-derived from the index when the data is used): a load under a branch makes the compiler
-    // wait for ALL outstanding loads at every use.
+    struct Fetched {
+        u4v v[kLoads];
+        uint2 e[kPairU];
+    };
+    // Loads of the wave's chunk number k and of the head of its pair list.  Past the end of the part every lane
+    // reads lane 0's addresses of the part's first chunk: a few cache lines, nothing new.
+    auto fetch = [&](int k, Fetched& r) {
+        const int idx = gw + k * stride;
+        const bool ok = idx < ncp;
+        const int c = c_lo + (ok ? idx : 0);
+        const uint32_t ln = ok ? lane : 0;
+        const uint32_t g0 = __builtin_amdgcn_readlane(gbv.x, k);
+        const uint32_t v0 = (uint32_t)c * (kLoads * kWave) + ln;
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j)  // vectors past the row's end re-read its last vector: no pair points there
+            r.v[j] = *reinterpret_cast<const u4v*>(trow + min(v0 + j * kWave, (uint32_t)nvec - 1u) * 16u);
+        const char* ep = reinterpret_cast<const char*>(pl_e) + (size_t)g0 * (kWave * 8);
+#pragma unroll
+        for (int k2 = 0; k2 < kPairU; ++k2) r.e[k2] = *reinterpret_cast<const uint2*>(ep + (ln * 8u + k2 * (kWave * 8)));
+    };
+    Fetched fa, fb;
+    fetch(0, fa);
+
+    // ---- (1) the drafter logits of this part's pairs -> LDS
     {
-        const int r0 = ls.st_start[p], r1 = ls.st_start[p + 1];
-        bool my_bad = false;
-        const uint32_t em = (DT == TLI_BF16) ? 0x7f80u : 0x7f800000u;     // NaN or +inf in a shared drafter logit
-        const uint32_t ninf = (DT == TLI_BF16) ? 0xff80u : 0xff800000u;   // must surface (-inf is legal)
-        // Every workgroup of a part walks the SAME lists.  Walking them in step would aim all CUs at the same few
-        // cache lines -- one L2 channel serving everybody while the others idle (measured: the lists, not the
-        // logits, set the pace).  Each sequence therefore starts its walk at its own offset and wraps around.
-        const int ns = r1 - r0;
-        const int rot_s = ns > 0 ? (int)(((unsigned)b * 40503u * 64u) % (unsigned)ns) : 0;
-        auto place = [&](int i) { const int j = i + rot_s; return j >= ns ? j - ns : j; };  // i in [0, ns)
-        int32_t xs[kStageU], xn[kStageU];
+        const int nvd = (ls.row_elems + EPV - 1) / EPV;
+        // The part's groups of 64 vectors are dealt to the waves in equal runs.  (The waves of a workgroup do not
+        // start together: they are launched four at a time, the last four some 17,000 cycles after the first.
+        // Giving the early ones more of the sweep was tried and moved the barrier by little: the late waves'
+        // own first round trips to memory are what it waits for.)
+        const int per_wave = (gr.y - gr.x + kScanWaves - 1) / kScanWaves;
+        const int gbeg = gr.x + wave * per_wave, gend = min(gbeg + per_wave, gr.y);
+        if (tid == 0)
+            *reinterpret_cast<uint32_t*>(part + dummy_index<DT>() * ESZ) = DT == TLI_BF16 ? 0xff80ff80u : 0xff800000u;
+        const uint32_t mine = (uint32_t)lane * 4;  // the lane's scratch word
+        const char* __restrict__ stab = reinterpret_cast<const char*>(ls.stab + (int64_t)p * ls.NV);
+        const uint32_t vlast = (uint32_t)min(gend * kWave, nvd) - 1u;  // the wave's last vector
+        for (int g0 = gbeg; g0 < gend; g0 += kStageV) {  // wave-uniform
+            u4v v[kStageV];
+            uint32_t tv[kStageV];
 #pragma unroll
-        for (int k = 0; k < kStageU; ++k) xs[k] = st_idx[min(r0 + place(min(tid + k * kScanWG, max(ns - 1, 0))), S - 1)];
-        for (int base = 0; base < ns; base += kStageU * kScanWG) {  // uniform bounds
-            raw_t ys[kStageU];
+            for (int u = 0; u < kStageV; ++u) {
+                // past the wave's last vector: that vector is done again, the same bytes to the same places
+                const uint32_t vi = min((uint32_t)(g0 + u) * kWave + lane, vlast);
+                v[u] = *reinterpret_cast<const u4v*>(drow + vi * 16u);
+                tv[u] = *reinterpret_cast<const uint32_t*>(stab + vi * 4u);
+            }
 #pragma unroll
-            for (int k = 0; k < kStageU; ++k) ys[k] = ld_row[xs[k]];
+            for (int u = 0; u < kStageV; ++u) {
+                const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+                // d = (LDS address of the lane's next kept logit) - mine, so address = mine + keep * d
+                uint32_t d = kTrashBytes + (tv[u] & 0xffffu) * ESZ - mine;
 #pragma unroll
-            for (int k = 0; k < kStageU; ++k)  // the next batch's positions travel while the gathers are out
-                xn[k] = st_idx[min(r0 + place(min(base + kStageU * kScanWG + tid + k * kScanWG, ns - 1)), S - 1)];
-#pragma unroll
-            for (int k = 0; k < kStageU; ++k) {
-                const int i = base + tid + k * kScanWG;
-                if (i < ns) {
-                    dpart[place(i)] = ys[k];
-                    if (((uint32_t)ys[k] & em) == em && (uint32_t)ys[k] != ninf) my_bad = true;
+                for (int i = 0; i < EPV; ++i) {
+                    const uint32_t k1 = (tv[u] >> (16 + i)) & 1u;
+                    uint32_t at;  // = mine + k1 * d (d < 2^24; written out because the compiler would mask d first)
+                    asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(at) : "v"(k1), "v"(d), "v"(mine));
+                    if (DT == TLI_BF16)
+                        *reinterpret_cast<uint16_t*>(lds + at) = (uint16_t)(i & 1 ? w[i >> 1] >> 16 : w[i >> 1]);
+                    else
+                        *reinterpret_cast<uint32_t*>(lds + at) = w[i];
+                    // d += k1 * ESZ, likewise (the compiler would keep a count and rebuild d from it, an instruction more)
+                    asm("v_lshl_add_u32 %0, %1, %2, %0" : "+v"(d) : "v"(k1), "n"(ESZ == 2 ? 1 : 2));
                 }
-                xs[k] = xn[k];
             }
         }
-        if (my_bad) fbad[b] = 1;
     }
     __syncthreads();
 
-    // ---- (2) stream target chunks past it: this wave takes chunks gw, gw + stride, ...
+    // NaN / +inf among the staged logits (the flag is stored at the very end: a pending store would turn every
+    // wait for a load into a wait for all of them)
+    BadTrack<DT> bt;
+    {
+        const int nfull = ns / EPV;
+        const uint4* lv = reinterpret_cast<const uint4*>(part);
+        for (int o = tid; o < nfull; o += kScanWG) {
+            const uint4 w = lv[o];
+            bt.add(w.x); bt.add(w.y); bt.add(w.z); bt.add(w.w);
+        }
+        if (tid < ns - nfull * EPV) bt.add_one(reinterpret_cast<const raw_t*>(part)[nfull * EPV + tid]);
+    }
+
+    // ---- (2) stream target chunks past it
     double* my_mn = mn + (int64_t)b * nC;
+    double* my_mn2 = DIAG ? mn2 + (int64_t)b * nC : nullptr;
     const ResidualParams rp = f.rp;
-    const char* tslot = reinterpret_cast<const char*>(tstage[wave]);
-    const char* dbase = reinterpret_cast<const char*>(dpart);
-    // min(p, q') of one pair = 2^min(log2 p, log2 q'): one exponential per pair.  An entry read through a
-    // clamped index is some other valid pair (in-range offsets); the caller drops its value.
+    const uint32_t tb = (uint32_t)(kPartBytes + wave * kSlotBytes);
+    // log2 p = x*ct - Lp and log2 q' = y*cd - Lq in two-term form.  The subtrahends are pinned to vector registers:
+    // an instruction may read one scalar register only, and the compiler would otherwise copy them over per use.
+    float nlp_hi = -rp.lp_hi, nlp_lo = -rp.lp_lo, nlq_hi = -rp.lq_hi, nlq_lo = -rp.lq_lo;
+    asm volatile("" : "+v"(nlp_hi), "+v"(nlp_lo), "+v"(nlq_hi), "+v"(nlq_lo));
+    // min(p, q') of one pair = 2^min(log2 p, log2 q'): one exponential per pair
     const float dq = f.dq;
     auto pair_min = [&](uint32_t e, float& second) -> float {
-        const uint32_t xr = *reinterpret_cast<const raw_t*>(tslot + (e & ((1u << kPairShift) - 1u)));
-        const uint32_t yr = *reinterpret_cast<const raw_t*>(dbase + (e >> kPairShift));
+        const uint32_t xr = *reinterpret_cast<const raw_t*>(lds + (tb + (e & 0xffffu)));
+        const uint32_t yr = *reinterpret_cast<const raw_t*>(part + (e >> kPairShift) * ESZ);
         const float xv = as_f(DT == TLI_BF16 ? xr << 16 : xr), yv = as_f(DT == TLI_BF16 ? yr << 16 : yr);
-        const float a = fmaf(xv, rp.ct_hi, -rp.lp_hi) + fmaf(xv, rp.ct_lo, -rp.lp_lo);
-        const float bq = fmaf(yv, rp.cd_hi, -rp.lq_hi) + fmaf(yv, rp.cd_lo, -rp.lq_lo);
+        const float a = fmaf(xv, rp.ct_hi, nlp_hi) + fmaf(xv, rp.ct_lo, nlp_lo);
+        const float bq = fmaf(yv, rp.cd_hi, nlq_hi) + fmaf(yv, rp.cd_lo, nlq_lo);
         if (DIAG) second = exp2_hw(fminf(a, bq - dq));
         return exp2_hw(fminf(a, bq));
     };
-    const int gw = sp * kScanWaves + wave, stride = nsplit * kScanWaves;
-    // Results stay in registers until the wave is through (lane i keeps the sum of the wave's i-th chunk):
+    // Results stay in registers until the wave is through (lane k keeps the sum of the wave's k-th chunk):
     // a store shares the loads' completion counter and completes out of order with them, so while one may
     // be pending every wait for a load degrades to a wait for all loads.
     double keep = 0.0, keep2 = 0.0;
-    int it = 0;
-    double* my_mn2 = DIAG ? mn2 + (int64_t)b * nC : nullptr;
-    const int ncp = c_hi - c_lo;  // chunks of this part; walked from a per-sequence offset, wrapping (see above)
-    const int rot_c = ncp > 0 ? (int)(((unsigned)b * 40503u) % (unsigned)ncp) : 0;
-    auto chunk_at = [&](int idx) { const int j = idx + rot_c; return c_lo + (j >= ncp ? j - ncp : j); };  // idx in [0, ncp)
-    auto flush = [&](int first_it, int n) {
-        const int idx = gw + (first_it + lane) * stride;
-        const int c = chunk_at(min(idx, max(ncp - 1, 0)));
-        if (lane < n && idx < ncp) {
-            my_mn[c] = keep;
-            if (DIAG) my_mn2[c] = keep2;
-        }
-    };
-    int ns0 = 0, ns1 = 0;  // list bounds of the next chunk, fetched one chunk ahead
-    if (gw < ncp) { ns0 = my_start[chunk_at(gw)]; ns1 = my_start[chunk_at(gw) + 1]; }
-    for (int idx = gw; idx < ncp; idx += stride) {
-        const int c = chunk_at(idx);
-        const int s0 = ns0, s1 = ns1;
-        {
-            const int cn = chunk_at(min(idx + stride, ncp - 1));
-            ns0 = my_start[cn]; ns1 = my_start[cn + 1];
-        }
-        u4v v[kLoads];
+    auto process = [&](const Fetched& r, int k) {
+        u4v* st = reinterpret_cast<u4v*>(lds + tb);
 #pragma unroll
-        for (int j = 0; j < kLoads; ++j)  // vectors past the row's end re-read its last vector: no pair points there
-            v[j] = rowv[min((c * kLoads + j) * kWave + lane, nvec - 1)];
-        uint32_t e[kPairU];
-#pragma unroll
-        for (int k = 0; k < kPairU; ++k) e[k] = pl_e[min(s0 + k * kWave + lane, S - 1)];
-        u4v* st = reinterpret_cast<u4v*>(tstage[wave]);
-#pragma unroll
-        for (int j = 0; j < kLoads; ++j) st[j * kWave + lane] = v[j];
+        for (int j = 0; j < kLoads; ++j) st[j * kWave + lane] = r.v[j];
         // one wave writes and reads its slot: its LDS operations execute in order and the compiler keeps
         // may-alias accesses in program order; the wave barrier only pins the schedule
         __builtin_amdgcn_wave_barrier();
-        float m[kPairU], m2[kPairU];
+        float acc = 0.f, acc2 = 0.f;
+        auto two = [&](uint2 e) {
+            float u0 = 0.f, u1 = 0.f;
+            const float t0 = pair_min(e.x, u0), t1 = pair_min(e.y, u1);
+            acc += t0 + t1;
+            if (DIAG) acc2 += u0 + u1;
+        };
+        const int g0 = __builtin_amdgcn_readlane(gbv.x, k), g1 = __builtin_amdgcn_readlane(gbv.y, k);
+        const int ng = g1 - g0;
 #pragma unroll
-        for (int k = 0; k < kPairU; ++k) {
-            float t2 = 0.f;
-            const float t = pair_min(e[k], t2);
-            const bool live = s0 + k * kWave + lane < s1;
-            m[k] = live ? t : 0.f;
-            m2[k] = live ? t2 : 0.f;
-        }
-#pragma unroll
-        for (int w = 1; w < kPairU; w <<= 1)  // the lane's few terms: pairwise in fp32, everything after in fp64
-#pragma unroll
-            for (int k = 0; k + w < kPairU; k += 2 * w) {
-                m[k] += m[k + w];
-                if (DIAG) m2[k] += m2[k + w];
-            }
-        double acc = (double)m[0], acc2 = (double)m2[0];
-        for (int i0 = s0 + kPairU * kWave; i0 < s1; i0 += kWave) {  // crowded chunk: the rest of its list
-            const int i = i0 + lane;
-            float t2 = 0.f;
-            const float t = pair_min(pl_e[min(i, S - 1)], t2);
-            acc += (double)(i < s1 ? t : 0.f);
-            if (DIAG) acc2 += (double)(i < s1 ? t2 : 0.f);
-        }
+        for (int k2 = 0; k2 < kPairU; ++k2)
+            if (k2 < ng) two(r.e[k2]);  // wave-uniform test
+        for (int g = g0 + kPairU; g < g1; ++g) two(pl_e[(int64_t)g * kWave + lane]);  // crowded chunk: the rest
         __builtin_amdgcn_wave_barrier();  // the slot is rewritten by the next chunk
-        acc = wave_sum_f64(acc);
-        if (lane == (it & (kWave - 1))) keep = acc;
+        // A chunk's sum is taken in fp32: a lane's dozen-odd terms in turn, the 64 lane totals on the DPP network
+        // (one instruction per step; a double takes five).  That is a relative 1e-7, the size of the exponential's
+        // own error; chunk sums are combined in fp64 downstream.
+        const float tot = wave_sum(acc);
+        if (lane == k) keep = (double)tot;
         if (DIAG) {
-            acc2 = wave_sum_f64(acc2);
-            if (lane == (it & (kWave - 1))) keep2 = acc2;
+            const float tot2 = wave_sum(acc2);
+            if (lane == k) keep2 = (double)tot2;
         }
-        ++it;
-        if ((it & (kWave - 1)) == 0) flush(it - kWave, kWave);  // only rows of more than 1024 chunks get here
+    };
+    int k = 0;
+    for (int idx = gw; idx < ncp; idx += 2 * stride, k += 2) {
+        fetch(k + 1, fb);
+        process(fa, k);
+        fetch(k + 2, fa);
+        if (idx + stride < ncp) process(fb, k + 1);
     }
-    flush(it & ~(kWave - 1), it & (kWave - 1));
+    {
+        const int idx = gw + lane * stride;
+        if (idx < ncp) {
+            my_mn[c_lo + idx] = keep;
+            if (DIAG) my_mn2[c_lo + idx] = keep2;
+        }
+    }
+    if (bt.bad()) fbad[b] = 1;
 }
 
 // kernel: draw the extra token of every sequence from its row's chunk tables.  grid (B), one wave.
@@ -1748,21 +1834,33 @@ struct tli_map {
     int32_t* d2r;    // dev [Vd]: rank of a shared drafter id, -1 otherwise   } the index of a token in a drafter row
     int32_t* t2r;    // dev [Vt padded to 8]: rank of a shared target id, -1   } stored in compact (rank-order) layout
     // Per dtype (index = tli_dtype), for the residual scan: the target chunks are cut into nparts parts (runs of
-    // whole chunks with at most part_cap shared pairs).  cb [nparts+1] first chunk of a part; st_start [nparts+1],
-    // st_x / st_r [S]: the pairs of a part in ascending drafter order, as drafter ids and as ranks (what one
-    // workgroup gathers into LDS, from a full or a compact drafter row); pl_start [nC+1], pl_e [S]: the pairs
-    // grouped by target chunk, entry = byte offset of the target id in its chunk | byte offset of the pair in its
-    // part's staging order << kPairShift.
-    int32_t nparts[2];
-    int32_t* cb[2];
-    int32_t* st_start[2];
-    int32_t* st_x[2];
-    int32_t* st_r[2];
-    int32_t* pl_start[2];
-    uint32_t* pl_e[2];
+    // whole chunks with at most part_cap shared pairs).  cb [nparts+1] first chunk of a part, part_n [nparts] its
+    // pairs.  Per drafter-row layout (0 full, 1 compact): NV vectors in a row (whole groups of 64); stab [nparts][NV]
+    // the staging table (which elements of a vector belong to the part, and where they go); grange [nparts] the groups that
+    // hold any; pl_e the pairs grouped by target chunk, a chunk's list padded to whole groups of kPairG, entry =
+    // byte offset of the target id in its chunk | index of the pair's staged logit << kPairShift (padding entries
+    // point at dummy_index; kPairU groups of padding close the list); pl_g [nC+1] first group of every chunk's
+    // list (the same for both layouts).
+    struct Scan {
+        int32_t nparts;
+        int32_t* cb;
+        int32_t* part_n;
+        int32_t* pl_g;
+        int32_t NV[2];
+        uint32_t* stab[2];
+        int2* grange[2];
+        uint2* pl_e[2];
+    } scan[2];
 };
 
 namespace {
+
+ScanLists scan_lists(const tli_map* m, int dt, int layout) {
+    const tli_map::Scan& sc = m->scan[dt];
+    return ScanLists{sc.nparts, layout ? m->S : m->Vd, sc.NV[layout], sc.cb, sc.part_n, sc.grange[layout],
+                     sc.stab[layout], sc.pl_g, sc.pl_e[layout]};
+}
+
 
 template <int DT, bool MASKED>
 void launch_draft(const void* logits, int64_t row_stride, int R, int V, float temp, const Plan& pl, float cs,
@@ -1913,12 +2011,11 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_SCAN, st);
-        const int nparts = a.map->nparts[DT];
+        const int nparts = a.map->scan[DT].nparts;
         // few sequences: deal the chunks of a (sequence, part) to several workgroups, up to one per CU
         int nsplit = 256 / (B * nparts);
         nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
-        const ScanLists ls{nparts, a.map->S, a.map->cb[DT], a.map->st_start[DT],
-                           a.compact ? a.map->st_r[DT] : a.map->st_x[DT], a.map->pl_start[DT], a.map->pl_e[DT]};
+        const ScanLists ls = scan_lists(a.map, DT, a.compact ? 1 : 0);
         hipLaunchKernelGGL((k_final_scan<DT, false>), dim3((unsigned)((B + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0,
                            st, a.logits_t, a.dv, B, K, Vt, Vd, a.pf.nC, nsplit, ls, a.cs_t, a.ratio_t, a.frow, a.tab_ref,
                            a.tab_s, a.mn, (double*)nullptr, a.fbad);
@@ -1978,10 +2075,10 @@ void launch_diag(const tli_map* map, const void* logits_t, const void* logits_d,
                        (float2*)nullptr);
     hipLaunchKernelGGL(k_diag_rows, dim3((rows + kWG - 1) / kWG), dim3(kWG), 0, st, part_t, pt.nsplit, part_q1, part_q2,
                        pd.nsplit, rows, K, ratio_t, ratio_d, c_t, c_d, frow, fbad, status);
-    const int nparts = map->nparts[DT];
+    const int nparts = map->scan[DT].nparts;
     int nsplit = 256 / (rows * nparts);
     nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
-    const ScanLists ls{nparts, map->S, map->cb[DT], map->st_start[DT], map->st_x[DT], map->pl_start[DT], map->pl_e[DT]};
+    const ScanLists ls = scan_lists(map, DT, 0);
     hipLaunchKernelGGL((k_final_scan<DT, true>), dim3((unsigned)((rows + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0, st,
                        logits_t, DrafterView{logits_d, (int64_t)Vd, nullptr, map->t2d}, rows, K, Vt, Vd, pt.nC, nsplit, ls,
                        cs_t, ratio_t, frow, (float*)nullptr, (float*)nullptr, mn, mn2, fbad);
@@ -2043,6 +2140,7 @@ void tli_profile_disable(void) {
     g_prof.mask = 0;
 }
 
+
 const char* tli_status_string(int status) {
     switch (status) {
         case TLI_OK: return "TLI_OK";
@@ -2080,13 +2178,19 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
         for (int32_t x = 0; x < Vd; ++x)
             if (d2t[x] >= 0) sh_x[r++] = x;
     }
-    std::vector<int32_t> pl_start[2], cb[2], st_start[2], st_x[2], st_r[2];
-    std::vector<uint32_t> pl_e[2];
-    int nparts[2];
+    struct HostScan {
+        std::vector<int32_t> cb, part_n, pl_g;
+        int NV[2];
+        std::vector<uint32_t> stab[2];
+        std::vector<int2> grange[2];
+        std::vector<uint2> pl_e[2];
+    } hs[2];
     for (int dt = 0; dt < 2; ++dt) {
+        HostScan& h = hs[dt];
         const int CH = dt == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
         const int cap = dt == TLI_BF16 ? part_cap<TLI_BF16>() : part_cap<TLI_F32>();
-        const int esz = dt == TLI_BF16 ? 2 : 4;
+        const int epv = dt == TLI_BF16 ? 8 : 4;
+        const uint32_t esz = dt == TLI_BF16 ? 2 : 4;
         const int nC = (Vt + CH - 1) / CH;
         // pairs per chunk, then parts: runs of whole chunks, filled evenly but never beyond what LDS holds
         std::vector<int32_t> cc(nC, 0);
@@ -2096,42 +2200,62 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
         int32_t biggest = 0;
         for (int c = 0; c < nC; ++c) biggest = cc[c] > biggest ? cc[c] : biggest;
         const int64_t limit = even + biggest < cap ? even + biggest : cap;
-        cb[dt].assign(1, 0);
+        h.cb.assign(1, 0);
         int64_t acc = 0;
         for (int c = 0; c < nC; ++c) {
-            if (acc > 0 && acc + cc[c] > limit) { cb[dt].push_back(c); acc = 0; }
+            if ((acc > 0 && acc + cc[c] > limit) || c - h.cb.back() >= kMaxPartChunks) { h.cb.push_back(c); acc = 0; }
             acc += cc[c];
         }
-        cb[dt].push_back(nC);
-        nparts[dt] = (int)cb[dt].size() - 1;
+        h.cb.push_back(nC);
+        const int nparts = (int)h.cb.size() - 1;
         std::vector<int32_t> part_of_chunk(nC);
-        for (int p = 0; p < nparts[dt]; ++p)
-            for (int c = cb[dt][p]; c < cb[dt][p + 1]; ++c) part_of_chunk[c] = p;
-        // staging order: the pairs of a part by ascending drafter id (ranks ascend with the drafter id)
-        st_start[dt].assign(nparts[dt] + 1, 0);
-        for (int c = 0; c < nC; ++c) st_start[dt][part_of_chunk[c] + 1] += cc[c];
-        for (int p = 0; p < nparts[dt]; ++p) st_start[dt][p + 1] += st_start[dt][p];
-        st_x[dt].resize(S);
-        st_r[dt].resize(S);
-        std::vector<int32_t> pos(S);  // place of pair (rank r) in its part's staging order
-        {
-            std::vector<int32_t> fill(st_start[dt].begin(), st_start[dt].end() - 1);
+        h.part_n.assign(nparts, 0);
+        for (int p = 0; p < nparts; ++p)
+            for (int c = h.cb[p]; c < h.cb[p + 1]; ++c) { part_of_chunk[c] = p; h.part_n[p] += cc[c]; }
+        h.pl_g.assign(nC + 1, 0);
+        for (int c = 0; c < nC; ++c) h.pl_g[c + 1] = h.pl_g[c] + (cc[c] + kPairG - 1) / kPairG;
+        for (int layout = 0; layout < 2; ++layout) {
+            // staging table: what the sweep over a drafter row (element index = drafter id in the full layout,
+            // rank in the compact one) keeps of every vector for a part, and where it puts it
+            const int64_t elems = layout ? S : Vd;
+            const int NV = (int)(((elems + epv - 1) / epv + kWave - 1) / kWave) * kWave;
+            h.NV[layout] = NV;
+            h.stab[layout].assign((size_t)nparts * NV, 0);
+            h.grange[layout].assign(nparts, make_int2(NV / kWave, 0));
             for (int32_t r = 0; r < S; ++r) {
+                const int64_t x = layout ? r : sh_x[r];
                 const int p = part_of_chunk[d2t[sh_x[r]] / CH];
-                pos[r] = fill[p] - st_start[dt][p];
-                st_x[dt][fill[p]] = sh_x[r];
-                st_r[dt][fill[p]] = r;
-                ++fill[p];
+                h.stab[layout][(size_t)p * NV + x / epv] |= 1u << (16 + x % epv);
+                const int g = (int)(x / epv / kWave);
+                if (g < h.grange[layout][p].x) h.grange[layout][p].x = g;
+                if (g + 1 > h.grange[layout][p].y) h.grange[layout][p].y = g + 1;
             }
-        }
-        // pairs grouped by target chunk (ranks ascending inside a chunk)
-        pl_start[dt].assign(nC + 1, 0);
-        for (int c = 0; c < nC; ++c) pl_start[dt][c + 1] = pl_start[dt][c] + cc[c];
-        pl_e[dt].resize(S);
-        std::vector<int32_t> fill(pl_start[dt].begin(), pl_start[dt].end() - 1);
-        for (int32_t r = 0; r < S; ++r) {
-            const int32_t t = d2t[sh_x[r]];
-            pl_e[dt][fill[t / CH]++] = (uint32_t)((t % CH) * esz) | ((uint32_t)(pos[r] * esz) << kPairShift);
+            for (int p = 0; p < nparts; ++p) {
+                if (h.grange[layout][p].y == 0) h.grange[layout][p] = make_int2(0, 0);  // a part without pairs
+                uint32_t run = 0;
+                for (int vi = 0; vi < NV; ++vi) {
+                    uint32_t& w = h.stab[layout][(size_t)p * NV + vi];
+                    const uint32_t cnt = (uint32_t)__builtin_popcount(w >> 16);
+                    w |= cnt ? run : 0;  // vectors that keep nothing never use the index
+                    run += cnt;
+                }
+            }
+            // pairs grouped by target chunk (ranks ascending inside a chunk): entry n of a chunk's list sits in
+            // group n / kPairG, lane n % 64, first or second of the lane's two by (n % kPairG) / 64
+            const uint32_t dummy = (uint32_t)(dt == TLI_BF16 ? dummy_index<TLI_BF16>() : dummy_index<TLI_F32>()) << kPairShift;
+            h.pl_e[layout].assign(((size_t)h.pl_g[nC] + kPairU) * kWave, make_uint2(dummy, dummy));
+            std::vector<int32_t> nth(nC, 0);
+            for (int32_t r = 0; r < S; ++r) {
+                const int64_t x = layout ? r : sh_x[r];
+                const int32_t t = d2t[sh_x[r]];
+                const int c = t / CH, p = part_of_chunk[c];
+                const uint32_t w = h.stab[layout][(size_t)p * NV + x / epv];
+                const uint32_t pos = (w & 0xffffu) + (uint32_t)__builtin_popcount((w >> 16) & ((1u << (x % epv)) - 1u));
+                const uint32_t e = (uint32_t)(t % CH) * esz | (pos << kPairShift);
+                const int n = nth[c]++;
+                uint2& slot = h.pl_e[layout][((size_t)h.pl_g[c] + n / kPairG) * kWave + n % kWave];
+                if ((n % kPairG) / kWave == 0) slot.x = e; else slot.y = e;
+            }
         }
     }
     // shared-id mask of the drafter vocabulary in lane-mask layout (see mask_bits), padded to whole chunks
@@ -2152,8 +2276,13 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
     m->Vd = Vd; m->Vt = Vt; m->S = S; m->d2t = nullptr; m->t2d = nullptr; m->lmask[0] = m->lmask[1] = nullptr;
     m->sh_x = nullptr; m->d2r = nullptr; m->t2r = nullptr;
     for (int dt = 0; dt < 2; ++dt) {
-        m->nparts[dt] = nparts[dt]; m->pl_start[dt] = nullptr; m->pl_e[dt] = nullptr;
-        m->cb[dt] = nullptr; m->st_start[dt] = nullptr; m->st_x[dt] = nullptr; m->st_r[dt] = nullptr;
+        tli_map::Scan& sc = m->scan[dt];
+        sc.nparts = (int32_t)hs[dt].part_n.size();
+        sc.cb = sc.part_n = sc.pl_g = nullptr;
+        for (int layout = 0; layout < 2; ++layout) {
+            sc.NV[layout] = hs[dt].NV[layout];
+            sc.stab[layout] = nullptr; sc.grange[layout] = nullptr; sc.pl_e[layout] = nullptr;
+        }
     }
     if (hipGetDevice(&m->device) != hipSuccess) { delete m; return TLI_ERR_HIP; }
     bool ok = hipMalloc(&m->d2t, d2t.size() * 4) == hipSuccess && hipMalloc(&m->t2d, t2d.size() * 4) == hipSuccess &&
@@ -2179,21 +2308,23 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
         return TLI_ERR_HIP;
     }
     for (int dt = 0; dt < 2; ++dt) {
-        ok = hipMalloc(&m->pl_start[dt], pl_start[dt].size() * 4) == hipSuccess &&
-             hipMalloc(&m->pl_e[dt], (size_t)S * 4) == hipSuccess &&
-             hipMalloc(&m->cb[dt], cb[dt].size() * 4) == hipSuccess &&
-             hipMalloc(&m->st_start[dt], st_start[dt].size() * 4) == hipSuccess &&
-             hipMalloc(&m->st_x[dt], (size_t)S * 4) == hipSuccess && hipMalloc(&m->st_r[dt], (size_t)S * 4) == hipSuccess;
-        if (!ok) { tli_free_map(m); return TLI_ERR_ALLOC; }
-        ok = hipMemcpy(m->pl_start[dt], pl_start[dt].data(), pl_start[dt].size() * 4, hipMemcpyHostToDevice) ==
-                 hipSuccess &&
-             hipMemcpy(m->pl_e[dt], pl_e[dt].data(), (size_t)S * 4, hipMemcpyHostToDevice) == hipSuccess &&
-             hipMemcpy(m->cb[dt], cb[dt].data(), cb[dt].size() * 4, hipMemcpyHostToDevice) == hipSuccess &&
-             hipMemcpy(m->st_start[dt], st_start[dt].data(), st_start[dt].size() * 4, hipMemcpyHostToDevice) ==
-                 hipSuccess &&
-             hipMemcpy(m->st_x[dt], st_x[dt].data(), (size_t)S * 4, hipMemcpyHostToDevice) == hipSuccess &&
-             hipMemcpy(m->st_r[dt], st_r[dt].data(), (size_t)S * 4, hipMemcpyHostToDevice) == hipSuccess;
-        if (!ok) { tli_free_map(m); return TLI_ERR_HIP; }
+        tli_map::Scan& sc = m->scan[dt];
+        const HostScan& h = hs[dt];
+        const struct { void** dev; const void* host; size_t bytes; } lists[] = {
+            {(void**)&sc.cb, h.cb.data(), h.cb.size() * 4},
+            {(void**)&sc.part_n, h.part_n.data(), h.part_n.size() * 4},
+            {(void**)&sc.pl_g, h.pl_g.data(), h.pl_g.size() * 4},
+            {(void**)&sc.stab[0], h.stab[0].data(), h.stab[0].size() * 4},
+            {(void**)&sc.stab[1], h.stab[1].data(), h.stab[1].size() * 4},
+            {(void**)&sc.grange[0], h.grange[0].data(), h.grange[0].size() * sizeof(int2)},
+            {(void**)&sc.grange[1], h.grange[1].data(), h.grange[1].size() * sizeof(int2)},
+            {(void**)&sc.pl_e[0], h.pl_e[0].data(), h.pl_e[0].size() * sizeof(uint2)},
+            {(void**)&sc.pl_e[1], h.pl_e[1].data(), h.pl_e[1].size() * sizeof(uint2)},
+        };
+        for (const auto& l : lists) {
+            if (hipMalloc(l.dev, l.bytes) != hipSuccess) { tli_free_map(m); return TLI_ERR_ALLOC; }
+            if (hipMemcpy(*l.dev, l.host, l.bytes, hipMemcpyHostToDevice) != hipSuccess) { tli_free_map(m); return TLI_ERR_HIP; }
+        }
     }
     *out_map = m;
     if (out_num_shared) *out_num_shared = S;
@@ -2210,12 +2341,11 @@ void tli_free_map(tli_map* m) {
     if (m->d2r) (void)hipFree(m->d2r);
     if (m->t2r) (void)hipFree(m->t2r);
     for (int dt = 0; dt < 2; ++dt) {
-        if (m->pl_start[dt]) (void)hipFree(m->pl_start[dt]);
-        if (m->pl_e[dt]) (void)hipFree(m->pl_e[dt]);
-        if (m->cb[dt]) (void)hipFree(m->cb[dt]);
-        if (m->st_start[dt]) (void)hipFree(m->st_start[dt]);
-        if (m->st_x[dt]) (void)hipFree(m->st_x[dt]);
-        if (m->st_r[dt]) (void)hipFree(m->st_r[dt]);
+        tli_map::Scan& sc = m->scan[dt];
+        void* const owned[] = {sc.cb, sc.part_n, sc.pl_g, sc.stab[0], sc.stab[1], sc.grange[0], sc.grange[1],
+                               sc.pl_e[0], sc.pl_e[1]};
+        for (void* q : owned)
+            if (q) (void)hipFree(q);
     }
     delete m;
 }
