@@ -416,10 +416,53 @@ __device__ __forceinline__ int wave_max_int(int v) {
 // Returns the first chunk whose inclusive prefix exceeds theta = u * total, with theta - (prefix before
 // it) in *theta_local; if rounding leaves no crossing, the last chunk with mass and +inf; -1 if the
 // total is not positive (zero, negative or NaN).  All results are wave-uniform.
+// P = chunks per lane held in registers: every mass is evaluated once, and a lane's loads (the chunk tables are in
+// memory for some callers) are all issued before the first is used -- one round trip instead of one per chunk
+// and pass.
+template <int P, class MassFn>
+__device__ __forceinline__ int find_chunk_p(int nC, int per, double u, MassFn mass, double* theta_local,
+                                            double* total_out) {
+    const int lane = threadIdx.x & 63;
+    const int c0 = min(nC, lane * per), c1 = min(nC, c0 + per);
+    double m[P];
+    double mine = 0.0;
+#pragma unroll
+    for (int k = 0; k < P; ++k) {  // past the lane's range: some valid chunk is evaluated and dropped
+        const double t = mass(min(c0 + k, nC - 1));
+        m[k] = c0 + k < c1 ? t : 0.0;
+    }
+#pragma unroll
+    for (int k = 0; k < P; ++k) mine += m[k];
+    double total;
+    const double excl = wave_excl_scan(mine, &total);
+    *total_out = total;
+    if (!(total > 0.0)) return -1;
+    const double theta = u * total;
+    double run = excl, before = 0.0;
+    int found = -1, last_pos = -1;
+#pragma unroll
+    for (int k = 0; k < P; ++k) {
+        const double t = m[k];
+        if (t > 0.0) last_pos = c0 + k;
+        if (found < 0 && c0 + k < c1 && run + t > theta) { found = c0 + k; before = run; }
+        run += t;
+    }
+    const unsigned long long hit = __ballot(found >= 0);
+    if (hit == 0ull) {
+        *theta_local = INFINITY;
+        return wave_max_int(last_pos);
+    }
+    const int src = (int)__builtin_ctzll(hit);  // lanes own ascending chunk ranges: lowest lane = first chunk
+    *theta_local = theta - __shfl(before, src, kWave);
+    return __shfl(found, src, kWave);
+}
+
 template <class MassFn>
 __device__ __forceinline__ int find_chunk(int nC, double u, MassFn mass, double* theta_local, double* total_out) {
     const int lane = threadIdx.x & 63;
     const int per = (nC + kWave - 1) / kWave;
+    if (per <= 2) return find_chunk_p<2>(nC, per, u, mass, theta_local, total_out);
+    if (per <= 4) return find_chunk_p<4>(nC, per, u, mass, theta_local, total_out);
     const int c0 = min(nC, lane * per), c1 = min(nC, c0 + per);
     double mine = 0.0;
     for (int c = c0; c < c1; ++c) mine += mass(c);
