@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel as read by rocprofv3 (FETCH_SIZE + WRITE_SIZE, each scaled by
 # what the same counter reads for the library's plain copy kernel); from profiles/*_hbm_traffic_pmc.md.
 # Counters cannot be read from inside this process, so the figure is carried here per workload.
-MEASURED_TRAFFIC_BYTES = {"large_vocab": 1048.59e6 + 2.16e6}
+MEASURED_TRAFFIC_BYTES = {"large_vocab": 1048.65e6 + 2.16e6}
 
 
 def parse():
