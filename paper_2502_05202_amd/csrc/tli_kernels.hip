@@ -311,33 +311,50 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const double kd = (ratio - 1.0) * kLn2;
+    // The (ref, s) of every chunk is parked in LDS (no global store sits between the streaming loads, and the
+    // running total is not advanced per chunk: that is a dozen fp64 instructions which every lane would
+    // execute for a wave-uniform value); the partial is reduced from there when the row is through.  The pairs
+    // are also what the residual of a rejected row takes its chunk sums of p from (ctab).
     __shared__ float2 stash[kLdsChunks];
-    Running run;
+    Running over;  // chunks beyond what LDS parks (rows of more than kLdsChunks chunks per workgroup)
     scan_chunks<DT, MASKED, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, (float)(ratio - 1.0), bits,
                                     [&](int c, float r, float sc) {
-                                        run.add(r, sc, kd);
-                                        // per-chunk pairs are kept too (the residual of a rejected row takes the
-                                        // chunk sums of p from here instead of re-summing the row); parked in LDS
-                                        // so that no global store sits between the streaming loads
-                                        if (ctab && lane == 0) {
-                                            const int i = c - split * cps;
-                                            if (i < kLdsChunks) stash[i] = make_float2(r, sc);
-                                            else ctab[(int64_t)row * nC + c] = make_float2(r, sc);
+                                        const int i = c - split * cps;
+                                        if (i < kLdsChunks) {
+                                            if (lane == 0) stash[i] = make_float2(r, sc);
+                                        } else {
+                                            over.add(r, sc, kd);
+                                            if (ctab && lane == 0) ctab[(int64_t)row * nC + c] = make_float2(r, sc);
                                         }
                                     });
     __shared__ float sref[kWaves];
     __shared__ double ssum[kWaves];
-    if (lane == 0) { sref[wave] = run.ref; ssum[wave] = run.s; }
     __syncthreads();
-    if (ctab) {
-        const int n_here = min(min(nC, (split + 1) * cps) - split * cps, kLdsChunks);
-        for (int i = threadIdx.x; i < n_here; i += kWG) ctab[(int64_t)row * nC + split * cps + i] = stash[i];
+    const int n_here = min(min(nC, (split + 1) * cps) - split * cps, kLdsChunks);
+    float r_mine = over.ref;
+    for (int i = threadIdx.x; i < n_here; i += kWG) {
+        const float2 e = stash[i];
+        r_mine = fmaxf(r_mine, e.x);
+        if (ctab) ctab[(int64_t)row * nC + split * cps + i] = e;
     }
+    r_mine = wave_max(r_mine);
+    if (lane == 0) sref[wave] = r_mine;
+    __syncthreads();
+    float R = sref[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) R = fmaxf(R, sref[w]);
+    double s_mine = lane == 0 ? over.s * exp2_diff(over.ref, R, kd) : 0.0;  // a wave's overflow total counts once
+    for (int i = threadIdx.x; i < n_here; i += kWG) {
+        const float2 e = stash[i];
+        s_mine += (double)e.y * exp2_diff(e.x, R, kd);
+    }
+    s_mine = wave_sum_f64(s_mine);
+    if (lane == 0) ssum[wave] = s_mine;
+    __syncthreads();
     if (threadIdx.x == 0) {
-        float R = sref[0];
-        for (int w = 1; w < kWaves; ++w) R = fmaxf(R, sref[w]);
         double S = 0.0;
-        for (int w = 0; w < kWaves; ++w) S += ssum[w] * exp2_diff(sref[w], R, kd);
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) S += ssum[w];
         Part p; p.ref = R; p.pad = 0.f; p.s = S;
         part[(int64_t)row * nsplit + split] = p;
     }
