@@ -68,6 +68,10 @@ RAGGED = [
     # more shared ids than one workgroup holds in LDS: the residual scan runs in 3 (fp32) / 2 (bf16) parts
     (70000, 60000, 50000, "f32", 2, 2, 1.0, 0.9),
     (2048 * 30 + 16, 2048 * 27 + 8, 50000, "bf16", 3, 2, 0.9, 1.1),
+    # rows of more than 1024 chunks: the normaliser kernel's LDS table overflows, and the residual scan's parts are
+    # cut by their chunk count (the second part of the fp32 case holds few pairs, a third may hold none)
+    (1024 * 1100 + 12, 3000, 2000, "f32", 2, 2, 1.0, 1.0),
+    (2048 * 1030 + 8, 2048 * 2 + 8, 4000, "bf16", 2, 1, 0.8, 0.9),
 ]
 
 
