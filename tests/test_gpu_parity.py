@@ -83,6 +83,28 @@ def test_ragged_sizes(oracle, case):
     _check(parity.run_case(oracle, inp))
 
 
+def _random_shape(i):
+    rng = np.random.default_rng(1000 + i)
+    dtype = "bf16" if rng.random() < 0.6 else "f32"
+    epv = 8 if dtype == "bf16" else 4
+    Vt, Vd = int(rng.integers(1, 40000)) * epv, int(rng.integers(1, 30000)) * epv
+    if rng.random() < 0.3:
+        Vt, Vd = Vd, Vt
+    S = min(Vt, Vd) if rng.random() < 0.3 else int(rng.integers(1, min(Vt, Vd) + 1))  # dense maps now and then
+    kind = (3, 4, 5)[int(rng.integers(0, 3))]
+    return synth.WORKLOADS[kind].scaled(Vt=Vt, Vd=Vd, S=S, dtype=dtype, B=int(rng.integers(1, 9)), K=int(rng.integers(1, 7)),
+                                        tau_t=float(rng.uniform(0.3, 1.5)), tau_d=float(rng.uniform(0.3, 1.5)), cfg=100 + i)
+
+
+@pytest.mark.parametrize("i", range(16))
+def test_random_shapes(oracle, i):
+    """Seeded random vocabulary sizes, overlaps (sparse to identical), storage types, temperatures and logit
+    recipes: one to several residual-scan parts, crowded and empty chunks, both row layouts of the map."""
+    w = _random_shape(i)
+    print(w)
+    _check(parity.run_case(oracle, synth.make_inputs(w, DEV), threads=8))
+
+
 def test_max_lookahead_and_zipf(oracle):
     w = synth.WORKLOADS[5].scaled(Vt=4096 + 64, Vd=2048 + 24, S=900, B=3, K=64)
     _check(parity.run_case(oracle, synth.make_inputs(w, DEV)))
