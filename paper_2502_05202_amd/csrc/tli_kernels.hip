@@ -859,12 +859,14 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
                                                const FinalOut& o) {
     constexpr int EPV = Traits<DT>::EPV;
     const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const char* rowp = static_cast<const char*>(logits_t) + (int64_t)f.t_row * Vt * Traits<DT>::ESZ;
     const double u = (double)o.u_fin[b];
     int tok = -1;
     int add_flags = 0;
     bool nonfinite = false;
     if (f.bonus) {
+        if (wave != 0) return;  // a bonus row is drawn by one wave, like a drafter row
         float M;
         double total;
         tok = sample_softmax_row<DT, false>(rowp, Vt, nC, cs_t, ratio_t, nullptr, tr, ts, u, &M, &total);
@@ -903,23 +905,50 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
             }
         }
         if (!nonfinite) {
-            float p[kLoads][EPV], w[kLoads][EPV];
+            // The chunk's 2048 ids, in id order: load j = 0..3, then lane, then element.  Wave j of the workgroup
+            // takes load j (a quarter of the table look-ups, gathers and exponentials each); the prefix over
+            // the loads is formed in the order a single wave would form it, so the draw does not depend on
+            // how many waves share it.
+            __shared__ double s_tot[kLoads];
+            __shared__ int s_found[kLoads], s_last[kLoads];
+            const int j = wave;  // kLoads waves
+            const int64_t vi = ((int64_t)c * kLoads + j) * kWave + lane;
+            float p[EPV], w[EPV];
+            residual_vec<DT>(rowp, vi, Vt, f.rp, t2d, ldp, p, w);
+            double wd[EPV];
+            double mine = 0.0;
 #pragma unroll
-            for (int j = 0; j < kLoads; ++j)
-                residual_vec<DT>(rowp, ((int64_t)c * kLoads + j) * kWave + lane, Vt, f.rp, t2d, ldp, p[j], w[j]);
-            ChunkWalk st;
-#pragma unroll
-            for (int j = 0; j < kLoads; ++j) {
-                const int64_t vi = ((int64_t)c * kLoads + j) * kWave + lane;
-                double wd[EPV];
-#pragma unroll
-                for (int i = 0; i < EPV; ++i) wd[i] = degenerate ? (double)p[j][i] : (double)w[j][i];
-                if (walk_vector<EPV>(st, wd, vi * EPV, theta_local)) break;
+            for (int i = 0; i < EPV; ++i) {
+                wd[i] = degenerate ? (double)p[i] : (double)w[i];
+                mine += wd[i];
             }
-            tok = walk_result(st);
+            double tot;
+            const double excl = wave_excl_scan(mine, &tot);
+            if (lane == 0) s_tot[j] = tot;
+            __syncthreads();
+            double base = 0.0;
+            for (int q = 0; q < j; ++q) base += s_tot[q];
+            double run = base + excl;
+            int fnd = -1, last_pos = -1;
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) {
+                run += wd[i];
+                if (wd[i] > 0.0) last_pos = (int)(vi * EPV + i);
+                if (fnd < 0 && run > theta_local) fnd = (int)(vi * EPV + i);
+            }
+            const unsigned long long hit = __ballot(fnd >= 0);
+            const int first = hit ? __shfl(fnd, (int)__builtin_ctzll(hit), kWave) : -1;
+            const int last = wave_max_int(last_pos);
+            if (lane == 0) { s_found[j] = first; s_last[j] = last; }
+            __syncthreads();
+            tok = -1;
+            for (int q = kLoads - 1; q >= 0; --q)
+                if (s_found[q] >= 0) tok = s_found[q];  // the first load with a crossing
+            if (tok < 0)  // no crossing: last id with weight > 0
+                for (int q = 0; q < kLoads; ++q) tok = max(tok, s_last[q]);
         }
     }
-    if (lane == 0) {
+    if (threadIdx.x == 0) {
         if (nonfinite) {
             o.n_accepted[b] = 0;
             for (int k = 0; k <= K; ++k) o.out_tok[(int64_t)b * (K + 1) + k] = -1;
@@ -1245,9 +1274,10 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     if (bt.bad()) fbad[b] = 1;
 }
 
-// kernel: draw the extra token of every sequence from its row's chunk tables.  grid (B), one wave.
+// kernel: draw the extra token of every sequence from its row's chunk tables.  grid (B), kLoads waves: every wave
+// finds the chunk for itself (the tables are small and shared), then each takes a quarter of the chunk.
 template <int DT>
-__global__ __launch_bounds__(kWave) void k_final_pick(const void* __restrict__ logits_t, DrafterView dv,
+__global__ __launch_bounds__(kLoads * kWave) void k_final_pick(const void* __restrict__ logits_t, DrafterView dv,
                                                        int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
                                                        const FinalRow* __restrict__ frow,
                                                        const int32_t* __restrict__ t2d,
@@ -2082,7 +2112,7 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
-        hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.dv, K, Vt, Vd, a.pf.nC,
+        hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kLoads * kWave), 0, st, a.logits_t, a.dv, K, Vt, Vd, a.pf.nC,
                            a.cs_t, a.ratio_t, a.frow, a.dv.t2x, a.tab_ref, a.tab_s, a.ctab, a.mn, a.fbad, fo);
     }
 }
