@@ -506,36 +506,45 @@ __device__ __forceinline__ int find_chunk(int nC, double u, MassFn mass, double*
     return __shfl(found, src, kWave);
 }
 
-// In-chunk search state: vectors are visited in id order (load j = 0..3, then lane, then element).
-struct ChunkWalk {
-    double base = 0.0;   // mass of the vectors already visited
-    int found = -1;      // first id whose inclusive prefix exceeds theta_local (uniform once set)
-    int last_pos = -1;   // per lane: last id with positive weight seen so far
-};
-
-// feed the weights of this lane's vector (ids e0 .. e0+N-1) of load j; returns true when found
+// In-chunk search by the kLoads waves of a workgroup.  The chunk's ids are taken in id order: load j = 0..3, then
+// lane, then element; wave j holds load j, `w` = the weights of this lane's vector (ids e0 .. e0+N-1).  Returns
+// (to every thread) the first id whose inclusive prefix exceeds theta_local, or, if rounding leaves no
+// crossing, the last id with a positive weight (-1 if there is none).  The prefix over the loads is added up in
+// load order, as one wave walking the four loads in turn would.  Every wave of the workgroup must call it.
 template <int N>
-__device__ __forceinline__ bool walk_vector(ChunkWalk& st, const double (&w)[N], int64_t e0, double theta_local) {
+__device__ __forceinline__ int chunk_draw(const double (&w)[N], int64_t e0, double theta_local) {
+    __shared__ double s_tot[kLoads];
+    __shared__ int s_found[kLoads], s_last[kLoads];
+    const int lane = threadIdx.x & 63;
+    const int j = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     double mine = 0.0;
 #pragma unroll
     for (int i = 0; i < N; ++i) mine += w[i];
     double tot;
-    double run = st.base + wave_excl_scan(mine, &tot);
-    int f = -1;
+    const double excl = wave_excl_scan(mine, &tot);
+    if (lane == 0) s_tot[j] = tot;
+    __syncthreads();
+    double base = 0.0;
+    for (int q = 0; q < j; ++q) base += s_tot[q];
+    double run = base + excl;
+    int f = -1, last_pos = -1;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         run += w[i];
-        if (w[i] > 0.0) st.last_pos = (int)(e0 + i);
+        if (w[i] > 0.0) last_pos = (int)(e0 + i);
         if (f < 0 && run > theta_local) f = (int)(e0 + i);
     }
-    st.base += tot;
     const unsigned long long hit = __ballot(f >= 0);
-    if (hit == 0ull) return false;
-    st.found = __shfl(f, (int)__builtin_ctzll(hit), kWave);
-    return true;
-}
-__device__ __forceinline__ int walk_result(const ChunkWalk& st) {
-    return st.found >= 0 ? st.found : wave_max_int(st.last_pos);  // no crossing: last id with weight > 0
+    const int first = hit ? __shfl(f, (int)__builtin_ctzll(hit), kWave) : -1;
+    const int last = wave_max_int(last_pos);
+    if (lane == 0) { s_found[j] = first; s_last[j] = last; }
+    __syncthreads();
+    int tok = -1;
+    for (int q = kLoads - 1; q >= 0; --q)
+        if (s_found[q] >= 0) tok = s_found[q];  // the first load with a crossing
+    if (tok < 0)
+        for (int q = 0; q < kLoads; ++q) tok = max(tok, s_last[q]);
+    return tok;
 }
 
 // weights of one 16-byte vector of a softmax row relative to reference `nref` (= -ref), as in
@@ -559,8 +568,10 @@ __device__ __forceinline__ void softmax_vec_weights(const uint4* rowv, int64_t v
     }
 }
 
-// Inverse-CDF sample of a (masked) softmax row from its chunk table, by one wave.  Returns the id, or
-// -1 if the row has no usable mass (then *total_out is NaN for a NaN/+inf logit, else 0).
+// Inverse-CDF sample of a (masked) softmax row from its chunk table, by the kLoads waves of a workgroup: every
+// wave finds the chunk for itself (the table is small), then each takes one of the chunk's loads.  Returns the
+// id, or -1 if the row has no usable mass (then *total_out is NaN for a NaN/+inf logit, else 0).  Every wave of
+// the workgroup must call it, with the same arguments.
 template <int DT, bool MASKED>
 __device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int nC, float cs, double ratio,
                                                   const uint64_t* bits,
@@ -568,6 +579,7 @@ __device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int n
                                                   double* total_out) {
     constexpr int EPV = Traits<DT>::EPV;
     const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     float m = -INFINITY;
     for (int c = lane; c < nC; c += kWave) m = fmaxf(m, tr[c]);
     const float M = wave_max(m);
@@ -580,15 +592,10 @@ __device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int n
         if (M == INFINITY) *total_out = NAN;
         return -1;
     }
-    ChunkWalk st;
-#pragma unroll 1
-    for (int j = 0; j < kLoads; ++j) {
-        const int64_t vi = ((int64_t)c * kLoads + j) * kWave + lane;
-        double w[EPV];
-        softmax_vec_weights<DT, MASKED>(static_cast<const uint4*>(rowp), vi, V, cs, -M, bits, w);
-        if (walk_vector<EPV>(st, w, vi * EPV, theta_local)) break;
-    }
-    return walk_result(st);
+    const int64_t vi = ((int64_t)c * kLoads + wave) * kWave + lane;
+    double w[EPV];
+    softmax_vec_weights<DT, MASKED>(static_cast<const uint4*>(rowp), vi, V, cs, -M, bits, w);
+    return chunk_draw<EPV>(w, vi * EPV, theta_local);
 }
 
 // ---- draft token of one drafter row from its chunk table ----------------------------------------
@@ -613,7 +620,7 @@ __device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V,
     double total;
     const int64_t at = (int64_t)row * o.stride;
     const int d = sample_softmax_row<DT, MASKED>(rowp, V, nC, cs, c_ratio, bits, tr, ts, (double)o.u_draft[at], &M, &total);
-    if ((threadIdx.x & 63) != 0) return;
+    if (threadIdx.x != 0) return;
     if (d < 0) {  // no usable mass: NaN/+inf among the logits that take part, or all of them -inf
         const bool nonfinite = (total != total);
         o.tok_d[at] = -1;
@@ -632,9 +639,9 @@ __device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V,
     o.row_status[at] = 0;
 }
 
-// kernel: sampler of the split path (rows cut over several workgroups by k_draft_scan).  grid (R), one wave.
+// kernel: sampler of the split path (rows cut over several workgroups by k_draft_scan).  grid (R), kLoads waves.
 template <int DT, bool MASKED>
-__global__ __launch_bounds__(kWave) void k_draft_pick(const void* __restrict__ logits, int64_t row_stride, int V,
+__global__ __launch_bounds__(kLoads * kWave) void k_draft_pick(const void* __restrict__ logits, int64_t row_stride, int V,
                                                      int nC, float cs, double c_ratio, double inv_temp,
                                                      const uint64_t* __restrict__ bits,
                                                      const int32_t* __restrict__ d2t,
@@ -647,7 +654,7 @@ __global__ __launch_bounds__(kWave) void k_draft_pick(const void* __restrict__ l
 }
 
 // kernel: one workgroup per drafter row scans it into a chunk table in LDS and samples from it at
-// once (by its first wave), while the other workgroups on the CU keep streaming their rows.
+// once, while the other workgroups on the CU keep streaming their rows.
 // grid (R); nC <= kLdsChunks.
 template <int DT, bool MASKED>
 __global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ logits, int64_t row_stride, int V,
@@ -659,7 +666,6 @@ __global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ lo
     const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
     table_scan<DT, MASKED>(reinterpret_cast<const u4v*>(rowp), 0, V, nC, nC, cs, c_ratio, bits, tr, ts);
     __syncthreads();
-    if (threadIdx.x >= kWave) return;  // the first wave samples; the others retire and free their slots
     draft_pick_row<DT, MASKED>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tr, ts, o);
 }
 
@@ -866,13 +872,12 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
     int add_flags = 0;
     bool nonfinite = false;
     if (f.bonus) {
-        if (wave != 0) return;  // a bonus row is drawn by one wave, like a drafter row
         float M;
         double total;
         tok = sample_softmax_row<DT, false>(rowp, Vt, nC, cs_t, ratio_t, nullptr, tr, ts, u, &M, &total);
         // no usable mass: NaN/+inf, or a bonus row of only -inf -- no distribution to sample either way
         if (tok < 0) nonfinite = true;
-        else if (lane == 0 && o.lse_p) o.lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
+        else if (threadIdx.x == 0 && o.lse_p) o.lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
     } else {
         const char* ldp = static_cast<const char*>(dv.base) + (int64_t)f.d_row * dv.row_stride * Traits<DT>::ESZ;
         // chunk masses: sum_chunk p (from the normaliser kernel's table of row n) minus the parts' sums of min(p, q')
@@ -905,47 +910,15 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
             }
         }
         if (!nonfinite) {
-            // The chunk's 2048 ids, in id order: load j = 0..3, then lane, then element.  Wave j of the workgroup
-            // takes load j (a quarter of the table look-ups, gathers and exponentials each); the prefix over
-            // the loads is formed in the order a single wave would form it, so the draw does not depend on
-            // how many waves share it.
-            __shared__ double s_tot[kLoads];
-            __shared__ int s_found[kLoads], s_last[kLoads];
-            const int j = wave;  // kLoads waves
-            const int64_t vi = ((int64_t)c * kLoads + j) * kWave + lane;
+            // wave j of the workgroup takes load j of the chunk: a quarter of the table look-ups, gathers and
+            // exponentials each
+            const int64_t vi = ((int64_t)c * kLoads + wave) * kWave + lane;
             float p[EPV], w[EPV];
             residual_vec<DT>(rowp, vi, Vt, f.rp, t2d, ldp, p, w);
             double wd[EPV];
-            double mine = 0.0;
 #pragma unroll
-            for (int i = 0; i < EPV; ++i) {
-                wd[i] = degenerate ? (double)p[i] : (double)w[i];
-                mine += wd[i];
-            }
-            double tot;
-            const double excl = wave_excl_scan(mine, &tot);
-            if (lane == 0) s_tot[j] = tot;
-            __syncthreads();
-            double base = 0.0;
-            for (int q = 0; q < j; ++q) base += s_tot[q];
-            double run = base + excl;
-            int fnd = -1, last_pos = -1;
-#pragma unroll
-            for (int i = 0; i < EPV; ++i) {
-                run += wd[i];
-                if (wd[i] > 0.0) last_pos = (int)(vi * EPV + i);
-                if (fnd < 0 && run > theta_local) fnd = (int)(vi * EPV + i);
-            }
-            const unsigned long long hit = __ballot(fnd >= 0);
-            const int first = hit ? __shfl(fnd, (int)__builtin_ctzll(hit), kWave) : -1;
-            const int last = wave_max_int(last_pos);
-            if (lane == 0) { s_found[j] = first; s_last[j] = last; }
-            __syncthreads();
-            tok = -1;
-            for (int q = kLoads - 1; q >= 0; --q)
-                if (s_found[q] >= 0) tok = s_found[q];  // the first load with a crossing
-            if (tok < 0)  // no crossing: last id with weight > 0
-                for (int q = 0; q < kLoads; ++q) tok = max(tok, s_last[q]);
+            for (int i = 0; i < EPV; ++i) wd[i] = degenerate ? (double)p[i] : (double)w[i];
+            tok = chunk_draw<EPV>(wd, vi * EPV, theta_local);
         }
     }
     if (threadIdx.x == 0) {
@@ -1970,7 +1943,7 @@ void launch_draft(const void* logits, int64_t row_stride, int R, int V, float te
     }
     {
         KernelTimer t(TLI_KERNEL_DRAFT_PICK, st);
-        hipLaunchKernelGGL((k_draft_pick<DT, MASKED>), dim3(R), dim3(kWave), 0, st, logits, row_stride, V, pl.nC, cs, ratio,
+        hipLaunchKernelGGL((k_draft_pick<DT, MASKED>), dim3(R), dim3(kLoads * kWave), 0, st, logits, row_stride, V, pl.nC, cs, ratio,
                            inv_temp, bits, d2t, tab_ref, tab_s, o);
     }
 }
