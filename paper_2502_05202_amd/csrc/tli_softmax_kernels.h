@@ -1,0 +1,380 @@
+// tli_softmax_kernels.h -- Row normalisers, chunk tables and the inverse-CDF samplers: the drafting side of the path (q' of the
+// intersection algorithm) and everything else that draws one token per softmax row.  Included by tli_kernels.hip
+// inside its unnamed namespace, after tli_device_common.h.
+#pragma once
+
+// ---- kernel: log-normaliser partials of rows -----------------------------------------------------
+// Standard SD appendix, verification loop: p_k(d_k) needs the normaliser of every target row k < K
+// (MASKED = false).  With MASKED = true the same scan runs over drafter rows restricted to the shared
+// ids (the normaliser of q' in the intersection algorithm), for callers that do not pass lse_q.
+// grid (rows * nsplit); row r = (b, k) with b = r / K, k = r % K.
+template <int DT, bool MASKED>
+__global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, int K, int64_t seq_stride,
+                                              int64_t row_stride, int V, int nC, int cps, int nsplit, float cs,
+                                              double ratio, const uint64_t* __restrict__ bits,
+                                              Part* __restrict__ part, float2* __restrict__ ctab) {
+    const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
+    const int b = row / K, k = row - b * K;
+    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
+                                                    (b * seq_stride + k * row_stride) * Traits<DT>::ESZ);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const double kd = (ratio - 1.0) * kLn2;
+    // The (ref, s) of every chunk is parked in LDS (no global store sits between the streaming loads, and the
+    // running total is not advanced per chunk: that is a dozen fp64 instructions which every lane would
+    // execute for a wave-uniform value); the partial is reduced from there when the row is through.  The pairs
+    // are also what the residual of a rejected row takes its chunk sums of p from (ctab).
+    __shared__ float2 stash[kLdsChunks];
+    Running over;  // chunks beyond what LDS parks (rows of more than kLdsChunks chunks per workgroup)
+    scan_chunks<DT, MASKED, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, (float)(ratio - 1.0), bits,
+                                    [&](int c, float r, float sc) {
+                                        const int i = c - split * cps;
+                                        if (i < kLdsChunks) {
+                                            if (lane == 0) stash[i] = make_float2(r, sc);
+                                        } else {
+                                            over.add(r, sc, kd);
+                                            if (ctab && lane == 0) ctab[(int64_t)row * nC + c] = make_float2(r, sc);
+                                        }
+                                    });
+    __shared__ float sref[kWaves];
+    __shared__ double ssum[kWaves];
+    __syncthreads();
+    const int n_here = min(min(nC, (split + 1) * cps) - split * cps, kLdsChunks);
+    float r_mine = over.ref;
+    for (int i = threadIdx.x; i < n_here; i += kWG) {
+        const float2 e = stash[i];
+        r_mine = fmaxf(r_mine, e.x);
+        if (ctab) ctab[(int64_t)row * nC + split * cps + i] = e;
+    }
+    r_mine = wave_max(r_mine);
+    if (lane == 0) sref[wave] = r_mine;
+    __syncthreads();
+    float R = sref[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) R = fmaxf(R, sref[w]);
+    double s_mine = lane == 0 ? over.s * exp2_diff(over.ref, R, kd) : 0.0;  // a wave's overflow total counts once
+    for (int i = threadIdx.x; i < n_here; i += kWG) {
+        const float2 e = stash[i];
+        s_mine += (double)e.y * exp2_diff(e.x, R, kd);
+    }
+    s_mine = wave_sum_f64(s_mine);
+    if (lane == 0) ssum[wave] = s_mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double S = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) S += ssum[w];
+        Part p; p.ref = R; p.pad = 0.f; p.s = S;
+        part[(int64_t)row * nsplit + split] = p;
+    }
+}
+
+// log-normaliser of a row from its partials: ln sum exp(x/temp) = ln2 * (ref * c_true/c + log2 S), where the
+// factor c_true/c takes out the common part of the fp32 rounding of c.  NaN if a logit was NaN/+inf,
+// -inf if the row has no mass.
+__device__ __forceinline__ double combine_parts(const Part* pr, int nsplit, double ratio) {
+    float R = pr[0].ref;
+    for (int s = 1; s < nsplit; ++s) R = fmaxf(R, pr[s].ref);
+    double S = 0.0;
+    for (int s = 0; s < nsplit; ++s) S += pr[s].s * exp2_diff(pr[s].ref, R, (ratio - 1.0) * kLn2);
+    if (S != S || R == INFINITY) return NAN;
+    if (!(S > 0.0)) return -INFINITY;
+    return kLn2 * ((double)R * ratio + log2(S));
+}
+
+// kernel: lse[row] from the partials of k_lse.  grid (ceil(rows / 256)).
+__global__ __launch_bounds__(kWG) void k_lse_finish(const Part* __restrict__ part, int rows, int nsplit, double ratio,
+                                                     double* __restrict__ lse) {
+    const int row = blockIdx.x * kWG + threadIdx.x;
+    if (row < rows) lse[row] = combine_parts(part + (int64_t)row * nsplit, nsplit, ratio);
+}
+
+// ---- kernel: per-chunk (ref, s) table of a softmax row, optionally masked to the shared ids ----
+// Used for drafter rows (masked: the intersection algorithm's q') and for the bonus target row.
+// Workgroup `split` of a row owns chunks [split*cps, (split+1)*cps).
+template <int DT, bool MASKED>
+__device__ __forceinline__ void table_scan(const u4v* rowv, int split, int V, int nC, int cps, float cs, double ratio,
+                                           const uint64_t* bits,
+                                  float* tab_ref, float* tab_s) {
+    const int lane = threadIdx.x & 63;
+    scan_chunks<DT, MASKED, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, (float)(ratio - 1.0), bits,
+                                    [&](int c, float r, float sc) {
+        if (lane == 0) { tab_ref[c] = r; tab_s[c] = sc; }
+    });
+}
+
+template <int DT, bool MASKED>
+__global__ __launch_bounds__(kWG) void k_draft_scan(const void* __restrict__ logits, int64_t row_stride, int V,
+                                                     int nC, int cps, int nsplit, float cs, double ratio,
+                                                     const uint64_t* __restrict__ bits, float* __restrict__ tab_ref,
+                                                     float* __restrict__ tab_s) {
+    const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
+    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
+                                                    (int64_t)row * row_stride * Traits<DT>::ESZ);
+    table_scan<DT, MASKED>(rowv, split, V, nC, cps, cs, ratio, bits, tab_ref + (int64_t)row * nC,
+                         tab_s + (int64_t)row * nC);
+}
+
+// ---- sampler: a workgroup of kLoads waves draws the token of a row from the row's chunk table ----
+// (Every wave finds the chunk for itself -- a few hundred table entries, no barrier -- then the waves share
+// the chosen chunk, one 16-byte load per lane each: the draw is a chain of dependent round trips to memory, and
+// this takes three of them out of it.)
+
+// exclusive prefix of v over the 64 lanes in fp64; *total = the wave's sum (uniform)
+__device__ __forceinline__ double wave_excl_scan(double v, double* total) {
+    const int lane = threadIdx.x & 63;
+    double inc = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const double t = __shfl_up(inc, d, kWave);
+        if (lane >= d) inc += t;
+    }
+    *total = __shfl(inc, kWave - 1, kWave);
+    return inc - v;
+}
+
+__device__ __forceinline__ int wave_max_int(int v) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) v = max(v, __shfl_xor(v, d, kWave));
+    return v;
+}
+
+// Chunk search.  Lane l owns the contiguous chunks [l*per, (l+1)*per); `mass(c)` is chunk c's fp64 mass.
+// Returns the first chunk whose inclusive prefix exceeds theta = u * total, with theta - (prefix before
+// it) in *theta_local; if rounding leaves no crossing, the last chunk with mass and +inf; -1 if the
+// total is not positive (zero, negative or NaN).  All results are wave-uniform.
+// P = chunks per lane held in registers: every mass is evaluated once, and a lane's loads (the chunk tables are in
+// memory for some callers) are all issued before the first is used -- one round trip instead of one per chunk
+// and pass.
+template <int P, class MassFn>
+__device__ __forceinline__ int find_chunk_p(int nC, int per, double u, MassFn mass, double* theta_local,
+                                            double* total_out) {
+    const int lane = threadIdx.x & 63;
+    const int c0 = min(nC, lane * per), c1 = min(nC, c0 + per);
+    double m[P];
+    double mine = 0.0;
+#pragma unroll
+    for (int k = 0; k < P; ++k) {  // past the lane's range: some valid chunk is evaluated and dropped
+        const double t = mass(min(c0 + k, nC - 1));
+        m[k] = c0 + k < c1 ? t : 0.0;
+    }
+#pragma unroll
+    for (int k = 0; k < P; ++k) mine += m[k];
+    double total;
+    const double excl = wave_excl_scan(mine, &total);
+    *total_out = total;
+    if (!(total > 0.0)) return -1;
+    const double theta = u * total;
+    double run = excl, before = 0.0;
+    int found = -1, last_pos = -1;
+#pragma unroll
+    for (int k = 0; k < P; ++k) {
+        const double t = m[k];
+        if (t > 0.0) last_pos = c0 + k;
+        if (found < 0 && c0 + k < c1 && run + t > theta) { found = c0 + k; before = run; }
+        run += t;
+    }
+    const unsigned long long hit = __ballot(found >= 0);
+    if (hit == 0ull) {
+        *theta_local = INFINITY;
+        return wave_max_int(last_pos);
+    }
+    const int src = (int)__builtin_ctzll(hit);  // lanes own ascending chunk ranges: lowest lane = first chunk
+    *theta_local = theta - __shfl(before, src, kWave);
+    return __shfl(found, src, kWave);
+}
+
+template <class MassFn>
+__device__ __forceinline__ int find_chunk(int nC, double u, MassFn mass, double* theta_local, double* total_out) {
+    const int lane = threadIdx.x & 63;
+    const int per = (nC + kWave - 1) / kWave;
+    if (per <= 2) return find_chunk_p<2>(nC, per, u, mass, theta_local, total_out);
+    if (per <= 4) return find_chunk_p<4>(nC, per, u, mass, theta_local, total_out);
+    const int c0 = min(nC, lane * per), c1 = min(nC, c0 + per);
+    double mine = 0.0;
+    for (int c = c0; c < c1; ++c) mine += mass(c);
+    double total;
+    const double excl = wave_excl_scan(mine, &total);
+    *total_out = total;
+    if (!(total > 0.0)) return -1;
+    const double theta = u * total;
+    double run = excl, before = 0.0;
+    int found = -1, last_pos = -1;
+    for (int c = c0; c < c1; ++c) {
+        const double t = mass(c);
+        if (t > 0.0) last_pos = c;
+        if (found < 0 && run + t > theta) { found = c; before = run; }
+        run += t;
+    }
+    const unsigned long long hit = __ballot(found >= 0);
+    if (hit == 0ull) {
+        *theta_local = INFINITY;
+        return wave_max_int(last_pos);
+    }
+    const int src = (int)__builtin_ctzll(hit);  // lanes own ascending chunk ranges: lowest lane = first chunk
+    *theta_local = theta - __shfl(before, src, kWave);
+    return __shfl(found, src, kWave);
+}
+
+// In-chunk search by the kLoads waves of a workgroup.  The chunk's ids are taken in id order: load j = 0..3, then
+// lane, then element; wave j holds load j, `w` = the weights of this lane's vector (ids e0 .. e0+N-1).  Returns
+// (to every thread) the first id whose inclusive prefix exceeds theta_local, or, if rounding leaves no
+// crossing, the last id with a positive weight (-1 if there is none).  The prefix over the loads is added up in
+// load order, as one wave walking the four loads in turn would.  Every wave of the workgroup must call it.
+template <int N>
+__device__ __forceinline__ int chunk_draw(const double (&w)[N], int64_t e0, double theta_local) {
+    __shared__ double s_tot[kLoads];
+    __shared__ int s_found[kLoads], s_last[kLoads];
+    const int lane = threadIdx.x & 63;
+    const int j = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    double mine = 0.0;
+#pragma unroll
+    for (int i = 0; i < N; ++i) mine += w[i];
+    double tot;
+    const double excl = wave_excl_scan(mine, &tot);
+    if (lane == 0) s_tot[j] = tot;
+    __syncthreads();
+    double base = 0.0;
+    for (int q = 0; q < j; ++q) base += s_tot[q];
+    double run = base + excl;
+    int f = -1, last_pos = -1;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        run += w[i];
+        if (w[i] > 0.0) last_pos = (int)(e0 + i);
+        if (f < 0 && run > theta_local) f = (int)(e0 + i);
+    }
+    const unsigned long long hit = __ballot(f >= 0);
+    const int first = hit ? __shfl(f, (int)__builtin_ctzll(hit), kWave) : -1;
+    const int last = wave_max_int(last_pos);
+    if (lane == 0) { s_found[j] = first; s_last[j] = last; }
+    __syncthreads();
+    int tok = -1;
+    for (int q = kLoads - 1; q >= 0; --q)
+        if (s_found[q] >= 0) tok = s_found[q];  // the first load with a crossing
+    if (tok < 0)
+        for (int q = 0; q < kLoads; ++q) tok = max(tok, s_last[q]);
+    return tok;
+}
+
+// weights of one 16-byte vector of a softmax row relative to reference `nref` (= -ref), as in
+// reduce_chunk: 2^(x*c - ref); elements >= V or masked out get 0.
+template <int DT, bool MASKED>
+__device__ __forceinline__ void softmax_vec_weights(const uint4* rowv, int64_t vi, int V, float cs, float nref,
+                                                    const uint64_t* bits, double* w) {
+    constexpr int EPV = Traits<DT>::EPV;
+    float x[EPV];
+    if (vi * EPV < V) {
+        unpack<DT>(rowv[vi], x);
+        const uint32_t mb = MASKED ? mask_bits<DT>(bits, vi) : 0xffu;  // same lane-mask words as the scan
+#pragma unroll
+        for (int i = 0; i < EPV; ++i) {
+            const bool live = (vi * EPV + i < V) && ((mb >> i) & 1u);
+            w[i] = live ? (double)exp2_hw(fmaf(x[i], cs, nref)) : 0.0;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < EPV; ++i) w[i] = 0.0;
+    }
+}
+
+// Inverse-CDF sample of a (masked) softmax row from its chunk table, by the kLoads waves of a workgroup: every
+// wave finds the chunk for itself (the table is small), then each takes one of the chunk's loads.  Returns the
+// id, or -1 if the row has no usable mass (then *total_out is NaN for a NaN/+inf logit, else 0).  Every wave of
+// the workgroup must call it, with the same arguments.
+template <int DT, bool MASKED>
+__device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int nC, float cs, double ratio,
+                                                  const uint64_t* bits,
+                                                  const float* tr, const float* ts, double u, float* M_out,
+                                                  double* total_out) {
+    constexpr int EPV = Traits<DT>::EPV;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    float m = -INFINITY;
+    for (int c = lane; c < nC; c += kWave) m = fmaxf(m, tr[c]);
+    const float M = wave_max(m);
+    *M_out = M;
+    const double kd = (ratio - 1.0) * kLn2;
+    double theta_local;
+    const int c = find_chunk(nC, u, [&](int cc) { return (double)ts[cc] * exp2_diff(tr[cc], M, kd); }, &theta_local,
+                             total_out);
+    if (c < 0) {
+        if (M == INFINITY) *total_out = NAN;
+        return -1;
+    }
+    const int64_t vi = ((int64_t)c * kLoads + wave) * kWave + lane;
+    double w[EPV];
+    softmax_vec_weights<DT, MASKED>(static_cast<const uint4*>(rowp), vi, V, cs, -M, bits, w);
+    return chunk_draw<EPV>(w, vi * EPV, theta_local);
+}
+
+// ---- draft token of one drafter row from its chunk table ----------------------------------------
+// Standard SD appendix, drafting loop, with q' of the intersection algorithm.
+struct DraftOut {
+    const float* u_draft;
+    int32_t *tok_d, *tok_t;
+    double *q_tok, *lse_q;
+    int32_t* row_status;
+    int64_t stride;  // entry of row r of every per-row array (u_draft included) is at index r * stride
+    const int32_t* r2d;  // compact rows: index in the row (= rank) -> drafter id; nullptr otherwise
+};
+
+// MASKED: the row is restricted to the shared ids (TLI's q').  Unmasked, the same code draws from the plain
+// softmax of a row of any vocabulary: the union algorithm's draft (d2t then marks tokens outside T with -1)
+// and the one-token-per-target-row draw of exact matching (d2t and tok_t null).
+template <int DT, bool MASKED>
+__device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V, int nC, float cs, double c_ratio,
+                                      double inv_temp, const uint64_t* bits, const int32_t* d2t, const float* tr,
+                                      const float* ts, const DraftOut& o) {
+    float M;
+    double total;
+    const int64_t at = (int64_t)row * o.stride;
+    const int d = sample_softmax_row<DT, MASKED>(rowp, V, nC, cs, c_ratio, bits, tr, ts, (double)o.u_draft[at], &M, &total);
+    if (threadIdx.x != 0) return;
+    if (d < 0) {  // no usable mass: NaN/+inf among the logits that take part, or all of them -inf
+        const bool nonfinite = (total != total);
+        o.tok_d[at] = -1;
+        if (o.tok_t) o.tok_t[at] = -1;
+        if (o.q_tok) o.q_tok[at] = 0.0;
+        if (o.lse_q) o.lse_q[at] = nonfinite ? NAN : -INFINITY;
+        o.row_status[at] = nonfinite ? TLI_FLAG_NONFINITE : TLI_FLAG_ZERO_MASS;
+        return;
+    }
+    const double lse = kLn2 * ((double)M * c_ratio + log2(total));
+    const int id = o.r2d ? o.r2d[d] : d;  // the id reported: a drafter id also when the row is in compact layout
+    o.tok_d[at] = id;
+    if (o.tok_t) o.tok_t[at] = d2t ? d2t[id] : id;
+    if (o.lse_q) o.lse_q[at] = lse;
+    if (o.q_tok) o.q_tok[at] = exp((double)load_elem<DT>(rowp, d) * inv_temp - lse);
+    o.row_status[at] = 0;
+}
+
+// kernel: sampler of the split path (rows cut over several workgroups by k_draft_scan).  grid (R), kLoads waves.
+template <int DT, bool MASKED>
+__global__ __launch_bounds__(kLoads * kWave) void k_draft_pick(const void* __restrict__ logits, int64_t row_stride, int V,
+                                                     int nC, float cs, double c_ratio, double inv_temp,
+                                                     const uint64_t* __restrict__ bits,
+                                                     const int32_t* __restrict__ d2t,
+                                                     const float* __restrict__ tab_ref,
+                                                     const float* __restrict__ tab_s, DraftOut o) {
+    const int row = blockIdx.x;
+    const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
+    draft_pick_row<DT, MASKED>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tab_ref + (int64_t)row * nC,
+                       tab_s + (int64_t)row * nC, o);
+}
+
+// kernel: one workgroup per drafter row scans it into a chunk table in LDS and samples from it at
+// once, while the other workgroups on the CU keep streaming their rows.
+// grid (R); nC <= kLdsChunks.
+template <int DT, bool MASKED>
+__global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ logits, int64_t row_stride, int V,
+                                                      int nC, float cs, double c_ratio, double inv_temp,
+                                                      const uint64_t* __restrict__ bits,
+                                                      const int32_t* __restrict__ d2t, DraftOut o) {
+    __shared__ float tr[kLdsChunks], ts[kLdsChunks];
+    const int row = blockIdx.x;
+    const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
+    table_scan<DT, MASKED>(reinterpret_cast<const u4v*>(rowp), 0, V, nC, nC, cs, c_ratio, bits, tr, ts);
+    __syncthreads();
+    draft_pick_row<DT, MASKED>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tr, ts, o);
+}

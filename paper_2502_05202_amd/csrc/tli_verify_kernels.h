@@ -1,0 +1,601 @@
+// tli_verify_kernels.h -- Verification: accept tests and first-reject scan, the residual distribution of the rejected position (chunk
+// masses, then the draw), the bonus row.  Included by tli_kernels.hip inside its unnamed namespace, after
+// tli_softmax_kernels.h.
+#pragma once
+
+// ---- how the verification kernels address the drafter logits ------------------------------------
+// Full layout: rows of Vd logits in drafter-id order.  Compact layout (a drafter head pruned to the shared
+// tokens): rows of S logits in rank order (rank = position among the shared ids, ascending drafter id).
+struct DrafterView {
+    const void* base;
+    int64_t row_stride;    // elements between consecutive rows
+    const int32_t* d2x;    // drafter id -> index in a row; nullptr = identity (full layout)
+    const int32_t* t2x;    // target id -> index in a row, -1 for target-only ids (t2d full, t2r compact)
+};
+
+// ---- what the final kernels need to know about a sequence, written once by the accept kernel ----
+struct ResidualParams {
+    float ct_hi, ct_lo, lp_hi, lp_lo;  // target: p = 2^(x*ct - Lp), Lp = lse_p * log2 e
+    float cd_hi, cd_lo, lq_hi, lq_lo;  // drafter: q' = 2^(y*cd - Lq)
+    int use_q;                         // 0: the rejected draft was unusable, q' = 0 everywhere
+};
+struct FinalRow {
+    int skip;       // sequence is flagged NONFINITE
+    int bonus;      // nothing rejected: sample from p of row K
+    int n;          // accepted count = index of the row the extra token comes from
+    int t_row;      // that row in the target tensor (dense row index), and its partner in the drafter tensor
+    int d_row;
+    float dq;       // diagnostics only: log2 q'(x) - log2 q(x) = (lse_q over D - lse_q over T∩D) * log2 e >= 0
+    ResidualParams rp;
+    double l2p;     // lse_p of row n, in log2 units
+};
+
+__device__ __forceinline__ void split_hi_lo(double v, float& hi, float& lo) {
+    hi = (float)v;
+    lo = (float)(v - (double)hi);
+}
+
+// scale c > 0 as hi + lo with hi < c, so that lo > 0
+__device__ __forceinline__ void split_scale(double c, float& hi, float& lo) {
+    hi = (float)c;
+    if ((double)hi >= c) hi = as_f(as_u(hi) - 1u);
+    lo = (float)(c - (double)hi);
+}
+
+// ---- kernel: accept tests and first-reject scan ------------------------------------------------
+// Standard SD appendix, verification loop and the count of accepted drafts.  grid (B), 64 threads;
+// lane k owns position k.
+template <int DT>
+__global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logits_t, DrafterView dv,
+                                                   int K, int Vt, int Vd, int nsplit, const Part* __restrict__ part,
+                                                   double ratio_t, double inv_temp_t, double inv_temp_d,
+                                                   const int32_t* __restrict__ d2t, const int32_t* __restrict__ tok_d,
+                                                   const double* __restrict__ lse_q, const float* __restrict__ u_acc,
+                                                   int32_t* __restrict__ n_accepted, int32_t* __restrict__ out_tok,
+                                                   uint8_t* __restrict__ accept, double* __restrict__ p_tok,
+                                                   double* __restrict__ q_tok, double* __restrict__ lse_p,
+                                                   int32_t* __restrict__ seq_status, double* __restrict__ ws_lse_p, double c_t,
+                                                   double c_d, FinalRow* __restrict__ frow, int32_t* __restrict__ fbad, int union_mode) {
+    const int b = blockIdx.x, k = threadIdx.x;
+    bool acc = true, nonfinite = false, bad = false;
+    int tt = -1;
+    double my_lse = 0.0, my_lq = 0.0;
+    if (k < K) {
+        const int64_t row = (int64_t)b * K + k;
+        const double lse = combine_parts(part + row * nsplit, nsplit, ratio_t);
+        nonfinite = lse != lse;
+        my_lse = lse;
+        ws_lse_p[row] = lse;
+        if (lse_p) lse_p[(int64_t)b * (K + 1) + k] = lse;
+        const int d = tok_d[row];
+        my_lq = lse_q[row];
+        double pd = 0.0, qd = 0.0;
+        acc = false;
+        // TLI: a draft must be a shared drafter id.  Union algorithm: any drafter id is a legal draft; one
+        // outside T has target probability 0 and is rejected by the test itself; every drafter logit takes
+        // part there, so a NaN normaliser (NaN/+inf somewhere in the row) flags the sequence.
+        if (d < 0 || d >= Vd || (!union_mode && d2t[d] < 0)) {
+            bad = true;
+        } else if (union_mode && my_lq != my_lq) {
+            nonfinite = true;
+        } else if (!nonfinite) {
+            tt = d2t[d];
+            const char* lt = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + k) * Vt * Traits<DT>::ESZ;
+            const char* ld = static_cast<const char*>(dv.base) + row * dv.row_stride * Traits<DT>::ESZ;
+            pd = (tt < 0 || lse == -INFINITY) ? 0.0 : exp((double)load_elem<DT>(lt, tt) * inv_temp_t - lse);
+            const int dx = dv.d2x ? dv.d2x[d] : d;
+            qd = (union_mode && my_lq == -INFINITY) ? 0.0 : exp((double)load_elem<DT>(ld, dx) * inv_temp_d - my_lq);
+            acc = (double)u_acc[row] * qd < pd;
+        }
+        if (accept) accept[row] = acc ? 1 : 0;
+        if (p_tok) p_tok[row] = pd;
+        if (q_tok) q_tok[row] = qd;
+    }
+    const unsigned long long rej = __ballot(k < K && !acc);
+    const bool any_nonfinite = __ballot(nonfinite) != 0ull;
+    const bool any_bad = __ballot(bad) != 0ull;
+    int n = rej ? (int)__builtin_ctzll(rej) : K;
+    if (any_nonfinite) n = 0;
+    if (k < K) out_tok[(int64_t)b * (K + 1) + k] = (k < n) ? tt : -1;
+    if (k == 0) {
+        out_tok[(int64_t)b * (K + 1) + K] = -1;
+        n_accepted[b] = n;
+        seq_status[b] = (any_nonfinite ? TLI_FLAG_NONFINITE : 0) | (any_bad ? TLI_FLAG_BAD_DRAFT : 0);
+        fbad[b] = 0;  // raised by the residual scan if the drafter row it reads holds NaN or +inf
+        if (lse_p) lse_p[(int64_t)b * (K + 1) + K] = NAN;
+    }
+    // one record per sequence for the final kernels, written by the lane that owns the row they will use
+    const bool residual = !any_nonfinite && n < K;
+    if (residual ? (k == n) : (k == 0)) {
+        FinalRow f;
+        f.skip = any_nonfinite ? 1 : 0;
+        f.bonus = (!any_nonfinite && n == K) ? 1 : 0;
+        f.n = n;
+        f.t_row = b * (K + 1) + (f.bonus ? K : n);
+        f.d_row = b * K + (f.bonus ? 0 : n);
+        f.dq = 0.f;
+        f.l2p = 0.0;
+        f.rp.use_q = 0;
+        f.rp.ct_hi = f.rp.ct_lo = f.rp.lp_hi = f.rp.lp_lo = 0.f;
+        f.rp.cd_hi = f.rp.cd_lo = f.rp.lq_hi = f.rp.lq_lo = 0.f;
+        if (residual) {
+            f.l2p = my_lse * kLog2e;
+            split_scale(c_t, f.rp.ct_hi, f.rp.ct_lo);
+            split_hi_lo(f.l2p, f.rp.lp_hi, f.rp.lp_lo);
+            // an unusable draft, or a drafter row without mass, has q' = 0 everywhere
+            if (!bad && (my_lq > -INFINITY || my_lq != my_lq)) {
+                f.rp.use_q = 1;
+                split_scale(c_d, f.rp.cd_hi, f.rp.cd_lo);
+                split_hi_lo(my_lq * kLog2e, f.rp.lq_hi, f.rp.lq_lo);
+            }
+        }
+        frow[b] = f;
+    }
+}
+
+// ---- extra token: weights of one vector of the residual row -----------------------------------
+// Standard SD appendix, last step: r(t) ∝ p(t) - min(p(t), q'(t)) = max(0, p(t) - q'(t)); q'(t) is
+// the adjusted drafter's probability of the drafter id that maps to t (0 for target-only ids).
+// p and q' are evaluated as 2^(x*c - L) with c and L split into fp32 hi + lo parts, so both carry
+// about one ulp of error: the difference of two nearly equal probabilities must not inherit the
+// rounding of a large exponent.
+// 2^(x*(c_hi+c_lo) - (l_hi+l_lo)) with one rounding of each partial product.  c_lo is strictly positive
+// (see split_scale), so a -inf logit gives -inf + -inf = -inf (probability 0), never inf - inf.
+__device__ __forceinline__ float exp2_split(float x, float c_hi, float c_lo, float l_hi, float l_lo) {
+    return exp2_hw(fmaf(x, c_hi, -l_hi) + fmaf(x, c_lo, -l_lo));
+}
+
+template <int DT>
+__device__ __forceinline__ void residual_vec(const void* rowp, int64_t vi, int V, const ResidualParams& rp,
+                                             const int32_t* __restrict__ t2d, const void* __restrict__ ld_row,
+                                             float* p, float* w) {
+    constexpr int EPV = Traits<DT>::EPV;
+    const int64_t nvec = (V + EPV - 1) / EPV;
+    const int64_t vc = vi < nvec ? vi : nvec - 1;
+    const int64_t e0 = vi * EPV;
+    float x[EPV];
+    unpack<DT>(static_cast<const uint4*>(rowp)[vc], x);
+    float y[EPV];
+    int32_t d[EPV];
+    if (rp.use_q) {
+#pragma unroll
+        for (int i = 0; i < EPV; i += 4) {
+            const int4 t = *reinterpret_cast<const int4*>(t2d + vc * EPV + i);  // t2d is padded to a multiple of 8
+            d[i] = t.x; d[i + 1] = t.y; d[i + 2] = t.z; d[i + 3] = t.w;
+        }
+#pragma unroll
+        for (int i = 0; i < EPV; ++i) y[i] = load_elem<DT>(ld_row, d[i] > 0 ? d[i] : 0);
+    }
+#pragma unroll
+    for (int i = 0; i < EPV; ++i) {
+        const bool live = e0 + i < V;
+        float pi = exp2_split(x[i], rp.ct_hi, rp.ct_lo, rp.lp_hi, rp.lp_lo);
+        pi = live ? pi : 0.f;
+        float qi = 0.f;
+        if (rp.use_q) {
+            qi = exp2_split(y[i], rp.cd_hi, rp.cd_lo, rp.lq_hi, rp.lq_lo);
+            qi = (live && d[i] >= 0) ? qi : 0.f;
+        }
+        p[i] = pi;
+        w[i] = fmaxf(0.f, pi - qi);
+        if (!(qi <= 3.0e38f)) w[i] = NAN;  // NaN or +inf in the drafter row must surface (fmaxf would drop it)
+    }
+}
+
+// ---- extra token of one sequence from the chunk tables of its row ------------------------------
+// Standard SD appendix, last step: writes out_tok[b, n_accepted[b]]; for bonus rows also lse_p[b, K].
+struct FinalOut {
+    const float* u_fin;
+    int32_t *n_accepted, *out_tok;
+    double* lse_p;
+    int32_t* seq_status;
+};
+
+template <int DT>
+__device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const void* logits_t, const DrafterView& dv,
+                                               int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
+                                               const int32_t* t2d, const float* tr, const float* ts,
+                                               const float2* ctab, const double* mn, const int32_t* fbad,
+                                               const FinalOut& o) {
+    constexpr int EPV = Traits<DT>::EPV;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const char* rowp = static_cast<const char*>(logits_t) + (int64_t)f.t_row * Vt * Traits<DT>::ESZ;
+    const double u = (double)o.u_fin[b];
+    int tok = -1;
+    int add_flags = 0;
+    bool nonfinite = false;
+    if (f.bonus) {
+        float M;
+        double total;
+        tok = sample_softmax_row<DT, false>(rowp, Vt, nC, cs_t, ratio_t, nullptr, tr, ts, u, &M, &total);
+        // no usable mass: NaN/+inf, or a bonus row of only -inf -- no distribution to sample either way
+        if (tok < 0) nonfinite = true;
+        else if (threadIdx.x == 0 && o.lse_p) o.lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
+    } else {
+        const char* ldp = static_cast<const char*>(dv.base) + (int64_t)f.d_row * dv.row_stride * Traits<DT>::ESZ;
+        // chunk masses: sum_chunk p (from the normaliser kernel's table of row n) minus the parts' sums of min(p, q')
+        const float2* crow = ctab + (int64_t)f.d_row * nC;
+        auto p_mass = [&](int cc) {
+            const float2 rs = crow[cc];
+            return (rs.x == -INFINITY) ? 0.0 : (double)rs.y * exp2((double)rs.x * ratio_t - f.l2p);
+        };
+        auto r_mass = [&](int cc) {
+            const double m = f.rp.use_q ? mn[cc] : 0.0;
+            const double t = p_mass(cc) - m;
+            return t > 0.0 ? t : (t != t ? t : 0.0);
+        };
+        double theta_local, total;
+        int c = -1;
+        bool degenerate = false;
+        if (f.rp.use_q && fbad[b]) {  // NaN or +inf among the shared drafter logits of row n
+            nonfinite = true;
+        } else {
+            c = find_chunk(nC, u, r_mass, &theta_local, &total);
+            if (c < 0) {
+                if (total != total) {
+                    nonfinite = true;
+                } else {  // residual identically zero: fall back to p of the same row
+                    degenerate = true;
+                    add_flags |= TLI_FLAG_DEGENERATE;
+                    c = find_chunk(nC, u, p_mass, &theta_local, &total);
+                    if (c < 0) nonfinite = true;
+                }
+            }
+        }
+        if (!nonfinite) {
+            // wave j of the workgroup takes load j of the chunk: a quarter of the table look-ups, gathers and
+            // exponentials each
+            const int64_t vi = ((int64_t)c * kLoads + wave) * kWave + lane;
+            float p[EPV], w[EPV];
+            residual_vec<DT>(rowp, vi, Vt, f.rp, t2d, ldp, p, w);
+            double wd[EPV];
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) wd[i] = degenerate ? (double)p[i] : (double)w[i];
+            tok = chunk_draw<EPV>(wd, vi * EPV, theta_local);
+        }
+    }
+    if (threadIdx.x == 0) {
+        if (nonfinite) {
+            o.n_accepted[b] = 0;
+            for (int k = 0; k <= K; ++k) o.out_tok[(int64_t)b * (K + 1) + k] = -1;
+            o.seq_status[b] |= TLI_FLAG_NONFINITE;
+        } else {
+            o.out_tok[(int64_t)b * (K + 1) + f.n] = tok;
+            if (add_flags) o.seq_status[b] |= add_flags;
+        }
+    }
+}
+
+// ---- kernel: chunk masses of the row the extra token is drawn from ------------------------------
+// Residual rows (first rejection at position n < K).  The extra token is drawn from
+// r(t) ∝ max(0, p_n(t) - q'_n(t)), and per chunk of target ids
+//     sum_chunk max(0, p - q') = sum_chunk p - sum_{shared ids of the chunk} min(p, q').
+// The first sum is known: the normaliser kernel left the chunk table (ref, s) of every target row, and
+// sum_chunk p = s * 2^(ref * c_true/c - lse_p * log2 e).  Only the second sum is computed here; it runs over
+// the shared PAIRS (target id, drafter id) alone.  The two vocabularies' orders are unrelated, so a pair
+// needs one random access on each side -- and random access is cheap only in LDS.  The target row is cut
+// into PARTS, runs of whole chunks holding at most part_cap pairs.  A workgroup owns one part of one row.
+//   (1) It sweeps the drafter row with plain 16-byte loads and packs the logits of the part's pairs into LDS in
+//       ascending drafter order.  Beside every vector of the row the map holds one word: which of the vector's
+//       elements belong to the part, and the LDS position of the first of them.  A lane stores all its
+//       elements, the unwanted ones to a scratch word of its own, so the sweep has no branch, no mask
+//       juggling and no index list.  (Gathering the part through an index list was tried first: a 2-byte
+//       gather costs the texture addresser ~30 cycles per wave instruction, more than the whole target row.)
+//   (2) Its waves stream the part's target chunks: a wave parks a chunk in its private LDS slot and walks the
+//       map's list of the chunk's pairs, each entry = (byte offset in chunk, index of the staged drafter
+//       logit), reading both logits from LDS.
+// Every target chunk is thus read once per row, every pair is owned by one lane of one wave, and sums are
+// per lane, then across lanes in a fixed order, so results do not depend on timing.
+// The kernel is short (tens of microseconds) and its waves are few (16 per CU): counters show it bound by
+// instruction issue and by dependent round trips, not by bandwidth.  Hence:
+//   * a chunk's pair list is padded to whole groups of 128 entries (two per lane, one 8-byte load) with
+//     entries that point at a -inf logit (min(p, 0) contributes exactly 0): a group is either all live or
+//     absent and the only test is a wave-uniform one; the list has kPairU groups of slack at its end, so the
+//     first kPairU groups of every chunk are fetched without looking at its length;
+//   * an entry is two 16-bit fields that the address arithmetic reads in place;
+//   * the loads of a wave's next chunk are in flight while it works on the current one (two register sets,
+//     alternating), those of its first chunk are issued before the staging sweep, and the list bounds of
+//     all its chunks come with one vector load (scalar loads would miss the scalar cache at every step, and
+//     a wait for one of them is a wait for everything else the wave has in flight on that counter);
+//   * no load sits under a branch (the compiler would then wait for ALL outstanding loads at every use): a
+//     fetch past the end of the part is made harmless, every lane reading the same few lines again.
+// Output: mn[b][chunk] = sum of min(p, q') over the chunk's pairs; the draw kernel forms the masses.
+// Bonus rows (nothing rejected) go through the same grid: the workgroups of a sequence split target row K
+// and scan it into a plain (ref, s) softmax table.
+// grid (B rounded up to 8) x nparts x nsplit; workgroups of flagged sequences exit at once.
+// nsplit > 1 (few sequences): the chunks of one (sequence, part) are dealt to nsplit workgroups, each with
+// its own copy of the part's drafter logits.
+constexpr int kScanWG = 1024;
+constexpr int kScanWaves = kScanWG / kWave;
+constexpr int kSlotBytes = kWave * kLoads * 16;  // one chunk
+constexpr int kTrashBytes = kWave * 4;           // LDS [0, 256): a word per lane for the elements a lane does not keep
+constexpr int kPartBytes = 92 * 1024;            // then the staged drafter logits of a part, the last 16 bytes of the
+                                                 // area hold the -inf logit that padding entries point at
+constexpr int kScanLds = kPartBytes + kScanWaves * kSlotBytes;  // then one chunk slot per wave
+constexpr int kPairG = 2 * kWave;      // entries in a group of a chunk's pair list: two per lane
+constexpr int kPairU = 6;              // groups fetched with a chunk (more: late loop)
+constexpr int kStageV = 8;             // drafter vectors a lane has in flight during the staging sweep
+constexpr int kPairShift = 16;         // entry = byte offset in chunk (< 4096) | index of the staged logit << 16
+constexpr int kMaxPartChunks = kWave * kScanWaves;  // a wave keeps a lane per chunk it handles
+static_assert(kScanLds <= 160 * 1024, "LDS of one CU");
+
+struct ScanLists {            // the map's lists for one dtype and one drafter-row layout, as the scan kernel reads them
+    int nparts;
+    int row_elems;            // valid entries of a drafter row: |D| (full layout) or |T∩D| (compact)
+    int NV;                   // vectors of a drafter row, rounded up to whole groups of 64
+    const int32_t* cb;        // [nparts+1] first chunk of every part
+    const int32_t* part_n;    // [nparts] pairs of every part
+    const int2* grange;       // [nparts] first and one-past-last group of 64 vectors that hold a logit of the part
+    const uint32_t* stab;     // [nparts][NV] per vector: staged index of its first logit of the part | which of its
+                              //     elements belong to the part << 16
+    const int32_t* pl_g;      // [nC+1] first group of every chunk's pair list
+    const uint2* pl_e;        // pairs grouped by chunk (two per lane and group), kPairU groups of slack at the end
+};
+// pairs a part may hold, and the index of the -inf logit
+template <int DT> constexpr int part_cap() { return (kPartBytes - kTrashBytes - 16) / Traits<DT>::ESZ; }
+template <int DT> constexpr int dummy_index() { return part_cap<DT>(); }
+static_assert(dummy_index<TLI_BF16>() < (1 << 16) && dummy_index<TLI_F32>() < (1 << 16), "16-bit staged index");
+
+// NaN or +inf among the staged drafter logits must surface (-inf is legal).  As signed integers the raw
+// patterns of +inf and the positive NaNs are the largest values, as unsigned ones the negative NaNs are (just
+// above -inf): two running maxima, taken on both halves of a dword at once for bf16.
+template <int DT> struct BadTrack;
+template <> struct BadTrack<TLI_BF16> {
+    typedef short s2v __attribute__((ext_vector_type(2)));
+    typedef unsigned short us2v __attribute__((ext_vector_type(2)));
+    s2v sm = {(short)-32768, (short)-32768};
+    us2v um = {0, 0};
+    __device__ __forceinline__ void add(uint32_t w) {
+        sm = __builtin_elementwise_max(sm, __builtin_bit_cast(s2v, w));
+        um = __builtin_elementwise_max(um, __builtin_bit_cast(us2v, w));
+    }
+    __device__ __forceinline__ void add_one(uint32_t raw) { add(raw | (raw << 16)); }
+    __device__ __forceinline__ bool bad() const {
+        return sm.x >= (short)0x7f80 || sm.y >= (short)0x7f80 || um.x > 0xff80u || um.y > 0xff80u;
+    }
+};
+template <> struct BadTrack<TLI_F32> {
+    int32_t sm = INT32_MIN;
+    uint32_t um = 0;
+    __device__ __forceinline__ void add(uint32_t w) {
+        sm = max(sm, (int32_t)w);
+        um = max(um, w);
+    }
+    __device__ __forceinline__ void add_one(uint32_t raw) { add(raw); }
+    __device__ __forceinline__ bool bad() const { return sm >= 0x7f800000 || um > 0xff800000u; }
+};
+
+// DIAG (acceptance-rate diagnostics): the items are all B*K positions instead of one row per sequence, and a
+// second sum runs beside the first with the drafter's unrestricted probabilities q = q' * 2^-dq:
+// mn = sum min(p, q') (TLI's expected acceptance rate), mn2 = sum min(p, q) (the union algorithm's).
+template <int DT, bool DIAG>
+__global__ __launch_bounds__(kScanWG) void k_final_scan(
+    const void* __restrict__ logits_t, DrafterView dv, int B, int K, int Vt, int Vd, int nC, int nsplit, ScanLists ls,
+    float cs_t, double ratio_t, const FinalRow* __restrict__ frow, float* __restrict__ tab_ref, float* __restrict__ tab_s, double* __restrict__ mn, double* __restrict__ mn2,
+    int32_t* __restrict__ fbad) {
+    constexpr int EPV = Traits<DT>::EPV;
+    constexpr int ESZ = Traits<DT>::ESZ;
+    typedef typename std::conditional<DT == TLI_BF16, uint16_t, uint32_t>::type raw_t;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[kScanLds];
+    unsigned char* const part = lds + kTrashBytes;  // staged logit i at part + i * ESZ
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  The workgroups of one sequence
+    // stream the same rows, so they are given ids that land on the same XCD, next to each other in time:
+    // id = slot * 8 + xcd, sequence = (slot / per_seq) * 8 + xcd, (part, split) = slot % per_seq.
+    const int nparts = ls.nparts;
+    const int per_seq = nparts * nsplit;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int b = (slot / per_seq) * 8 + xcd, sub = slot % per_seq;
+    const int p = sub / nsplit, sp = sub - p * nsplit;
+    if (b >= B) return;
+    // What the part is and where the lists of this wave's chunks begin do not depend on the sequence: they are
+    // fetched beside the sequence's record rather than after it.
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int c_lo = ls.cb[p], c_hi = ls.cb[p + 1];
+    const int2 gr = ls.grange[p];
+    const int ns = ls.part_n[p];
+    const int ncp = c_hi - c_lo;  // 1 .. kMaxPartChunks
+    const int gw = sp * kScanWaves + wave, stride = nsplit * kScanWaves;  // this wave takes chunks gw, gw + stride, ...
+    const int32_t* __restrict__ pl_g = ls.pl_g;
+    const uint2* __restrict__ pl_e = ls.pl_e;
+    // The list bounds (in groups of kPairG entries) of the wave's chunks: lane k holds those of its k-th chunk,
+    // lanes past the wave's last chunk those of the part's first chunk.
+    int2 gbv;
+    {
+        const int idx = gw + lane * stride;
+        const int c = c_lo + (idx < ncp ? idx : 0);
+        gbv = make_int2(pl_g[c], pl_g[c + 1]);
+    }
+    const FinalRow f = frow[b];
+    if (f.skip) return;
+    if (f.bonus) {
+        const u4v* rowk = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) + (int64_t)f.t_row * Vt * ESZ);
+        float* br = tab_ref + (int64_t)b * nC;
+        float* bs = tab_s + (int64_t)b * nC;
+        const int cps = (nC + per_seq - 1) / per_seq;
+        scan_chunks<DT, false, kScanWaves>(rowk, Vt, min(nC, sub * cps), min(nC, (sub + 1) * cps), cs_t,
+                                           (float)(ratio_t - 1.0), nullptr, [&](int c, float r, float sc) {
+                                               if (lane == 0) { br[c] = r; bs[c] = sc; }
+                                           });
+        return;
+    }
+    if (!f.rp.use_q) return;  // q' = 0 everywhere: the masses are the chunk sums of p, nothing to subtract
+    // rows as byte pointers: every offset below fits 32 bits, which keeps the address arithmetic to one instruction
+    const char* __restrict__ drow = static_cast<const char*>(dv.base) + (int64_t)f.d_row * dv.row_stride * ESZ;
+    const char* __restrict__ trow = static_cast<const char*>(logits_t) + (int64_t)f.t_row * Vt * ESZ;
+    const int nvec = (Vt + EPV - 1) / EPV;
+
+    struct Fetched {
+        u4v v[kLoads];
+        uint2 e[kPairU];
+    };
+    // Loads of the wave's chunk number k and of the head of its pair list.  Past the end of the part every lane
+    // reads lane 0's addresses of the part's first chunk: a few cache lines, nothing new.
+    auto fetch = [&](int k, Fetched& r) {
+        const int idx = gw + k * stride;
+        const bool ok = idx < ncp;
+        const int c = c_lo + (ok ? idx : 0);
+        const uint32_t ln = ok ? lane : 0;
+        const uint32_t g0 = __builtin_amdgcn_readlane(gbv.x, k);
+        const uint32_t v0 = (uint32_t)c * (kLoads * kWave) + ln;
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j)  // vectors past the row's end re-read its last vector: no pair points there
+            r.v[j] = *reinterpret_cast<const u4v*>(trow + min(v0 + j * kWave, (uint32_t)nvec - 1u) * 16u);
+        const char* ep = reinterpret_cast<const char*>(pl_e) + (size_t)g0 * (kWave * 8);
+#pragma unroll
+        for (int k2 = 0; k2 < kPairU; ++k2) r.e[k2] = *reinterpret_cast<const uint2*>(ep + (ln * 8u + k2 * (kWave * 8)));
+    };
+    Fetched fa, fb;
+    fetch(0, fa);
+
+    // ---- (1) the drafter logits of this part's pairs -> LDS
+    {
+        const int nvd = (ls.row_elems + EPV - 1) / EPV;
+        // The part's groups of 64 vectors are dealt to the waves in equal runs.  (The waves of a workgroup do not
+        // start together: they are launched four at a time, the last four some 17,000 cycles after the first.
+        // Giving the early ones more of the sweep was tried and moved the barrier by little: the late waves'
+        // own first round trips to memory are what it waits for.)
+        const int per_wave = (gr.y - gr.x + kScanWaves - 1) / kScanWaves;
+        const int gbeg = gr.x + wave * per_wave, gend = min(gbeg + per_wave, gr.y);
+        if (tid == 0)
+            *reinterpret_cast<uint32_t*>(part + dummy_index<DT>() * ESZ) = DT == TLI_BF16 ? 0xff80ff80u : 0xff800000u;
+        const uint32_t mine = (uint32_t)lane * 4;  // the lane's scratch word
+        const char* __restrict__ stab = reinterpret_cast<const char*>(ls.stab + (int64_t)p * ls.NV);
+        const uint32_t vlast = (uint32_t)min(gend * kWave, nvd) - 1u;  // the wave's last vector
+        for (int g0 = gbeg; g0 < gend; g0 += kStageV) {  // wave-uniform
+            u4v v[kStageV];
+            uint32_t tv[kStageV];
+#pragma unroll
+            for (int u = 0; u < kStageV; ++u) {
+                // past the wave's last vector: that vector is done again, the same bytes to the same places
+                const uint32_t vi = min((uint32_t)(g0 + u) * kWave + lane, vlast);
+                v[u] = *reinterpret_cast<const u4v*>(drow + vi * 16u);
+                tv[u] = *reinterpret_cast<const uint32_t*>(stab + vi * 4u);
+            }
+#pragma unroll
+            for (int u = 0; u < kStageV; ++u) {
+                const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+                // d = (LDS address of the lane's next kept logit) - mine, so address = mine + keep * d
+                uint32_t d = kTrashBytes + (tv[u] & 0xffffu) * ESZ - mine;
+#pragma unroll
+                for (int i = 0; i < EPV; ++i) {
+                    const uint32_t k1 = (tv[u] >> (16 + i)) & 1u;
+                    uint32_t at;  // = mine + k1 * d (d < 2^24; written out because the compiler would mask d first)
+                    asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(at) : "v"(k1), "v"(d), "v"(mine));
+                    if (DT == TLI_BF16)
+                        *reinterpret_cast<uint16_t*>(lds + at) = (uint16_t)(i & 1 ? w[i >> 1] >> 16 : w[i >> 1]);
+                    else
+                        *reinterpret_cast<uint32_t*>(lds + at) = w[i];
+                    // d += k1 * ESZ, likewise (the compiler would keep a count and rebuild d from it, an instruction more)
+                    asm("v_lshl_add_u32 %0, %1, %2, %0" : "+v"(d) : "v"(k1), "n"(ESZ == 2 ? 1 : 2));
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // NaN / +inf among the staged logits (the flag is stored at the very end: a pending store would turn every
+    // wait for a load into a wait for all of them)
+    BadTrack<DT> bt;
+    {
+        const int nfull = ns / EPV;
+        const uint4* lv = reinterpret_cast<const uint4*>(part);
+        for (int o = tid; o < nfull; o += kScanWG) {
+            const uint4 w = lv[o];
+            bt.add(w.x); bt.add(w.y); bt.add(w.z); bt.add(w.w);
+        }
+        if (tid < ns - nfull * EPV) bt.add_one(reinterpret_cast<const raw_t*>(part)[nfull * EPV + tid]);
+    }
+
+    // ---- (2) stream target chunks past it
+    double* my_mn = mn + (int64_t)b * nC;
+    double* my_mn2 = DIAG ? mn2 + (int64_t)b * nC : nullptr;
+    const ResidualParams rp = f.rp;
+    const uint32_t tb = (uint32_t)(kPartBytes + wave * kSlotBytes);
+    // log2 p = x*ct - Lp and log2 q' = y*cd - Lq in two-term form.  The subtrahends are pinned to vector registers:
+    // an instruction may read one scalar register only, and the compiler would otherwise copy them over per use.
+    float nlp_hi = -rp.lp_hi, nlp_lo = -rp.lp_lo, nlq_hi = -rp.lq_hi, nlq_lo = -rp.lq_lo;
+    asm volatile("" : "+v"(nlp_hi), "+v"(nlp_lo), "+v"(nlq_hi), "+v"(nlq_lo));
+    // min(p, q') of one pair = 2^min(log2 p, log2 q'): one exponential per pair
+    const float dq = f.dq;
+    auto pair_min = [&](uint32_t e, float& second) -> float {
+        const uint32_t xr = *reinterpret_cast<const raw_t*>(lds + (tb + (e & 0xffffu)));
+        const uint32_t yr = *reinterpret_cast<const raw_t*>(part + (e >> kPairShift) * ESZ);
+        const float xv = as_f(DT == TLI_BF16 ? xr << 16 : xr), yv = as_f(DT == TLI_BF16 ? yr << 16 : yr);
+        const float a = fmaf(xv, rp.ct_hi, nlp_hi) + fmaf(xv, rp.ct_lo, nlp_lo);
+        const float bq = fmaf(yv, rp.cd_hi, nlq_hi) + fmaf(yv, rp.cd_lo, nlq_lo);
+        if (DIAG) second = exp2_hw(fminf(a, bq - dq));
+        return exp2_hw(fminf(a, bq));
+    };
+    // Results stay in registers until the wave is through (lane k keeps the sum of the wave's k-th chunk):
+    // a store shares the loads' completion counter and completes out of order with them, so while one may
+    // be pending every wait for a load degrades to a wait for all loads.
+    double keep = 0.0, keep2 = 0.0;
+    auto process = [&](const Fetched& r, int k) {
+        u4v* st = reinterpret_cast<u4v*>(lds + tb);
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) st[j * kWave + lane] = r.v[j];
+        // one wave writes and reads its slot: its LDS operations execute in order and the compiler keeps
+        // may-alias accesses in program order; the wave barrier only pins the schedule
+        __builtin_amdgcn_wave_barrier();
+        float acc = 0.f, acc2 = 0.f;
+        auto two = [&](uint2 e) {
+            float u0 = 0.f, u1 = 0.f;
+            const float t0 = pair_min(e.x, u0), t1 = pair_min(e.y, u1);
+            acc += t0 + t1;
+            if (DIAG) acc2 += u0 + u1;
+        };
+        const int g0 = __builtin_amdgcn_readlane(gbv.x, k), g1 = __builtin_amdgcn_readlane(gbv.y, k);
+        const int ng = g1 - g0;
+#pragma unroll
+        for (int k2 = 0; k2 < kPairU; ++k2)
+            if (k2 < ng) two(r.e[k2]);  // wave-uniform test
+        for (int g = g0 + kPairU; g < g1; ++g) two(pl_e[(int64_t)g * kWave + lane]);  // crowded chunk: the rest
+        __builtin_amdgcn_wave_barrier();  // the slot is rewritten by the next chunk
+        // A chunk's sum is taken in fp32: a lane's dozen-odd terms in turn, the 64 lane totals on the DPP network
+        // (one instruction per step; a double takes five).  That is a relative 1e-7, the size of the exponential's
+        // own error; chunk sums are combined in fp64 downstream.
+        const float tot = wave_sum(acc);
+        if (lane == k) keep = (double)tot;
+        if (DIAG) {
+            const float tot2 = wave_sum(acc2);
+            if (lane == k) keep2 = (double)tot2;
+        }
+    };
+    int k = 0;
+    for (int idx = gw; idx < ncp; idx += 2 * stride, k += 2) {
+        fetch(k + 1, fb);
+        process(fa, k);
+        fetch(k + 2, fa);
+        if (idx + stride < ncp) process(fb, k + 1);
+    }
+    {
+        const int idx = gw + lane * stride;
+        if (idx < ncp) {
+            my_mn[c_lo + idx] = keep;
+            if (DIAG) my_mn2[c_lo + idx] = keep2;
+        }
+    }
+    if (bt.bad()) fbad[b] = 1;
+}
+
+// kernel: draw the extra token of every sequence from its row's chunk tables.  grid (B), kLoads waves: every wave
+// finds the chunk for itself (the tables are small and shared), then each takes a quarter of the chunk.
+template <int DT>
+__global__ __launch_bounds__(kLoads * kWave) void k_final_pick(const void* __restrict__ logits_t, DrafterView dv,
+                                                       int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
+                                                       const FinalRow* __restrict__ frow,
+                                                       const int32_t* __restrict__ t2d,
+                                                       const float* __restrict__ tab_ref,
+                                                       const float* __restrict__ tab_s,
+                                                       const float2* __restrict__ ctab,
+                                                       const double* __restrict__ mn,
+                                                       const int32_t* __restrict__ fbad, FinalOut o) {
+    const int b = blockIdx.x;
+    const FinalRow f = frow[b];
+    if (f.skip) return;
+    final_pick_row<DT>(f, b, logits_t, dv, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
+                       tab_s + (int64_t)b * nC, ctab, mn + (int64_t)b * nC, fbad, o);
+}
