@@ -45,7 +45,8 @@ typedef enum {
     TLI_ERR_NOT_INJECTIVE = -3,      /* two drafter ids map to the same target id                      */
     TLI_ERR_EMPTY_INTERSECTION = -4, /* no shared token: q' would be 0/0 and nothing can be accepted   */
     TLI_ERR_ALLOC = -5,              /* device allocation failed, or the workspace is too small        */
-    TLI_ERR_HIP = -6                 /* a HIP runtime call failed                                      */
+    TLI_ERR_HIP = -6,                /* a HIP runtime call failed                                      */
+    TLI_ERR_INTERNAL = -7            /* the library's own tables failed their consistency check        */
 } tli_status;
 
 /* bits of row_status / seq_status */
@@ -70,6 +71,20 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
 void tli_free_map(tli_map* map);
 /* Vd, Vt and |T∩D| of a map (any pointer may be NULL). */
 int tli_map_info(const tli_map* map, int32_t* Vd, int32_t* Vt, int32_t* num_shared);
+/*
+ * Host-only rehearsal of tli_build_map (intersection algorithm: everything it needs to know about T∩D): runs the
+ * same argument checks and builds the same tables, touches no device, and then replays on the host what the
+ * residual-scan kernel does with them, for both storage types and both drafter-row layouts: every index the kernel
+ * would form must stay inside the tables and the LDS area it addresses, every staged slot must be written exactly
+ * once, and every shared pair (target id, drafter id) must be visited exactly once with both sides matching d2t.
+ *   out_num_shared   : receives |T∩D| (may be NULL)
+ *   out_nparts [2]   : receives the number of parts the target chunks are cut into, per tli_dtype (may be NULL)
+ *   out_failed_check : receives 0, or a number naming the check that failed (may be NULL)
+ * Returns what tli_build_map would return for these arguments short of ALLOC/HIP, or TLI_ERR_INTERNAL if a
+ * consistency check fails (a defect of the library, never of the input).
+ */
+int tli_map_dry_run(const int32_t* d2t_host, int32_t Vd, int32_t Vt, int32_t* out_num_shared, int32_t* out_nparts,
+                    int32_t* out_failed_check);
 
 /*
  * Bytes of device scratch that tli_draft_sample (with R <= B*K rows) and tli_verify (with these B, K)

@@ -24,7 +24,7 @@ EXPORTS = (
     "tli_union_draft_sample", "tli_union_verify", "tli_acceptance_rates_workspace_bytes", "tli_acceptance_rates",
     "tli_sample_rows_workspace_bytes", "tli_sample_rows", "tli_greedy_draft", "tli_exact_match_workspace_bytes",
     "tli_exact_match_verify", "tli_draft_sample_compact", "tli_verify_compact",
-    "tli_warp_workspace_bytes", "tli_warp_rows",
+    "tli_warp_workspace_bytes", "tli_warp_rows", "tli_map_dry_run",
 )
 KERNELS = ("lse", "accept", "final_scan", "final_pick", "draft_scan", "draft_pick")
 
@@ -161,6 +161,18 @@ def tli_build_map(d2t, Vt: int) -> TliMap:
     if rc != 0:
         raise TliError(rc, "tli_build_map")
     return TliMap(out.value, int(arr.shape[0]), int(Vt), S.value)
+
+
+def tli_map_dry_run(d2t, Vt: int) -> dict:
+    """Host-only rehearsal of tli_build_map: same checks and tables, no device, plus the library's replay of what
+    the residual-scan kernel does with them.  Returns status, num_shared, nparts (per dtype) and failed_check."""
+    lib = load_library()
+    arr = np.ascontiguousarray(np.asarray(d2t), dtype=np.int32)
+    S, bad = ctypes.c_int32(), ctypes.c_int32()
+    nparts = (ctypes.c_int32 * 2)()
+    rc = lib.tli_map_dry_run(arr.ctypes.data_as(ctypes.c_void_p), arr.shape[0], int(Vt), ctypes.byref(S), nparts,
+                             ctypes.byref(bad))
+    return dict(status=int(rc), num_shared=S.value, nparts=(nparts[0], nparts[1]), failed_check=bad.value)
 
 
 def tli_workspace_bytes(B: int, K: int, Vt: int, Vd: int, dtype: int) -> int:

@@ -479,16 +479,34 @@ const char* tli_status_string(int status) {
         case TLI_ERR_EMPTY_INTERSECTION: return "TLI_ERR_EMPTY_INTERSECTION";
         case TLI_ERR_ALLOC: return "TLI_ERR_ALLOC";
         case TLI_ERR_HIP: return "TLI_ERR_HIP";
+        case TLI_ERR_INTERNAL: return "TLI_ERR_INTERNAL";
         default: return "TLI_ERR_UNKNOWN";
     }
 }
 
-int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out_map, int32_t* out_num_shared) {
-    if (out_map) *out_map = nullptr;
-    if (out_num_shared) *out_num_shared = 0;
-    if (!d2t_host || !out_map || Vd < 1 || Vt < 1) return TLI_ERR_INVALID_ARG;
+namespace {
+
+// Everything tli_build_map computes before it touches the device.
+struct HostScan {  // the residual scan's lists for one dtype (see tli_map::Scan)
+    std::vector<int32_t> cb, part_n, pl_g;
+    int NV[2];
+    std::vector<uint32_t> stab[2];
+    std::vector<int2> grange[2];
+    std::vector<uint2> pl_e[2];
+};
+struct HostMap {
+    int32_t S = 0;
+    std::vector<int32_t> d2t, t2d, sh_x;
+    HostScan hs[2];
+    std::vector<uint64_t> lmask[2];
+};
+
+int build_host_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, HostMap& hm) {
+    if (!d2t_host || Vd < 1 || Vt < 1) return TLI_ERR_INVALID_ARG;
     const size_t Vd_pad = ((size_t)Vd + 7) & ~(size_t)7, Vt_pad = ((size_t)Vt + 7) & ~(size_t)7;
-    std::vector<int32_t> d2t(Vd_pad, -1), t2d(Vt_pad, -1);
+    std::vector<int32_t>&d2t = hm.d2t, &t2d = hm.t2d, &sh_x = hm.sh_x;
+    d2t.assign(Vd_pad, -1);
+    t2d.assign(Vt_pad, -1);
     int32_t S = 0;
     for (int32_t x = 0; x < Vd; ++x) {
         const int32_t t = d2t_host[x];
@@ -500,20 +518,16 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
         ++S;
     }
     if (S == 0) return TLI_ERR_EMPTY_INTERSECTION;
-    // rank -> drafter id, and per dtype the pair lists of the residual scan (see tli_map)
-    std::vector<int32_t> sh_x(S);
+    hm.S = S;
+    // rank -> drafter id, and per dtype the lists of the residual scan (see tli_map)
+    sh_x.resize(S);
     {
         int32_t r = 0;
         for (int32_t x = 0; x < Vd; ++x)
             if (d2t[x] >= 0) sh_x[r++] = x;
     }
-    struct HostScan {
-        std::vector<int32_t> cb, part_n, pl_g;
-        int NV[2];
-        std::vector<uint32_t> stab[2];
-        std::vector<int2> grange[2];
-        std::vector<uint2> pl_e[2];
-    } hs[2];
+    HostScan* hs = hm.hs;
+    std::vector<uint64_t>* lmask = hm.lmask;
     for (int dt = 0; dt < 2; ++dt) {
         HostScan& h = hs[dt];
         const int CH = dt == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
@@ -588,7 +602,6 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
         }
     }
     // shared-id mask of the drafter vocabulary in lane-mask layout (see mask_bits), padded to whole chunks
-    std::vector<uint64_t> lmask[2];
     for (int dt = 0; dt < 2; ++dt) {
         const int epv = dt == TLI_BF16 ? 8 : 4;
         const int chunk = kWave * kLoads * epv;
@@ -600,6 +613,128 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
             lmask[dt][(vi >> 6) * epv + (x % epv)] |= 1ull << (vi & 63);
         }
     }
+    return TLI_OK;
+}
+
+// Replays, on the host, what the residual scan does with the lists of one dtype and one row layout -- the sweep
+// that packs a part's drafter logits into LDS, then the walk over every chunk's pair list -- and checks that
+// every read stays inside what was built, that every staged slot is written once, and that every shared pair
+// (target id, drafter id) is visited exactly once, its two sides matching the map.  0 if so, else the number of
+// the first check that failed.
+int check_host_scan(const HostMap& hm, int32_t Vd, int32_t Vt, int dt, int layout) {
+    const HostScan& h = hm.hs[dt];
+    const int CH = dt == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
+    const int cap = dt == TLI_BF16 ? part_cap<TLI_BF16>() : part_cap<TLI_F32>();
+    const uint32_t dummy_idx = (uint32_t)(dt == TLI_BF16 ? dummy_index<TLI_BF16>() : dummy_index<TLI_F32>());
+    const int epv = dt == TLI_BF16 ? 8 : 4;
+    const uint32_t esz = dt == TLI_BF16 ? 2 : 4;
+    const int nC = (Vt + CH - 1) / CH;
+    const int nparts = (int)h.part_n.size();
+    const int64_t elems = layout ? hm.S : Vd;
+    const int64_t nvd = (elems + epv - 1) / epv;
+    const int NV = h.NV[layout];
+    if ((int)h.cb.size() != nparts + 1 || h.cb[0] != 0 || h.cb[nparts] != nC || (int)h.pl_g.size() != nC + 1) return 1;
+    if (NV % kWave != 0 || NV < nvd || h.stab[layout].size() != (size_t)nparts * NV) return 2;
+    if (h.pl_e[layout].size() != ((size_t)h.pl_g[nC] + kPairU) * kWave) return 3;
+    int64_t total = 0;
+    std::vector<std::vector<int64_t>> staged(nparts);
+    for (int p = 0; p < nparts; ++p) {
+        const int nch = h.cb[p + 1] - h.cb[p];
+        if (nch < 1 || nch > kMaxPartChunks || h.part_n[p] < 0 || h.part_n[p] > cap) return 4;
+        total += h.part_n[p];
+        staged[p].assign(h.part_n[p], -1);
+        const int2 gr = h.grange[layout][p];
+        if (gr.x < 0 || gr.y > NV / kWave || (h.part_n[p] > 0 && gr.x >= gr.y)) return 5;
+        for (int64_t vi = 0; vi < NV; ++vi) {
+            const uint32_t w = h.stab[layout][(size_t)p * NV + vi];
+            const bool swept = vi >= (int64_t)gr.x * kWave && vi < (int64_t)gr.y * kWave && vi < nvd;
+            if (!swept) {
+                if (w >> 16) return 6;  // a logit the sweep never reaches
+                continue;
+            }
+            uint32_t idx = w & 0xffffu;
+            for (int i = 0; i < epv; ++i) {
+                if (!((w >> (16 + i)) & 1u)) continue;
+                const int64_t e = vi * epv + i;
+                if (e >= elems || idx >= (uint32_t)h.part_n[p] || staged[p][idx] != -1) return 7;
+                staged[p][idx++] = e;
+            }
+        }
+        for (int64_t e : staged[p])
+            if (e < 0) return 8;
+    }
+    if (total != hm.S) return 9;
+    std::vector<uint8_t> seen(hm.S, 0);
+    std::vector<int32_t> rank_of(Vd, -1);
+    for (int32_t r = 0; r < hm.S; ++r) rank_of[hm.sh_x[r]] = r;
+    int64_t visited = 0;
+    int p = 0;
+    for (int c = 0; c < nC; ++c) {
+        while (c >= h.cb[p + 1]) ++p;
+        if (h.pl_g[c + 1] < h.pl_g[c]) return 10;
+        for (int64_t g = h.pl_g[c]; g < h.pl_g[c + 1]; ++g)
+            for (int l = 0; l < kWave; ++l) {
+                const uint2 two = h.pl_e[layout][(size_t)g * kWave + l];
+                for (uint32_t e : {two.x, two.y}) {
+                    const uint32_t toff = e & 0xffffu, idx = e >> kPairShift;
+                    if (idx == dummy_idx) {
+                        if (toff != 0) return 11;
+                        continue;
+                    }
+                    if (toff % esz || toff / esz >= (uint32_t)CH || idx >= (uint32_t)h.part_n[p]) return 12;
+                    const int64_t t = (int64_t)c * CH + toff / esz;
+                    const int64_t x = layout ? hm.sh_x[staged[p][idx]] : staged[p][idx];
+                    if (t >= Vt || hm.d2t[x] != t) return 13;
+                    const int32_t r = rank_of[x];
+                    if (seen[r]) return 14;
+                    seen[r] = 1;
+                    ++visited;
+                }
+            }
+    }
+    if (visited != hm.S) return 15;
+    for (size_t i = (size_t)h.pl_g[nC] * kWave; i < h.pl_e[layout].size(); ++i) {  // the slack behind the last list
+        const uint2 two = h.pl_e[layout][i];
+        if (two.x != dummy_idx << kPairShift || two.y != dummy_idx << kPairShift) return 16;
+    }
+    return 0;
+}
+
+}  // namespace
+
+int tli_map_dry_run(const int32_t* d2t_host, int32_t Vd, int32_t Vt, int32_t* out_num_shared, int32_t* out_nparts,
+                    int32_t* out_failed_check) {
+    if (out_num_shared) *out_num_shared = 0;
+    if (out_failed_check) *out_failed_check = 0;
+    HostMap hm;
+    const int rc = build_host_map(d2t_host, Vd, Vt, hm);
+    if (rc != TLI_OK) return rc;
+    if (out_num_shared) *out_num_shared = hm.S;
+    for (int dt = 0; dt < 2; ++dt) {
+        if (out_nparts) out_nparts[dt] = (int32_t)hm.hs[dt].part_n.size();
+        for (int layout = 0; layout < 2; ++layout) {
+            const int bad = check_host_scan(hm, Vd, Vt, dt, layout);
+            if (bad) {
+                if (out_failed_check) *out_failed_check = 1000 * (2 * dt + layout + 1) + bad;
+                return TLI_ERR_INTERNAL;
+            }
+        }
+    }
+    return TLI_OK;
+}
+
+int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out_map, int32_t* out_num_shared) {
+    if (out_map) *out_map = nullptr;
+    if (out_num_shared) *out_num_shared = 0;
+    if (!out_map) return TLI_ERR_INVALID_ARG;
+    HostMap hm;
+    const int rc = build_host_map(d2t_host, Vd, Vt, hm);
+    if (rc != TLI_OK) return rc;
+    const int32_t S = hm.S;
+    const std::vector<int32_t>&d2t = hm.d2t, &t2d = hm.t2d, &sh_x = hm.sh_x;
+    const HostScan* hs = hm.hs;
+    const std::vector<uint64_t>* lmask = hm.lmask;
+    const size_t Vd_pad = d2t.size(), Vt_pad = t2d.size();
     tli_map* m = new (std::nothrow) tli_map();
     if (!m) return TLI_ERR_ALLOC;
     m->Vd = Vd; m->Vt = Vt; m->S = S; m->d2t = nullptr; m->t2d = nullptr; m->lmask[0] = m->lmask[1] = nullptr;

@@ -90,3 +90,31 @@ def test_new_entry_points_reject_null_arguments(lib):
     assert lib.tli_sample_rows_workspace_bytes(0, 8, 0) == 0 and lib.tli_sample_rows_workspace_bytes(4, 1000, 1) > 0
     assert lib.tli_exact_match_workspace_bytes(2, 64, 100, 0) == 0 and lib.tli_exact_match_workspace_bytes(2, 3, 100, 0) > 0
     assert lib.tli_warp_workspace_bytes(3, 100, 1) > 0 and lib.tli_warp_workspace_bytes(3, 100, 9) == 0
+
+
+def test_map_tables_replayed_on_the_host(lib):
+    """tli_map_dry_run builds the map's tables without a device and replays what the residual-scan kernel does
+    with them (sweep of the drafter row into LDS slots, walk of every chunk's pair list): in bounds, every slot
+    written once, every shared pair visited once with both sides matching d2t.  Shapes: one and several parts for
+    both storage types, sparse and identical vocabularies, a single shared token, rows of more than 1024 chunks,
+    shared ids bunched at one end of either vocabulary."""
+    from paper_2502_05202_amd import synth
+    cases = [(64, 48, 32), (128256, 32000, 24000), (151936, 49152, 40000), (256000, 128256, 90000),
+             (202048, 128256, 60000), (2048 * 3, 2048 * 3, 2048 * 3), (70000, 60000, 50000), (8, 8, 1),
+             (1024 * 1100 + 12, 3000, 2000), (50000, 20000, 1)]
+    for Vt, Vd, S in cases:
+        d2t = synth.make_d2t(Vd, Vt, S, seed=Vt + S)
+        r = binding.tli_map_dry_run(d2t, Vt)
+        assert r["status"] == 0 and r["failed_check"] == 0 and r["num_shared"] == S, (Vt, Vd, S, r)
+        assert r["nparts"][0] >= r["nparts"][1] >= 1  # fp32 logits take twice the LDS of bf16 ones
+    assert binding.tli_map_dry_run(synth.make_d2t(128256, 256000, 90000, seed=1), 256000)["nparts"] == (4, 2)
+    # bunched: the first S drafter ids map to the last S target ids, in reverse
+    Vd, Vt, S = 40000, 90000, 30000
+    d2t = np.full(Vd, -1, np.int32)
+    d2t[:S] = Vt - 1 - np.arange(S)
+    assert binding.tli_map_dry_run(d2t, Vt)["status"] == 0
+    # the same argument checks as tli_build_map
+    assert binding.tli_map_dry_run([0, 1, 7], 7)["status"] == -2
+    assert binding.tli_map_dry_run([3, 1, 3], 7)["status"] == -3
+    assert binding.tli_map_dry_run([-1, -1], 7)["status"] == -4
+    assert binding.status_string(-7) == "TLI_ERR_INTERNAL"
