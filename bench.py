@@ -221,6 +221,25 @@ def main():
                     peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
                     traffic=MEASURED_TRAFFIC_BYTES.get(w.name),
                     bytes_per_launch=lse_bytes, avg_launch_us=round(1e6 * lse_avg_s, 2), launches=lse_n)
+    # the second yardstick: a read-only pass with plain 16-byte loads over the very rows k_lse reads (the target
+    # tensor, a workgroup per row as in k_lse; the row's tail beyond whole 4 KB chunks is left out)
+    row_bytes = w.Vt * esz // 4096 * 4096
+    if row_bytes and (w.Vt * esz) % 16 == 0:
+        flat = inp["logits_t"].reshape(-1)
+        rd_out = torch.zeros(flat.numel() * esz // row_bytes + 1, dtype=torch.int32, device=dev)
+        n_rd = max(5, args.steps // 8)
+        read_gbs = {}
+        for nt in (0, 1):
+            if (w.Vt * esz) % 4096 == 0:  # rows are whole chunks: read the tensor as it lies
+                fn = lambda: binding.tli_calib_read(flat, row_bytes, bool(nt), rd_out)
+                nbytes = flat.numel() * esz
+            else:  # read whole chunks of a contiguous stretch of the same size
+                nbytes = flat.numel() * esz // row_bytes * row_bytes
+                fn = lambda: binding.tli_calib_read(flat, row_bytes, bool(nt), rd_out, nbytes=nbytes)
+            fn()
+            read_gbs["nontemporal" if nt else "plain"] = round(nbytes / (1e-3 * time_call(fn, n_rd)) / 1e9, 1)
+        roofline["read_kernel_gbs"] = read_gbs
+        roofline["frac_of_read_kernel"] = round(achieved / max(read_gbs.values()), 4)
     extra = dict(
         draft_ms=round(draft_ms, 4), verify_ms=round(verify_ms, 4),
         verify_only_positions_per_s=round(positions / (1e-3 * verify_ms), 1),

@@ -288,6 +288,18 @@ void tli_profile_disable(void);
  * compared with its known traffic (bytes read + bytes written) to calibrate those counters.
  */
 int tli_calib_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_stream);
+/*
+ * Benchmark utility (not part of the method): a read-only streaming pass over `bytes` of device memory with plain
+ * 16-byte loads, the yardstick beside the vendor's peak that the streaming kernels are held against.  The buffer is
+ * read as bytes / slab_bytes contiguous slabs, a workgroup of 256 threads per slab, in the access pattern of the
+ * normaliser kernel (slab_bytes = one logit row's bytes gives that kernel's launch shape).
+ *   src_dev      dev, 16-byte aligned; bytes a multiple of slab_bytes; slab_bytes a multiple of 4096
+ *   nontemporal  0: ordinary loads, 1: loads that bypass cache allocation (what the kernels use)
+ *   out_dev      dev [bytes / slab_bytes] uint32 scratch (a word per workgroup; practically never written)
+ * Only enqueues a kernel on the stream.
+ */
+int tli_calib_read(const void* src_dev, size_t bytes, size_t slab_bytes, int32_t nontemporal, uint32_t* out_dev,
+                   void* hip_stream);
 
 /* Human-readable name of a tli_status value. */
 const char* tli_status_string(int status);

@@ -24,7 +24,7 @@ EXPORTS = (
     "tli_union_draft_sample", "tli_union_verify", "tli_acceptance_rates_workspace_bytes", "tli_acceptance_rates",
     "tli_sample_rows_workspace_bytes", "tli_sample_rows", "tli_greedy_draft", "tli_exact_match_workspace_bytes",
     "tli_exact_match_verify", "tli_draft_sample_compact", "tli_verify_compact",
-    "tli_warp_workspace_bytes", "tli_warp_rows", "tli_map_dry_run",
+    "tli_warp_workspace_bytes", "tli_warp_rows", "tli_map_dry_run", "tli_calib_read",
 )
 KERNELS = ("lse", "accept", "final_scan", "final_pick", "draft_scan", "draft_pick")
 
@@ -98,6 +98,10 @@ def load_library() -> ctypes.CDLL:
     lib.tli_profile_disable.restype = None
     lib.tli_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.tli_calib_copy.restype = ctypes.c_int
+    lib.tli_calib_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_size_t, i32, vp, vp]
+    lib.tli_calib_read.restype = ctypes.c_int
+    lib.tli_map_dry_run.argtypes = [vp, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.tli_map_dry_run.restype = ctypes.c_int
     lib.tli_status_string.argtypes = [ctypes.c_int]
     lib.tli_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -444,3 +448,14 @@ def tli_calib_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
     rc = load_library().tli_calib_copy(_ptr(src), _ptr(dst), n, _stream(stream))
     if rc != 0:
         raise TliError(rc, "tli_calib_copy")
+
+
+def tli_calib_read(src: torch.Tensor, slab_bytes: int, nontemporal: bool, out: torch.Tensor, nbytes: int | None = None,
+                   stream=None) -> None:
+    """Read-only streaming pass over the first nbytes of src (default: all) in slabs of slab_bytes, one workgroup each;
+    out: uint32/int32 device scratch with a word per slab."""
+    n = src.numel() * src.element_size() if nbytes is None else int(nbytes)
+    assert out.numel() >= n // slab_bytes
+    rc = load_library().tli_calib_read(_ptr(src), n, int(slab_bytes), int(bool(nontemporal)), _ptr(out), _stream(stream))
+    if rc != 0:
+        raise TliError(rc, "tli_calib_read")

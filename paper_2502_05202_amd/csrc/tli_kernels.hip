@@ -425,6 +425,20 @@ int tli_calib_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
     return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
 }
 
+int tli_calib_read(const void* src, size_t bytes, size_t slab_bytes, int32_t nontemporal, uint32_t* out, void* hip_stream) {
+    constexpr size_t chunk_bytes = (size_t)kWave * kLoads * 16;
+    if (!src || !out || !aligned16(src) || slab_bytes == 0 || slab_bytes % chunk_bytes != 0 || bytes == 0 ||
+        bytes % slab_bytes != 0 || bytes / slab_bytes > 0x7fffffffu)
+        return TLI_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)(bytes / slab_bytes));
+    const hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (nontemporal)
+        hipLaunchKernelGGL(k_calib_read<true>, grid, dim3(kWG), 0, st, static_cast<const u4v*>(src), slab_bytes / 16, out);
+    else
+        hipLaunchKernelGGL(k_calib_read<false>, grid, dim3(kWG), 0, st, static_cast<const u4v*>(src), slab_bytes / 16, out);
+    return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
+}
+
 int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls, int32_t every) {
     tli_profile_disable();
     if (max_calls < 1 || max_calls > (1 << 20) || every < 1) return TLI_ERR_INVALID_ARG;

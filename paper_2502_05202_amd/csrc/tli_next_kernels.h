@@ -501,3 +501,38 @@ __global__ __launch_bounds__(kWG) void k_calib_copy(const u4v* __restrict__ src,
     const size_t stride = (size_t)gridDim.x * kWG;
     for (size_t i = (size_t)blockIdx.x * kWG + threadIdx.x; i < nvec; i += stride) dst[i] = src[i];
 }
+
+// ---- plain read, the yardstick the streaming kernels are held against ---------------------------------
+// Reads `slabs` contiguous slabs of `slab_vec` 16-byte vectors, a workgroup per slab, in the normaliser kernel's
+// own access pattern (a wave owns chunks of 64 lanes x 4 loads, the next chunk's loads in flight) and does
+// nothing with the data but fold it into one word per workgroup, so that the loads cannot be dropped.
+template <bool NT>
+__global__ __launch_bounds__(kWG) void k_calib_read(const u4v* __restrict__ src, size_t slab_vec, uint32_t* __restrict__ out) {
+    const u4v* base = src + (size_t)blockIdx.x * slab_vec;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const size_t nchunks = slab_vec / (kWave * kLoads);
+    u4v acc = {0u, 0u, 0u, 0u};
+    auto load = [&](size_t c, u4v (&v)[kLoads]) {
+        const u4v* q = base + c * (kWave * kLoads) + lane;
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) v[j] = NT ? __builtin_nontemporal_load(q + j * kWave) : q[j * kWave];
+    };
+    auto fold = [&](const u4v (&v)[kLoads]) {
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) acc ^= v[j];
+    };
+    size_t c = wave;
+    if (c < nchunks) {
+        u4v a[kLoads], b[kLoads];
+        load(c, a);
+        for (; c + kWaves < nchunks; c += kWaves) {
+            load(c + kWaves, b);
+            fold(a);
+#pragma unroll
+            for (int j = 0; j < kLoads; ++j) a[j] = b[j];
+        }
+        fold(a);
+    }
+    const uint32_t w = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (w == 0x9e3779b9u) out[blockIdx.x] = w;  // practically never: the store only keeps the loads alive
+}

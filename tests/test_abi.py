@@ -72,6 +72,8 @@ def test_hot_calls_reject_null_arguments(lib):
     assert lib.tli_verify(z, z, z, 0, 1, 1, 1.0, 1.0, z, z, z, z, z, z, z, z, z, z, z, z, 0, z) == -1
     assert lib.tli_map_info(z, None, None, None) == -1
     lib.tli_free_map(z)  # freeing NULL is a no-op
+    assert lib.tli_calib_read(z, 4096, 4096, 0, z, z) == -1
+    assert lib.tli_calib_copy(z, z, 16, z) == -1
 
 
 def test_new_entry_points_reject_null_arguments(lib):
