@@ -114,10 +114,27 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
+    def time_each(fn, n):
+        """one HIP-event pair per call: (median, min) in ms"""
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        torch.cuda.synchronize()
+        for e0, e1 in evs:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        ts = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        return ts[len(ts) // 2], ts[0]
+
     n_sep = max(5, args.steps // 2)
     draft_ms = time_call(lambda: binding.tli_draft_sample(m, inp["logits_d"], w.tau_d, u_draft, ws, out=d_out), n_sep)
     verify_ms = time_call(lambda: binding.tli_verify(m, inp["logits_t"], inp["logits_d"], w.tau_t, w.tau_d, d_out["tok_d"],
                                                      d_out["lse_q"], u_acc, inp["u_fin"], ws, out=v_out), n_sep)
+    verify_med_ms, verify_min_ms = time_each(
+        lambda: binding.tli_verify(m, inp["logits_t"], inp["logits_d"], w.tau_t, w.tau_d, d_out["tok_d"], d_out["lse_q"],
+                                   u_acc, inp["u_fin"], ws, out=v_out), max(50, n_sep // 2))
+    draft_med_ms, draft_min_ms = time_each(
+        lambda: binding.tli_draft_sample(m, inp["logits_d"], w.tau_d, u_draft, ws, out=d_out), max(50, n_sep // 2))
     # ---- the drafting loop at its real shape: one tli_draft_sample call per lookahead position on the B rows
     # logits_d[:, k, :] (as after each drafter forward), then tli_verify; eager, and captured in a HIP graph
     def iteration():
@@ -272,6 +289,8 @@ def main():
         roofline["frac_of_read_kernel"] = round(achieved / max(read_gbs.values()), 4)
     extra = dict(
         draft_ms=round(draft_ms, 4), verify_ms=round(verify_ms, 4),
+        verify_ms_median_min=[round(verify_med_ms, 4), round(verify_min_ms, 4)],
+        draft_ms_median_min=[round(draft_med_ms, 4), round(draft_min_ms, 4)],
         verify_only_positions_per_s=round(positions / (1e-3 * verify_ms), 1),
         verify_algorithmic_gbs=round(verify_bytes / (1e-3 * verify_ms) / 1e9, 1),
         verify_frac_of_peak=round(verify_bytes / (1e-3 * verify_ms) / 1e9 / HBM_PEAK_GBS, 4),
