@@ -26,6 +26,16 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC_BYTES = {"large_vocab": 1048.65e6 + 2.16e6}
 
 
+def _cpu_model() -> str:
+    try:
+        for l in open("/proc/cpuinfo"):
+            if l.startswith("model name"):
+                return l.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -334,7 +344,7 @@ def main():
                    sample=f"first {nseq} of {w.B} sequences of the same batch, draft+verify, {cores} threads, "
                           f"{c1 - c0:.1f} s",
                    single_thread_value=round(n1 * w.K / (s1 - s0), 2), single_thread_sample=f"first {n1} sequences",
-                   host_cpus=os.cpu_count())
+                   host_cpus=os.cpu_count(), cpu_model=_cpu_model())
 
     line = dict(
         metric="verified_draft_positions_per_s", value=round(value, 1), unit="positions/s", n_gpus=1, steps=args.steps,
