@@ -72,6 +72,18 @@ void tli_free_map(tli_map* map);
 /* Vd, Vt and |T∩D| of a map (any pointer may be NULL). */
 int tli_map_info(const tli_map* map, int32_t* Vd, int32_t* Vt, int32_t* num_shared);
 /*
+ * Host-only convenience (notation paragraph: a vocabulary is a set of strings, so two tokens are shared iff their
+ * strings are equal): d2t from the two vocabularies' token strings by exact byte equality.  Token x of a vocabulary
+ * is the bytes [offs[x], offs[x+1]) of its byte array (any bytes, no terminator).
+ *   bytes_d, offs_d [Vd+1] host : the drafter's tokens;  bytes_t, offs_t [Vt+1] host : the target's
+ *   d2t_out [Vd] host           : receives the target id of every drafter id, or -1
+ *   out_num_shared              : receives |T∩D| (may be NULL)
+ * TLI_ERR_NOT_INJECTIVE if a string occurs twice in one vocabulary (a set has no duplicates),
+ * TLI_ERR_OUT_OF_RANGE if offsets do not ascend.  Touches no device.
+ */
+int tli_d2t_from_strings(const char* bytes_d, const int64_t* offs_d, int32_t Vd, const char* bytes_t, const int64_t* offs_t,
+                         int32_t Vt, int32_t* d2t_out, int32_t* out_num_shared);
+/*
  * Host-only rehearsal of tli_build_map (intersection algorithm: everything it needs to know about T∩D): runs the
  * same argument checks and builds the same tables, touches no device, and then replays on the host what the
  * residual-scan kernel does with them, for both storage types and both drafter-row layouts: every index the kernel

@@ -25,6 +25,7 @@ EXPORTS = (
     "tli_sample_rows_workspace_bytes", "tli_sample_rows", "tli_greedy_draft", "tli_exact_match_workspace_bytes",
     "tli_exact_match_verify", "tli_draft_sample_compact", "tli_verify_compact",
     "tli_warp_workspace_bytes", "tli_warp_rows", "tli_map_dry_run", "tli_calib_read",
+    "tli_d2t_from_strings",
 )
 KERNELS = ("lse", "accept", "final_scan", "final_pick", "draft_scan", "draft_pick")
 
@@ -102,6 +103,8 @@ def load_library() -> ctypes.CDLL:
     lib.tli_calib_read.restype = ctypes.c_int
     lib.tli_map_dry_run.argtypes = [vp, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.tli_map_dry_run.restype = ctypes.c_int
+    lib.tli_d2t_from_strings.argtypes = [ctypes.c_char_p, vp, i32, ctypes.c_char_p, vp, i32, vp, ctypes.POINTER(i32)]
+    lib.tli_d2t_from_strings.restype = ctypes.c_int
     lib.tli_status_string.argtypes = [ctypes.c_int]
     lib.tli_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -165,6 +168,28 @@ def tli_build_map(d2t, Vt: int) -> TliMap:
     if rc != 0:
         raise TliError(rc, "tli_build_map")
     return TliMap(out.value, int(arr.shape[0]), int(Vt), S.value)
+
+
+def _pack_tokens(tokens):
+    raw = [t.encode("utf-8") if isinstance(t, str) else bytes(t) for t in tokens]
+    offs = np.zeros(len(raw) + 1, np.int64)
+    np.cumsum([len(r) for r in raw], out=offs[1:])
+    return b"".join(raw), offs
+
+
+def tli_d2t_from_strings(tokens_d, tokens_t) -> np.ndarray:
+    """d2t (int32 [Vd]) from the two vocabularies' token strings (str or bytes) by exact equality; host only."""
+    lib = load_library()
+    bd, od = _pack_tokens(tokens_d)
+    bt, ot = _pack_tokens(tokens_t)
+    out = np.empty(len(tokens_d), np.int32)
+    S = ctypes.c_int32()
+    rc = lib.tli_d2t_from_strings(bd, od.ctypes.data_as(ctypes.c_void_p), len(tokens_d), bt,
+                                  ot.ctypes.data_as(ctypes.c_void_p), len(tokens_t), out.ctypes.data_as(ctypes.c_void_p),
+                                  ctypes.byref(S))
+    if rc != 0:
+        raise TliError(rc, "tli_d2t_from_strings")
+    return out
 
 
 def tli_map_dry_run(d2t, Vt: int) -> dict:

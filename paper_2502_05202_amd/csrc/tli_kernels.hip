@@ -19,6 +19,8 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <string_view>
+#include <unordered_map>
 #include <type_traits>
 #include <vector>
 
@@ -715,6 +717,36 @@ int check_host_scan(const HostMap& hm, int32_t Vd, int32_t Vt, int dt, int layou
 }
 
 }  // namespace
+
+int tli_d2t_from_strings(const char* bytes_d, const int64_t* offs_d, int32_t Vd, const char* bytes_t, const int64_t* offs_t,
+                         int32_t Vt, int32_t* d2t_out, int32_t* out_num_shared) {
+    if (out_num_shared) *out_num_shared = 0;
+    if (!offs_d || !offs_t || !d2t_out || Vd < 1 || Vt < 1) return TLI_ERR_INVALID_ARG;
+    for (int32_t t = 0; t < Vt; ++t)
+        if (offs_t[t] < 0 || offs_t[t + 1] < offs_t[t]) return TLI_ERR_OUT_OF_RANGE;
+    for (int32_t x = 0; x < Vd; ++x)
+        if (offs_d[x] < 0 || offs_d[x + 1] < offs_d[x]) return TLI_ERR_OUT_OF_RANGE;
+    if ((!bytes_t && offs_t[Vt] > 0) || (!bytes_d && offs_d[Vd] > 0)) return TLI_ERR_INVALID_ARG;
+    auto token = [](const char* bytes, const int64_t* offs, int32_t i) {
+        return std::string_view(bytes ? bytes + offs[i] : "", (size_t)(offs[i + 1] - offs[i]));
+    };
+    std::unordered_map<std::string_view, int32_t> in_t;
+    in_t.reserve((size_t)Vt * 2);
+    for (int32_t t = 0; t < Vt; ++t)
+        if (!in_t.emplace(token(bytes_t, offs_t, t), t).second) return TLI_ERR_NOT_INJECTIVE;
+    std::unordered_map<std::string_view, int32_t> in_d;
+    in_d.reserve((size_t)Vd * 2);
+    int32_t S = 0;
+    for (int32_t x = 0; x < Vd; ++x) {
+        const std::string_view s = token(bytes_d, offs_d, x);
+        if (!in_d.emplace(s, x).second) return TLI_ERR_NOT_INJECTIVE;
+        const auto hit = in_t.find(s);
+        d2t_out[x] = hit == in_t.end() ? -1 : hit->second;
+        S += hit != in_t.end();
+    }
+    if (out_num_shared) *out_num_shared = S;
+    return TLI_OK;
+}
 
 int tli_map_dry_run(const int32_t* d2t_host, int32_t Vd, int32_t Vt, int32_t* out_num_shared, int32_t* out_nparts,
                     int32_t* out_failed_check) {

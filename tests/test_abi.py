@@ -22,7 +22,7 @@ def lib():
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "tli.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tli_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(tli_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -120,3 +120,26 @@ def test_map_tables_replayed_on_the_host(lib):
     assert binding.tli_map_dry_run([3, 1, 3], 7)["status"] == -3
     assert binding.tli_map_dry_run([-1, -1], 7)["status"] == -4
     assert binding.status_string(-7) == "TLI_ERR_INTERNAL"
+
+
+def test_d2t_from_token_strings(lib):
+    """Vocabularies are sets of strings; the shared tokens are the equal strings (the paper's notation paragraph and
+    its three tiny examples)."""
+    ex = binding.tli_d2t_from_strings
+    assert ex(["a", "b", "c"], ["a", "b"]).tolist() == [0, 1, -1]      # T={a,b}, D={a,b,c}
+    assert ex(["b"], ["a"]).tolist() == [-1]                            # disjoint
+    assert ex(["b"], ["a", "b"]).tolist() == [1]
+    assert ex(["a", "b"], ["a"]).tolist() == [0, -1]
+    # any bytes, the empty string and prefixes of one another are tokens of their own
+    assert ex([b"\x00", b"", b"ab", b"a\x00b"], [b"a\x00b", b"abc", b"", b"\x00\x00"]).tolist() == [-1, 2, -1, 0]
+    rng = np.random.default_rng(3)
+    words = [f"tok{i}" for i in rng.permutation(5000)]
+    D, T = words[:3000], list(reversed(words[1000:4500]))
+    want = {w: i for i, w in enumerate(T)}
+    assert ex(D, T).tolist() == [want.get(w, -1) for w in D]
+    with pytest.raises(binding.TliError):
+        ex(["a", "a"], ["a"])                                           # a set has no duplicates
+    with pytest.raises(binding.TliError):
+        ex(["a"], ["b", "b"])
+    # what comes out is what tli_build_map takes
+    assert binding.tli_map_dry_run(ex(D, T), len(T))["num_shared"] == 2000
