@@ -106,7 +106,8 @@ def test_iteration_in_a_hip_graph_replays_exactly():
 
 
 COMPACT = [(5, 3, 2048 * 3 + 40, 2048 * 2 + 24, 1500, "bf16"), (3, 4, 1024 * 4 + 28, 1024 + 4, 700, "f32"),
-           (300, 2, 5000, 4104, 1501, "bf16"), (2, 2, 2048 * 30 + 16, 2048 * 27 + 8, 50000, "bf16")]
+           (300, 2, 5000, 4104, 1501, "bf16"), (2, 2, 2048 * 30 + 16, 2048 * 27 + 8, 50000, "bf16"),
+           (2, 2, 70000, 60000, 50000, "f32")]  # the last two: 2 and 3 parts in the residual scan
 
 
 @pytest.mark.parametrize("shape", COMPACT, ids=[f"B{c[0]}_S{c[4]}_{c[5]}" for c in COMPACT])
