@@ -18,6 +18,7 @@ SHAPES = [
     (3, 4, 1024 * 4 + 28, 1024 + 4, 700, "f32", 1.0, 1.0),
     (40, 2, 10000, 30000, 9000, "bf16", 0.8, 1.1),
     (2, 2, 2048 * 30 + 16, 2048 * 27 + 8, 50000, "bf16", 0.9, 1.0),
+    (2, 2, 70000, 60000, 50000, "f32", 1.0, 0.9),  # three parts in the residual scan
 ]
 IDS = [f"B{c[0]}_Vt{c[2]}_{c[5]}" for c in SHAPES]
 
