@@ -264,6 +264,65 @@ def test_hot_calls_reject_bad_arguments():
     m.free()
 
 
+def test_buffers_beyond_32_bit_offsets(oracle):
+    """A batch whose logit buffers pass 2^31 elements and 2^32 bytes (target 9.7 GB, drafter 4.3 GB): the large-vocabulary
+    shape with B = 2104.  The batch is 263 copies of 8 drawn sequences, copy i rotated by i ids along the vocabulary
+    so that no two sequences hold the same rows, with uniforms of its own per sequence; the oracle runs on the
+    sequences either side of every offset where a 31-, 32- or 33-bit byte or element count wraps, the first and the
+    last."""
+    base = synth.WORKLOADS[4].scaled(B=8)
+    inp = synth.make_inputs(base, DEV)
+    reps, K, Vt, Vd = 263, base.K, base.Vt, base.Vd
+    B = 8 * reps
+    assert B * K * Vd > 2 ** 31 and B * (K + 1) * Vt * 2 > 2 ** 33
+    lt = torch.empty(B, K + 1, Vt, dtype=torch.bfloat16, device=DEV)
+    ld = torch.empty(B, K, Vd, dtype=torch.bfloat16, device=DEV)
+    for i in range(reps):
+        lt[8 * i:8 * i + 8] = torch.roll(inp["logits_t"], i, dims=2)
+        ld[8 * i:8 * i + 8] = torch.roll(inp["logits_d"], i, dims=2)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(4104)
+    u_draft, u_acc = synth._uniform24(B * K, gen, DEV), synth._uniform24(B * K, gen, DEV)
+    u_fin = synth._uniform24(B, gen, DEV)
+    m = binding.tli_build_map(inp["d2t"], Vt)
+    ws = binding.alloc_workspace(B, K, m, binding.TLI_BF16, DEV)
+    g_draft = binding.tli_draft_sample(m, ld, base.tau_d, u_draft, ws)
+    g_ver = binding.tli_verify(m, lt, ld, base.tau_t, base.tau_d, g_draft["tok_d"], g_draft["lse_q"], u_acc, u_fin, ws)
+    torch.cuda.synchronize()
+    seq_t, seq_d = (K + 1) * Vt, K * Vd                  # elements per sequence
+    pick = {0, 1, B - 2, B - 1}
+    for bits in (30, 31, 32):                             # element counts; the byte counts are one bit on
+        for per in (seq_t, seq_d):
+            b = (1 << bits) // per
+            pick |= {x for x in (b - 1, b, b + 1) if 0 <= x < B}
+    pick = sorted(pick)
+    assert len(pick) >= 14 and pick[-1] == B - 1
+    sel = torch.tensor(pick, device=DEV)
+    rows = (sel[:, None] * K + torch.arange(K, device=DEV)[None, :]).reshape(-1)
+    lt_np, ld_np = synth.logits_to_numpy(lt[sel]), synth.logits_to_numpy(ld[sel])
+    rows_h = rows.cpu().numpy()
+    gd = {k: v[rows_h] for k, v in parity.to_host(g_draft).items()}
+    rep_d, _ = parity.compare_draft(oracle, ld_np.reshape(len(pick) * K, Vd), base.tau_d, inp["d2t"],
+                                    u_draft[rows].cpu().numpy().astype(np.float64), gd, threads=8)
+    gv = {k: v[pick] for k, v in parity.to_host(g_ver).items()}
+    rep_v, _ = parity.compare_verify(oracle, lt_np, ld_np, base.tau_t, base.tau_d, inp["d2t"], gd["tok_d"],
+                                     u_acc[rows].cpu().numpy().astype(np.float64).reshape(len(pick), K),
+                                     u_fin[sel].cpu().numpy().astype(np.float64), gv, threads=8)
+    print(pick, dict(rep_d), dict(rep_v))
+    _check(dict(draft=rep_d, verify=rep_v, chained=None))
+    # every sequence of the batch, by what holds at any size: flags clear, counts in range, an extra token after
+    # the accepted drafts and nothing behind it
+    allv = parity.to_host(g_ver)
+    n = allv["n_accepted"]
+    assert np.all(allv["status"] == 0) and np.all((0 <= n) & (n <= K))
+    extra = allv["out_tok"][np.arange(B), n]
+    assert np.all((0 <= extra) & (extra < Vt))
+    assert np.all(allv["out_tok"][np.arange(K + 1)[None, :] > n[:, None]] == -1)
+    m.free()
+    del lt, ld, ws
+    torch.cuda.empty_cache()
+
+
 FULL = [2, 3, 4, 5]
 
 
