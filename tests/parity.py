@@ -215,3 +215,25 @@ def run_case(oracle_mod, inp: dict, threads=16, chain=True):
                                   to_host(g_ver2), threads=threads)
     m.free()
     return dict(draft=rep_d, verify=rep_v, chained=rep_c, ref_draft=ref_d, ref_verify=ref_v, gpu_verify=to_host(g_ver))
+
+
+def rolled_copies(x: torch.Tensor, reps: int) -> torch.Tensor:
+    """[n, ...] -> [n * reps, ...]: copy i is x rotated by i ids along the last (vocabulary) axis, so that no two
+    blocks hold the same rows (for buffers larger than any drawn input)."""
+    out = torch.empty((x.shape[0] * reps,) + tuple(x.shape[1:]), dtype=x.dtype, device=x.device)
+    n = x.shape[0]
+    for i in range(reps):
+        out[n * i:n * (i + 1)] = torch.roll(x, i, dims=-1)
+    return out
+
+
+def around_wraps(n_items: int, item_elems: list[int], bits=(30, 31, 32)) -> list[int]:
+    """Indices of the items (sequences, rows) either side of every offset where an element count of `bits` bits
+    wraps (for 2-byte storage the byte count is one bit on), for each per-item size given; plus the first two and
+    the last two."""
+    pick = {0, 1, n_items - 2, n_items - 1}
+    for b in bits:
+        for per in item_elems:
+            i = (1 << b) // per
+            pick |= {i - 1, i, i + 1}
+    return sorted(i for i in pick if 0 <= i < n_items)

@@ -332,9 +332,13 @@ def test_full_size_large_vocab_next_rows(oracle):
 WARP = [("bf16", 2048 * 3 + 40, 9, 2048 * 3 + 48), ("f32", 5000, 4, 5000), ("bf16", 151936, 3, 151936), ("f32", 33000, 2, 33000)]
 
 
-def _check_warp(oracle, view, rows, tau, top_k, top_p, d2t, m):
+def _check_warp(oracle, view, rows, tau, top_k, top_p, d2t, m, pick=None):
+    """pick: compare only these rows of `view` (then `rows` holds just those, in that order)."""
     g = binding.tli_warp_rows(view, tau, top_k, top_p, m=m)
     torch.cuda.synchronize()
+    if pick is not None:
+        at = torch.as_tensor(pick, device=view.device)
+        g = {k: v[at] for k, v in g.items()}
     ref = oracle.warp_rows(rows, parity.f32(tau), top_k, float(np.float32(top_p)), d2t=d2t, threads=8)
     gs, gk, gt = g["status"].cpu().numpy(), g["kept"].cpu().numpy(), g["thr"].cpu().numpy().astype(np.float64)
     assert np.array_equal(gs, ref["status"])
@@ -403,3 +407,102 @@ def test_warp_rows_flags_and_map(oracle):
     dr = oracle.draft_sample(synth.logits_to_numpy(g["logits"]), parity.f32(0.9), d2t, u.cpu().numpy().astype(np.float64))
     assert np.array_equal(d["tok_d"].cpu().numpy(), dr["tok_d"])
     m.free()
+
+
+def test_next_rows_beyond_32_bit_offsets(oracle):
+    """The neighbouring entry points on buffers that pass 2^31 elements and 2^32 bytes (rows of the large-vocabulary
+    shape, rotated copies of 8 drawn sequences): the oracle runs on the rows and sequences either side of every
+    offset where a 30-, 31- or 32-bit element count wraps, the first and the last."""
+    base = synth.WORKLOADS[4].scaled(B=8)
+    inp = synth.make_inputs(base, DEV)
+    K, Vt, Vd, d2t = base.K, base.Vt, base.Vd, inp["d2t"]
+    tt, td = parity.f32(base.tau_t), parity.f32(base.tau_d)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(8496)
+    # ---- one token per row, argmax, exact-match tail, warpers: 8496 rows of 256000 bf16 (4.35 GB)
+    lt = parity.rolled_copies(inp["logits_t"], 118)
+    B, m1 = lt.shape[0], K + 1
+    R = B * m1
+    assert R * Vt > 2 ** 31
+    flat = lt.reshape(R, Vt)
+    u = synth._uniform24(R, gen, DEV)
+    un = u.cpu().numpy().astype(np.float64)
+    pick = parity.around_wraps(R, [Vt])
+    rows = synth.logits_to_numpy(flat[torch.tensor(pick, device=DEV)])
+    seqs = parity.around_wraps(B, [m1 * Vt])
+    lt_np = synth.logits_to_numpy(lt[torch.tensor(seqs, device=DEV)])
+    for tau in (base.tau_t, 0.0):
+        g = parity.to_host(binding.tli_sample_rows(flat, tau, u))
+        ref = oracle.sample_rows(rows, parity.f32(tau), un[pick], threads=8)
+        gp = {k: v[pick] for k, v in g.items()}
+        if tau == 0.0:
+            assert np.array_equal(gp["tok"], ref["tok"]) and np.array_equal(gp["status"], ref["status"])
+        else:
+            rep = parity.compare_row_tokens(oracle, rows, tau, un[pick], gp["tok"], gp["status"], ref,
+                                            lambda r: oracle.softmax(rows[r], parity.f32(tau))[0])
+            assert rep["hard"] == 0 and rep["token_near_ties"] == 0
+            assert np.abs(gp["lse"] - ref["lse"]).max() < 5e-7
+        assert np.all(g["status"] == 0) and np.all((0 <= g["tok"]) & (g["tok"] < Vt))
+        # drafts: the target's own tokens, one of them changed in most sequences
+        draft = g["tok"].reshape(B, m1)[:, :K].copy()
+        for b in range(B):
+            if b % (K + 2) < K:
+                draft[b, b % (K + 2)] = (draft[b, b % (K + 2)] + 1) % Vt
+        ge = parity.to_host(binding.tli_exact_match_verify(lt, tau, torch.from_numpy(draft).to(DEV), u.reshape(B, m1)))
+        re_ = oracle.exact_match_verify(lt_np, parity.f32(tau), draft[seqs], un.reshape(B, m1)[seqs], threads=8)
+        for i, b in enumerate(seqs):
+            diff = np.nonzero(ge["tgt_tok"][b] != re_["tgt_tok"][i])[0]
+            if diff.size:  # only a draw inside the oracle's near-tie window may differ
+                assert tau > 0 and np.all(re_["margin"][i, diff] < parity.NEAR_TIE), (tau, b, diff)
+                continue
+            assert ge["n_accepted"][b] == re_["n_acc"][i] and np.array_equal(ge["out_tok"][b], re_["out_tok"][i])
+        want_n = np.array([b % (K + 2) if b % (K + 2) < K else K for b in range(B)])
+        assert np.array_equal(ge["n_accepted"], want_n)
+    near = _check_warp(oracle, flat, rows, base.tau_t, 50, 0.9, None, None, pick=pick)
+    assert near == 0
+    del lt, flat
+    torch.cuda.empty_cache()
+    # ---- union algorithm, acceptance rates, greedy drafts: B = 2104 (target 9.7 GB, drafter 4.3 GB)
+    reps = 263
+    lt, ld = parity.rolled_copies(inp["logits_t"], reps), parity.rolled_copies(inp["logits_d"], reps)
+    B = 8 * reps
+    assert B * K * Vd > 2 ** 31
+    u_draft, u_acc = synth._uniform24(B * K, gen, DEV), synth._uniform24(B * K, gen, DEV)
+    u_fin = synth._uniform24(B, gen, DEV)
+    mp = binding.tli_build_map(d2t, Vt)
+    ws = binding.alloc_workspace(B, K, mp, binding.TLI_BF16, DEV)
+    seqs = parity.around_wraps(B, [m1 * Vt, K * Vd])
+    sel = torch.tensor(seqs, device=DEV)
+    prow = (sel[:, None] * K + torch.arange(K, device=DEV)[None, :]).reshape(-1)
+    prow_h = prow.cpu().numpy()
+    lt_np, ld_np = synth.logits_to_numpy(lt[sel]), synth.logits_to_numpy(ld[sel])
+    rows_d = ld_np.reshape(len(seqs) * K, Vd)
+    ud = u_draft[prow].cpu().numpy().astype(np.float64)
+    g_all = binding.tli_union_draft_sample(mp, ld, base.tau_d, u_draft, ws)
+    g = {k: v[prow_h] for k, v in parity.to_host(g_all).items()}
+    ref = oracle.union_draft_sample(rows_d, td, d2t, ud, threads=8)
+    rep = parity.compare_row_tokens(oracle, rows_d, td, ud, g["tok_d"], g["status"], ref,
+                                    lambda r: oracle.softmax(rows_d[r], td)[0])
+    assert rep["hard"] == 0 and np.abs(g["lse_q"] - ref["lse_q"]).max() < 5e-7
+    gv = binding.tli_union_verify(mp, lt, ld, base.tau_t, base.tau_d, g_all["tok_d"], g_all["lse_q"], u_acc, u_fin, ws)
+    torch.cuda.synchronize()
+    gvp = {k: v[seqs] for k, v in parity.to_host(gv).items()}
+    rv, _ = parity.compare_verify(oracle, lt_np, ld_np, base.tau_t, base.tau_d, d2t, g["tok_d"],
+                                  u_acc[prow].cpu().numpy().astype(np.float64).reshape(len(seqs), K),
+                                  u_fin[sel].cpu().numpy().astype(np.float64), gvp, threads=8, fn="union_verify")
+    print("union verify", seqs, dict(rv))
+    assert rv["hard"] == 0 and rv["max_lse_err"] < 5e-7
+    ga = parity.to_host(binding.tli_acceptance_rates(mp, lt, ld, base.tau_t, base.tau_d))
+    ra = oracle.acceptance_rates(lt_np[:, :K].reshape(-1, Vt), rows_d, tt, td, d2t, threads=8)
+    assert np.all(ga["status"] == 0) and np.all(ra["status"] == 0)
+    for name in ("alpha_tli", "alpha_union"):
+        rel = np.abs(ga[name].reshape(-1)[prow_h] - ra[name]) / ra[name]
+        print(name, "max rel", rel.max())
+        assert rel.max() < 2e-6
+    assert np.all(ga["alpha_union"] <= ga["alpha_tli"] * (1 + 1e-9)) and np.all(ga["alpha_tli"] <= 1 + 1e-9)
+    gd = parity.to_host(binding.tli_greedy_draft(mp, ld, ws))
+    rd = oracle.greedy_draft(rows_d, d2t, threads=8)
+    assert np.array_equal(gd["tok_d"][prow_h], rd["tok_d"]) and np.all(gd["status"] == 0)
+    mp.free()
+    del lt, ld, ws
+    torch.cuda.empty_cache()

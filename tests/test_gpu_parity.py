@@ -275,11 +275,7 @@ def test_buffers_beyond_32_bit_offsets(oracle):
     reps, K, Vt, Vd = 263, base.K, base.Vt, base.Vd
     B = 8 * reps
     assert B * K * Vd > 2 ** 31 and B * (K + 1) * Vt * 2 > 2 ** 33
-    lt = torch.empty(B, K + 1, Vt, dtype=torch.bfloat16, device=DEV)
-    ld = torch.empty(B, K, Vd, dtype=torch.bfloat16, device=DEV)
-    for i in range(reps):
-        lt[8 * i:8 * i + 8] = torch.roll(inp["logits_t"], i, dims=2)
-        ld[8 * i:8 * i + 8] = torch.roll(inp["logits_d"], i, dims=2)
+    lt, ld = parity.rolled_copies(inp["logits_t"], reps), parity.rolled_copies(inp["logits_d"], reps)
     gen = torch.Generator(device=DEV)
     gen.manual_seed(4104)
     u_draft, u_acc = synth._uniform24(B * K, gen, DEV), synth._uniform24(B * K, gen, DEV)
@@ -289,13 +285,7 @@ def test_buffers_beyond_32_bit_offsets(oracle):
     g_draft = binding.tli_draft_sample(m, ld, base.tau_d, u_draft, ws)
     g_ver = binding.tli_verify(m, lt, ld, base.tau_t, base.tau_d, g_draft["tok_d"], g_draft["lse_q"], u_acc, u_fin, ws)
     torch.cuda.synchronize()
-    seq_t, seq_d = (K + 1) * Vt, K * Vd                  # elements per sequence
-    pick = {0, 1, B - 2, B - 1}
-    for bits in (30, 31, 32):                             # element counts; the byte counts are one bit on
-        for per in (seq_t, seq_d):
-            b = (1 << bits) // per
-            pick |= {x for x in (b - 1, b, b + 1) if 0 <= x < B}
-    pick = sorted(pick)
+    pick = parity.around_wraps(B, [(K + 1) * Vt, K * Vd])
     assert len(pick) >= 14 and pick[-1] == B - 1
     sel = torch.tensor(pick, device=DEV)
     rows = (sel[:, None] * K + torch.arange(K, device=DEV)[None, :]).reshape(-1)
