@@ -23,6 +23,9 @@
  *   - The hot calls (tli_draft_sample, tli_verify) only enqueue kernels on the given HIP stream: no
  *     allocation, no synchronisation.  On a non-zero return nothing was enqueued.
  *   - Data-dependent trouble is reported per row / per sequence as TLI_FLAG_* bits, never by aborting.
+ *   - Sizes: 1 <= K <= 64 draft positions per sequence; row counts (R, B*K, B*(m+1)) up to 2^31/64;
+ *     vocabularies up to 2^30 ids.  Offsets into the logit buffers are 64-bit: a buffer may hold more
+ *     than 2^31 elements.  Anything outside these limits returns TLI_ERR_INVALID_ARG (workspace queries: 0).
  */
 #ifndef TLI_H
 #define TLI_H

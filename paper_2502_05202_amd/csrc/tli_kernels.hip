@@ -86,6 +86,10 @@ Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// vocabulary sizes the chunk arithmetic (int32 ids, counts rounded up to whole chunks) is written for
+constexpr int kMaxVocab = 1 << 30;
+bool vocab_ok(int V) { return V >= 1 && V <= kMaxVocab; }
+
 // ---- optional per-kernel timing with HIP events on the caller's stream -------------------------
 struct Profile {
     bool on = false;
@@ -223,7 +227,7 @@ int sample_rows_impl(const void* logits, int dtype, int64_t row_stride, int R, i
                      int32_t* status, int64_t io_stride, void* workspace, size_t workspace_bytes, hipStream_t st,
                      const int32_t* r2d = nullptr) {
     if (!logits || !u || !tok || !status || !workspace) return TLI_ERR_INVALID_ARG;
-    if (R < 1 || R > 0x7fffffff / 64 || V < 1 || !(temp > 0.f) || !std::isfinite(temp) || io_stride < 1)
+    if (R < 1 || R > 0x7fffffff / 64 || !vocab_ok(V) || !(temp > 0.f) || !std::isfinite(temp) || io_stride < 1)
         return TLI_ERR_INVALID_ARG;
     if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
     const int epv = dtype == TLI_BF16 ? 8 : 4;
@@ -262,7 +266,7 @@ int argmax_rows_impl(const void* logits, int dtype, int64_t row_stride, int R, i
                      const int32_t* d2t, int32_t* tok, int32_t* tok_t, double* p_tok, double* lse, int32_t* status,
                      int64_t io_stride, void* workspace, size_t workspace_bytes, hipStream_t st) {
     if (!logits || !tok || !status || !workspace) return TLI_ERR_INVALID_ARG;
-    if (R < 1 || R > 0x7fffffff / 64 || V < 1 || io_stride < 1) return TLI_ERR_INVALID_ARG;
+    if (R < 1 || R > 0x7fffffff / 64 || !vocab_ok(V) || io_stride < 1) return TLI_ERR_INVALID_ARG;
     if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
     const int epv = dtype == TLI_BF16 ? 8 : 4;
     if (row_stride < V || row_stride % epv != 0 || !aligned16(logits) || !aligned16(workspace)) return TLI_ERR_INVALID_ARG;
@@ -518,7 +522,7 @@ struct HostMap {
 };
 
 int build_host_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, HostMap& hm) {
-    if (!d2t_host || Vd < 1 || Vt < 1) return TLI_ERR_INVALID_ARG;
+    if (!d2t_host || !vocab_ok(Vd) || !vocab_ok(Vt)) return TLI_ERR_INVALID_ARG;
     const size_t Vd_pad = ((size_t)Vd + 7) & ~(size_t)7, Vt_pad = ((size_t)Vt + 7) & ~(size_t)7;
     std::vector<int32_t>&d2t = hm.d2t, &t2d = hm.t2d, &sh_x = hm.sh_x;
     d2t.assign(Vd_pad, -1);
@@ -721,7 +725,7 @@ int check_host_scan(const HostMap& hm, int32_t Vd, int32_t Vt, int dt, int layou
 int tli_d2t_from_strings(const char* bytes_d, const int64_t* offs_d, int32_t Vd, const char* bytes_t, const int64_t* offs_t,
                          int32_t Vt, int32_t* d2t_out, int32_t* out_num_shared) {
     if (out_num_shared) *out_num_shared = 0;
-    if (!offs_d || !offs_t || !d2t_out || Vd < 1 || Vt < 1) return TLI_ERR_INVALID_ARG;
+    if (!offs_d || !offs_t || !d2t_out || !vocab_ok(Vd) || !vocab_ok(Vt)) return TLI_ERR_INVALID_ARG;
     for (int32_t t = 0; t < Vt; ++t)
         if (offs_t[t] < 0 || offs_t[t + 1] < offs_t[t]) return TLI_ERR_OUT_OF_RANGE;
     for (int32_t x = 0; x < Vd; ++x)
@@ -869,7 +873,7 @@ int tli_map_info(const tli_map* m, int32_t* Vd, int32_t* Vt, int32_t* S) {
 }
 
 size_t tli_workspace_bytes(int32_t B, int32_t K, int32_t Vt, int32_t Vd, tli_dtype dtype) {
-    if (B < 1 || K < 1 || K > kMaxK || Vt < 1 || Vd < 1 || (dtype != TLI_F32 && dtype != TLI_BF16)) return 0;
+    if (B < 1 || K < 1 || K > kMaxK || !vocab_ok(Vt) || !vocab_ok(Vd) || (dtype != TLI_F32 && dtype != TLI_BF16)) return 0;
     if ((int64_t)B * K > 0x7fffffff / 64) return 0;
     return layout(B, K, Vt, Vd, dtype).total;
 }
@@ -933,7 +937,7 @@ int tli_acceptance_rates(const tli_map* map, const void* logits_t, const void* l
 }
 
 size_t tli_warp_workspace_bytes(int32_t R, int32_t V, tli_dtype dtype) {
-    if (R < 1 || R > 0x7fffffff / 64 || V < 1 || (dtype != TLI_F32 && dtype != TLI_BF16)) return 0;
+    if (R < 1 || R > 0x7fffffff / 64 || !vocab_ok(V) || (dtype != TLI_F32 && dtype != TLI_BF16)) return 0;
     const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
     const Plan pl = make_plan(V, R, chunk);
     return align256((size_t)R * pl.nsplit * sizeof(Part)) + align256((size_t)R * sizeof(WarpRow));
@@ -943,7 +947,7 @@ int tli_warp_rows(const tli_map* map, const void* logits, tli_dtype dtype, int64
                   float temp, int32_t top_k, float top_p, void* logits_out, int64_t out_stride_elems, float* thr,
                   int32_t* kept, int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!logits || !logits_out || !row_status || !workspace) return TLI_ERR_INVALID_ARG;
-    if (R < 1 || R > 0x7fffffff / 64 || V < 1 || !(temp > 0.f) || !std::isfinite(temp)) return TLI_ERR_INVALID_ARG;
+    if (R < 1 || R > 0x7fffffff / 64 || !vocab_ok(V) || !(temp > 0.f) || !std::isfinite(temp)) return TLI_ERR_INVALID_ARG;
     if (!(top_p > 0.f) || (map && V != map->Vd)) return TLI_ERR_INVALID_ARG;
     if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
     const int epv = dtype == TLI_BF16 ? 8 : 4;
@@ -990,7 +994,7 @@ int tli_warp_rows(const tli_map* map, const void* logits, tli_dtype dtype, int64
 }
 
 size_t tli_sample_rows_workspace_bytes(int32_t R, int32_t V, tli_dtype dtype) {
-    if (R < 1 || R > 0x7fffffff / 64 || V < 1 || (dtype != TLI_F32 && dtype != TLI_BF16)) return 0;
+    if (R < 1 || R > 0x7fffffff / 64 || !vocab_ok(V) || (dtype != TLI_F32 && dtype != TLI_BF16)) return 0;
     return rows_workspace(R, V, dtype);
 }
 
@@ -1020,7 +1024,7 @@ int tli_exact_match_verify(const void* logits_t, tli_dtype dtype, int32_t B, int
                            void* hip_stream) {
     if (!logits_t || !draft_t || !n_accepted || !out_tok || !tgt_tok || !seq_status || !workspace)
         return TLI_ERR_INVALID_ARG;
-    if (B < 1 || m < 1 || m >= kMaxK || (int64_t)B * (m + 1) > 0x7fffffff / 64 || Vt < 1) return TLI_ERR_INVALID_ARG;
+    if (B < 1 || m < 1 || m >= kMaxK || (int64_t)B * (m + 1) > 0x7fffffff / 64 || !vocab_ok(Vt)) return TLI_ERR_INVALID_ARG;
     if (!(temp_t >= 0.f) || !std::isfinite(temp_t) || (temp_t > 0.f && !u)) return TLI_ERR_INVALID_ARG;
     if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
     const int epv = dtype == TLI_BF16 ? 8 : 4;
@@ -1040,7 +1044,7 @@ int tli_exact_match_verify(const void* logits_t, tli_dtype dtype, int32_t B, int
 }
 
 size_t tli_exact_match_workspace_bytes(int32_t B, int32_t m, int32_t Vt, tli_dtype dtype) {
-    if (B < 1 || m < 1 || m >= kMaxK || (int64_t)B * (m + 1) > 0x7fffffff / 64 || Vt < 1 ||
+    if (B < 1 || m < 1 || m >= kMaxK || (int64_t)B * (m + 1) > 0x7fffffff / 64 || !vocab_ok(Vt) ||
         (dtype != TLI_F32 && dtype != TLI_BF16))
         return 0;
     const int R = B * (m + 1);

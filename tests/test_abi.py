@@ -51,6 +51,8 @@ def test_build_map_validation(lib):
     assert lib.tli_build_map(arr.ctypes.data_as(ctypes.c_void_p), 0, 7, ctypes.byref(ctypes.c_void_p()), None) == -1
     assert lib.tli_build_map(arr.ctypes.data_as(ctypes.c_void_p), 3, 0, ctypes.byref(ctypes.c_void_p()), None) == -1
     assert lib.tli_build_map(arr.ctypes.data_as(ctypes.c_void_p), 3, 7, None, None) == -1
+    assert lib.tli_build_map(arr.ctypes.data_as(ctypes.c_void_p), 3, (1 << 30) + 1, ctypes.byref(ctypes.c_void_p()), None) == -1
+    assert binding.tli_workspace_bytes(1, 1, (1 << 30) + 1, 10, binding.TLI_F32) == 0
 
 
 def test_status_strings_and_workspace(lib):
