@@ -316,6 +316,15 @@ int tli_calib_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_s
 int tli_calib_read(const void* src_dev, size_t bytes, size_t slab_bytes, int32_t nontemporal, uint32_t* out_dev,
                    void* hip_stream);
 
+/*
+ * Benchmark utility (not part of the method): what the HIP runtime reports for the current device, so that a
+ * bandwidth figure can be quoted against the machine's own numbers beside the vendor's.
+ *   out [4] host : memory clock in kHz, memory bus width in bits, compute units, engine clock in kHz
+ *                  (0 for an attribute the runtime does not report)
+ * TLI_ERR_HIP if no device can be queried.
+ */
+int tli_device_info(int32_t* out);
+
 /* Human-readable name of a tli_status value. */
 const char* tli_status_string(int status);
 

@@ -24,7 +24,7 @@ EXPORTS = (
     "tli_union_draft_sample", "tli_union_verify", "tli_acceptance_rates_workspace_bytes", "tli_acceptance_rates",
     "tli_sample_rows_workspace_bytes", "tli_sample_rows", "tli_greedy_draft", "tli_exact_match_workspace_bytes",
     "tli_exact_match_verify", "tli_draft_sample_compact", "tli_verify_compact",
-    "tli_warp_workspace_bytes", "tli_warp_rows", "tli_map_dry_run", "tli_calib_read",
+    "tli_warp_workspace_bytes", "tli_warp_rows", "tli_map_dry_run", "tli_calib_read", "tli_device_info",
     "tli_d2t_from_strings",
 )
 KERNELS = ("lse", "accept", "final_scan", "final_pick", "draft_scan", "draft_pick")
@@ -101,6 +101,8 @@ def load_library() -> ctypes.CDLL:
     lib.tli_calib_copy.restype = ctypes.c_int
     lib.tli_calib_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_size_t, i32, vp, vp]
     lib.tli_calib_read.restype = ctypes.c_int
+    lib.tli_device_info.argtypes = [ctypes.POINTER(i32)]
+    lib.tli_device_info.restype = ctypes.c_int
     lib.tli_map_dry_run.argtypes = [vp, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.tli_map_dry_run.restype = ctypes.c_int
     lib.tli_d2t_from_strings.argtypes = [ctypes.c_char_p, vp, i32, ctypes.c_char_p, vp, i32, vp, ctypes.POINTER(i32)]
@@ -484,3 +486,13 @@ def tli_calib_read(src: torch.Tensor, slab_bytes: int, nontemporal: bool, out: t
     rc = load_library().tli_calib_read(_ptr(src), n, int(slab_bytes), int(bool(nontemporal)), _ptr(out), _stream(stream))
     if rc != 0:
         raise TliError(rc, "tli_calib_read")
+
+
+def tli_device_info() -> dict:
+    """Memory clock (kHz), memory bus width (bits), compute units and engine clock (kHz) as the HIP runtime reports
+    them for the current device (0 where it reports nothing)."""
+    out = (ctypes.c_int32 * 4)()
+    rc = load_library().tli_device_info(out)
+    if rc != 0:
+        raise TliError(rc, "tli_device_info")
+    return dict(memory_clock_khz=int(out[0]), memory_bus_bits=int(out[1]), compute_units=int(out[2]), clock_khz=int(out[3]))

@@ -445,6 +445,21 @@ int tli_calib_read(const void* src, size_t bytes, size_t slab_bytes, int32_t non
     return hipGetLastError() == hipSuccess ? TLI_OK : TLI_ERR_HIP;
 }
 
+int tli_device_info(int32_t* out) {
+    if (!out) return TLI_ERR_INVALID_ARG;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return TLI_ERR_HIP;
+    const hipDeviceAttribute_t attr[4] = {hipDeviceAttributeMemoryClockRate, hipDeviceAttributeMemoryBusWidth,
+                                          hipDeviceAttributeMultiprocessorCount, hipDeviceAttributeClockRate};
+    for (int i = 0; i < 4; ++i) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, attr[i], dev) != hipSuccess) v = 0;
+        out[i] = v;
+    }
+    (void)hipGetLastError();  // an attribute the runtime does not know is reported as 0, not as a sticky error
+    return TLI_OK;
+}
+
 int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls, int32_t every) {
     tli_profile_disable();
     if (max_calls < 1 || max_calls > (1 << 20) || every < 1) return TLI_ERR_INVALID_ARG;

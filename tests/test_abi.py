@@ -76,6 +76,7 @@ def test_hot_calls_reject_null_arguments(lib):
     lib.tli_free_map(z)  # freeing NULL is a no-op
     assert lib.tli_calib_read(z, 4096, 4096, 0, z, z) == -1
     assert lib.tli_calib_copy(z, z, 16, z) == -1
+    assert lib.tli_device_info(None) == -1
 
 
 def test_new_entry_points_reject_null_arguments(lib):
