@@ -186,6 +186,58 @@ __device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane
     s_out = wave_sum(s);
 }
 
+// The same reduction for two sums at once -- over every id of the chunk (s_all) and over the shared ids only
+// (s_sh) -- with one exponential per logit: both are formed against the lane's maximum over ALL its ids and leave
+// with the chunk reference of the full sum.  That is only as accurate as a reduction of the shared ids alone while
+// the shared maximum of the chunk lies within 2^64 of the full one (the shared terms that matter then stay normal
+// fp32 numbers); `ok` (wave-uniform) says so, and is false as well for a chunk without shared mass or with a +inf
+// or NaN maximum: the caller then reduces the shared ids on their own.
+template <int DT, bool WHOLE>
+__device__ __forceinline__ void reduce_chunk_both(const ChunkRegs& r, int c, int lane, int V, float cs, float dl,
+                                                  const uint64_t* bits, float& ref_out, float& s_all_out,
+                                                  float& s_sh_out, bool& ok) {
+    constexpr int EPV = Traits<DT>::EPV;
+    constexpr int N = EPV * kLoads;
+    float x[N];
+    const int64_t v0 = (int64_t)c * (kWave * kLoads) + lane;
+    float m = -INFINITY, msh = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+        unpack<DT>(to_uint4(r.v[j]), x + j * EPV);
+        const int64_t vi = v0 + j * kWave;
+        const uint64_t* w = bits + ((int64_t)c * kLoads + j) * EPV;  // wave-uniform address: scalar loads
+#pragma unroll
+        for (int i = 0; i < EPV; ++i) {
+            if (!WHOLE && vi * EPV + i >= V) x[j * EPV + i] = -INFINITY;
+            const bool keep = __builtin_amdgcn_inverse_ballot_w64(w[i]);
+            m = fmaxf(m, x[j * EPV + i]);
+            msh = fmaxf(msh, keep ? x[j * EPV + i] : -INFINITY);
+        }
+    }
+    const float ref = m * cs;  // the rounded product that the fma below subtracts (see reduce_chunk)
+    const float nref = (m == -INFINITY) ? 0.f : -ref;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f}, ash[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+        const uint64_t* w = bits + ((int64_t)c * kLoads + j) * EPV;
+#pragma unroll
+        for (int i = 0; i < EPV; ++i) {
+            const float e = exp2_hw(fmaf(x[j * EPV + i], cs, nref));
+            const bool keep = __builtin_amdgcn_inverse_ballot_w64(w[i]);
+            acc[i & 3] += e;
+            ash[i & 3] += keep ? e : 0.f;
+        }
+    }
+    const float rmax = wave_max(ref), rsh = wave_max(msh * cs);
+    ok = rmax < INFINITY && rsh > -INFINITY && rmax - rsh <= 64.f;
+    const float R = ceilf(rmax);
+    const float e = ref - R;
+    const float f = (m == -INFINITY) ? 0.f : exp2_hw(fmaf(e, dl, e));
+    ref_out = R;
+    s_all_out = wave_sum((m == -INFINITY) ? 0.f : ((acc[0] + acc[1]) + (acc[2] + acc[3])) * f);
+    s_sh_out = wave_sum((m == -INFINITY) ? 0.f : ((ash[0] + ash[1]) + (ash[2] + ash[3])) * f);
+}
+
 // Stream the chunks c_begin + wave, + NW, ... < c_end of one row (NW = waves in the workgroup) through
 // `proc(regs, c, whole)` (whole: std::true_type if every element of the chunk is < V).  Whole chunks run in
 // a two-stage register pipeline: the loads of the next chunk are in flight while the current one is

@@ -403,11 +403,8 @@ void launch_diag(const tli_map* map, const void* logits_t, const void* logits_d,
     hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * pt.nsplit), dim3(kWG), 0, st, logits_t, K,
                        (int64_t)(K + 1) * Vt, (int64_t)Vt, Vt, pt.nC, pt.cps, pt.nsplit, cs_t, ratio_t,
                        (const uint64_t*)nullptr, part_t, (float2*)nullptr);
-    hipLaunchKernelGGL((k_lse<DT, true>), dim3((unsigned)rows * pd.nsplit), dim3(kWG), 0, st, logits_d, K, (int64_t)K * Vd,
-                       (int64_t)Vd, Vd, pd.nC, pd.cps, pd.nsplit, cs_d, ratio_d, map->lmask[DT], part_q1, (float2*)nullptr);
-    hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * pd.nsplit), dim3(kWG), 0, st, logits_d, K, (int64_t)K * Vd,
-                       (int64_t)Vd, Vd, pd.nC, pd.cps, pd.nsplit, cs_d, ratio_d, (const uint64_t*)nullptr, part_q2,
-                       (float2*)nullptr);
+    hipLaunchKernelGGL((k_lse_both<DT>), dim3((unsigned)rows * pd.nsplit), dim3(kWG), 0, st, logits_d, K, (int64_t)K * Vd,
+                       (int64_t)Vd, Vd, pd.nC, pd.cps, pd.nsplit, cs_d, ratio_d, map->lmask[DT], part_q1, part_q2);
     hipLaunchKernelGGL(k_diag_rows, dim3((rows + kWG - 1) / kWG), dim3(kWG), 0, st, part_t, pt.nsplit, part_q1, part_q2,
                        pd.nsplit, rows, K, ratio_t, ratio_d, c_t, c_d, frow, fbad, status);
     const int nparts = map->scan[DT].nparts;

@@ -6,6 +6,80 @@
 // ---- expected acceptance rates of every position ------------------------------------------------
 // Table of expected acceptance rates: alpha_union = sum_{T∩D} min{p, q}, alpha_tli = sum_{T∩D} min{p, q'} with
 // q' = q / sum_{T∩D} q; the theorem on the intersection algorithm states alpha_union <= alpha_tli.
+// A workgroup's partial normaliser from the (ref, s) pairs its waves parked in LDS (+ a wave's running total of the
+// chunks that did not fit there).  Called by all threads, after a barrier; ends with one.
+__device__ __forceinline__ void finish_partial(const float2* stash, int n_here, const Running& over, double kd,
+                                               float* sref, double* ssum, Part* out) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    float r_mine = over.ref;
+    for (int i = threadIdx.x; i < n_here; i += kWG) r_mine = fmaxf(r_mine, stash[i].x);
+    r_mine = wave_max(r_mine);
+    if (lane == 0) sref[wave] = r_mine;
+    __syncthreads();
+    float R = sref[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) R = fmaxf(R, sref[w]);
+    double s_mine = lane == 0 ? over.s * exp2_diff(over.ref, R, kd) : 0.0;  // a wave's overflow total counts once
+    for (int i = threadIdx.x; i < n_here; i += kWG) {
+        const float2 e = stash[i];
+        s_mine += (double)e.y * exp2_diff(e.x, R, kd);
+    }
+    s_mine = wave_sum_f64(s_mine);
+    if (lane == 0) ssum[wave] = s_mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double S = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) S += ssum[w];
+        Part p; p.ref = R; p.pad = 0.f; p.s = S;
+        *out = p;
+    }
+    __syncthreads();
+}
+
+// kernel: both drafter normalisers of every position in one pass over the drafter rows -- over the shared ids
+// (q' of the intersection algorithm, part_sh) and over all of D (q of the union algorithm, part_all).
+// grid (rows * nsplit), as k_lse.
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_lse_both(const void* __restrict__ logits, int K, int64_t seq_stride,
+                                                   int64_t row_stride, int V, int nC, int cps, int nsplit, float cs,
+                                                   double ratio, const uint64_t* __restrict__ bits,
+                                                   Part* __restrict__ part_sh, Part* __restrict__ part_all) {
+    const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
+    const int b = row / K, k = row - b * K;
+    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
+                                                    (b * seq_stride + k * row_stride) * Traits<DT>::ESZ);
+    const int lane = threadIdx.x & 63;
+    const double kd = (ratio - 1.0) * kLn2;
+    const float dl = (float)(ratio - 1.0);
+    __shared__ float2 stash_all[kLdsChunks], stash_sh[kLdsChunks];
+    __shared__ float sref[kWaves];
+    __shared__ double ssum[kWaves];
+    Running over_all, over_sh;
+    const int c0 = split * cps, c1 = min(nC, (split + 1) * cps);
+    stream_chunks<DT, kWaves>(rowv, V, c0, c1, [&](const ChunkRegs& r, int c, auto whole) {
+        float ref, s_all, ref_sh, s_sh;
+        bool ok;
+        reduce_chunk_both<DT, decltype(whole)::value>(r, c, lane, V, cs, dl, bits, ref, s_all, s_sh, ok);
+        ref_sh = ref;
+        if (!ok) reduce_chunk<DT, true, decltype(whole)::value>(r, c, lane, V, cs, dl, bits, ref_sh, s_sh);
+        const int i = c - c0;
+        if (i < kLdsChunks) {
+            if (lane == 0) {
+                stash_all[i] = make_float2(ref, s_all);
+                stash_sh[i] = make_float2(ref_sh, s_sh);
+            }
+        } else {
+            over_all.add(ref, s_all, kd);
+            over_sh.add(ref_sh, s_sh, kd);
+        }
+    });
+    __syncthreads();
+    const int n_here = min(c1 - c0, kLdsChunks);
+    finish_partial(stash_all, n_here, over_all, kd, sref, ssum, part_all + (int64_t)row * nsplit + split);
+    finish_partial(stash_sh, n_here, over_sh, kd, sref, ssum, part_sh + (int64_t)row * nsplit + split);
+}
+
 // kernel: one record per position (b, k) from the three normalisers (target row, drafter row over the
 // shared ids, drafter row over all of D).  grid (ceil(rows / 256)).
 __global__ __launch_bounds__(kWG) void k_diag_rows(const Part* __restrict__ part_t, int nsplit_t,

@@ -122,6 +122,40 @@ def test_acceptance_rates(oracle, shape):
     m.free()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_acceptance_rates_when_unshared_logits_dwarf_the_shared(oracle, dtype):
+    """Both drafter normalisers come from one pass that shares its exponentials; where the shared ids of a chunk lie
+    far below its largest logit (here: one unshared logit of +80 in the first chunk of every other row), or a chunk
+    holds no shared id at all (every chunk but the first), the shared ones are reduced on their own."""
+    chunk = 2048 if dtype == "bf16" else 1024
+    Vd, Vt, B, K, S = chunk * 3 + 24, 5000, 4, 3, 400
+    rng = np.random.default_rng(11)
+    d2t = np.full(Vd, -1, np.int32)
+    sh = np.sort(rng.permutation(chunk)[:S])                      # shared drafter ids: first chunk only
+    d2t[sh] = rng.permutation(Vt)[:S].astype(np.int32)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(12)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    lt = (torch.randn(B, K + 1, Vt, generator=gen, device=DEV) * 3).to(tdt)
+    ld = (torch.randn(B, K, Vd, generator=gen, device=DEV) * 3).to(tdt)
+    big = int(np.setdiff1d(np.arange(chunk), sh)[5])
+    ld[::2, :, big] = 80.0
+    m = binding.tli_build_map(d2t, Vt)
+    g = parity.to_host(binding.tli_acceptance_rates(m, lt, ld, 0.9, 1.0))
+    ref = oracle.acceptance_rates(synth.logits_to_numpy(lt)[:, :K].reshape(B * K, Vt),
+                                  synth.logits_to_numpy(ld).reshape(B * K, Vd), parity.f32(0.9), parity.f32(1.0), d2t, threads=4)
+    assert np.all(ref["status"] == 0) and np.all(g["status"] == 0)
+    for name in ("alpha_tli", "alpha_union"):
+        rel = np.abs(g[name].reshape(-1) - ref[name]) / ref[name]
+        print(name, "max rel err", rel.max(), "range", ref[name].min(), ref[name].max())
+        # a rate of 1e-31 is a sum of terms 2^-100: the fp32 exponent argument resolves 4e-6 there, so such a rate is
+        # held to the path's general 1e-5, the others to the 2e-6 of every other acceptance-rate test
+        assert rel.max() < (1e-5 if name == "alpha_union" else 2e-6)
+        assert rel[ref[name] > 1e-6].max() < 2e-6
+    assert ref["alpha_union"].reshape(B, K)[0].max() < 1e-20 < ref["alpha_union"].reshape(B, K)[1].min()
+    m.free()
+
+
 @pytest.mark.parametrize("dtype,V,R,stride", [("bf16", 2048 * 3 + 40, 9, 2048 * 3 + 48), ("f32", 5000, 3, 5000),
                                                ("bf16", 151936, 2, 151936), ("bf16", 4104, 1500, 4104)])
 def test_sample_rows_and_argmax(oracle, dtype, V, R, stride):
