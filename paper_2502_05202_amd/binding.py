@@ -386,8 +386,9 @@ def tli_warp_rows(logits: torch.Tensor, temp: float, top_k: int, top_p: float, m
     assert logits.is_cuda and logits.dim() == 2 and logits.stride(-1) == 1
     R, V = logits.shape
     code = _dtype_code(logits)
-    if out is None:
-        out = torch.empty_like(logits, memory_format=torch.contiguous_format)
+    if out is None:  # rows start on 16-byte boundaries: the row stride is V rounded up to whole vectors
+        epv = 16 // logits.element_size()
+        out = torch.empty((R, (V + epv - 1) // epv * epv), dtype=logits.dtype, device=logits.device)[:, :V]
     assert out.shape == logits.shape and out.dtype == logits.dtype and out.stride(-1) == 1
     if workspace is None:
         workspace = torch.empty(int(lib.tli_warp_workspace_bytes(R, V, code)), dtype=torch.uint8, device=logits.device)

@@ -363,7 +363,9 @@ def test_full_size_large_vocab_next_rows(oracle):
 
 
 # ---------------------------------------------------------------- logit warpers
-WARP = [("bf16", 2048 * 3 + 40, 9, 2048 * 3 + 48), ("f32", 5000, 4, 5000), ("bf16", 151936, 3, 151936), ("f32", 33000, 2, 33000)]
+WARP = [("bf16", 2048 * 3 + 40, 9, 2048 * 3 + 48), ("f32", 5000, 4, 5000), ("bf16", 151936, 3, 151936), ("f32", 33000, 2, 33000),
+        # rows that do not end on a vector boundary (the warped copy gets a row stride of whole vectors)
+        ("bf16", 18847, 3, 18848), ("f32", 5001, 2, 5008)]
 
 
 def _check_warp(oracle, view, rows, tau, top_k, top_p, d2t, m, pick=None):
