@@ -135,7 +135,10 @@ def test_compact_drafter_layout(oracle, shape):
     rep, ref = parity.compare_draft(oracle, ld_np.reshape(B * K, Vd), w.tau_d, d2t, ud, gh, threads=8)
     assert rep["hard"] == 0 and rep["max_lse_err"] < 5e-7
     full = parity.to_host(binding.tli_draft_sample(m, inp["logits_d"], w.tau_d, inp["u_draft"].reshape(-1), ws))
-    assert np.array_equal(gh["tok_d"], full["tok_d"]) and np.array_equal(gh["tok_t"], full["tok_t"])
+    # the two layouts cut a row into different chunks: only a draw inside the oracle's near-tie window may differ
+    differ = gh["tok_d"] != full["tok_d"]
+    assert np.all(ref["margin"][differ] < parity.NEAR_TIE), np.nonzero(differ)[0]
+    assert np.array_equal(gh["tok_t"][~differ], full["tok_t"][~differ])
     ua = inp["u_acc"].cpu().numpy().astype(np.float64)
     uf = inp["u_fin"].cpu().numpy().astype(np.float64)
     tok = torch.from_numpy(ref["tok_d"]).to(DEV)
