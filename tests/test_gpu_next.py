@@ -542,3 +542,28 @@ def test_next_rows_beyond_32_bit_offsets(oracle):
     mp.free()
     del lt, ld, ws
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("i", range(8))
+def test_random_shapes_next_rows(oracle, i):
+    """Seeded random vocabulary sizes, overlaps, storage types, temperatures and batch shapes through the parity
+    checks above (union algorithm, acceptance rates, exact-match tail, one token per row, warpers), within what those
+    checks assume of a shape (unshared drafter ids exist, two positions or more, rows longer than the stretch the warp
+    test blanks out)."""
+    rng = np.random.default_rng(7000 + i)
+    dtype = "bf16" if rng.random() < 0.6 else "f32"
+    epv = 8 if dtype == "bf16" else 4
+    Vt, Vd = int(rng.integers(40, 12000)) * epv, int(rng.integers(40, 9000)) * epv
+    if rng.random() < 0.3:
+        Vt, Vd = Vd, Vt
+    S = int(rng.integers(1, int(0.8 * min(Vt, Vd)) + 1))
+    shape = (int(rng.integers(1, 7)), int(rng.integers(2, 6)), Vt, Vd, S, dtype, float(rng.uniform(0.4, 1.4)),
+             float(rng.uniform(0.4, 1.4)))
+    V, R = int(rng.integers(300, 60000)), int(rng.integers(1, 12))
+    stride = (V + epv - 1) // epv * epv + epv * int(rng.integers(0, 3))
+    print(shape, (V, R, stride))
+    test_union_draft_and_verify(oracle, shape)
+    test_acceptance_rates(oracle, shape)
+    test_exact_match_tail_sampled(oracle, shape)
+    test_sample_rows_and_argmax(oracle, dtype, V, R, stride)
+    test_warp_rows(oracle, dtype, V, R, stride)
