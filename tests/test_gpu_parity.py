@@ -138,6 +138,55 @@ def test_nearly_identical_models(oracle, rho, dtype):
     assert (n < w.K).any()  # some rows do sample from a residual
 
 
+STRESS = ["scale_up", "scale_down", "neginf", "ties", "const", "onehot", "cold", "hot"]
+
+
+@pytest.mark.parametrize("mode", STRESS)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_value_distributions(oracle, mode, dtype):
+    """The same path on logits far from the workloads' recipes: magnitudes of +-100 and of 0.1, half of every row at
+    -inf, logits rounded to halves (ties everywhere), constant rows (a uniform distribution: every chunk edge is a
+    CDF tie candidate), rows with a single finite logit, temperatures of 0.04 and of 8."""
+    tt, td = {"cold": (0.05, 0.04), "hot": (8.0, 6.0)}.get(mode, (0.9, 1.1))
+    w = synth.WORKLOADS[4].scaled(Vt=2048 * 9 + 24, Vd=2048 * 6 + 16, S=7000, dtype=dtype, B=6, K=4, tau_t=tt, tau_d=td,
+                                  cfg=400 + STRESS.index(mode))
+    inp = synth.make_inputs(w, DEV)
+    lt, ld = inp["logits_t"], inp["logits_d"]
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(17)
+    if mode in ("scale_up", "scale_down"):
+        f = 12.0 if mode == "scale_up" else 0.05
+        lt.copy_((lt.float() * f).to(lt.dtype))
+        ld.copy_((ld.float() * f).to(ld.dtype))
+    elif mode == "neginf":
+        lt[torch.rand(lt.shape, generator=gen, device=DEV) < 0.5] = float("-inf")
+        ld[torch.rand(ld.shape, generator=gen, device=DEV) < 0.5] = float("-inf")
+    elif mode == "ties":
+        lt.copy_((torch.round(lt.float() * 2) / 2).to(lt.dtype))
+        ld.copy_((torch.round(ld.float() * 2) / 2).to(ld.dtype))
+    elif mode == "const":
+        lt[:, ::2, :] = 1.25
+        ld[:, ::2, :] = -3.5
+    elif mode == "onehot":
+        rng = np.random.default_rng(3)
+        sh = np.nonzero(inp["d2t"] >= 0)[0]
+        lt[:] = float("-inf")
+        ld[:] = float("-inf")
+        for b in range(w.B):
+            for k in range(w.K):
+                x = int(sh[rng.integers(0, len(sh))])
+                ld[b, k, x] = 0.5
+                lt[b, k, int(rng.integers(0, w.Vt))] = 1.0
+                if (b + k) % 2:
+                    lt[b, k, int(inp["d2t"][x])] = 2.0  # the draft's own target id carries mass: accepted now and then
+            lt[b, w.K, int(rng.integers(0, w.Vt))] = 0.0
+    res = parity.run_case(oracle, inp, threads=8)
+    _check(res)
+    if mode == "onehot":
+        n = res["ref_verify"]["n_acc"]
+        assert (n > 0).any() and (n < w.K).any()
+
+
 def test_row_stride_and_unaligned_vocab(oracle):
     """tli_draft_sample on rows that are views into a wider buffer; Vd not a multiple of the vector."""
     Vd, Vt, S, R, stride = 3001, 4000, 1200, 9, 3008
