@@ -515,7 +515,7 @@ __global__ __launch_bounds__(kWG) void k_warp_apply(const void* __restrict__ log
     const int nvec = (V + EPV - 1) / EPV;
     const unsigned int npat = (DT == TLI_BF16) ? 0xff80u : 0xff800000u;
     const int lane = threadIdx.x & 63;
-    int n = 0;
+    int n = 0, n_k = 0;  // survivors of both warpers; survivors of top-k alone (all competing ids if it is off)
     stream_chunks<DT, kWaves>(rowv, V, 0, nC, [&](const ChunkRegs& r, int c, auto) {
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
@@ -528,9 +528,11 @@ __global__ __launch_bounds__(kWG) void k_warp_apply(const void* __restrict__ log
             uint32_t o[EPV];
 #pragma unroll
             for (int i = 0; i < EPV; ++i) {
-                const bool live = vi * EPV + i < V && ((mb >> i) & 1u) && !w.status && x[i] > -INFINITY &&
-                                  (!any || warp_key<DT>(x[i]) >= tkey);
+                const bool competes = vi * EPV + i < V && ((mb >> i) & 1u) && !w.status && x[i] > -INFINITY;
+                const uint32_t key = warp_key<DT>(x[i]);
+                const bool live = competes && (!any || key >= tkey);
                 n += live ? 1 : 0;
+                n_k += (competes && (!w.k_on || key >= w.kprefix)) ? 1 : 0;
                 o[i] = live ? (DT == TLI_BF16 ? as_u(x[i]) >> 16 : as_u(x[i])) : npat;
             }
             uint32_t nw[4];
@@ -557,15 +559,18 @@ __global__ __launch_bounds__(kWG) void k_warp_apply(const void* __restrict__ log
         }
     });
 #pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) n += __shfl_xor(n, d, kWave);
-    __shared__ int sn[kWaves];
-    if ((threadIdx.x & 63) == 0) sn[threadIdx.x >> 6] = n;
+    for (int d = 1; d < kWave; d <<= 1) { n += __shfl_xor(n, d, kWave); n_k += __shfl_xor(n_k, d, kWave); }
+    __shared__ int sn[kWaves], snk[kWaves];
+    if ((threadIdx.x & 63) == 0) { sn[threadIdx.x >> 6] = n; snk[threadIdx.x >> 6] = n_k; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        int tot = 0;
-        for (int i = 0; i < kWaves; ++i) tot += sn[i];
+        int tot = 0, tot_k = 0;
+        for (int i = 0; i < kWaves; ++i) { tot += sn[i]; tot_k += snk[i]; }
         if (kept) kept[row] = tot;
-        if (thr) thr[row] = w.status ? NAN : (any ? warp_unkey<DT>(tkey) : -INFINITY);
+        // the threshold reported is the value that decided: top-p's only if it dropped something that top-k had
+        // kept, else top-k's (the k-th largest logit), else -inf
+        const float th = tot < tot_k ? warp_unkey<DT>(tkey) : (w.k_on ? warp_unkey<DT>(w.kprefix) : -INFINITY);
+        if (thr) thr[row] = w.status ? NAN : th;
         status[row] = w.status;
     }
 }
