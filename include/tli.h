@@ -49,7 +49,8 @@ typedef enum {
     TLI_ERR_EMPTY_INTERSECTION = -4, /* no shared token: q' would be 0/0 and nothing can be accepted   */
     TLI_ERR_ALLOC = -5,              /* device allocation failed, or the workspace is too small        */
     TLI_ERR_HIP = -6,                /* a HIP runtime call failed                                      */
-    TLI_ERR_INTERNAL = -7            /* the library's own tables failed their consistency check        */
+    TLI_ERR_INTERNAL = -7,           /* the library's own tables failed their consistency check        */
+    TLI_ERR_TOO_LARGE = -8           /* tli_verify_static: the problem needs more than the fixed scratch */
 } tli_status;
 
 /* bits of row_status / seq_status */
@@ -156,6 +157,26 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
                const float* u_acc, const float* u_fin, int32_t* n_accepted, int32_t* out_tok,
                uint8_t* accept, double* p_tok, double* q_tok, double* lse_p, int32_t* seq_status,
                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * tli_verify for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and kernels as tli_verify, without
+ * the workspace: the scratch is a fixed array inside the library's device code, tli_verify_static_max_bytes() =
+ * 8 MiB on every GPU the library runs on, held until the process ends.  The call allocates nothing and only
+ * enqueues kernels on the stream (the array's device address is looked up when a map is built on the device).
+ *   TLI_ERR_TOO_LARGE   : tli_workspace_bytes(B, K, Vt, Vd, dtype) exceeds the fixed scratch; nothing was enqueued
+ *                         (the large-vocabulary batch B=256, K=8, Vt=256000, Vd=128256 in bf16 needs 3.6 MB)
+ *   TLI_ERR_INVALID_ARG : also when the current device is not the one the map was built on
+ * All calls on one GPU share that GPU's array: two calls whose kernels may overlap (different streams, or a graph
+ * replayed beside an eager call) race on it; calls on one stream are ordered and safe.  Nothing in the scratch has
+ * to start at zero, so the previous call's contents do no harm.
+ */
+size_t tli_verify_static_max_bytes(void);
+int tli_verify_static(const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype, int32_t B,
+                      int32_t K, float temp_t, float temp_d, const int32_t* tok_d, const double* lse_q,
+                      const float* u_acc, const float* u_fin, int32_t* n_accepted, int32_t* out_tok,
+                      uint8_t* accept, double* p_tok, double* q_tok, double* lse_p, int32_t* seq_status,
+                      void* hip_stream);
 
 /*
  * Compact drafter layout, for a drafter whose output head is pruned to the shared tokens (the intersection

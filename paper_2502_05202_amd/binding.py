@@ -25,7 +25,7 @@ EXPORTS = (
     "tli_sample_rows_workspace_bytes", "tli_sample_rows", "tli_greedy_draft", "tli_exact_match_workspace_bytes",
     "tli_exact_match_verify", "tli_draft_sample_compact", "tli_verify_compact",
     "tli_warp_workspace_bytes", "tli_warp_rows", "tli_map_dry_run", "tli_calib_read", "tli_device_info",
-    "tli_d2t_from_strings",
+    "tli_d2t_from_strings", "tli_verify_static", "tli_verify_static_max_bytes",
 )
 KERNELS = ("lse", "accept", "final_scan", "final_pick", "draft_scan", "draft_pick")
 
@@ -62,6 +62,11 @@ def load_library() -> ctypes.CDLL:
     lib.tli_verify.argtypes = [vp, vp, vp, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                vp, vp, vp, ctypes.c_size_t, vp]
     lib.tli_verify.restype = ctypes.c_int
+    lib.tli_verify_static.argtypes = [vp, vp, vp, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                      vp, vp, vp]
+    lib.tli_verify_static.restype = ctypes.c_int
+    lib.tli_verify_static_max_bytes.argtypes = []
+    lib.tli_verify_static_max_bytes.restype = ctypes.c_size_t
     lib.tli_draft_sample_compact.argtypes = lib.tli_draft_sample.argtypes
     lib.tli_draft_sample_compact.restype = ctypes.c_int
     lib.tli_verify_compact.argtypes = [vp, vp, vp, i64, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp, vp,
@@ -322,6 +327,28 @@ def tli_verify(m: TliMap, logits_t: torch.Tensor, logits_d: torch.Tensor, temp_t
                         _stream(stream))
     if rc != 0:
         raise TliError(rc, _entry)
+    return out
+
+
+def tli_verify_static(m: TliMap, logits_t: torch.Tensor, logits_d: torch.Tensor, temp_t: float, temp_d: float,
+                      tok_d: torch.Tensor, lse_q, u_acc: torch.Tensor, u_fin: torch.Tensor, out: dict,
+                      stream=None) -> dict:
+    """tli_verify without a workspace (the library's fixed scratch); `out` must be given: nothing is allocated."""
+    lib = load_library()
+    B, K1, Vt = logits_t.shape
+    K = K1 - 1
+    assert logits_t.is_cuda and logits_t.is_contiguous() and logits_d.is_contiguous()
+    assert tuple(logits_d.shape) == (B, K, m.Vd) and Vt == m.Vt and logits_t.dtype == logits_d.dtype
+    assert tok_d.dtype == torch.int32 and tok_d.numel() == B * K and tok_d.is_contiguous()
+    assert lse_q is None or (lse_q.dtype == torch.float64 and lse_q.numel() == B * K and lse_q.is_contiguous())
+    assert u_acc.dtype == torch.float32 and u_acc.numel() == B * K and u_acc.is_contiguous()
+    assert u_fin.dtype == torch.float32 and u_fin.numel() == B and u_fin.is_contiguous()
+    rc = lib.tli_verify_static(m.handle, _ptr(logits_t), _ptr(logits_d), _dtype_code(logits_t), B, K, float(temp_t),
+                               float(temp_d), _ptr(tok_d), _ptr(lse_q), _ptr(u_acc), _ptr(u_fin), _ptr(out["n_accepted"]),
+                               _ptr(out["out_tok"]), _ptr(out.get("accept")), _ptr(out.get("p_tok")),
+                               _ptr(out.get("q_tok")), _ptr(out.get("lse_p")), _ptr(out["status"]), _stream(stream))
+    if rc != 0:
+        raise TliError(rc, "tli_verify_static")
     return out
 
 

@@ -18,6 +18,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string_view>
 #include <unordered_map>
@@ -419,6 +420,35 @@ void launch_diag(const tli_map* map, const void* logits_t, const void* logits_d,
 }
 }  // namespace
 
+// ---- scratch of the entry point that allocates nothing (tli_verify_static) -----------------------------
+// A fixed device array that lives in the library's code object: every GPU the library runs on holds its own copy
+// at its own address until the process ends.  In host code the array's NAME is only a handle for the symbol, not a
+// device address; the address on a given device is asked for once, with that device current, and kept.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the CURRENT device (which must be `dev`); resolved on first use
+int static_scratch(int dev, void** out) {
+    if (dev < 0 || dev >= kMaxDevices) return TLI_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return TLI_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return TLI_OK;
+}
+}  // namespace
+
 extern "C" {
 
 int tli_calib_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
@@ -512,6 +542,7 @@ const char* tli_status_string(int status) {
         case TLI_ERR_ALLOC: return "TLI_ERR_ALLOC";
         case TLI_ERR_HIP: return "TLI_ERR_HIP";
         case TLI_ERR_INTERNAL: return "TLI_ERR_INTERNAL";
+        case TLI_ERR_TOO_LARGE: return "TLI_ERR_TOO_LARGE";
         default: return "TLI_ERR_UNKNOWN";
     }
 }
@@ -811,6 +842,10 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
         }
     }
     if (hipGetDevice(&m->device) != hipSuccess) { delete m; return TLI_ERR_HIP; }
+    {   // the static scratch of tli_verify_static is looked up here, so that call itself only enqueues kernels
+        void* unused = nullptr;
+        (void)static_scratch(m->device, &unused);
+    }
     bool ok = hipMalloc(&m->d2t, d2t.size() * 4) == hipSuccess && hipMalloc(&m->t2d, t2d.size() * 4) == hipSuccess &&
               hipMalloc(&m->lmask[0], lmask[0].size() * 8) == hipSuccess &&
               hipMalloc(&m->lmask[1], lmask[1].size() * 8) == hipSuccess;
@@ -1126,6 +1161,28 @@ int tli_verify(const tli_map* map, const void* logits_t, const void* logits_d, t
                void* hip_stream) {
     return verify_impl(0, 0, map, logits_t, logits_d, dtype, B, K, temp_t, temp_d, tok_d, lse_q, u_acc, u_fin, n_accepted,
                        out_tok, accept, p_tok, q_tok, lse_p, seq_status, workspace, workspace_bytes, hip_stream);
+}
+
+size_t tli_verify_static_max_bytes(void) { return kStaticScratchBytes; }
+
+int tli_verify_static(const tli_map* map, const void* logits_t, const void* logits_d, tli_dtype dtype, int32_t B, int32_t K,
+                      float temp_t, float temp_d, const int32_t* tok_d, const double* lse_q, const float* u_acc,
+                      const float* u_fin, int32_t* n_accepted, int32_t* out_tok, uint8_t* accept, double* p_tok,
+                      double* q_tok, double* lse_p, int32_t* seq_status, void* hip_stream) {
+    if (!map) return TLI_ERR_INVALID_ARG;
+    const size_t need = tli_workspace_bytes(B, K, map->Vt, map->Vd, dtype);
+    if (need == 0) return TLI_ERR_INVALID_ARG;
+    if (need > kStaticScratchBytes) return TLI_ERR_TOO_LARGE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return TLI_ERR_HIP;
+    if (dev != map->device) return TLI_ERR_INVALID_ARG;  // the map's tables and the scratch must be on the current device
+    void* ws = nullptr;
+    const int rc = static_scratch(dev, &ws);
+    if (rc != TLI_OK) return rc;
+    // Nothing in the scratch has to start at zero: every kernel of the call writes what a later one reads (the
+    // per-sequence flag is reset by the accept kernel), so the previous call's contents are simply overwritten.
+    return verify_impl(0, 0, map, logits_t, logits_d, dtype, B, K, temp_t, temp_d, tok_d, lse_q, u_acc, u_fin, n_accepted,
+                       out_tok, accept, p_tok, q_tok, lse_p, seq_status, ws, kStaticScratchBytes, hip_stream);
 }
 
 int tli_verify_compact(const tli_map* map, const void* logits_t, const void* logits_c, int64_t c_row_stride_elems,
