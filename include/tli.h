@@ -62,8 +62,9 @@ enum {
 };
 
 /*
- * Vocabulary intersection T∩D (the paper treats vocabularies as sets of strings; two tokens are
- * shared iff their strings are equal, which the caller resolves into d2t).
+ * Vocabulary intersection T∩D (section "Preliminaries", the notation paragraph: a vocabulary is a set of
+ * strings, so two tokens are shared iff their strings are equal, which the caller resolves into d2t; the
+ * intersection algorithm needs nothing else of the two vocabularies).
  *   d2t_host [Vd] host : target id of drafter id x, or -1 if x is not in T.  Must be injective on
  *                        the ids it maps.
  *   out_map            : receives the new map (tables live on the current HIP device).
@@ -295,58 +296,6 @@ int tli_warp_rows(const tli_map* map, const void* logits, tli_dtype dtype, int64
                   int32_t V, float temp, int32_t top_k, float top_p, void* logits_out, int64_t out_stride_elems,
                   float* thr, int32_t* kept, int32_t* row_status, void* workspace, size_t workspace_bytes,
                   void* hip_stream);
-
-/*
- * Optional per-kernel timing for benchmarks (not part of the method): while enabled, the hot calls
- * record a HIP event pair around each selected kernel on the caller's stream.  Not thread-safe.
- *   tli_profile_enable  : creates 2*max_calls events per selected kernel (bit k of kernel_mask selects
- *                         kernel k of tli_kernel_id) and records one launch in `every` (an event between two
- *                         kernels costs a few microseconds of idle GPU, so a timed loop samples);
- *                         recording stops silently once the events are used up.
- *   tli_profile_collect : waits for the recorded events of one kernel, returns the summed duration
- *                         in milliseconds and the number of launches, and resets that kernel's counter.
- *   tli_profile_disable : destroys the events.
- */
-typedef enum {
-    TLI_KERNEL_LSE = 0,        /* tli_verify: log-normalisers of the K target rows of every sequence      */
-    TLI_KERNEL_ACCEPT = 1,     /* tli_verify: accept tests + first-reject scan                            */
-    TLI_KERNEL_FINAL_SCAN = 2, /* tli_verify: chunk masses of the residual / bonus rows                   */
-    TLI_KERNEL_FINAL_PICK = 3, /* tli_verify: draw of the extra token                                     */
-    TLI_KERNEL_DRAFT_SCAN = 4, /* row samplers: scan of the rows (+ the draw, one workgroup/row); argmax scan  */
-    TLI_KERNEL_DRAFT_PICK = 5, /* row samplers: the draw when rows are split over workgroups; argmax finish   */
-    TLI_KERNEL_COUNT = 6
-} tli_kernel_id;
-int tli_profile_enable(uint32_t kernel_mask, int32_t max_calls, int32_t every);
-int tli_profile_collect(int32_t kernel, double* total_ms, int32_t* launches);
-void tli_profile_disable(void);
-
-/*
- * Benchmark utility (not part of the method): a plain device-to-device copy of `bytes` (multiple of
- * 16, both pointers 16-byte aligned) by kernel k_calib_copy.  Hardware byte counters read for it are
- * compared with its known traffic (bytes read + bytes written) to calibrate those counters.
- */
-int tli_calib_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_stream);
-/*
- * Benchmark utility (not part of the method): a read-only streaming pass over `bytes` of device memory with plain
- * 16-byte loads, the yardstick beside the vendor's peak that the streaming kernels are held against.  The buffer is
- * read as bytes / slab_bytes contiguous slabs, a workgroup of 256 threads per slab, in the access pattern of the
- * normaliser kernel (slab_bytes = one logit row's bytes gives that kernel's launch shape).
- *   src_dev      dev, 16-byte aligned; bytes a multiple of slab_bytes; slab_bytes a multiple of 4096
- *   nontemporal  0: ordinary loads, 1: loads that bypass cache allocation (what the kernels use)
- *   out_dev      dev [bytes / slab_bytes] uint32 scratch (a word per workgroup; practically never written)
- * Only enqueues a kernel on the stream.
- */
-int tli_calib_read(const void* src_dev, size_t bytes, size_t slab_bytes, int32_t nontemporal, uint32_t* out_dev,
-                   void* hip_stream);
-
-/*
- * Benchmark utility (not part of the method): what the HIP runtime reports for the current device, so that a
- * bandwidth figure can be quoted against the machine's own numbers beside the vendor's.
- *   out [4] host : memory clock in kHz, memory bus width in bits, compute units, engine clock in kHz
- *                  (0 for an attribute the runtime does not report)
- * TLI_ERR_HIP if no device can be queried.
- */
-int tli_device_info(int32_t* out);
 
 /* Human-readable name of a tli_status value. */
 const char* tli_status_string(int status);

@@ -1,4 +1,4 @@
-"""Thin ctypes binding over the C ABI in include/tli.h (same names, argument marshalling only).
+"""Thin ctypes binding over the C ABI in include/tli.h and include/tli_bench.h (same names, argument marshalling only).
 
 torch is used for device buffers and the current HIP stream; every step of the path runs in the
 library's kernels.  There is no CPU fallback: if libtli.so is missing or fails to load, the first
@@ -26,6 +26,7 @@ EXPORTS = (
     "tli_exact_match_verify", "tli_draft_sample_compact", "tli_verify_compact",
     "tli_warp_workspace_bytes", "tli_warp_rows", "tli_map_dry_run", "tli_calib_read", "tli_device_info",
     "tli_d2t_from_strings", "tli_verify_static", "tli_verify_static_max_bytes",
+    "tli_tune_final_path",
 )
 KERNELS = ("lse", "accept", "final_scan", "final_pick", "draft_scan", "draft_pick")
 
@@ -67,6 +68,8 @@ def load_library() -> ctypes.CDLL:
     lib.tli_verify_static.restype = ctypes.c_int
     lib.tli_verify_static_max_bytes.argtypes = []
     lib.tli_verify_static_max_bytes.restype = ctypes.c_size_t
+    lib.tli_tune_final_path.argtypes = [i32]
+    lib.tli_tune_final_path.restype = ctypes.c_int
     lib.tli_draft_sample_compact.argtypes = lib.tli_draft_sample.argtypes
     lib.tli_draft_sample_compact.restype = ctypes.c_int
     lib.tli_verify_compact.argtypes = [vp, vp, vp, i64, ctypes.c_int, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp, vp,
@@ -116,6 +119,13 @@ def load_library() -> ctypes.CDLL:
     lib.tli_status_string.restype = ctypes.c_char_p
     _lib = lib
     return lib
+
+
+def tli_tune_final_path(path: int) -> None:
+    """Form of tli_verify's first steps: 0 by batch size, 1 split, 2 a workgroup per sequence (see tli_bench.h)."""
+    rc = load_library().tli_tune_final_path(int(path))
+    if rc != 0:
+        raise TliError(rc, "tli_tune_final_path")
 
 
 def status_string(code: int) -> str:

@@ -26,12 +26,14 @@
 #include <vector>
 
 #include "tli.h"
+#include "tli_bench.h"
 
 namespace {
 
 #include "tli_device_common.h"
 #include "tli_softmax_kernels.h"
 #include "tli_verify_kernels.h"
+#include "tli_seq_kernels.h"
 #include "tli_next_kernels.h"
 
 // ======================================= host side ============================================
@@ -45,7 +47,10 @@ struct Plan {
 Plan make_plan(int V, int rows, int chunk) {
     Plan p;
     p.nC = (V + chunk - 1) / chunk;
-    const int target_wgs = 2048;  // ~8 workgroups of 4 waves on each of the 256 CUs
+#ifndef TLI_TARGET_WGS
+#define TLI_TARGET_WGS 2048
+#endif
+    const int target_wgs = TLI_TARGET_WGS;  // ~8 workgroups of 4 waves on each of the 256 CUs
     int want = (target_wgs + rows - 1) / rows;
     int cap = (p.nC + kWaves - 1) / kWaves;  // keep at least one chunk per wave
     p.nsplit = want < 1 ? 1 : (want > cap ? cap : want);
@@ -53,6 +58,9 @@ Plan make_plan(int V, int rows, int chunk) {
     p.nsplit = (p.nC + p.cps - 1) / p.cps;
     return p;
 }
+
+// dynamic LDS of k_lse: the chunk pairs a workgroup parks
+size_t lse_shmem(const Plan& p) { return (size_t)(p.cps < kLdsChunks ? p.cps : kLdsChunks) * sizeof(float2); }
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -121,6 +129,10 @@ struct KernelTimer {  // records start on construction, stop on destruction, if 
     }
 };
 
+// which form the first steps of tli_verify take: 0 = by batch size, 1 = split (k_lse, k_accept), 2 = a workgroup per
+// sequence (k_lse_accept_seq) wherever it fits.  Set by tli_tune_final_path (tests and benchmarks).
+int g_final_path = 0;
+
 struct DraftOut;
 template <int DT, bool MASKED>
 void launch_draft(const void* logits, int64_t row_stride, int R, int V, float temp, const Plan& pl, float cs,
@@ -153,6 +165,7 @@ struct VerifyArgs {
     int32_t* fbad;
     int union_mode;  // 0: TLI (q' over the shared ids); 1: the union algorithm (q over all of D)
     DrafterView dv;
+    int skip_lse_p = 0;  // launch_verify_lse: only the drafter normalisers (if asked for), not the target rows
     int compact;     // drafter rows hold the S shared logits in rank order
     int d_valid;     // valid entries of a drafter row (Vd, or S in the compact layout)
 };
@@ -179,6 +192,7 @@ struct tli_map {
     // list (the same for both layouts).
     struct Scan {
         int32_t nparts;
+        int32_t max_part_chunks;  // chunks of the largest part
         int32_t* cb;
         int32_t* part_n;
         int32_t* pl_g;
@@ -311,47 +325,55 @@ size_t rows_workspace(int R, int V, int dtype) {
     return tabs > parts ? tabs : parts;
 }
 
-template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
+// drafter normalisers if the caller passed none, then the normaliser partials of the K target rows of every sequence
+template <int DT> const double* launch_verify_lse(const VerifyArgs& a, hipStream_t st) {
     const int Vt = a.map->Vt, Vd = a.map->Vd, B = a.B, K = a.K, rows = B * K;
-    FinalOut fo;
-    fo.u_fin = a.u_fin; fo.n_accepted = a.n_accepted; fo.out_tok = a.out_tok; fo.lse_p = a.lse_p;
-    fo.seq_status = a.seq_status;
     const double* lse_q = a.lse_q;
     if (!lse_q) {  // the caller did not keep the drafter normalisers: one scan of the drafter rows (masked for TLI
                    // in the full layout; a compact row holds the shared ids only)
         const int64_t rs = a.dv.row_stride;
         if (a.union_mode || a.compact)
-            hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), 0, st, a.dv.base, K,
+            hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), lse_shmem(a.pd), st, a.dv.base, K,
                                (int64_t)K * rs, rs, a.d_valid, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d, a.ratio_d,
                                (const uint64_t*)nullptr, a.part_d, (float2*)nullptr);
         else
-            hipLaunchKernelGGL((k_lse<DT, true>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), 0, st, a.dv.base, K,
+            hipLaunchKernelGGL((k_lse<DT, true>), dim3((unsigned)rows * a.pd.nsplit), dim3(kWG), lse_shmem(a.pd), st, a.dv.base, K,
                                (int64_t)K * rs, rs, a.d_valid, a.pd.nC, a.pd.cps, a.pd.nsplit, a.cs_d, a.ratio_d,
                                a.map->lmask[DT], a.part_d, (float2*)nullptr);
         hipLaunchKernelGGL(k_lse_finish, dim3((rows + kWG - 1) / kWG), dim3(kWG), 0, st, a.part_d, rows, a.pd.nsplit,
                            a.ratio_d, a.ws_lse_q);
         lse_q = a.ws_lse_q;
     }
-    {
+    if (!a.skip_lse_p) {
         KernelTimer t(TLI_KERNEL_LSE, st);
-        hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * a.pl.nsplit), dim3(kWG), 0, st, a.logits_t, K,
+        hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * a.pl.nsplit), dim3(kWG), lse_shmem(a.pl), st, a.logits_t, K,
                            (int64_t)(K + 1) * Vt, (int64_t)Vt, Vt, a.pl.nC, a.pl.cps, a.pl.nsplit, a.cs_t, a.ratio_t,
                            nullptr, a.part, a.ctab);
     }
-    {
+    return lse_q;
+}
+
+// accept tests, first-reject scan and the extra token of every sequence, from the normaliser partials
+template <int DT>
+void launch_verify_tail(const VerifyArgs& a, const double* lse_q, hipStream_t st, bool accept_done = false) {
+    const int Vt = a.map->Vt, Vd = a.map->Vd, B = a.B, K = a.K;
+    FinalOut fo;
+    fo.u_fin = a.u_fin; fo.n_accepted = a.n_accepted; fo.out_tok = a.out_tok; fo.lse_p = a.lse_p;
+    fo.seq_status = a.seq_status;
+    if (!accept_done) {
         KernelTimer t(TLI_KERNEL_ACCEPT, st);
         hipLaunchKernelGGL(k_accept<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.dv, K, Vt, Vd, a.pl.nsplit,
                            a.part, a.ratio_t, a.inv_t, a.inv_d, a.map->d2t, a.tok_d, lse_q, a.u_acc, a.n_accepted,
                            a.out_tok, a.accept, a.p_tok, a.q_tok, a.lse_p, a.seq_status, a.ws_lse_p, a.c_t, a.c_d, a.frow,
                            a.fbad, a.union_mode);
     }
+    const int nparts = a.map->scan[DT].nparts;
+    const ScanLists ls = scan_lists(a.map, DT, a.compact ? 1 : 0);
     {
         KernelTimer t(TLI_KERNEL_FINAL_SCAN, st);
-        const int nparts = a.map->scan[DT].nparts;
         // few sequences: deal the chunks of a (sequence, part) to several workgroups, up to one per CU
         int nsplit = 256 / (B * nparts);
         nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
-        const ScanLists ls = scan_lists(a.map, DT, a.compact ? 1 : 0);
         hipLaunchKernelGGL((k_final_scan<DT, false>), dim3((unsigned)((B + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0,
                            st, a.logits_t, a.dv, B, K, Vt, Vd, a.pf.nC, nsplit, ls, a.cs_t, a.ratio_t, a.frow, a.tab_ref,
                            a.tab_s, a.mn, (double*)nullptr, a.fbad);
@@ -361,6 +383,41 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
         hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kLoads * kWave), 0, st, a.logits_t, a.dv, K, Vt, Vd, a.pf.nC,
                            a.cs_t, a.ratio_t, a.frow, a.dv.t2x, a.tab_ref, a.tab_s, a.ctab, a.mn, a.fbad, fo);
     }
+}
+
+
+// A workgroup per sequence runs normalisers and accept tests in one kernel (k_lse_accept_seq) when the batch gives
+// every compute unit about one sequence or several (a last round of few workgroups would leave the chip idle) and two
+// tables of a row's chunk pairs fit its LDS.
+bool use_seq_form(const VerifyArgs& a) {
+    if (a.pf.nC > kSeqMaxChunks || g_final_path == 1) return false;
+    if (g_final_path == 2) return true;
+    const int cus = 256, rounds = (a.B + cus - 1) / cus;
+    return a.B >= 200 && (double)a.B / ((double)rounds * cus) >= 0.78;
+}
+
+template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
+    if (use_seq_form(a)) {
+        VerifyArgs q = a;  // of the first step only the drafter normalisers, if the caller passed none
+        q.skip_lse_p = 1;
+        const double* lse_q = launch_verify_lse<DT>(q, st);
+        SeqIn in;
+        in.d2t = a.map->d2t; in.tok_d = a.tok_d; in.lse_q = lse_q; in.u_acc = a.u_acc; in.ratio_t = a.ratio_t;
+        in.inv_temp_t = a.inv_t; in.inv_temp_d = a.inv_d; in.c_t = a.c_t; in.c_d = a.c_d; in.cs_t = a.cs_t;
+        in.union_mode = a.union_mode;
+        SeqOut out;
+        out.n_accepted = a.n_accepted; out.out_tok = a.out_tok; out.accept = a.accept; out.p_tok = a.p_tok;
+        out.q_tok = a.q_tok; out.lse_p = a.lse_p; out.seq_status = a.seq_status; out.frow = a.frow; out.fbad = a.fbad;
+        {
+            KernelTimer t(TLI_KERNEL_LSE, st);
+            hipLaunchKernelGGL(k_lse_accept_seq<DT>, dim3(a.B), dim3(kScanWG), 0, st, a.logits_t, a.dv, a.K, a.map->Vt,
+                               a.map->Vd, a.pf.nC, in, a.ctab, out);
+        }
+        launch_verify_tail<DT>(a, lse_q, st, /*accept_done=*/true);
+        return;
+    }
+    const double* lse_q = launch_verify_lse<DT>(a, st);
+    launch_verify_tail<DT>(a, lse_q, st);
 }
 
 }  // namespace
@@ -401,7 +458,7 @@ void launch_diag(const tli_map* map, const void* logits_t, const void* logits_d,
     int32_t* fbad = reinterpret_cast<int32_t*>(ws + w.fbad);
     double* mn = reinterpret_cast<double*>(ws + w.mn);
     double* mn2 = reinterpret_cast<double*>(ws + w.mn2);
-    hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * pt.nsplit), dim3(kWG), 0, st, logits_t, K,
+    hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * pt.nsplit), dim3(kWG), lse_shmem(pt), st, logits_t, K,
                        (int64_t)(K + 1) * Vt, (int64_t)Vt, Vt, pt.nC, pt.cps, pt.nsplit, cs_t, ratio_t,
                        (const uint64_t*)nullptr, part_t, (float2*)nullptr);
     hipLaunchKernelGGL((k_lse_both<DT>), dim3((unsigned)rows * pd.nsplit), dim3(kWG), 0, st, logits_d, K, (int64_t)K * Vd,
@@ -519,6 +576,12 @@ int tli_profile_collect(int32_t kernel, double* total_ms, int32_t* launches) {
     return TLI_OK;
 }
 
+int tli_tune_final_path(int32_t path) {
+    if (path < 0 || path > 2) return TLI_ERR_INVALID_ARG;
+    g_final_path = path;
+    return TLI_OK;
+}
+
 void tli_profile_disable(void) {
     for (int k = 0; k < TLI_KERNEL_COUNT; ++k) {
         for (auto& e : g_prof.ev[k])
@@ -552,6 +615,7 @@ namespace {
 // Everything tli_build_map computes before it touches the device.
 struct HostScan {  // the residual scan's lists for one dtype (see tli_map::Scan)
     std::vector<int32_t> cb, part_n, pl_g;
+    int max_part_chunks = 0;
     int NV[2];
     std::vector<uint32_t> stab[2];
     std::vector<int2> grange[2];
@@ -616,8 +680,11 @@ int build_host_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, HostMap& hm)
         const int nparts = (int)h.cb.size() - 1;
         std::vector<int32_t> part_of_chunk(nC);
         h.part_n.assign(nparts, 0);
-        for (int p = 0; p < nparts; ++p)
+        h.max_part_chunks = 0;
+        for (int p = 0; p < nparts; ++p) {
             for (int c = h.cb[p]; c < h.cb[p + 1]; ++c) { part_of_chunk[c] = p; h.part_n[p] += cc[c]; }
+            if (h.cb[p + 1] - h.cb[p] > h.max_part_chunks) h.max_part_chunks = h.cb[p + 1] - h.cb[p];
+        }
         h.pl_g.assign(nC + 1, 0);
         for (int c = 0; c < nC; ++c) h.pl_g[c + 1] = h.pl_g[c] + (cc[c] + kPairG - 1) / kPairG;
         for (int layout = 0; layout < 2; ++layout) {
@@ -835,6 +902,7 @@ int tli_build_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, tli_map** out
     for (int dt = 0; dt < 2; ++dt) {
         tli_map::Scan& sc = m->scan[dt];
         sc.nparts = (int32_t)hs[dt].part_n.size();
+        sc.max_part_chunks = hs[dt].max_part_chunks;
         sc.cb = sc.part_n = sc.pl_g = nullptr;
         for (int layout = 0; layout < 2; ++layout) {
             sc.NV[layout] = hs[dt].NV[layout];
@@ -1014,7 +1082,7 @@ int tli_warp_rows(const tli_map* map, const void* logits, tli_dtype dtype, int64
     const dim3 rows_grid(R), lse_grid((unsigned)R * pl.nsplit);
 #define TLI_WARP_RUN(DT, MASKED, BITS)                                                                                   \
     do {                                                                                                                  \
-        hipLaunchKernelGGL((k_lse<DT, MASKED>), lse_grid, dim3(kWG), 0, s, logits, 1, row_stride_elems, row_stride_elems, \
+        hipLaunchKernelGGL((k_lse<DT, MASKED>), lse_grid, dim3(kWG), lse_shmem(pl), s, logits, 1, row_stride_elems, row_stride_elems, \
                            V, pl.nC, pl.cps, pl.nsplit, cs, ratio, BITS, part, (float2*)nullptr);                        \
         hipLaunchKernelGGL(k_warp_init, dim3((R + kWG - 1) / kWG), dim3(kWG), 0, s, part, pl.nsplit, ratio, R, top_k,     \
                            use_p, st);                                                                                    \

@@ -2,6 +2,9 @@
 // intersection algorithm) and everything else that draws one token per softmax row.  Included by tli_kernels.hip
 // inside its unnamed namespace, after tli_device_common.h.
 #pragma once
+#ifndef TLI_LSE_ORDER
+#define TLI_LSE_ORDER 1
+#endif
 
 // ---- kernel: log-normaliser partials of rows -----------------------------------------------------
 // Standard SD appendix, verification loop: p_k(d_k) needs the normaliser of every target row k < K
@@ -13,8 +16,16 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
                                               int64_t row_stride, int V, int nC, int cps, int nsplit, float cs,
                                               double ratio, const uint64_t* __restrict__ bits,
                                               Part* __restrict__ part, float2* __restrict__ ctab) {
+#if TLI_LSE_ORDER == 1
+    const int slot = blockIdx.x / nsplit, split = blockIdx.x - slot * nsplit;
+    const int nB = (int)(gridDim.x / nsplit) / K;
+    const int kk = slot / nB;
+    const int b = slot - kk * nB, k = K - 1 - kk;
+    const int row = b * K + k;
+#else
     const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
     const int b = row / K, k = row - b * K;
+#endif
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
                                                     (b * seq_stride + k * row_stride) * Traits<DT>::ESZ);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -24,7 +35,8 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
     // running total is not advanced per chunk: that is a dozen fp64 instructions which every lane would
     // execute for a wave-uniform value); the partial is reduced from there when the row is through.  The pairs
     // are also what the residual of a rejected row takes its chunk sums of p from (ctab).
-    __shared__ float2 stash[kLdsChunks];
+    extern __shared__ float2 stash[];  // min(cps, kLdsChunks) entries: a workgroup that keeps little LDS leaves the
+                                       // CU's LDS to kernels running beside it
     Running over;  // chunks beyond what LDS parks (rows of more than kLdsChunks chunks per workgroup)
     scan_chunks<DT, MASKED, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, (float)(ratio - 1.0), bits,
                                     [&](int c, float r, float sc) {
@@ -220,7 +232,9 @@ __device__ __forceinline__ int find_chunk(int nC, double u, MassFn mass, double*
 // lane, then element; wave j holds load j, `w` = the weights of this lane's vector (ids e0 .. e0+N-1).  Returns
 // (to every thread) the first id whose inclusive prefix exceeds theta_local, or, if rounding leaves no
 // crossing, the last id with a positive weight (-1 if there is none).  The prefix over the loads is added up in
-// load order, as one wave walking the four loads in turn would.  Every wave of the workgroup must call it.
+// load order, as one wave walking the four loads in turn would.  Every wave of the workgroup must call it; in a
+// workgroup of more than kLoads waves the further ones take no part in the result (they only keep step at the
+// barriers) and receive it like the others.
 template <int N>
 __device__ __forceinline__ int chunk_draw(const double (&w)[N], int64_t e0, double theta_local) {
     __shared__ double s_tot[kLoads];
@@ -232,10 +246,10 @@ __device__ __forceinline__ int chunk_draw(const double (&w)[N], int64_t e0, doub
     for (int i = 0; i < N; ++i) mine += w[i];
     double tot;
     const double excl = wave_excl_scan(mine, &tot);
-    if (lane == 0) s_tot[j] = tot;
+    if (lane == 0 && j < kLoads) s_tot[j] = tot;  // (a larger workgroup's further waves only keep step)
     __syncthreads();
     double base = 0.0;
-    for (int q = 0; q < j; ++q) base += s_tot[q];
+    for (int q = 0; q < min(j, kLoads); ++q) base += s_tot[q];
     double run = base + excl;
     int f = -1, last_pos = -1;
 #pragma unroll
@@ -247,7 +261,7 @@ __device__ __forceinline__ int chunk_draw(const double (&w)[N], int64_t e0, doub
     const unsigned long long hit = __ballot(f >= 0);
     const int first = hit ? __shfl(f, (int)__builtin_ctzll(hit), kWave) : -1;
     const int last = wave_max_int(last_pos);
-    if (lane == 0) { s_found[j] = first; s_last[j] = last; }
+    if (lane == 0 && j < kLoads) { s_found[j] = first; s_last[j] = last; }
     __syncthreads();
     int tok = -1;
     for (int q = kLoads - 1; q >= 0; --q)
@@ -304,7 +318,12 @@ __device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int n
     }
     const int64_t vi = ((int64_t)c * kLoads + wave) * kWave + lane;
     double w[EPV];
-    softmax_vec_weights<DT, MASKED>(static_cast<const uint4*>(rowp), vi, V, cs, -M, bits, w);
+    if (wave < kLoads) {
+        softmax_vec_weights<DT, MASKED>(static_cast<const uint4*>(rowp), vi, V, cs, -M, bits, w);
+    } else {
+#pragma unroll
+        for (int i = 0; i < EPV; ++i) w[i] = 0.0;
+    }
     return chunk_draw<EPV>(w, vi * EPV, theta_local);
 }
 

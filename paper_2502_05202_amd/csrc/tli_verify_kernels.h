@@ -191,78 +191,101 @@ struct FinalOut {
     int32_t* seq_status;
 };
 
-template <int DT>
-__device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const void* logits_t, const DrafterView& dv,
-                                               int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
-                                               const int32_t* t2d, const float* tr, const float* ts,
-                                               const float2* ctab, const double* mn, const int32_t* fbad,
-                                               const FinalOut& o) {
+// what the draw of one sequence's extra token came to (the same in every thread of the workgroup)
+struct PickResult {
+    int tok;         // the token, -1 if there is none
+    int add_flags;   // TLI_FLAG_DEGENERATE if the fallback was taken
+    bool nonfinite;  // no distribution to draw from: NaN/+inf in a row that takes part, or a bonus row without mass
+    double lse_bonus;  // bonus rows: log-normaliser of row K
+};
+
+// MN: float or double chunk sums of min(p, q') (read only for residual rows with a usable draft)
+template <int DT, class MN>
+__device__ __forceinline__ PickResult final_pick_core(const FinalRow& f, int b, const void* logits_t, const DrafterView& dv,
+                                                      int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
+                                                      const int32_t* t2d, const float* tr, const float* ts,
+                                                      const float2* ctab, const MN* mn, bool drafter_bad, double u) {
     constexpr int EPV = Traits<DT>::EPV;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const char* rowp = static_cast<const char*>(logits_t) + (int64_t)f.t_row * Vt * Traits<DT>::ESZ;
-    const double u = (double)o.u_fin[b];
-    int tok = -1;
-    int add_flags = 0;
-    bool nonfinite = false;
+    PickResult res;
+    res.tok = -1; res.add_flags = 0; res.nonfinite = false; res.lse_bonus = NAN;
     if (f.bonus) {
         float M;
         double total;
-        tok = sample_softmax_row<DT, false>(rowp, Vt, nC, cs_t, ratio_t, nullptr, tr, ts, u, &M, &total);
+        res.tok = sample_softmax_row<DT, false>(rowp, Vt, nC, cs_t, ratio_t, nullptr, tr, ts, u, &M, &total);
         // no usable mass: NaN/+inf, or a bonus row of only -inf -- no distribution to sample either way
-        if (tok < 0) nonfinite = true;
-        else if (threadIdx.x == 0 && o.lse_p) o.lse_p[(int64_t)b * (K + 1) + K] = kLn2 * ((double)M * ratio_t + log2(total));
+        if (res.tok < 0) res.nonfinite = true;
+        else res.lse_bonus = kLn2 * ((double)M * ratio_t + log2(total));
+        return res;
+    }
+    const char* ldp = static_cast<const char*>(dv.base) + (int64_t)f.d_row * dv.row_stride * Traits<DT>::ESZ;
+    // chunk masses: sum_chunk p (from the normaliser kernel's table of row n) minus the parts' sums of min(p, q')
+    const float2* crow = ctab + (int64_t)f.d_row * nC;
+    auto p_mass = [&](int cc) {
+        const float2 rs = crow[cc];
+        return (rs.x == -INFINITY) ? 0.0 : (double)rs.y * exp2((double)rs.x * ratio_t - f.l2p);
+    };
+    auto r_mass = [&](int cc) {
+        const double m = f.rp.use_q ? (double)mn[cc] : 0.0;
+        const double t = p_mass(cc) - m;
+        return t > 0.0 ? t : (t != t ? t : 0.0);
+    };
+    double theta_local, total;
+    int c = -1;
+    bool degenerate = false;
+    if (f.rp.use_q && drafter_bad) {  // NaN or +inf among the shared drafter logits of row n
+        res.nonfinite = true;
     } else {
-        const char* ldp = static_cast<const char*>(dv.base) + (int64_t)f.d_row * dv.row_stride * Traits<DT>::ESZ;
-        // chunk masses: sum_chunk p (from the normaliser kernel's table of row n) minus the parts' sums of min(p, q')
-        const float2* crow = ctab + (int64_t)f.d_row * nC;
-        auto p_mass = [&](int cc) {
-            const float2 rs = crow[cc];
-            return (rs.x == -INFINITY) ? 0.0 : (double)rs.y * exp2((double)rs.x * ratio_t - f.l2p);
-        };
-        auto r_mass = [&](int cc) {
-            const double m = f.rp.use_q ? mn[cc] : 0.0;
-            const double t = p_mass(cc) - m;
-            return t > 0.0 ? t : (t != t ? t : 0.0);
-        };
-        double theta_local, total;
-        int c = -1;
-        bool degenerate = false;
-        if (f.rp.use_q && fbad[b]) {  // NaN or +inf among the shared drafter logits of row n
-            nonfinite = true;
-        } else {
-            c = find_chunk(nC, u, r_mass, &theta_local, &total);
-            if (c < 0) {
-                if (total != total) {
-                    nonfinite = true;
-                } else {  // residual identically zero: fall back to p of the same row
-                    degenerate = true;
-                    add_flags |= TLI_FLAG_DEGENERATE;
-                    c = find_chunk(nC, u, p_mass, &theta_local, &total);
-                    if (c < 0) nonfinite = true;
-                }
+        c = find_chunk(nC, u, r_mass, &theta_local, &total);
+        if (c < 0) {
+            if (total != total) {
+                res.nonfinite = true;
+            } else {  // residual identically zero: fall back to p of the same row
+                degenerate = true;
+                res.add_flags |= TLI_FLAG_DEGENERATE;
+                c = find_chunk(nC, u, p_mass, &theta_local, &total);
+                if (c < 0) res.nonfinite = true;
             }
         }
-        if (!nonfinite) {
-            // wave j of the workgroup takes load j of the chunk: a quarter of the table look-ups, gathers and
-            // exponentials each
-            const int64_t vi = ((int64_t)c * kLoads + wave) * kWave + lane;
+    }
+    if (!res.nonfinite) {
+        // wave j of the workgroup takes load j of the chunk: a quarter of the table look-ups, gathers and
+        // exponentials each
+        const int64_t vi = ((int64_t)c * kLoads + wave) * kWave + lane;
+        double wd[EPV];
+        if (wave < kLoads) {
             float p[EPV], w[EPV];
             residual_vec<DT>(rowp, vi, Vt, f.rp, t2d, ldp, p, w);
-            double wd[EPV];
 #pragma unroll
             for (int i = 0; i < EPV; ++i) wd[i] = degenerate ? (double)p[i] : (double)w[i];
-            tok = chunk_draw<EPV>(wd, vi * EPV, theta_local);
+        } else {  // a larger workgroup's further waves take no part in the draw
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) wd[i] = 0.0;
         }
+        res.tok = chunk_draw<EPV>(wd, vi * EPV, theta_local);
     }
+    return res;
+}
+
+template <int DT>
+__device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const void* logits_t, const DrafterView& dv,
+                                               int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
+                                               const int32_t* t2d, const float* tr, const float* ts,
+                                               const float2* ctab, const double* mn, bool drafter_bad,
+                                               const FinalOut& o) {
+    const PickResult r = final_pick_core<DT>(f, b, logits_t, dv, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tr, ts, ctab, mn,
+                                             drafter_bad, (double)o.u_fin[b]);
     if (threadIdx.x == 0) {
-        if (nonfinite) {
+        if (r.nonfinite) {
             o.n_accepted[b] = 0;
             for (int k = 0; k <= K; ++k) o.out_tok[(int64_t)b * (K + 1) + k] = -1;
             o.seq_status[b] |= TLI_FLAG_NONFINITE;
         } else {
-            o.out_tok[(int64_t)b * (K + 1) + f.n] = tok;
-            if (add_flags) o.seq_status[b] |= add_flags;
+            o.out_tok[(int64_t)b * (K + 1) + f.n] = r.tok;
+            if (f.bonus && o.lse_p) o.lse_p[(int64_t)b * (K + 1) + K] = r.lse_bonus;
+            if (r.add_flags) o.seq_status[b] |= r.add_flags;
         }
     }
 }
@@ -597,5 +620,5 @@ __global__ __launch_bounds__(kLoads * kWave) void k_final_pick(const void* __res
     const FinalRow f = frow[b];
     if (f.skip) return;
     final_pick_row<DT>(f, b, logits_t, dv, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
-                       tab_s + (int64_t)b * nC, ctab, mn + (int64_t)b * nC, fbad, o);
+                       tab_s + (int64_t)b * nC, ctab, mn + (int64_t)b * nC, f.rp.use_q && fbad[b] != 0, o);
 }

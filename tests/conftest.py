@@ -16,3 +16,15 @@ def oracle():
 
     _oracle.build()
     return _oracle
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _final_path_from_env():
+    """TLI_FINAL_PATH=1|2 runs the whole suite with one form of tli_verify's extra-token step forced (see
+    tli_tune_final_path); unset, the library chooses by shape."""
+    v = os.environ.get("TLI_FINAL_PATH")
+    if v:
+        from paper_2502_05202_amd import binding
+
+        binding.tli_tune_final_path(int(v))
+    yield

@@ -1,4 +1,4 @@
-"""CPU-only checks of the C-ABI library: it loads, exports every function include/tli.h declares,
+"""CPU-only checks of the C-ABI library: it loads, exports every function include/*.h declares,
 and its argument validation (which runs before any HIP call) returns the documented codes."""
 import ctypes
 import os
@@ -20,7 +20,8 @@ def lib():
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "tli.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include")))
+                   if h.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(tli_[a-z0-9_]+)\s*\(", text)))
 
