@@ -226,8 +226,8 @@ int tli_union_verify(const tli_map* map, const void* logits_t, const void* logit
  *   logits_t dev [B,K+1,Vt] (row K of a sequence is not used), logits_d dev [B,K,Vd], both dense
  *   alpha_tli, alpha_union dev [B,K] fp64; pos_status dev [B,K] int32: NONFINITE (a target logit or ANY drafter
  *   logit of the position is NaN/+inf: both rates NaN) or ZERO_MASS (no drafter mass on the shared ids: both 0).
- * The terms are fp32: a rate is good to about 1e-6 relative while it is above one in a million; smaller ones lose
- * relative accuracy with their size (a rate of 1e-36 to 1e-4 of itself) and one below 1e-38 may come out 0.
+ * Both rates are good to 1e-5 relative at any size an fp64 number holds: positions whose rates come out below 2^-24
+ * from the fp32 terms are summed a second time with fp64 exponent arguments and exactly scaled terms.
  * Scratch: tli_acceptance_rates_workspace_bytes (it depends on the map).
  */
 size_t tli_acceptance_rates_workspace_bytes(const tli_map* map, int32_t B, int32_t K, tli_dtype dtype);

@@ -374,9 +374,9 @@ void launch_verify_tail(const VerifyArgs& a, const double* lse_q, hipStream_t st
         // few sequences: deal the chunks of a (sequence, part) to several workgroups, up to one per CU
         int nsplit = 256 / (B * nparts);
         nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
-        hipLaunchKernelGGL((k_final_scan<DT, false>), dim3((unsigned)((B + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0,
+        hipLaunchKernelGGL((k_final_scan<DT, 0>), dim3((unsigned)((B + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0,
                            st, a.logits_t, a.dv, B, K, Vt, Vd, a.pf.nC, nsplit, ls, a.cs_t, a.ratio_t, a.frow, a.tab_ref,
-                           a.tab_s, a.mn, (double*)nullptr, a.fbad);
+                           a.tab_s, a.mn, (double*)nullptr, a.fbad, (const int32_t*)nullptr);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
@@ -423,7 +423,7 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
 }  // namespace
 
 namespace {
-struct DiagLayout { size_t part_t, part_q1, part_q2, frow, fbad, mn, mn2, total; };
+struct DiagLayout { size_t part_t, part_q1, part_q2, frow, fbad, redo, mn, mn2, total; };
 DiagLayout diag_layout(const tli_map* map, int B, int K, int dtype) {
     const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
     const int rows = B * K;
@@ -435,6 +435,7 @@ DiagLayout diag_layout(const tli_map* map, int B, int K, int dtype) {
     w.part_q2 = off; off += align256((size_t)rows * pd.nsplit * sizeof(Part));
     w.frow = off; off += align256((size_t)rows * sizeof(FinalRow));
     w.fbad = off; off += align256((size_t)rows * sizeof(int32_t));
+    w.redo = off; off += align256((size_t)rows * sizeof(int32_t));
     const size_t tab = (size_t)rows * pt.nC * sizeof(double);
     w.mn = off; off += align256(tab);
     w.mn2 = off; off += align256(tab);
@@ -469,11 +470,18 @@ void launch_diag(const tli_map* map, const void* logits_t, const void* logits_d,
     int nsplit = 256 / (rows * nparts);
     nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
     const ScanLists ls = scan_lists(map, DT, 0);
-    hipLaunchKernelGGL((k_final_scan<DT, true>), dim3((unsigned)((rows + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0, st,
-                       logits_t, DrafterView{logits_d, (int64_t)Vd, nullptr, map->t2d}, rows, K, Vt, Vd, pt.nC, nsplit, ls,
-                       cs_t, ratio_t, frow, (float*)nullptr, (float*)nullptr, mn, mn2, fbad);
-    hipLaunchKernelGGL(k_diag_finish, dim3(rows), dim3(kWave), 0, st, frow, mn, mn2, rows, pt.nC, alpha_tli,
-                       alpha_union);
+    int32_t* redo = reinterpret_cast<int32_t*>(ws + w.redo);
+    const dim3 scan_grid((unsigned)((rows + 7) / 8) * 8 * nparts * nsplit);
+    const DrafterView dvw{logits_d, (int64_t)Vd, nullptr, map->t2d};
+    hipLaunchKernelGGL((k_final_scan<DT, 1>), scan_grid, dim3(kScanWG), 0, st, logits_t, dvw, rows, K, Vt, Vd, pt.nC, nsplit,
+                       ls, cs_t, ratio_t, frow, (float*)nullptr, (float*)nullptr, mn, mn2, fbad, (const int32_t*)nullptr);
+    hipLaunchKernelGGL(k_diag_finish, dim3(rows), dim3(kWave), 0, st, frow, mn, mn2, rows, pt.nC, alpha_tli, alpha_union,
+                       redo, 0);
+    // the positions whose rates are tiny (normally none: their workgroups leave at once) again, with fp64 arguments
+    hipLaunchKernelGGL((k_final_scan<DT, 2>), scan_grid, dim3(kScanWG), 0, st, logits_t, dvw, rows, K, Vt, Vd, pt.nC, nsplit,
+                       ls, cs_t, ratio_t, frow, (float*)nullptr, (float*)nullptr, mn, mn2, fbad, redo);
+    hipLaunchKernelGGL(k_diag_finish, dim3(rows), dim3(kWave), 0, st, frow, mn, mn2, rows, pt.nC, alpha_tli, alpha_union,
+                       redo, 1);
 }
 }  // namespace
 

@@ -120,10 +120,15 @@ __global__ __launch_bounds__(kWG) void k_diag_rows(const Part* __restrict__ part
 }
 
 // kernel: alpha of every position = sum over parts and chunks of the scan's partial sums.  grid (rows), one wave.
+// pass 0 (after the fp32 scan) also marks in redo the positions with a rate below 2^-24: their terms lie where the
+// fp32 scan's exponent arguments and range no longer give 1e-5; pass 1 (after the fp64-argument scan of those
+// positions) rewrites only them.
 __global__ __launch_bounds__(kWave) void k_diag_finish(const FinalRow* __restrict__ frow, const double* __restrict__ mn,
                                                         const double* __restrict__ mn2, int rows, int nC,
-                                                        double* __restrict__ alpha_tli, double* __restrict__ alpha_union) {
+                                                        double* __restrict__ alpha_tli, double* __restrict__ alpha_union,
+                                                        int32_t* __restrict__ redo, int pass) {
     const int r = blockIdx.x, lane = threadIdx.x;
+    if (pass == 1 && !redo[r]) return;
     const FinalRow f = frow[r];
     double a1 = 0.0, a2 = 0.0;
     if (f.skip) {
@@ -135,7 +140,11 @@ __global__ __launch_bounds__(kWave) void k_diag_finish(const FinalRow* __restric
         a1 = wave_sum_f64(a1);
         a2 = wave_sum_f64(a2);
     }
-    if (lane == 0) { alpha_tli[r] = a1; alpha_union[r] = a2; }
+    if (lane == 0) {
+        alpha_tli[r] = a1;
+        alpha_union[r] = a2;
+        if (pass == 0) redo[r] = (!f.skip && f.rp.use_q && (a1 < 0x1p-24 || a2 < 0x1p-24)) ? 1 : 0;
+    }
 }
 
 // ---- temperature zero: argmax of rows ----------------------------------------------------------

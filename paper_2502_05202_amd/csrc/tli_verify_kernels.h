@@ -392,11 +392,16 @@ template <> struct BadTrack<TLI_F32> {
 // DIAG (acceptance-rate diagnostics): the items are all B*K positions instead of one row per sequence, and a
 // second sum runs beside the first with the drafter's unrestricted probabilities q = q' * 2^-dq:
 // mn = sum min(p, q') (TLI's expected acceptance rate), mn2 = sum min(p, q) (the union algorithm's).
-template <int DT, bool DIAG>
+// MODE 2 is the same diagnostic scan with the exponent arguments in fp64 and every term scaled by an exact power of
+// two: for the positions marked in `redo`, whose rates came out so small in MODE 1 that the fp32 arguments (good to
+// 2^-24 of their magnitude, i.e. 5e-6 of a term at 2^-100) and the fp32 range (nothing below 2^-126) show.
+template <int DT, int MODE>
 __global__ __launch_bounds__(kScanWG) void k_final_scan(
     const void* __restrict__ logits_t, DrafterView dv, int B, int K, int Vt, int Vd, int nC, int nsplit, ScanLists ls,
     float cs_t, double ratio_t, const FinalRow* __restrict__ frow, float* __restrict__ tab_ref, float* __restrict__ tab_s, double* __restrict__ mn, double* __restrict__ mn2,
-    int32_t* __restrict__ fbad) {
+    int32_t* __restrict__ fbad, const int32_t* __restrict__ redo) {
+    constexpr bool DIAG = MODE != 0;
+    constexpr bool EXACT = MODE == 2;
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int ESZ = Traits<DT>::ESZ;
     typedef typename std::conditional<DT == TLI_BF16, uint16_t, uint32_t>::type raw_t;
@@ -431,6 +436,7 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         const int c = c_lo + (idx < ncp ? idx : 0);
         gbv = make_int2(pl_g[c], pl_g[c + 1]);
     }
+    if (EXACT && !redo[b]) return;
     const FinalRow f = frow[b];
     if (f.skip) return;
     if (f.bonus) {
@@ -552,6 +558,23 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         if (DIAG) second = exp2_hw(fminf(a, bq - dq));
         return exp2_hw(fminf(a, bq));
     };
+    // MODE 2: log2 p and log2 q' in fp64, a term = 2^fraction (the hardware exponential on an argument in
+    // [-0.5, 0.5]) times an exact power of two, in fp64: good to the exponential's 1e-7 at any size
+    const double ct64 = (double)rp.ct_hi + (double)rp.ct_lo, cd64 = (double)rp.cd_hi + (double)rp.cd_lo;
+    const double lq64 = (double)rp.lq_hi + (double)rp.lq_lo;
+    auto exp2_wide = [](double m) -> double {
+        if (!(m > -1070.0)) return m != m ? m : 0.0;  // -inf, or below what fp64 holds (NaN stays NaN)
+        const double n = rint(m);
+        return ldexp((double)exp2_hw((float)(m - n)), (int)n);
+    };
+    auto pair_min_wide = [&](uint32_t e, double& second) -> double {
+        const uint32_t xr = *reinterpret_cast<const raw_t*>(lds + (tb + (e & 0xffffu)));
+        const uint32_t yr = *reinterpret_cast<const raw_t*>(part + (e >> kPairShift) * ESZ);
+        const float xv = as_f(DT == TLI_BF16 ? xr << 16 : xr), yv = as_f(DT == TLI_BF16 ? yr << 16 : yr);
+        const double a = fma((double)xv, ct64, -f.l2p), bq = fma((double)yv, cd64, -lq64);
+        second = exp2_wide(fmin(a, bq - (double)dq));
+        return exp2_wide(fmin(a, bq));
+    };
     // Results stay in registers until the wave is through (lane k keeps the sum of the wave's k-th chunk):
     // a store shares the loads' completion counter and completes out of order with them, so while one may
     // be pending every wait for a load degrades to a wait for all loads.
@@ -564,11 +587,19 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         // may-alias accesses in program order; the wave barrier only pins the schedule
         __builtin_amdgcn_wave_barrier();
         float acc = 0.f, acc2 = 0.f;
+        double wacc = 0.0, wacc2 = 0.0;
         auto two = [&](uint2 e) {
-            float u0 = 0.f, u1 = 0.f;
-            const float t0 = pair_min(e.x, u0), t1 = pair_min(e.y, u1);
-            acc += t0 + t1;
-            if (DIAG) acc2 += u0 + u1;
+            if (EXACT) {
+                double u0, u1;
+                const double t0 = pair_min_wide(e.x, u0), t1 = pair_min_wide(e.y, u1);
+                wacc += t0 + t1;
+                wacc2 += u0 + u1;
+            } else {
+                float u0 = 0.f, u1 = 0.f;
+                const float t0 = pair_min(e.x, u0), t1 = pair_min(e.y, u1);
+                acc += t0 + t1;
+                if (DIAG) acc2 += u0 + u1;
+            }
         };
         const int g0 = __builtin_amdgcn_readlane(gbv.x, k), g1 = __builtin_amdgcn_readlane(gbv.y, k);
         const int ng = g1 - g0;
@@ -580,11 +611,16 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         // A chunk's sum is taken in fp32: a lane's dozen-odd terms in turn, the 64 lane totals on the DPP network
         // (one instruction per step; a double takes five).  That is a relative 1e-7, the size of the exponential's
         // own error; chunk sums are combined in fp64 downstream.
-        const float tot = wave_sum(acc);
-        if (lane == k) keep = (double)tot;
-        if (DIAG) {
-            const float tot2 = wave_sum(acc2);
-            if (lane == k) keep2 = (double)tot2;
+        if (EXACT) {
+            const double tot = wave_sum_f64(wacc), tot2 = wave_sum_f64(wacc2);
+            if (lane == k) { keep = tot; keep2 = tot2; }
+        } else {
+            const float tot = wave_sum(acc);
+            if (lane == k) keep = (double)tot;
+            if (DIAG) {
+                const float tot2 = wave_sum(acc2);
+                if (lane == k) keep2 = (double)tot2;
+            }
         }
     };
     int k = 0;
