@@ -32,7 +32,7 @@ class Workload:
     kind: str         # "noise" | "corr" | "zipf"
     sigma: float = 0.0
     noise: float = 0.0      # kind=noise: std of the N(0, noise^2) added on shared ids
-    only_mu: float = 0.0    # kind=noise: mean of target-only logits
+    only_mu: float = 0.0    # kind=noise, corr: mean of target-only logits (corr: of the bonus row too)
     rho: float = 0.0        # kind=corr: drafter/target correlation on shared ids
 
     def scaled(self, **kw) -> "Workload":
@@ -95,7 +95,7 @@ def make_inputs(w: Workload, device="cpu", seed: int | None = None) -> dict:
             t[:K, t_idx] = d[:, d_idx] + randn(K, d_idx.numel()) * w.noise
         elif w.kind == "corr":
             d = randn(K, Vd) * w.sigma
-            t = randn(K + 1, Vt) * w.sigma
+            t = randn(K + 1, Vt) * w.sigma + w.only_mu
             t[:K, t_idx] = w.rho * d[:, d_idx] + math.sqrt(1.0 - w.rho ** 2) * w.sigma * randn(K, d_idx.numel())
         elif w.kind == "zipf":
             rank = torch.rand(K + 1, Vd, generator=gen, device=device).argsort(dim=1)

@@ -138,6 +138,42 @@ def test_nearly_identical_models(oracle, rho, dtype):
     assert (n < w.K).any()  # some rows do sample from a residual
 
 
+def test_full_size_half_accepted(oracle):
+    """The large-vocabulary batch (B=256, K=8, Vt=256000, Vd=128256, bf16) with a drafter close to the target --
+    correlation 0.997 on the shared ids, target-only ids without mass -- so that about half of the drafts are
+    accepted: every count 0..K occurs, rows n >= 1 are the ones the extra token is drawn from, and the bonus row is
+    used by about one sequence in five."""
+    w = synth.WORKLOADS[4].scaled(rho=0.997, only_mu=-40.0, cfg=41)
+    res = parity.run_case(oracle, synth.make_inputs(w, DEV), threads=16, chain=True)
+    _check(res)
+    n = res["ref_verify"]["n_acc"]
+    print("accepted counts:", np.bincount(n, minlength=w.K + 1).tolist(), "mean", n.mean())
+    assert set(n.tolist()) == set(range(w.K + 1))
+    assert abs(n.mean() - w.K / 2) < 1.5
+    assert res["verify"]["compared_tokens"] >= w.B - 2 and res["chained"]["compared_tokens"] >= w.B - 4
+
+
+def test_full_size_every_draft_accepted(oracle):
+    """The large-vocabulary batch with the target's shared logits equal to the drafter's and its other ids without
+    mass: p = q' on every drafted token, all K drafts of all 256 sequences are accepted, and every extra token is a
+    draw from row K (with its log-normaliser) -- the bonus scan at the size and launch shape of the benchmark."""
+    w = synth.WORKLOADS[4].scaled(cfg=42)
+    inp = synth.make_inputs(w, DEV)
+    d2t = inp["d2t"]
+    d_idx = torch.from_numpy(np.nonzero(d2t >= 0)[0]).to(DEV)
+    t_idx = torch.from_numpy(d2t[d2t >= 0].astype(np.int64)).to(DEV)
+    lt, ld = inp["logits_t"], inp["logits_d"]
+    lt[:, : w.K] = -100.0
+    for b in range(w.B):
+        lt[b, : w.K, t_idx] = ld[b][:, d_idx]
+    inp["u_acc"].clamp_(max=1.0 - 2.0 ** -10)  # p/q' is 1 to rounding: a uniform within 1e-6 of 1 would be a near-tie
+    res = parity.run_case(oracle, inp, threads=16, chain=True)
+    _check(res)
+    assert np.all(res["ref_verify"]["n_acc"] == w.K) and np.all(res["gpu_verify"]["n_accepted"] == w.K)
+    assert res["verify"]["compared_tokens"] == w.B and res["chained"]["compared_tokens"] == w.B
+    assert not np.isnan(res["gpu_verify"]["lse_p"]).any()
+
+
 STRESS = ["scale_up", "scale_down", "neginf", "ties", "const", "onehot", "cold", "hot"]
 
 
