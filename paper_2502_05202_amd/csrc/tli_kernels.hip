@@ -65,7 +65,7 @@ size_t lse_shmem(const Plan& p) { return (size_t)(p.cps < kLdsChunks ? p.cps : k
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {  // offsets into the caller's scratch
-    size_t part, part_d, ws_lse_p, ws_lse_q, ctab, frow, fbad, tab_ref, tab_s, mn, total;
+    size_t part, part_d, ws_lse_p, ws_lse_q, ctab, frow, fbad, tab_ref, tab_s, mn, rmass, total;
 };
 
 Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
@@ -89,6 +89,8 @@ Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
     w.tab_s = off; off += align256(tab * sizeof(float));
     // the residual scan's sums of min(p, q'), one per chunk of the row the extra token is drawn from
     w.mn = off; off += align256(tab_rows_t * sizeof(double));
+    // ... and the chunk masses themselves, for rows whose residual is a small part of p (precise_chunk_masses)
+    w.rmass = off; off += align256(tab_rows_t * sizeof(double));
     w.total = off;
     return w;
 }
@@ -159,7 +161,7 @@ struct VerifyArgs {
     float cs_d;
     double ratio_d;
     float *tab_ref, *tab_s;
-    double* mn;
+    double *mn, *rmass;
     float2* ctab;
     FinalRow* frow;
     int32_t* fbad;
@@ -376,12 +378,12 @@ void launch_verify_tail(const VerifyArgs& a, const double* lse_q, hipStream_t st
         nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
         hipLaunchKernelGGL((k_final_scan<DT, 0>), dim3((unsigned)((B + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0,
                            st, a.logits_t, a.dv, B, K, Vt, Vd, a.pf.nC, nsplit, ls, a.cs_t, a.ratio_t, a.frow, a.tab_ref,
-                           a.tab_s, a.mn, (double*)nullptr, a.fbad, (const int32_t*)nullptr);
+                           a.tab_s, a.mn, (double*)nullptr, a.fbad, (const int32_t*)nullptr, a.ctab, a.rmass);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
         hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kLoads * kWave), 0, st, a.logits_t, a.dv, K, Vt, Vd, a.pf.nC,
-                           a.cs_t, a.ratio_t, a.frow, a.dv.t2x, a.tab_ref, a.tab_s, a.ctab, a.mn, a.fbad, fo);
+                           a.cs_t, a.ratio_t, a.frow, a.dv.t2x, a.tab_ref, a.tab_s, a.ctab, a.mn, a.rmass, a.fbad, fo);
     }
 }
 
@@ -474,12 +476,14 @@ void launch_diag(const tli_map* map, const void* logits_t, const void* logits_d,
     const dim3 scan_grid((unsigned)((rows + 7) / 8) * 8 * nparts * nsplit);
     const DrafterView dvw{logits_d, (int64_t)Vd, nullptr, map->t2d};
     hipLaunchKernelGGL((k_final_scan<DT, 1>), scan_grid, dim3(kScanWG), 0, st, logits_t, dvw, rows, K, Vt, Vd, pt.nC, nsplit,
-                       ls, cs_t, ratio_t, frow, (float*)nullptr, (float*)nullptr, mn, mn2, fbad, (const int32_t*)nullptr);
+                       ls, cs_t, ratio_t, frow, (float*)nullptr, (float*)nullptr, mn, mn2, fbad, (const int32_t*)nullptr,
+                       (const float2*)nullptr, (double*)nullptr);
     hipLaunchKernelGGL(k_diag_finish, dim3(rows), dim3(kWave), 0, st, frow, mn, mn2, rows, pt.nC, alpha_tli, alpha_union,
                        redo, 0);
     // the positions whose rates are tiny (normally none: their workgroups leave at once) again, with fp64 arguments
     hipLaunchKernelGGL((k_final_scan<DT, 2>), scan_grid, dim3(kScanWG), 0, st, logits_t, dvw, rows, K, Vt, Vd, pt.nC, nsplit,
-                       ls, cs_t, ratio_t, frow, (float*)nullptr, (float*)nullptr, mn, mn2, fbad, redo);
+                       ls, cs_t, ratio_t, frow, (float*)nullptr, (float*)nullptr, mn, mn2, fbad, redo, (const float2*)nullptr,
+                       (double*)nullptr);
     hipLaunchKernelGGL(k_diag_finish, dim3(rows), dim3(kWave), 0, st, frow, mn, mn2, rows, pt.nC, alpha_tli, alpha_union,
                        redo, 1);
 }
@@ -1222,7 +1226,7 @@ static int verify_impl(int union_mode, int64_t compact_stride, const tli_map* ma
     a.dv.d2x = compact ? map->d2r : nullptr;
     a.dv.t2x = compact ? map->t2r : map->t2d;
     a.pd = make_plan(a.d_valid, rows, chunk); a.cs_d = (float)c_d; a.ratio_d = c_d / (double)a.cs_d; a.tab_ref = tab_ref; a.tab_s = tab_s;
-    a.mn = reinterpret_cast<double*>(ws + w.mn); a.fbad = reinterpret_cast<int32_t*>(ws + w.fbad); a.ctab = reinterpret_cast<float2*>(ws + w.ctab);
+    a.mn = reinterpret_cast<double*>(ws + w.mn); a.rmass = reinterpret_cast<double*>(ws + w.rmass); a.fbad = reinterpret_cast<int32_t*>(ws + w.fbad); a.ctab = reinterpret_cast<float2*>(ws + w.ctab);
     a.frow = reinterpret_cast<FinalRow*>(ws + w.frow);
     a.union_mode = union_mode;
     if (dtype == TLI_BF16) launch_verify<TLI_BF16>(a, st);

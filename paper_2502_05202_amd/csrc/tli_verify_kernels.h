@@ -145,10 +145,45 @@ __device__ __forceinline__ float exp2_split(float x, float c_hi, float c_lo, flo
     return exp2_hw(fmaf(x, c_hi, -l_hi) + fmaf(x, c_lo, -l_lo));
 }
 
+// The residual weight of a shared target id in the form that stays accurate when q' is close to p:
+//     max(0, p - q') = p * (1 - 2^d),  d = log2 q' - log2 p < 0  (0 for d >= 0),
+// with d formed in fp64 from the two logits and the two normalisers.  p - q' taken from two fp32 values, each good
+// to 1e-7 of itself, is good to 1e-7 of p -- useless once the two models agree to a percent; here the weight keeps
+// 1e-7 of ITSELF (p's own error) whatever the distance.  NaN for a NaN or +inf drafter logit (it must surface).
+struct ResidualWide {
+    double ct, l2p, cd, l2q;  // log2 p = x * ct - l2p, log2 q' = y * cd - l2q
+};
+__device__ __forceinline__ ResidualWide widen(const ResidualParams& rp, double l2p) {
+    ResidualWide w;
+    w.ct = (double)rp.ct_hi + (double)rp.ct_lo;
+    w.cd = (double)rp.cd_hi + (double)rp.cd_lo;
+    w.l2p = l2p;
+    w.l2q = (double)rp.lq_hi + (double)rp.lq_lo;
+    return w;
+}
+__device__ __forceinline__ double residual_weight(float p, float xv, float yv, const ResidualWide& rw) {
+    if (!(yv <= 3.0e38f)) return NAN;
+    if (!(p > 0.f)) return p != p ? NAN : 0.0;
+    const double d = fma((double)yv, rw.cd, -rw.l2q) - fma((double)xv, rw.ct, -rw.l2p);
+    if (!(d < 0.0)) return 0.0;
+    // 1 - 2^d.  Below d = -1 nothing cancels: the hardware exponential's 6e-8 is 6e-8 of the result (d = -inf, a -inf
+    // drafter logit, gives 1: the whole of p).  Above, the series of -expm1(z), z = d ln 2 in (-0.7, 0), in fp32 on the
+    // fp64 difference (ten terms: z^11/11! < 1e-9; each step rounds a value near 1, so the factor keeps ~1e-7).
+    // Both are evaluated and one is chosen: no lane waits for another's branch.
+    const float fd = (float)d;
+    const float far = 1.f - exp2_hw(fd);
+    const float z = fd * 0.693147180559945309f;
+    float t = 1.f / 10.f;
+#pragma unroll
+    for (int k = 9; k >= 2; --k) t = fmaf(t, z, 1.f) * (1.f / (float)k);  // t = 1/2 + z/6 + z^2/24 + ...
+    const float near = -(z * fmaf(t, z, 1.f));
+    return (double)p * (double)(fd < -1.f ? far : near);
+}
+
 template <int DT>
-__device__ __forceinline__ void residual_vec(const void* rowp, int64_t vi, int V, const ResidualParams& rp,
+__device__ __forceinline__ void residual_vec(const void* rowp, int64_t vi, int V, const ResidualParams& rp, double l2p,
                                              const int32_t* __restrict__ t2d, const void* __restrict__ ld_row,
-                                             float* p, float* w) {
+                                             float* p, double* w) {
     constexpr int EPV = Traits<DT>::EPV;
     const int64_t nvec = (V + EPV - 1) / EPV;
     const int64_t vc = vi < nvec ? vi : nvec - 1;
@@ -166,19 +201,14 @@ __device__ __forceinline__ void residual_vec(const void* rowp, int64_t vi, int V
 #pragma unroll
         for (int i = 0; i < EPV; ++i) y[i] = load_elem<DT>(ld_row, d[i] > 0 ? d[i] : 0);
     }
+    const ResidualWide rw = widen(rp, l2p);
 #pragma unroll
     for (int i = 0; i < EPV; ++i) {
         const bool live = e0 + i < V;
         float pi = exp2_split(x[i], rp.ct_hi, rp.ct_lo, rp.lp_hi, rp.lp_lo);
         pi = live ? pi : 0.f;
-        float qi = 0.f;
-        if (rp.use_q) {
-            qi = exp2_split(y[i], rp.cd_hi, rp.cd_lo, rp.lq_hi, rp.lq_lo);
-            qi = (live && d[i] >= 0) ? qi : 0.f;
-        }
         p[i] = pi;
-        w[i] = fmaxf(0.f, pi - qi);
-        if (!(qi <= 3.0e38f)) w[i] = NAN;  // NaN or +inf in the drafter row must surface (fmaxf would drop it)
+        w[i] = (rp.use_q && live && d[i] >= 0) ? residual_weight(pi, x[i], y[i], rw) : (double)pi;
     }
 }
 
@@ -204,7 +234,8 @@ template <int DT, class MN>
 __device__ __forceinline__ PickResult final_pick_core(const FinalRow& f, int b, const void* logits_t, const DrafterView& dv,
                                                       int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
                                                       const int32_t* t2d, const float* tr, const float* ts,
-                                                      const float2* ctab, const MN* mn, bool drafter_bad, double u) {
+                                                      const float2* ctab, const MN* mn, const double* rmass,
+                                                      bool drafter_bad, double u) {
     constexpr int EPV = Traits<DT>::EPV;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -229,6 +260,7 @@ __device__ __forceinline__ PickResult final_pick_core(const FinalRow& f, int b, 
     };
     auto r_mass = [&](int cc) {
         const double m = f.rp.use_q ? (double)mn[cc] : 0.0;
+        if (m < 0.0) return rmass[cc];  // the scan formed this chunk's mass itself (see precise_chunk_masses)
         const double t = p_mass(cc) - m;
         return t > 0.0 ? t : (t != t ? t : 0.0);
     };
@@ -256,10 +288,11 @@ __device__ __forceinline__ PickResult final_pick_core(const FinalRow& f, int b, 
         const int64_t vi = ((int64_t)c * kLoads + wave) * kWave + lane;
         double wd[EPV];
         if (wave < kLoads) {
-            float p[EPV], w[EPV];
-            residual_vec<DT>(rowp, vi, Vt, f.rp, t2d, ldp, p, w);
+            float p[EPV];
+            double w[EPV];
+            residual_vec<DT>(rowp, vi, Vt, f.rp, f.l2p, t2d, ldp, p, w);
 #pragma unroll
-            for (int i = 0; i < EPV; ++i) wd[i] = degenerate ? (double)p[i] : (double)w[i];
+            for (int i = 0; i < EPV; ++i) wd[i] = degenerate ? (double)p[i] : w[i];
         } else {  // a larger workgroup's further waves take no part in the draw
 #pragma unroll
             for (int i = 0; i < EPV; ++i) wd[i] = 0.0;
@@ -273,10 +306,10 @@ template <int DT>
 __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const void* logits_t, const DrafterView& dv,
                                                int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
                                                const int32_t* t2d, const float* tr, const float* ts,
-                                               const float2* ctab, const double* mn, bool drafter_bad,
-                                               const FinalOut& o) {
+                                               const float2* ctab, const double* mn, const double* rmass,
+                                               bool drafter_bad, const FinalOut& o) {
     const PickResult r = final_pick_core<DT>(f, b, logits_t, dv, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tr, ts, ctab, mn,
-                                             drafter_bad, (double)o.u_fin[b]);
+                                             rmass, drafter_bad, (double)o.u_fin[b]);
     if (threadIdx.x == 0) {
         if (r.nonfinite) {
             o.n_accepted[b] = 0;
@@ -389,6 +422,74 @@ template <> struct BadTrack<TLI_F32> {
     __device__ __forceinline__ bool bad() const { return sm >= 0x7f800000 || um > 0xff800000u; }
 };
 
+// Residual masses of a workgroup's target chunks for a row on which the two models nearly agree.  The fast walk
+// forms a chunk's mass as (sum of p over the chunk, from the normaliser kernel) - (sum of min(p, q') over its pairs):
+// two fp32 sums, each good to 1e-7 of the chunk's p mass, so their difference is only that good -- and the draw
+// needs it to 1e-6 of the ROW's residual mass R.  When a workgroup finds its chunks' residual below a quarter of
+// their p mass, it forms the masses again here, with nothing subtracted that does not cancel exactly:
+//     mass = (sum over every id of the chunk of p  -  sum over the pairs of p)  +  sum over the pairs of max(0, p - q'),
+// all three in fp64 over fp32 terms, p of a shared id being the same fp32 number in both sums (same instructions, same
+// operands), so the first difference is the target-only ids' mass to fp64 rounding; the last sum takes its terms from
+// residual_weight.  Padding entries of a pair list (first id of the chunk against a -inf drafter logit) add the same p
+// to the second and the third sum.  The chunk's mass goes to rmass, and mn gets -1: "take rmass" for the draw.
+// Plain loop, no pipelining: rows that need it are rows whose drafts are mostly accepted.
+template <int DT>
+__device__ __noinline__ void precise_chunk_masses(unsigned char* lds, uint32_t tb, const char* trow, int nvec, int Vt,
+                                                  const int32_t* pl_g, const uint2* pl_e, int c_lo, int ncp, int gw,
+                                                  int stride, ResidualParams rp, double l2p, double* rmass_row,
+                                                  double* mn_row) {
+    constexpr int EPV = Traits<DT>::EPV;
+    constexpr int ESZ = Traits<DT>::ESZ;
+    typedef typename std::conditional<DT == TLI_BF16, uint16_t, uint32_t>::type raw_t;
+    const int lane = threadIdx.x & 63;
+    unsigned char* const part = lds + kTrashBytes;
+    const ResidualWide rw = widen(rp, l2p);
+    for (int idx = gw; idx < ncp; idx += stride) {  // wave-uniform
+        const int c = c_lo + idx;
+        const uint32_t v0 = (uint32_t)c * (kLoads * kWave) + lane;
+        u4v v[kLoads];
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j)
+            v[j] = *reinterpret_cast<const u4v*>(trow + min(v0 + j * kWave, (uint32_t)nvec - 1u) * 16u);
+        u4v* st = reinterpret_cast<u4v*>(lds + tb);
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) st[j * kWave + lane] = v[j];
+        __builtin_amdgcn_wave_barrier();
+        double s_all = 0.0, s_pairs = 0.0, s_w = 0.0;
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            float x[EPV];
+            unpack<DT>(to_uint4(v[j]), x);
+            const int64_t e0 = (int64_t)(v0 + j * kWave) * EPV;
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) {
+                const float pi = exp2_split(x[i], rp.ct_hi, rp.ct_lo, rp.lp_hi, rp.lp_lo);
+                s_all += (e0 + i < Vt) ? (double)pi : 0.0;
+            }
+        }
+        auto one = [&](uint32_t e) {
+            const uint32_t xr = *reinterpret_cast<const raw_t*>(lds + (tb + (e & 0xffffu)));
+            const uint32_t yr = *reinterpret_cast<const raw_t*>(part + (e >> kPairShift) * ESZ);
+            const float xv = as_f(DT == TLI_BF16 ? xr << 16 : xr), yv = as_f(DT == TLI_BF16 ? yr << 16 : yr);
+            const float pi = exp2_split(xv, rp.ct_hi, rp.ct_lo, rp.lp_hi, rp.lp_lo);
+            s_pairs += (double)pi;
+            s_w += residual_weight(pi, xv, yv, rw);
+        };
+        const int g1 = pl_g[c + 1];
+        for (int g = pl_g[c]; g < g1; ++g) {
+            const uint2 e = pl_e[(int64_t)g * kWave + lane];
+            one(e.x);
+            one(e.y);
+        }
+        __builtin_amdgcn_wave_barrier();  // the slot is rewritten by the next chunk
+        const double mass = (wave_sum_f64(s_all) - wave_sum_f64(s_pairs)) + wave_sum_f64(s_w);
+        if (lane == 0) {
+            rmass_row[c] = mass > 0.0 ? mass : (mass != mass ? mass : 0.0);
+            mn_row[c] = -1.0;
+        }
+    }
+}
+
 // DIAG (acceptance-rate diagnostics): the items are all B*K positions instead of one row per sequence, and a
 // second sum runs beside the first with the drafter's unrestricted probabilities q = q' * 2^-dq:
 // mn = sum min(p, q') (TLI's expected acceptance rate), mn2 = sum min(p, q) (the union algorithm's).
@@ -399,7 +500,8 @@ template <int DT, int MODE>
 __global__ __launch_bounds__(kScanWG) void k_final_scan(
     const void* __restrict__ logits_t, DrafterView dv, int B, int K, int Vt, int Vd, int nC, int nsplit, ScanLists ls,
     float cs_t, double ratio_t, const FinalRow* __restrict__ frow, float* __restrict__ tab_ref, float* __restrict__ tab_s, double* __restrict__ mn, double* __restrict__ mn2,
-    int32_t* __restrict__ fbad, const int32_t* __restrict__ redo) {
+    int32_t* __restrict__ fbad, const int32_t* __restrict__ redo, const float2* __restrict__ ctab,
+    double* __restrict__ rmass) {
     constexpr bool DIAG = MODE != 0;
     constexpr bool EXACT = MODE == 2;
     constexpr int EPV = Traits<DT>::EPV;
@@ -623,6 +725,13 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
             }
         }
     };
+    // (for the question asked after the walk: the p mass of the wave's chunks, lane k the k-th; loaded here so that
+    // the answer does not wait for memory)
+    float2 my_rs = make_float2(-INFINITY, 0.f);
+    if (MODE == 0) {
+        const int idx = gw + lane * stride;
+        if (idx < ncp) my_rs = ctab[(int64_t)f.d_row * nC + c_lo + idx];
+    }
     int k = 0;
     for (int idx = gw; idx < ncp; idx += 2 * stride, k += 2) {
         fetch(k + 1, fb);
@@ -630,7 +739,30 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         fetch(k + 2, fa);
         if (idx + stride < ncp) process(fb, k + 1);
     }
-    {
+    bool precise = false;
+    if (MODE == 0) {
+        // How much of these chunks' p mass is residual?  Below a quarter, the masses are formed again without the
+        // cancelling subtraction (see precise_chunk_masses).  Lane k: the wave's k-th chunk.
+        const int idx = gw + lane * stride;
+        float pm = 0.f, rm = 0.f;  // a rough figure is all the question needs
+        if (idx < ncp) {
+            pm = (my_rs.x == -INFINITY) ? 0.f : my_rs.y * exp2_hw((float)((double)my_rs.x * ratio_t - f.l2p));
+            rm = fmaxf(pm - (float)keep, 0.f);
+        }
+        pm = wave_sum(pm);
+        rm = wave_sum(rm);
+        float* dec = reinterpret_cast<float*>(lds);  // the sweep's scratch words: free since the barrier behind it
+        if (lane == 0) { dec[2 * wave] = pm; dec[2 * wave + 1] = rm; }
+        __syncthreads();
+        float P = 0.f, R = 0.f;
+#pragma unroll
+        for (int w = 0; w < kScanWaves; ++w) { P += dec[2 * w]; R += dec[2 * w + 1]; }
+        precise = R < 0.25f * P;  // (false for NaN sums: the draw reports those)
+    }
+    if (precise) {
+        precise_chunk_masses<DT>(lds, tb, trow, nvec, Vt, pl_g, pl_e, c_lo, ncp, gw, stride, rp, f.l2p,
+                                 rmass + (int64_t)b * nC, my_mn);
+    } else {
         const int idx = gw + lane * stride;
         if (idx < ncp) {
             my_mn[c_lo + idx] = keep;
@@ -651,10 +783,12 @@ __global__ __launch_bounds__(kLoads * kWave) void k_final_pick(const void* __res
                                                        const float* __restrict__ tab_s,
                                                        const float2* __restrict__ ctab,
                                                        const double* __restrict__ mn,
+                                                       const double* __restrict__ rmass,
                                                        const int32_t* __restrict__ fbad, FinalOut o) {
     const int b = blockIdx.x;
     const FinalRow f = frow[b];
     if (f.skip) return;
     final_pick_row<DT>(f, b, logits_t, dv, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
-                       tab_s + (int64_t)b * nC, ctab, mn + (int64_t)b * nC, f.rp.use_q && fbad[b] != 0, o);
+                       tab_s + (int64_t)b * nC, ctab, mn + (int64_t)b * nC, rmass + (int64_t)b * nC,
+                       f.rp.use_q && fbad[b] != 0, o);
 }

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _check(res, allow_near=True):
+def _check(res, allow_near=True, allow_small_residual=False):
     for name in ("draft", "verify", "chained"):
         rep = res[name]
         if rep is None:
@@ -25,6 +25,8 @@ def _check(res, allow_near=True):
         assert rep["max_lse_err"] < 5e-7 and rep["max_prob_rel"] < 1e-6, dict(rep)
         if not allow_near:
             assert rep["accept_near_ties"] == 0 and rep["token_near_ties"] == 0
+        if not allow_small_residual:
+            assert rep["token_small_residual_ties"] == 0, dict(rep)
 
 
 @pytest.mark.parametrize("seed", [0, 1, 2, 3])
@@ -136,6 +138,40 @@ def test_nearly_identical_models(oracle, rho, dtype):
     _check(res)
     n = res["ref_verify"]["n_acc"]
     assert (n < w.K).any()  # some rows do sample from a residual
+
+
+@pytest.mark.parametrize("delta,dtype", [(1e-2, "f32"), (1e-3, "f32"), (2e-4, "f32"), (2e-2, "bf16")])
+def test_small_residuals_on_many_sequences(oracle, delta, dtype):
+    """Every token shared, equal temperatures, target logits = drafter logits + N(0, delta^2): the residual mass R of
+    a rejected position is of order delta (down to 1e-4 here), and the chunk masses that pick the extra token are
+    small differences of chunk sums that each carry 1e-7 of their own size (the scan then forms them again without
+    the cancelling subtraction).  Hundreds of sequences per case.  At delta = 1e-2 and above every draw must equal the
+    oracle's or be a counted near-tie; below, the normalisers' own 5e-7 shows at 5e-7 / R of the residual, and a draw
+    may also differ inside that window of probability mass (counted separately, a few per hundred at most)."""
+    V, B, K = 2048 * 6 + 264, 320, 2
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(int(delta * 1e6) + 5)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    ld = (torch.randn(B, K, V, generator=gen, device=DEV) * 2.5).to(tdt)
+    lt = torch.empty(B, K + 1, V, dtype=tdt, device=DEV)
+    lt[:, :K] = (ld.float() + delta * torch.randn(B, K, V, generator=gen, device=DEV)).to(tdt)
+    lt[:, K] = (torch.randn(B, V, generator=gen, device=DEV) * 2.5).to(tdt)
+    w = synth.WORKLOADS[3].scaled(Vt=V, Vd=V, S=V, B=B, K=K, dtype=dtype, tau_t=0.8, tau_d=0.8)
+    perm = np.random.default_rng(9).permutation(V).astype(np.int32)
+    lt[:, :K] = lt[:, :K].clone()[:, :, torch.from_numpy(np.argsort(perm)).to(DEV)]  # target id of drafter id x is perm[x]
+    inp = dict(workload=w, d2t=perm, logits_t=lt, logits_d=ld,
+               u_draft=synth._uniform24(B * K, gen, DEV).reshape(B, K),
+               u_acc=1.0 - 0.2 * delta * synth._uniform24(B * K, gen, DEV).reshape(B, K),  # close to 1: rejections happen
+               u_fin=synth._uniform24(B, gen, DEV))
+    res = parity.run_case(oracle, inp, threads=16)
+    _check(res, allow_small_residual=delta < 5e-3)
+    n = res["ref_verify"]["n_acc"]
+    rejected = int((n < K).sum())
+    print(f"delta {delta}: {rejected} of {B} sequences draw from a residual; near-tie draws:",
+          res["verify"]["token_near_ties"], "at 1e-8:", res["verify"]["token_near_ties_tight"],
+          "beyond 1e-6 of the residual but within 5e-7 of mass:", res["verify"]["token_small_residual_ties"])
+    assert rejected >= B // 10
+    assert res["verify"]["token_small_residual_ties"] <= rejected // 20
 
 
 def test_full_size_half_accepted(oracle):
