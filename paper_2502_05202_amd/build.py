@@ -6,7 +6,7 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
-SOURCES = [os.path.join(_HERE, "csrc", "tli_kernels.hip")]
+SOURCES = [os.path.join(_HERE, "csrc", "tli_kernels.hip"), os.path.join(_HERE, "csrc", "tli_host_map.cpp")]
 LIB = os.path.join(_HERE, "libtli.so")
 
 HIPCC_FLAGS = [

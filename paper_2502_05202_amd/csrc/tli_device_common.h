@@ -1,26 +1,14 @@
 // tli_device_common.h -- Constants, storage traits, wave64 reductions, chunk loads and the per-chunk reduction that every kernel of the
-// path is built from.  Included by tli_kernels.hip inside its unnamed namespace.
+// path is built from.  Included by tli_kernels.hip inside its unnamed namespace (after tli_layout.h, whose names --
+// kWave, kLoads, Traits, chunk_elems -- are in scope there).
 #pragma once
 
-constexpr int kWave = 64;
 constexpr int kWG = 256;
 constexpr int kWaves = kWG / kWave;
-constexpr int kLoads = 4;
 constexpr int kMaxK = 64;
 constexpr int kLdsChunks = 1024;  // chunk-table entries a workgroup may park in LDS
 constexpr double kLn2 = 0.693147180559945309417232121458;
 constexpr double kLog2e = 1.44269504088896340735992468100;
-
-template <int DT> struct Traits;
-template <> struct Traits<TLI_F32> {
-    static constexpr int EPV = 4;  // elements per 16-byte vector
-    static constexpr int ESZ = 4;
-};
-template <> struct Traits<TLI_BF16> {
-    static constexpr int EPV = 8;
-    static constexpr int ESZ = 2;
-};
-template <int DT> constexpr int chunk_elems() { return kWave * kLoads * Traits<DT>::EPV; }
 
 __device__ __forceinline__ float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t as_u(float f) { return __builtin_bit_cast(uint32_t, f); }

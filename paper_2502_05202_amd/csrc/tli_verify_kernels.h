@@ -362,19 +362,7 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
 // grid (B rounded up to 8) x nparts x nsplit; workgroups of flagged sequences exit at once.
 // nsplit > 1 (few sequences): the chunks of one (sequence, part) are dealt to nsplit workgroups, each with
 // its own copy of the part's drafter logits.
-constexpr int kScanWG = 1024;
-constexpr int kScanWaves = kScanWG / kWave;
-constexpr int kSlotBytes = kWave * kLoads * 16;  // one chunk
-constexpr int kTrashBytes = kWave * 4;           // LDS [0, 256): a word per lane for the elements a lane does not keep
-constexpr int kPartBytes = 92 * 1024;            // then the staged drafter logits of a part, the last 16 bytes of the
-                                                 // area hold the -inf logit that padding entries point at
-constexpr int kScanLds = kPartBytes + kScanWaves * kSlotBytes;  // then one chunk slot per wave
-constexpr int kPairG = 2 * kWave;      // entries in a group of a chunk's pair list: two per lane
-constexpr int kPairU = 6;              // groups fetched with a chunk (more: late loop)
 constexpr int kStageV = 8;             // drafter vectors a lane has in flight during the staging sweep
-constexpr int kPairShift = 16;         // entry = byte offset in chunk (< 4096) | index of the staged logit << 16
-constexpr int kMaxPartChunks = kWave * kScanWaves;  // a wave keeps a lane per chunk it handles
-static_assert(kScanLds <= 160 * 1024, "LDS of one CU");
 
 struct ScanLists {            // the map's lists for one dtype and one drafter-row layout, as the scan kernel reads them
     int nparts;
@@ -388,11 +376,6 @@ struct ScanLists {            // the map's lists for one dtype and one drafter-r
     const int32_t* pl_g;      // [nC+1] first group of every chunk's pair list
     const uint2* pl_e;        // pairs grouped by chunk (two per lane and group), kPairU groups of slack at the end
 };
-// pairs a part may hold, and the index of the -inf logit
-template <int DT> constexpr int part_cap() { return (kPartBytes - kTrashBytes - 16) / Traits<DT>::ESZ; }
-template <int DT> constexpr int dummy_index() { return part_cap<DT>(); }
-static_assert(dummy_index<TLI_BF16>() < (1 << 16) && dummy_index<TLI_F32>() < (1 << 16), "16-bit staged index");
-
 // NaN or +inf among the staged drafter logits must surface (-inf is legal).  As signed integers the raw
 // patterns of +inf and the positive NaNs are the largest values, as unsigned ones the negative NaNs are (just
 // above -inf): two running maxima, taken on both halves of a dword at once for bf16.

@@ -147,3 +147,38 @@ def test_d2t_from_token_strings(lib):
         ex(["a"], ["b", "b"])
     # what comes out is what tli_build_map takes
     assert binding.tli_map_dry_run(ex(D, T), len(T))["num_shared"] == 2000
+
+
+def test_map_builder_under_address_and_ub_sanitizers(tmp_path):
+    """The host-side table builder (argument checks, parts, staging tables, pair lists, the host replay of the residual
+    scan's indexing, the string join) is plain C++ in a file of its own: built here with g++ -fsanitize=address,undefined
+    -- no HIP, no device -- and driven over the workloads' vocabulary shapes, bunched and identical vocabularies,
+    invalid maps, the string join, and a seeded fuzz of (Vd, Vt, S, layout of the shared ids).  A sanitizer report, a
+    failed consistency check or an unexpected status fails the test."""
+    import subprocess
+
+    csrc = os.path.join(ROOT, "paper_2502_05202_amd", "csrc")
+    exe = str(tmp_path / "hostmap_san")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                    "-static-libasan", "-static-libubsan",  # the runtimes inside the executable: no library order to mind
+                    "-I", os.path.join(ROOT, "include"), "-I", csrc, os.path.join(csrc, "tli_host_map.cpp"),
+                    os.path.join(ROOT, "tests", "hostmap_san_driver.cpp"), "-o", exe], check=True)
+    cases = [
+        (48, 64, 32, 1, 0), (32000, 128256, 24000, 2, 0), (49152, 151936, 40000, 3, 0), (128256, 256000, 90000, 4, 0),
+        (128256, 202048, 60000, 5, 0),                       # the five workloads
+        (60000, 70000, 50000, 6, 1), (130000, 130000, 130000, 7, 2), (4096, 8200, 1, 8, 0),
+        (5000, 2048 * 1100 + 8, 3000, 9, 0),                 # a row of more than 1024 chunks
+        (9000, 7000, 500, 10, 3), (9000, 7000, 500, 11, 3), (9000, 7000, 500, 12, 3),   # the three refusals
+        (3000, 5000, 1200, 13, 4), (20000, 9000, 8000, 14, 4),                          # through token strings
+    ]
+    rng = np.random.default_rng(2025)
+    for i in range(24):  # seeded fuzz
+        Vd, Vt = int(rng.integers(8, 200000)), int(rng.integers(8, 300000))
+        S = int(rng.integers(1, min(Vd, Vt) + 1))
+        cases.append((Vd, Vt, S, 100 + i, int(rng.integers(0, 2))))
+    args = [str(v) for c in cases for v in c]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    res = subprocess.run([exe] + args, capture_output=True, text=True, env=env)
+    assert res.returncode == 0, res.stdout[-3000:] + res.stderr[-3000:]
+    assert "runtime error" not in res.stderr and "AddressSanitizer" not in res.stderr, res.stderr[-3000:]
+    assert res.stdout.count("failed_check 0") == len(cases)
