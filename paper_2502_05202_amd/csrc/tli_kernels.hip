@@ -69,7 +69,7 @@ size_t lse_shmem(const Plan& p) { return (size_t)(p.cps < kLdsChunks ? p.cps : k
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {  // offsets into the caller's scratch
-    size_t part, part_d, ws_lse_p, ws_lse_q, ctab, frow, fbad, tab_ref, tab_s, mn, rmass, total;
+    size_t part, part_d, ws_lse_p, ws_lse_q, ctab, frow, fbad, tab_ref, tab_s, rmass, total;
 };
 
 Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
@@ -91,9 +91,7 @@ Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
     w.fbad = off; off += align256((size_t)B * sizeof(int32_t));
     w.tab_ref = off; off += align256(tab * sizeof(float));
     w.tab_s = off; off += align256(tab * sizeof(float));
-    // the residual scan's sums of min(p, q'), one per chunk of the row the extra token is drawn from
-    w.mn = off; off += align256(tab_rows_t * sizeof(double));
-    // ... and the chunk masses themselves, for rows whose residual is a small part of p (precise_chunk_masses)
+    // the residual scan's chunk masses, one per chunk of the row the extra token is drawn from
     w.rmass = off; off += align256(tab_rows_t * sizeof(double));
     w.total = off;
     return w;
@@ -162,7 +160,7 @@ struct VerifyArgs {
     float cs_d;
     double ratio_d;
     float *tab_ref, *tab_s;
-    double *mn, *rmass;
+    double* rmass;
     float2* ctab;
     FinalRow* frow;
     int32_t* fbad;
@@ -379,12 +377,12 @@ void launch_verify_tail(const VerifyArgs& a, const double* lse_q, hipStream_t st
         nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
         hipLaunchKernelGGL((k_final_scan<DT, 0>), dim3((unsigned)((B + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0,
                            st, a.logits_t, a.dv, B, K, Vt, Vd, a.pf.nC, nsplit, ls, a.cs_t, a.ratio_t, a.frow, a.tab_ref,
-                           a.tab_s, a.mn, (double*)nullptr, a.fbad, (const int32_t*)nullptr, a.ctab, a.rmass);
+                           a.tab_s, (double*)nullptr, (double*)nullptr, a.fbad, (const int32_t*)nullptr, a.ctab, a.rmass);
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
         hipLaunchKernelGGL(k_final_pick<DT>, dim3(B), dim3(kLoads * kWave), 0, st, a.logits_t, a.dv, K, Vt, Vd, a.pf.nC,
-                           a.cs_t, a.ratio_t, a.frow, a.dv.t2x, a.tab_ref, a.tab_s, a.ctab, a.mn, a.rmass, a.fbad, fo);
+                           a.cs_t, a.ratio_t, a.frow, a.dv.t2x, a.tab_ref, a.tab_s, a.ctab, a.rmass, a.fbad, fo);
     }
 }
 
@@ -954,7 +952,7 @@ static int verify_impl(int union_mode, int64_t compact_stride, const tli_map* ma
     a.dv.d2x = compact ? map->d2r : nullptr;
     a.dv.t2x = compact ? map->t2r : map->t2d;
     a.pd = make_plan(a.d_valid, rows, chunk); a.cs_d = (float)c_d; a.ratio_d = c_d / (double)a.cs_d; a.tab_ref = tab_ref; a.tab_s = tab_s;
-    a.mn = reinterpret_cast<double*>(ws + w.mn); a.rmass = reinterpret_cast<double*>(ws + w.rmass); a.fbad = reinterpret_cast<int32_t*>(ws + w.fbad); a.ctab = reinterpret_cast<float2*>(ws + w.ctab);
+    a.rmass = reinterpret_cast<double*>(ws + w.rmass); a.fbad = reinterpret_cast<int32_t*>(ws + w.fbad); a.ctab = reinterpret_cast<float2*>(ws + w.ctab);
     a.frow = reinterpret_cast<FinalRow*>(ws + w.frow);
     a.union_mode = union_mode;
     if (dtype == TLI_BF16) launch_verify<TLI_BF16>(a, st);

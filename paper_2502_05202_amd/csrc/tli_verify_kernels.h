@@ -229,13 +229,12 @@ struct PickResult {
     double lse_bonus;  // bonus rows: log-normaliser of row K
 };
 
-// MN: float or double chunk sums of min(p, q') (read only for residual rows with a usable draft)
-template <int DT, class MN>
+template <int DT>
 __device__ __forceinline__ PickResult final_pick_core(const FinalRow& f, int b, const void* logits_t, const DrafterView& dv,
                                                       int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
                                                       const int32_t* t2d, const float* tr, const float* ts,
-                                                      const float2* ctab, const MN* mn, const double* rmass,
-                                                      bool drafter_bad, double u) {
+                                                      const float2* ctab, const double* rmass, bool drafter_bad,
+                                                      double u) {
     constexpr int EPV = Traits<DT>::EPV;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -252,18 +251,15 @@ __device__ __forceinline__ PickResult final_pick_core(const FinalRow& f, int b, 
         return res;
     }
     const char* ldp = static_cast<const char*>(dv.base) + (int64_t)f.d_row * dv.row_stride * Traits<DT>::ESZ;
-    // chunk masses: sum_chunk p (from the normaliser kernel's table of row n) minus the parts' sums of min(p, q')
+    // chunk masses: the scan left them (sum_chunk p - sum of min(p, q'), or formed without that subtraction, see
+    // precise_chunk_masses); a row without a usable draft has q' = 0 and its masses are the chunk sums of p, from
+    // the normaliser kernel's table of row n
     const float2* crow = ctab + (int64_t)f.d_row * nC;
     auto p_mass = [&](int cc) {
         const float2 rs = crow[cc];
         return (rs.x == -INFINITY) ? 0.0 : (double)rs.y * exp2((double)rs.x * ratio_t - f.l2p);
     };
-    auto r_mass = [&](int cc) {
-        const double m = f.rp.use_q ? (double)mn[cc] : 0.0;
-        if (m < 0.0) return rmass[cc];  // the scan formed this chunk's mass itself (see precise_chunk_masses)
-        const double t = p_mass(cc) - m;
-        return t > 0.0 ? t : (t != t ? t : 0.0);
-    };
+    auto r_mass = [&](int cc) { return f.rp.use_q ? rmass[cc] : p_mass(cc); };
     double theta_local, total;
     int c = -1;
     bool degenerate = false;
@@ -306,10 +302,10 @@ template <int DT>
 __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const void* logits_t, const DrafterView& dv,
                                                int K, int Vt, int Vd, int nC, float cs_t, double ratio_t,
                                                const int32_t* t2d, const float* tr, const float* ts,
-                                               const float2* ctab, const double* mn, const double* rmass,
-                                               bool drafter_bad, const FinalOut& o) {
-    const PickResult r = final_pick_core<DT>(f, b, logits_t, dv, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tr, ts, ctab, mn,
-                                             rmass, drafter_bad, (double)o.u_fin[b]);
+                                               const float2* ctab, const double* rmass, bool drafter_bad,
+                                               const FinalOut& o) {
+    const PickResult r = final_pick_core<DT>(f, b, logits_t, dv, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tr, ts, ctab, rmass,
+                                             drafter_bad, (double)o.u_fin[b]);
     if (threadIdx.x == 0) {
         if (r.nonfinite) {
             o.n_accepted[b] = 0;
@@ -414,13 +410,12 @@ template <> struct BadTrack<TLI_F32> {
 // all three in fp64 over fp32 terms, p of a shared id being the same fp32 number in both sums (same instructions, same
 // operands), so the first difference is the target-only ids' mass to fp64 rounding; the last sum takes its terms from
 // residual_weight.  Padding entries of a pair list (first id of the chunk against a -inf drafter logit) add the same p
-// to the second and the third sum.  The chunk's mass goes to rmass, and mn gets -1: "take rmass" for the draw.
+// to the second and the third sum.  The chunk's mass goes to rmass, where the fast walk's would have gone.
 // Plain loop, no pipelining: rows that need it are rows whose drafts are mostly accepted.
 template <int DT>
 __device__ __noinline__ void precise_chunk_masses(unsigned char* lds, uint32_t tb, const char* trow, int nvec, int Vt,
                                                   const int32_t* pl_g, const uint2* pl_e, int c_lo, int ncp, int gw,
-                                                  int stride, ResidualParams rp, double l2p, double* rmass_row,
-                                                  double* mn_row) {
+                                                  int stride, ResidualParams rp, double l2p, double* rmass_row) {
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int ESZ = Traits<DT>::ESZ;
     typedef typename std::conditional<DT == TLI_BF16, uint16_t, uint32_t>::type raw_t;
@@ -466,10 +461,7 @@ __device__ __noinline__ void precise_chunk_masses(unsigned char* lds, uint32_t t
         }
         __builtin_amdgcn_wave_barrier();  // the slot is rewritten by the next chunk
         const double mass = (wave_sum_f64(s_all) - wave_sum_f64(s_pairs)) + wave_sum_f64(s_w);
-        if (lane == 0) {
-            rmass_row[c] = mass > 0.0 ? mass : (mass != mass ? mass : 0.0);
-            mn_row[c] = -1.0;
-        }
+        if (lane == 0) rmass_row[c] = mass > 0.0 ? mass : (mass != mass ? mass : 0.0);
     }
 }
 
@@ -624,7 +616,7 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     }
 
     // ---- (2) stream target chunks past it
-    double* my_mn = mn + (int64_t)b * nC;
+    double* my_mn = DIAG ? mn + (int64_t)b * nC : nullptr;
     double* my_mn2 = DIAG ? mn2 + (int64_t)b * nC : nullptr;
     const ResidualParams rp = f.rp;
     const uint32_t tb = (uint32_t)(kPartBytes + wave * kSlotBytes);
@@ -723,14 +715,19 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         if (idx + stride < ncp) process(fb, k + 1);
     }
     bool precise = false;
+    double mass_fast = 0.0;
     if (MODE == 0) {
         // How much of these chunks' p mass is residual?  Below a quarter, the masses are formed again without the
         // cancelling subtraction (see precise_chunk_masses).  Lane k: the wave's k-th chunk.
         const int idx = gw + lane * stride;
         float pm = 0.f, rm = 0.f;  // a rough figure is all the question needs
         if (idx < ncp) {
-            pm = (my_rs.x == -INFINITY) ? 0.f : my_rs.y * exp2_hw((float)((double)my_rs.x * ratio_t - f.l2p));
-            rm = fmaxf(pm - (float)keep, 0.f);
+            // the chunk's mass as the draw takes it: sum_chunk p (the normaliser kernel's pair) - sum of min(p, q')
+            const double pmd = (my_rs.x == -INFINITY) ? 0.0 : (double)my_rs.y * exp2((double)my_rs.x * ratio_t - f.l2p);
+            const double t = pmd - keep;
+            mass_fast = t > 0.0 ? t : (t != t ? t : 0.0);
+            pm = (float)pmd;
+            rm = (float)mass_fast;
         }
         pm = wave_sum(pm);
         rm = wave_sum(rm);
@@ -744,12 +741,12 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     }
     if (precise) {
         precise_chunk_masses<DT>(lds, tb, trow, nvec, Vt, pl_g, pl_e, c_lo, ncp, gw, stride, rp, f.l2p,
-                                 rmass + (int64_t)b * nC, my_mn);
+                                 rmass + (int64_t)b * nC);
     } else {
         const int idx = gw + lane * stride;
         if (idx < ncp) {
-            my_mn[c_lo + idx] = keep;
-            if (DIAG) my_mn2[c_lo + idx] = keep2;
+            if (DIAG) { my_mn[c_lo + idx] = keep; my_mn2[c_lo + idx] = keep2; }
+            else rmass[(int64_t)b * nC + c_lo + idx] = mass_fast;
         }
     }
     if (bt.bad()) fbad[b] = 1;
@@ -765,13 +762,19 @@ __global__ __launch_bounds__(kLoads * kWave) void k_final_pick(const void* __res
                                                        const float* __restrict__ tab_ref,
                                                        const float* __restrict__ tab_s,
                                                        const float2* __restrict__ ctab,
-                                                       const double* __restrict__ mn,
                                                        const double* __restrict__ rmass,
                                                        const int32_t* __restrict__ fbad, FinalOut o) {
     const int b = blockIdx.x;
+    // the chunk masses do not wait for the sequence's record: both round trips are started together (for rows that
+    // have none the words read here are never looked at)
+    __shared__ double s_mass[kLdsChunks];
+    const bool staged = nC <= kLdsChunks;
+    if (staged)
+        for (int c = threadIdx.x; c < nC; c += kLoads * kWave) s_mass[c] = rmass[(int64_t)b * nC + c];
+    const int bad = fbad[b];
     const FinalRow f = frow[b];
+    __syncthreads();
     if (f.skip) return;
     final_pick_row<DT>(f, b, logits_t, dv, K, Vt, Vd, nC, cs_t, ratio_t, t2d, tab_ref + (int64_t)b * nC,
-                       tab_s + (int64_t)b * nC, ctab, mn + (int64_t)b * nC, rmass + (int64_t)b * nC,
-                       f.rp.use_q && fbad[b] != 0, o);
+                       tab_s + (int64_t)b * nC, ctab, staged ? s_mass : rmass + (int64_t)b * nC, f.rp.use_q && bad != 0, o);
 }
