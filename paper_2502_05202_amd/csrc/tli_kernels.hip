@@ -411,7 +411,7 @@ template <int DT> void launch_verify(const VerifyArgs& a, hipStream_t st) {
         out.q_tok = a.q_tok; out.lse_p = a.lse_p; out.seq_status = a.seq_status; out.frow = a.frow; out.fbad = a.fbad;
         {
             KernelTimer t(TLI_KERNEL_LSE, st);
-            hipLaunchKernelGGL(k_lse_accept_seq<DT>, dim3(a.B), dim3(kScanWG), 0, st, a.logits_t, a.dv, a.K, a.map->Vt,
+            hipLaunchKernelGGL(k_lse_accept_seq<DT>, dim3(a.B), dim3(kSeqWG), 0, st, a.logits_t, a.dv, a.K, a.map->Vt,
                                a.map->Vd, a.pf.nC, in, a.ctab, out);
         }
         launch_verify_tail<DT>(a, lse_q, st, /*accept_done=*/true);

@@ -4,8 +4,8 @@
 
 // Standard SD appendix, verification loop and count of accepted drafts, in one kernel (k_lse + k_accept of the
 // split form, without the kernel boundary between them and its chain of dependent round trips).  A workgroup of
-// 16 waves owns a sequence:
-//   * waves 1..15 stream the sequence's K target rows, one row at a time, chunk pairs (ref, s) into one of two
+// 1 + kSeqStreamWaves waves owns a sequence:
+//   * waves 1.. stream the sequence's K target rows, one row at a time, chunk pairs (ref, s) into one of two
 //     tables in LDS; sequence b takes row (b + i) mod K at step i, so the rows a compute unit reads at one time
 //     are spread over the positions;
 //   * wave 0 is the sequence's clerk: while the others stream the next row it reduces the last row's pairs to the
@@ -13,9 +13,13 @@
 //     accept test the moment row k is through -- its draft's two logits were gathered when the kernel started;
 //   * when every row is through the clerk runs the first-reject scan and writes the sequence's outputs and the
 //     record the extra-token kernels start from, exactly as k_accept does.
-// The streaming rate is that of k_lse (the same chunk loop, 15 waves of a compute unit on one row instead of 32 waves
-// on eight rows).  Requires nC <= kSeqMaxChunks; grid (B), kScanWG threads.
+// The chunk loop is k_lse's.  Eight streaming waves per compute unit (64 KB of loads in flight each, 16 MB over the
+// chip) is where the rate peaks: 153-156 us for the large-vocabulary batch's 1.05 GB against 157 us with 10 to 15
+// waves, 163 with 6, 180 with 4 or 5 -- and against 175 / 188 us with two / three chunks in flight per wave instead of one.
+// Requires nC <= kSeqMaxChunks; grid (B), kSeqWG threads.
 constexpr int kSeqMaxChunks = 1024;  // chunks of a target row: two tables of pairs in LDS
+constexpr int kSeqStreamWaves = 8;
+constexpr int kSeqWG = (1 + kSeqStreamWaves) * kWave;
 
 struct SeqIn {
     const int32_t *d2t, *tok_d;
@@ -35,7 +39,7 @@ struct SeqOut {
 };
 
 template <int DT>
-__global__ __launch_bounds__(kScanWG) void k_lse_accept_seq(const void* __restrict__ logits_t, DrafterView dv, int K,
+__global__ __launch_bounds__(kSeqWG) void k_lse_accept_seq(const void* __restrict__ logits_t, DrafterView dv, int K,
                                                             int Vt, int Vd, int nC, SeqIn in, float2* __restrict__ ctab,
                                                             SeqOut out) {
     constexpr int ESZ = Traits<DT>::ESZ;
@@ -69,13 +73,13 @@ __global__ __launch_bounds__(kScanWG) void k_lse_accept_seq(const void* __restri
     }
 
     for (int i = 0; i <= K; ++i) {
-        if (i < K && wave != 0) {  // waves 1..15: row (rot + i) mod K -> table i & 1; chunk c by wave 1 + c % 15
+        if (i < K && wave != 0) {  // streaming waves: row (rot + i) mod K -> table i & 1; chunk c by wave 1 + c % 8
             const int k = (rot + i) % K;
             const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) +
                                                             ((int64_t)b * (K + 1) + k) * Vt * ESZ);
             float2* buf = stash + (i & 1) * kSeqMaxChunks;
-            // (first chunk -1: the scan gives wave w the chunks first + w, first + w + 15, ...)
-            scan_chunks<DT, false, kScanWaves - 1>(rowv, Vt, -1, nC, in.cs_t, (float)(in.ratio_t - 1.0), nullptr,
+            // (first chunk -1: the scan gives wave w the chunks first + w, first + w + 8, ...)
+            scan_chunks<DT, false, kSeqStreamWaves>(rowv, Vt, -1, nC, in.cs_t, (float)(in.ratio_t - 1.0), nullptr,
                                                    [&](int c, float r, float sc) {
                                                        if (lane == 0) buf[c] = make_float2(r, sc);
                                                    });
