@@ -24,10 +24,12 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel as read by rocprofv3 (FETCH_SIZE + WRITE_SIZE, each scaled by
 # what the same counter reads for the library's plain copy kernel); from profiles/*_hbm_traffic_pmc.md.
 # Counters cannot be read from inside this process, so the figure is carried here per workload.
-MEASURED_TRAFFIC = {
-    "large_vocab": dict(bytes=1048.65e6 + 2.16e6,
-                        source="profiles/large_vocab_all_kernels_hbm_traffic_pmc.md (rocprofv3 --pmc FETCH_SIZE, then "
-                               "WRITE_SIZE, of a separate run of this command; carried here, not measured by this run)"),
+_PMC_NOTE = (" (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, of a separate run of this command, scaled by the copy "
+             "kernel's reading; carried here, not measured by this run)")
+MEASURED_TRAFFIC = {  # fetched + written bytes per launch of the dominant kernel
+    "large_vocab": dict(bytes=1049.24e6 + 2.19e6, source="profiles/large_vocab_all_kernels_hbm_traffic_pmc.md" + _PMC_NOTE),
+    "mismatch": dict(bytes=517.35e6 + 1.16e6, source="profiles/mismatch_all_kernels_hbm_traffic_pmc.md" + _PMC_NOTE),
+    "batched": dict(bytes=97.42e6 + 0.32e6, source="profiles/batched_all_kernels_hbm_traffic_pmc.md" + _PMC_NOTE),
 }
 DOMINANT_KERNEL = {  # what the library launches for the target rows' log-normalisers, by batch size
     True: "k_lse_accept_seq (log-normalisers of the K target rows of every sequence, accept tests as the rows complete)",
