@@ -210,6 +210,31 @@ def test_full_size_every_draft_accepted(oracle):
     assert not np.isnan(res["gpu_verify"]["lse_p"]).any()
 
 
+@pytest.mark.parametrize("dtype,B", [("f32", 6), ("bf16", 70)])
+def test_bonus_and_residual_rows_in_one_batch_at_full_vocabulary(oracle, dtype, B):
+    """Vt = 256000 with a mixed batch: even sequences have the target's shared logits equal to the drafter's (all K
+    drafts accepted, the extra token is a draw from row K), odd ones keep the recipe's target rows (rejected early,
+    residual draw).  fp32 with 50000 shared ids runs the residual scan in three parts, and with six sequences every
+    row -- the bonus rows too -- is split over several workgroups; bf16 with seventy sequences takes one workgroup
+    per part."""
+    w = synth.WORKLOADS[4].scaled(B=B, K=3, Vd=60000, S=50000, dtype=dtype, cfg=43)
+    inp = synth.make_inputs(w, DEV)
+    d2t = inp["d2t"]
+    d_idx = torch.from_numpy(np.nonzero(d2t >= 0)[0]).to(DEV)
+    t_idx = torch.from_numpy(d2t[d2t >= 0].astype(np.int64)).to(DEV)
+    lt, ld = inp["logits_t"], inp["logits_d"]
+    for b in range(0, B, 2):
+        lt[b, : w.K] = -100.0
+        lt[b, : w.K, t_idx] = ld[b][:, d_idx]
+    inp["u_acc"].clamp_(max=1.0 - 2.0 ** -10)
+    res = parity.run_case(oracle, inp, threads=16, chain=True)
+    _check(res)
+    n = res["ref_verify"]["n_acc"]
+    assert np.all(n[0::2] == w.K) and (n[1::2] < w.K).sum() >= (B // 2) - 3
+    assert res["verify"]["compared_tokens"] >= B - 1
+    assert not np.isnan(res["gpu_verify"]["lse_p"][0::2]).any()
+
+
 STRESS = ["scale_up", "scale_down", "neginf", "ties", "const", "onehot", "cold", "hot"]
 
 
