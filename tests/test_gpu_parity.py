@@ -350,6 +350,50 @@ def test_flags_and_edge_inputs(oracle):
     m.free()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_residual_identically_zero_is_flagged_degenerate(oracle, dtype):
+    """SD appendix, last step, with p = q' exactly and a rejected draft: the residual is identically zero and the
+    extra token is drawn from p (flag DEGENERATE).  A drafter cannot draw such a token, a caller can pass one: both
+    models put all their mass, in equal halves (or quarters), on the same ids -- sums of powers of two, so the
+    oracle's q' equals its p to the last bit -- and the draft is a shared id whose logit is -inf on both sides
+    (p(d) = q'(d) = 0: u * 0 < 0 is false).  Ids in different chunks; the last sequence is an ordinary one."""
+    V, B, K = 2048 * 3 + 16, 5, 2
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    w = synth.WORKLOADS[3].scaled(Vt=V, Vd=V, S=V, B=B, K=K, dtype=dtype, tau_t=0.5, tau_d=0.5)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(11)
+    lt = torch.full((B, K + 1, V), float("-inf"), dtype=tdt, device=DEV)
+    heavy = [[5, 4100], [2047, 2048], [0, 100, 3000, V - 1], [4099]]
+    for b, ids in enumerate(heavy):
+        lt[b, :K, ids] = 1.5
+    lt[:, K] = (torch.randn(B, V, generator=gen, device=DEV) * 2).to(tdt)
+    lt[B - 1] = (torch.randn(K + 1, V, generator=gen, device=DEV) * 2).to(tdt)
+    ld = lt[:, :K].clone()
+    d2t = np.arange(V, dtype=np.int32)
+    tok = np.full((B, K), 7, np.int32)
+    tok[1, 0] = 2047  # accepted (p/q' = 1, u < 1), then the -inf id at position 1
+    u_acc = synth._uniform24(B * K, gen, DEV).reshape(B, K).clamp_(max=0.9)
+    u_fin = synth._uniform24(B, gen, DEV)
+    m = binding.tli_build_map(d2t, V)
+    code = binding.TLI_F32 if dtype == "f32" else binding.TLI_BF16
+    ws = binding.alloc_workspace(B, K, m, code, DEV)
+    g = parity.to_host(binding.tli_verify(m, lt, ld, w.tau_t, w.tau_d, torch.from_numpy(tok).to(DEV), None,
+                                           u_acc.reshape(-1), u_fin, ws))
+    torch.cuda.synchronize()
+    rep, ref = parity.compare_verify(oracle, synth.logits_to_numpy(lt), synth.logits_to_numpy(ld), w.tau_t, w.tau_d,
+                                     d2t, tok, u_acc.cpu().numpy().astype(np.float64),
+                                     u_fin.cpu().numpy().astype(np.float64), g)
+    print(dict(rep), ref["status"], g["status"], ref["n_acc"], g["out_tok"])
+    assert rep["hard"] == 0 and rep["token_near_ties"] == 0
+    for b in range(B - 1):
+        assert ref["status"][b] == oracle.DEGENERATE and g["status"][b] == binding.FLAG_DEGENERATE, b
+        n = 1 if b == 1 else 0
+        assert ref["n_acc"][b] == n and g["n_accepted"][b] == n
+        assert g["out_tok"][b, n] == ref["out_tok"][b, n] and g["out_tok"][b, n] in heavy[b]
+    assert ref["status"][B - 1] == 0 and g["status"][B - 1] == 0
+    m.free()
+
+
 def test_verify_recomputes_missing_lse_q(oracle):
     """tli_verify with lse_q = NULL (one extra masked scan of the drafter rows) against the oracle."""
     for w in (synth.WORKLOADS[3].scaled(B=12, K=4, Vt=30000, Vd=2048 * 5 + 64, S=4000),
