@@ -3,6 +3,7 @@
 // and no HIP type: this file is also built alone with -fsanitize=address,undefined for the CPU tests.
 #include "tli_host_map.h"
 
+#include <algorithm>
 #include <cstring>
 #include <string_view>
 #include <unordered_map>
@@ -101,21 +102,66 @@ int build_host_map(const int32_t* d2t_host, int32_t Vd, int32_t Vt, HostMap& hm)
                     run += cnt;
                 }
             }
-            // pairs grouped by target chunk (ranks ascending inside a chunk): entry n of a chunk's list sits in
-            // group n / kPairG, lane n % 64, first or second of the lane's two by (n % kPairG) / 64
+            // pairs grouped by target chunk.  A group is read by a wave as two rounds of 64 two-byte (four-byte) LDS
+            // reads of the target logits and two of the staged drafter logits; LDS serves a half-wave of 32 lanes
+            // from 32 banks of 4 bytes in one pass when no two lanes want different words of one bank.  So a
+            // chunk's pairs are dealt to the half-wave slots of its groups (4 per group) one by one, the pairs from
+            // the most crowded banks first, each to the slot where it adds the fewest passes (then the fewest
+            // lanes of its two banks, then the emptiest).  Any fixed order is as good as any other for the sums.
             const uint32_t dummy = (uint32_t)(dt == TLI_BF16 ? dummy_index<TLI_BF16>() : dummy_index<TLI_F32>()) << kPairShift;
             h.pl_e[layout].assign(((size_t)h.pl_g[nC] + kPairU) * kWave, mk_u2(dummy, dummy));
-            std::vector<int32_t> nth(nC, 0);
+            std::vector<std::vector<uint32_t>> of_chunk(nC);
+            for (int c = 0; c < nC; ++c) of_chunk[c].reserve(cc[c]);
             for (int32_t r = 0; r < S; ++r) {
                 const int64_t x = layout ? r : sh_x[r];
                 const int32_t t = d2t[sh_x[r]];
                 const int c = t / CH, p = part_of_chunk[c];
                 const uint32_t w = h.stab[layout][(size_t)p * NV + x / epv];
                 const uint32_t pos = (w & 0xffffu) + (uint32_t)__builtin_popcount((w >> 16) & ((1u << (x % epv)) - 1u));
-                const uint32_t e = (uint32_t)(t % CH) * esz | (pos << kPairShift);
-                const int n = nth[c]++;
-                UInt2& slot = h.pl_e[layout][((size_t)h.pl_g[c] + n / kPairG) * kWave + n % kWave];
-                if ((n % kPairG) / kWave == 0) slot.x = e; else slot.y = e;
+                of_chunk[c].push_back((uint32_t)(t % CH) * esz | (pos << kPairShift));
+            }
+            constexpr int kBanks = 32, kHalf = kWave / 2;
+            std::vector<int32_t> order, degx(kBanks), degy(kBanks);
+            std::vector<uint8_t> cx, cy;
+            std::vector<int32_t> fill, mx, my;
+            for (int c = 0; c < nC; ++c) {
+                const std::vector<uint32_t>& es = of_chunk[c];
+                const int n = (int)es.size();
+                const int H = (h.pl_g[c + 1] - h.pl_g[c]) * (kPairG / kHalf);
+                auto bank_x = [&](uint32_t e) { return (int)(((e & 0xffffu) / 4u) % kBanks); };
+                auto bank_y = [&](uint32_t e) { return (int)(((e >> kPairShift) * esz / 4u) % kBanks); };
+                std::fill(degx.begin(), degx.end(), 0);
+                std::fill(degy.begin(), degy.end(), 0);
+                for (uint32_t e : es) { ++degx[bank_x(e)]; ++degy[bank_y(e)]; }
+                order.resize(n);
+                for (int i = 0; i < n; ++i) order[i] = i;
+                std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+                    return degx[bank_x(es[a])] + degy[bank_y(es[a])] > degx[bank_x(es[b])] + degy[bank_y(es[b])];
+                });
+                cx.assign((size_t)H * kBanks, 0);
+                cy.assign((size_t)H * kBanks, 0);
+                fill.assign(H, 0); mx.assign(H, 1); my.assign(H, 1);
+                for (int i : order) {
+                    const uint32_t e = es[i];
+                    const int bx = bank_x(e), by = bank_y(e);
+                    int best = -1;
+                    int64_t best_key = 0;
+                    for (int s = 0; s < H; ++s) {
+                        if (fill[s] >= kHalf) continue;
+                        const int nx = cx[(size_t)s * kBanks + bx] + 1, ny = cy[(size_t)s * kBanks + by] + 1;
+                        const int added = (nx > mx[s] ? nx - mx[s] : 0) + (ny > my[s] ? ny - my[s] : 0);
+                        const int64_t key = ((int64_t)added << 32) | ((int64_t)(nx + ny) << 16) | fill[s];
+                        if (best < 0 || key < best_key) { best = s; best_key = key; }
+                    }
+                    const int s = best;  // n <= 32 * H: a slot with a free lane exists
+                    const int nx = ++cx[(size_t)s * kBanks + bx], ny = ++cy[(size_t)s * kBanks + by];
+                    if (nx > mx[s]) mx[s] = nx;
+                    if (ny > my[s]) my[s] = ny;
+                    // slot s = group s / 4, the lanes' first (second) entries for s % 4 < 2 (>= 2), lanes 0..31 or 32..63
+                    const int lane = (s % 2) * kHalf + fill[s]++;
+                    UInt2& two = h.pl_e[layout][((size_t)h.pl_g[c] + s / 4) * kWave + lane];
+                    if ((s % 4) / 2 == 0) two.x = e; else two.y = e;
+                }
             }
         }
     }
