@@ -274,12 +274,21 @@ def main():
         ok = ar["status"] == 0
         next_rows["mean_alpha_tli"] = round(float(ar["alpha_tli"][ok].mean()), 4)
         next_rows["mean_alpha_union"] = round(float(ar["alpha_union"][ok].mean()), 4)
-        # top-k / top-p warp of the target rows (one lse pass + radix levels + the rewrite; bytes = rows read once)
+        # top-k / top-p warp of the target rows (sweeps for the thresholds + the rewrite; bytes = rows read once)
         warped = torch.empty_like(inp["logits_t"]).reshape(rows_t, w.Vt)
         lt_rows = inp["logits_t"].reshape(rows_t, w.Vt)
         timed("warp_rows_top_k50_top_p0.9", lambda: binding.tli_warp_rows(lt_rows, w.tau_t, 50, 0.9, out=warped),
               rows_t * w.Vt * esz)
         del warped
+        wws = torch.empty(int(binding.load_library().tli_warp_workspace_bytes(rows_t, w.Vt, code)), dtype=torch.uint8,
+                          device=dev)
+        timed("warp_thresholds_top_k50_top_p0.9", lambda: binding.tli_warp_rows(lt_rows, w.tau_t, 50, 0.9, rewrite=False,
+                                                                               workspace=wws),
+              rows_t * w.Vt * esz)
+        timed("warp_thresholds_top_k50", lambda: binding.tli_warp_rows(lt_rows, w.tau_t, 50, 1.0, rewrite=False,
+                                                                      workspace=wws), rows_t * w.Vt * esz)
+        timed("warp_thresholds_top_p0.9", lambda: binding.tli_warp_rows(lt_rows, w.tau_t, 0, 0.9, rewrite=False,
+                                                                       workspace=wws), rows_t * w.Vt * esz)
         # compact drafter layout: rows hold only the shared tokens' logits (a head pruned to the intersection)
         sh_x = torch.from_numpy(np.nonzero(inp["d2t"] >= 0)[0]).to(dev)
         epv = 16 // esz

@@ -416,25 +416,30 @@ def tli_sample_rows(logits: torch.Tensor, temp: float, u: torch.Tensor | None, w
 
 
 def tli_warp_rows(logits: torch.Tensor, temp: float, top_k: int, top_p: float, m: TliMap | None = None,
-                  out: torch.Tensor | None = None, workspace: torch.Tensor | None = None, stream=None) -> dict:
+                  out: torch.Tensor | None = None, workspace: torch.Tensor | None = None, stream=None,
+                  rewrite: bool = True) -> dict:
     """top-k / top-p on rows logits [R, V]: returns the warped rows (dropped = -inf; `out` may be `logits` itself),
-    thr, kept, status.  With a map only the shared drafter ids compete."""
+    thr, kept, status.  With a map only the shared drafter ids compete.  rewrite=False: thresholds and status only
+    (thr = the lowest value kept, -inf if no warper is active for the row)."""
     lib = load_library()
     assert logits.is_cuda and logits.dim() == 2 and logits.stride(-1) == 1
     R, V = logits.shape
     code = _dtype_code(logits)
-    if out is None:  # rows start on 16-byte boundaries: the row stride is V rounded up to whole vectors
-        epv = 16 // logits.element_size()
-        out = torch.empty((R, (V + epv - 1) // epv * epv), dtype=logits.dtype, device=logits.device)[:, :V]
-    assert out.shape == logits.shape and out.dtype == logits.dtype and out.stride(-1) == 1
-    if workspace is None:
-        workspace = torch.empty(int(lib.tli_warp_workspace_bytes(R, V, code)), dtype=torch.uint8, device=logits.device)
     dev = logits.device
-    res = dict(logits=out, thr=torch.empty(R, dtype=torch.float32, device=dev),
-               kept=torch.empty(R, dtype=torch.int32, device=dev), status=torch.empty(R, dtype=torch.int32, device=dev))
+    if workspace is None:
+        workspace = torch.empty(int(lib.tli_warp_workspace_bytes(R, V, code)), dtype=torch.uint8, device=dev)
+    res = dict(thr=torch.empty(R, dtype=torch.float32, device=dev), status=torch.empty(R, dtype=torch.int32, device=dev))
+    if rewrite:
+        if out is None:  # rows start on 16-byte boundaries: the row stride is V rounded up to whole vectors
+            epv = 16 // logits.element_size()
+            out = torch.empty((R, (V + epv - 1) // epv * epv), dtype=logits.dtype, device=dev)[:, :V]
+        assert out.shape == logits.shape and out.dtype == logits.dtype and out.stride(-1) == 1
+        res["logits"] = out
+        res["kept"] = torch.empty(R, dtype=torch.int32, device=dev)
     rc = lib.tli_warp_rows(None if m is None else m.handle, _ptr(logits), code, logits.stride(0), R, V, float(temp),
-                           int(top_k), float(top_p), _ptr(out), out.stride(0), _ptr(res["thr"]), _ptr(res["kept"]),
-                           _ptr(res["status"]), _ptr(workspace), workspace.numel(), _stream(stream))
+                           int(top_k), float(top_p), _ptr(out) if rewrite else None, out.stride(0) if rewrite else 0,
+                           _ptr(res["thr"]), _ptr(res.get("kept")), _ptr(res["status"]), _ptr(workspace),
+                           workspace.numel(), _stream(stream))
     if rc != 0:
         raise TliError(rc, "tli_warp_rows")
     return res

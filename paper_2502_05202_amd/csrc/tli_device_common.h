@@ -174,6 +174,26 @@ __device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane
     s_out = wave_sum(s);
 }
 
+// reduce_chunk's arithmetic on values that are already unpacked (and masked): for kernels that look at the values
+// themselves as well
+template <int N>
+__device__ __forceinline__ void reduce_values(const float* x, float cs, float dl, float& ref_out, float& s_out) {
+    float m = x[0];
+#pragma unroll
+    for (int i = 1; i < N; ++i) m = fmaxf(m, x[i]);
+    const float ref = m * cs;
+    const float nref = (m == -INFINITY) ? 0.f : -ref;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[i & 3] += exp2_hw(fmaf(x[i], cs, nref));
+    float s = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    const float R = ceilf(wave_max(ref));
+    const float e = ref - R;
+    s = (m == -INFINITY) ? 0.f : s * exp2_hw(fmaf(e, dl, e));
+    ref_out = R;
+    s_out = wave_sum(s);
+}
+
 // The same reduction for two sums at once -- over every id of the chunk (s_all) and over the shared ids only
 // (s_sh) -- with one exponential per logit: both are formed against the lane's maximum over ALL its ids and leave
 // with the chunk reference of the full sum.  That is only as accurate as a reduction of the shared ids alone while

@@ -791,49 +791,55 @@ int tli_acceptance_rates(const tli_map* map, const void* logits_t, const void* l
 
 size_t tli_warp_workspace_bytes(int32_t R, int32_t V, tli_dtype dtype) {
     if (R < 1 || R > 0x7fffffff / 64 || !vocab_ok(V) || (dtype != TLI_F32 && dtype != TLI_BF16)) return 0;
-    const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
-    const Plan pl = make_plan(V, R, chunk);
-    return align256((size_t)R * pl.nsplit * sizeof(Part)) + align256((size_t)R * sizeof(WarpRow));
+    return align256((size_t)R * sizeof(WarpRow));
 }
 
 int tli_warp_rows(const tli_map* map, const void* logits, tli_dtype dtype, int64_t row_stride_elems, int32_t R, int32_t V,
                   float temp, int32_t top_k, float top_p, void* logits_out, int64_t out_stride_elems, float* thr,
                   int32_t* kept, int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (!logits || !logits_out || !row_status || !workspace) return TLI_ERR_INVALID_ARG;
+    if (!logits || !row_status || !workspace) return TLI_ERR_INVALID_ARG;
+    if (!logits_out && (kept || !thr)) return TLI_ERR_INVALID_ARG;  // thresholds only: they are the result
     if (R < 1 || R > 0x7fffffff / 64 || !vocab_ok(V) || !(temp > 0.f) || !std::isfinite(temp)) return TLI_ERR_INVALID_ARG;
     if (!(top_p > 0.f) || (map && V != map->Vd)) return TLI_ERR_INVALID_ARG;
     if (dtype != TLI_F32 && dtype != TLI_BF16) return TLI_ERR_INVALID_ARG;
     const int epv = dtype == TLI_BF16 ? 8 : 4;
-    if (row_stride_elems < V || row_stride_elems % epv != 0 || out_stride_elems < V || out_stride_elems % epv != 0 ||
-        !aligned16(logits) || !aligned16(logits_out) || !aligned16(workspace))
+    if (row_stride_elems < V || row_stride_elems % epv != 0 || !aligned16(logits) || !aligned16(workspace))
+        return TLI_ERR_INVALID_ARG;
+    if (logits_out && (out_stride_elems < V || out_stride_elems % epv != 0 || !aligned16(logits_out)))
         return TLI_ERR_INVALID_ARG;
     if (workspace_bytes < tli_warp_workspace_bytes(R, V, dtype)) return TLI_ERR_ALLOC;
     const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
-    const Plan pl = make_plan(V, R, chunk);
-    Part* part = reinterpret_cast<Part*>(workspace);
-    WarpRow* st = reinterpret_cast<WarpRow*>(static_cast<char*>(workspace) + align256((size_t)R * pl.nsplit * sizeof(Part)));
+    const int nC = (V + chunk - 1) / chunk;
+    WarpRow* st = reinterpret_cast<WarpRow*>(workspace);
     const double c_true = kLog2e / (double)temp;
     const float cs = (float)c_true;
     const double ratio = c_true / (double)cs;
     const int use_p = top_p < 1.f ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const dim3 rows_grid(R), lse_grid((unsigned)R * pl.nsplit);
+    const dim3 rows_grid(R);
+    // One sweep of the rows per launch: the normaliser with top-k's first digit; top-k's middle digit (three-digit
+    // keys); top-k's last digit with the start of top-p; what is left of top-p (rows that have nothing left to
+    // decide at a level leave at once); the rewrite, if asked for.
 #define TLI_WARP_RUN(DT, MASKED, BITS)                                                                                   \
     do {                                                                                                                  \
-        hipLaunchKernelGGL((k_lse<DT, MASKED>), lse_grid, dim3(kWG), lse_shmem(pl), s, logits, 1, row_stride_elems, row_stride_elems, \
-                           V, pl.nC, pl.cps, pl.nsplit, cs, ratio, BITS, part, (float2*)nullptr);                        \
-        hipLaunchKernelGGL(k_warp_init, dim3((R + kWG - 1) / kWG), dim3(kWG), 0, s, part, pl.nsplit, ratio, R, top_k,     \
-                           use_p, st);                                                                                    \
-        if (top_k > 0)                                                                                                    \
-            for (int level = 0; level < WarpKey<DT>::LEVELS; ++level)                                                     \
+        hipLaunchKernelGGL((k_warp_first<DT, MASKED>), rows_grid, dim3(kWG), 0, s, logits, row_stride_elems, V, nC, cs,   \
+                           ratio, BITS, top_k, use_p, st);                                                                \
+        if (top_k > 0) {                                                                                                  \
+            for (int level = 1; level < WarpKey<DT>::LEVELS - 1; ++level)                                                 \
                 hipLaunchKernelGGL((k_warp_level<DT, MASKED, 0>), rows_grid, dim3(kWG), 0, s, logits, row_stride_elems,   \
-                                   V, pl.nC, level, top_p, c_true, BITS, st);                                             \
+                                   V, nC, level, top_p, c_true, BITS, st);                                                \
+            hipLaunchKernelGGL((k_warp_klast<DT, MASKED>), rows_grid, dim3(kWG), 0, s, logits, row_stride_elems, V, nC,   \
+                               top_p, c_true, BITS, st);                                                                  \
+        }                                                                                                                 \
         if (use_p)                                                                                                        \
             for (int level = 0; level < WarpKey<DT>::LEVELS; ++level)                                                     \
                 hipLaunchKernelGGL((k_warp_level<DT, MASKED, 1>), rows_grid, dim3(kWG), 0, s, logits, row_stride_elems,   \
-                                   V, pl.nC, level, top_p, c_true, BITS, st);                                             \
-        hipLaunchKernelGGL((k_warp_apply<DT, MASKED>), rows_grid, dim3(kWG), 0, s, logits, row_stride_elems, V, pl.nC,    \
-                           BITS, st, logits_out, out_stride_elems, thr, kept, row_status);                                \
+                                   V, nC, level, top_p, c_true, BITS, st);                                                \
+        if (logits_out)                                                                                                   \
+            hipLaunchKernelGGL((k_warp_apply<DT, MASKED>), rows_grid, dim3(kWG), 0, s, logits, row_stride_elems, V, nC,   \
+                               BITS, st, logits_out, out_stride_elems, thr, kept, row_status);                            \
+        else                                                                                                              \
+            hipLaunchKernelGGL(k_warp_finish<DT>, dim3((R + kWG - 1) / kWG), dim3(kWG), 0, s, st, R, thr, row_status);    \
     } while (0)
     if (map) {
         if (dtype == TLI_BF16) TLI_WARP_RUN(TLI_BF16, true, map->lmask[TLI_BF16]);

@@ -315,7 +315,13 @@ __global__ __launch_bounds__(kWave) void k_match(const int32_t* __restrict__ tgt
 // point so that sums do not depend on the order of arrival) -- and then picks the digit in which the
 // threshold lies.  Logits crowd into a handful of leading digits (sign and exponent), so the lanes of a wave
 // would queue on the same few LDS words: the histogram is kept in several interleaved copies, one per lane
-// group, and folded after the scan.  A last pass writes the rows with every dropped logit set to -inf.
+// group, and folded after the scan.  A last pass writes the rows with every dropped logit set to -inf (or only
+// the thresholds are returned).
+// Passes that can share a sweep of the rows do: the first digit of top-k is counted while the row's normaliser
+// is formed (k_warp_first), and the sweep for top-k's last digit also gathers what top-p needs to start among
+// the survivors -- their mass per first digit -- so that top-p's first digit (and, for two-digit keys, its second
+// whenever it falls in top-k's own bin) is decided there too (k_warp_klast).  Top-k 50 + top-p 0.9 on bf16 rows
+// is then two sweeps and the rewrite instead of six.
 constexpr int kWarpBinsMax = 2048;
 constexpr double kMassScale = 281474976710656.0;  // 2^48
 template <int DT> struct WarpKey;
@@ -357,15 +363,59 @@ struct WarpRow {
     uint32_t pprefix;     // same for the top-p threshold
     uint32_t k_rem;       // the threshold is the k_rem-th largest key below the prefix
     int32_t k_on, p_on;   // the warper is active for this row (top-k turns itself off when k >= competing ids)
+    int32_t p_level;      // the next digit top-p has to decide (LEVELS: it is through)
     int32_t status;
 };
 
-// kernel: start the per-row state from the row normalisers.  grid (ceil(R / 256)).
-__global__ __launch_bounds__(kWG) void k_warp_init(const Part* __restrict__ part, int nsplit, double ratio, int R,
-                                                    int top_k, int use_p, WarpRow* __restrict__ st) {
-    const int r = blockIdx.x * kWG + threadIdx.x;
-    if (r >= R) return;
-    const double lse = combine_parts(part + (int64_t)r * nsplit, nsplit, ratio);
+// kernel: the row's normaliser, the start of its state, and -- with top-k on -- the first digit of top-k's
+// threshold, from one sweep of the row.  grid (R), 256 threads.
+template <int DT, bool MASKED>
+__global__ __launch_bounds__(kWG) void k_warp_first(const void* __restrict__ logits, int64_t row_stride, int V, int nC,
+                                                     float cs, double ratio, const uint64_t* __restrict__ bits,
+                                                     int top_k, int use_p, WarpRow* __restrict__ st) {
+    constexpr int EPV = Traits<DT>::EPV;
+    constexpr int N = EPV * kLoads;
+    constexpr int COPIES = WarpKey<DT>::COPIES;
+    constexpr int nbits = WarpKey<DT>::bits(0), shift = WarpKey<DT>::shift(0), nbins = 1 << nbits;
+    const int row = blockIdx.x;
+    __shared__ uint32_t cnt_c[WarpKey<DT>::BINS * COPIES];
+    const bool count = top_k > 0;
+    if (count)
+        for (int i = threadIdx.x; i < nbins * COPIES; i += kWG) cnt_c[i] = 0u;
+    __syncthreads();
+    const int copy = threadIdx.x & (COPIES - 1);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const double kd = (ratio - 1.0) * kLn2;
+    const float dl = (float)(ratio - 1.0);
+    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ);
+    Running run;
+    stream_chunks<DT, kWaves>(rowv, V, 0, nC, [&](const ChunkRegs& r, int c, auto whole) {
+        float x[N];
+        chunk_values<DT, MASKED, decltype(whole)::value>(r, c, lane, V, bits, x);
+        float ref, sum;
+        reduce_values<N>(x, cs, dl, ref, sum);
+        run.add(ref, sum, kd);
+        if (count) {
+#pragma unroll
+            for (int i = 0; i < N; ++i)
+                if (x[i] > -INFINITY)
+                    atomicAdd(&cnt_c[((warp_key<DT>(x[i]) >> shift) & (uint32_t)(nbins - 1)) * COPIES + copy], 1u);
+        }
+    });
+    __shared__ Part sp[kWaves];
+    __shared__ uint32_t cnt[WarpKey<DT>::BINS];
+    if (lane == 0) { sp[wave].ref = run.ref; sp[wave].pad = 0.f; sp[wave].s = run.s; }
+    __syncthreads();
+    if (count)
+        for (int i = threadIdx.x; i < nbins; i += kWG) {  // fold the copies
+            uint32_t c = 0;
+#pragma unroll
+            for (int k = 0; k < COPIES; ++k) c += cnt_c[i * COPIES + k];
+            cnt[i] = c;
+        }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    const double lse = combine_parts(sp, kWaves, ratio);
     WarpRow w;
     w.l2 = lse * kLog2e;
     w.zk = 0; w.p_above = 0; w.target = 0; w.kprefix = 0; w.pprefix = 0;
@@ -373,7 +423,23 @@ __global__ __launch_bounds__(kWG) void k_warp_init(const Part* __restrict__ part
     w.status = lse != lse ? TLI_FLAG_NONFINITE : (lse == -INFINITY ? TLI_FLAG_ZERO_MASS : 0);
     w.k_on = (top_k > 0 && !w.status) ? 1 : 0;
     w.p_on = (use_p && !w.status) ? 1 : 0;
-    st[r] = w;
+    w.p_level = 0;
+    if (w.k_on) {
+        // no more competing ids than k: top-k drops nothing and turns itself off; else the digit d with
+        // #above(d) < k <= #above(d) + cnt[d], from the top
+        uint32_t total = 0;
+        for (int d = 0; d < nbins; ++d) total += cnt[d];
+        if (total <= w.k_rem) {
+            w.k_on = 0;
+        } else {
+            uint32_t ac = 0;
+            int d = nbins - 1;
+            while (ac + cnt[d] < w.k_rem) ac += cnt[d--];  // ends: the total exceeds k
+            w.kprefix = (uint32_t)d;
+            w.k_rem -= ac;
+        }
+    }
+    st[row] = w;
 }
 
 // kernel: one level of the radix descent.  MODE 0: top-k (counts, and the mass that survives); MODE 1: top-p.
@@ -386,7 +452,7 @@ __global__ __launch_bounds__(kWG) void k_warp_level(const void* __restrict__ log
     constexpr int N = EPV * kLoads;
     const int row = blockIdx.x;
     WarpRow w = st[row];
-    if (MODE == 0 ? !w.k_on : !w.p_on) return;
+    if (MODE == 0 ? !w.k_on : (!w.p_on || w.p_level != level)) return;
     const int nbits = WarpKey<DT>::bits(level), shift = WarpKey<DT>::shift(level), nbins = 1 << nbits;
     const uint32_t prefix = MODE == 0 ? w.kprefix : w.pprefix;
     constexpr int COPIES = WarpKey<DT>::COPIES;
@@ -503,7 +569,142 @@ __global__ __launch_bounds__(kWG) void k_warp_level(const void* __restrict__ log
             o.pprefix = (prefix << nbits) | (uint32_t)found;
             o.p_above = found_am;
         }
+        if (t == 0) st[row].p_level = level + 1;
     }
+}
+
+// kernel: the last digit of top-k's threshold and, from the same sweep, the start of top-p among the survivors.
+// Beside the counts of the last digit under top-k's prefix the sweep gathers the mass per FIRST digit of the elements
+// above the prefix whose first digit is larger than the prefix's, and the mass of the rest above the prefix
+// (three-digit keys only); those elements are fewer than k, so their histogram needs no copies and the branch that
+// forms a mass is rarely taken.  The elements under the prefix need none formed one by one: a last digit fixes the
+// whole key, so the mass of a bin is its count times the mass of that one value.  Once the threshold is known these
+// give the mass that survives top-k, top-p's target, its first digit, and -- for two-digit keys, when that digit is
+// top-k's own -- its second.  grid (R), 256 threads.
+template <int DT, bool MASKED>
+__global__ __launch_bounds__(kWG) void k_warp_klast(const void* __restrict__ logits, int64_t row_stride, int V, int nC,
+                                                     float top_p, double c_true, const uint64_t* __restrict__ bits,
+                                                     WarpRow* __restrict__ st) {
+    constexpr int EPV = Traits<DT>::EPV;
+    constexpr int N = EPV * kLoads;
+    constexpr int L = WarpKey<DT>::LEVELS, level = L - 1;
+    constexpr int nbits = WarpKey<DT>::bits(level), nbins = 1 << nbits;  // the last digit sits at shift 0
+    constexpr int nbits0 = WarpKey<DT>::bits(0), shift0 = WarpKey<DT>::shift(0), nbins0 = 1 << nbits0;
+    constexpr int COPIES = WarpKey<DT>::COPIES;
+    const int row = blockIdx.x;
+    const WarpRow w = st[row];
+    if (!w.k_on) return;
+    const uint32_t prefix = w.kprefix;                        // the digits above the last
+    const uint32_t k0 = prefix >> (shift0 - nbits);           // the first of them
+    const bool use_p = w.p_on != 0;
+    __shared__ uint32_t cnt_c[nbins * COPIES];
+    __shared__ uint32_t cnt[nbins];
+    __shared__ unsigned long long mass[nbins];
+    __shared__ unsigned long long mass0[nbins0];
+    __shared__ unsigned long long mid;
+    for (int i = threadIdx.x; i < nbins * COPIES; i += kWG) cnt_c[i] = 0u;
+    for (int i = threadIdx.x; i < nbins0; i += kWG) mass0[i] = 0ull;
+    if (threadIdx.x == 0) mid = 0ull;
+    __syncthreads();
+    const int copy = threadIdx.x & (COPIES - 1);
+    const int lane = threadIdx.x & 63;
+    float ch, cl, lh, ll;
+    split_scale(c_true, ch, cl);
+    split_hi_lo(w.l2, lh, ll);
+    unsigned long long mid_mine = 0ull;
+    const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ);
+    stream_chunks<DT, kWaves>(rowv, V, 0, nC, [&](const ChunkRegs& r, int c, auto whole) {
+        float x[N];
+        chunk_values<DT, MASKED, decltype(whole)::value>(r, c, lane, V, bits, x);
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            if (!(x[i] > -INFINITY)) continue;
+            const uint32_t key = warp_key<DT>(x[i]);
+            const uint32_t hp = key >> nbits;
+            if (hp < prefix) continue;  // below the threshold whatever its last digit is
+            if (hp == prefix) {
+                atomicAdd(&cnt_c[(key & (uint32_t)(nbins - 1)) * COPIES + copy], 1u);
+            } else if (use_p) {  // above the threshold: a survivor
+                const unsigned long long fx = (unsigned long long)((double)exp2_split(x[i], ch, cl, lh, ll) * kMassScale);
+                const uint32_t d0 = key >> shift0;
+                if (d0 > k0) atomicAdd(&mass0[d0], fx);
+                else mid_mine += fx;
+            }
+        }
+    });
+    if (L > 2 && use_p) {
+#pragma unroll
+        for (int dd = 1; dd < kWave; dd <<= 1) mid_mine += __shfl_xor(mid_mine, dd, kWave);
+        if (lane == 0 && mid_mine) atomicAdd(&mid, mid_mine);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nbins; i += kWG) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int k = 0; k < COPIES; ++k) c += cnt_c[i * COPIES + k];
+        cnt[i] = c;
+        unsigned long long m = 0ull;
+        if (use_p && c) {  // every element of the bin has the key (prefix, i): c equal masses
+            const float xv = warp_unkey<DT>((prefix << nbits) | (uint32_t)i);
+            m = (unsigned long long)c * (unsigned long long)((double)exp2_split(xv, ch, cl, lh, ll) * kMassScale);
+        }
+        mass[i] = m;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    // top-k: the last digit.  At least k_rem elements lie under the prefix (that is how the prefix was chosen).
+    uint32_t ac = 0;
+    int dk = nbins - 1;
+    while (dk > 0 && ac + cnt[dk] < w.k_rem) ac += cnt[dk--];
+    WarpRow o = w;
+    o.kprefix = (prefix << nbits) | (uint32_t)dk;
+    o.k_rem = w.k_rem - ac;
+    if (use_p) {
+        unsigned long long surv = 0ull, above0 = 0ull;
+        for (int d = nbins - 1; d >= dk; --d) surv += mass[d];
+        for (int d0 = nbins0 - 1; d0 > (int)k0; --d0) above0 += mass0[d0];
+        const unsigned long long here = mid + surv;  // the survivors whose first digit is top-k's
+        o.zk = above0 + here;
+        o.target = (unsigned long long)((double)top_p * (double)o.zk);
+        // top-p's first digit: the lowest one with mass whose strictly-above mass is still below the target
+        unsigned long long am = 0ull, found_am = 0ull;
+        int found = -1;
+        for (int d0 = nbins0 - 1; d0 > (int)k0; --d0) {
+            if (mass0[d0] > 0ull && am < o.target) { found = d0; found_am = am; }
+            am += mass0[d0];
+        }
+        if (here > 0ull && am < o.target) { found = (int)k0; found_am = am; }
+        if (found < 0) {  // no survivor carries mass at this resolution: top-p has nothing to decide
+            o.pprefix = 0u; o.p_above = 0ull; o.p_level = L;
+        } else if (found > (int)k0 || L > 2) {
+            o.pprefix = (uint32_t)found; o.p_above = found_am; o.p_level = 1;
+        } else {  // two-digit keys, top-k's own first digit: the survivors there are the digits >= dk counted above
+            unsigned long long am1 = found_am, f1_am = found_am;
+            int f1 = dk;
+            for (int d = nbins - 1; d >= dk; --d) {
+                if (mass[d] > 0ull && am1 < o.target) { f1 = d; f1_am = am1; }
+                am1 += mass[d];
+            }
+            o.pprefix = (k0 << nbits) | (uint32_t)f1; o.p_above = f1_am; o.p_level = L;
+        }
+    }
+    st[row] = o;
+}
+
+// kernel: thresholds and flags without the rewrite.  The threshold is the lowest value that is kept: top-p's if it
+// lies above top-k's, else top-k's, else -inf (no warper active for the row).  grid (ceil(R / 256)).
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_warp_finish(const WarpRow* __restrict__ st, int R, float* __restrict__ thr,
+                                                      int32_t* __restrict__ status) {
+    const int r = blockIdx.x * kWG + threadIdx.x;
+    if (r >= R) return;
+    const WarpRow w = st[r];
+    uint32_t tkey = 0;
+    bool any = false;
+    if (w.k_on) { tkey = w.kprefix; any = true; }
+    if (w.p_on && (!any || w.pprefix > tkey)) { tkey = w.pprefix; any = true; }
+    if (thr) thr[r] = w.status ? NAN : (any ? warp_unkey<DT>(tkey) : -INFINITY);
+    status[r] = w.status;
 }
 
 // kernel: write the warped rows (dropped logits = -inf), thresholds and survivor counts.  grid (R), 256 threads.

@@ -433,6 +433,24 @@ def _check_warp(oracle, view, rows, tau, top_k, top_p, d2t, m, pick=None):
             assert np.array_equal(out[r].view(np.uint32), want.view(np.uint32)) or np.array_equal(out[r], want)
         else:
             assert np.array_equal(out[r], want)
+    # thresholds only (no rewrite): the rows at or above the threshold are the oracle's kept set
+    g2 = binding.tli_warp_rows(view, tau, top_k, top_p, m=m, rewrite=False)
+    torch.cuda.synchronize()
+    if pick is not None:
+        g2 = {k: v[at] for k, v in g2.items()}
+    t2 = g2["thr"].cpu().numpy().astype(np.float64)
+    assert np.array_equal(g2["status"].cpu().numpy(), ref["status"])
+    fl = (rows.astype(np.uint32) << 16).view(np.float32) if rows.dtype == np.uint16 else rows
+    competes = fl > -np.inf
+    if d2t is not None:
+        competes &= (np.asarray(d2t) >= 0)[None, :]
+    for r in range(rows.shape[0]):
+        if ref["status"][r]:
+            assert np.isnan(t2[r])
+            continue
+        if gk[r] != ref["kept"][r]:
+            continue  # the near-tie rows counted above
+        assert np.array_equal(competes[r] & (fl[r] >= t2[r]), ref["keep_mask"][r].astype(bool)), (r, t2[r], gt[r])
     return near
 
 
