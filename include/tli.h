@@ -283,19 +283,40 @@ int tli_exact_match_verify(const void* logits_t, tli_dtype dtype, int32_t B, int
  *   top_p < 1 : on what survived top-k (renormalised at `temp`), keep x iff the probability mass of the strictly
  *               larger logits is < top_p (the smallest top set reaching top_p; the largest logit always survives).
  * logits_out receives the rows with every dropped logit set to -inf (same dtype; it may alias `logits`), so every
- * other entry point runs unchanged on warped rows.  With a map only the shared drafter ids compete (V must be Vd)
+ * other entry point runs unchanged on warped rows.  logits_out = NULL (then kept must be NULL and thr must not):
+ * no rewrite, only the thresholds -- thr is then the lowest value kept (-inf if no warper is active for the row) --
+ * for tli_sample_rows_warped / tli_draft_sample_warped, which read the rows as they are.  With a map only the shared drafter ids compete (V must be Vd)
  * and unshared ids are dropped: the warped adjusted drafter of the intersection algorithm.
  *   logits dev [R rows, row_stride_elems apart, V valid], logits_out dev [R rows, out_stride_elems apart]
  *   thr dev [R] fp32: the threshold (-inf if nothing was dropped, NaN if the row is flagged); may be NULL
  *   kept dev [R] int32: number of surviving ids; may be NULL.  row_status dev [R]: NONFINITE / ZERO_MASS (such rows
  *   come out all -inf).
- * One workgroup per row and one pass over the rows per radix level: built for batches, not tuned for few rows.
+ * One workgroup per row; top-k 50 + top-p 0.9 on two-digit (bf16) keys takes two sweeps of the rows and the
+ * rewrite: built for batches, not tuned for few rows.
  */
 size_t tli_warp_workspace_bytes(int32_t R, int32_t V, tli_dtype dtype);
 int tli_warp_rows(const tli_map* map, const void* logits, tli_dtype dtype, int64_t row_stride_elems, int32_t R,
                   int32_t V, float temp, int32_t top_k, float top_p, void* logits_out, int64_t out_stride_elems,
                   float* thr, int32_t* kept, int32_t* row_status, void* workspace, size_t workspace_bytes,
                   void* hip_stream);
+
+/*
+ * The same draws on rows that are warped by threshold instead of rewritten: only the logits >= thr[row] take part
+ * (thr from tli_warp_rows with logits_out = NULL, on the same rows, at the same temperature; -inf = the row as it
+ * is).  tli_sample_rows_warped is tli_sample_rows (temp > 0), tli_draft_sample_warped is tli_draft_sample (the
+ * warped adjusted drafter: thr from tli_warp_rows with the map); p_tok / q_tok and lse are those of the warped,
+ * renormalised distribution.  A row whose thr is NaN was flagged by the warp and is flagged here again.
+ *   thr dev [R] fp32, entry of row r at index r * io_stride like the other per-row arrays.
+ * Everything else as in the plain calls, the scratch included.
+ */
+int tli_sample_rows_warped(const void* logits, tli_dtype dtype, int64_t row_stride_elems, int32_t R, int32_t V, float temp,
+                           const float* thr, const float* u, int32_t* tok, double* p_tok, double* lse,
+                           int32_t* row_status, int64_t io_stride, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+int tli_draft_sample_warped(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems,
+                            int32_t R, float temp_d, const float* thr, const float* u_draft, int32_t* tok_d,
+                            int32_t* tok_t, double* q_tok, double* lse_q, int32_t* row_status, int64_t io_stride,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Human-readable name of a tli_status value. */
 const char* tli_status_string(int status);

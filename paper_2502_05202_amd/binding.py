@@ -26,7 +26,7 @@ EXPORTS = (
     "tli_exact_match_verify", "tli_draft_sample_compact", "tli_verify_compact",
     "tli_warp_workspace_bytes", "tli_warp_rows", "tli_map_dry_run", "tli_calib_read", "tli_device_info",
     "tli_d2t_from_strings", "tli_verify_static", "tli_verify_static_max_bytes",
-    "tli_tune_final_path",
+    "tli_tune_final_path", "tli_sample_rows_warped", "tli_draft_sample_warped",
 )
 KERNELS = ("lse", "accept", "final_scan", "final_pick", "draft_scan", "draft_pick")
 
@@ -92,6 +92,12 @@ def load_library() -> ctypes.CDLL:
     lib.tli_sample_rows_workspace_bytes.restype = ctypes.c_size_t
     lib.tli_sample_rows.argtypes = [vp, ctypes.c_int, i64, i32, i32, f32, vp, vp, vp, vp, vp, i64, vp, ctypes.c_size_t, vp]
     lib.tli_sample_rows.restype = ctypes.c_int
+    lib.tli_sample_rows_warped.argtypes = [vp, ctypes.c_int, i64, i32, i32, f32, vp, vp, vp, vp, vp, vp, i64, vp,
+                                           ctypes.c_size_t, vp]
+    lib.tli_sample_rows_warped.restype = ctypes.c_int
+    lib.tli_draft_sample_warped.argtypes = [vp, vp, ctypes.c_int, i64, i32, f32, vp, vp, vp, vp, vp, vp, vp, i64, vp,
+                                            ctypes.c_size_t, vp]
+    lib.tli_draft_sample_warped.restype = ctypes.c_int
     lib.tli_greedy_draft.argtypes = [vp, vp, ctypes.c_int, i64, i32, vp, vp, vp, i64, vp, ctypes.c_size_t, vp]
     lib.tli_greedy_draft.restype = ctypes.c_int
     lib.tli_exact_match_workspace_bytes.argtypes = [i32, i32, i32, ctypes.c_int]
@@ -396,8 +402,9 @@ def tli_acceptance_rates(m: TliMap, logits_t: torch.Tensor, logits_d: torch.Tens
 
 
 def tli_sample_rows(logits: torch.Tensor, temp: float, u: torch.Tensor | None, workspace: torch.Tensor | None = None,
-                    stream=None) -> dict:
-    """One token per row of logits [R, V] (contiguous last dim): softmax draw, or argmax at temp == 0."""
+                    stream=None, thr: torch.Tensor | None = None) -> dict:
+    """One token per row of logits [R, V] (contiguous last dim): softmax draw, or argmax at temp == 0.
+    thr [R] fp32: the rows warped by threshold (tli_sample_rows_warped; temp > 0)."""
     lib = load_library()
     assert logits.is_cuda and logits.dim() == 2 and logits.stride(-1) == 1
     R, V = logits.shape
@@ -407,11 +414,39 @@ def tli_sample_rows(logits: torch.Tensor, temp: float, u: torch.Tensor | None, w
     dev = logits.device
     out = dict(tok=torch.empty(R, dtype=torch.int32, device=dev), p_tok=torch.empty(R, dtype=torch.float64, device=dev),
                lse=torch.empty(R, dtype=torch.float64, device=dev), status=torch.empty(R, dtype=torch.int32, device=dev))
-    rc = lib.tli_sample_rows(_ptr(logits), code, logits.stride(0), R, V, float(temp), _ptr(u), _ptr(out["tok"]),
-                             _ptr(out["p_tok"]), _ptr(out["lse"]), _ptr(out["status"]), 1, _ptr(workspace),
-                             workspace.numel(), _stream(stream))
+    if thr is not None:
+        assert thr.dtype == torch.float32 and thr.numel() == R and thr.is_contiguous()
+        rc = lib.tli_sample_rows_warped(_ptr(logits), code, logits.stride(0), R, V, float(temp), _ptr(thr), _ptr(u),
+                                        _ptr(out["tok"]), _ptr(out["p_tok"]), _ptr(out["lse"]), _ptr(out["status"]), 1,
+                                        _ptr(workspace), workspace.numel(), _stream(stream))
+    else:
+        rc = lib.tli_sample_rows(_ptr(logits), code, logits.stride(0), R, V, float(temp), _ptr(u), _ptr(out["tok"]),
+                                 _ptr(out["p_tok"]), _ptr(out["lse"]), _ptr(out["status"]), 1, _ptr(workspace),
+                                 workspace.numel(), _stream(stream))
     if rc != 0:
         raise TliError(rc, "tli_sample_rows")
+    return out
+
+
+def tli_draft_sample_warped(m: TliMap, logits_d: torch.Tensor, temp_d: float, thr: torch.Tensor, u_draft: torch.Tensor,
+                            workspace: torch.Tensor, stream=None) -> dict:
+    """tli_draft_sample on rows logits_d [R, Vd] warped by the thresholds thr [R] (from tli_warp_rows(..., m=m,
+    rewrite=False) on the same rows)."""
+    lib = load_library()
+    assert logits_d.is_cuda and logits_d.dim() == 2 and logits_d.stride(-1) == 1 and logits_d.shape[1] == m.Vd
+    R = logits_d.shape[0]
+    assert thr.dtype == torch.float32 and thr.numel() == R and thr.is_contiguous()
+    assert u_draft.dtype == torch.float32 and u_draft.numel() == R and u_draft.is_contiguous()
+    dev = logits_d.device
+    out = dict(tok_d=torch.empty(R, dtype=torch.int32, device=dev), tok_t=torch.empty(R, dtype=torch.int32, device=dev),
+               q_tok=torch.empty(R, dtype=torch.float64, device=dev), lse_q=torch.empty(R, dtype=torch.float64, device=dev),
+               status=torch.empty(R, dtype=torch.int32, device=dev))
+    rc = lib.tli_draft_sample_warped(m.handle, _ptr(logits_d), _dtype_code(logits_d), logits_d.stride(0), R, float(temp_d),
+                                     _ptr(thr), _ptr(u_draft), _ptr(out["tok_d"]), _ptr(out["tok_t"]), _ptr(out["q_tok"]),
+                                     _ptr(out["lse_q"]), _ptr(out["status"]), 1, _ptr(workspace), workspace.numel(),
+                                     _stream(stream))
+    if rc != 0:
+        raise TliError(rc, "tli_draft_sample_warped")
     return out
 
 

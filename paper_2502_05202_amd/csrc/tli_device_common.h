@@ -126,9 +126,12 @@ template <int DT> __device__ __forceinline__ uint32_t mask_bits(const uint64_t* 
 // Reduce one chunk held in registers to (ref, s): sum 2^(x*c) over the chunk = s * 2^ref, with
 // ref = ceil(max over the chunk of fp32(x*c)) (-inf and s = 0 for a chunk without finite entries).
 // A NaN or +inf logit turns s into NaN.  Wave-uniform results.  WHOLE: every element is < V.
-template <int DT, bool MASKED, bool WHOLE>
+// MASKED: bit 0 = only the ids marked in `bits` take part; bit 1 = only logits >= thr do (a warped row, given by
+// its threshold instead of rewritten; a NaN logit still shows).
+template <int DT, int MASKED, bool WHOLE>
 __device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane, int V, float cs, float dl,
-                                             const uint64_t* bits, float& ref_out, float& s_out) {
+                                             const uint64_t* bits, float& ref_out, float& s_out,
+                                             float thr = -INFINITY) {
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int N = EPV * kLoads;
     float x[N];
@@ -142,13 +145,17 @@ __device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane
             for (int i = 0; i < EPV; ++i)
                 if (vi * EPV + i >= V) x[j * EPV + i] = -INFINITY;
         }
-        if (MASKED) {
+        if (MASKED & 1) {
             const uint64_t* w = bits + ((int64_t)c * kLoads + j) * EPV;  // wave-uniform address: scalar loads
 #pragma unroll
             for (int i = 0; i < EPV; ++i) {
                 const bool keep = __builtin_amdgcn_inverse_ballot_w64(w[i]);
                 x[j * EPV + i] = keep ? x[j * EPV + i] : -INFINITY;
             }
+        }
+        if (MASKED & 2) {
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) x[j * EPV + i] = x[j * EPV + i] < thr ? -INFINITY : x[j * EPV + i];
         }
     }
     float m = x[0];
@@ -289,13 +296,13 @@ __device__ __forceinline__ void stream_chunks(const u4v* rowv, int V, int c_begi
 }
 
 // the softmax scan: every chunk reduced to (ref, s) and handed to `sink(c, ref, s)`
-template <int DT, bool MASKED, int NW, class Sink>
+template <int DT, int MASKED, int NW, class Sink>
 __device__ __forceinline__ void scan_chunks(const u4v* rowv, int V, int c_begin, int c_end, float cs, float dl,
-                                            const uint64_t* bits, Sink&& sink) {
+                                            const uint64_t* bits, Sink&& sink, float thr = -INFINITY) {
     const int lane = threadIdx.x & 63;
     stream_chunks<DT, NW>(rowv, V, c_begin, c_end, [&](const ChunkRegs& r, int c, auto whole) {
         float ref, sum;
-        reduce_chunk<DT, MASKED, decltype(whole)::value>(r, c, lane, V, cs, dl, bits, ref, sum);
+        reduce_chunk<DT, MASKED, decltype(whole)::value>(r, c, lane, V, cs, dl, bits, ref, sum, thr);
         sink(c, ref, sum);
     });
 }

@@ -135,7 +135,7 @@ struct KernelTimer {  // records start on construction, stop on destruction, if 
 int g_final_path = 0;
 
 struct DraftOut;
-template <int DT, bool MASKED>
+template <int DT, int MASKED>
 void launch_draft(const void* logits, int64_t row_stride, int R, int V, float temp, const Plan& pl, float cs,
                   double ratio, const uint64_t* bits, const int32_t* d2t, const DraftOut& o, float* tab_ref,
                   float* tab_s, hipStream_t st);
@@ -213,10 +213,16 @@ ScanLists scan_lists(const tli_map* m, int dt, int layout) {
 }
 
 
-template <int DT, bool MASKED>
+template <int DT, int MASKED>
 void launch_draft(const void* logits, int64_t row_stride, int R, int V, float temp, const Plan& pl, float cs,
                   double ratio, const uint64_t* bits, const int32_t* d2t, const DraftOut& o, float* tab_ref,
                   float* tab_s, hipStream_t st) {
+    if constexpr (!(MASKED & 2)) {
+        if (o.thr) {  // rows given with thresholds: the same kernels with the filter compiled in
+            launch_draft<DT, MASKED | 2>(logits, row_stride, R, V, temp, pl, cs, ratio, bits, d2t, o, tab_ref, tab_s, st);
+            return;
+        }
+    }
     const double inv_temp = 1.0 / (double)temp;
     if (pl.nsplit == 1 && pl.nC <= kLdsChunks) {  // enough rows to fill the chip with one workgroup per row
         KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
@@ -227,7 +233,7 @@ void launch_draft(const void* logits, int64_t row_stride, int R, int V, float te
     {
         KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
         hipLaunchKernelGGL((k_draft_scan<DT, MASKED>), dim3((unsigned)R * pl.nsplit), dim3(kWG), 0, st, logits, row_stride,
-                           V, pl.nC, pl.cps, pl.nsplit, cs, ratio, bits, tab_ref, tab_s);
+                           V, pl.nC, pl.cps, pl.nsplit, cs, ratio, bits, tab_ref, tab_s, o.thr, o.stride);
     }
     {
         KernelTimer t(TLI_KERNEL_DRAFT_PICK, st);
@@ -241,7 +247,7 @@ void launch_draft(const void* logits, int64_t row_stride, int R, int V, float te
 int sample_rows_impl(const void* logits, int dtype, int64_t row_stride, int R, int V, float temp, uint64_t* const* bits2,
                      const int32_t* d2t, const float* u, int32_t* tok, int32_t* tok_t, double* p_tok, double* lse,
                      int32_t* status, int64_t io_stride, void* workspace, size_t workspace_bytes, hipStream_t st,
-                     const int32_t* r2d = nullptr) {
+                     const int32_t* r2d = nullptr, const float* thr = nullptr) {
     if (!logits || !u || !tok || !status || !workspace) return TLI_ERR_INVALID_ARG;
     if (R < 1 || R > 0x7fffffff / 64 || !vocab_ok(V) || !(temp > 0.f) || !std::isfinite(temp) || io_stride < 1)
         return TLI_ERR_INVALID_ARG;
@@ -263,6 +269,7 @@ int sample_rows_impl(const void* logits, int dtype, int64_t row_stride, int R, i
     o.u_draft = u; o.tok_d = tok; o.tok_t = tok_t; o.q_tok = p_tok; o.lse_q = lse; o.row_status = status;
     o.stride = io_stride;
     o.r2d = r2d;
+    o.thr = thr;
     if (bits2) {
         if (dtype == TLI_BF16)
             launch_draft<TLI_BF16, true>(logits, row_stride, R, V, temp, pl, cs, ratio, bits2[TLI_BF16], d2t, o, tab_ref, tab_s, st);
@@ -741,6 +748,16 @@ int tli_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, 
                             static_cast<hipStream_t>(hip_stream));
 }
 
+int tli_draft_sample_warped(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems,
+                            int32_t R, float temp_d, const float* thr, const float* u_draft, int32_t* tok_d,
+                            int32_t* tok_t, double* q_tok, double* lse_q, int32_t* row_status, int64_t io_stride,
+                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!map || !tok_t || !lse_q || !thr) return TLI_ERR_INVALID_ARG;
+    return sample_rows_impl(logits_d, dtype, row_stride_elems, R, map->Vd, temp_d, map->lmask, map->d2t, u_draft, tok_d,
+                            tok_t, q_tok, lse_q, row_status, io_stride, workspace, workspace_bytes,
+                            static_cast<hipStream_t>(hip_stream), nullptr, thr);
+}
+
 int tli_draft_sample_compact(const tli_map* map, const void* logits_c, tli_dtype dtype, int64_t row_stride_elems,
                              int32_t R, float temp_d, const float* u_draft, int32_t* tok_d, int32_t* tok_t, double* q_tok,
                              double* lse_q, int32_t* row_status, int64_t io_stride, void* workspace,
@@ -866,6 +883,16 @@ int tli_sample_rows(const void* logits, tli_dtype dtype, int64_t row_stride_elem
                                 row_status, io_stride, workspace, workspace_bytes, st);
     return sample_rows_impl(logits, dtype, row_stride_elems, R, V, temp, nullptr, nullptr, u, tok, nullptr, p_tok, lse,
                             row_status, io_stride, workspace, workspace_bytes, st);
+}
+
+int tli_sample_rows_warped(const void* logits, tli_dtype dtype, int64_t row_stride_elems, int32_t R, int32_t V, float temp,
+                           const float* thr, const float* u, int32_t* tok, double* p_tok, double* lse,
+                           int32_t* row_status, int64_t io_stride, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+    if (!thr) return TLI_ERR_INVALID_ARG;
+    return sample_rows_impl(logits, dtype, row_stride_elems, R, V, temp, nullptr, nullptr, u, tok, nullptr, p_tok, lse,
+                            row_status, io_stride, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream),
+                            nullptr, thr);
 }
 
 int tli_greedy_draft(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems, int32_t R,

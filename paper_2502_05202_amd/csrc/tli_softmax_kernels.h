@@ -104,27 +104,28 @@ __global__ __launch_bounds__(kWG) void k_lse_finish(const Part* __restrict__ par
 // ---- kernel: per-chunk (ref, s) table of a softmax row, optionally masked to the shared ids ----
 // Used for drafter rows (masked: the intersection algorithm's q') and for the bonus target row.
 // Workgroup `split` of a row owns chunks [split*cps, (split+1)*cps).
-template <int DT, bool MASKED>
+template <int DT, int MASKED>
 __device__ __forceinline__ void table_scan(const u4v* rowv, int split, int V, int nC, int cps, float cs, double ratio,
                                            const uint64_t* bits,
-                                  float* tab_ref, float* tab_s) {
+                                  float* tab_ref, float* tab_s, float thr = -INFINITY) {
     const int lane = threadIdx.x & 63;
     scan_chunks<DT, MASKED, kWaves>(rowv, V, split * cps, min(nC, (split + 1) * cps), cs, (float)(ratio - 1.0), bits,
                                     [&](int c, float r, float sc) {
         if (lane == 0) { tab_ref[c] = r; tab_s[c] = sc; }
-    });
+    }, thr);
 }
 
-template <int DT, bool MASKED>
+template <int DT, int MASKED>
 __global__ __launch_bounds__(kWG) void k_draft_scan(const void* __restrict__ logits, int64_t row_stride, int V,
                                                      int nC, int cps, int nsplit, float cs, double ratio,
                                                      const uint64_t* __restrict__ bits, float* __restrict__ tab_ref,
-                                                     float* __restrict__ tab_s) {
+                                                     float* __restrict__ tab_s, const float* __restrict__ thr,
+                                                     int64_t thr_stride) {
     const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
                                                     (int64_t)row * row_stride * Traits<DT>::ESZ);
     table_scan<DT, MASKED>(rowv, split, V, nC, cps, cs, ratio, bits, tab_ref + (int64_t)row * nC,
-                         tab_s + (int64_t)row * nC);
+                         tab_s + (int64_t)row * nC, (MASKED & 2) ? thr[(int64_t)row * thr_stride] : -INFINITY);
 }
 
 // ---- sampler: a workgroup of kLoads waves draws the token of a row from the row's chunk table ----
@@ -273,17 +274,17 @@ __device__ __forceinline__ int chunk_draw(const double (&w)[N], int64_t e0, doub
 
 // weights of one 16-byte vector of a softmax row relative to reference `nref` (= -ref), as in
 // reduce_chunk: 2^(x*c - ref); elements >= V or masked out get 0.
-template <int DT, bool MASKED>
+template <int DT, int MASKED>
 __device__ __forceinline__ void softmax_vec_weights(const uint4* rowv, int64_t vi, int V, float cs, float nref,
-                                                    const uint64_t* bits, double* w) {
+                                                    const uint64_t* bits, double* w, float thr = -INFINITY) {
     constexpr int EPV = Traits<DT>::EPV;
     float x[EPV];
     if (vi * EPV < V) {
         unpack<DT>(rowv[vi], x);
-        const uint32_t mb = MASKED ? mask_bits<DT>(bits, vi) : 0xffu;  // same lane-mask words as the scan
+        const uint32_t mb = (MASKED & 1) ? mask_bits<DT>(bits, vi) : 0xffu;  // same lane-mask words as the scan
 #pragma unroll
         for (int i = 0; i < EPV; ++i) {
-            const bool live = (vi * EPV + i < V) && ((mb >> i) & 1u);
+            const bool live = (vi * EPV + i < V) && ((mb >> i) & 1u) && !((MASKED & 2) && x[i] < thr);
             w[i] = live ? (double)exp2_hw(fmaf(x[i], cs, nref)) : 0.0;
         }
     } else {
@@ -296,11 +297,11 @@ __device__ __forceinline__ void softmax_vec_weights(const uint4* rowv, int64_t v
 // wave finds the chunk for itself (the table is small), then each takes one of the chunk's loads.  Returns the
 // id, or -1 if the row has no usable mass (then *total_out is NaN for a NaN/+inf logit, else 0).  Every wave of
 // the workgroup must call it, with the same arguments.
-template <int DT, bool MASKED>
+template <int DT, int MASKED>
 __device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int nC, float cs, double ratio,
                                                   const uint64_t* bits,
                                                   const float* tr, const float* ts, double u, float* M_out,
-                                                  double* total_out) {
+                                                  double* total_out, float thr = -INFINITY) {
     constexpr int EPV = Traits<DT>::EPV;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -319,7 +320,7 @@ __device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int n
     const int64_t vi = ((int64_t)c * kLoads + wave) * kWave + lane;
     double w[EPV];
     if (wave < kLoads) {
-        softmax_vec_weights<DT, MASKED>(static_cast<const uint4*>(rowp), vi, V, cs, -M, bits, w);
+        softmax_vec_weights<DT, MASKED>(static_cast<const uint4*>(rowp), vi, V, cs, -M, bits, w, thr);
     } else {
 #pragma unroll
         for (int i = 0; i < EPV; ++i) w[i] = 0.0;
@@ -334,21 +335,23 @@ struct DraftOut {
     int32_t *tok_d, *tok_t;
     double *q_tok, *lse_q;
     int32_t* row_status;
-    int64_t stride;  // entry of row r of every per-row array (u_draft included) is at index r * stride
+    int64_t stride;  // entry of row r of every per-row array (u_draft and thr included) is at index r * stride
     const int32_t* r2d;  // compact rows: index in the row (= rank) -> drafter id; nullptr otherwise
+    const float* thr;    // rows warped by threshold (MASKED bit 1): only logits >= thr[row] take part
 };
 
 // MASKED: the row is restricted to the shared ids (TLI's q').  Unmasked, the same code draws from the plain
 // softmax of a row of any vocabulary: the union algorithm's draft (d2t then marks tokens outside T with -1)
 // and the one-token-per-target-row draw of exact matching (d2t and tok_t null).
-template <int DT, bool MASKED>
+template <int DT, int MASKED>
 __device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V, int nC, float cs, double c_ratio,
                                       double inv_temp, const uint64_t* bits, const int32_t* d2t, const float* tr,
                                       const float* ts, const DraftOut& o) {
     float M;
     double total;
     const int64_t at = (int64_t)row * o.stride;
-    const int d = sample_softmax_row<DT, MASKED>(rowp, V, nC, cs, c_ratio, bits, tr, ts, (double)o.u_draft[at], &M, &total);
+    const int d = sample_softmax_row<DT, MASKED>(rowp, V, nC, cs, c_ratio, bits, tr, ts, (double)o.u_draft[at], &M, &total,
+                                                 (MASKED & 2) ? o.thr[at] : -INFINITY);
     if (threadIdx.x != 0) return;
     if (d < 0) {  // no usable mass: NaN/+inf among the logits that take part, or all of them -inf
         const bool nonfinite = (total != total);
@@ -369,7 +372,7 @@ __device__ __forceinline__ void draft_pick_row(const void* rowp, int row, int V,
 }
 
 // kernel: sampler of the split path (rows cut over several workgroups by k_draft_scan).  grid (R), kLoads waves.
-template <int DT, bool MASKED>
+template <int DT, int MASKED>
 __global__ __launch_bounds__(kLoads * kWave) void k_draft_pick(const void* __restrict__ logits, int64_t row_stride, int V,
                                                      int nC, float cs, double c_ratio, double inv_temp,
                                                      const uint64_t* __restrict__ bits,
@@ -385,7 +388,7 @@ __global__ __launch_bounds__(kLoads * kWave) void k_draft_pick(const void* __res
 // kernel: one workgroup per drafter row scans it into a chunk table in LDS and samples from it at
 // once, while the other workgroups on the CU keep streaming their rows.
 // grid (R); nC <= kLdsChunks.
-template <int DT, bool MASKED>
+template <int DT, int MASKED>
 __global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ logits, int64_t row_stride, int V,
                                                       int nC, float cs, double c_ratio, double inv_temp,
                                                       const uint64_t* __restrict__ bits,
@@ -393,7 +396,8 @@ __global__ __launch_bounds__(kWG) void k_draft_fused(const void* __restrict__ lo
     __shared__ float tr[kLdsChunks], ts[kLdsChunks];
     const int row = blockIdx.x;
     const char* rowp = static_cast<const char*>(logits) + (int64_t)row * row_stride * Traits<DT>::ESZ;
-    table_scan<DT, MASKED>(reinterpret_cast<const u4v*>(rowp), 0, V, nC, nC, cs, c_ratio, bits, tr, ts);
+    table_scan<DT, MASKED>(reinterpret_cast<const u4v*>(rowp), 0, V, nC, nC, cs, c_ratio, bits, tr, ts,
+                           (MASKED & 2) ? o.thr[(int64_t)row * o.stride] : -INFINITY);
     __syncthreads();
     draft_pick_row<DT, MASKED>(rowp, row, V, nC, cs, c_ratio, inv_temp, bits, d2t, tr, ts, o);
 }

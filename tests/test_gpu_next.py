@@ -502,6 +502,54 @@ def test_warp_rows_flags_and_map(oracle):
     m.free()
 
 
+@pytest.mark.parametrize("dtype,V,R", [("bf16", 2048 * 5 + 24, 40), ("f32", 1024 * 9 + 4, 24), ("bf16", 151936, 6)])
+def test_draws_from_rows_warped_by_threshold(oracle, dtype, V, R):
+    """One token per row from rows given with their thresholds (no rewrite) against the oracle's draw from the rows the
+    oracle warped; the same for TLI drafts with a map (only shared ids compete for the threshold and for the draw).
+    Small batches run the split kernels, R = 40 x 28 rows of the first case the one-workgroup-per-row kernel."""
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(V + R)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    reps = 28 if V < 20000 and dtype == "bf16" else 1
+    rows_t = (torch.randn(R * reps, V, generator=gen, device=DEV) * 3).to(tdt)
+    rows_t[0, 10:300] = float("-inf")
+    rows_t[1, :] = 1.25  # a constant row: nothing is dropped
+    u = synth._uniform24(R * reps, gen, DEV)
+    rows = synth.logits_to_numpy(rows_t)
+    un = u.cpu().numpy().astype(np.float64)
+    near = 0
+    for top_k, top_p, tau in [(50, 0.9, 0.8), (0, 0.7, 1.1), (5, 1.0, 1.0), (300, 0.99, 0.6)]:
+        wr = oracle.warp_rows(rows, parity.f32(tau), top_k, float(np.float32(top_p)), threads=8)
+        ninf = 0xFF80 if rows.dtype == np.uint16 else np.float32(-np.inf)
+        warped = np.where(wr["keep_mask"].astype(bool), rows, ninf)
+        ref = oracle.sample_rows(warped, parity.f32(tau), un, threads=8)
+        gw = binding.tli_warp_rows(rows_t, tau, top_k, top_p, rewrite=False)
+        g = parity.to_host(binding.tli_sample_rows(rows_t, tau, u, thr=gw["thr"]))
+        ok = wr["margin"] >= parity.NEAR_TIE  # rows whose top-p cut the oracle itself decided inside the window aside
+        rep = parity.compare_row_tokens(oracle, warped[ok], tau, un[ok], g["tok"][ok], g["status"][ok],
+                                        {k: v[ok] for k, v in ref.items()},
+                                        lambda r: oracle.softmax(warped[ok][r], parity.f32(tau))[0])
+        assert rep["hard"] == 0, dict(rep)
+        near += rep["token_near_ties"] + int((~ok).sum())
+        assert np.abs(g["lse"][ok] - ref["lse"][ok]).max() < 5e-7
+    # TLI drafts from warped drafter rows
+    w = synth.WORKLOADS[3].scaled(B=1, K=1, Vt=V + 1000, Vd=V, S=V // 2, cfg=77)
+    d2t = synth.make_d2t(w.Vd, w.Vt, w.S, 77)
+    m = binding.tli_build_map(d2t, w.Vt)
+    ws = binding.alloc_workspace(R * reps, 1, m, binding.TLI_BF16 if dtype == "bf16" else binding.TLI_F32, DEV)
+    for top_k, top_p, tau in [(20, 0.9, 0.9), (0, 0.8, 1.0)]:
+        wr = oracle.warp_rows(rows, parity.f32(tau), top_k, float(np.float32(top_p)), d2t=d2t, threads=8)
+        warped = np.where(wr["keep_mask"].astype(bool), rows, ninf)
+        gw = binding.tli_warp_rows(rows_t, tau, top_k, top_p, m=m, rewrite=False)
+        g = parity.to_host(binding.tli_draft_sample_warped(m, rows_t, tau, gw["thr"], u, ws))
+        ok = wr["margin"] >= parity.NEAR_TIE
+        repd, _ = parity.compare_draft(oracle, warped[ok], tau, d2t, un[ok], {k: v[ok] for k, v in g.items()}, threads=8)
+        assert repd["hard"] == 0, dict(repd)
+        near += repd["token_near_ties"] + int((~ok).sum())
+    print("near-tie draws or cuts:", near)
+    m.free()
+
+
 def test_next_rows_beyond_32_bit_offsets(oracle):
     """The neighbouring entry points on buffers that pass 2^31 elements and 2^32 bytes (rows of the large-vocabulary
     shape, rotated copies of 8 drawn sequences): the oracle runs on the rows and sequences either side of every
