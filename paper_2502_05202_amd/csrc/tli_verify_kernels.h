@@ -168,14 +168,21 @@ __device__ __forceinline__ double residual_weight(float p, float xv, float yv, c
     if (!(d < 0.0)) return 0.0;
     // 1 - 2^d.  Below d = -1 nothing cancels: the hardware exponential's 6e-8 is 6e-8 of the result (d = -inf, a -inf
     // drafter logit, gives 1: the whole of p).  Above, the series of -expm1(z), z = d ln 2 in (-0.7, 0), in fp32 on the
-    // fp64 difference (ten terms: z^11/11! < 1e-9; each step rounds a value near 1, so the factor keeps ~1e-7).
+    // fp64 difference (ten terms: z^11/11! < 1e-9; the last steps round values near 1, so the factor keeps ~1e-7).
     // Both are evaluated and one is chosen: no lane waits for another's branch.
     const float fd = (float)d;
     const float far = 1.f - exp2_hw(fd);
     const float z = fd * 0.693147180559945309f;
-    float t = 1.f / 10.f;
-#pragma unroll
-    for (int k = 9; k >= 2; --k) t = fmaf(t, z, 1.f) * (1.f / (float)k);  // t = 1/2 + z/6 + z^2/24 + ...
+    // 1 + z/2! + z^2/3! + ... + z^9/10!, by Horner
+    float t = 1.f / 3628800.f;
+    t = fmaf(t, z, 1.f / 362880.f);
+    t = fmaf(t, z, 1.f / 40320.f);
+    t = fmaf(t, z, 1.f / 5040.f);
+    t = fmaf(t, z, 1.f / 720.f);
+    t = fmaf(t, z, 1.f / 120.f);
+    t = fmaf(t, z, 1.f / 24.f);
+    t = fmaf(t, z, 1.f / 6.f);
+    t = fmaf(t, z, 0.5f);
     const float near = -(z * fmaf(t, z, 1.f));
     return (double)p * (double)(fd < -1.f ? far : near);
 }
@@ -359,6 +366,7 @@ __device__ __forceinline__ void final_pick_row(const FinalRow& f, int b, const v
 // nsplit > 1 (few sequences): the chunks of one (sequence, part) are dealt to nsplit workgroups, each with
 // its own copy of the part's drafter logits.
 constexpr int kStageV = 8;             // drafter vectors a lane has in flight during the staging sweep
+constexpr float kPreciseBelow = 0.1f;  // see precise_chunk_masses
 
 struct ScanLists {            // the map's lists for one dtype and one drafter-row layout, as the scan kernel reads them
     int nparts;
@@ -404,31 +412,40 @@ template <> struct BadTrack<TLI_F32> {
 // Residual masses of a workgroup's target chunks for a row on which the two models nearly agree.  The fast walk
 // forms a chunk's mass as (sum of p over the chunk, from the normaliser kernel) - (sum of min(p, q') over its pairs):
 // two fp32 sums, each good to 1e-7 of the chunk's p mass, so their difference is only that good -- and the draw
-// needs it to 1e-6 of the ROW's residual mass R.  When a workgroup finds its chunks' residual below a quarter of
-// their p mass, it forms the masses again here, with nothing subtracted that does not cancel exactly:
+// needs the row's masses to 1e-6 of the ROW's residual mass R.  All the p mass of a row is one, so with a tenth of
+// it residual (and a workgroup's own chunks are a part of the row's) the fast masses will do whatever they are; and a
+// chunk whose own residual is a tenth or more of its p mass is good to 1e-6 of itself.  The other chunks of a
+// workgroup that cannot see that tenth are formed again here, with nothing subtracted that does not cancel exactly:
 //     mass = (sum over every id of the chunk of p  -  sum over the pairs of p)  +  sum over the pairs of max(0, p - q'),
 // all three in fp64 over fp32 terms, p of a shared id being the same fp32 number in both sums (same instructions, same
 // operands), so the first difference is the target-only ids' mass to fp64 rounding; the last sum takes its terms from
 // residual_weight.  Padding entries of a pair list (first id of the chunk against a -inf drafter logit) add the same p
 // to the second and the third sum.  The chunk's mass goes to rmass, where the fast walk's would have gone.
-// Plain loop, no pipelining: rows that need it are rows whose drafts are mostly accepted.
 template <int DT>
 __device__ __noinline__ void precise_chunk_masses(unsigned char* lds, uint32_t tb, const char* trow, int nvec, int Vt,
-                                                  const int32_t* pl_g, const uint2* pl_e, int c_lo, int ncp, int gw,
-                                                  int stride, ResidualParams rp, double l2p, double* rmass_row) {
+                                                  const int32_t* pl_g, const uint2* pl_e, int c_lo,
+                                                  const uint16_t* list, int n_list, int w, int nw, ResidualParams rp,
+                                                  double l2p, double* rmass_row) {
     constexpr int EPV = Traits<DT>::EPV;
     constexpr int ESZ = Traits<DT>::ESZ;
     typedef typename std::conditional<DT == TLI_BF16, uint16_t, uint32_t>::type raw_t;
     const int lane = threadIdx.x & 63;
     unsigned char* const part = lds + kTrashBytes;
     const ResidualWide rw = widen(rp, l2p);
-    for (int idx = gw; idx < ncp; idx += stride) {  // wave-uniform
-        const int c = c_lo + idx;
+    // the workgroup's list of chunks is dealt to its waves in turn: whoever owned a chunk in the walk, the heavy
+    // ones are spread evenly now
+    for (int i = w; i < n_list; i += nw) {  // wave-uniform
+        const int c = c_lo + (int)list[i];
         const uint32_t v0 = (uint32_t)c * (kLoads * kWave) + lane;
         u4v v[kLoads];
 #pragma unroll
         for (int j = 0; j < kLoads; ++j)
             v[j] = *reinterpret_cast<const u4v*>(trow + min(v0 + j * kWave, (uint32_t)nvec - 1u) * 16u);
+        // the head of the chunk's pair list with them (the list is padded: reading kPairU groups is always in bounds)
+        const int g0 = pl_g[c], g1 = pl_g[c + 1];
+        uint2 eh[kPairU];
+#pragma unroll
+        for (int k2 = 0; k2 < kPairU; ++k2) eh[k2] = pl_e[(int64_t)(g0 + k2) * kWave + lane];
         u4v* st = reinterpret_cast<u4v*>(lds + tb);
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) st[j * kWave + lane] = v[j];
@@ -453,8 +470,10 @@ __device__ __noinline__ void precise_chunk_masses(unsigned char* lds, uint32_t t
             s_pairs += (double)pi;
             s_w += residual_weight(pi, xv, yv, rw);
         };
-        const int g1 = pl_g[c + 1];
-        for (int g = pl_g[c]; g < g1; ++g) {
+#pragma unroll
+        for (int k2 = 0; k2 < kPairU; ++k2)
+            if (g0 + k2 < g1) { one(eh[k2].x); one(eh[k2].y); }  // wave-uniform test
+        for (int g = g0 + kPairU; g < g1; ++g) {
             const uint2 e = pl_e[(int64_t)g * kWave + lane];
             one(e.x);
             one(e.y);
@@ -714,19 +733,21 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         fetch(k + 2, fa);
         if (idx + stride < ncp) process(fb, k + 1);
     }
-    bool precise = false;
-    double mass_fast = 0.0;
-    if (MODE == 0) {
-        // How much of these chunks' p mass is residual?  Below a quarter, the masses are formed again without the
-        // cancelling subtraction (see precise_chunk_masses).  Lane k: the wave's k-th chunk.
-        const int idx = gw + lane * stride;
-        float pm = 0.f, rm = 0.f;  // a rough figure is all the question needs
-        if (idx < ncp) {
+    __shared__ uint16_t again_list[kMaxPartChunks];  // the workgroup's chunks that are formed again in the precise form
+    __shared__ int again_n;                          // (as offsets from c_lo)
+    if (MODE == 0 && tid == 0) again_n = 0;  // (a barrier lies between this and the first append)
+    const int my_idx = gw + lane * stride;  // lane k: the wave's k-th chunk
+    if (DIAG) {
+        if (my_idx < ncp) { my_mn[c_lo + my_idx] = keep; my_mn2[c_lo + my_idx] = keep2; }
+    } else {
+        double mass_fast = 0.0, my_p = 0.0;
+        float pm = 0.f, rm = 0.f;  // rough figures are all the questions below need
+        if (my_idx < ncp) {
             // the chunk's mass as the draw takes it: sum_chunk p (the normaliser kernel's pair) - sum of min(p, q')
-            const double pmd = (my_rs.x == -INFINITY) ? 0.0 : (double)my_rs.y * exp2((double)my_rs.x * ratio_t - f.l2p);
-            const double t = pmd - keep;
+            my_p = (my_rs.x == -INFINITY) ? 0.0 : (double)my_rs.y * exp2((double)my_rs.x * ratio_t - f.l2p);
+            const double t = my_p - keep;
             mass_fast = t > 0.0 ? t : (t != t ? t : 0.0);
-            pm = (float)pmd;
+            pm = (float)my_p;
             rm = (float)mass_fast;
         }
         pm = wave_sum(pm);
@@ -734,19 +755,23 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         float* dec = reinterpret_cast<float*>(lds);  // the sweep's scratch words: free since the barrier behind it
         if (lane == 0) { dec[2 * wave] = pm; dec[2 * wave + 1] = rm; }
         __syncthreads();
-        float P = 0.f, R = 0.f;
+        float P = 0.f, R = 0.f;  // the workgroup's p mass and residual mass (the same in every wave)
 #pragma unroll
         for (int w = 0; w < kScanWaves; ++w) { P += dec[2 * w]; R += dec[2 * w + 1]; }
-        precise = R < 0.25f * P;  // (false for NaN sums: the draw reports those)
-    }
-    if (precise) {
-        precise_chunk_masses<DT>(lds, tb, trow, nvec, Vt, pl_g, pl_e, c_lo, ncp, gw, stride, rp, f.l2p,
-                                 rmass + (int64_t)b * nC);
-    } else {
-        const int idx = gw + lane * stride;
-        if (idx < ncp) {
-            if (DIAG) { my_mn[c_lo + idx] = keep; my_mn2[c_lo + idx] = keep2; }
-            else rmass[(int64_t)b * nC + c_lo + idx] = mass_fast;
+        // Which chunks need the precise form (see precise_chunk_masses)?  None if the workgroup's chunks hold a tenth
+        // of the row's p mass (one) as residual, or a quarter of their own (their errors then add up to 4e-7 of it).
+        // Else those that hold less than a tenth of their own p mass as residual -- but not the light ones: the chunks
+        // with less p mass than their even share of 2.5 R add up to 2.5e-7 of R between them (R less what the fast
+        // sums themselves may have added to it).  NaN sums ask for nothing: the draw reports those.
+        const bool some = R < kPreciseBelow && R < 0.25f * P;
+        const double light = 2.5 * (double)fmaxf(R - 2e-7f * P, 0.f) / (double)ncp;
+        const bool again = some && my_idx < ncp && mass_fast < (double)kPreciseBelow * my_p && my_p > light;
+        if (my_idx < ncp && !again) rmass[(int64_t)b * nC + c_lo + my_idx] = mass_fast;
+        if (some) {  // (uniform over the workgroup: every wave meets at this barrier or none does)
+            if (again) again_list[atomicAdd(&again_n, 1)] = (uint16_t)my_idx;
+            __syncthreads();
+            precise_chunk_masses<DT>(lds, tb, trow, nvec, Vt, pl_g, pl_e, c_lo, again_list, again_n, wave, kScanWaves, rp,
+                                     f.l2p, rmass + (int64_t)b * nC);
         }
     }
     if (bt.bad()) fbad[b] = 1;
