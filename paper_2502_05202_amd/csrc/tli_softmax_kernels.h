@@ -84,11 +84,39 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
 // log-normaliser of a row from its partials: ln sum exp(x/temp) = ln2 * (ref * c_true/c + log2 S), where the
 // factor c_true/c takes out the common part of the fp32 rounding of c.  NaN if a logit was NaN/+inf,
 // -inf if the row has no mass.
+// The partials are fetched kPartBatch at a time, all loads of a batch issued before the first is used (a loop of
+// one load and its use per step is a chain of round trips: 32 of them for 16 partials); the arithmetic and its
+// order are those of the plain loop.
+constexpr int kPartBatch = 16;
 __device__ __forceinline__ double combine_parts(const Part* pr, int nsplit, double ratio) {
-    float R = pr[0].ref;
-    for (int s = 1; s < nsplit; ++s) R = fmaxf(R, pr[s].ref);
+    const double kd = (ratio - 1.0) * kLn2;
+    Part first[kPartBatch];  // partials 0 .. kPartBatch - 1 (past the last: the last again), kept for both passes
+#pragma unroll
+    for (int u = 0; u < kPartBatch; ++u) first[u] = pr[min(u, nsplit - 1)];
+    float R = first[0].ref;
+#pragma unroll
+    for (int u = 1; u < kPartBatch; ++u)
+        if (u < nsplit) R = fmaxf(R, first[u].ref);
+    for (int s0 = kPartBatch; s0 < nsplit; s0 += kPartBatch) {
+        float r[kPartBatch];
+#pragma unroll
+        for (int u = 0; u < kPartBatch; ++u) r[u] = pr[min(s0 + u, nsplit - 1)].ref;
+#pragma unroll
+        for (int u = 0; u < kPartBatch; ++u)
+            if (s0 + u < nsplit) R = fmaxf(R, r[u]);
+    }
     double S = 0.0;
-    for (int s = 0; s < nsplit; ++s) S += pr[s].s * exp2_diff(pr[s].ref, R, (ratio - 1.0) * kLn2);
+#pragma unroll
+    for (int u = 0; u < kPartBatch; ++u)
+        if (u < nsplit) S += first[u].s * exp2_diff(first[u].ref, R, kd);
+    for (int s0 = kPartBatch; s0 < nsplit; s0 += kPartBatch) {
+        Part q[kPartBatch];
+#pragma unroll
+        for (int u = 0; u < kPartBatch; ++u) q[u] = pr[min(s0 + u, nsplit - 1)];
+#pragma unroll
+        for (int u = 0; u < kPartBatch; ++u)
+            if (s0 + u < nsplit) S += q[u].s * exp2_diff(q[u].ref, R, kd);
+    }
     if (S != S || R == INFINITY) return NAN;
     if (!(S > 0.0)) return -INFINITY;
     return kLn2 * ((double)R * ratio + log2(S));

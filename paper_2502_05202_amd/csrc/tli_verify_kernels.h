@@ -62,30 +62,39 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
     double my_lse = 0.0, my_lq = 0.0;
     if (k < K) {
         const int64_t row = (int64_t)b * K + k;
+        // The draft's two logits are at the end of a chain of three dependent loads (draft, its target id, the
+        // logits): it is started before the partials are combined, not after.
+        const int d = tok_d[row];
+        my_lq = lse_q[row];
+        const float u = u_acc[row];
+        const bool d_ok = d >= 0 && d < Vd;
+        const int td = d_ok ? d2t[d] : -1;
+        // TLI: a draft must be a shared drafter id.  Union algorithm: any drafter id is a legal draft; one
+        // outside T has target probability 0 and is rejected by the test itself; every drafter logit takes
+        // part there, so a NaN normaliser (NaN/+inf somewhere in the row) flags the sequence.
+        bad = !d_ok || (!union_mode && td < 0);
+        float xt = 0.f, xd = 0.f;
+        if (!bad) {
+            const char* lt = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + k) * Vt * Traits<DT>::ESZ;
+            const char* ld = static_cast<const char*>(dv.base) + row * dv.row_stride * Traits<DT>::ESZ;
+            if (td >= 0) xt = load_elem<DT>(lt, td);
+            xd = load_elem<DT>(ld, dv.d2x ? dv.d2x[d] : d);
+        }
         const double lse = combine_parts(part + row * nsplit, nsplit, ratio_t);
         nonfinite = lse != lse;
         my_lse = lse;
         ws_lse_p[row] = lse;
         if (lse_p) lse_p[(int64_t)b * (K + 1) + k] = lse;
-        const int d = tok_d[row];
-        my_lq = lse_q[row];
         double pd = 0.0, qd = 0.0;
         acc = false;
-        // TLI: a draft must be a shared drafter id.  Union algorithm: any drafter id is a legal draft; one
-        // outside T has target probability 0 and is rejected by the test itself; every drafter logit takes
-        // part there, so a NaN normaliser (NaN/+inf somewhere in the row) flags the sequence.
-        if (d < 0 || d >= Vd || (!union_mode && d2t[d] < 0)) {
-            bad = true;
+        if (bad) {
         } else if (union_mode && my_lq != my_lq) {
             nonfinite = true;
         } else if (!nonfinite) {
-            tt = d2t[d];
-            const char* lt = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + k) * Vt * Traits<DT>::ESZ;
-            const char* ld = static_cast<const char*>(dv.base) + row * dv.row_stride * Traits<DT>::ESZ;
-            pd = (tt < 0 || lse == -INFINITY) ? 0.0 : exp((double)load_elem<DT>(lt, tt) * inv_temp_t - lse);
-            const int dx = dv.d2x ? dv.d2x[d] : d;
-            qd = (union_mode && my_lq == -INFINITY) ? 0.0 : exp((double)load_elem<DT>(ld, dx) * inv_temp_d - my_lq);
-            acc = (double)u_acc[row] * qd < pd;
+            tt = td;
+            pd = (tt < 0 || lse == -INFINITY) ? 0.0 : exp((double)xt * inv_temp_t - lse);
+            qd = (union_mode && my_lq == -INFINITY) ? 0.0 : exp((double)xd * inv_temp_d - my_lq);
+            acc = (double)u * qd < pd;
         }
         if (accept) accept[row] = acc ? 1 : 0;
         if (p_tok) p_tok[row] = pd;
