@@ -123,6 +123,32 @@ template <int DT> __device__ __forceinline__ uint32_t mask_bits(const uint64_t* 
     return mb;
 }
 
+// The logits of a chunk held in registers, as floats: x[j * EPV + i] = element i of load j; ids past the vocabulary and
+// (MASKED) ids not marked in `bits` read as -inf.
+template <int DT, bool MASKED, bool WHOLE>
+__device__ __forceinline__ void chunk_values(const ChunkRegs& r, int c, int lane, int V, const uint64_t* bits, float* x) {
+    constexpr int EPV = Traits<DT>::EPV;
+    const int64_t v0 = (int64_t)c * (kWave * kLoads) + lane;
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+        unpack<DT>(to_uint4(r.v[j]), x + j * EPV);
+        const int64_t vi = v0 + j * kWave;
+        if (!WHOLE) {
+#pragma unroll
+            for (int i = 0; i < EPV; ++i)
+                if (vi * EPV + i >= V) x[j * EPV + i] = -INFINITY;
+        }
+        if (MASKED) {
+            const uint64_t* w = bits + ((int64_t)c * kLoads + j) * EPV;
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) {
+                const bool keep = __builtin_amdgcn_inverse_ballot_w64(w[i]);
+                x[j * EPV + i] = keep ? x[j * EPV + i] : -INFINITY;
+            }
+        }
+    }
+}
+
 // Reduce one chunk held in registers to (ref, s): sum 2^(x*c) over the chunk = s * 2^ref, with
 // ref = ceil(max over the chunk of fp32(x*c)) (-inf and s = 0 for a chunk without finite entries).
 // A NaN or +inf logit turns s into NaN.  Wave-uniform results.  WHOLE: every element is < V.
@@ -176,7 +202,9 @@ __device__ __forceinline__ void reduce_chunk(const ChunkRegs& r, int c, int lane
     // (1 + dl) = c_true / c: the lane is moved to the chunk reference in the TRUE scale, which takes the
     // fp32 rounding of c out of everything but the spread of logits inside one lane
     const float e = ref - R;
-    s = (m == -INFINITY) ? 0.f : s * exp2_hw(fmaf(e, dl, e));
+    // (a lane whose largest logit is -inf: its sum is 0 as it stands -- or NaN, if a NaN sits among its -inf
+    // logits, which the maximum does not see and which must surface)
+    s = (m == -INFINITY) ? s : s * exp2_hw(fmaf(e, dl, e));
     ref_out = R;
     s_out = wave_sum(s);
 }
@@ -196,7 +224,9 @@ __device__ __forceinline__ void reduce_values(const float* x, float cs, float dl
     float s = (acc[0] + acc[1]) + (acc[2] + acc[3]);
     const float R = ceilf(wave_max(ref));
     const float e = ref - R;
-    s = (m == -INFINITY) ? 0.f : s * exp2_hw(fmaf(e, dl, e));
+    // (a lane whose largest logit is -inf: its sum is 0 as it stands -- or NaN, if a NaN sits among its -inf
+    // logits, which the maximum does not see and which must surface)
+    s = (m == -INFINITY) ? s : s * exp2_hw(fmaf(e, dl, e));
     ref_out = R;
     s_out = wave_sum(s);
 }
@@ -249,8 +279,10 @@ __device__ __forceinline__ void reduce_chunk_both(const ChunkRegs& r, int c, int
     const float e = ref - R;
     const float f = (m == -INFINITY) ? 0.f : exp2_hw(fmaf(e, dl, e));
     ref_out = R;
-    s_all_out = wave_sum((m == -INFINITY) ? 0.f : ((acc[0] + acc[1]) + (acc[2] + acc[3])) * f);
-    s_sh_out = wave_sum((m == -INFINITY) ? 0.f : ((ash[0] + ash[1]) + (ash[2] + ash[3])) * f);
+    // (largest logit -inf: the sums are 0 as they stand, or NaN if a NaN sits among the lane's -inf logits)
+    const float sa = (acc[0] + acc[1]) + (acc[2] + acc[3]), ss = (ash[0] + ash[1]) + (ash[2] + ash[3]);
+    s_all_out = wave_sum((m == -INFINITY) ? sa : sa * f);
+    s_sh_out = wave_sum((m == -INFINITY) ? ss : ss * f);
 }
 
 // Stream the chunks c_begin + wave, + NW, ... < c_end of one row (NW = waves in the workgroup) through

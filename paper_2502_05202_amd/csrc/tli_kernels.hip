@@ -224,6 +224,12 @@ void launch_draft(const void* logits, int64_t row_stride, int R, int V, float te
         }
     }
     const double inv_temp = 1.0 / (double)temp;
+    if (R <= kRowMaxRows && pl.nC <= kRowChunks) {  // few short rows: each in the registers of one workgroup, one kernel
+        KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
+        hipLaunchKernelGGL((k_draft_row<DT, MASKED>), dim3(R), dim3(kRowWaves * kWave), 0, st, logits, row_stride, V, pl.nC,
+                           cs, ratio, inv_temp, bits, d2t, o);
+        return;
+    }
     if (pl.nsplit == 1 && pl.nC <= kLdsChunks) {  // enough rows to fill the chip with one workgroup per row
         KernelTimer t(TLI_KERNEL_DRAFT_SCAN, st);
         hipLaunchKernelGGL((k_draft_fused<DT, MASKED>), dim3(R), dim3(kWG), 0, st, logits, row_stride, V, pl.nC, cs, ratio,

@@ -160,30 +160,6 @@ struct ArgPart {  // best of (a split of) a row
     int32_t pad;
 };
 
-template <int DT, bool MASKED, bool WHOLE>
-__device__ __forceinline__ void chunk_values(const ChunkRegs& r, int c, int lane, int V, const uint64_t* bits, float* x) {
-    constexpr int EPV = Traits<DT>::EPV;
-    const int64_t v0 = (int64_t)c * (kWave * kLoads) + lane;
-#pragma unroll
-    for (int j = 0; j < kLoads; ++j) {
-        unpack<DT>(to_uint4(r.v[j]), x + j * EPV);
-        const int64_t vi = v0 + j * kWave;
-        if (!WHOLE) {
-#pragma unroll
-            for (int i = 0; i < EPV; ++i)
-                if (vi * EPV + i >= V) x[j * EPV + i] = -INFINITY;
-        }
-        if (MASKED) {
-            const uint64_t* w = bits + ((int64_t)c * kLoads + j) * EPV;
-#pragma unroll
-            for (int i = 0; i < EPV; ++i) {
-                const bool keep = __builtin_amdgcn_inverse_ballot_w64(w[i]);
-                x[j * EPV + i] = keep ? x[j * EPV + i] : -INFINITY;
-            }
-        }
-    }
-}
-
 template <int DT, bool MASKED>
 __global__ __launch_bounds__(kWG) void k_argmax(const void* __restrict__ logits, int64_t row_stride, int V, int nC,
                                                  int cps, int nsplit, const uint64_t* __restrict__ bits,

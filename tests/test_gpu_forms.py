@@ -95,3 +95,39 @@ def test_forms_agree_on_flagged_sequences(oracle):
                                    inp["u_fin"].cpu().numpy().astype(np.float64), res[1])
     assert rep["hard"] == 0
     m.free()
+
+
+@pytest.mark.parametrize("dtype,Vd", [("bf16", 2048 * 5 + 72), ("f32", 1024 * 32), ("f32", 1024 * 2 + 4)])
+def test_draft_forms_agree_on_flagged_and_plain_rows(oracle, dtype, Vd):
+    """Few short rows are drawn by one kernel that keeps a row in a workgroup's registers, more rows by a scan kernel
+    and a draw kernel: the same tokens, normalisers and flags bit for bit -- NaN, +inf and massless rows included --
+    and both as the oracle has them."""
+    R = 300  # one call: the two-kernel form; three calls of 100 rows: the single-kernel form
+    w = synth.WORKLOADS[3].scaled(B=R, K=1, Vt=5000, Vd=Vd, S=min(Vd, 5000) // 2, dtype=dtype, cfg=61)
+    inp = synth.make_inputs(w, DEV, seed=4300)
+    ld = inp["logits_d"].reshape(R, Vd).clone()
+    shared = np.nonzero(inp["d2t"] >= 0)[0]
+    unshared = np.nonzero(inp["d2t"] < 0)[0]
+    ld[3, int(shared[5])] = float("nan")
+    ld[7, int(shared[-1])] = float("inf")
+    ld[11, int(unshared[0])] = float("-inf")     # outside the intersection (the oracle wants those finite or -inf)
+    ld[13, torch.from_numpy(shared).to(DEV)] = float("-inf")  # no mass on the shared ids
+    ld[17, int(shared[0])] = float("-inf")
+    ld[250, int(shared[len(shared) // 2])] = float("nan")
+    m = binding.tli_build_map(inp["d2t"], w.Vt)
+    code = binding.TLI_F32 if dtype == "f32" else binding.TLI_BF16
+    ws = binding.alloc_workspace(R, 1, m, code, DEV)
+    u = inp["u_draft"].reshape(-1)
+    whole = parity.to_host(binding.tli_draft_sample(m, ld, w.tau_d, u, ws))
+    parts = [parity.to_host(binding.tli_draft_sample(m, ld[i:i + 100], w.tau_d, u[i:i + 100].contiguous(), ws))
+             for i in range(0, R, 100)]
+    torch.cuda.synchronize()
+    for k in ("tok_d", "tok_t", "status", "lse_q", "q_tok"):
+        joined = np.concatenate([p[k] for p in parts])
+        assert np.array_equal(joined, whole[k], equal_nan=k in ("lse_q", "q_tok")), k
+    assert whole["status"][3] == oracle.NONFINITE and whole["status"][7] == oracle.NONFINITE
+    assert whole["status"][13] == oracle.ZERO_MASS and whole["status"][11] == 0 and whole["status"][17] == 0
+    rep, _ = parity.compare_draft(oracle, synth.logits_to_numpy(ld), w.tau_d, inp["d2t"],
+                                  u.cpu().numpy().astype(np.float64), whole, threads=8)
+    assert rep["hard"] == 0
+    m.free()

@@ -351,6 +351,31 @@ def test_flags_and_edge_inputs(oracle):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_nan_whose_neighbours_are_all_minus_inf_is_flagged(oracle, dtype):
+    """A NaN logit must flag its row also where nothing finite stands near it: in a stretch of -inf target logits,
+    and on a shared drafter id whose neighbours are all outside a sparse intersection (a maximum taken by the hardware
+    skips NaN operands, so a reduction that starts from the maximum has to look for them separately)."""
+    w = synth.WORKLOADS[3].scaled(Vt=2048 * 5 + 72, Vd=2048 * 4 + 8, S=300, B=14, K=2, dtype=dtype)
+    inp = synth.make_inputs(w, DEV, seed=911)
+    shared = np.nonzero(inp["d2t"] >= 0)[0]
+    lt, ld = inp["logits_t"], inp["logits_d"]
+    lt[1, 0, 2048:2048 * 3] = float("-inf")
+    lt[1, 0, 2048 + 777] = float("nan")
+    lt[2, 2, :] = float("-inf")          # a bonus row without mass ...
+    lt[3, 1, :] = float("-inf")
+    lt[3, 1, 4242] = float("nan")        # ... and a row that is all -inf but for a NaN
+    for b in range(4, w.B):              # 20 rows, the NaN on a different shared id in each
+        for k in range(w.K):
+            ld[b, k, int(shared[((b * w.K + k) * 13) % len(shared)])] = float("nan")
+    res = parity.run_case(oracle, inp, chain=True)
+    _check(res)
+    sd = res["ref_draft"]["status"].reshape(w.B, w.K)
+    assert (sd[4:] == oracle.NONFINITE).all() and (sd[:4] == 0).all()
+    sv = res["ref_verify"]["status"]
+    assert sv[1] & oracle.NONFINITE and sv[3] & oracle.NONFINITE
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_residual_identically_zero_is_flagged_degenerate(oracle, dtype):
     """SD appendix, last step, with p = q' exactly and a rejected draft: the residual is identically zero and the
     extra token is drawn from p (flag DEGENERATE).  A drafter cannot draw such a token, a caller can pass one: both

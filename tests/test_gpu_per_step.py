@@ -22,7 +22,9 @@ def _per_step_draft(m, inp, w, ws, out=None):
 
 
 @pytest.mark.parametrize("shape", [(1, 5, 9000, 7000, 2500, "f32"), (37, 4, 30000, 2048 * 5 + 64, 4000, "bf16"),
-                                   (300, 3, 5000, 4104, 1500, "bf16")])
+                                   (300, 3, 5000, 4104, 1500, "bf16"),
+                                   # per position the single-kernel form (rows held in registers), batched the split one
+                                   (100, 3, 5000, 2048 * 9 + 264, 1500, "bf16"), (90, 4, 6000, 1024 * 31 + 4, 2500, "f32")])
 def test_per_step_drafts_match_oracle_and_batched_call(oracle, shape):
     B, K, Vt, Vd, S, dtype = shape
     w = synth.WORKLOADS[3].scaled(B=B, K=K, Vt=Vt, Vd=Vd, S=S, dtype=dtype, cfg=60)
