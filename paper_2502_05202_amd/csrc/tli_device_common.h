@@ -356,7 +356,7 @@ struct Running {
     double s = 0.0;
     __device__ __forceinline__ void add(float r, float sc, double kd) {
         const float nr = fmaxf(ref, r);
-        if (nr == -INFINITY) return;
+        if (nr == -INFINITY) { s += (double)sc; return; }  // sc is 0 -- or NaN (a NaN among -inf logits), which must stay
         s = s * exp2_diff(ref, nr, kd) + (double)sc * exp2_diff(r, nr, kd);
         ref = nr;
     }

@@ -115,6 +115,12 @@ def test_acceptance_rates(oracle, shape):
         ld[0, 0, int(np.nonzero(d2t < 0)[0][0])] = float("nan")
         ld[1, 1, torch.from_numpy(np.nonzero(d2t >= 0)[0]).to(DEV)] = float("-inf")
         lt[2, 0, : w.Vt // 2] = float("-inf")
+    if w.B >= 4:  # a NaN with nothing but -inf around it still flags its position (target row; shared drafter id)
+        lt[3, 0, : w.Vt // 2] = float("-inf")
+        lt[3, 0, 11] = float("nan")
+        sh_ = np.nonzero(d2t >= 0)[0]
+        ld[3, 1, : w.Vd // 2] = float("-inf")
+        ld[3, 1, int(sh_[0])] = float("nan")
     m = binding.tli_build_map(d2t, w.Vt)
     g = parity.to_host(binding.tli_acceptance_rates(m, lt, ld, w.tau_t, w.tau_d))
     lt_np = synth.logits_to_numpy(lt)[:, : w.K].reshape(w.B * w.K, w.Vt)
@@ -311,6 +317,8 @@ def test_exact_match_tail_sampled(oracle, shape):
             draft[b, m - 1] = -1
     if B >= 3:
         lt[2, 1, 9] = float("nan")
+        lt[1, 0, : w.Vt // 2] = float("-inf")  # a NaN with nothing but -inf around it
+        lt[1, 0, 3] = float("nan")
         lt_np = synth.logits_to_numpy(lt)
     g = parity.to_host(binding.tli_exact_match_verify(lt, w.tau_t, torch.from_numpy(draft).to(DEV), u))
     ref = oracle.exact_match_verify(lt_np, tau, draft, un, threads=8)
@@ -487,6 +495,8 @@ def test_warp_rows_flags_and_map(oracle):
     ld[1, int(sh[3])] = float("nan")
     ld[2, torch.from_numpy(sh).to(DEV)] = float("-inf")
     ld[3, int(np.nonzero(d2t < 0)[0][0])] = float("nan")  # unshared: ignored
+    ld[5, :2048 + 100] = float("-inf")  # a NaN with nothing but -inf around it
+    ld[5, int(sh[1])] = float("nan")
     m = binding.tli_build_map(d2t, w.Vt)
     rows = synth.logits_to_numpy(ld)
     for top_k, top_p in [(20, 1.0), (0, 0.9), (40, 0.8)]:

@@ -375,6 +375,20 @@ def test_nan_whose_neighbours_are_all_minus_inf_is_flagged(oracle, dtype):
     assert sv[1] & oracle.NONFINITE and sv[3] & oracle.NONFINITE
 
 
+def test_nan_in_a_minus_inf_chunk_beyond_the_lds_table_is_flagged(oracle):
+    """The same in a target row of more than 1024 chunks, in a chunk that the normaliser kernel no longer parks in LDS
+    but folds into a running sum as it goes."""
+    w = synth.WORKLOADS[3].scaled(Vt=1024 * 1100 + 12, Vd=3000, S=2000, B=3, K=2, dtype="f32")
+    inp = synth.make_inputs(w, DEV, seed=912)
+    lt = inp["logits_t"]
+    lt[1, 1, 1024 * 1050: 1024 * 1052] = float("-inf")
+    lt[1, 1, 1024 * 1051 + 5] = float("nan")
+    res = parity.run_case(oracle, inp, chain=False)
+    _check(res)
+    sv = res["ref_verify"]["status"]
+    assert sv[1] & oracle.NONFINITE and sv[0] == 0 and sv[2] == 0
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_residual_identically_zero_is_flagged_degenerate(oracle, dtype):
     """SD appendix, last step, with p = q' exactly and a rejected draft: the residual is identically zero and the
