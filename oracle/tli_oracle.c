@@ -84,13 +84,19 @@ int tlo_softmax(const void *logits, int dtype, int64_t n, double tau, double *pr
 /*
  * TLI's adjusted drafter.  q = softmax(logits_d / tau_d) over all of D, then
  * q'(x) = q(x) / sum_{y shared} q(y) for shared x (d2t[x] >= 0), 0 otherwise.
- * q[Vd] and qprime[Vd] are outputs; *log_norm_shared = log sum_{y shared} exp(logits_d[y]/tau_d),
- * the normaliser that turns a shared logit straight into log q'.
- * Status: NONFINITE if a SHARED logit is NaN/+inf; ZERO_MASS if the shared ids have total mass 0.
+ * The quotient is taken in log space: with z = logits_d / tau_d,
+ *     q(x) / sum_{y shared} q(y) = exp(z_x - L_all) / exp(L_sh - L_all) = exp(z_x - L_sh),
+ * L_sh = log sum_{y shared} exp(z_y) formed around the shared ids' own maximum.  (Divided as two fp64 numbers the
+ * quotient turns into 0/0 once every shared id lies some 745 nats below the drafter's largest logit -- a cold
+ * drafter whose favourites are outside the intersection -- although q' is then as well defined as anywhere.)
+ * q[Vd] and qprime[Vd] are outputs; *log_norm_shared = L_sh, the normaliser that turns a shared logit straight
+ * into log q'.
+ * Status: NONFINITE if a SHARED logit is NaN/+inf; ZERO_MASS if the shared ids have total mass 0 (all -inf).
  * Unshared drafter logits must be finite or -inf (the method never looks at them again).
  */
 int tlo_adjusted_drafter(const void *logits_d, int dtype, int64_t Vd, double tau_d, const int32_t *d2t,
                          double *q, double *qprime, double *log_norm_shared) {
+    double Ms = -INFINITY;
     for (int64_t x = 0; x < Vd; ++x) {
         if (d2t[x] < 0) continue;
         double z = load_logit(logits_d, dtype, x);
@@ -99,19 +105,22 @@ int tlo_adjusted_drafter(const void *logits_d, int dtype, int64_t Vd, double tau
             *log_norm_shared = NAN;
             return TLO_NONFINITE;
         }
+        if (z / tau_d > Ms) Ms = z / tau_d;
     }
     double log_norm_all;
     tlo_softmax(logits_d, dtype, Vd, tau_d, q, &log_norm_all);
-    double mass = 0.0;
-    for (int64_t x = 0; x < Vd; ++x)
-        if (d2t[x] >= 0) mass += q[x];
-    if (!(mass > 0.0)) {
+    if (Ms == -INFINITY) {
         for (int64_t x = 0; x < Vd; ++x) qprime[x] = 0.0;
         *log_norm_shared = -INFINITY;
         return TLO_ZERO_MASS;
     }
-    for (int64_t x = 0; x < Vd; ++x) qprime[x] = (d2t[x] >= 0) ? q[x] / mass : 0.0;
-    *log_norm_shared = log_norm_all + log(mass);
+    double Zs = 0.0;
+    for (int64_t x = 0; x < Vd; ++x) {
+        qprime[x] = (d2t[x] >= 0) ? exp(load_logit(logits_d, dtype, x) / tau_d - Ms) : 0.0;
+        Zs += qprime[x];
+    }
+    for (int64_t x = 0; x < Vd; ++x) qprime[x] /= Zs;
+    *log_norm_shared = Ms + log(Zs);
     return 0;
 }
 

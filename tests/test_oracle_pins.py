@@ -117,6 +117,26 @@ def test_softmax_and_qprime_match_scipy(oracle, dtype, tau):
             assert np.all(qp[d2t < 0] == 0.0)
 
 
+def test_qprime_of_a_cold_drafter_whose_favourites_are_unshared(oracle):
+    """Closed form: two shared ids with logits a, b and an unshared logit far above them.  q' over the intersection is
+    the two-point softmax 1 / (1 + exp(+-(a - b)/tau)) however far below the unshared logit they lie -- also when
+    q(a), q(b) themselves are below the smallest fp64 number -- and the draft is the first id iff u < q'(a)."""
+    tau = 0.05
+    for gap in (1.0, 30.0, 60.0):  # the shared ids lie gap / tau = 20, 600, 1200 nats below the largest logit
+        ld = np.array([[-gap, 0.0, -gap - 0.03, -5.0]], np.float32)
+        d2t = np.array([0, -1, 1, -1], np.int32)
+        q, qp, lse_q, st = oracle.adjusted_drafter(ld[0], tau, d2t)
+        assert st == 0 and qp[1] == 0.0 and qp[3] == 0.0
+        a, c = np.float64(ld[0, 0]), np.float64(ld[0, 2])
+        want_a = 1.0 / (1.0 + np.exp((c - a) / tau))
+        np.testing.assert_allclose(qp[0], want_a, rtol=1e-12)
+        np.testing.assert_allclose(qp[2], 1.0 - want_a, rtol=1e-12)
+        np.testing.assert_allclose(lse_q, a / tau + np.log1p(np.exp((c - a) / tau)), rtol=1e-13)
+        for u, tok in ((want_a - 1e-9, 0), (want_a + 1e-9, 2)):
+            r = oracle.draft_sample(ld, tau, d2t, np.array([u]))
+            assert r["status"][0] == 0 and r["tok_d"][0] == tok and r["tok_t"][0] == d2t[tok]
+
+
 def test_bf16_bits_are_read_exactly(oracle):
     vals = torch.tensor([1.0, -2.5, 3.140625, 0.0078125, -100.0], dtype=torch.bfloat16)
     bits = synth.logits_to_numpy(vals)
