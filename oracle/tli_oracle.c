@@ -432,18 +432,22 @@ void tlo_acceptance_rates(const void *logits_t, int64_t stride_t, const void *lo
         double lp, lq;
         int st = tlo_softmax(lt, dtype, Vt, tau_t, p, &lp) | tlo_softmax(ld, dtype, Vd, tau_d, q, &lq);
         if (st) { status[r] = TLO_NONFINITE; alpha_tli[r] = NAN; alpha_union[r] = NAN; continue; }
-        double mass = 0.0;
+        /* q(t) / sum_{x shared} q(x) in log space, as in tlo_adjusted_drafter: exp(z_t - Ms) / Zs */
+        double Ms = -INFINITY, Zs = 0.0;
         for (int64_t x = 0; x < Vd; ++x)
-            if (d2t[x] >= 0) mass += q[x];
+            if (d2t[x] >= 0 && load_logit(ld, dtype, x) / tau_d > Ms) Ms = load_logit(ld, dtype, x) / tau_d;
+        if (Ms > -INFINITY)
+            for (int64_t x = 0; x < Vd; ++x)
+                if (d2t[x] >= 0) Zs += exp(load_logit(ld, dtype, x) / tau_d - Ms);
         double au = 0.0, at = 0.0;
         for (int64_t x = 0; x < Vd; ++x) {
             if (d2t[x] < 0) continue;
             au += fmin(p[d2t[x]], q[x]);
-            if (mass > 0.0) at += fmin(p[d2t[x]], q[x] / mass);
+            if (Ms > -INFINITY) at += fmin(p[d2t[x]], exp(load_logit(ld, dtype, x) / tau_d - Ms) / Zs);
         }
         alpha_union[r] = au;
         alpha_tli[r] = at;
-        status[r] = (mass > 0.0) ? 0 : TLO_ZERO_MASS;
+        status[r] = (Ms > -INFINITY) ? 0 : TLO_ZERO_MASS;
     }
 }
 
