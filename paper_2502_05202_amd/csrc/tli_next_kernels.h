@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kWG) void k_diag_rows(const Part* __restrict__ part
     f.n = k;
     f.t_row = b * (K + 1) + k;
     f.d_row = r;
-    f.dq = 0.f;
+    f.dq = f.dq_lo = 0.f;
     f.l2p = 0.0;
     f.rp.use_q = 0;
     f.rp.ct_hi = f.rp.ct_lo = f.rp.lp_hi = f.rp.lp_lo = 0.f;
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kWG) void k_diag_rows(const Part* __restrict__ part
         split_hi_lo(f.l2p, f.rp.lp_hi, f.rp.lp_lo);
         split_scale(c_d, f.rp.cd_hi, f.rp.cd_lo);
         split_hi_lo(lq1 * kLog2e, f.rp.lq_hi, f.rp.lq_lo);
-        f.dq = (float)((lq2 - lq1) * kLog2e);
+        split_hi_lo((lq2 - lq1) * kLog2e, f.dq, f.dq_lo);
     }
     frow[r] = f;
     fbad[r] = 0;

@@ -149,7 +149,7 @@ __global__ __launch_bounds__(kSeqWG) void k_lse_accept_seq(const void* __restric
         f.n = n;
         f.t_row = b * (K + 1) + (f.bonus ? K : n);
         f.d_row = b * K + (f.bonus ? 0 : n);
-        f.dq = 0.f;
+        f.dq = f.dq_lo = 0.f;
         f.l2p = 0.0;
         f.rp.use_q = 0;
         f.rp.ct_hi = f.rp.ct_lo = f.rp.lp_hi = f.rp.lp_lo = 0.f;

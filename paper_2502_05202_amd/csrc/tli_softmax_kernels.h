@@ -321,6 +321,18 @@ __device__ __forceinline__ void softmax_vec_weights(const uint4* rowv, int64_t v
     }
 }
 
+// Mass of a chunk of a softmax row relative to the row's reference M, from the chunk's table entry (ref, s).  A chunk
+// whose reference lies more than kChunkFloor below M is given no mass: the draw forms the weights of a chunk's ids in
+// fp32 relative to M, where those of such a chunk all flush to zero, and a draw that landed there -- u = 0 with such
+// a chunk in front, u next to 1 with one at the end -- would find no id.  (All such chunks together hold less than
+// 2^-100 of the row: the sum, and the normaliser formed from it, do not change.)  A chunk kept has an id of weight
+// 2^-121 or more.  A NaN sum stays a NaN.
+constexpr float kChunkFloor = 120.f;
+__device__ __forceinline__ double chunk_mass(float ref, float s, float M, double kd) {
+    if (ref < M - kChunkFloor && s == s) return 0.0;
+    return (double)s * exp2_diff(ref, M, kd);
+}
+
 // Inverse-CDF sample of a (masked) softmax row from its chunk table, by the kLoads waves of a workgroup: every
 // wave finds the chunk for itself (the table is small), then each takes one of the chunk's loads.  Returns the
 // id, or -1 if the row has no usable mass (then *total_out is NaN for a NaN/+inf logit, else 0).  Every wave of
@@ -339,8 +351,7 @@ __device__ __forceinline__ int sample_softmax_row(const void* rowp, int V, int n
     *M_out = M;
     const double kd = (ratio - 1.0) * kLn2;
     double theta_local;
-    const int c = find_chunk(nC, u, [&](int cc) { return (double)ts[cc] * exp2_diff(tr[cc], M, kd); }, &theta_local,
-                             total_out);
+    const int c = find_chunk(nC, u, [&](int cc) { return chunk_mass(tr[cc], ts[cc], M, kd); }, &theta_local, total_out);
     if (c < 0) {
         if (M == INFINITY) *total_out = NAN;
         return -1;
@@ -542,7 +553,7 @@ __global__ __launch_bounds__(kRowWaves * kWave) void k_draft_row(const void* __r
     const float M = wave_max(m);
     const double kd = (c_ratio - 1.0) * kLn2;
     double theta_local, total;
-    const int cs_chunk = find_chunk(nC, (double)o.u_draft[at], [&](int cc) { return (double)ts[cc] * exp2_diff(tr[cc], M, kd); },
+    const int cs_chunk = find_chunk(nC, (double)o.u_draft[at], [&](int cc) { return chunk_mass(tr[cc], ts[cc], M, kd); },
                                     &theta_local, &total);
     if (cs_chunk >= 0 && wave == cs_chunk % kRowWaves) {  // the wave that holds it
         const int q_sel = cs_chunk / kRowWaves;

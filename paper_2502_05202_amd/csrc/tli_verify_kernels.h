@@ -27,6 +27,7 @@ struct FinalRow {
     int d_row;
     float dq;       // diagnostics only: log2 q'(x) - log2 q(x) = (lse_q over D - lse_q over T∩D) * log2 e >= 0
     ResidualParams rp;
+    float dq_lo;    // what dq's rounding to fp32 left out (the wide form of the diagnostic scan adds it back)
     double l2p;     // lse_p of row n, in log2 units
 };
 
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
         f.n = n;
         f.t_row = b * (K + 1) + (f.bonus ? K : n);
         f.d_row = b * K + (f.bonus ? 0 : n);
-        f.dq = 0.f;
+        f.dq = f.dq_lo = 0.f;
         f.l2p = 0.0;
         f.rp.use_q = 0;
         f.rp.ct_hi = f.rp.ct_lo = f.rp.lp_hi = f.rp.lp_lo = 0.f;
@@ -271,30 +272,47 @@ __device__ __forceinline__ PickResult final_pick_core(const FinalRow& f, int b, 
     // precise_chunk_masses); a row without a usable draft has q' = 0 and its masses are the chunk sums of p, from
     // the normaliser kernel's table of row n
     const float2* crow = ctab + (int64_t)f.d_row * nC;
+    // A chunk with mass in the table can still hold no id whose weight shows in fp32: probabilities below 2^-126 flush
+    // to zero, and a chunk sum of p less a sum of min(p, q') that should be 0 is rounding noise of either sign.  A
+    // draw that lands in one (u = 0 with such a chunk in front; one time in 10^7 or fewer otherwise) takes the chunk
+    // out and searches again, instead of returning no token.
+    constexpr int kEmptyMax = 4;
+    int skip[kEmptyMax];
+#pragma unroll
+    for (int i = 0; i < kEmptyMax; ++i) skip[i] = -1;
+    int nskip = 0;
+    auto skipped = [&](int cc) {
+        bool s = false;
+#pragma unroll
+        for (int i = 0; i < kEmptyMax; ++i) s |= cc == skip[i];
+        return s;
+    };
     auto p_mass = [&](int cc) {
         const float2 rs = crow[cc];
-        return (rs.x == -INFINITY) ? 0.0 : (double)rs.y * exp2((double)rs.x * ratio_t - f.l2p);
+        return (rs.x == -INFINITY || skipped(cc)) ? 0.0 : (double)rs.y * exp2((double)rs.x * ratio_t - f.l2p);
     };
-    auto r_mass = [&](int cc) { return f.rp.use_q ? rmass[cc] : p_mass(cc); };
+    auto r_mass = [&](int cc) { return f.rp.use_q ? (skipped(cc) ? 0.0 : rmass[cc]) : p_mass(cc); };
     double theta_local, total;
-    int c = -1;
     bool degenerate = false;
     if (f.rp.use_q && drafter_bad) {  // NaN or +inf among the shared drafter logits of row n
         res.nonfinite = true;
-    } else {
-        c = find_chunk(nC, u, r_mass, &theta_local, &total);
-        if (c < 0) {
-            if (total != total) {
-                res.nonfinite = true;
-            } else {  // residual identically zero: fall back to p of the same row
-                degenerate = true;
-                res.add_flags |= TLI_FLAG_DEGENERATE;
-                c = find_chunk(nC, u, p_mass, &theta_local, &total);
-                if (c < 0) res.nonfinite = true;
-            }
-        }
+        return res;
     }
-    if (!res.nonfinite) {
+    for (;;) {
+        const int c = degenerate ? find_chunk(nC, u, p_mass, &theta_local, &total) : find_chunk(nC, u, r_mass, &theta_local, &total);
+        if (c < 0) {
+            if (total != total || degenerate) {  // NaN somewhere, or p has no mass either
+                res.nonfinite = true;
+                return res;
+            }
+            // residual identically zero: fall back to p of the same row
+            degenerate = true;
+            res.add_flags |= TLI_FLAG_DEGENERATE;
+#pragma unroll
+            for (int i = 0; i < kEmptyMax; ++i) skip[i] = -1;
+            nskip = 0;
+            continue;
+        }
         // wave j of the workgroup takes load j of the chunk: a quarter of the table look-ups, gathers and
         // exponentials each
         const int64_t vi = ((int64_t)c * kLoads + wave) * kWave + lane;
@@ -309,7 +327,12 @@ __device__ __forceinline__ PickResult final_pick_core(const FinalRow& f, int b, 
 #pragma unroll
             for (int i = 0; i < EPV; ++i) wd[i] = 0.0;
         }
-        res.tok = chunk_draw<EPV>(wd, vi * EPV, theta_local);
+        res.tok = chunk_draw<EPV>(wd, vi * EPV, theta_local);  // (the same in every thread)
+        if (res.tok >= 0 || nskip == kEmptyMax) break;
+#pragma unroll
+        for (int i = 0; i < kEmptyMax; ++i)
+            if (i == nskip) skip[i] = c;
+        ++nskip;
     }
     return res;
 }
@@ -667,6 +690,7 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
     // [-0.5, 0.5]) times an exact power of two, in fp64: good to the exponential's 1e-7 at any size
     const double ct64 = (double)rp.ct_hi + (double)rp.ct_lo, cd64 = (double)rp.cd_hi + (double)rp.cd_lo;
     const double lq64 = (double)rp.lq_hi + (double)rp.lq_lo;
+    const double dq64 = (double)f.dq + (double)f.dq_lo;
     auto exp2_wide = [](double m) -> double {
         if (!(m > -1070.0)) return m != m ? m : 0.0;  // -inf, or below what fp64 holds (NaN stays NaN)
         const double n = rint(m);
@@ -677,7 +701,7 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         const uint32_t yr = *reinterpret_cast<const raw_t*>(part + (e >> kPairShift) * ESZ);
         const float xv = as_f(DT == TLI_BF16 ? xr << 16 : xr), yv = as_f(DT == TLI_BF16 ? yr << 16 : yr);
         const double a = fma((double)xv, ct64, -f.l2p), bq = fma((double)yv, cd64, -lq64);
-        second = exp2_wide(fmin(a, bq - (double)dq));
+        second = exp2_wide(fmin(a, bq - dq64));
         return exp2_wide(fmin(a, bq));
     };
     // Results stay in registers until the wave is through (lane k keeps the sum of the wave's k-th chunk):

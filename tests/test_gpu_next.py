@@ -169,6 +169,37 @@ def test_acceptance_rates_when_unshared_logits_dwarf_the_shared(oracle, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_acceptance_rates_of_a_cold_drafter_whose_favourite_is_unshared(oracle, dtype):
+    """A drafter at temperature 0.05 with one unshared logit 8 to 14 above every shared one: q = q' * 2^-dq with dq
+    between 230 and 400 binary orders, alpha_union between 1e-70 and 1e-120.  dq has to enter the sums with more than
+    the 24 bits of an fp32 (2^-24 of 300 is 1.2e-5 of the rate)."""
+    chunk = 2048 if dtype == "bf16" else 1024
+    Vd, Vt, B, K, S = chunk * 2 + 40, chunk * 2 + 24, 5, 3, 900
+    rng = np.random.default_rng(41)
+    d2t = np.full(Vd, -1, np.int32)
+    sh = np.sort(rng.permutation(Vd)[:S])
+    d2t[sh] = rng.permutation(Vt)[:S].astype(np.int32)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(42)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    ld = (torch.randn(B, K, Vd, generator=gen, device=DEV) * 0.5).to(tdt)
+    lt = (torch.randn(B, K + 1, Vt, generator=gen, device=DEV) * 2).to(tdt)
+    un = int(np.setdiff1d(np.arange(Vd), sh)[7])
+    for b in range(B):
+        for k in range(K):
+            ld[b, k, un] = 10.0 + 2.0 * ((b * K + k) % 4)
+    m = binding.tli_build_map(d2t, Vt)
+    g = parity.to_host(binding.tli_acceptance_rates(m, lt, ld, 1.0, 0.05))
+    ref = oracle.acceptance_rates(synth.logits_to_numpy(lt)[:, :K].reshape(B * K, Vt),
+                                  synth.logits_to_numpy(ld).reshape(B * K, Vd), 1.0, parity.f32(0.05), d2t, threads=4)
+    assert np.all(ref["status"] == 0) and np.all(g["status"] == 0)
+    assert 1e-130 < ref["alpha_union"].min() and ref["alpha_union"].max() < 1e-60
+    for name in ("alpha_tli", "alpha_union"):
+        print(name, "max rel err", _rates_close(g[name], ref[name]), "range", ref[name].min(), ref[name].max())
+    m.free()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_acceptance_rates_of_nearly_disjoint_models(oracle, dtype):
     """Drafter and target that put their mass on different shared tokens: the rates run from 1e-3 down to 1e-200,
     far below what an fp32 term holds, and every one of them must still be good to 1e-5 relative."""

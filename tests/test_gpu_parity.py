@@ -390,6 +390,31 @@ def test_nan_in_a_minus_inf_chunk_beyond_the_lds_table_is_flagged(oracle):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_draws_at_the_ends_of_the_cdf_skip_chunks_below_fp32(oracle, dtype):
+    """u = 0 and u = 1 - 2^-24 with a first and a last chunk whose ids all lie 180-230 binary orders below the row's
+    largest weight: in fp64 they carry mass (the oracle's draw at u = 0 is the first of them), in the fp32 weights of
+    the GPU's in-chunk search they are zero.  The GPU must return the neighbouring id that has weight -- a draw
+    within 2^-180 of the oracle's, a near-tie to the comparison -- not "no token"."""
+    chunk = 2048 if dtype == "bf16" else 1024
+    w = synth.WORKLOADS[3].scaled(Vt=chunk * 4, Vd=chunk * 3, S=chunk * 2, B=6, K=3, dtype=dtype, tau_t=0.7, tau_d=0.3)
+    inp = synth.make_inputs(w, DEV, seed=913)
+    lt, ld = inp["logits_t"], inp["logits_d"]
+    ld[:, :, :chunk] = -40.0
+    ld[:, :, -chunk:] = -40.0
+    lt[:, :, :chunk] = -80.0
+    lt[:, :, -chunk:] = -80.0
+    inp["u_draft"][0::2, :] = 0.0
+    inp["u_draft"][1::2, :] = 1.0 - 2.0 ** -24
+    inp["u_fin"][0::2] = 0.0
+    inp["u_fin"][1::2] = 1.0 - 2.0 ** -24
+    res = parity.run_case(oracle, inp, chain=True)
+    _check(res)
+    assert (res["ref_draft"]["status"] == 0).all() and (res["gpu_verify"]["status"] == 0).all()
+    out, n = res["gpu_verify"]["out_tok"], res["gpu_verify"]["n_accepted"]
+    assert all(out[b, n[b]] >= 0 for b in range(w.B))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_residual_identically_zero_is_flagged_degenerate(oracle, dtype):
     """SD appendix, last step, with p = q' exactly and a rejected draft: the residual is identically zero and the
     extra token is drawn from p (flag DEGENERATE).  A drafter cannot draw such a token, a caller can pass one: both
