@@ -92,6 +92,7 @@ def compare_draft(oracle_mod, ld_np, tau_d, d2t, u_draft, gpu: dict, ref: dict |
             print(f"HARD draft mismatch row {r}: gpu {gpu['tok_d'][r]} oracle {ref['tok_d'][r]} margin {m} dist {dist}")
     same = ok & (gpu["tok_d"] == ref["tok_d"])
     assert np.array_equal(gpu["tok_t"][same], ref["tok_t"][same])
+    same &= ref["q_tok"] >= 1e-290  # (below that fp64 no longer holds a probability with all its bits)
     rel = np.abs(gpu["q_tok"][same] - ref["q_tok"][same]) / ref["q_tok"][same]
     if rel.size:
         rep["max_prob_rel"] = float(rel.max())
@@ -123,8 +124,10 @@ def compare_verify(oracle_mod, lt_np, ld_np, tau_t, tau_d, d2t, tok_d, u_acc, u_
         assert e < REL_TOL, f"seq {b}: lse_p differs by {e}"
         for name in ("p_tok", "q_tok"):
             r_, g_ = ref[name][b], gpu[name][b]
-            nz = r_ > 0
-            assert np.all(g_[~nz] == 0.0)
+            # the relative bound is for probabilities that fp64 holds with all its bits; at 1e-290 and below (a
+            # subnormal has as few as one) both sides only have to be that small
+            nz = r_ >= 1e-290
+            assert np.all(g_[~nz] < 1e-289)
             if nz.any():
                 rel = (np.abs(g_[nz] - r_[nz]) / r_[nz]).max()
                 rep["max_prob_rel"] = max(rep["max_prob_rel"], float(rel))
