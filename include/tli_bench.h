@@ -27,7 +27,7 @@ extern "C" {
  */
 typedef enum {
     TLI_KERNEL_LSE = 0,        /* tli_verify: log-normalisers of the K target rows of every sequence      */
-    TLI_KERNEL_ACCEPT = 1,     /* tli_verify: accept tests + first-reject scan                            */
+    TLI_KERNEL_ACCEPT = 1,     /* (no kernel of its own any more: the accept tests run inside ids 0 or 2)   */
     TLI_KERNEL_FINAL_SCAN = 2, /* tli_verify: chunk masses of the residual / bonus rows                   */
     TLI_KERNEL_FINAL_PICK = 3, /* tli_verify: draw of the extra token                                     */
     TLI_KERNEL_DRAFT_SCAN = 4, /* row samplers: scan of the rows (+ the draw, one workgroup/row); argmax scan  */

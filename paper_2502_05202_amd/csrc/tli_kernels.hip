@@ -69,7 +69,7 @@ size_t lse_shmem(const Plan& p) { return (size_t)(p.cps < kLdsChunks ? p.cps : k
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {  // offsets into the caller's scratch
-    size_t part, part_d, ws_lse_p, ws_lse_q, ctab, frow, fbad, tab_ref, tab_s, rmass, total;
+    size_t part, part_d, ws_lse_q, ctab, frow, fbad, tab_ref, tab_s, rmass, total;
 };
 
 Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
@@ -84,7 +84,6 @@ Workspace layout(int B, int K, int Vt, int Vd, int dtype) {
     const Plan pd = make_plan(Vd, (int)rows, chunk);
     w.part = off; off += align256((size_t)rows * pl.nsplit * sizeof(Part));
     w.part_d = off; off += align256((size_t)rows * pd.nsplit * sizeof(Part));
-    w.ws_lse_p = off; off += align256((size_t)rows * sizeof(double));
     w.ws_lse_q = off; off += align256((size_t)rows * sizeof(double));
     w.ctab = off; off += align256((size_t)rows * nCt * sizeof(float2));
     w.frow = off; off += align256((size_t)B * sizeof(FinalRow));
@@ -130,8 +129,9 @@ struct KernelTimer {  // records start on construction, stop on destruction, if 
     }
 };
 
-// which form the first steps of tli_verify take: 0 = by batch size, 1 = split (k_lse, k_accept), 2 = a workgroup per
-// sequence (k_lse_accept_seq) wherever it fits.  Set by tli_tune_final_path (tests and benchmarks).
+// which form the first steps of tli_verify take: 0 = by batch size, 1 = split (k_lse; the accept tests in the
+// residual scan's workgroups), 2 = a workgroup per sequence (k_lse_accept_seq) wherever it fits.  Set by
+// tli_tune_final_path (tests and benchmarks).
 int g_final_path = 0;
 
 struct DraftOut;
@@ -155,7 +155,7 @@ struct VerifyArgs {
     double *p_tok, *q_tok, *lse_p;
     int32_t* seq_status;
     Part *part, *part_d;
-    double *ws_lse_p, *ws_lse_q;
+    double* ws_lse_q;
     Plan pd;
     float cs_d;
     double ratio_d;
@@ -362,7 +362,7 @@ template <int DT> const double* launch_verify_lse(const VerifyArgs& a, hipStream
         KernelTimer t(TLI_KERNEL_LSE, st);
         hipLaunchKernelGGL((k_lse<DT, false>), dim3((unsigned)rows * a.pl.nsplit), dim3(kWG), lse_shmem(a.pl), st, a.logits_t, K,
                            (int64_t)(K + 1) * Vt, (int64_t)Vt, Vt, a.pl.nC, a.pl.cps, a.pl.nsplit, a.cs_t, a.ratio_t,
-                           nullptr, a.part, a.ctab);
+                           nullptr, a.part, a.ctab, a.fbad);
     }
     return lse_q;
 }
@@ -374,13 +374,16 @@ void launch_verify_tail(const VerifyArgs& a, const double* lse_q, hipStream_t st
     FinalOut fo;
     fo.u_fin = a.u_fin; fo.n_accepted = a.n_accepted; fo.out_tok = a.out_tok; fo.lse_p = a.lse_p;
     fo.seq_status = a.seq_status;
-    if (!accept_done) {
-        KernelTimer t(TLI_KERNEL_ACCEPT, st);
-        hipLaunchKernelGGL(k_accept<DT>, dim3(B), dim3(kWave), 0, st, a.logits_t, a.dv, K, Vt, Vd, a.pl.nsplit,
-                           a.part, a.ratio_t, a.inv_t, a.inv_d, a.map->d2t, a.tok_d, lse_q, a.u_acc, a.n_accepted,
-                           a.out_tok, a.accept, a.p_tok, a.q_tok, a.lse_p, a.seq_status, a.ws_lse_p, a.c_t, a.c_d, a.frow,
-                           a.fbad, a.union_mode);
-    }
+    AcceptIn in;
+    in.part = a.part; in.nsplit = a.pl.nsplit; in.ratio_t = a.ratio_t; in.inv_temp_t = a.inv_t; in.inv_temp_d = a.inv_d;
+    in.c_t = a.c_t; in.c_d = a.c_d; in.d2t = a.map->d2t; in.tok_d = a.tok_d; in.lse_q = lse_q; in.u_acc = a.u_acc;
+    in.union_mode = a.union_mode;
+    AcceptOut out;
+    out.n_accepted = a.n_accepted; out.out_tok = a.out_tok; out.accept = a.accept; out.p_tok = a.p_tok;
+    out.q_tok = a.q_tok; out.lse_p = a.lse_p; out.seq_status = a.seq_status; out.frow = a.frow;
+    // split form: the accept tests run inside the residual scan's workgroups (1.5-3 us less than a kernel of their own:
+    // 24.0 -> 22.5 us for one sequence, 44.4 -> 42.8 us for 64, 115.3 -> 113.5 us for 128, same-run A/B)
+    const bool fuse = !accept_done;
     const int nparts = a.map->scan[DT].nparts;
     const ScanLists ls = scan_lists(a.map, DT, a.compact ? 1 : 0);
     {
@@ -388,9 +391,15 @@ void launch_verify_tail(const VerifyArgs& a, const double* lse_q, hipStream_t st
         // few sequences: deal the chunks of a (sequence, part) to several workgroups, up to one per CU
         int nsplit = 256 / (B * nparts);
         nsplit = nsplit < 1 ? 1 : (nsplit > 4 ? 4 : nsplit);
-        hipLaunchKernelGGL((k_final_scan<DT, 0>), dim3((unsigned)((B + 7) / 8) * 8 * nparts * nsplit), dim3(kScanWG), 0,
-                           st, a.logits_t, a.dv, B, K, Vt, Vd, a.pf.nC, nsplit, ls, a.cs_t, a.ratio_t, a.frow, a.tab_ref,
-                           a.tab_s, (double*)nullptr, (double*)nullptr, a.fbad, (const int32_t*)nullptr, a.ctab, a.rmass);
+        const dim3 grid((unsigned)((B + 7) / 8) * 8 * nparts * nsplit);
+        if (fuse)
+            hipLaunchKernelGGL((k_final_scan<DT, 0, true>), grid, dim3(kScanWG), 0, st, a.logits_t, a.dv, B, K, Vt, Vd,
+                               a.pf.nC, nsplit, ls, a.cs_t, a.ratio_t, a.frow, a.tab_ref, a.tab_s, (double*)nullptr,
+                               (double*)nullptr, a.fbad, (const int32_t*)nullptr, a.ctab, a.rmass, in, out);
+        else
+            hipLaunchKernelGGL((k_final_scan<DT, 0, false>), grid, dim3(kScanWG), 0, st, a.logits_t, a.dv, B, K, Vt, Vd,
+                               a.pf.nC, nsplit, ls, a.cs_t, a.ratio_t, a.frow, a.tab_ref, a.tab_s, (double*)nullptr,
+                               (double*)nullptr, a.fbad, (const int32_t*)nullptr, a.ctab, a.rmass, AcceptIn(), AcceptOut());
     }
     {
         KernelTimer t(TLI_KERNEL_FINAL_PICK, st);
@@ -965,7 +974,6 @@ static int verify_impl(int union_mode, int64_t compact_stride, const tli_map* ma
     if (workspace_bytes < w.total) return TLI_ERR_ALLOC;
     char* ws = static_cast<char*>(workspace);
     Part* part = reinterpret_cast<Part*>(ws + w.part);
-    double* ws_lse_p = reinterpret_cast<double*>(ws + w.ws_lse_p);
     float* tab_ref = reinterpret_cast<float*>(ws + w.tab_ref);
     float* tab_s = reinterpret_cast<float*>(ws + w.tab_s);
     const int chunk = dtype == TLI_BF16 ? chunk_elems<TLI_BF16>() : chunk_elems<TLI_F32>();
@@ -982,7 +990,7 @@ static int verify_impl(int union_mode, int64_t compact_stride, const tli_map* ma
     a.c_t = c_t; a.c_d = c_d; a.cs_t = cs_t; a.ratio_t = ratio_t; a.inv_t = inv_t; a.inv_d = inv_d;
     a.tok_d = tok_d; a.lse_q = lse_q; a.u_acc = u_acc; a.u_fin = u_fin; a.n_accepted = n_accepted;
     a.out_tok = out_tok; a.accept = accept; a.p_tok = p_tok; a.q_tok = q_tok; a.lse_p = lse_p;
-    a.seq_status = seq_status; a.part = part; a.ws_lse_p = ws_lse_p;
+    a.seq_status = seq_status; a.part = part;
     a.part_d = reinterpret_cast<Part*>(ws + w.part_d); a.ws_lse_q = reinterpret_cast<double*>(ws + w.ws_lse_q);
     a.compact = compact ? 1 : 0;
     a.d_valid = compact ? map->S : Vd;

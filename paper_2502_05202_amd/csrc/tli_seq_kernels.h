@@ -2,8 +2,8 @@
 // compute unit and more).  Included by tli_kernels.hip inside its unnamed namespace, after tli_verify_kernels.h.
 #pragma once
 
-// Standard SD appendix, verification loop and count of accepted drafts, in one kernel (k_lse + k_accept of the
-// split form, without the kernel boundary between them and its chain of dependent round trips).  A workgroup of
+// Standard SD appendix, verification loop and count of accepted drafts, in one kernel (k_lse + the accept tests of the
+// split form, without a kernel boundary between the normalisers and the tests).  A workgroup of
 // 1 + kSeqStreamWaves waves owns a sequence:
 //   * waves 1.. stream the sequence's K target rows, one row at a time, chunk pairs (ref, s) into one of two
 //     tables in LDS; sequence b takes row (b + i) mod K at step i, so the rows a compute unit reads at one time
@@ -12,7 +12,7 @@
 //     row's log-normaliser (and leaves the pairs in ctab for the residual step), and lane k takes position k's
 //     accept test the moment row k is through -- its draft's two logits were gathered when the kernel started;
 //   * when every row is through the clerk runs the first-reject scan and writes the sequence's outputs and the
-//     record the extra-token kernels start from, exactly as k_accept does.
+//     record the extra-token kernels start from, exactly as accept_sequence does.
 // The chunk loop is k_lse's.  Eight streaming waves per compute unit (64 KB of loads in flight each, 16 MB over the
 // chip) is where the rate peaks: 153-156 us for the large-vocabulary batch's 1.05 GB against 157 us with 10 to 15
 // waves, 163 with 6, 180 with 4 or 5 -- and against 175 / 188 us with two / three chunks in flight per wave instead of one.
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kSeqWG) void k_lse_accept_seq(const void* __restric
         const int d = in.tok_d[row];
         my_lq = in.lse_q[row];
         my_u = in.u_acc[row];
-        // TLI: a draft must be a shared drafter id.  Union algorithm: any drafter id is a legal draft (see k_accept).
+        // TLI: a draft must be a shared drafter id.  Union algorithm: any drafter id is a legal draft (see accept_sequence).
         if (d < 0 || d >= Vd || (!in.union_mode && in.d2t[d] < 0)) {
             bad = true;
         } else {
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(kSeqWG) void k_lse_accept_seq(const void* __restric
         __syncthreads();
     }
     if (wave != 0) return;
-    // ---- first-reject scan and the record for the extra-token kernels (as k_accept)
+    // ---- first-reject scan and the record for the extra-token kernels (as accept_sequence)
     const int k = lane;
     const unsigned long long rej = __ballot(k < K && !acc);
     const bool any_nonfinite = __ballot(nonfinite) != 0ull;
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(kSeqWG) void k_lse_accept_seq(const void* __restric
             f.l2p = my_lse * kLog2e;
             split_scale(in.c_t, f.rp.ct_hi, f.rp.ct_lo);
             split_hi_lo(f.l2p, f.rp.lp_hi, f.rp.lp_lo);
-            if (!bad && (my_lq > -INFINITY || my_lq != my_lq)) {  // see k_accept
+            if (!bad && (my_lq > -INFINITY || my_lq != my_lq)) {  // see accept_sequence
                 f.rp.use_q = 1;
                 split_scale(in.c_d, f.rp.cd_hi, f.rp.cd_lo);
                 split_hi_lo(my_lq * kLog2e, f.rp.lq_hi, f.rp.lq_lo);

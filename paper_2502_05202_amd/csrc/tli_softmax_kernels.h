@@ -15,7 +15,8 @@ template <int DT, bool MASKED>
 __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, int K, int64_t seq_stride,
                                               int64_t row_stride, int V, int nC, int cps, int nsplit, float cs,
                                               double ratio, const uint64_t* __restrict__ bits,
-                                              Part* __restrict__ part, float2* __restrict__ ctab) {
+                                              Part* __restrict__ part, float2* __restrict__ ctab,
+                                              int32_t* __restrict__ fbad = nullptr) {
 #if TLI_LSE_ORDER == 1
     const int slot = blockIdx.x / nsplit, split = blockIdx.x - slot * nsplit;
     const int nB = (int)(gridDim.x / nsplit) / K;
@@ -31,6 +32,9 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const double kd = (ratio - 1.0) * kLn2;
+    // verification without an accept kernel: the sequence's "drafter row of the residual holds NaN or +inf" flag
+    // starts at 0 here (the residual scan's workgroups raise it, the draw reads it)
+    if (fbad && k == 0 && split == 0 && threadIdx.x == 0) fbad[b] = 0;
     // The (ref, s) of every chunk is parked in LDS (no global store sits between the streaming loads, and the
     // running total is not advanced per chunk: that is a dozen fp64 instructions which every lane would
     // execute for a wave-uniform value); the partial is reduced from there when the row is through.  The pairs

@@ -43,21 +43,31 @@ __device__ __forceinline__ void split_scale(double c, float& hi, float& lo) {
     lo = (float)(c - (double)hi);
 }
 
-// ---- kernel: accept tests and first-reject scan ------------------------------------------------
-// Standard SD appendix, verification loop and the count of accepted drafts.  grid (B), 64 threads;
-// lane k owns position k.
+// ---- accept tests and first-reject scan of one sequence ------------------------------------------
+// Standard SD appendix, verification loop and the count of accepted drafts, from the normaliser partials of the
+// sequence's K target rows.  One wave, lane k owns position k.  Returns the sequence's record for the extra-token
+// step, the same in every lane; if `write`, also stores the sequence's outputs and that record.
+struct AcceptIn {
+    const Part* part;  // [B*K][nsplit] partial normalisers of the target rows
+    int nsplit;
+    double ratio_t, inv_temp_t, inv_temp_d, c_t, c_d;
+    const int32_t *d2t, *tok_d;
+    const double* lse_q;
+    const float* u_acc;
+    int union_mode;
+};
+struct AcceptOut {
+    int32_t *n_accepted, *out_tok;
+    uint8_t* accept;
+    double *p_tok, *q_tok, *lse_p;
+    int32_t* seq_status;
+    FinalRow* frow;
+};
+
 template <int DT>
-__global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logits_t, DrafterView dv,
-                                                   int K, int Vt, int Vd, int nsplit, const Part* __restrict__ part,
-                                                   double ratio_t, double inv_temp_t, double inv_temp_d,
-                                                   const int32_t* __restrict__ d2t, const int32_t* __restrict__ tok_d,
-                                                   const double* __restrict__ lse_q, const float* __restrict__ u_acc,
-                                                   int32_t* __restrict__ n_accepted, int32_t* __restrict__ out_tok,
-                                                   uint8_t* __restrict__ accept, double* __restrict__ p_tok,
-                                                   double* __restrict__ q_tok, double* __restrict__ lse_p,
-                                                   int32_t* __restrict__ seq_status, double* __restrict__ ws_lse_p, double c_t,
-                                                   double c_d, FinalRow* __restrict__ frow, int32_t* __restrict__ fbad, int union_mode) {
-    const int b = blockIdx.x, k = threadIdx.x;
+__device__ __forceinline__ FinalRow accept_sequence(int b, const void* __restrict__ logits_t, const DrafterView& dv, int K,
+                                                    int Vt, int Vd, const AcceptIn& in, const AcceptOut& out, bool write) {
+    const int k = threadIdx.x & 63;
     bool acc = true, nonfinite = false, bad = false;
     int tt = -1;
     double my_lse = 0.0, my_lq = 0.0;
@@ -65,15 +75,15 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
         const int64_t row = (int64_t)b * K + k;
         // The draft's two logits are at the end of a chain of three dependent loads (draft, its target id, the
         // logits): it is started before the partials are combined, not after.
-        const int d = tok_d[row];
-        my_lq = lse_q[row];
-        const float u = u_acc[row];
+        const int d = in.tok_d[row];
+        my_lq = in.lse_q[row];
+        const float u = in.u_acc[row];
         const bool d_ok = d >= 0 && d < Vd;
-        const int td = d_ok ? d2t[d] : -1;
+        const int td = d_ok ? in.d2t[d] : -1;
         // TLI: a draft must be a shared drafter id.  Union algorithm: any drafter id is a legal draft; one
         // outside T has target probability 0 and is rejected by the test itself; every drafter logit takes
         // part there, so a NaN normaliser (NaN/+inf somewhere in the row) flags the sequence.
-        bad = !d_ok || (!union_mode && td < 0);
+        bad = !d_ok || (!in.union_mode && td < 0);
         float xt = 0.f, xd = 0.f;
         if (!bad) {
             const char* lt = static_cast<const char*>(logits_t) + ((int64_t)b * (K + 1) + k) * Vt * Traits<DT>::ESZ;
@@ -81,66 +91,70 @@ __global__ __launch_bounds__(kWave) void k_accept(const void* __restrict__ logit
             if (td >= 0) xt = load_elem<DT>(lt, td);
             xd = load_elem<DT>(ld, dv.d2x ? dv.d2x[d] : d);
         }
-        const double lse = combine_parts(part + row * nsplit, nsplit, ratio_t);
+        const double lse = combine_parts(in.part + row * in.nsplit, in.nsplit, in.ratio_t);
         nonfinite = lse != lse;
         my_lse = lse;
-        ws_lse_p[row] = lse;
-        if (lse_p) lse_p[(int64_t)b * (K + 1) + k] = lse;
         double pd = 0.0, qd = 0.0;
         acc = false;
         if (bad) {
-        } else if (union_mode && my_lq != my_lq) {
+        } else if (in.union_mode && my_lq != my_lq) {
             nonfinite = true;
         } else if (!nonfinite) {
             tt = td;
-            pd = (tt < 0 || lse == -INFINITY) ? 0.0 : exp((double)xt * inv_temp_t - lse);
-            qd = (union_mode && my_lq == -INFINITY) ? 0.0 : exp((double)xd * inv_temp_d - my_lq);
+            pd = (tt < 0 || lse == -INFINITY) ? 0.0 : exp((double)xt * in.inv_temp_t - lse);
+            qd = (in.union_mode && my_lq == -INFINITY) ? 0.0 : exp((double)xd * in.inv_temp_d - my_lq);
             acc = (double)u * qd < pd;
         }
-        if (accept) accept[row] = acc ? 1 : 0;
-        if (p_tok) p_tok[row] = pd;
-        if (q_tok) q_tok[row] = qd;
+        if (write) {
+            if (out.lse_p) out.lse_p[(int64_t)b * (K + 1) + k] = lse;
+            if (out.accept) out.accept[row] = acc ? 1 : 0;
+            if (out.p_tok) out.p_tok[row] = pd;
+            if (out.q_tok) out.q_tok[row] = qd;
+        }
     }
     const unsigned long long rej = __ballot(k < K && !acc);
     const bool any_nonfinite = __ballot(nonfinite) != 0ull;
     const bool any_bad = __ballot(bad) != 0ull;
     int n = rej ? (int)__builtin_ctzll(rej) : K;
     if (any_nonfinite) n = 0;
-    if (k < K) out_tok[(int64_t)b * (K + 1) + k] = (k < n) ? tt : -1;
-    if (k == 0) {
-        out_tok[(int64_t)b * (K + 1) + K] = -1;
-        n_accepted[b] = n;
-        seq_status[b] = (any_nonfinite ? TLI_FLAG_NONFINITE : 0) | (any_bad ? TLI_FLAG_BAD_DRAFT : 0);
-        fbad[b] = 0;  // raised by the residual scan if the drafter row it reads holds NaN or +inf
-        if (lse_p) lse_p[(int64_t)b * (K + 1) + K] = NAN;
-    }
-    // one record per sequence for the final kernels, written by the lane that owns the row they will use
-    const bool residual = !any_nonfinite && n < K;
-    if (residual ? (k == n) : (k == 0)) {
-        FinalRow f;
-        f.skip = any_nonfinite ? 1 : 0;
-        f.bonus = (!any_nonfinite && n == K) ? 1 : 0;
-        f.n = n;
-        f.t_row = b * (K + 1) + (f.bonus ? K : n);
-        f.d_row = b * K + (f.bonus ? 0 : n);
-        f.dq = f.dq_lo = 0.f;
-        f.l2p = 0.0;
-        f.rp.use_q = 0;
-        f.rp.ct_hi = f.rp.ct_lo = f.rp.lp_hi = f.rp.lp_lo = 0.f;
-        f.rp.cd_hi = f.rp.cd_lo = f.rp.lq_hi = f.rp.lq_lo = 0.f;
-        if (residual) {
-            f.l2p = my_lse * kLog2e;
-            split_scale(c_t, f.rp.ct_hi, f.rp.ct_lo);
-            split_hi_lo(f.l2p, f.rp.lp_hi, f.rp.lp_lo);
-            // an unusable draft, or a drafter row without mass, has q' = 0 everywhere
-            if (!bad && (my_lq > -INFINITY || my_lq != my_lq)) {
-                f.rp.use_q = 1;
-                split_scale(c_d, f.rp.cd_hi, f.rp.cd_lo);
-                split_hi_lo(my_lq * kLog2e, f.rp.lq_hi, f.rp.lq_lo);
-            }
+    if (write) {
+        if (k < K) out.out_tok[(int64_t)b * (K + 1) + k] = (k < n) ? tt : -1;
+        if (k == 0) {
+            out.out_tok[(int64_t)b * (K + 1) + K] = -1;
+            out.n_accepted[b] = n;
+            out.seq_status[b] = (any_nonfinite ? TLI_FLAG_NONFINITE : 0) | (any_bad ? TLI_FLAG_BAD_DRAFT : 0);
+            if (out.lse_p) out.lse_p[(int64_t)b * (K + 1) + K] = NAN;
         }
-        frow[b] = f;
     }
+    // the record: what the lane that owns the row the extra token comes from knows, handed to every lane
+    const bool residual = !any_nonfinite && n < K;
+    const int owner = residual ? n : 0;
+    const double o_lse = __shfl(my_lse, owner, kWave), o_lq = __shfl(my_lq, owner, kWave);
+    const bool o_bad = __shfl((int)bad, owner, kWave) != 0;
+    FinalRow f;
+    f.skip = any_nonfinite ? 1 : 0;
+    f.bonus = (!any_nonfinite && n == K) ? 1 : 0;
+    f.n = n;
+    f.t_row = b * (K + 1) + (f.bonus ? K : n);
+    f.d_row = b * K + (f.bonus ? 0 : n);
+    f.dq = f.dq_lo = 0.f;
+    f.l2p = 0.0;
+    f.rp.use_q = 0;
+    f.rp.ct_hi = f.rp.ct_lo = f.rp.lp_hi = f.rp.lp_lo = 0.f;
+    f.rp.cd_hi = f.rp.cd_lo = f.rp.lq_hi = f.rp.lq_lo = 0.f;
+    if (residual) {
+        f.l2p = o_lse * kLog2e;
+        split_scale(in.c_t, f.rp.ct_hi, f.rp.ct_lo);
+        split_hi_lo(f.l2p, f.rp.lp_hi, f.rp.lp_lo);
+        // an unusable draft, or a drafter row without mass, has q' = 0 everywhere
+        if (!o_bad && (o_lq > -INFINITY || o_lq != o_lq)) {
+            f.rp.use_q = 1;
+            split_scale(in.c_d, f.rp.cd_hi, f.rp.cd_lo);
+            split_hi_lo(o_lq * kLog2e, f.rp.lq_hi, f.rp.lq_lo);
+        }
+    }
+    if (write && k == 0) out.frow[b] = f;
+    return f;
 }
 
 // ---- extra token: weights of one vector of the residual row -----------------------------------
@@ -522,12 +536,15 @@ __device__ __noinline__ void precise_chunk_masses(unsigned char* lds, uint32_t t
 // MODE 2 is the same diagnostic scan with the exponent arguments in fp64 and every term scaled by an exact power of
 // two: for the positions marked in `redo`, whose rates came out so small in MODE 1 that the fp32 arguments (good to
 // 2^-24 of their magnitude, i.e. 5e-6 of a term at 2^-100) and the fp32 range (nothing below 2^-126) show.
-template <int DT, int MODE>
+// ACCEPT (MODE 0 only; small batches, which keep the split form): the sequence's record is not read from `frow` but
+// formed here -- wave 0 of every workgroup of the sequence runs accept_sequence and hands the record to the other
+// waves through LDS; the sequence's first workgroup stores the outputs.  A kernel launch and its start-up less.
+template <int DT, int MODE, bool ACCEPT = false>
 __global__ __launch_bounds__(kScanWG) void k_final_scan(
     const void* __restrict__ logits_t, DrafterView dv, int B, int K, int Vt, int Vd, int nC, int nsplit, ScanLists ls,
     float cs_t, double ratio_t, const FinalRow* __restrict__ frow, float* __restrict__ tab_ref, float* __restrict__ tab_s, double* __restrict__ mn, double* __restrict__ mn2,
     int32_t* __restrict__ fbad, const int32_t* __restrict__ redo, const float2* __restrict__ ctab,
-    double* __restrict__ rmass) {
+    double* __restrict__ rmass, AcceptIn ain = AcceptIn(), AcceptOut aout = AcceptOut()) {
     constexpr bool DIAG = MODE != 0;
     constexpr bool EXACT = MODE == 2;
     constexpr int EPV = Traits<DT>::EPV;
@@ -565,7 +582,15 @@ __global__ __launch_bounds__(kScanWG) void k_final_scan(
         gbv = make_int2(pl_g[c], pl_g[c + 1]);
     }
     if (EXACT && !redo[b]) return;
-    const FinalRow f = frow[b];
+    __shared__ FinalRow s_frow;
+    if (ACCEPT) {
+        if (wave == 0) {
+            const FinalRow mine = accept_sequence<DT>(b, logits_t, dv, K, Vt, Vd, ain, aout, sub == 0);
+            if (lane == 0) s_frow = mine;
+        }
+        __syncthreads();
+    }
+    const FinalRow f = ACCEPT ? s_frow : frow[b];
     if (f.skip) return;
     if (f.bonus) {
         const u4v* rowk = reinterpret_cast<const u4v*>(static_cast<const char*>(logits_t) + (int64_t)f.t_row * Vt * ESZ);
