@@ -126,6 +126,9 @@ size_t tli_workspace_bytes(int32_t B, int32_t K, int32_t Vt, int32_t Vd, tli_dty
  *                     and fills column k of [B,K] arrays: the shape of the drafting loop, one call after
  *                     each drafter forward, whose results tli_verify then takes as they are.
  * Unshared drafter logits are never inspected.
+ * The draw is the ascending inverse CDF, min{x : C_x > u * C_last}, with the weights of a row's ids formed in fp32
+ * relative to the row's largest: an id whose weight lies more than 2^120 below it is not drawn (u = 0 returns the
+ * first id above that floor; together the ids below it hold less than 2^-100 of the row).
  */
 int tli_draft_sample(const tli_map* map, const void* logits_d, tli_dtype dtype, int64_t row_stride_elems,
                      int32_t R, float temp_d, const float* u_draft, int32_t* tok_d, int32_t* tok_t,
