@@ -2,9 +2,6 @@
 // intersection algorithm) and everything else that draws one token per softmax row.  Included by tli_kernels.hip
 // inside its unnamed namespace, after tli_device_common.h.
 #pragma once
-#ifndef TLI_LSE_ORDER
-#define TLI_LSE_ORDER 1
-#endif
 
 // ---- kernel: log-normaliser partials of rows -----------------------------------------------------
 // Standard SD appendix, verification loop: p_k(d_k) needs the normaliser of every target row k < K
@@ -17,16 +14,9 @@ __global__ __launch_bounds__(kWG) void k_lse(const void* __restrict__ logits, in
                                               double ratio, const uint64_t* __restrict__ bits,
                                               Part* __restrict__ part, float2* __restrict__ ctab,
                                               int32_t* __restrict__ fbad = nullptr) {
-#if TLI_LSE_ORDER == 1
-    const int slot = blockIdx.x / nsplit, split = blockIdx.x - slot * nsplit;
-    const int nB = (int)(gridDim.x / nsplit) / K;
-    const int kk = slot / nB;
-    const int b = slot - kk * nB, k = K - 1 - kk;
-    const int row = b * K + k;
-#else
+    // (rows in memory order: position-major or reversed orders make no difference on rows that come from HBM)
     const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
     const int b = row / K, k = row - b * K;
-#endif
     const u4v* rowv = reinterpret_cast<const u4v*>(static_cast<const char*>(logits) +
                                                     (b * seq_stride + k * row_stride) * Traits<DT>::ESZ);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
